@@ -1,0 +1,206 @@
+"""float64 CPU oracle for the spectrogram transforms of arXiv 1912.12055.
+
+TEST INFRASTRUCTURE ONLY.  This package wraps ``nna_oracle.c`` (plain C, naive
+loops, double precision) through ctypes.  Only ``tests/``, the smoke check and
+the bench's ``cpu_baseline`` leg may import it; the GPU library never does and
+shares no code with it.  Function names follow the C file; every array is
+row-major with the frame axis fastest: ``[B, bins, T]``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "nna_oracle.c")
+_LIB = os.path.join(_HERE, "libnna_oracle.so")
+
+MAGNITUDE, POWER, LOG = 0, 1, 2
+WIN_HANN, WIN_RECT = 0, 1
+MEL_SLANEY, MEL_HTK = 0, 1
+LOG_FLOOR = 1e-10
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fast-math: the summation order is the C file's)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+_LL = ctypes.c_longlong
+_D = ctypes.c_double
+_I = ctypes.c_int
+_PF = ctypes.POINTER(ctypes.c_float)
+_PD = ctypes.POINTER(ctypes.c_double)
+_PLL = ctypes.POINTER(ctypes.c_longlong)
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        L.orc_threads.restype = _I
+        L.orc_reflect_index.restype = _LL
+        L.orc_reflect_index.argtypes = [_LL, _LL]
+        L.orc_num_frames.restype = _LL
+        L.orc_num_frames.argtypes = [_LL, _LL, _LL, _I]
+        L.orc_window.argtypes = [_I, _LL, _PD]
+        L.orc_stft_complex.argtypes = [_PF, _LL, _LL, _I, _I, _I, _I, _PD, _PD]
+        L.orc_stft.argtypes = [_PF, _LL, _LL, _I, _I, _I, _I, _I, _PD]
+        L.orc_hz_to_mel.restype = _D
+        L.orc_hz_to_mel.argtypes = [_D, _I]
+        L.orc_mel_to_hz.restype = _D
+        L.orc_mel_to_hz.argtypes = [_D, _I]
+        L.orc_mel_filterbank.argtypes = [_I, _I, _I, _D, _D, _I, _I, _PD, _PD]
+        L.orc_mel.argtypes = [_PF, _LL, _LL, _I, _I, _I, _I, _I, _I, _D, _D, _I, _I, _D, _PD]
+        L.orc_cqt_Q.restype = _D
+        L.orc_cqt_Q.argtypes = [_I]
+        L.orc_cqt_lengths.argtypes = [_I, _D, _I, _I, _PLL, _PD]
+        L.orc_cqt_default_taps.restype = _LL
+        L.orc_cqt_default_taps.argtypes = [_I, _D, _I]
+        L.orc_cqt_kernels.argtypes = [_I, _D, _I, _I, _I, _LL, _PD, _PD]
+        L.orc_cqt.argtypes = [_PF, _LL, _LL, _I, _I, _D, _I, _I, _I, _I, _LL, _I, _PD]
+        _lib = L
+    return _lib
+
+
+class OracleError(ValueError):
+    pass
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise OracleError(f"{what}: oracle returned {rc} ({'invalid argument' if rc == 1 else 'out of memory'})")
+
+
+def _x(x):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if x.ndim == 1:
+        x = x[None, :]
+    if x.ndim != 2:
+        raise OracleError("x must be [B, L]")
+    return x
+
+
+def _pf(a):
+    return a.ctypes.data_as(_PF)
+
+
+def _pd(a):
+    return a.ctypes.data_as(_PD)
+
+
+def threads() -> int:
+    return int(lib().orc_threads())
+
+
+def reflect_index(j: int, L: int) -> int:
+    return int(lib().orc_reflect_index(j, L))
+
+
+def num_frames(L: int, N: int, hop: int, center: bool = True) -> int:
+    return int(lib().orc_num_frames(L, N, hop, int(center)))
+
+
+def window(kind: int, N: int) -> np.ndarray:
+    w = np.empty(N, dtype=np.float64)
+    _check(lib().orc_window(kind, N, _pd(w)), "window")
+    return w
+
+
+def stft_complex(x, n_fft=2048, hop=512, window=WIN_HANN, center=True):
+    x = _x(x)
+    B, L = x.shape
+    T = num_frames(L, n_fft, hop, center)
+    if T < 1:
+        raise OracleError("signal too short")
+    re = np.empty((B, n_fft // 2 + 1, T), dtype=np.float64)
+    im = np.empty_like(re)
+    _check(lib().orc_stft_complex(_pf(x), B, L, n_fft, hop, window, int(center), _pd(re), _pd(im)), "stft_complex")
+    return re, im
+
+
+def stft(x, n_fft=2048, hop=512, window=WIN_HANN, center=True, fmt=MAGNITUDE):
+    x = _x(x)
+    B, L = x.shape
+    T = num_frames(L, n_fft, hop, center)
+    if T < 1:
+        raise OracleError("signal too short")
+    out = np.empty((B, n_fft // 2 + 1, T), dtype=np.float64)
+    _check(lib().orc_stft(_pf(x), B, L, n_fft, hop, window, int(center), fmt, _pd(out)), "stft")
+    return out
+
+
+def hz_to_mel(f: float, scale=MEL_SLANEY) -> float:
+    return float(lib().orc_hz_to_mel(f, scale))
+
+
+def mel_to_hz(m: float, scale=MEL_SLANEY) -> float:
+    return float(lib().orc_mel_to_hz(m, scale))
+
+
+def mel_filterbank(sr, n_fft, n_mels, fmin=0.0, fmax=0.0, scale=MEL_SLANEY, norm_area=True):
+    W = np.empty((n_mels, n_fft // 2 + 1), dtype=np.float64)
+    edges = np.empty(n_mels + 2, dtype=np.float64)
+    _check(lib().orc_mel_filterbank(sr, n_fft, n_mels, fmin, fmax, scale, int(norm_area), _pd(W), _pd(edges)),
+           "mel_filterbank")
+    return W, edges
+
+
+def mel(x, sr=22050, n_fft=2048, hop=512, window=WIN_HANN, center=True, n_mels=128, fmin=0.0, fmax=0.0,
+        scale=MEL_SLANEY, norm_area=True, power=2.0):
+    x = _x(x)
+    B, L = x.shape
+    T = num_frames(L, n_fft, hop, center)
+    if T < 1:
+        raise OracleError("signal too short")
+    out = np.empty((B, n_mels, T), dtype=np.float64)
+    _check(lib().orc_mel(_pf(x), B, L, sr, n_fft, hop, window, int(center), n_mels, fmin, fmax, scale,
+                         int(norm_area), float(power), _pd(out)), "mel")
+    return out
+
+
+def cqt_Q(bins_per_octave: int) -> float:
+    return float(lib().orc_cqt_Q(bins_per_octave))
+
+
+def cqt_lengths(sr, fmin, n_bins, bins_per_octave):
+    Nk = np.empty(n_bins, dtype=np.int64)
+    fk = np.empty(n_bins, dtype=np.float64)
+    _check(lib().orc_cqt_lengths(sr, fmin, n_bins, bins_per_octave, Nk.ctypes.data_as(_PLL), _pd(fk)), "cqt_lengths")
+    return Nk, fk
+
+
+def cqt_default_taps(sr, fmin, bins_per_octave) -> int:
+    return int(lib().orc_cqt_default_taps(sr, fmin, bins_per_octave))
+
+
+def cqt_kernels(sr, fmin, n_bins, bins_per_octave, window=WIN_HANN, n_taps=0):
+    if n_taps <= 0:
+        n_taps = cqt_default_taps(sr, fmin, bins_per_octave)
+    kre = np.empty((n_bins, n_taps), dtype=np.float64)
+    kim = np.empty_like(kre)
+    _check(lib().orc_cqt_kernels(sr, fmin, n_bins, bins_per_octave, window, n_taps, _pd(kre), _pd(kim)), "cqt_kernels")
+    return kre, kim
+
+
+def cqt(x, sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, window=WIN_HANN, center=True,
+        n_taps=0, fmt=MAGNITUDE):
+    x = _x(x)
+    B, L = x.shape
+    if n_taps <= 0:
+        n_taps = cqt_default_taps(sr, fmin, bins_per_octave)
+    T = num_frames(L, n_taps, hop, center)
+    if T < 1:
+        raise OracleError("signal too short")
+    out = np.empty((B, n_bins, T), dtype=np.float64)
+    _check(lib().orc_cqt(_pf(x), B, L, sr, hop, fmin, n_bins, bins_per_octave, window, int(center), n_taps, fmt,
+                         _pd(out)), "cqt")
+    return out

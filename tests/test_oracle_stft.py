@@ -1,0 +1,190 @@
+"""Pins for the STFT part of the CPU oracle (CPU only).
+
+Each test checks the oracle against something other than itself: values the paper
+prints, closed forms, invariants, numpy's FFT on independently framed data, or a
+textbook complex DFT written out here.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1912_12055_amd import signals
+
+
+def _golden_rows(path):
+    rows = []
+    for line in open(path):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            rows.append(line.split())
+    return rows
+
+
+def test_reflect_index_hand_example():
+    # x = [0 1 2 3 4 5] padded by 3 on both sides, edge sample not repeated
+    want = [3, 2, 1, 0, 1, 2, 3, 4, 5, 4, 3, 2]
+    got = [oracle.reflect_index(i - 3, 6) for i in range(12)]
+    assert got == want
+    assert got == list(np.pad(np.arange(6), 3, mode="reflect"))
+
+
+@pytest.mark.parametrize("L,N,hop,T", [(22050, 2048, 512, 44), (110250, 2048, 512, 216), (220500, 16384, 512, 431),
+                                        (176400, 2048, 512, 345), (176400, 65536, 512, 345)])
+def test_num_frames_matches_workload_shapes(L, N, hop, T):
+    assert oracle.num_frames(L, N, hop, True) == T
+    assert oracle.num_frames(L, N, hop, True) == 1 + L // hop
+
+
+def test_num_frames_uncentred():
+    assert oracle.num_frames(2048, 2048, 512, False) == 1
+    assert oracle.num_frames(2047, 2048, 512, False) == 0
+    assert oracle.num_frames(2048 + 511, 2048, 512, False) == 1
+    assert oracle.num_frames(2048 + 512, 2048, 512, False) == 2
+
+
+def test_bin_frequencies_printed_in_paper(golden_dir):
+    # eq. (f-k-conversion) with the worked numbers of Sec. II-B; the oracle's Mel
+    # filterbank evaluates its triangles at exactly these frequencies (checked through
+    # the filter peak positions in test_oracle_mel.py); here the formula itself.
+    for k, f in _golden_rows(golden_dir + "/bin_freqs.txt"):
+        assert abs(int(k) * 44100 / 2048 - float(f)) < 0.006
+
+
+def test_hann_window_closed_forms():
+    for N in (8, 128, 2048, 371):
+        w = oracle.window(oracle.WIN_HANN, N)
+        assert w[0] == 0.0
+        assert abs(w.sum() - N / 2) < 1e-9  # periodic Hann sums to N/2 exactly
+        np.testing.assert_allclose(w[1:], w[1:][::-1], atol=1e-15)  # w[n] = w[N-n]
+        if N % 2 == 0:
+            assert abs(w[N // 2] - 1.0) < 1e-15
+        if N % 4 == 0:
+            assert abs(w[N // 4] - 0.5) < 1e-15
+    assert np.all(oracle.window(oracle.WIN_RECT, 16) == 1.0)
+
+
+@pytest.mark.parametrize("N", [8, 16, 64])
+def test_dft_equals_textbook_complex_dft(N):
+    # rectangular window, no centring, a single frame: eq. (DFT2) is the textbook DFT
+    rng = np.random.default_rng(N)
+    x = rng.standard_normal(N).astype(np.float32)
+    re, im = oracle.stft_complex(x, n_fft=N, hop=N, window=oracle.WIN_RECT, center=False)
+    n = np.arange(N)
+    for k in range(N // 2 + 1):
+        X = np.sum(x.astype(np.float64) * np.exp(-2j * np.pi * k * n / N))
+        assert abs(re[0, k, 0] - X.real) < 1e-12 * N
+        assert abs(im[0, k, 0] - X.imag) < 1e-12 * N
+
+
+def test_stft_equals_numpy_fft_on_independently_framed_signal():
+    # Hann, centred, several frames; framing and padding redone here with numpy
+    rng = np.random.default_rng(7)
+    L, N, hop = 1000, 256, 64
+    x = rng.standard_normal((2, L)).astype(np.float32)
+    re, im = oracle.stft_complex(x, n_fft=N, hop=hop)
+    T = 1 + L // hop
+    assert re.shape == (2, N // 2 + 1, T)
+    w = 0.5 - 0.5 * np.cos(2 * np.pi * np.arange(N) / N)
+    for b in range(2):
+        xp = np.pad(x[b].astype(np.float64), N // 2, mode="reflect")
+        for t in range(T):
+            X = np.fft.rfft(w * xp[t * hop:t * hop + N])
+            np.testing.assert_allclose(re[b, :, t], X.real, atol=1e-10)
+            np.testing.assert_allclose(im[b, :, t], X.imag, atol=1e-10)
+
+
+def test_stft_hop_not_dividing_window():
+    rng = np.random.default_rng(8)
+    L, N, hop = 700, 96, 25
+    x = rng.standard_normal(L).astype(np.float32)
+    mag = oracle.stft(x, n_fft=N, hop=hop, window=oracle.WIN_HANN, center=False)
+    T = 1 + (L - N) // hop
+    assert mag.shape == (1, N // 2 + 1, T)
+    w = 0.5 - 0.5 * np.cos(2 * np.pi * np.arange(N) / N)
+    for t in range(T):
+        X = np.fft.rfft(w * x[t * hop:t * hop + N].astype(np.float64))
+        np.testing.assert_allclose(mag[0, :, t], np.abs(X), atol=1e-10)
+
+
+@pytest.mark.parametrize("k0,phase", [(3, 0.0), (100, 0.7), (777, 2.0), (1020, -1.1)])
+def test_tone_on_bin_peaks_at_A_sumw_over_2(k0, phase):
+    # x[n] = A cos(2 pi k0 n / N + phase): |X[k0]| = A*sum(w)/2 = 512 A for N = 2048,
+    # |X[k0 +- 1]| = A*N/8, every other bin zero (Hann spectrum has three lines).
+    N, A = 2048, 0.37
+    x = (A * np.cos(2 * np.pi * k0 * np.arange(N) / N + phase))
+    mag = oracle.stft(x.astype(np.float64).astype(np.float32), n_fft=N, hop=N, center=False)[0, :, 0]
+    assert int(np.argmax(mag)) == k0
+    assert abs(mag[k0] - 512.0 * A) < 2e-4  # float32 input rounding only
+    assert abs(mag[k0 - 1] - A * N / 8) < 2e-4 and abs(mag[k0 + 1] - A * N / 8) < 2e-4
+    others = np.delete(mag, [k0 - 1, k0, k0 + 1])
+    assert others.max() < 2e-4
+
+
+def test_dc_signal():
+    N, c = 512, 0.25  # exactly representable
+    x = np.full(N, c, dtype=np.float32)
+    mag = oracle.stft(x, n_fft=N, hop=N, center=False)[0, :, 0]
+    assert abs(mag[0] - c * N / 2) < 1e-10
+    assert abs(mag[1] - c * N / 4) < 1e-10
+    assert mag[2:].max() < 1e-10
+
+
+def test_parseval_per_frame():
+    rng = np.random.default_rng(11)
+    L, N, hop = 4096, 512, 128
+    x = rng.standard_normal(L).astype(np.float32)
+    pw = oracle.stft(x, n_fft=N, hop=hop, fmt=oracle.POWER)[0]
+    w = 0.5 - 0.5 * np.cos(2 * np.pi * np.arange(N) / N)
+    xp = np.pad(x.astype(np.float64), N // 2, mode="reflect")
+    for t in range(pw.shape[1]):
+        energy = np.sum((w * xp[t * hop:t * hop + N]) ** 2)
+        two_sided = (pw[0, t] + pw[N // 2, t] + 2.0 * pw[1:N // 2, t].sum()) / N
+        assert abs(energy - two_sided) < 1e-10 * max(1.0, energy)
+
+
+def test_impulse_appears_only_in_frames_that_cover_it():
+    L, N, hop = 4000, 256, 64
+    for at in (0, 5, 1000, 1031, L - 1):
+        x = signals.impulse(L, at)
+        pw = oracle.stft(x, n_fft=N, hop=hop, fmt=oracle.POWER)[0]
+        energy = pw.sum(axis=0)
+        T = pw.shape[1]
+        xp_len = L + N
+        # positions of the impulse and of its mirror images in the padded signal
+        pos = [i for i in range(xp_len) if oracle.reflect_index(i - N // 2, L) == at]
+        for t in range(T):
+            # the Hann window is zero at its first sample, so offset 0 does not count
+            covered = any(0 < p - t * hop < N for p in pos)
+            assert (energy[t] > 1e-20) == covered, (at, t)
+
+
+def test_output_formats_agree():
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal(3000).astype(np.float32)
+    mag = oracle.stft(x, n_fft=128, hop=32, fmt=oracle.MAGNITUDE)
+    pw = oracle.stft(x, n_fft=128, hop=32, fmt=oracle.POWER)
+    lg = oracle.stft(x, n_fft=128, hop=32, fmt=oracle.LOG)
+    re, im = oracle.stft_complex(x, n_fft=128, hop=32)
+    np.testing.assert_allclose(pw, re ** 2 + im ** 2, rtol=1e-14)
+    np.testing.assert_allclose(mag, np.hypot(re, im), rtol=1e-14)
+    np.testing.assert_allclose(lg, np.log(np.maximum(pw, oracle.LOG_FLOOR)), rtol=1e-14)
+    silent = oracle.stft(np.zeros(3000, np.float32), n_fft=128, hop=32, fmt=oracle.LOG)
+    assert np.all(silent == np.log(oracle.LOG_FLOOR))
+
+
+def test_batch_order_is_preserved():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((3, 2000)).astype(np.float32)
+    both = oracle.stft(x, n_fft=128, hop=64)
+    for b in range(3):
+        np.testing.assert_array_equal(both[b], oracle.stft(x[b], n_fft=128, hop=64)[0])
+
+
+def test_rejects_bad_arguments():
+    x = np.zeros(100, np.float32)
+    with pytest.raises(oracle.OracleError):
+        oracle.stft(x, n_fft=256, hop=64)  # centre pad 128 >= L: reflection undefined
+    with pytest.raises(oracle.OracleError):
+        oracle.stft(x, n_fft=63, hop=16)  # odd window
+    with pytest.raises(oracle.OracleError):
+        oracle.stft(x, n_fft=256, hop=64, center=False)  # shorter than one window
