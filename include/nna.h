@@ -1,0 +1,161 @@
+/*
+ * nna.h -- C ABI of the MI355X (gfx950) waveform -> spectrogram library.
+ *
+ * The library computes the transforms of arXiv 1912.12055 ("nnAudio") as strided
+ * 1-D convolutions of a batch of waveforms with fixed kernel banks:
+ *   STFT   windowed cos/sin DFT kernels, eq. (DFT2) and Sec. III-A
+ *   Mel    triangular Mel filterbank applied to the STFT magnitude/power, Sec. III-B
+ *   CQT    full-length time-domain complex constant-Q kernels ("CQT1992v2"),
+ *          eqs. (Q), (N_k), (CQT) and Sec. III-C "CQT with time domain kernels"
+ *
+ * A plan (nna_plan_*) builds the kernel bank once on the host in double precision,
+ * rounds it to float32 and uploads it in the tile order the GPU kernels read; the
+ * paper calls this step initialisation and excludes it from its timings (Sec. IV-A).
+ * A transform call (nna_stft / nna_mel / nna_cqt) enqueues one fused GPU kernel on
+ * the caller's HIP stream.
+ *
+ * Conventions for every entry point
+ *   - All arrays are contiguous, row-major float32.  x_dev is [B, L] (B waveforms of
+ *     L samples); outputs are [B, bins, T] with the frame axis T fastest, in the
+ *     same waveform order as the input (Sec. IV-A: "maintaining the order").
+ *   - x_dev / out_dev are DEVICE pointers on the plan's device, owned by the caller.
+ *     host_out of nna_plan_bank is a HOST pointer.
+ *   - T = 1 + floor((L + 2*pad - K) / hop), K = n_fft or n_taps, pad = K/2 when
+ *     center != 0 (mirror reflection that does not repeat the edge sample) else 0.
+ *   - Transform calls allocate nothing, do not synchronise and return as soon as the
+ *     kernel is enqueued on `hip_stream` (a hipStream_t cast to void*; NULL = the
+ *     default stream).  Plans are immutable after creation and may be shared
+ *     between threads.
+ *   - Every function returns an nna_status; on failure nothing is enqueued, an
+ *     output plan pointer is set to NULL and nna_last_error() describes the problem
+ *     (thread-local text).  Nothing throws or aborts across this boundary.
+ *   - There is no CPU fallback: on a machine without a usable GPU plan creation for
+ *     device >= 0 fails with NNA_ERR_HIP.  device == -1 builds a host-only plan that
+ *     can be inspected (nna_out_shape, nna_plan_bank, nna_plan_info) but not run.
+ */
+#ifndef NNA_H
+#define NNA_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct nna_plan nna_plan; /* opaque; owns the device kernel banks */
+
+typedef enum {
+  NNA_OK = 0,
+  NNA_ERR_INVALID_ARG = 1, /* null pointer, out-of-range parameter, wrong plan kind */
+  NNA_ERR_UNSUPPORTED = 2, /* valid request this build does not implement */
+  NNA_ERR_SHAPE = 3,       /* B or L unusable with this plan (too short, too large) */
+  NNA_ERR_ALLOC = 4,       /* host or device allocation failed */
+  NNA_ERR_HIP = 5          /* a HIP runtime call failed (no device, launch error) */
+} nna_status;
+
+typedef enum {
+  NNA_OUT_MAGNITUDE = 0, /* sqrt(Re^2 + Im^2) */
+  NNA_OUT_POWER = 1,     /* Re^2 + Im^2 */
+  NNA_OUT_LOG = 2        /* ln(max(Re^2 + Im^2, 1e-10)): log compression, Fig. 1 caption */
+} nna_output;
+
+typedef enum {
+  NNA_WIN_HANN = 0, /* periodic Hann, w[n] = 1/2 - 1/2 cos(2 pi n / N) */
+  NNA_WIN_RECT = 1
+} nna_window;
+
+typedef enum {
+  NNA_MEL_SLANEY = 0, /* eq. (mel-stanley): linear below 1 kHz, logarithmic above */
+  NNA_MEL_HTK = 1     /* eq. (mel-o): 2595 log10(1 + f/700) */
+} nna_mel_scale;
+
+typedef enum { NNA_KIND_STFT = 0, NNA_KIND_MEL = 1, NNA_KIND_CQT = 2 } nna_kind;
+
+/*
+ * STFT plan (Sec. III-A; defaults of the paper's STFT layer: n_fft 2048, hop 512,
+ * Hann, center, reflect).  Bank: rows Re_k[n] = w[n] cos(2 pi k n / N) and
+ * Im_k[n] = -w[n] sin(2 pi k n / N), k = 0..N/2 (eq. (DFT2) with the window folded
+ * into the kernels).  Output bins F = n_fft/2 + 1.
+ *   sr     sample rate in Hz (kept for reporting; the DFT bank does not depend on it)
+ *   n_fft  even, >= 8;  hop >= 1;  center 0/1;  device: HIP device index or -1.
+ */
+nna_status nna_plan_stft(nna_plan** plan, int sr, int n_fft, int hop, nna_window win, int center,
+                         nna_output fmt, int device);
+
+/*
+ * Mel-spectrogram plan (Sec. III-B, Fig. 3): the STFT above followed, inside the same
+ * kernel, by Mel[m,t] = sum_j W[m,j] |X_t[j]|^power.  W is the triangular filterbank
+ * between n_mels+2 points equally spaced on the chosen mel scale from fmin to fmax
+ * (fmax <= 0 means sr/2), evaluated at the bin frequencies j*sr/n_fft (eq.
+ * (f-k-conversion)); norm_area != 0 scales filter m by 2/(f[m+2]-f[m]).
+ * power must be 1 or 2.  Output bins = n_mels.
+ */
+nna_status nna_plan_mel(nna_plan** plan, int sr, int n_fft, int hop, nna_window win, int center,
+                        int n_mels, double fmin, double fmax, nna_mel_scale scale, int norm_area,
+                        double power, int device);
+
+/*
+ * Constant-Q plan with time-domain kernels (Sec. III-C).  Bin k has centre frequency
+ * f_k = fmin 2^(k/b), Q = 1/(2^(1/b) - 1) cycles and length N_k = ceil(Q sr / f_k);
+ * its kernel is window(N_k)[n] exp(-2 pi i Q n / N_k) / sum(window(N_k)) (L1 norm),
+ * placed in taps [s_k, s_k + N_k), s_k = (n_taps - N_k) / 2 (integer division), of a
+ * bank row of n_taps taps.  n_taps == 0 picks the next power of two >= N_0; n_taps
+ * must be even and >= N_0, and the top bin must lie below sr/2.  Output bins = n_bins.
+ */
+nna_status nna_plan_cqt(nna_plan** plan, int sr, int hop, double fmin, int n_bins, int bins_per_octave,
+                        nna_window win, int center, int n_taps, nna_output fmt, int device);
+
+/* Output shape [B, *n_bins, *n_frames] for a batch of B waveforms of L samples.
+ * NNA_ERR_SHAPE if L is too short (center: L <= pad; otherwise L < K) or B < 1. */
+nna_status nna_out_shape(const nna_plan* plan, long long B, long long L, long long* n_bins,
+                         long long* n_frames);
+
+/* out_dev[B, n_fft/2+1, T] = STFT of x_dev[B, L] in the plan's output format.
+ * The plan must come from nna_plan_stft. */
+nna_status nna_stft(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
+                    void* hip_stream);
+
+/* out_dev[B, n_mels, T] = Mel spectrogram of x_dev[B, L]; plan from nna_plan_mel.
+ * The STFT itself is never written to memory. */
+nna_status nna_mel(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
+                   void* hip_stream);
+
+/* out_dev[B, n_bins, T] = constant-Q spectrogram of x_dev[B, L]; plan from nna_plan_cqt. */
+nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
+                   void* hip_stream);
+
+/*
+ * Inspection: the kernel bank exactly as the GPU holds it (float32 values widened to
+ * double), un-permuted to the logical layout [rows, K] with row 2k = Re part and row
+ * 2k+1 = Im part of bin k (rows = 2*(n_fft/2+1) for STFT/Mel, 2*n_bins for CQT;
+ * K = n_fft or n_taps).  For a device plan the data is read back from device memory
+ * (synchronous).  cap = capacity of host_out in doubles; NNA_ERR_INVALID_ARG if too
+ * small.  The required size is returned by nna_plan_info (rows * K).
+ */
+nna_status nna_plan_bank(const nna_plan* plan, double* host_out, size_t cap);
+
+/* Mel plans only: the filterbank W[n_mels, n_fft/2+1] as the GPU holds it. */
+nna_status nna_plan_mel_weights(const nna_plan* plan, double* host_out, size_t cap);
+
+/*
+ * Plan facts, each written if its pointer is non-NULL: kind, logical bank rows, taps K,
+ * output bins, flops the kernels execute per frame (multiply-add = 2, zero-padded
+ * taps they do not skip included) and algorithmic flops per frame (non-zero taps only:
+ * 2*K*rows_nonzero for the DFT bank, 4*sum_k N_k for the CQT, plus 2*nnz(W) for Mel).
+ */
+nna_status nna_plan_info(const nna_plan* plan, int* kind, long long* bank_rows, long long* taps,
+                         long long* out_bins, double* executed_flops_per_frame,
+                         double* algorithmic_flops_per_frame);
+
+/* CQT plans only: kernel lengths N_k, k = 0..n_bins-1 (host array of n_bins entries). */
+nna_status nna_plan_cqt_lengths(const nna_plan* plan, long long* host_out, size_t cap);
+
+void nna_plan_destroy(nna_plan* plan); /* NULL is allowed */
+
+const char* nna_status_str(nna_status s);
+const char* nna_last_error(void); /* text of this thread's last failure, "" if none */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NNA_H */

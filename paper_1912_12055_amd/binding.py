@@ -1,0 +1,198 @@
+"""Thin ctypes binding of the C ABI in include/nna.h.
+
+Argument marshalling only: every step of the transforms runs in the HIP library.
+PyTorch supplies device memory and streams.  There is no fallback: if libnna.so is
+missing the import of this module's functions raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnna.so")
+
+NNA_OK = 0
+NNA_ERR_INVALID_ARG, NNA_ERR_UNSUPPORTED, NNA_ERR_SHAPE, NNA_ERR_ALLOC, NNA_ERR_HIP = 1, 2, 3, 4, 5
+NNA_OUT_MAGNITUDE, NNA_OUT_POWER, NNA_OUT_LOG = 0, 1, 2
+NNA_WIN_HANN, NNA_WIN_RECT = 0, 1
+NNA_MEL_SLANEY, NNA_MEL_HTK = 0, 1
+NNA_KIND_STFT, NNA_KIND_MEL, NNA_KIND_CQT = 0, 1, 2
+
+# every symbol include/nna.h declares
+EXPORTS = [
+    "nna_plan_stft", "nna_plan_mel", "nna_plan_cqt", "nna_out_shape", "nna_stft", "nna_mel", "nna_cqt",
+    "nna_plan_bank", "nna_plan_mel_weights", "nna_plan_info", "nna_plan_cqt_lengths", "nna_plan_destroy",
+    "nna_status_str", "nna_last_error",
+]
+
+_c = ctypes
+_LL = _c.c_longlong
+_VP = _c.c_void_p
+_lib = None
+
+
+class NnaError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"nna status {status}: {message}")
+        self.status = status
+        self.message = message
+
+
+def lib():
+    """Load libnna.so (built in-tree by build.py / __graft_entry__.build())."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_1912_12055_amd.build` "
+                "(there is no CPU fallback)")
+        L = _c.CDLL(LIB_PATH)
+        PP = _c.POINTER(_VP)
+        L.nna_plan_stft.argtypes = [PP, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int]
+        L.nna_plan_mel.argtypes = [PP, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_double,
+                                   _c.c_double, _c.c_int, _c.c_int, _c.c_double, _c.c_int]
+        L.nna_plan_cqt.argtypes = [PP, _c.c_int, _c.c_int, _c.c_double, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
+                                   _c.c_int, _c.c_int, _c.c_int]
+        L.nna_out_shape.argtypes = [_VP, _LL, _LL, _c.POINTER(_LL), _c.POINTER(_LL)]
+        for name in ("nna_stft", "nna_mel", "nna_cqt"):
+            getattr(L, name).argtypes = [_VP, _VP, _LL, _LL, _VP, _VP]
+        L.nna_plan_bank.argtypes = [_VP, _c.POINTER(_c.c_double), _c.c_size_t]
+        L.nna_plan_mel_weights.argtypes = [_VP, _c.POINTER(_c.c_double), _c.c_size_t]
+        L.nna_plan_info.argtypes = [_VP, _c.POINTER(_c.c_int), _c.POINTER(_LL), _c.POINTER(_LL), _c.POINTER(_LL),
+                                    _c.POINTER(_c.c_double), _c.POINTER(_c.c_double)]
+        L.nna_plan_cqt_lengths.argtypes = [_VP, _c.POINTER(_LL), _c.c_size_t]
+        L.nna_plan_destroy.argtypes = [_VP]
+        L.nna_plan_destroy.restype = None
+        L.nna_status_str.argtypes = [_c.c_int]
+        L.nna_status_str.restype = _c.c_char_p
+        L.nna_last_error.restype = _c.c_char_p
+        for name in EXPORTS:
+            if name not in ("nna_plan_destroy", "nna_status_str", "nna_last_error"):
+                getattr(L, name).restype = _c.c_int
+        _lib = L
+    return _lib
+
+
+def nna_last_error() -> str:
+    return lib().nna_last_error().decode()
+
+
+def nna_status_str(status: int) -> str:
+    return lib().nna_status_str(status).decode()
+
+
+def _check(status: int):
+    if status != NNA_OK:
+        raise NnaError(status, nna_last_error() or nna_status_str(status))
+
+
+class Plan:
+    """Owns one nna_plan*; destroyed with the object."""
+
+    def __init__(self, handle: int, device: int):
+        self.handle = handle
+        self.device = device
+
+    def __del__(self):
+        h, self.handle = getattr(self, "handle", None), None
+        if h and _lib is not None:
+            _lib.nna_plan_destroy(h)
+
+    def info(self) -> dict:
+        kind = _c.c_int()
+        rows, taps, bins = _LL(), _LL(), _LL()
+        ex, alg = _c.c_double(), _c.c_double()
+        _check(lib().nna_plan_info(self.handle, kind, rows, taps, bins, ex, alg))
+        return dict(kind=kind.value, bank_rows=rows.value, taps=taps.value, out_bins=bins.value,
+                    executed_flops_per_frame=ex.value, algorithmic_flops_per_frame=alg.value)
+
+
+def _new_plan(fn, args, device):
+    h = _VP()
+    _check(fn(_c.byref(h), *args, device))
+    return Plan(h.value, device)
+
+
+def nna_plan_stft(sr=22050, n_fft=2048, hop=512, win=NNA_WIN_HANN, center=True, fmt=NNA_OUT_MAGNITUDE,
+                  device=0) -> Plan:
+    return _new_plan(lib().nna_plan_stft, (sr, n_fft, hop, win, int(center), fmt), device)
+
+
+def nna_plan_mel(sr=22050, n_fft=2048, hop=512, win=NNA_WIN_HANN, center=True, n_mels=128, fmin=0.0, fmax=0.0,
+                 scale=NNA_MEL_SLANEY, norm_area=True, power=2.0, device=0) -> Plan:
+    return _new_plan(lib().nna_plan_mel,
+                     (sr, n_fft, hop, win, int(center), n_mels, float(fmin), float(fmax), scale, int(norm_area),
+                      float(power)), device)
+
+
+def nna_plan_cqt(sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, win=NNA_WIN_HANN, center=True,
+                 n_taps=0, fmt=NNA_OUT_MAGNITUDE, device=0) -> Plan:
+    return _new_plan(lib().nna_plan_cqt,
+                     (sr, hop, float(fmin), n_bins, bins_per_octave, win, int(center), n_taps, fmt), device)
+
+
+def nna_out_shape(plan: Plan, B: int, L: int):
+    nb, nf = _LL(), _LL()
+    _check(lib().nna_out_shape(plan.handle, B, L, nb, nf))
+    return nb.value, nf.value
+
+
+def nna_plan_bank(plan: Plan) -> np.ndarray:
+    i = plan.info()
+    out = np.empty((i["bank_rows"], i["taps"]), dtype=np.float64)
+    _check(lib().nna_plan_bank(plan.handle, out.ctypes.data_as(_c.POINTER(_c.c_double)), out.size))
+    return out
+
+
+def nna_plan_mel_weights(plan: Plan) -> np.ndarray:
+    i = plan.info()
+    out = np.empty((i["out_bins"], i["bank_rows"] // 2), dtype=np.float64)
+    _check(lib().nna_plan_mel_weights(plan.handle, out.ctypes.data_as(_c.POINTER(_c.c_double)), out.size))
+    return out
+
+
+def nna_plan_cqt_lengths(plan: Plan) -> np.ndarray:
+    i = plan.info()
+    out = np.empty(i["out_bins"], dtype=np.int64)
+    _check(lib().nna_plan_cqt_lengths(plan.handle, out.ctypes.data_as(_c.POINTER(_LL)), out.size))
+    return out
+
+
+def _run(fn, plan: Plan, x, out, stream):
+    import torch
+
+    if not (isinstance(x, torch.Tensor) and x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()):
+        raise TypeError("x must be a contiguous float32 CUDA tensor [B, L]")
+    if x.dim() != 2:
+        raise TypeError("x must be [B, L]")
+    if x.device.index != plan.device:
+        raise ValueError("x lives on a different device than the plan")
+    B, L = x.shape
+    bins, frames = nna_out_shape(plan, B, L)
+    if out is None:
+        out = torch.empty((B, bins, frames), dtype=torch.float32, device=x.device)
+    elif not (out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
+              and tuple(out.shape) == (B, bins, frames) and out.device == x.device):
+        raise TypeError(f"out must be a contiguous float32 CUDA tensor of shape {(B, bins, frames)}")
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    _check(fn(plan.handle, x.data_ptr(), B, L, out.data_ptr(), stream))
+    return out
+
+
+def nna_stft(plan: Plan, x, out=None, stream=None):
+    """out[B, n_fft/2+1, T] = STFT of x[B, L] (device tensors; asynchronous on `stream`)."""
+    return _run(lib().nna_stft, plan, x, out, stream)
+
+
+def nna_mel(plan: Plan, x, out=None, stream=None):
+    """out[B, n_mels, T] = Mel spectrogram of x[B, L]."""
+    return _run(lib().nna_mel, plan, x, out, stream)
+
+
+def nna_cqt(plan: Plan, x, out=None, stream=None):
+    """out[B, n_bins, T] = constant-Q spectrogram of x[B, L]."""
+    return _run(lib().nna_cqt, plan, x, out, stream)

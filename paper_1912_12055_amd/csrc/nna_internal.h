@@ -1,0 +1,93 @@
+// Internal declarations shared by the host planner (nna_plan.hip) and the kernels
+// (nna_kernels.hip).  Nothing here is part of the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/nna.h"
+
+namespace nna {
+
+// ---- tile geometry (compile-time, shared by planner and kernels) ---------------------
+// STFT / Mel kernel: v_mfma_f32_32x32x2_f32, workgroup tile 128 bank rows x 128 frames.
+constexpr int ST_ROWS = 128;      // bank rows per row tile (= 64 bins: Re/Im interleaved)
+constexpr int ST_RB = 4;          // 32-row MFMA blocks per row tile
+constexpr int ST_FRAMES = 128;    // frames per workgroup (4 waves x 32)
+constexpr int ST_KC = 32;         // taps per LDS chunk
+constexpr int ST_PITCH = 36;      // LDS row pitch in floats (KC + 4: conflict-free b128 reads)
+constexpr int ST_KG = 8;          // taps per bank fragment (float4 per lane, two lane halves)
+constexpr int ST_NKG = ST_KC / ST_KG;
+constexpr int ST_LDS_ROWS = 192;  // LDS rows per buffer (frames + overlap rows)
+constexpr int ST_MEL_BLOCKS = 4;  // 32-mel MFMA blocks per pass (128 mels)
+
+// CQT kernel: v_mfma_f32_16x16x4_f32, workgroup tile 16 bank rows (8 bins) x 256 frames.
+constexpr int CQ_ROWS = 16;
+constexpr int CQ_FRAMES = 256;    // 4 waves x 4 blocks of 16 frames
+constexpr int CQ_KC = 16;         // taps per LDS chunk = taps per bank fragment
+constexpr int CQ_PITCH = 20;
+constexpr int CQ_LDS_ROWS_MAX = 512;
+constexpr int CQ_PREFETCH = 4;    // bank fragments in flight per wave
+
+// How frames map onto the batch of waveforms.
+struct FrameGeom {
+  const float* x;       // [B, L]
+  long long B, L;
+  long long n_frames;   // B * T
+  int T;                // frames per waveform
+  int hop;
+  int pad;              // samples of reflection padding in front (K/2 or 0)
+  int vec_ok;           // 16-byte loads of four consecutive samples are aligned
+};
+
+struct StftParams {
+  FrameGeom g;
+  const float4* bank;   // [row tile][group][ST_RB][64 lanes] float4
+  float* out;
+  int n_rt;             // row tiles
+  int n_chunks;         // LDS chunks per row tile
+  int nj;               // hop-shifts per chunk (n_fft/hop when the frames overlap in LDS, else 1)
+  int n_half;           // n_fft / 2: number of (Re,Im) slots that exist
+  int fmt;              // nna_output (STFT) ; Mel: 1 = magnitude before the filterbank, 2 = power
+  long long n_ft;       // frame tiles
+  int tile_frames;      // frames per tile (<= ST_FRAMES; smaller only when many short waveforms share a tile)
+  // Mel only
+  const float4* melw;   // [pass][row tile][ST_RB][ST_MEL_BLOCKS][2][64 lanes] float4
+  const unsigned char* mel_mask;  // [pass][row tile][ST_RB]: bit mb set if that 32-mel block is non-zero
+  const float* mel_wnyq;          // [n_mels] weight of the Nyquist bin
+  const int* mel_pass_rt;         // [pass][2]: first row tile, one past the last
+  int n_mels;
+  int n_pass;
+  int mel_nyq_any;
+};
+
+struct CqtChunk {
+  int c0;   // first tap column of the chunk (within the hop, or absolute when frames do not overlap)
+  int jlo;  // first hop-shift that has non-zero taps in this chunk
+  int nj;   // number of hop-shifts (bank fragments) in this chunk
+  int pad_;
+};
+
+struct CqtParams {
+  FrameGeom g;
+  const float4* bank;         // per row block: [fragment][64 lanes] float4, fragments in loop order
+  const long long* rb_frag0;  // [n_rb] first fragment of the row block
+  const CqtChunk* chunks;     // [n_rb][n_chunks]
+  const int* rb_jspan;        // [n_rb] LDS rows added per waveform segment + 1
+  float* out;
+  int n_rb;
+  int n_chunks;
+  int n_bins;
+  int fmt;
+  int lds_rows;               // rows per LDS buffer
+  int tile_frames;            // frames per tile (<= CQ_FRAMES)
+  long long n_ft;
+};
+
+hipError_t launch_stft(const StftParams& p, bool mel, hipStream_t stream);
+hipError_t launch_cqt(const CqtParams& p, hipStream_t stream);
+hipError_t kernels_init();  // per-process function attributes
+
+}  // namespace nna

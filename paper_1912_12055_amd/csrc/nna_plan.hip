@@ -1,0 +1,912 @@
+// Host side of the library: argument checking, kernel-bank construction in double precision,
+// permutation of the banks into the order the GPU kernels stream them, and the C ABI itself.
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <new>
+
+#include "nna_internal.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+nna_status fail(nna_status s, const std::string& msg) {
+  g_err = msg;
+  return s;
+}
+
+nna_status fail_hip(hipError_t e, const char* what) {
+  g_err = std::string(what) + ": " + hipGetErrorString(e);
+  return NNA_ERR_HIP;
+}
+
+constexpr double kPi = 3.141592653589793238462643383279502884;
+
+}  // namespace
+
+struct nna_plan {
+  int kind = 0;
+  int device = -1;
+  int sr = 0, hop = 0, center = 0, window = 0, fmt = 0;
+  int K = 0;    // taps: n_fft or n_taps
+  int pad = 0;  // reflection padding in front
+  bool sliding = false;
+
+  // STFT / Mel
+  int n_half = 0, n_rt = 0, n_chunks = 0, nj = 1;
+  long long bank_groups = 0;
+  // Mel
+  int n_mels = 0, mel_power = 2, n_pass = 0, mel_nyq_any = 0;
+  std::vector<float> h_melW;  // [n_mels, F] as rounded to float32
+
+  // CQT
+  int n_bins = 0, bpo = 0, n_rb = 0;
+  double cq_fmin = 0, Q = 0;
+  std::vector<long long> Nk, sk;
+  std::vector<long long> h_rb_frag0;
+  std::vector<nna::CqtChunk> h_chunks;
+  std::vector<int> h_rb_jspan;
+  int max_jspan = 1;
+
+  double exec_flops = 0, alg_flops = 0;
+
+  // host copy of the packed bank (host-only plans keep it; device plans drop it after upload)
+  std::vector<float> h_bank;
+  size_t bank_floats = 0;
+
+  // device buffers
+  float* d_bank = nullptr;
+  float* d_melw = nullptr;
+  unsigned char* d_mel_mask = nullptr;
+  float* d_mel_wnyq = nullptr;
+  int* d_mel_pass_rt = nullptr;
+  long long* d_rb_frag0 = nullptr;
+  nna::CqtChunk* d_chunks = nullptr;
+  int* d_rb_jspan = nullptr;
+};
+
+namespace {
+
+using nna::CQ_FRAMES;
+using nna::CQ_KC;
+using nna::CQ_LDS_ROWS_MAX;
+using nna::CQ_PREFETCH;
+using nna::CQ_ROWS;
+using nna::ST_FRAMES;
+using nna::ST_KC;
+using nna::ST_KG;
+using nna::ST_LDS_ROWS;
+using nna::ST_MEL_BLOCKS;
+using nna::ST_NKG;
+using nna::ST_RB;
+using nna::ST_ROWS;
+
+double window_value(int win, long long n, long long N) {
+  if (win == NNA_WIN_RECT) return 1.0;
+  return 0.5 - 0.5 * std::cos(2.0 * kPi * (double)n / (double)N);  // periodic Hann
+}
+
+// ---- device helpers -----------------------------------------------------------------
+std::once_flag g_init_flag;
+hipError_t g_init_err = hipSuccess;
+
+template <typename T>
+nna_status upload(T** dst, const void* src, size_t bytes, const char* what) {
+  *dst = nullptr;
+  if (bytes == 0) bytes = 16;
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(dst), bytes);
+  if (e != hipSuccess) {
+    *dst = nullptr;
+    if (e == hipErrorOutOfMemory) return fail(NNA_ERR_ALLOC, std::string("hipMalloc failed for ") + what);
+    return fail_hip(e, what);
+  }
+  if (src) {
+    e = hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice);
+    if (e != hipSuccess) return fail_hip(e, what);
+  }
+  return NNA_OK;
+}
+
+struct DeviceGuard {
+  int prev = -1;
+  bool switched = false;
+  hipError_t enter(int dev) {
+    hipError_t e = hipGetDevice(&prev);
+    if (e != hipSuccess) return e;
+    if (prev != dev) {
+      e = hipSetDevice(dev);
+      if (e != hipSuccess) return e;
+      switched = true;
+    }
+    return hipSuccess;
+  }
+  ~DeviceGuard() {
+    if (switched) (void)hipSetDevice(prev);
+  }
+};
+
+nna_status check_device(int device) {
+  if (device < -1) return fail(NNA_ERR_INVALID_ARG, "device must be >= -1");
+  if (device >= 0) {
+    int count = 0;
+    hipError_t e = hipGetDeviceCount(&count);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDeviceCount");
+    if (device >= count) return fail(NNA_ERR_HIP, "no such HIP device");
+  }
+  return NNA_OK;
+}
+
+// ---- STFT bank ----------------------------------------------------------------------
+// Logical bank value of packed row `pr`, tap k (double).  Packed rows interleave (Re, Im)
+// per slot; slot 0 carries the two purely real bins k = 0 and k = N/2, slot s carries bin s.
+struct DftTable {
+  std::vector<double> c, s, w;
+  int N;
+  DftTable(int N_, int win) : c(N_), s(N_), w(N_), N(N_) {
+    for (int m = 0; m < N; ++m) {
+      c[m] = std::cos(2.0 * kPi * (double)m / (double)N);
+      s[m] = std::sin(2.0 * kPi * (double)m / (double)N);
+      w[m] = window_value(win, m, N);
+    }
+  }
+  // eq. (DFT2) with the window folded in: Re kernel w cos(2 pi k n/N), Im kernel -w sin(...)
+  double re(int k, int n) const { return w[n] * c[(int)(((long long)k * n) % N)]; }
+  double im(int k, int n) const { return -w[n] * s[(int)(((long long)k * n) % N)]; }
+};
+
+double stft_packed_value(const DftTable& t, int n_half, int pr, int k) {
+  if (k >= t.N) return 0.0;
+  const int slot = pr >> 1, part = pr & 1;
+  if (slot >= n_half) return 0.0;
+  if (slot == 0) return part == 0 ? t.re(0, k) : t.re(n_half, k);
+  return part == 0 ? t.re(slot, k) : t.im(slot, k);
+}
+
+// tap index of (chunk c, shift j, fragment kg, lane half h, element e)
+inline int stft_tap(const nna_plan* p, int c, int j, int kg, int h, int e) {
+  return j * p->hop + c * ST_KC + kg * ST_KG + 4 * h + e;
+}
+
+void build_stft_bank(nna_plan* p) {
+  const int N = p->K;
+  p->n_half = N / 2;
+  p->n_rt = (N + ST_ROWS - 1) / ST_ROWS;  // packed rows = 2 * n_half = N
+  const int J = (p->hop > 0 && N % p->hop == 0) ? N / p->hop : 0;
+  p->sliding = J >= 1 && J <= 32 && p->hop % ST_KC == 0;
+  if (p->sliding) {
+    p->nj = J;
+    p->n_chunks = p->hop / ST_KC;
+  } else {
+    p->nj = 1;
+    p->n_chunks = (N + ST_KC - 1) / ST_KC;
+  }
+  const long long G = (long long)p->n_chunks * p->nj * ST_NKG;  // fragment groups per row tile
+  p->bank_groups = G * p->n_rt;
+  p->bank_floats = (size_t)(p->bank_groups + ST_NKG) * ST_RB * 64 * 4;  // + prefetch overrun
+  p->h_bank.assign(p->bank_floats, 0.0f);
+  DftTable tab(N, p->window);
+  for (int rt = 0; rt < p->n_rt; ++rt)
+    for (int c = 0; c < p->n_chunks; ++c)
+      for (int j = 0; j < p->nj; ++j)
+        for (int kg = 0; kg < ST_NKG; ++kg) {
+          const long long g = ((long long)c * p->nj + j) * ST_NKG + kg;
+          for (int rb = 0; rb < ST_RB; ++rb)
+            for (int lane = 0; lane < 64; ++lane) {
+              const int h = lane >> 5, r = lane & 31;
+              const int pr = rt * ST_ROWS + rb * 32 + r;
+              float* dst = &p->h_bank[((((size_t)rt * G + g) * ST_RB + rb) * 64 + lane) * 4];
+              for (int e = 0; e < 4; ++e)
+                dst[e] = (float)stft_packed_value(tab, p->n_half, pr, stft_tap(p, c, j, kg, h, e));
+            }
+        }
+  const double k_exec = (double)p->n_chunks * p->nj * ST_KC;
+  p->exec_flops = 2.0 * k_exec * (double)p->n_rt * ST_ROWS;
+  p->alg_flops = 2.0 * (double)N * (double)N;  // N non-zero rows (cos 0..N/2, sin 1..N/2-1) x N taps
+}
+
+// ---- Mel filterbank (Sec. III-B) ------------------------------------------------------
+struct MelAxis {
+  int scale;
+  // Slaney / Auditory-Toolbox constants of eq. (mel-stanley): 200/3 Hz per mel below the
+  // 1 kHz break (mel 15), 27 mels per factor 6.4 above
+  static constexpr double hz_per_mel = 200.0 / 3.0;
+  static constexpr double brk_hz = 1000.0;
+  static constexpr double brk_mel = 15.0;
+  double to_mel(double f) const {
+    if (scale == NNA_MEL_HTK) return 2595.0 * std::log10(1.0 + f / 700.0);
+    return f < brk_hz ? f / hz_per_mel : brk_mel + std::log(f / brk_hz) * 27.0 / std::log(6.4);
+  }
+  double to_hz(double m) const {
+    if (scale == NNA_MEL_HTK) return 700.0 * (std::pow(10.0, m / 2595.0) - 1.0);
+    return m < brk_mel ? m * hz_per_mel : brk_hz * std::exp((m - brk_mel) * std::log(6.4) / 27.0);
+  }
+};
+
+void build_mel_weights(nna_plan* p, double fmin, double fmax, int scale, int norm_area) {
+  const int F = p->n_half + 1, M = p->n_mels;
+  MelAxis ax{scale};
+  std::vector<double> edge(M + 2);
+  const double m0 = ax.to_mel(fmin), m1 = ax.to_mel(fmax);
+  for (int i = 0; i < M + 2; ++i) edge[i] = ax.to_hz(m0 + (m1 - m0) * i / (double)(M + 1));
+  edge[0] = fmin;  // end points exactly as given
+  edge[M + 1] = fmax;
+  p->h_melW.assign((size_t)M * F, 0.0f);
+  for (int m = 0; m < M; ++m) {
+    const double lo = edge[m], mid = edge[m + 1], hi = edge[m + 2];
+    const double scale_m = norm_area ? 2.0 / (hi - lo) : 1.0;
+    for (int j = 0; j < F; ++j) {
+      const double nu = (double)j * (double)p->sr / (double)p->K;  // eq. (f-k-conversion)
+      double v = 0.0;
+      if (nu > lo && nu < hi) v = nu <= mid ? (nu - lo) / (mid - lo) : (hi - nu) / (hi - mid);
+      p->h_melW[(size_t)m * F + j] = (float)(v * scale_m);
+    }
+  }
+}
+
+struct MelDeviceLayout {
+  std::vector<float> frag;          // [pass][rt][rb][mb][2][64][4]
+  std::vector<unsigned char> mask;  // [pass][rt][rb]
+  std::vector<float> wnyq;          // [n_mels]
+  std::vector<int> pass_rt;         // [pass][2]
+};
+
+MelDeviceLayout layout_mel(nna_plan* p) {
+  MelDeviceLayout out;
+  const int F = p->n_half + 1, M = p->n_mels;
+  const int per_pass = 32 * ST_MEL_BLOCKS;
+  p->n_pass = (M + per_pass - 1) / per_pass;
+  out.frag.assign((size_t)p->n_pass * p->n_rt * ST_RB * ST_MEL_BLOCKS * 2 * 64 * 4, 0.0f);
+  out.mask.assign((size_t)p->n_pass * p->n_rt * ST_RB, 0);
+  out.wnyq.assign(M, 0.0f);
+  out.pass_rt.assign((size_t)p->n_pass * 2, 0);
+  p->mel_nyq_any = 0;
+  for (int m = 0; m < M; ++m) {
+    out.wnyq[m] = p->h_melW[(size_t)m * F + p->n_half];
+    if (out.wnyq[m] != 0.0f) p->mel_nyq_any = 1;
+  }
+  double nnz = 0, exec_blocks = 0;
+  for (size_t i = 0; i < p->h_melW.size(); ++i) nnz += p->h_melW[i] != 0.0f;
+  for (int pass = 0; pass < p->n_pass; ++pass) {
+    int rt_lo = p->n_rt, rt_hi = 0;
+    bool nyq = false;
+    for (int m = pass * per_pass; m < std::min(M, (pass + 1) * per_pass); ++m) {
+      for (int j = 0; j < p->n_half; ++j)
+        if (p->h_melW[(size_t)m * F + j] != 0.0f) {
+          rt_lo = std::min(rt_lo, j / (ST_ROWS / 2));
+          rt_hi = std::max(rt_hi, j / (ST_ROWS / 2) + 1);
+        }
+      nyq = nyq || out.wnyq[m] != 0.0f;
+    }
+    if (nyq) rt_lo = 0;
+    if (rt_hi <= rt_lo) {  // no non-zero weight at all: still visit one tile so the zeros get written
+      rt_lo = 0;
+      rt_hi = std::max(rt_hi, 1);
+    }
+    out.pass_rt[2 * pass] = rt_lo;
+    out.pass_rt[2 * pass + 1] = rt_hi;
+    for (int rt = rt_lo; rt < rt_hi; ++rt)
+      for (int rb = 0; rb < ST_RB; ++rb)
+        for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb) {
+          bool any = false;
+          for (int v = 0; v < 2; ++v)
+            for (int lane = 0; lane < 64; ++lane) {
+              const int h = lane >> 5, mm = lane & 31;
+              const int mel = pass * per_pass + mb * 32 + mm;
+              for (int e = 0; e < 4; ++e) {
+                const int idx8 = v * 4 + e, q = idx8 >> 1, e2 = idx8 & 1;
+                const int bin = rt * (ST_ROWS / 2) + rb * 16 + 4 * q + 2 * h + e2;
+                float w = 0.0f;
+                if (mel < M && bin < p->n_half) w = p->h_melW[(size_t)mel * F + bin];
+                out.frag[((((((size_t)pass * p->n_rt + rt) * ST_RB + rb) * ST_MEL_BLOCKS + mb) * 2 + v) * 64 + lane) * 4 + e] = w;
+                any = any || w != 0.0f;
+              }
+            }
+          if (any) {
+            out.mask[((size_t)pass * p->n_rt + rt) * ST_RB + rb] |= (unsigned char)(1u << mb);
+            exec_blocks += 1;
+          }
+        }
+  }
+  // executed flops: every pass sweeps its row tile range with the full DFT contraction
+  double dft_exec = 0;
+  const double k_exec = (double)p->n_chunks * p->nj * ST_KC;
+  for (int pass = 0; pass < p->n_pass; ++pass)
+    dft_exec += 2.0 * k_exec * ST_ROWS * (out.pass_rt[2 * pass + 1] - out.pass_rt[2 * pass]);
+  p->exec_flops = dft_exec + exec_blocks * 2.0 * 32 * 16;  // 8 MFMA 32x32x2 per block, per frame: 32 mels x 16 slots
+  p->alg_flops = 2.0 * (double)p->K * (double)p->K + 2.0 * nnz;
+  return out;
+}
+
+// ---- CQT bank (Sec. III-C) ------------------------------------------------------------
+struct CqtKernelGen {
+  const nna_plan* p;
+  std::vector<double> wsum;
+  explicit CqtKernelGen(const nna_plan* p_) : p(p_), wsum(p_->n_bins) {
+    for (int k = 0; k < p->n_bins; ++k) {
+      double s = 0;
+      for (long long n = 0; n < p->Nk[k]; ++n) s += window_value(p->window, n, p->Nk[k]);
+      wsum[k] = s;
+    }
+  }
+  // logical bank value: row 2k = Re, 2k+1 = Im of window(N_k)[n] exp(-2 pi i Q n / N_k) / sum(window)
+  double value(int row, long long tap) const {
+    const int k = row >> 1;
+    if (k >= p->n_bins || tap >= p->K) return 0.0;
+    const long long n = tap - p->sk[k];
+    if (n < 0 || n >= p->Nk[k]) return 0.0;
+    const double w = window_value(p->window, n, p->Nk[k]) / wsum[k];
+    const double ph = 2.0 * kPi * p->Q * (double)n / (double)p->Nk[k];
+    return (row & 1) ? -w * std::sin(ph) : w * std::cos(ph);
+  }
+};
+
+inline long long floor_div(long long a, long long b) { return a >= 0 ? a / b : -((-a + b - 1) / b); }
+inline long long ceil_div(long long a, long long b) { return -floor_div(-a, b); }
+
+void build_cqt_bank(nna_plan* p) {
+  const long long K = p->K;
+  p->n_rb = (2 * p->n_bins + CQ_ROWS - 1) / CQ_ROWS;
+  const long long J = (K % p->hop == 0) ? K / p->hop : 0;
+  p->sliding = J >= 1 && J <= 128 && p->hop % CQ_KC == 0;
+  // tap support [s, e) of every row block
+  std::vector<long long> s_rb(p->n_rb), e_rb(p->n_rb);
+  for (int rb = 0; rb < p->n_rb; ++rb) {
+    long long s = K, e = 0;
+    for (int k = rb * (CQ_ROWS / 2); k < std::min(p->n_bins, (rb + 1) * (CQ_ROWS / 2)); ++k) {
+      s = std::min(s, p->sk[k]);
+      e = std::max(e, p->sk[k] + p->Nk[k]);
+    }
+    s_rb[rb] = s;
+    e_rb[rb] = e;
+  }
+  if (p->sliding) {
+    p->n_chunks = p->hop / CQ_KC;
+  } else {
+    long long most = 1;
+    for (int rb = 0; rb < p->n_rb; ++rb)
+      most = std::max(most, ceil_div(e_rb[rb], CQ_KC) - s_rb[rb] / CQ_KC);
+    p->n_chunks = (int)most;
+  }
+  p->h_chunks.assign((size_t)p->n_rb * p->n_chunks, nna::CqtChunk{0, 0, 0, 0});
+  p->h_rb_jspan.assign(p->n_rb, 1);
+  p->h_rb_frag0.assign(p->n_rb, 0);
+  long long frag = 0;
+  p->max_jspan = 1;
+  for (int rb = 0; rb < p->n_rb; ++rb) {
+    p->h_rb_frag0[rb] = frag;
+    int jspan = 1;
+    for (int c = 0; c < p->n_chunks; ++c) {
+      nna::CqtChunk ck{0, 0, 0, 0};
+      if (p->sliding) {
+        // taps j*hop + c0 + [0, KC) intersect [s, e)  <=>  j*hop + c0 + KC > s  and  j*hop + c0 < e
+        ck.c0 = c * CQ_KC;
+        long long jlo = floor_div(s_rb[rb] - ck.c0 - CQ_KC, p->hop) + 1;
+        long long jhi = ceil_div(e_rb[rb] - ck.c0, p->hop);
+        jlo = std::max(jlo, 0LL);
+        jhi = std::min(jhi, J);
+        ck.jlo = (int)jlo;
+        ck.nj = (int)std::max(0LL, jhi - jlo);
+        if (ck.nj == 0) ck.jlo = 0;
+      } else {
+        const long long first = s_rb[rb] / CQ_KC;
+        const long long last = ceil_div(e_rb[rb], CQ_KC);
+        ck.c0 = (int)((first + c) * CQ_KC);
+        ck.jlo = 0;
+        ck.nj = (first + c) < last ? 1 : 0;
+        if (ck.nj == 0) ck.c0 = 0;
+      }
+      jspan = std::max(jspan, ck.nj);
+      frag += ck.nj;
+      p->h_chunks[(size_t)rb * p->n_chunks + c] = ck;
+    }
+    p->h_rb_jspan[rb] = jspan;
+    p->max_jspan = std::max(p->max_jspan, jspan);
+  }
+  p->bank_groups = frag;
+  p->bank_floats = (size_t)(frag + CQ_PREFETCH) * 64 * 4;
+  p->h_bank.assign(p->bank_floats, 0.0f);
+  CqtKernelGen gen(p);
+  for (int rb = 0; rb < p->n_rb; ++rb) {
+    long long f = p->h_rb_frag0[rb];
+    for (int c = 0; c < p->n_chunks; ++c) {
+      const nna::CqtChunk& ck = p->h_chunks[(size_t)rb * p->n_chunks + c];
+      for (int jj = 0; jj < ck.nj; ++jj, ++f)
+        for (int lane = 0; lane < 64; ++lane) {
+          const int q = lane >> 4, r = lane & 15;
+          const long long tap0 = (long long)(ck.jlo + jj) * (p->sliding ? p->hop : 0) + ck.c0 + 4 * q;
+          float* dst = &p->h_bank[((size_t)f * 64 + lane) * 4];
+          for (int e = 0; e < 4; ++e) dst[e] = (float)gen.value(rb * CQ_ROWS + r, tap0 + e);
+        }
+    }
+  }
+  double sumN = 0;
+  for (int k = 0; k < p->n_bins; ++k) sumN += (double)p->Nk[k];
+  p->exec_flops = 2.0 * (double)frag * CQ_KC * CQ_ROWS;
+  p->alg_flops = 4.0 * sumN;
+}
+
+nna_status finish_plan(nna_plan* p, nna_plan** out, const MelDeviceLayout* mel) {
+  if (p->device >= 0) {
+    DeviceGuard guard;
+    hipError_t e = guard.enter(p->device);
+    if (e != hipSuccess) {
+      delete p;
+      return fail_hip(e, "hipSetDevice");
+    }
+    std::call_once(g_init_flag, [] { g_init_err = nna::kernels_init(); });
+    if (g_init_err != hipSuccess) {
+      delete p;
+      return fail_hip(g_init_err, "kernel attribute setup");
+    }
+    nna_status s = upload(&p->d_bank, p->h_bank.data(), p->bank_floats * sizeof(float), "kernel bank");
+    if (s == NNA_OK && mel) {
+      s = upload(&p->d_melw, mel->frag.data(), mel->frag.size() * sizeof(float), "mel weights");
+      if (s == NNA_OK) s = upload(&p->d_mel_mask, mel->mask.data(), mel->mask.size(), "mel mask");
+      if (s == NNA_OK) s = upload(&p->d_mel_wnyq, mel->wnyq.data(), mel->wnyq.size() * sizeof(float), "mel nyquist weights");
+      if (s == NNA_OK) s = upload(&p->d_mel_pass_rt, mel->pass_rt.data(), mel->pass_rt.size() * sizeof(int), "mel pass table");
+    }
+    if (s == NNA_OK && p->kind == NNA_KIND_CQT) {
+      s = upload(&p->d_rb_frag0, p->h_rb_frag0.data(), p->h_rb_frag0.size() * sizeof(long long), "cqt fragment table");
+      if (s == NNA_OK) s = upload(&p->d_chunks, p->h_chunks.data(), p->h_chunks.size() * sizeof(nna::CqtChunk), "cqt chunk table");
+      if (s == NNA_OK) s = upload(&p->d_rb_jspan, p->h_rb_jspan.data(), p->h_rb_jspan.size() * sizeof(int), "cqt span table");
+    }
+    if (s != NNA_OK) {
+      const std::string keep = g_err;
+      nna_plan_destroy(p);
+      g_err = keep;
+      return s;
+    }
+    std::vector<float>().swap(p->h_bank);  // the device copy is the bank from here on
+  }
+  *out = p;
+  return NNA_OK;
+}
+
+nna_status check_common(nna_plan** plan, int sr, int hop, int win, int center, int device) {
+  if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan output pointer is NULL");
+  *plan = nullptr;
+  if (sr < 1) return fail(NNA_ERR_INVALID_ARG, "sr must be >= 1");
+  if (hop < 1) return fail(NNA_ERR_INVALID_ARG, "hop must be >= 1");
+  if (win != NNA_WIN_HANN && win != NNA_WIN_RECT) return fail(NNA_ERR_INVALID_ARG, "unknown window");
+  if (center != 0 && center != 1) return fail(NNA_ERR_INVALID_ARG, "center must be 0 or 1");
+  return check_device(device);
+}
+
+nna_status check_stft_args(int n_fft) {
+  if (n_fft < 8 || (n_fft & 1)) return fail(NNA_ERR_INVALID_ARG, "n_fft must be even and >= 8");
+  if (n_fft > (1 << 20)) return fail(NNA_ERR_UNSUPPORTED, "n_fft above 2^20 is not supported");
+  return NNA_OK;
+}
+
+// frames per waveform, or 0 if the signal is too short
+long long frames_of(const nna_plan* p, long long L) {
+  if (p->center) {
+    if (L <= p->pad) return 0;  // mirror reflection needs pad <= L-1
+  } else if (L < p->K) {
+    return 0;
+  }
+  return 1 + (L + 2LL * p->pad - p->K) / p->hop;
+}
+
+// Largest frame tile (<= cap) whose LDS rows  M + segments(M,T)*extra  fit in `rows_max`.
+int pick_tile_frames(int cap, long long T, int extra, int rows_max) {
+  for (int M = cap; M >= 1; --M) {
+    const long long nseg = 1 + (M - 1 + T - 1) / T;
+    if ((long long)M + nseg * extra <= rows_max) return M;
+  }
+  return 0;
+}
+
+nna_status check_call(const nna_plan* plan, int kind, const float* x, long long B, long long L, float* out,
+                      long long* T_out) {
+  if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
+  if (plan->kind != kind) return fail(NNA_ERR_INVALID_ARG, "plan was built for a different transform");
+  if (!x || !out) return fail(NNA_ERR_INVALID_ARG, "x_dev / out_dev is NULL");
+  if (plan->device < 0) return fail(NNA_ERR_UNSUPPORTED, "host-only plan (device = -1) cannot run transforms");
+  if (B < 1) return fail(NNA_ERR_SHAPE, "B must be >= 1");
+  const long long T = frames_of(plan, L);
+  if (T < 1) return fail(NNA_ERR_SHAPE, plan->center ? "L must exceed the reflection padding (K/2)" : "L is shorter than one window");
+  if (T > 0x7fffffffLL / 4 || L > (1LL << 40) || B > (1LL << 40) / T) return fail(NNA_ERR_SHAPE, "batch too large");
+  *T_out = T;
+  return NNA_OK;
+}
+
+nna::FrameGeom make_geom(const nna_plan* p, const float* x, long long B, long long L, long long T) {
+  nna::FrameGeom g;
+  g.x = x;
+  g.B = B;
+  g.L = L;
+  g.T = (int)T;
+  g.n_frames = B * T;
+  g.hop = p->hop;
+  g.pad = p->pad;
+  g.vec_ok = (L % 4 == 0) && (p->hop % 4 == 0) && (p->pad % 4 == 0) && ((reinterpret_cast<uintptr_t>(x) & 15) == 0);
+  return g;
+}
+
+nna_status run_stft_like(const nna_plan* plan, int kind, const float* x, long long B, long long L, float* out,
+                         void* stream) {
+  long long T = 0;
+  nna_status s = check_call(plan, kind, x, B, L, out, &T);
+  if (s != NNA_OK) return s;
+  const int M = pick_tile_frames(ST_FRAMES, T, plan->nj - 1, ST_LDS_ROWS);
+  if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
+  nna::StftParams P;
+  std::memset(&P, 0, sizeof(P));
+  P.g = make_geom(plan, x, B, L, T);
+  P.bank = reinterpret_cast<const float4*>(plan->d_bank);
+  P.out = out;
+  P.n_rt = plan->n_rt;
+  P.n_chunks = plan->n_chunks;
+  P.nj = plan->nj;
+  P.n_half = plan->n_half;
+  P.tile_frames = M;
+  P.n_ft = (P.g.n_frames + M - 1) / M;
+  if (kind == NNA_KIND_MEL) {
+    P.fmt = plan->mel_power;
+    P.melw = reinterpret_cast<const float4*>(plan->d_melw);
+    P.mel_mask = plan->d_mel_mask;
+    P.mel_wnyq = plan->d_mel_wnyq;
+    P.mel_pass_rt = plan->d_mel_pass_rt;
+    P.n_mels = plan->n_mels;
+    P.n_pass = plan->n_pass;
+    P.mel_nyq_any = plan->mel_nyq_any;
+  } else {
+    P.fmt = plan->fmt;
+  }
+  DeviceGuard guard;
+  hipError_t e = guard.enter(plan->device);
+  if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+  e = nna::launch_stft(P, kind == NNA_KIND_MEL, reinterpret_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  return NNA_OK;
+}
+
+}  // namespace
+
+// =======================================================================================
+// C ABI
+// =======================================================================================
+extern "C" {
+
+nna_status nna_plan_stft(nna_plan** plan, int sr, int n_fft, int hop, nna_window win, int center, nna_output fmt,
+                         int device) {
+  nna_status s = check_common(plan, sr, hop, win, center, device);
+  if (s != NNA_OK) return s;
+  if ((s = check_stft_args(n_fft)) != NNA_OK) return s;
+  if (fmt != NNA_OUT_MAGNITUDE && fmt != NNA_OUT_POWER && fmt != NNA_OUT_LOG)
+    return fail(NNA_ERR_INVALID_ARG, "unknown output format");
+  nna_plan* p = new (std::nothrow) nna_plan;
+  if (!p) return fail(NNA_ERR_ALLOC, "out of host memory");
+  try {
+    p->kind = NNA_KIND_STFT;
+    p->device = device;
+    p->sr = sr;
+    p->hop = hop;
+    p->center = center;
+    p->window = win;
+    p->fmt = fmt;
+    p->K = n_fft;
+    p->pad = center ? n_fft / 2 : 0;
+    build_stft_bank(p);
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return fail(NNA_ERR_ALLOC, "out of host memory while building the DFT bank");
+  }
+  return finish_plan(p, plan, nullptr);
+}
+
+nna_status nna_plan_mel(nna_plan** plan, int sr, int n_fft, int hop, nna_window win, int center, int n_mels,
+                        double fmin, double fmax, nna_mel_scale scale, int norm_area, double power, int device) {
+  nna_status s = check_common(plan, sr, hop, win, center, device);
+  if (s != NNA_OK) return s;
+  if ((s = check_stft_args(n_fft)) != NNA_OK) return s;
+  if (n_mels < 1 || n_mels > 4096) return fail(NNA_ERR_INVALID_ARG, "n_mels must be in [1, 4096]");
+  if (scale != NNA_MEL_SLANEY && scale != NNA_MEL_HTK) return fail(NNA_ERR_INVALID_ARG, "unknown mel scale");
+  if (!(power == 1.0 || power == 2.0)) return fail(NNA_ERR_INVALID_ARG, "power must be 1 or 2");
+  if (!(fmax > 0.0)) fmax = 0.5 * sr;
+  if (!(fmin >= 0.0) || !(fmax > fmin) || fmax > 0.5 * sr)
+    return fail(NNA_ERR_INVALID_ARG, "need 0 <= fmin < fmax <= sr/2");
+  nna_plan* p = new (std::nothrow) nna_plan;
+  if (!p) return fail(NNA_ERR_ALLOC, "out of host memory");
+  MelDeviceLayout mel;
+  try {
+    p->kind = NNA_KIND_MEL;
+    p->device = device;
+    p->sr = sr;
+    p->hop = hop;
+    p->center = center;
+    p->window = win;
+    p->K = n_fft;
+    p->pad = center ? n_fft / 2 : 0;
+    p->n_mels = n_mels;
+    p->mel_power = power == 1.0 ? 1 : 2;
+    build_stft_bank(p);
+    build_mel_weights(p, fmin, fmax, scale, norm_area);
+    mel = layout_mel(p);
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return fail(NNA_ERR_ALLOC, "out of host memory while building the Mel plan");
+  }
+  return finish_plan(p, plan, &mel);
+}
+
+nna_status nna_plan_cqt(nna_plan** plan, int sr, int hop, double fmin, int n_bins, int bins_per_octave,
+                        nna_window win, int center, int n_taps, nna_output fmt, int device) {
+  nna_status s = check_common(plan, sr, hop, win, center, device);
+  if (s != NNA_OK) return s;
+  if (!(fmin > 0.0)) return fail(NNA_ERR_INVALID_ARG, "fmin must be > 0");
+  if (n_bins < 1 || n_bins > 4096) return fail(NNA_ERR_INVALID_ARG, "n_bins must be in [1, 4096]");
+  if (bins_per_octave < 1 || bins_per_octave > 1024) return fail(NNA_ERR_INVALID_ARG, "bins_per_octave must be in [1, 1024]");
+  if (fmt != NNA_OUT_MAGNITUDE && fmt != NNA_OUT_POWER && fmt != NNA_OUT_LOG)
+    return fail(NNA_ERR_INVALID_ARG, "unknown output format");
+  if (n_taps < 0) return fail(NNA_ERR_INVALID_ARG, "n_taps must be >= 0");
+  const double top = fmin * std::pow(2.0, (double)(n_bins - 1) / bins_per_octave);
+  if (!(top < 0.5 * sr)) return fail(NNA_ERR_INVALID_ARG, "the top CQT bin must lie below sr/2");
+  nna_plan* p = new (std::nothrow) nna_plan;
+  if (!p) return fail(NNA_ERR_ALLOC, "out of host memory");
+  try {
+    p->kind = NNA_KIND_CQT;
+    p->device = device;
+    p->sr = sr;
+    p->hop = hop;
+    p->center = center;
+    p->window = win;
+    p->fmt = fmt;
+    p->n_bins = n_bins;
+    p->bpo = bins_per_octave;
+    p->cq_fmin = fmin;
+    p->Q = 1.0 / (std::exp2(1.0 / bins_per_octave) - 1.0);  // eq. (Q)
+    p->Nk.resize(n_bins);
+    p->sk.resize(n_bins);
+    for (int k = 0; k < n_bins; ++k) {
+      const double fk = fmin * std::exp2((double)k / bins_per_octave);
+      p->Nk[k] = (long long)std::ceil(p->Q * (double)sr / fk);  // eq. (N_k), in double
+    }
+    if (p->Nk[0] > (1LL << 24)) {
+      delete p;
+      return fail(NNA_ERR_UNSUPPORTED, "CQT kernels longer than 2^24 taps are not supported");
+    }
+    long long taps = n_taps;
+    if (taps == 0) {
+      taps = 1;
+      while (taps < p->Nk[0]) taps <<= 1;
+      if (taps < 2) taps = 2;
+    }
+    if (taps & 1) {
+      delete p;
+      return fail(NNA_ERR_INVALID_ARG, "n_taps must be even");
+    }
+    if (taps < p->Nk[0]) {
+      char msg[160];
+      std::snprintf(msg, sizeof msg, "n_taps = %lld is shorter than the longest kernel (%lld taps)", taps, p->Nk[0]);
+      delete p;
+      return fail(NNA_ERR_INVALID_ARG, msg);
+    }
+    p->K = (int)taps;
+    p->pad = center ? (int)(taps / 2) : 0;
+    for (int k = 0; k < n_bins; ++k) p->sk[k] = (taps - p->Nk[k]) / 2;
+    build_cqt_bank(p);
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return fail(NNA_ERR_ALLOC, "out of host memory while building the CQT bank");
+  }
+  return finish_plan(p, plan, nullptr);
+}
+
+nna_status nna_out_shape(const nna_plan* plan, long long B, long long L, long long* n_bins, long long* n_frames) {
+  if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
+  if (B < 1) return fail(NNA_ERR_SHAPE, "B must be >= 1");
+  const long long T = frames_of(plan, L);
+  if (T < 1) return fail(NNA_ERR_SHAPE, plan->center ? "L must exceed the reflection padding (K/2)" : "L is shorter than one window");
+  if (n_bins) *n_bins = plan->kind == NNA_KIND_STFT ? plan->n_half + 1 : plan->kind == NNA_KIND_MEL ? plan->n_mels : plan->n_bins;
+  if (n_frames) *n_frames = T;
+  return NNA_OK;
+}
+
+nna_status nna_stft(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev, void* hip_stream) {
+  return run_stft_like(plan, NNA_KIND_STFT, x_dev, B, L, out_dev, hip_stream);
+}
+
+nna_status nna_mel(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev, void* hip_stream) {
+  return run_stft_like(plan, NNA_KIND_MEL, x_dev, B, L, out_dev, hip_stream);
+}
+
+nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev, void* hip_stream) {
+  long long T = 0;
+  nna_status s = check_call(plan, NNA_KIND_CQT, x_dev, B, L, out_dev, &T);
+  if (s != NNA_OK) return s;
+  const int extra = plan->max_jspan - 1;
+  const int M = pick_tile_frames(CQ_FRAMES, T, extra, CQ_LDS_ROWS_MAX);
+  if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
+  nna::CqtParams P;
+  std::memset(&P, 0, sizeof(P));
+  P.g = make_geom(plan, x_dev, B, L, T);
+  P.bank = reinterpret_cast<const float4*>(plan->d_bank);
+  P.rb_frag0 = plan->d_rb_frag0;
+  P.chunks = plan->d_chunks;
+  P.rb_jspan = plan->d_rb_jspan;
+  P.out = out_dev;
+  P.n_rb = plan->n_rb;
+  P.n_chunks = plan->n_chunks;
+  P.n_bins = plan->n_bins;
+  P.fmt = plan->fmt;
+  P.tile_frames = M;
+  const long long nseg = 1 + (M - 1 + T - 1) / T;
+  P.lds_rows = (int)(M + nseg * extra);
+  P.n_ft = (P.g.n_frames + M - 1) / M;
+  DeviceGuard guard;
+  hipError_t e = guard.enter(plan->device);
+  if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+  e = nna::launch_cqt(P, reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  return NNA_OK;
+}
+
+nna_status nna_plan_bank(const nna_plan* plan, double* host_out, size_t cap) {
+  if (!plan || !host_out) return fail(NNA_ERR_INVALID_ARG, "plan / host_out is NULL");
+  const long long rows = plan->kind == NNA_KIND_CQT ? 2LL * plan->n_bins : 2LL * (plan->n_half + 1);
+  const long long K = plan->K;
+  if ((unsigned long long)cap < (unsigned long long)(rows * K)) return fail(NNA_ERR_INVALID_ARG, "host_out is too small");
+  std::vector<float> tmp;
+  const float* src = nullptr;
+  try {
+    if (plan->device >= 0) {
+      tmp.resize(plan->bank_floats);
+      DeviceGuard guard;
+      hipError_t e = guard.enter(plan->device);
+      if (e == hipSuccess) e = hipMemcpy(tmp.data(), plan->d_bank, plan->bank_floats * sizeof(float), hipMemcpyDeviceToHost);
+      if (e != hipSuccess) return fail_hip(e, "bank read-back");
+      src = tmp.data();
+    } else {
+      src = plan->h_bank.data();
+    }
+  } catch (const std::bad_alloc&) {
+    return fail(NNA_ERR_ALLOC, "out of host memory");
+  }
+  std::fill(host_out, host_out + rows * K, 0.0);
+  if (plan->kind == NNA_KIND_CQT) {
+    for (int rb = 0; rb < plan->n_rb; ++rb) {
+      long long f = plan->h_rb_frag0[rb];
+      for (int c = 0; c < plan->n_chunks; ++c) {
+        const nna::CqtChunk& ck = plan->h_chunks[(size_t)rb * plan->n_chunks + c];
+        for (int jj = 0; jj < ck.nj; ++jj, ++f)
+          for (int lane = 0; lane < 64; ++lane) {
+            const int q = lane >> 4, r = lane & 15;
+            const long long row = (long long)rb * CQ_ROWS + r;
+            const long long tap0 = (long long)(ck.jlo + jj) * (plan->sliding ? plan->hop : 0) + ck.c0 + 4 * q;
+            for (int e = 0; e < 4; ++e) {
+              const float v = src[((size_t)f * 64 + lane) * 4 + e];
+              if (row < rows && tap0 + e < K) host_out[row * K + tap0 + e] = (double)v;
+            }
+          }
+      }
+    }
+  } else {
+    const long long G = (long long)plan->n_chunks * plan->nj * ST_NKG;
+    for (int rt = 0; rt < plan->n_rt; ++rt)
+      for (int c = 0; c < plan->n_chunks; ++c)
+        for (int j = 0; j < plan->nj; ++j)
+          for (int kg = 0; kg < ST_NKG; ++kg) {
+            const long long g = ((long long)c * plan->nj + j) * ST_NKG + kg;
+            for (int rb = 0; rb < ST_RB; ++rb)
+              for (int lane = 0; lane < 64; ++lane) {
+                const int h = lane >> 5, r = lane & 31;
+                const int pr = rt * ST_ROWS + rb * 32 + r;
+                const int slot = pr >> 1, part = pr & 1;
+                if (slot >= plan->n_half) continue;
+                // packed slot 0 = (Re bin 0, Re bin N/2); slot s = (Re, Im) of bin s
+                const long long row = slot == 0 ? (part == 0 ? 0 : 2LL * plan->n_half) : 2LL * slot + part;
+                for (int e = 0; e < 4; ++e) {
+                  const int k = stft_tap(plan, c, j, kg, h, e);
+                  if (k < K) host_out[row * K + k] = (double)src[((((size_t)rt * G + g) * ST_RB + rb) * 64 + lane) * 4 + e];
+                }
+              }
+          }
+  }
+  return NNA_OK;
+}
+
+nna_status nna_plan_mel_weights(const nna_plan* plan, double* host_out, size_t cap) {
+  if (!plan || !host_out) return fail(NNA_ERR_INVALID_ARG, "plan / host_out is NULL");
+  if (plan->kind != NNA_KIND_MEL) return fail(NNA_ERR_INVALID_ARG, "not a Mel plan");
+  const size_t F = plan->n_half + 1, M = plan->n_mels;
+  if (cap < M * F) return fail(NNA_ERR_INVALID_ARG, "host_out is too small");
+  if (plan->device < 0) {
+    for (size_t i = 0; i < M * F; ++i) host_out[i] = (double)plan->h_melW[i];
+    return NNA_OK;
+  }
+  // read the device fragments back and undo the permutation
+  const int per_pass = 32 * ST_MEL_BLOCKS;
+  const size_t n = (size_t)plan->n_pass * plan->n_rt * ST_RB * ST_MEL_BLOCKS * 2 * 64 * 4;
+  std::vector<float> frag, wnyq;
+  try {
+    frag.resize(n);
+    wnyq.resize(M);
+  } catch (const std::bad_alloc&) {
+    return fail(NNA_ERR_ALLOC, "out of host memory");
+  }
+  {
+    DeviceGuard guard;
+    hipError_t e = guard.enter(plan->device);
+    if (e == hipSuccess) e = hipMemcpy(frag.data(), plan->d_melw, n * sizeof(float), hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(wnyq.data(), plan->d_mel_wnyq, M * sizeof(float), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail_hip(e, "mel weight read-back");
+  }
+  std::fill(host_out, host_out + M * F, 0.0);
+  for (int pass = 0; pass < plan->n_pass; ++pass)
+    for (int rt = 0; rt < plan->n_rt; ++rt)
+      for (int rb = 0; rb < ST_RB; ++rb)
+        for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb)
+          for (int v = 0; v < 2; ++v)
+            for (int lane = 0; lane < 64; ++lane) {
+              const int h = lane >> 5, mm = lane & 31;
+              const size_t mel = (size_t)pass * per_pass + mb * 32 + mm;
+              for (int e = 0; e < 4; ++e) {
+                const int idx8 = v * 4 + e, q = idx8 >> 1, e2 = idx8 & 1;
+                const size_t bin = (size_t)rt * (ST_ROWS / 2) + rb * 16 + 4 * q + 2 * h + e2;
+                const float w = frag[((((((size_t)pass * plan->n_rt + rt) * ST_RB + rb) * ST_MEL_BLOCKS + mb) * 2 + v) * 64 + lane) * 4 + e];
+                if (mel < M && bin < (size_t)plan->n_half && w != 0.0f) host_out[mel * F + bin] = (double)w;
+              }
+            }
+  for (size_t m = 0; m < M; ++m) host_out[m * F + plan->n_half] = (double)wnyq[m];
+  return NNA_OK;
+}
+
+nna_status nna_plan_info(const nna_plan* plan, int* kind, long long* bank_rows, long long* taps, long long* out_bins,
+                         double* executed_flops_per_frame, double* algorithmic_flops_per_frame) {
+  if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
+  if (kind) *kind = plan->kind;
+  if (bank_rows) *bank_rows = plan->kind == NNA_KIND_CQT ? 2LL * plan->n_bins : 2LL * (plan->n_half + 1);
+  if (taps) *taps = plan->K;
+  if (out_bins) *out_bins = plan->kind == NNA_KIND_STFT ? plan->n_half + 1 : plan->kind == NNA_KIND_MEL ? plan->n_mels : plan->n_bins;
+  if (executed_flops_per_frame) *executed_flops_per_frame = plan->exec_flops;
+  if (algorithmic_flops_per_frame) *algorithmic_flops_per_frame = plan->alg_flops;
+  return NNA_OK;
+}
+
+nna_status nna_plan_cqt_lengths(const nna_plan* plan, long long* host_out, size_t cap) {
+  if (!plan || !host_out) return fail(NNA_ERR_INVALID_ARG, "plan / host_out is NULL");
+  if (plan->kind != NNA_KIND_CQT) return fail(NNA_ERR_INVALID_ARG, "not a CQT plan");
+  if (cap < (size_t)plan->n_bins) return fail(NNA_ERR_INVALID_ARG, "host_out is too small");
+  for (int k = 0; k < plan->n_bins; ++k) host_out[k] = plan->Nk[k];
+  return NNA_OK;
+}
+
+void nna_plan_destroy(nna_plan* plan) {
+  if (!plan) return;
+  if (plan->device >= 0) {
+    DeviceGuard guard;
+    if (guard.enter(plan->device) == hipSuccess) {
+      (void)hipFree(plan->d_bank);
+      (void)hipFree(plan->d_melw);
+      (void)hipFree(plan->d_mel_mask);
+      (void)hipFree(plan->d_mel_wnyq);
+      (void)hipFree(plan->d_mel_pass_rt);
+      (void)hipFree(plan->d_rb_frag0);
+      (void)hipFree(plan->d_chunks);
+      (void)hipFree(plan->d_rb_jspan);
+    }
+  }
+  delete plan;
+}
+
+const char* nna_status_str(nna_status s) {
+  switch (s) {
+    case NNA_OK: return "ok";
+    case NNA_ERR_INVALID_ARG: return "invalid argument";
+    case NNA_ERR_UNSUPPORTED: return "unsupported";
+    case NNA_ERR_SHAPE: return "unusable batch shape";
+    case NNA_ERR_ALLOC: return "allocation failed";
+    case NNA_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+const char* nna_last_error(void) { return g_err.c_str(); }
+
+}  // extern "C"
