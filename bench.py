@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Throughput of the spectrogram hot path on one MI355X.
+
+One step = one pass of the whole path over the 1,770-waveform workloads: nna_stft and
+nna_mel on 1,770 x 176,400 samples @ 44.1 kHz (n_fft 2048, hop 512, 128 mels) and nna_cqt on
+1,770 x 176,400 samples @ 44.1 kHz (168 bins, 24 per octave, 65,536 taps).  Inputs are
+seeded synthetic waveforms already resident in HBM; plans (kernel banks) are built before
+timing, as the paper excludes initialisation from its timings (Sec. IV-A).
+
+Prints one JSON line: whole-job GSamples/s (input samples consumed by the three transforms
+per second), per-transform figures, the MFMA roofline of the dominant kernel measured with
+HIP events on the launch stream, and the float64 CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0
+
+
+def _read_traffic():
+    """HBM bytes per launch of each kernel from the committed rocprofv3 counter summary, if any."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_1770x176400.json.txt")
+    try:
+        return json.load(open(path))
+    except Exception:
+        return {}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--batch", type=int, default=1770, help="waveforms per transform (default: the full workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy, so that a rocprofv3 --pmc run of this command "
+                         "holds a kernel of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
+    ap.add_argument("--only", choices=["stft", "mel", "cqt"], default=None,
+                    help="time a single transform (profiling aid); the JSON line then covers that one only")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (waveforms are independent, so more GPUs would "
+              "just shard the batch); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_1912_12055_amd import binding as nb
+    from paper_1912_12055_amd import signals
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU fallback", file=sys.stderr)
+        return 2
+    nb.lib()
+    dev = torch.device("cuda:0")
+    B, L, sr = args.batch, 176400, 44100
+
+    def resident(cfg_id):
+        x = torch.empty((B, L), dtype=torch.float32, device=dev)
+        for s in range(0, B, 256):
+            idx = list(range(s, min(B, s + 256)))
+            x[s:s + len(idx)] = torch.from_numpy(signals.batch(cfg_id, idx, workers=16)).to(dev)
+        return x
+
+    t0 = time.time()
+    x4 = resident(4)
+    x5 = resident(5)
+    t_gen = time.time() - t0
+
+    t0 = time.time()
+    p_stft = nb.nna_plan_stft(sr=sr, n_fft=2048, hop=512, device=0)
+    p_mel = nb.nna_plan_mel(sr=sr, n_fft=2048, hop=512, n_mels=128, fmin=0.0, fmax=22050.0, device=0)
+    p_cqt = nb.nna_plan_cqt(sr=sr, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24, n_taps=0, device=0)
+    t_plan = time.time() - t0
+
+    T = 1 + L // 512
+    o_stft = torch.empty((B, 1025, T), dtype=torch.float32, device=dev)
+    o_mel = torch.empty((B, 128, T), dtype=torch.float32, device=dev)
+    o_cqt = torch.empty((B, 168, T), dtype=torch.float32, device=dev)
+
+    legs = {
+        "stft": (lambda: nb.nna_stft(p_stft, x4, o_stft), p_stft, o_stft),
+        "mel": (lambda: nb.nna_mel(p_mel, x4, o_mel), p_mel, o_mel),
+        "cqt": (lambda: nb.nna_cqt(p_cqt, x5, o_cqt), p_cqt, o_cqt),
+    }
+    names = [args.only] if args.only else ["stft", "mel", "cqt"]
+
+    def step(events=None):
+        for n in names:
+            if events is not None:
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                legs[n][0]()
+                b.record()
+                events[n].append((a, b))
+            else:
+                legs[n][0]()
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)  # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = {n: [] for n in names}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_per_step = 1e3 * wall / args.steps
+    samples_per_step = len(names) * B * L
+    value = samples_per_step / (wall / args.steps) / 1e9
+
+    traffic = _read_traffic()
+    per = {}
+    for n in names:
+        ms = float(np.mean([a.elapsed_time(b) for a, b in events[n]]))
+        info = legs[n][1].info()
+        frames = B * T
+        alg = info["algorithmic_flops_per_frame"] * frames
+        exe = info["executed_flops_per_frame"] * frames
+        out_bytes = legs[n][2].numel() * 4
+        per[n] = {
+            "ms": round(ms, 4),
+            "gsamples_per_s": round(B * L / ms / 1e6, 4),
+            "frames_per_s": round(frames / ms * 1e3, 1),
+            "algorithmic_tflops": round(alg / ms / 1e9, 3),
+            "executed_tflops": round(exe / ms / 1e9, 3),
+            "mfma_frac": round(alg / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+            "mfma_frac_executed": round(exe / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+            "algorithmic_gb": round((B * L * 4 + out_bytes) / 1e9, 4),
+            "hbm_frac": round((B * L * 4 + out_bytes) / ms / 1e6 / PEAK_HBM_GBS, 5),
+            "hbm_traffic_bytes": traffic.get(n),
+        }
+    dom = max(names, key=lambda n: per[n]["ms"])
+    roofline = {
+        "kernel": {"stft": "stft_kernel<false>", "mel": "stft_kernel<true>", "cqt": "cqt_kernel"}[dom],
+        "bound": "mfma",
+        "achieved": per[dom]["algorithmic_tflops"],
+        "peak": PEAK_FP32_MFMA_TFLOPS,
+        "unit": "TFLOP/s",
+        "frac": per[dom]["mfma_frac"],
+        "traffic": traffic.get(dom),
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        n_cpu = min(B, 96)
+        idx = sorted({int(i) for i in np.linspace(0, B - 1, n_cpu)})
+        n_cpu = len(idx)
+        xs4 = signals.batch(4, idx)
+        xs5 = signals.batch(5, idx)
+        t0 = time.perf_counter()
+        done = 0
+        if "stft" in names:
+            oracle.stft(xs4, n_fft=2048, hop=512)
+            done += 1
+        if "mel" in names:
+            oracle.mel(xs4, sr=sr, n_fft=2048, hop=512, n_mels=128, fmin=0.0, fmax=22050.0)
+            done += 1
+        if "cqt" in names:
+            oracle.cqt(xs5, sr=sr, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24, n_taps=65536)
+            done += 1
+        t_cpu = time.perf_counter() - t0
+        cpu = {
+            "value": round(done * n_cpu * L / t_cpu / 1e9, 6),
+            "unit": "GSamples/s",
+            "cores": oracle.threads(),
+            "kind": "oracle",
+            "sample": f"{n_cpu} of the {B} waveforms (evenly spaced indices) through the same {done} transforms, "
+                      f"{t_cpu:.1f} s of float64 oracle time",
+        }
+
+    line = {
+        "metric": "GSamples/s per transform (STFT/Mel/CQT) + % of MFMA roofline, 1 MI355X",
+        "value": round(value, 4),
+        "unit": "GSamples/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": "1,770 waveforms x 176,400 samples @ 44.1 kHz through " + "+".join(names)
+                        + " (STFT/Mel: n_fft 2048, hop 512, 128 mels; CQT: 168 bins, 24/octave, 65,536 taps)",
+            "batch": B, "samples_per_waveform": L, "frames_per_waveform": T,
+            "value_definition": "input samples consumed by the timed transforms per second, whole step",
+        },
+        "per_transform": per,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "setup_s": {"input_generation": round(t_gen, 2), "plans": round(t_plan, 2)},
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
