@@ -16,6 +16,8 @@
 // stores coalesce without a transpose.
 #include "nna_internal.h"
 
+#include <type_traits>
+
 namespace nna {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -49,54 +51,124 @@ struct TileMap {
   }
 };
 
-__device__ __forceinline__ float load_reflect(const float* __restrict__ xb, long long i, long long L) {
-  long long r = i < 0 ? -i : (i >= L ? 2 * (L - 1) - i : i);
-  r = r < 0 ? 0 : (r >= L ? L - 1 : r);  // only reachable under zero-padded bank columns
-  return xb[r];
+// ---------------------------------------------------------------------------------------
+// Hand-scheduled global loads.  The compiler's own wait-count insertion is conservative at loop
+// headers (it waited for nearly every outstanding load at the top of each K iteration, which
+// exposed the full L2 latency), so the streaming loads are issued through inline asm and waited
+// for with explicit s_waitcnt vmcnt(N).  Loads return in issue order, so "vmcnt(N)" guarantees
+// that everything older than the N youngest requests has landed; N must therefore never exceed
+// the number of requests issued after the one being waited for.  Every code path below issues
+// a fixed number of load instructions so that these counts hold.  The "+v" operands tie the
+// wait to the registers it protects: no use of them can be scheduled above it.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void gload16(f32x4& dst, const void* p) {
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(p));
+}
+template <int OFF>
+__device__ __forceinline__ void gload16_off(f32x4& dst, const void* p) {
+  asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(dst) : "v"(p), "n"(OFF));
+}
+template <int N>
+__device__ __forceinline__ void wait_vm(f32x4& a) {
+  asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a) : "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void wait_vm(f32x4& a, f32x4& b, f32x4& c, f32x4& d) {
+  asm volatile("s_waitcnt vmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void wait_vm(f32x4 (&r)[6]) {
+  asm volatile("s_waitcnt vmcnt(%6)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]) : "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void wait_vm(f32x4 (&r)[8]) {
+  asm volatile("s_waitcnt vmcnt(%8)"
+               : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7])
+               : "n"(N));
 }
 
-// Global -> registers for one LDS chunk: rows [0, rows_used) x KC columns starting at sample
-// column c0 of S-row (sigma + jlo).  256 threads, NPASS passes of 256*4/KC rows.
-template <int KC, int NPASS>
-__device__ __forceinline__ void load_chunk(float4 (&R)[NPASS], const FrameGeom& g, const TileMap& tm,
-                                           int rows_used, int jlo, int c0, int tid) {
-  constexpr int V = KC / 4;
-  constexpr int RPP = 256 / V;
-  const int cv = tid % V, r0 = tid / V;
-#pragma unroll
-  for (int p = 0; p < NPASS; ++p) {
-    const int row = p * RPP + r0;
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (row < rows_used) {
-      long long b;
-      int sigma;
-      tm.decode(row, b, sigma);
-      if (b < g.B) {
-        const long long i0 = (long long)(sigma + jlo) * g.hop + c0 + cv * 4 - g.pad;
-        const float* __restrict__ xb = g.x + b * g.L;
-        if (g.vec_ok && i0 >= 0 && i0 + 3 < g.L) {
-          v = *reinterpret_cast<const float4*>(xb + i0);
-        } else {
-          v.x = load_reflect(xb, i0, g.L);
-          v.y = load_reflect(xb, i0 + 1, g.L);
-          v.z = load_reflect(xb, i0 + 2, g.L);
-          v.w = load_reflect(xb, i0 + 3, g.L);
-        }
-      }
-    }
-    R[p] = v;
+// ---------------------------------------------------------------------------------------
+// Framing loader.  LDS row r of a tile is S-row sigma of waveform b (table `rowinfo`, built
+// once per tile).  A thread fetches 4 consecutive columns of one row per pass with ONE 16-byte
+// load: the 4 padded samples i0..i0+3 always map, after mirror reflection at either end of the
+// waveform, into one window of 4 consecutive stored samples, so the load takes that window and
+// a 2-bit-per-element selector (identity 0xE4 in the interior) reorders it when the chunk is
+// written to LDS.  Selector 0xFF marks rows that do not exist (zero fill; the load then reads a
+// dummy address so that the number of issued loads is the same on every path).
+// ---------------------------------------------------------------------------------------
+constexpr unsigned SEL_IDENTITY = 0xE4u, SEL_ZERO = 0xFFu;
+
+__device__ __forceinline__ int reflect_clamped(int j, int L) {
+  int r = j < 0 ? -j : (j >= L ? 2 * (L - 1) - j : j);
+  return r < 0 ? 0 : (r >= L ? L - 1 : r);  // the clamp is only reachable under zero bank columns
+}
+
+template <int NROWS>
+__device__ __forceinline__ void build_rowinfo(int2* rowinfo, const TileMap& tm, int rows_used, long long B, int tid) {
+  for (int row = tid; row < NROWS; row += 256) {
+    long long b;
+    int sigma;
+    tm.decode(row, b, sigma);
+    const bool ok = row < rows_used && b < B;
+    rowinfo[row] = ok ? make_int2((int)b, sigma) : make_int2(-1, 0);
   }
 }
 
+template <int KC, int NPASS>
+__device__ __forceinline__ void issue_chunk(f32x4 (&R)[NPASS], unsigned (&sel)[NPASS], const FrameGeom& g,
+                                            const int2* rowinfo, int jlo, int c0, int tid) {
+  constexpr int V = KC / 4;
+  constexpr int RPP = 256 / V;
+  const int cv = tid % V, r0 = tid / V;
+  const int L = (int)g.L;
+#pragma unroll
+  for (int p = 0; p < NPASS; ++p) {
+    const int2 ri = rowinfo[p * RPP + r0];
+    const float* ptr = g.x;
+    unsigned s = SEL_ZERO;
+    if (ri.x >= 0) {
+      const int i0 = (ri.y + jlo) * g.hop + c0 + cv * 4 - g.pad;
+      const float* xb = g.x + (long long)ri.x * g.L;
+      if (i0 >= 0 && i0 + 3 < L) {
+        ptr = xb + i0;
+        s = SEL_IDENTITY;
+      } else {
+        const int i_0 = reflect_clamped(i0, L), i_1 = reflect_clamped(i0 + 1, L);
+        const int i_2 = reflect_clamped(i0 + 2, L), i_3 = reflect_clamped(i0 + 3, L);
+        int w0 = min(min(i_0, i_1), min(i_2, i_3));
+        w0 = min(w0, L - 4);
+        ptr = xb + w0;
+        s = (unsigned)min(i_0 - w0, 3) | ((unsigned)min(i_1 - w0, 3) << 2) | ((unsigned)min(i_2 - w0, 3) << 4) |
+            ((unsigned)min(i_3 - w0, 3) << 6);
+      }
+    }
+    gload16(R[p], ptr);
+    sel[p] = s;
+  }
+}
+
+__device__ __forceinline__ float pick4(const f32x4& v, unsigned k) {
+  return k == 0 ? v.x : k == 1 ? v.y : k == 2 ? v.z : v.w;
+}
+
 template <int KC, int PITCH, int NPASS>
-__device__ __forceinline__ void store_chunk(const float4 (&R)[NPASS], float* lds, int rows_alloc, int tid) {
+__device__ __forceinline__ void store_chunk(const f32x4 (&R)[NPASS], const unsigned (&sel)[NPASS], float* lds,
+                                            int rows_alloc, int tid) {
   constexpr int V = KC / 4;
   constexpr int RPP = 256 / V;
   const int cv = tid % V, r0 = tid / V;
 #pragma unroll
   for (int p = 0; p < NPASS; ++p) {
     const int row = p * RPP + r0;
-    if (row < rows_alloc) *reinterpret_cast<float4*>(lds + row * PITCH + cv * 4) = R[p];
+    f32x4 v = R[p];
+    const unsigned s = sel[p];
+    if (s != SEL_IDENTITY) {
+      if (s == SEL_ZERO)
+        v = (f32x4){0.f, 0.f, 0.f, 0.f};
+      else
+        v = (f32x4){pick4(v, s & 3), pick4(v, (s >> 2) & 3), pick4(v, (s >> 4) & 3), pick4(v, (s >> 6) & 3)};
+    }
+    if (row < rows_alloc) *reinterpret_cast<f32x4*>(lds + row * PITCH + cv * 4) = v;
   }
 }
 
@@ -115,12 +187,22 @@ __device__ __forceinline__ float format_power(float pw, int fmt) {
 // Row tiles are visited one after the other; in the Mel variant the power of each finished row
 // tile is contracted, straight from the accumulator registers, with the matching slice of the
 // filterbank by a second MFMA into 128 mel x 32 frame accumulators.
+//
+// Pipeline per LDS chunk `it` (KC taps of every hop-shift): the tile of chunk it+1, requested
+// one chunk earlier, is written to the other LDS buffer; the tile of chunk it+2 is requested;
+// then nj * ST_NKG fragment groups of 16 MFMAs run, each group waiting only for its own bank
+// fragments (requested RING groups earlier) and re-requesting its ring slot afterwards.
 // ---------------------------------------------------------------------------------------
-constexpr int ST_NPASS = ST_LDS_ROWS / (256 / (ST_KC / 4));  // 192 / 32 = 6
+constexpr int ST_RPP = 256 / (ST_KC / 4);          // LDS rows written per loader pass (32)
+constexpr int ST_NPASS = ST_LDS_ROWS / ST_RPP;     // 192 / 32 = 6
+constexpr int ST_RING_STFT = 4;  // bank fragment groups in flight per wave
+constexpr int ST_RING_MEL = 2;   // fewer in the Mel variant: its 64 extra accumulators need the registers
 
-template <bool MEL>
+template <bool MEL, int RING>
 __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
+  static_assert(ST_NKG % RING == 0, "ring depth must divide the fragment groups per LDS row");
   __shared__ __attribute__((aligned(16))) float lds[2][ST_LDS_ROWS * ST_PITCH];
+  __shared__ int2 rowinfo[ST_LDS_ROWS];
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
@@ -171,6 +253,12 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
   tm.extra = P.nj - 1;
   const int rows_used = tm.frame_row(m_valid - 1) + tm.extra + 1;
 
+  const int n_chunks = P.n_chunks;
+  const int total = (rt_end - rt_begin) * n_chunks;
+  if (total <= 0) return;
+
+  build_rowinfo<ST_LDS_ROWS>(rowinfo, tm, rows_used, g.B, tid);
+
   // this lane's frame
   const int fi_lane = wave * 32 + n;
   const bool valid = fi_lane < m_valid;
@@ -180,12 +268,9 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
   const int row_lane = valid ? tm.frame_row(fi_lane) : 0;
   const int a_off = row_lane * ST_PITCH + 4 * h;
 
-  const int n_chunks = P.n_chunks;
-  const int total = (rt_end - rt_begin) * n_chunks;
-  if (total <= 0) return;
   const int groups_per_rt = n_chunks * P.nj * ST_NKG;
-  const float4* __restrict__ bankp =
-      P.bank + ((long long)rt_begin * groups_per_rt) * (ST_RB * 64) + lane;
+  const f32x4* bankp =
+      reinterpret_cast<const f32x4*>(P.bank) + ((long long)rt_begin * groups_per_rt) * (ST_RB * 64) + lane;
 
   f32x16 acc[ST_RB];
 #pragma unroll
@@ -201,47 +286,84 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) macc[mb][r] = 0.f;
   }
+  __syncthreads();  // rowinfo is complete
 
-  // ---- prologue: chunk 0 into LDS buffer 0, chunk 1 into registers, first bank fragments --
-  float4 R[ST_NPASS];
-  load_chunk<ST_KC, ST_NPASS>(R, g, tm, rows_used, 0, 0, tid);
-  store_chunk<ST_KC, ST_PITCH, ST_NPASS>(R, lds[0], ST_LDS_ROWS, tid);
-  if (total > 1) load_chunk<ST_KC, ST_NPASS>(R, g, tm, rows_used, 0, (1 % n_chunks) * ST_KC, tid);
+  // ---- prologue: chunk 0 into LDS buffer 0, chunk 1 requested, first RING bank groups requested --
+  f32x4 R[ST_NPASS];
+  unsigned sel[ST_NPASS];
+  issue_chunk<ST_KC, ST_NPASS>(R, sel, g, rowinfo, 0, 0, tid);
+  wait_vm<0>(R);
+  store_chunk<ST_KC, ST_PITCH, ST_NPASS>(R, sel, lds[0], ST_LDS_ROWS, tid);
+  issue_chunk<ST_KC, ST_NPASS>(R, sel, g, rowinfo, 0, (1 % n_chunks) * ST_KC, tid);
 
-  float4 bq[ST_NKG][ST_RB];
+  f32x4 bq[RING][ST_RB];
 #pragma unroll
-  for (int kg = 0; kg < ST_NKG; ++kg)
-#pragma unroll
-    for (int rb = 0; rb < ST_RB; ++rb) bq[kg][rb] = bankp[(kg * ST_RB + rb) * 64];
-  bankp += ST_NKG * ST_RB * 64;
+  for (int s = 0; s < RING; ++s) {
+    gload16_off<0>(bq[s][0], bankp);
+    gload16_off<1024>(bq[s][1], bankp);
+    gload16_off<2048>(bq[s][2], bankp);
+    gload16_off<3072>(bq[s][3], bankp);
+    bankp += ST_RB * 64;
+  }
   __syncthreads();
+
+  // loads younger than a ring slot's request when its group starts: the other RING-1 slots,
+  // plus (for the first RING groups of a chunk) the chunk tile requested at the chunk's start
+  constexpr int W_REST = (RING - 1) * ST_RB;
+  constexpr int W_FIRST = W_REST + ST_NPASS;
 
   int c = 0;            // chunk inside the current row tile
   int rt = rt_begin;
+  const int nj = P.nj;
   for (int it = 0; it < total; ++it) {
-    if (it + 1 < total) store_chunk<ST_KC, ST_PITCH, ST_NPASS>(R, lds[(it + 1) & 1], ST_LDS_ROWS, tid);
-    if (it + 2 < total) load_chunk<ST_KC, ST_NPASS>(R, g, tm, rows_used, 0, ((it + 2) % n_chunks) * ST_KC, tid);
+    // tile of chunk it+1 (requested one chunk ago; at least RING*ST_RB bank loads are younger)
+    wait_vm<RING * ST_RB>(R);
+    store_chunk<ST_KC, ST_PITCH, ST_NPASS>(R, sel, lds[(it + 1) & 1], ST_LDS_ROWS, tid);
+    // request the tile of chunk it+2 (always: the wait counts rely on it; unused at the very end)
+    issue_chunk<ST_KC, ST_NPASS>(R, sel, g, rowinfo, 0, ((it + 2) % n_chunks) * ST_KC, tid);
+    __builtin_amdgcn_sched_barrier(0);
 
-    const float* __restrict__ A = lds[it & 1] + a_off;
-    for (int jj = 0; jj < P.nj; ++jj) {
+    const float* A = lds[it & 1] + a_off;
+    f32x4 a_cur = *reinterpret_cast<const f32x4*>(A);
+
+    auto group = [&](auto first_tag, int jj, auto kg_tag) {
+      constexpr bool kFirst = decltype(first_tag)::value;
+      constexpr int kg = decltype(kg_tag)::value;
+      constexpr int s = kg % RING;
+      // the frames fragment of the next group is read from LDS while this group's MFMAs run
+      const int nxt = kg + 1 < ST_NKG ? jj * ST_PITCH + (kg + 1) * ST_KG : (jj + 1 < nj ? (jj + 1) * ST_PITCH : 0);
+      const f32x4 a_nxt = *reinterpret_cast<const f32x4*>(A + nxt);
+      wait_vm<(kFirst && kg < RING) ? W_FIRST : W_REST>(bq[s][0], bq[s][1], bq[s][2], bq[s][3]);
 #pragma unroll
-      for (int kg = 0; kg < ST_NKG; ++kg) {
-        const float4 a = *reinterpret_cast<const float4*>(A + jj * ST_PITCH + kg * ST_KG);
-        const float av[4] = {a.x, a.y, a.z, a.w};
+      for (int e = 0; e < 4; ++e) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-#pragma unroll
-          for (int rb = 0; rb < ST_RB; ++rb) {
-            const float bv = e == 0 ? bq[kg][rb].x : e == 1 ? bq[kg][rb].y : e == 2 ? bq[kg][rb].z : bq[kg][rb].w;
-            acc[rb] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av[e], acc[rb], 0, 0, 0);
-          }
-        }
-        // refill this ring slot with the fragment ST_NKG groups ahead (the bank allocation is
-        // padded by ST_NKG groups, so the tail reads stay in bounds)
-#pragma unroll
-        for (int rb = 0; rb < ST_RB; ++rb) bq[kg][rb] = bankp[(kg * ST_RB + rb) * 64];
+        for (int rb = 0; rb < ST_RB; ++rb)
+          acc[rb] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][rb][e], a_cur[e], acc[rb], 0, 0, 0);
       }
-      bankp += ST_NKG * ST_RB * 64;
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // the LDS read first,
+      __builtin_amdgcn_sched_group_barrier(0x008, 16, 0); // then the 16 MFMAs
+      __builtin_amdgcn_sched_barrier(0);
+      // re-request this ring slot: the group RING ahead (the bank allocation is padded by
+      // ST_NKG groups, so the tail requests stay in bounds)
+      gload16_off<0>(bq[s][0], bankp);
+      gload16_off<1024>(bq[s][1], bankp);
+      gload16_off<2048>(bq[s][2], bankp);
+      gload16_off<3072>(bq[s][3], bankp);
+      bankp += ST_RB * 64;
+      __builtin_amdgcn_sched_barrier(0);
+      a_cur = a_nxt;
+    };
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    group(T_{}, 0, std::integral_constant<int, 0>{});
+    group(T_{}, 0, std::integral_constant<int, 1>{});
+    group(T_{}, 0, std::integral_constant<int, 2>{});
+    group(T_{}, 0, std::integral_constant<int, 3>{});
+    for (int jj = 1; jj < nj; ++jj) {
+      group(F_{}, jj, std::integral_constant<int, 0>{});
+      group(F_{}, jj, std::integral_constant<int, 1>{});
+      group(F_{}, jj, std::integral_constant<int, 2>{});
+      group(F_{}, jj, std::integral_constant<int, 3>{});
     }
 
     if (++c == n_chunks) {
@@ -312,6 +434,13 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
     __syncthreads();
   }
 
+  // Drain: the last tile request and the last RING bank requests are never consumed.  Their
+  // destination registers must stay reserved until the data has landed -- a register the
+  // compiler reuses while a load into it is in flight would be overwritten behind its back.
+  wait_vm<0>(R);
+#pragma unroll
+  for (int s = 0; s < RING; ++s) wait_vm<0>(bq[s][0], bq[s][1], bq[s][2], bq[s][3]);
+
   if constexpr (MEL) {
     // Nyquist-bin term (its power lives in lane n of the first lane half) and the store.
     float nyq_n = 0.f;
@@ -340,12 +469,17 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
 // 2q+1 in r = 2,3.  Only the taps inside the block's longest kernel are visited: per LDS chunk
 // the planner lists the hop-shifts [jlo, jlo+nj) that hold non-zero taps.
 // ---------------------------------------------------------------------------------------
-constexpr int CQ_NPASS = CQ_LDS_ROWS_MAX / (256 / (CQ_KC / 4));  // 512 / 64 = 8
+constexpr int CQ_RPP = 256 / (CQ_KC / 4);            // LDS rows written per loader pass (64)
+constexpr int CQ_NPASS = CQ_LDS_ROWS_MAX / CQ_RPP;  // 512 / 64 = 8
 
 __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
   extern __shared__ __attribute__((aligned(16))) float dyn_lds[];
-  float* lds0 = dyn_lds;
-  float* lds1 = dyn_lds + (size_t)P.lds_rows * CQ_PITCH;
+  __shared__ int2 rowinfo[CQ_LDS_ROWS_MAX];
+  // dynamic LDS: this row block's chunk table (read every chunk; kept out of the vector-memory
+  // path so that fetching a descriptor never waits on the streaming loads), then two tile buffers
+  int4* s_chunks = reinterpret_cast<int4*>(dyn_lds);
+  float* lds0 = dyn_lds + (size_t)P.n_chunks * 4;
+  float* lds1 = lds0 + (size_t)P.lds_rows * CQ_PITCH;
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
@@ -365,7 +499,8 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
   tm.t0 = (int)(f0 - tm.b0 * g.T);
   tm.n0 = (g.T - tm.t0) < m_valid ? (g.T - tm.t0) : m_valid;
   tm.extra = P.rb_jspan[rb] - 1;
-  const int last_row = tm.frame_row(m_valid - 1);  // a chunk with nj hop-shifts reads rows [0, last_row + nj)
+  const int rows_used = tm.frame_row(m_valid - 1) + tm.extra + 1;
+  build_rowinfo<CQ_LDS_ROWS_MAX>(rowinfo, tm, rows_used, g.B, tid);
 
   bool valid[4];
   int a_off[4];
@@ -381,60 +516,126 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
     o_off[fb] = (b * P.n_bins) * g.T + t;
   }
 
-  const CqtChunk* __restrict__ chunks = P.chunks + (long long)rb * P.n_chunks;
-  const float4* __restrict__ bankp = P.bank + P.rb_frag0[rb] * 64 + lane;
+  {
+    const int4* __restrict__ src = reinterpret_cast<const int4*>(P.chunks + (long long)rb * P.n_chunks);
+    for (int i = tid; i < P.n_chunks; i += 256) s_chunks[i] = src[i];
+  }
+  auto chunk_at = [&](int i) {
+    const int4 v = s_chunks[i];
+    CqtChunk ck;
+    ck.c0 = __builtin_amdgcn_readfirstlane(v.x);
+    ck.jlo = __builtin_amdgcn_readfirstlane(v.y);
+    ck.nj = __builtin_amdgcn_readfirstlane(v.z);
+    ck.pad_ = 0;
+    return ck;
+  };
+  const f32x4* bankp = reinterpret_cast<const f32x4*>(P.bank) + P.rb_frag0[rb] * 64 + lane;
 
   f32x4 acc[4];
 #pragma unroll
   for (int fb = 0; fb < 4; ++fb) acc[fb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  __syncthreads();  // rowinfo and the chunk table are complete
 
   const int n_chunks = P.n_chunks;
-  float4 R[CQ_NPASS];
+  f32x4 R[CQ_NPASS];
+  unsigned sel[CQ_NPASS];
   {
-    const CqtChunk ck = chunks[0];
-    load_chunk<CQ_KC, CQ_NPASS>(R, g, tm, ck.nj > 0 ? last_row + ck.nj : 0, ck.jlo, ck.c0, tid);
-    store_chunk<CQ_KC, CQ_PITCH, CQ_NPASS>(R, lds0, P.lds_rows, tid);
+    const CqtChunk ck = chunk_at(0);
+    issue_chunk<CQ_KC, CQ_NPASS>(R, sel, g, rowinfo, ck.jlo, ck.c0, tid);
+    wait_vm<0>(R);
+    store_chunk<CQ_KC, CQ_PITCH, CQ_NPASS>(R, sel, lds0, P.lds_rows, tid);
   }
-  if (n_chunks > 1) {
-    const CqtChunk ck = chunks[1];
-    load_chunk<CQ_KC, CQ_NPASS>(R, g, tm, ck.nj > 0 ? last_row + ck.nj : 0, ck.jlo, ck.c0, tid);
+  {
+    const CqtChunk ck = chunk_at(n_chunks > 1 ? 1 : 0);
+    issue_chunk<CQ_KC, CQ_NPASS>(R, sel, g, rowinfo, ck.jlo, ck.c0, tid);
   }
-  // bank fragment pipeline (the allocation is padded by CQ_PREFETCH fragments)
-  float4 b0 = bankp[0 * 64], b1 = bankp[1 * 64], b2 = bankp[2 * 64], b3 = bankp[3 * 64];
-  bankp += CQ_PREFETCH * 64;
+  // bank fragment pipeline: CQ_PREFETCH requests in flight (the allocation is padded by that many)
+  f32x4 bq[CQ_PREFETCH];
+#pragma unroll
+  for (int i = 0; i < CQ_PREFETCH; ++i) {
+    gload16(bq[i], bankp);
+    bankp += 64;
+  }
   __syncthreads();
 
+  // requests younger than the oldest fragment when its group starts: the other CQ_PREFETCH-1
+  // fragments, plus (first CQ_PREFETCH groups of a chunk) the chunk tile requested at its start
+  constexpr int W_REST = CQ_PREFETCH - 1;
+  constexpr int W_FIRST = W_REST + CQ_NPASS;
+
+  int nj_prev = CQ_PREFETCH;  // bank requests certainly issued after the pending tile request
   for (int it = 0; it < n_chunks; ++it) {
     float* cur = (it & 1) ? lds1 : lds0;
     float* nxt = (it & 1) ? lds0 : lds1;
-    if (it + 1 < n_chunks) store_chunk<CQ_KC, CQ_PITCH, CQ_NPASS>(R, nxt, P.lds_rows, tid);
-    if (it + 2 < n_chunks) {
-      const CqtChunk ck = chunks[it + 2];
-      load_chunk<CQ_KC, CQ_NPASS>(R, g, tm, ck.nj > 0 ? last_row + ck.nj : 0, ck.jlo, ck.c0, tid);
+    // the pending tile has at least CQ_PREFETCH younger bank requests unless the previous chunk
+    // was empty; the conditional full wait carries no register operands on purpose (a tied asm
+    // in each branch would make the compiler copy the in-flight registers at the merge)
+    if (nj_prev < CQ_PREFETCH) asm volatile("s_waitcnt vmcnt(0)");
+    wait_vm<CQ_PREFETCH>(R);
+    store_chunk<CQ_KC, CQ_PITCH, CQ_NPASS>(R, sel, nxt, P.lds_rows, tid);
+    {
+      const CqtChunk ck = chunk_at(it + 2 < n_chunks ? it + 2 : n_chunks - 1);
+      issue_chunk<CQ_KC, CQ_NPASS>(R, sel, g, rowinfo, ck.jlo, ck.c0, tid);
     }
-    const int nj = chunks[it].nj;
-    for (int jj = 0; jj < nj; ++jj) {
-      float4 a[4];
+    __builtin_amdgcn_sched_barrier(0);
+
+    const int nj = chunk_at(it).nj;
+    nj_prev = nj;
+    f32x4 a_cur[4];
 #pragma unroll
-      for (int fb = 0; fb < 4; ++fb)
-        a[fb] = *reinterpret_cast<const float4*>(cur + a_off[fb] + jj * CQ_PITCH);
-      const float4 bk = b0;
-      b0 = b1;
-      b1 = b2;
-      b2 = b3;
-      b3 = *bankp;
+    for (int fb = 0; fb < 4; ++fb) a_cur[fb] = *reinterpret_cast<const f32x4*>(cur + a_off[fb]);
+
+    // One fragment group: 16 taps, 16 MFMAs.  `slot` is the ring register that holds this
+    // group's bank fragment; it is a compile-time constant because a register with a load in
+    // flight must never be copied.  The planner pads every chunk to a multiple of CQ_PREFETCH
+    // groups (zero fragments), so group jj of any chunk always lives in slot jj % CQ_PREFETCH.
+    auto group = [&](auto first_tag, auto slot_tag, int jj) {
+      constexpr bool kFirst = decltype(first_tag)::value;
+      constexpr int slot = decltype(slot_tag)::value;
+      const int nxt_off = jj + 1 < nj ? (jj + 1) * CQ_PITCH : 0;
+      f32x4 a_nxt[4];
+#pragma unroll
+      for (int fb = 0; fb < 4; ++fb) a_nxt[fb] = *reinterpret_cast<const f32x4*>(cur + a_off[fb] + nxt_off);
+      wait_vm<kFirst ? W_FIRST : W_REST>(bq[slot]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+#pragma unroll
+        for (int fb = 0; fb < 4; ++fb)
+          acc[fb] = __builtin_amdgcn_mfma_f32_16x16x4f32(bq[slot][e], a_cur[fb][e], acc[fb], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);   // the 4 LDS reads first,
+      __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);  // then the 16 MFMAs
+      __builtin_amdgcn_sched_barrier(0);
+      gload16(bq[slot], bankp);
       bankp += 64;
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int fb = 0; fb < 4; ++fb) acc[fb] = __builtin_amdgcn_mfma_f32_16x16x4f32(bk.x, a[fb].x, acc[fb], 0, 0, 0);
-#pragma unroll
-      for (int fb = 0; fb < 4; ++fb) acc[fb] = __builtin_amdgcn_mfma_f32_16x16x4f32(bk.y, a[fb].y, acc[fb], 0, 0, 0);
-#pragma unroll
-      for (int fb = 0; fb < 4; ++fb) acc[fb] = __builtin_amdgcn_mfma_f32_16x16x4f32(bk.z, a[fb].z, acc[fb], 0, 0, 0);
-#pragma unroll
-      for (int fb = 0; fb < 4; ++fb) acc[fb] = __builtin_amdgcn_mfma_f32_16x16x4f32(bk.w, a[fb].w, acc[fb], 0, 0, 0);
+      for (int fb = 0; fb < 4; ++fb) a_cur[fb] = a_nxt[fb];
+    };
+    static_assert(CQ_PREFETCH == 4, "the group sequence below is written for a ring of 4");
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, 1>;
+    using S2 = std::integral_constant<int, 2>;
+    using S3 = std::integral_constant<int, 3>;
+    if (nj > 0) {
+      group(std::true_type{}, S0{}, 0);
+      group(std::true_type{}, S1{}, 1);
+      group(std::true_type{}, S2{}, 2);
+      group(std::true_type{}, S3{}, 3);
+      for (int jj = 4; jj < nj; jj += 4) {
+        group(std::false_type{}, S0{}, jj);
+        group(std::false_type{}, S1{}, jj + 1);
+        group(std::false_type{}, S2{}, jj + 2);
+        group(std::false_type{}, S3{}, jj + 3);
+      }
     }
     __syncthreads();
   }
+
+  // drain the requests that are never consumed (see the STFT kernel)
+  wait_vm<0>(R);
+#pragma unroll
+  for (int i = 0; i < CQ_PREFETCH; ++i) wait_vm<0>(bq[i]);
 
   const int bin0 = rb * (CQ_ROWS / 2) + 2 * q;
 #pragma unroll
@@ -451,11 +652,12 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
 // ---------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------
-static constexpr size_t CQ_LDS_BYTES_MAX = 2ull * CQ_LDS_ROWS_MAX * CQ_PITCH * sizeof(float);
+// LDS per workgroup is 160 KB; the CQT kernel also has 4 KB of static LDS (row table)
+static constexpr size_t CQ_DYN_LDS_MAX = 160 * 1024 - CQ_LDS_ROWS_MAX * sizeof(int2);
 
 hipError_t kernels_init() {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(cqt_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)CQ_LDS_BYTES_MAX);
+                             (int)CQ_DYN_LDS_MAX);
 }
 
 hipError_t launch_stft(const StftParams& p, bool mel, hipStream_t stream) {
@@ -469,9 +671,9 @@ hipError_t launch_stft(const StftParams& p, bool mel, hipStream_t stream) {
   }
   if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   if (mel)
-    hipLaunchKernelGGL(stft_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL((stft_kernel<true, ST_RING_MEL>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   else
-    hipLaunchKernelGGL(stft_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL((stft_kernel<false, ST_RING_STFT>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 
@@ -479,7 +681,8 @@ hipError_t launch_cqt(const CqtParams& p, hipStream_t stream) {
   const long long blocks = p.n_ft * p.n_rb;
   if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   if (p.lds_rows > CQ_LDS_ROWS_MAX) return hipErrorInvalidValue;
-  const size_t lds = 2ull * p.lds_rows * CQ_PITCH * sizeof(float);
+  const size_t lds = (size_t)p.n_chunks * sizeof(CqtChunk) + 2ull * p.lds_rows * CQ_PITCH * sizeof(float);
+  if (lds > CQ_DYN_LDS_MAX) return hipErrorInvalidValue;
   hipLaunchKernelGGL(cqt_kernel, dim3((unsigned)blocks), dim3(256), lds, stream, p);
   return hipGetLastError();
 }

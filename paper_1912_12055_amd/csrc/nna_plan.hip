@@ -351,7 +351,6 @@ void build_cqt_bank(nna_plan* p) {
   const long long K = p->K;
   p->n_rb = (2 * p->n_bins + CQ_ROWS - 1) / CQ_ROWS;
   const long long J = (K % p->hop == 0) ? K / p->hop : 0;
-  p->sliding = J >= 1 && J <= 128 && p->hop % CQ_KC == 0;
   // tap support [s, e) of every row block
   std::vector<long long> s_rb(p->n_rb), e_rb(p->n_rb);
   for (int rb = 0; rb < p->n_rb; ++rb) {
@@ -363,6 +362,13 @@ void build_cqt_bank(nna_plan* p) {
     s_rb[rb] = s;
     e_rb[rb] = e;
   }
+  // Overlapping frames share LDS rows when the hop divides the taps and is a whole number of
+  // chunks, and the longest kernel's hop-shifts (+ ring padding) leave room for at least 16
+  // frames of a tile that spans two waveforms: 16 + 2 * (shifts - 1) <= CQ_LDS_ROWS_MAX.
+  long long span_max = 0;
+  for (int rb = 0; rb < p->n_rb; ++rb) span_max = std::max(span_max, e_rb[rb] - s_rb[rb]);
+  const long long shifts_max = (ceil_div(span_max, p->hop) + 1 + CQ_PREFETCH - 1) / CQ_PREFETCH * CQ_PREFETCH;
+  p->sliding = J >= 1 && p->hop % CQ_KC == 0 && 16 + 2 * (shifts_max - 1) <= CQ_LDS_ROWS_MAX;
   if (p->sliding) {
     p->n_chunks = p->hop / CQ_KC;
   } else {
@@ -399,6 +405,10 @@ void build_cqt_bank(nna_plan* p) {
         ck.nj = (first + c) < last ? 1 : 0;
         if (ck.nj == 0) ck.c0 = 0;
       }
+      // the kernel consumes fragments four at a time (its register ring has four fixed slots):
+      // pad with all-zero fragments; pad_ keeps the number of real ones
+      ck.pad_ = ck.nj;
+      ck.nj = (ck.nj + CQ_PREFETCH - 1) / CQ_PREFETCH * CQ_PREFETCH;
       jspan = std::max(jspan, ck.nj);
       frag += ck.nj;
       p->h_chunks[(size_t)rb * p->n_chunks + c] = ck;
@@ -414,13 +424,15 @@ void build_cqt_bank(nna_plan* p) {
     long long f = p->h_rb_frag0[rb];
     for (int c = 0; c < p->n_chunks; ++c) {
       const nna::CqtChunk& ck = p->h_chunks[(size_t)rb * p->n_chunks + c];
-      for (int jj = 0; jj < ck.nj; ++jj, ++f)
+      for (int jj = 0; jj < ck.nj; ++jj, ++f) {
+        if (jj >= ck.pad_) continue;  // zero padding fragment
         for (int lane = 0; lane < 64; ++lane) {
           const int q = lane >> 4, r = lane & 15;
           const long long tap0 = (long long)(ck.jlo + jj) * (p->sliding ? p->hop : 0) + ck.c0 + 4 * q;
           float* dst = &p->h_bank[((size_t)f * 64 + lane) * 4];
           for (int e = 0; e < 4; ++e) dst[e] = (float)gen.value(rb * CQ_ROWS + r, tap0 + e);
         }
+      }
     }
   }
   double sumN = 0;
@@ -774,7 +786,8 @@ nna_status nna_plan_bank(const nna_plan* plan, double* host_out, size_t cap) {
       long long f = plan->h_rb_frag0[rb];
       for (int c = 0; c < plan->n_chunks; ++c) {
         const nna::CqtChunk& ck = plan->h_chunks[(size_t)rb * plan->n_chunks + c];
-        for (int jj = 0; jj < ck.nj; ++jj, ++f)
+        for (int jj = 0; jj < ck.nj; ++jj, ++f) {
+          if (jj >= ck.pad_) continue;  // zero padding fragment
           for (int lane = 0; lane < 64; ++lane) {
             const int q = lane >> 4, r = lane & 15;
             const long long row = (long long)rb * CQ_ROWS + r;
@@ -784,6 +797,7 @@ nna_status nna_plan_bank(const nna_plan* plan, double* host_out, size_t cap) {
               if (row < rows && tap0 + e < K) host_out[row * K + tap0 + e] = (double)v;
             }
           }
+        }
       }
     }
   } else {
