@@ -20,7 +20,7 @@ constexpr int ST_KC = 32;         // taps per LDS chunk
 constexpr int ST_PITCH = 36;      // LDS row pitch in floats (KC + 4: conflict-free b128 reads)
 constexpr int ST_KG = 8;          // taps per bank fragment (float4 per lane, two lane halves)
 constexpr int ST_NKG = ST_KC / ST_KG;
-constexpr int ST_LDS_ROWS = 192;  // LDS rows per buffer (frames + overlap rows)
+constexpr int ST_LDS_ROWS = 160;  // LDS rows per buffer (frames + overlap rows)
 constexpr int ST_MEL_BLOCKS = 4;  // 32-mel MFMA blocks per pass (128 mels)
 
 // CQT kernel: v_mfma_f32_16x16x4_f32, workgroup tile 16 bank rows (8 bins) x 256 frames.
@@ -76,6 +76,7 @@ struct CqtParams {
   const long long* rb_frag0;  // [n_rb] first fragment of the row block
   const CqtChunk* chunks;     // [n_rb][n_chunks]
   const int* rb_jspan;        // [n_rb] LDS rows added per waveform segment + 1
+  const int* rb_nchunks;      // [n_rb] chunks of the row block that hold taps (listed first in `chunks`)
   float* out;
   int n_rb;
   int n_chunks;

@@ -77,8 +77,8 @@ __device__ __forceinline__ void wait_vm(f32x4& a, f32x4& b, f32x4& c, f32x4& d) 
   asm volatile("s_waitcnt vmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
 }
 template <int N>
-__device__ __forceinline__ void wait_vm(f32x4 (&r)[6]) {
-  asm volatile("s_waitcnt vmcnt(%6)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]) : "n"(N));
+__device__ __forceinline__ void wait_vm(f32x4 (&r)[5]) {
+  asm volatile("s_waitcnt vmcnt(%5)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]) : "n"(N));
 }
 template <int N>
 __device__ __forceinline__ void wait_vm(f32x4 (&r)[8]) {
@@ -88,63 +88,89 @@ __device__ __forceinline__ void wait_vm(f32x4 (&r)[8]) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Framing loader.  LDS row r of a tile is S-row sigma of waveform b (table `rowinfo`, built
-// once per tile).  A thread fetches 4 consecutive columns of one row per pass with ONE 16-byte
-// load: the 4 padded samples i0..i0+3 always map, after mirror reflection at either end of the
-// waveform, into one window of 4 consecutive stored samples, so the load takes that window and
-// a 2-bit-per-element selector (identity 0xE4 in the interior) reorders it when the chunk is
-// written to LDS.  Selector 0xFF marks rows that do not exist (zero fill; the load then reads a
-// dummy address so that the number of issued loads is the same on every path).
+// Framing loader.  LDS row r of a tile is S-row sigma of waveform b.  A thread fetches 4
+// consecutive columns of one row per pass with ONE 16-byte load: the 4 padded samples
+// i0..i0+3 always map, after mirror reflection at either end of the waveform, into one window
+// of 4 consecutive stored samples, so the load takes that window and a 2-bit-per-element
+// selector (identity 0xE4 in the interior) reorders it when the chunk is written to LDS.
+// Selector 0xFF marks rows that do not exist (zero fill; the load then reads a dummy address so
+// that the number of issued loads is the same on every path).
+// The (pass -> row) descriptors are computed once per tile and kept in registers, so that the
+// per-chunk work in the common interior case is one add and one compare per pass.
 // ---------------------------------------------------------------------------------------
 constexpr unsigned SEL_IDENTITY = 0xE4u, SEL_ZERO = 0xFFu;
+constexpr int kNoRow = -0x40000000;  // i0 of a row that does not exist: fails the interior test for any shift
 
 __device__ __forceinline__ int reflect_clamped(int j, int L) {
   int r = j < 0 ? -j : (j >= L ? 2 * (L - 1) - j : j);
   return r < 0 ? 0 : (r >= L ? L - 1 : r);  // the clamp is only reachable under zero bank columns
 }
 
-template <int NROWS>
-__device__ __forceinline__ void build_rowinfo(int2* rowinfo, const TileMap& tm, int rows_used, long long B, int tid) {
-  for (int row = tid; row < NROWS; row += 256) {
-    long long b;
-    int sigma;
-    tm.decode(row, b, sigma);
-    const bool ok = row < rows_used && b < B;
-    rowinfo[row] = ok ? make_int2((int)b, sigma) : make_int2(-1, 0);
-  }
-}
+template <int NPASS>
+struct RowDesc {
+  const float* xb[NPASS];  // waveform of the row this thread serves in pass p (nullptr: no such row)
+  int i0[NPASS];           // padded-signal sample index of (row, this thread's first column) at shift 0, column 0
+};
 
 template <int KC, int NPASS>
-__device__ __forceinline__ void issue_chunk(f32x4 (&R)[NPASS], unsigned (&sel)[NPASS], const FrameGeom& g,
-                                            const int2* rowinfo, int jlo, int c0, int tid) {
+__device__ __forceinline__ void build_rowdesc(RowDesc<NPASS>& rd, const FrameGeom& g, const TileMap& tm,
+                                              int rows_used, int tid) {
   constexpr int V = KC / 4;
   constexpr int RPP = 256 / V;
   const int cv = tid % V, r0 = tid / V;
-  const int L = (int)g.L;
 #pragma unroll
   for (int p = 0; p < NPASS; ++p) {
-    const int2 ri = rowinfo[p * RPP + r0];
-    const float* ptr = g.x;
-    unsigned s = SEL_ZERO;
-    if (ri.x >= 0) {
-      const int i0 = (ri.y + jlo) * g.hop + c0 + cv * 4 - g.pad;
-      const float* xb = g.x + (long long)ri.x * g.L;
-      if (i0 >= 0 && i0 + 3 < L) {
-        ptr = xb + i0;
-        s = SEL_IDENTITY;
-      } else {
+    const int row = p * RPP + r0;
+    long long b;
+    int sigma;
+    tm.decode(row, b, sigma);
+    const bool ok = row < rows_used && b < g.B;
+    rd.xb[p] = ok ? g.x + b * g.L : nullptr;
+    rd.i0[p] = ok ? sigma * g.hop + cv * 4 - g.pad : kNoRow;
+  }
+}
+
+// `shift` = (first hop-shift of the chunk) * hop + (first column of the chunk).
+// Returns true (uniformly over the wave) if some lane's window touches an end of its waveform or
+// its row does not exist; only then are the selectors `sel` meaningful.  Exactly NPASS loads are
+// issued on every path, after the (load-free) address computation.
+template <int NPASS>
+__device__ __forceinline__ bool issue_chunk(f32x4 (&R)[NPASS], unsigned (&sel)[NPASS], const FrameGeom& g,
+                                            const RowDesc<NPASS>& rd, int shift) {
+  const int L = (int)g.L;
+  const float* ptr[NPASS];
+  bool special = false;
+#pragma unroll
+  for (int p = 0; p < NPASS; ++p) {
+    const int i0 = rd.i0[p] + shift;
+    ptr[p] = rd.xb[p] + i0;
+    special |= (unsigned)i0 > (unsigned)(L - 4);
+  }
+  const bool any_special = __builtin_amdgcn_ballot_w64(special) != 0;
+  if (any_special) {
+#pragma unroll
+    for (int p = 0; p < NPASS; ++p) {
+      const int i0 = rd.i0[p] + shift;
+      const float* xb = rd.xb[p];
+      unsigned s = SEL_IDENTITY;
+      if (xb == nullptr) {
+        ptr[p] = g.x;
+        s = SEL_ZERO;
+      } else if ((unsigned)i0 > (unsigned)(L - 4)) {
         const int i_0 = reflect_clamped(i0, L), i_1 = reflect_clamped(i0 + 1, L);
         const int i_2 = reflect_clamped(i0 + 2, L), i_3 = reflect_clamped(i0 + 3, L);
         int w0 = min(min(i_0, i_1), min(i_2, i_3));
         w0 = min(w0, L - 4);
-        ptr = xb + w0;
+        ptr[p] = xb + w0;
         s = (unsigned)min(i_0 - w0, 3) | ((unsigned)min(i_1 - w0, 3) << 2) | ((unsigned)min(i_2 - w0, 3) << 4) |
             ((unsigned)min(i_3 - w0, 3) << 6);
       }
+      sel[p] = s;
     }
-    gload16(R[p], ptr);
-    sel[p] = s;
   }
+#pragma unroll
+  for (int p = 0; p < NPASS; ++p) gload16(R[p], ptr[p]);
+  return any_special;
 }
 
 __device__ __forceinline__ float pick4(const f32x4& v, unsigned k) {
@@ -152,30 +178,74 @@ __device__ __forceinline__ float pick4(const f32x4& v, unsigned k) {
 }
 
 template <int KC, int PITCH, int NPASS>
-__device__ __forceinline__ void store_chunk(const f32x4 (&R)[NPASS], const unsigned (&sel)[NPASS], float* lds,
-                                            int rows_alloc, int tid) {
+__device__ __forceinline__ void store_chunk(const f32x4 (&R)[NPASS], const unsigned (&sel)[NPASS], bool special,
+                                            float* lds, int rows_alloc, int tid) {
   constexpr int V = KC / 4;
   constexpr int RPP = 256 / V;
   const int cv = tid % V, r0 = tid / V;
+  float* dst = lds + r0 * PITCH + cv * 4;
+  if (!special) {  // uniform over the wave: every window is an interior one
 #pragma unroll
-  for (int p = 0; p < NPASS; ++p) {
-    const int row = p * RPP + r0;
-    f32x4 v = R[p];
-    const unsigned s = sel[p];
-    if (s != SEL_IDENTITY) {
-      if (s == SEL_ZERO)
-        v = (f32x4){0.f, 0.f, 0.f, 0.f};
-      else
-        v = (f32x4){pick4(v, s & 3), pick4(v, (s >> 2) & 3), pick4(v, (s >> 4) & 3), pick4(v, (s >> 6) & 3)};
+    for (int p = 0; p < NPASS; ++p)
+      if (p * RPP + r0 < rows_alloc) *reinterpret_cast<f32x4*>(dst + p * RPP * PITCH) = R[p];
+  } else {
+#pragma unroll
+    for (int p = 0; p < NPASS; ++p) {
+      f32x4 v = R[p];
+      const unsigned s = sel[p];
+      if (s != SEL_IDENTITY) {
+        if (s == SEL_ZERO)
+          v = (f32x4){0.f, 0.f, 0.f, 0.f};
+        else
+          v = (f32x4){pick4(v, s & 3), pick4(v, (s >> 2) & 3), pick4(v, (s >> 4) & 3), pick4(v, (s >> 6) & 3)};
+      }
+      if (p * RPP + r0 < rows_alloc) *reinterpret_cast<f32x4*>(dst + p * RPP * PITCH) = v;
     }
-    if (row < rows_alloc) *reinterpret_cast<f32x4*>(lds + row * PITCH + cv * 4) = v;
   }
 }
 
-__device__ __forceinline__ float format_power(float pw, int fmt) {
-  if (fmt == NNA_OUT_MAGNITUDE) return sqrtf(pw);
-  if (fmt == NNA_OUT_POWER) return pw;
-  return logf(fmaxf(pw, 1e-10f));
+template <int FMT>
+__device__ __forceinline__ float format_power(float pw) {
+  if constexpr (FMT == NNA_OUT_MAGNITUDE)
+    return __builtin_amdgcn_sqrtf(pw);  // v_sqrt_f32: 1 ulp, far inside the 1e-3 tolerance
+  else if constexpr (FMT == NNA_OUT_POWER)
+    return pw;
+  else
+    return logf(fmaxf(pw, 1e-10f));
+}
+
+// Output of one finished STFT row tile: 64 (Re, Im) slots x this wave's 32 frames.  `op` points
+// at (waveform, bin 0, frame) of this lane; consecutive lanes hold consecutive frames, so every
+// store instruction writes two 128-byte runs.
+template <int FMT>
+__device__ __forceinline__ void stft_store_tile(const f32x16 (&acc)[ST_RB], float* __restrict__ op, long long T,
+                                                int slot_base, int h, int n_half) {
+  float* __restrict__ p = op + (slot_base + 2 * h) * T;
+  if (slot_base > 0 && slot_base + ST_ROWS / 2 <= n_half) {
+    // interior tile: all 64 slots exist and none is the packed DC/Nyquist slot
+#pragma unroll
+    for (int rb = 0; rb < ST_RB; ++rb)
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const float re = acc[rb][2 * u], im = acc[rb][2 * u + 1];
+        p[(rb * 16 + 4 * (u >> 1) + (u & 1)) * T] = format_power<FMT>(re * re + im * im);
+      }
+  } else {
+#pragma unroll
+    for (int rb = 0; rb < ST_RB; ++rb)
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const float re = acc[rb][2 * u], im = acc[rb][2 * u + 1];
+        const int k = rb * 16 + 4 * (u >> 1) + (u & 1);
+        const int slot = slot_base + 2 * h + k;
+        if (slot == 0) {  // slot 0 packs the two purely real bins: DC and Nyquist
+          op[0] = format_power<FMT>(re * re);
+          op[n_half * T] = format_power<FMT>(im * im);
+        } else if (slot < n_half) {
+          p[k * T] = format_power<FMT>(re * re + im * im);
+        }
+      }
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -194,7 +264,8 @@ __device__ __forceinline__ float format_power(float pw, int fmt) {
 // fragments (requested RING groups earlier) and re-requesting its ring slot afterwards.
 // ---------------------------------------------------------------------------------------
 constexpr int ST_RPP = 256 / (ST_KC / 4);          // LDS rows written per loader pass (32)
-constexpr int ST_NPASS = ST_LDS_ROWS / ST_RPP;     // 192 / 32 = 6
+constexpr int ST_NPASS = ST_LDS_ROWS / ST_RPP;     // 160 / 32 = 5
+constexpr int ST_RG = 4;         // row tiles one STFT workgroup handles (amortises its start-up, re-uses its frames)
 constexpr int ST_RING_STFT = 4;  // bank fragment groups in flight per wave
 constexpr int ST_RING_MEL = 2;   // fewer in the Mel variant: its 64 extra accumulators need the registers
 
@@ -202,7 +273,6 @@ template <bool MEL, int RING>
 __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
   static_assert(ST_NKG % RING == 0, "ring depth must divide the fragment groups per LDS row");
   __shared__ __attribute__((aligned(16))) float lds[2][ST_LDS_ROWS * ST_PITCH];
-  __shared__ int2 rowinfo[ST_LDS_ROWS];
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
@@ -218,28 +288,30 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
     rt_end = P.mel_pass_rt[2 * pass + 1];
   } else {
     // XCD-aware order: workgroup ids are dealt round-robin to the 8 XCDs.  Each XCD walks its
-    // own contiguous range of frame tiles in groups of 64; inside a group the row tile is the
-    // slow index, so the ~64 workgroups resident on an XCD share one 1 MB bank tile in its L2.
+    // own contiguous range of frame tiles in groups of 64; inside a group the row group (ST_RG
+    // consecutive row tiles handled by one workgroup) is the slow index, so the ~64 workgroups
+    // resident on an XCD stream the same bank tiles through its L2.
     constexpr int GROUP = 64;
+    const int n_rg = (P.n_rt + ST_RG - 1) / ST_RG;
     const long long bid = blockIdx.x;
     const int xcd = (int)(bid & 7);
     const long long idx = bid >> 3;
     const long long ft_per_xcd = (P.n_ft + 7) / 8;
-    const long long per_group = (long long)GROUP * P.n_rt;
+    const long long per_group = (long long)GROUP * n_rg;
     const long long grp = idx / per_group;
     const int rem = (int)(idx - grp * per_group);
     const long long grp_first = grp * GROUP;
     long long grp_size = ft_per_xcd - grp_first;
     if (grp_size > GROUP) grp_size = GROUP;
     if (grp_size <= 0) return;
-    const int rt = rem / (int)grp_size;
-    const int fi = rem - rt * (int)grp_size;
-    if (rt >= P.n_rt) return;
+    const int rg = rem / (int)grp_size;
+    const int fi = rem - rg * (int)grp_size;
+    if (rg >= n_rg) return;
     const long long ft_local = grp_first + fi;
     ft = xcd * ft_per_xcd + ft_local;
     if (ft >= P.n_ft) return;
-    rt_begin = rt;
-    rt_end = rt + 1;
+    rt_begin = rg * ST_RG;
+    rt_end = rt_begin + ST_RG < P.n_rt ? rt_begin + ST_RG : P.n_rt;
   }
 
   const FrameGeom& g = P.g;
@@ -257,7 +329,8 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
   const int total = (rt_end - rt_begin) * n_chunks;
   if (total <= 0) return;
 
-  build_rowinfo<ST_LDS_ROWS>(rowinfo, tm, rows_used, g.B, tid);
+  RowDesc<ST_NPASS> rd;
+  build_rowdesc<ST_KC, ST_NPASS>(rd, g, tm, rows_used, tid);
 
   // this lane's frame
   const int fi_lane = wave * 32 + n;
@@ -286,15 +359,13 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) macc[mb][r] = 0.f;
   }
-  __syncthreads();  // rowinfo is complete
-
   // ---- prologue: chunk 0 into LDS buffer 0, chunk 1 requested, first RING bank groups requested --
   f32x4 R[ST_NPASS];
   unsigned sel[ST_NPASS];
-  issue_chunk<ST_KC, ST_NPASS>(R, sel, g, rowinfo, 0, 0, tid);
+  bool special = issue_chunk<ST_NPASS>(R, sel, g, rd, 0);
   wait_vm<0>(R);
-  store_chunk<ST_KC, ST_PITCH, ST_NPASS>(R, sel, lds[0], ST_LDS_ROWS, tid);
-  issue_chunk<ST_KC, ST_NPASS>(R, sel, g, rowinfo, 0, (1 % n_chunks) * ST_KC, tid);
+  store_chunk<ST_KC, ST_PITCH, ST_NPASS>(R, sel, special, lds[0], ST_LDS_ROWS, tid);
+  special = issue_chunk<ST_NPASS>(R, sel, g, rd, (1 % n_chunks) * ST_KC);
 
   f32x4 bq[RING][ST_RB];
 #pragma unroll
@@ -318,9 +389,9 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
   for (int it = 0; it < total; ++it) {
     // tile of chunk it+1 (requested one chunk ago; at least RING*ST_RB bank loads are younger)
     wait_vm<RING * ST_RB>(R);
-    store_chunk<ST_KC, ST_PITCH, ST_NPASS>(R, sel, lds[(it + 1) & 1], ST_LDS_ROWS, tid);
+    store_chunk<ST_KC, ST_PITCH, ST_NPASS>(R, sel, special, lds[(it + 1) & 1], ST_LDS_ROWS, tid);
     // request the tile of chunk it+2 (always: the wait counts rely on it; unused at the very end)
-    issue_chunk<ST_KC, ST_NPASS>(R, sel, g, rowinfo, 0, ((it + 2) % n_chunks) * ST_KC, tid);
+    special = issue_chunk<ST_NPASS>(R, sel, g, rd, ((it + 2) % n_chunks) * ST_KC);
     __builtin_amdgcn_sched_barrier(0);
 
     const float* A = lds[it & 1] + a_off;
@@ -335,19 +406,31 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
       const f32x4 a_nxt = *reinterpret_cast<const f32x4*>(A + nxt);
       wait_vm<(kFirst && kg < RING) ? W_FIRST : W_REST>(bq[s][0], bq[s][1], bq[s][2], bq[s][3]);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
+      for (int e = 0; e < 3; ++e) {
 #pragma unroll
         for (int rb = 0; rb < ST_RB; ++rb)
           acc[rb] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][rb][e], a_cur[e], acc[rb], 0, 0, 0);
       }
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // the LDS read first,
-      __builtin_amdgcn_sched_group_barrier(0x008, 16, 0); // then the 16 MFMAs
+      __builtin_amdgcn_sched_group_barrier(0x008, 12, 0); // then 12 MFMAs
       __builtin_amdgcn_sched_barrier(0);
-      // re-request this ring slot: the group RING ahead (the bank allocation is padded by
-      // ST_NKG groups, so the tail requests stay in bounds)
+      // The last four MFMAs each free one fragment register quad; its re-request (the group RING
+      // ahead; the bank allocation is padded by ST_NKG groups, so the tail requests stay in bounds)
+      // is issued right behind it, in the shadow of the 64-cycle MFMA.
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][0][3], a_cur[3], acc[0], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
       gload16_off<0>(bq[s][0], bankp);
+      __builtin_amdgcn_sched_barrier(0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][1][3], a_cur[3], acc[1], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
       gload16_off<1024>(bq[s][1], bankp);
+      __builtin_amdgcn_sched_barrier(0);
+      acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][2][3], a_cur[3], acc[2], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
       gload16_off<2048>(bq[s][2], bankp);
+      __builtin_amdgcn_sched_barrier(0);
+      acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][3][3], a_cur[3], acc[3], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
       gload16_off<3072>(bq[s][3], bankp);
       bankp += ST_RB * 64;
       __builtin_amdgcn_sched_barrier(0);
@@ -371,23 +454,14 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
       c = 0;
       const int slot_base = rt * (ST_ROWS / 2);
       if constexpr (!MEL) {
-        const long long F = P.n_half + 1;
-        float* __restrict__ op = P.out + (b_lane * F) * g.T + t_lane;
-#pragma unroll
-        for (int rb = 0; rb < ST_RB; ++rb) {
-#pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            const float re = acc[rb][2 * u], im = acc[rb][2 * u + 1];
-            const int slot = slot_base + rb * 16 + 4 * (u >> 1) + 2 * h + (u & 1);
-            if (valid) {
-              if (slot == 0) {  // slot 0 packs the two purely real bins: DC and Nyquist
-                op[0] = format_power(re * re, P.fmt);
-                op[(long long)P.n_half * g.T] = format_power(im * im, P.fmt);
-              } else if (slot < P.n_half) {
-                op[(long long)slot * g.T] = format_power(re * re + im * im, P.fmt);
-              }
-            }
-          }
+        if (valid) {
+          float* __restrict__ op = P.out + (b_lane * (P.n_half + 1)) * g.T + t_lane;
+          if (P.fmt == NNA_OUT_MAGNITUDE)
+            stft_store_tile<NNA_OUT_MAGNITUDE>(acc, op, g.T, slot_base, h, P.n_half);
+          else if (P.fmt == NNA_OUT_POWER)
+            stft_store_tile<NNA_OUT_POWER>(acc, op, g.T, slot_base, h, P.n_half);
+          else
+            stft_store_tile<NNA_OUT_LOG>(acc, op, g.T, slot_base, h, P.n_half);
         }
       } else {
         const unsigned char* __restrict__ maskp = P.mel_mask + ((long long)pass * P.n_rt + rt) * ST_RB;
@@ -403,9 +477,9 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
             if (rb == 0 && u == 0 && h == 0 && slot_base == 0) {  // DC / Nyquist slot
               v = re * re;
               nyq = im * im;
-              if (P.fmt == 1) nyq = sqrtf(nyq);
+              if (P.fmt == 1) nyq = __builtin_amdgcn_sqrtf(nyq);
             }
-            pw[u] = P.fmt == 1 ? sqrtf(v) : v;
+            pw[u] = P.fmt == 1 ? __builtin_amdgcn_sqrtf(v) : v;
           }
           const unsigned mask = maskp[rb];
 #pragma unroll
@@ -474,7 +548,6 @@ constexpr int CQ_NPASS = CQ_LDS_ROWS_MAX / CQ_RPP;  // 512 / 64 = 8
 
 __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
   extern __shared__ __attribute__((aligned(16))) float dyn_lds[];
-  __shared__ int2 rowinfo[CQ_LDS_ROWS_MAX];
   // dynamic LDS: this row block's chunk table (read every chunk; kept out of the vector-memory
   // path so that fetching a descriptor never waits on the streaming loads), then two tile buffers
   int4* s_chunks = reinterpret_cast<int4*>(dyn_lds);
@@ -500,7 +573,8 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
   tm.n0 = (g.T - tm.t0) < m_valid ? (g.T - tm.t0) : m_valid;
   tm.extra = P.rb_jspan[rb] - 1;
   const int rows_used = tm.frame_row(m_valid - 1) + tm.extra + 1;
-  build_rowinfo<CQ_LDS_ROWS_MAX>(rowinfo, tm, rows_used, g.B, tid);
+  RowDesc<CQ_NPASS> rd;
+  build_rowdesc<CQ_KC, CQ_NPASS>(rd, g, tm, rows_used, tid);
 
   bool valid[4];
   int a_off[4];
@@ -516,9 +590,10 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
     o_off[fb] = (b * P.n_bins) * g.T + t;
   }
 
+  const int n_chunks = P.rb_nchunks[rb];  // >= 1, every listed chunk holds a whole ring of fragments
   {
     const int4* __restrict__ src = reinterpret_cast<const int4*>(P.chunks + (long long)rb * P.n_chunks);
-    for (int i = tid; i < P.n_chunks; i += 256) s_chunks[i] = src[i];
+    for (int i = tid; i < n_chunks; i += 256) s_chunks[i] = src[i];
   }
   auto chunk_at = [&](int i) {
     const int4 v = s_chunks[i];
@@ -534,20 +609,20 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
   f32x4 acc[4];
 #pragma unroll
   for (int fb = 0; fb < 4; ++fb) acc[fb] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  __syncthreads();  // rowinfo and the chunk table are complete
+  __syncthreads();  // the chunk table is complete
 
-  const int n_chunks = P.n_chunks;
   f32x4 R[CQ_NPASS];
   unsigned sel[CQ_NPASS];
+  bool special;
   {
     const CqtChunk ck = chunk_at(0);
-    issue_chunk<CQ_KC, CQ_NPASS>(R, sel, g, rowinfo, ck.jlo, ck.c0, tid);
+    special = issue_chunk<CQ_NPASS>(R, sel, g, rd, ck.jlo * g.hop + ck.c0);
     wait_vm<0>(R);
-    store_chunk<CQ_KC, CQ_PITCH, CQ_NPASS>(R, sel, lds0, P.lds_rows, tid);
+    store_chunk<CQ_KC, CQ_PITCH, CQ_NPASS>(R, sel, special, lds0, P.lds_rows, tid);
   }
   {
     const CqtChunk ck = chunk_at(n_chunks > 1 ? 1 : 0);
-    issue_chunk<CQ_KC, CQ_NPASS>(R, sel, g, rowinfo, ck.jlo, ck.c0, tid);
+    special = issue_chunk<CQ_NPASS>(R, sel, g, rd, ck.jlo * g.hop + ck.c0);
   }
   // bank fragment pipeline: CQ_PREFETCH requests in flight (the allocation is padded by that many)
   f32x4 bq[CQ_PREFETCH];
@@ -563,24 +638,19 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
   constexpr int W_REST = CQ_PREFETCH - 1;
   constexpr int W_FIRST = W_REST + CQ_NPASS;
 
-  int nj_prev = CQ_PREFETCH;  // bank requests certainly issued after the pending tile request
   for (int it = 0; it < n_chunks; ++it) {
     float* cur = (it & 1) ? lds1 : lds0;
     float* nxt = (it & 1) ? lds0 : lds1;
-    // the pending tile has at least CQ_PREFETCH younger bank requests unless the previous chunk
-    // was empty; the conditional full wait carries no register operands on purpose (a tied asm
-    // in each branch would make the compiler copy the in-flight registers at the merge)
-    if (nj_prev < CQ_PREFETCH) asm volatile("s_waitcnt vmcnt(0)");
+    // the pending tile has at least CQ_PREFETCH younger bank requests (no listed chunk is empty)
     wait_vm<CQ_PREFETCH>(R);
-    store_chunk<CQ_KC, CQ_PITCH, CQ_NPASS>(R, sel, nxt, P.lds_rows, tid);
+    store_chunk<CQ_KC, CQ_PITCH, CQ_NPASS>(R, sel, special, nxt, P.lds_rows, tid);
     {
       const CqtChunk ck = chunk_at(it + 2 < n_chunks ? it + 2 : n_chunks - 1);
-      issue_chunk<CQ_KC, CQ_NPASS>(R, sel, g, rowinfo, ck.jlo, ck.c0, tid);
+      special = issue_chunk<CQ_NPASS>(R, sel, g, rd, ck.jlo * g.hop + ck.c0);
     }
     __builtin_amdgcn_sched_barrier(0);
 
-    const int nj = chunk_at(it).nj;
-    nj_prev = nj;
+    const int nj = chunk_at(it).nj;  // a positive multiple of CQ_PREFETCH
     f32x4 a_cur[4];
 #pragma unroll
     for (int fb = 0; fb < 4; ++fb) a_cur[fb] = *reinterpret_cast<const f32x4*>(cur + a_off[fb]);
@@ -617,7 +687,7 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
     using S1 = std::integral_constant<int, 1>;
     using S2 = std::integral_constant<int, 2>;
     using S3 = std::integral_constant<int, 3>;
-    if (nj > 0) {
+    {
       group(std::true_type{}, S0{}, 0);
       group(std::true_type{}, S1{}, 1);
       group(std::true_type{}, S2{}, 2);
@@ -642,18 +712,25 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
   for (int fb = 0; fb < 4; ++fb) {
     if (!valid[fb]) continue;
     float* __restrict__ op = P.out + o_off[fb];
+    const float p0 = acc[fb][0] * acc[fb][0] + acc[fb][1] * acc[fb][1];
+    const float p1 = acc[fb][2] * acc[fb][2] + acc[fb][3] * acc[fb][3];
+    const int f = P.fmt;
     if (bin0 < P.n_bins)
-      op[(long long)bin0 * g.T] = format_power(acc[fb][0] * acc[fb][0] + acc[fb][1] * acc[fb][1], P.fmt);
+      op[(long long)bin0 * g.T] = f == NNA_OUT_MAGNITUDE ? format_power<NNA_OUT_MAGNITUDE>(p0)
+                                  : f == NNA_OUT_POWER   ? p0
+                                                         : format_power<NNA_OUT_LOG>(p0);
     if (bin0 + 1 < P.n_bins)
-      op[(long long)(bin0 + 1) * g.T] = format_power(acc[fb][2] * acc[fb][2] + acc[fb][3] * acc[fb][3], P.fmt);
+      op[(long long)(bin0 + 1) * g.T] = f == NNA_OUT_MAGNITUDE ? format_power<NNA_OUT_MAGNITUDE>(p1)
+                                        : f == NNA_OUT_POWER   ? p1
+                                                               : format_power<NNA_OUT_LOG>(p1);
   }
 }
 
 // ---------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------
-// LDS per workgroup is 160 KB; the CQT kernel also has 4 KB of static LDS (row table)
-static constexpr size_t CQ_DYN_LDS_MAX = 160 * 1024 - CQ_LDS_ROWS_MAX * sizeof(int2);
+// LDS per workgroup is 160 KB
+static constexpr size_t CQ_DYN_LDS_MAX = 160 * 1024;
 
 hipError_t kernels_init() {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(cqt_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -667,7 +744,7 @@ hipError_t launch_stft(const StftParams& p, bool mel, hipStream_t stream) {
   } else {
     const long long ft_per_xcd = (p.n_ft + 7) / 8;
     const long long groups = (ft_per_xcd + 63) / 64;
-    blocks = 8 * groups * 64 * p.n_rt;
+    blocks = 8 * groups * 64 * ((p.n_rt + ST_RG - 1) / ST_RG);
   }
   if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   if (mel)

@@ -49,7 +49,7 @@ struct nna_plan {
   std::vector<long long> Nk, sk;
   std::vector<long long> h_rb_frag0;
   std::vector<nna::CqtChunk> h_chunks;
-  std::vector<int> h_rb_jspan;
+  std::vector<int> h_rb_jspan, h_rb_nchunks;
   int max_jspan = 1;
 
   double exec_flops = 0, alg_flops = 0;
@@ -67,6 +67,7 @@ struct nna_plan {
   long long* d_rb_frag0 = nullptr;
   nna::CqtChunk* d_chunks = nullptr;
   int* d_rb_jspan = nullptr;
+  int* d_rb_nchunks = nullptr;
 };
 
 namespace {
@@ -379,6 +380,7 @@ void build_cqt_bank(nna_plan* p) {
   }
   p->h_chunks.assign((size_t)p->n_rb * p->n_chunks, nna::CqtChunk{0, 0, 0, 0});
   p->h_rb_jspan.assign(p->n_rb, 1);
+  p->h_rb_nchunks.assign(p->n_rb, 0);
   p->h_rb_frag0.assign(p->n_rb, 0);
   long long frag = 0;
   p->max_jspan = 1;
@@ -411,7 +413,8 @@ void build_cqt_bank(nna_plan* p) {
       ck.nj = (ck.nj + CQ_PREFETCH - 1) / CQ_PREFETCH * CQ_PREFETCH;
       jspan = std::max(jspan, ck.nj);
       frag += ck.nj;
-      p->h_chunks[(size_t)rb * p->n_chunks + c] = ck;
+      // only chunks that hold taps are listed (compacted to the front of the row block's table)
+      if (ck.nj > 0) p->h_chunks[(size_t)rb * p->n_chunks + p->h_rb_nchunks[rb]++] = ck;
     }
     p->h_rb_jspan[rb] = jspan;
     p->max_jspan = std::max(p->max_jspan, jspan);
@@ -422,7 +425,7 @@ void build_cqt_bank(nna_plan* p) {
   CqtKernelGen gen(p);
   for (int rb = 0; rb < p->n_rb; ++rb) {
     long long f = p->h_rb_frag0[rb];
-    for (int c = 0; c < p->n_chunks; ++c) {
+    for (int c = 0; c < p->h_rb_nchunks[rb]; ++c) {
       const nna::CqtChunk& ck = p->h_chunks[(size_t)rb * p->n_chunks + c];
       for (int jj = 0; jj < ck.nj; ++jj, ++f) {
         if (jj >= ck.pad_) continue;  // zero padding fragment
@@ -465,6 +468,7 @@ nna_status finish_plan(nna_plan* p, nna_plan** out, const MelDeviceLayout* mel) 
       s = upload(&p->d_rb_frag0, p->h_rb_frag0.data(), p->h_rb_frag0.size() * sizeof(long long), "cqt fragment table");
       if (s == NNA_OK) s = upload(&p->d_chunks, p->h_chunks.data(), p->h_chunks.size() * sizeof(nna::CqtChunk), "cqt chunk table");
       if (s == NNA_OK) s = upload(&p->d_rb_jspan, p->h_rb_jspan.data(), p->h_rb_jspan.size() * sizeof(int), "cqt span table");
+      if (s == NNA_OK) s = upload(&p->d_rb_nchunks, p->h_rb_nchunks.data(), p->h_rb_nchunks.size() * sizeof(int), "cqt chunk count table");
     }
     if (s != NNA_OK) {
       const std::string keep = g_err;
@@ -522,7 +526,9 @@ nna_status check_call(const nna_plan* plan, int kind, const float* x, long long 
   if (B < 1) return fail(NNA_ERR_SHAPE, "B must be >= 1");
   const long long T = frames_of(plan, L);
   if (T < 1) return fail(NNA_ERR_SHAPE, plan->center ? "L must exceed the reflection padding (K/2)" : "L is shorter than one window");
-  if (T > 0x7fffffffLL / 4 || L > (1LL << 40) || B > (1LL << 40) / T) return fail(NNA_ERR_SHAPE, "batch too large");
+  // the kernels index samples of one waveform with 32-bit integers (padded index < L + 2K)
+  if (T > 0x7fffffffLL / 4 || L > 0x7fffffffLL - 4LL * plan->K - 64 || B > 0x7fffffffLL || B > (1LL << 40) / T)
+    return fail(NNA_ERR_SHAPE, "batch too large");
   *T_out = T;
   return NNA_OK;
 }
@@ -742,6 +748,7 @@ nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long l
   P.rb_frag0 = plan->d_rb_frag0;
   P.chunks = plan->d_chunks;
   P.rb_jspan = plan->d_rb_jspan;
+  P.rb_nchunks = plan->d_rb_nchunks;
   P.out = out_dev;
   P.n_rb = plan->n_rb;
   P.n_chunks = plan->n_chunks;
@@ -784,7 +791,7 @@ nna_status nna_plan_bank(const nna_plan* plan, double* host_out, size_t cap) {
   if (plan->kind == NNA_KIND_CQT) {
     for (int rb = 0; rb < plan->n_rb; ++rb) {
       long long f = plan->h_rb_frag0[rb];
-      for (int c = 0; c < plan->n_chunks; ++c) {
+      for (int c = 0; c < plan->h_rb_nchunks[rb]; ++c) {
         const nna::CqtChunk& ck = plan->h_chunks[(size_t)rb * plan->n_chunks + c];
         for (int jj = 0; jj < ck.nj; ++jj, ++f) {
           if (jj >= ck.pad_) continue;  // zero padding fragment
@@ -904,6 +911,7 @@ void nna_plan_destroy(nna_plan* plan) {
       (void)hipFree(plan->d_rb_frag0);
       (void)hipFree(plan->d_chunks);
       (void)hipFree(plan->d_rb_jspan);
+      (void)hipFree(plan->d_rb_nchunks);
     }
   }
   delete plan;

@@ -4,11 +4,8 @@ The kernels request their streaming loads through inline asm and wait for them w
 ``s_waitcnt vmcnt(N)``; the compiler therefore does not know which registers have a load in
 flight.  It is free to copy, spill or reuse such a register, and any of those would read or
 clobber data that has not landed yet.  This module compiles the kernels to assembly and scans
-every kernel linearly: between a ``global_load`` and the ``s_waitcnt vmcnt`` that retires it no
-other instruction may name the load's destination registers.  (Control flow is ignored, which
-makes the check conservative inside straight-line code and blind to loop back-edges; the
-sources keep the in-flight registers in loop-carried variables with fixed roles for that
-reason.)
+every kernel's control-flow graph: between a ``global_load`` and the ``s_waitcnt vmcnt`` that
+retires it no other instruction, on any path, may name the load's destination registers.
 """
 from __future__ import annotations
 
@@ -32,39 +29,105 @@ def _regs(text: str) -> set:
     return out
 
 
+_MAX_VARIANTS = 256
+
+
+def _step(pending: tuple, lineno: int, t: str, op: str, bad: dict) -> tuple:
+    """Apply one instruction to one in-flight list (tuple of frozenset(dst regs), oldest first).
+
+    Stores also count in vmcnt; leaving them out of the model only makes it stricter (a wait then
+    retires fewer loads in the model than on the machine)."""
+    if op == "s_waitcnt":
+        m = re.search(r"vmcnt\((\d+)\)", t)
+        if m:
+            n = int(m.group(1))
+            if n == 0:
+                return ()
+            if n < len(pending):
+                return pending[len(pending) - n:]
+        return pending
+    if op.startswith("global_load") or op.startswith("buffer_load"):
+        ops = t[len(op):].split(",")
+        dst, src = _regs(ops[0]), _regs(",".join(ops[1:]))
+        for rs in pending:
+            if rs & (src | dst):
+                bad.setdefault(lineno, f"{t}   [touches v{sorted(rs & (src | dst))}, destination of a load in flight]")
+        return pending + (frozenset(dst),)
+    touched = _regs(t)
+    for rs in pending:
+        if rs & touched:
+            bad.setdefault(lineno, f"{t}   [v{sorted(rs & touched)} is the destination of a load in flight]")
+            break
+    return pending
+
+
 def check_kernel(lines) -> list:
-    """Violations [(line_no, text)] of one kernel's instruction list."""
-    pending = []  # (line_no, destination registers), oldest first; stores hold an empty set
-    bad = []
+    """Violations [(line_no, text)] of one kernel.
+
+    The kernel is split into basic blocks; the set of possible in-flight load lists is propagated
+    along every control-flow edge to a fixed point (loads retire in order, so a list is trimmed to
+    its N youngest entries by ``s_waitcnt vmcnt(N)``)."""
+    insts = []  # (lineno, text, op)
+    labels = {}
     for i, raw in enumerate(lines, 1):
         t = raw.split(";")[0].strip()
-        if not t or t.endswith(":") or t.startswith("."):
+        if not t:
             continue
-        op = t.split()[0]
-        if op == "s_waitcnt":
-            m = re.search(r"vmcnt\((\d+)\)", t)
-            if m:
-                n = int(m.group(1))
-                pending = pending[len(pending) - n:] if 0 < n < len(pending) else ([] if n == 0 else pending)
+        if t.endswith(":"):
+            labels[t[:-1]] = len(insts)
             continue
-        if op.startswith("global_load") or op.startswith("buffer_load"):
-            ops = t[len(op):].split(",")
-            dst, src = _regs(ops[0]), _regs(",".join(ops[1:]))
-            for ln, rs in pending:
-                if rs & (src | dst):
-                    bad.append((i, f"{t}   [touches registers of the load at line {ln}]"))
-            pending.append((i, dst))
+        if t.startswith("."):
             continue
-        if op.startswith("global_store") or op.startswith("buffer_store"):
-            pending.append((i, set()))  # stores count in vmcnt as well
-        touched = _regs(t)
-        for ln, rs in pending:
-            if rs & touched:
-                bad.append((i, f"{t}   [v{sorted(rs & touched)} in flight since line {ln}]"))
-                break
+        insts.append((i, t, t.split()[0]))
+    if not insts:
+        return []
+    # basic block leaders
+    leaders = {0} | set(labels.values())
+    for k, (_, t, op) in enumerate(insts):
+        if op.startswith("s_cbranch") or op in ("s_branch", "s_endpgm", "s_setpc_b64"):
+            leaders.add(k + 1)
+    leaders = sorted(x for x in leaders if x < len(insts))
+    block_of = {}
+    for bi, start in enumerate(leaders):
+        end = leaders[bi + 1] if bi + 1 < len(leaders) else len(insts)
+        block_of[start] = (start, end)
+    succs = {}
+    for start, (s0, e0) in block_of.items():
+        _, t, op = insts[e0 - 1]
+        out = []
         if op == "s_endpgm":
-            pending = []
-    return bad
+            pass
+        elif op == "s_branch":
+            out.append(labels[t.split()[1]])
+        elif op.startswith("s_cbranch"):
+            out.append(labels[t.split()[1]])
+            if e0 < len(insts):
+                out.append(e0)
+        elif e0 < len(insts):
+            out.append(e0)
+        succs[start] = out
+    bad = {}
+    entry_states = {0: {()}}
+    work = [0]
+    while work:
+        start = work.pop()
+        s0, e0 = block_of[start]
+        outs = set()
+        for pend in entry_states[start]:
+            cur = pend
+            for k in range(s0, e0):
+                ln, t, op = insts[k]
+                cur = _step(cur, ln, t, op, bad)
+            outs.add(cur)
+        for nxt in succs[start]:
+            have = entry_states.setdefault(nxt, set())
+            new = outs - have
+            if new:
+                have |= new
+                if len(have) > _MAX_VARIANTS:
+                    raise RuntimeError("in-flight load analysis did not converge")
+                work.append(nxt)
+    return sorted(bad.items())
 
 
 def compile_to_asm(extra_flags=()) -> str:
@@ -86,8 +149,8 @@ def check_all(asm_text: str) -> dict:
     for k, (i, name) in enumerate(starts):
         j = starts[k + 1][0] if k + 1 < len(starts) else len(src)
         body = src[i:j]
-        end = next((x for x, l in enumerate(body) if "s_endpgm" in l), len(body) - 1)
-        res[name] = check_kernel(body[:end + 1])
+        end = next((x for x, l in enumerate(body) if l.startswith(".Lfunc_end")), len(body))
+        res[name] = check_kernel(body[:end])
     return res
 
 
