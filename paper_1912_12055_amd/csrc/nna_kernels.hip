@@ -68,6 +68,12 @@ template <int OFF>
 __device__ __forceinline__ void gload16_off(f32x4& dst, const void* p) {
   asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(dst) : "v"(p), "n"(OFF));
 }
+// scalar base + per-lane 32-bit offset form: no 64-bit address registers to read, so the
+// request costs the issuing wave (almost) no MFMA issue time
+template <int OFF>
+__device__ __forceinline__ void gload16_s(f32x4& dst, unsigned lane_off, const void* sbase) {
+  asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3" : "=v"(dst) : "v"(lane_off), "s"(sbase), "n"(OFF));
+}
 template <int N>
 __device__ __forceinline__ void wait_vm(f32x4& a) {
   asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a) : "n"(N));
@@ -131,14 +137,13 @@ __device__ __forceinline__ void build_rowdesc(RowDesc<NPASS>& rd, const FrameGeo
 }
 
 // `shift` = (first hop-shift of the chunk) * hop + (first column of the chunk).
-// Returns true (uniformly over the wave) if some lane's window touches an end of its waveform or
-// its row does not exist; only then are the selectors `sel` meaningful.  Exactly NPASS loads are
-// issued on every path, after the (load-free) address computation.
+// prepare_chunk computes the NPASS load addresses of a chunk (no memory access).  It returns
+// true (uniformly over the wave) if some lane's window touches an end of its waveform or its row
+// does not exist; only then are the selectors `sel` meaningful.
 template <int NPASS>
-__device__ __forceinline__ bool issue_chunk(f32x4 (&R)[NPASS], unsigned (&sel)[NPASS], const FrameGeom& g,
-                                            const RowDesc<NPASS>& rd, int shift) {
+__device__ __forceinline__ bool prepare_chunk(const float* (&ptr)[NPASS], unsigned (&sel)[NPASS], const FrameGeom& g,
+                                              const RowDesc<NPASS>& rd, int shift) {
   const int L = (int)g.L;
-  const float* ptr[NPASS];
   bool special = false;
 #pragma unroll
   for (int p = 0; p < NPASS; ++p) {
@@ -168,6 +173,15 @@ __device__ __forceinline__ bool issue_chunk(f32x4 (&R)[NPASS], unsigned (&sel)[N
       sel[p] = s;
     }
   }
+  return any_special;
+}
+
+// Exactly NPASS loads are issued on every path.
+template <int NPASS>
+__device__ __forceinline__ bool issue_chunk(f32x4 (&R)[NPASS], unsigned (&sel)[NPASS], const FrameGeom& g,
+                                            const RowDesc<NPASS>& rd, int shift) {
+  const float* ptr[NPASS];
+  const bool any_special = prepare_chunk<NPASS>(ptr, sel, g, rd, shift);
 #pragma unroll
   for (int p = 0; p < NPASS; ++p) gload16(R[p], ptr[p]);
   return any_special;
@@ -342,8 +356,6 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
   const int a_off = row_lane * ST_PITCH + 4 * h;
 
   const int groups_per_rt = n_chunks * P.nj * ST_NKG;
-  const f32x4* bankp =
-      reinterpret_cast<const f32x4*>(P.bank) + ((long long)rt_begin * groups_per_rt) * (ST_RB * 64) + lane;
 
   f32x16 acc[ST_RB];
 #pragma unroll
@@ -367,86 +379,100 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
   store_chunk<ST_KC, ST_PITCH, ST_NPASS>(R, sel, special, lds[0], ST_LDS_ROWS, tid);
   special = issue_chunk<ST_NPASS>(R, sel, g, rd, (1 % n_chunks) * ST_KC);
 
+  // The bank is streamed with scalar-base loads: `bank_s` is uniform, each lane adds its 16 bytes.
+  const unsigned lane_off = (unsigned)lane * 16u;
+  const char* bank_s = reinterpret_cast<const char*>(P.bank) + ((long long)rt_begin * groups_per_rt) * (ST_RB * 64 * 16);
   f32x4 bq[RING][ST_RB];
 #pragma unroll
   for (int s = 0; s < RING; ++s) {
-    gload16_off<0>(bq[s][0], bankp);
-    gload16_off<1024>(bq[s][1], bankp);
-    gload16_off<2048>(bq[s][2], bankp);
-    gload16_off<3072>(bq[s][3], bankp);
-    bankp += ST_RB * 64;
+    gload16_s<0>(bq[s][0], lane_off, bank_s);
+    gload16_s<1024>(bq[s][1], lane_off, bank_s);
+    gload16_s<2048>(bq[s][2], lane_off, bank_s);
+    gload16_s<3072>(bq[s][3], lane_off, bank_s);
+    bank_s += ST_RB * 64 * 16;
   }
   __syncthreads();
 
-  // loads younger than a ring slot's request when its group starts: the other RING-1 slots,
-  // plus (for the first RING groups of a chunk) the chunk tile requested at the chunk's start
-  constexpr int W_REST = (RING - 1) * ST_RB;
-  constexpr int W_FIRST = W_REST + ST_NPASS;
+  // Loads retire in order.  When a group starts, the requests younger than its own ring slot are
+  // the other RING-1 slots (and, for some groups, the chunk tile: never counted, which is the
+  // safe side).  The tile in R was requested in the second group of the previous chunk (or in the
+  // prologue) and is followed by at least min(3, RING) whole slots.
+  constexpr int W_SLOT = (RING - 1) * ST_RB;
+  constexpr int W_TILE = (RING < 3 ? RING : 3) * ST_RB;
+  constexpr int TASK_NONE = 0, TASK_STORE = 1, TASK_LOAD = 2;
+  float* const stage_dst0 = &lds[0][0] + (tid / (ST_KC / 4)) * ST_PITCH + (tid % (ST_KC / 4)) * 4;
 
   int c = 0;            // chunk inside the current row tile
   int rt = rt_begin;
   const int nj = P.nj;
   for (int it = 0; it < total; ++it) {
-    // tile of chunk it+1 (requested one chunk ago; at least RING*ST_RB bank loads are younger)
-    wait_vm<RING * ST_RB>(R);
-    store_chunk<ST_KC, ST_PITCH, ST_NPASS>(R, sel, special, lds[(it + 1) & 1], ST_LDS_ROWS, tid);
-    // request the tile of chunk it+2 (always: the wait counts rely on it; unused at the very end)
-    special = issue_chunk<ST_NPASS>(R, sel, g, rd, ((it + 2) % n_chunks) * ST_KC);
+    // R holds the tile of chunk it+1.  In the common case (every window interior) its LDS writes
+    // and the requests for chunk it+2 are spread over the first two fragment groups below, one
+    // instruction behind every other MFMA, so that they cost no MFMA issue time; only the address
+    // arithmetic (and the rare edge handling) happens here.
+    wait_vm<W_TILE>(R);
+    const bool special_store = special;
+    if (special_store)
+      store_chunk<ST_KC, ST_PITCH, ST_NPASS>(R, sel, true, lds[(it + 1) & 1], ST_LDS_ROWS, tid);
+    const float* ptr[ST_NPASS];
+    special = prepare_chunk<ST_NPASS>(ptr, sel, g, rd, ((it + 2) % n_chunks) * ST_KC);
+    float* const stage_dst = stage_dst0 + ((it + 1) & 1) * (ST_LDS_ROWS * ST_PITCH);
     __builtin_amdgcn_sched_barrier(0);
 
     const float* A = lds[it & 1] + a_off;
     f32x4 a_cur = *reinterpret_cast<const f32x4*>(A);
 
-    auto group = [&](auto first_tag, int jj, auto kg_tag) {
-      constexpr bool kFirst = decltype(first_tag)::value;
+    auto group = [&](auto task_tag, int jj, auto kg_tag) {
+      constexpr int TASK = decltype(task_tag)::value;
       constexpr int kg = decltype(kg_tag)::value;
       constexpr int s = kg % RING;
       // the frames fragment of the next group is read from LDS while this group's MFMAs run
       const int nxt = kg + 1 < ST_NKG ? jj * ST_PITCH + (kg + 1) * ST_KG : (jj + 1 < nj ? (jj + 1) * ST_PITCH : 0);
       const f32x4 a_nxt = *reinterpret_cast<const f32x4*>(A + nxt);
-      wait_vm<(kFirst && kg < RING) ? W_FIRST : W_REST>(bq[s][0], bq[s][1], bq[s][2], bq[s][3]);
+      wait_vm<W_SLOT>(bq[s][0], bq[s][1], bq[s][2], bq[s][3]);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // the LDS read goes first
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int e = 0; e < 3; ++e) {
-#pragma unroll
-        for (int rb = 0; rb < ST_RB; ++rb)
-          acc[rb] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][rb][e], a_cur[e], acc[rb], 0, 0, 0);
+      for (int m = 0; m < 16; ++m) {
+        const int e = m >> 2, rb = m & 3;
+        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][rb][e], a_cur[e], acc[rb], 0, 0, 0);
+        if (TASK != TASK_NONE && (m & 1) && (m >> 1) < ST_NPASS) {
+          const int p = m >> 1;
+          __builtin_amdgcn_sched_barrier(0);
+          if (TASK == TASK_STORE) {
+            if (!special_store) *reinterpret_cast<f32x4*>(stage_dst + p * ST_RPP * ST_PITCH) = R[p];
+          } else {
+            gload16(R[p], ptr[p]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (m >= 12) {
+          // this MFMA was the last reader of fragment quad rb: re-request it (the group RING
+          // ahead; the bank allocation is padded by ST_NKG groups, so the tail stays in bounds)
+          __builtin_amdgcn_sched_barrier(0);
+          if (rb == 0) gload16_s<0>(bq[s][0], lane_off, bank_s);
+          if (rb == 1) gload16_s<1024>(bq[s][1], lane_off, bank_s);
+          if (rb == 2) gload16_s<2048>(bq[s][2], lane_off, bank_s);
+          if (rb == 3) gload16_s<3072>(bq[s][3], lane_off, bank_s);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // the LDS read first,
-      __builtin_amdgcn_sched_group_barrier(0x008, 12, 0); // then 12 MFMAs
-      __builtin_amdgcn_sched_barrier(0);
-      // The last four MFMAs each free one fragment register quad; its re-request (the group RING
-      // ahead; the bank allocation is padded by ST_NKG groups, so the tail requests stay in bounds)
-      // is issued right behind it, in the shadow of the 64-cycle MFMA.
-      acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][0][3], a_cur[3], acc[0], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      gload16_off<0>(bq[s][0], bankp);
-      __builtin_amdgcn_sched_barrier(0);
-      acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][1][3], a_cur[3], acc[1], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      gload16_off<1024>(bq[s][1], bankp);
-      __builtin_amdgcn_sched_barrier(0);
-      acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][2][3], a_cur[3], acc[2], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      gload16_off<2048>(bq[s][2], bankp);
-      __builtin_amdgcn_sched_barrier(0);
-      acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][3][3], a_cur[3], acc[3], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      gload16_off<3072>(bq[s][3], bankp);
-      bankp += ST_RB * 64;
-      __builtin_amdgcn_sched_barrier(0);
+      bank_s += ST_RB * 64 * 16;
       a_cur = a_nxt;
     };
-    using T_ = std::true_type;
-    using F_ = std::false_type;
-    group(T_{}, 0, std::integral_constant<int, 0>{});
-    group(T_{}, 0, std::integral_constant<int, 1>{});
-    group(T_{}, 0, std::integral_constant<int, 2>{});
-    group(T_{}, 0, std::integral_constant<int, 3>{});
+    using K0 = std::integral_constant<int, 0>;
+    using K1 = std::integral_constant<int, 1>;
+    using K2 = std::integral_constant<int, 2>;
+    using K3 = std::integral_constant<int, 3>;
+    group(std::integral_constant<int, TASK_STORE>{}, 0, K0{});
+    group(std::integral_constant<int, TASK_LOAD>{}, 0, K1{});
+    group(std::integral_constant<int, TASK_NONE>{}, 0, K2{});
+    group(std::integral_constant<int, TASK_NONE>{}, 0, K3{});
     for (int jj = 1; jj < nj; ++jj) {
-      group(F_{}, jj, std::integral_constant<int, 0>{});
-      group(F_{}, jj, std::integral_constant<int, 1>{});
-      group(F_{}, jj, std::integral_constant<int, 2>{});
-      group(F_{}, jj, std::integral_constant<int, 3>{});
+      group(std::integral_constant<int, TASK_NONE>{}, jj, K0{});
+      group(std::integral_constant<int, TASK_NONE>{}, jj, K1{});
+      group(std::integral_constant<int, TASK_NONE>{}, jj, K2{});
+      group(std::integral_constant<int, TASK_NONE>{}, jj, K3{});
     }
 
     if (++c == n_chunks) {
