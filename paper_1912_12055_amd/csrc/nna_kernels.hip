@@ -630,7 +630,9 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
     ck.pad_ = 0;
     return ck;
   };
-  const f32x4* bankp = reinterpret_cast<const f32x4*>(P.bank) + P.rb_frag0[rb] * 64 + lane;
+  // the bank fragments are streamed with scalar-base loads: uniform base + 16 bytes per lane
+  const unsigned lane_off = (unsigned)lane * 16u;
+  const char* bank_s = reinterpret_cast<const char*>(P.bank) + P.rb_frag0[rb] * (64 * 16);
 
   f32x4 acc[4];
 #pragma unroll
@@ -654,26 +656,36 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
   f32x4 bq[CQ_PREFETCH];
 #pragma unroll
   for (int i = 0; i < CQ_PREFETCH; ++i) {
-    gload16(bq[i], bankp);
-    bankp += 64;
+    gload16_s<0>(bq[i], lane_off, bank_s);
+    bank_s += 64 * 16;
   }
   __syncthreads();
 
-  // requests younger than the oldest fragment when its group starts: the other CQ_PREFETCH-1
-  // fragments, plus (first CQ_PREFETCH groups of a chunk) the chunk tile requested at its start
-  constexpr int W_REST = CQ_PREFETCH - 1;
-  constexpr int W_FIRST = W_REST + CQ_NPASS;
+  // Loads retire in order.  When a group starts, the requests younger than its own fragment are
+  // the other CQ_PREFETCH-1 fragments (the chunk tile is never counted: the safe side).  The tile
+  // in R was requested in the second group of the previous chunk (or in the prologue) and is
+  // followed by at least CQ_PREFETCH-1 fragment requests (every chunk has >= CQ_PREFETCH groups).
+  constexpr int W_SLOT = CQ_PREFETCH - 1;
+  constexpr int W_TILE = CQ_PREFETCH - 1;
+  constexpr int TASK_NONE = 0, TASK_STORE = 1, TASK_LOAD = 2;
+  const int stage_off = (tid / (CQ_KC / 4)) * CQ_PITCH + (tid % (CQ_KC / 4)) * 4;
+  const int n_pass_rows = (P.lds_rows + CQ_RPP - 1) / CQ_RPP;  // loader passes that have LDS rows
 
   for (int it = 0; it < n_chunks; ++it) {
     float* cur = (it & 1) ? lds1 : lds0;
     float* nxt = (it & 1) ? lds0 : lds1;
-    // the pending tile has at least CQ_PREFETCH younger bank requests (no listed chunk is empty)
-    wait_vm<CQ_PREFETCH>(R);
-    store_chunk<CQ_KC, CQ_PITCH, CQ_NPASS>(R, sel, special, nxt, P.lds_rows, tid);
+    // R holds the tile of chunk it+1.  In the common case its LDS writes and the requests for
+    // chunk it+2 are spread over the first two fragment groups (one instruction behind every other
+    // MFMA); only the address arithmetic and the rare edge handling happen here.
+    wait_vm<W_TILE>(R);
+    const bool special_store = special;
+    if (special_store) store_chunk<CQ_KC, CQ_PITCH, CQ_NPASS>(R, sel, true, nxt, P.lds_rows, tid);
+    const float* ptr[CQ_NPASS];
     {
       const CqtChunk ck = chunk_at(it + 2 < n_chunks ? it + 2 : n_chunks - 1);
-      special = issue_chunk<CQ_NPASS>(R, sel, g, rd, ck.jlo * g.hop + ck.c0);
+      special = prepare_chunk<CQ_NPASS>(ptr, sel, g, rd, ck.jlo * g.hop + ck.c0);
     }
+    float* const stage_dst = nxt + stage_off;
     __builtin_amdgcn_sched_barrier(0);
 
     const int nj = chunk_at(it).nj;  // a positive multiple of CQ_PREFETCH
@@ -685,45 +697,53 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
     // group's bank fragment; it is a compile-time constant because a register with a load in
     // flight must never be copied.  The planner pads every chunk to a multiple of CQ_PREFETCH
     // groups (zero fragments), so group jj of any chunk always lives in slot jj % CQ_PREFETCH.
-    auto group = [&](auto first_tag, auto slot_tag, int jj) {
-      constexpr bool kFirst = decltype(first_tag)::value;
+    auto group = [&](auto task_tag, auto slot_tag, int jj) {
+      constexpr int TASK = decltype(task_tag)::value;
       constexpr int slot = decltype(slot_tag)::value;
       const int nxt_off = jj + 1 < nj ? (jj + 1) * CQ_PITCH : 0;
       f32x4 a_nxt[4];
 #pragma unroll
       for (int fb = 0; fb < 4; ++fb) a_nxt[fb] = *reinterpret_cast<const f32x4*>(cur + a_off[fb] + nxt_off);
-      wait_vm<kFirst ? W_FIRST : W_REST>(bq[slot]);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-#pragma unroll
-        for (int fb = 0; fb < 4; ++fb)
-          acc[fb] = __builtin_amdgcn_mfma_f32_16x16x4f32(bq[slot][e], a_cur[fb][e], acc[fb], 0, 0, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);   // the 4 LDS reads first,
-      __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);  // then the 16 MFMAs
+      wait_vm<W_SLOT>(bq[slot]);
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);  // the 4 LDS reads go first
       __builtin_amdgcn_sched_barrier(0);
-      gload16(bq[slot], bankp);
-      bankp += 64;
+#pragma unroll
+      for (int m = 0; m < 16; ++m) {
+        const int e = m >> 2, fb = m & 3;
+        acc[fb] = __builtin_amdgcn_mfma_f32_16x16x4f32(bq[slot][e], a_cur[fb][e], acc[fb], 0, 0, 0);
+        if (TASK != TASK_NONE && (m & 1)) {
+          const int p = m >> 1;  // 0..7 = CQ_NPASS passes
+          __builtin_amdgcn_sched_barrier(0);
+          if (TASK == TASK_STORE) {
+            if (!special_store && p < n_pass_rows) *reinterpret_cast<f32x4*>(stage_dst + p * CQ_RPP * CQ_PITCH) = R[p];
+          } else {
+            gload16(R[p], ptr[p]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      gload16_s<0>(bq[slot], lane_off, bank_s);
+      bank_s += 64 * 16;
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int fb = 0; fb < 4; ++fb) a_cur[fb] = a_nxt[fb];
     };
-    static_assert(CQ_PREFETCH == 4, "the group sequence below is written for a ring of 4");
+    static_assert(CQ_PREFETCH == 4 && CQ_NPASS == 8, "the group sequence below is written for a ring of 4 and 8 passes");
     using S0 = std::integral_constant<int, 0>;
     using S1 = std::integral_constant<int, 1>;
     using S2 = std::integral_constant<int, 2>;
     using S3 = std::integral_constant<int, 3>;
-    {
-      group(std::true_type{}, S0{}, 0);
-      group(std::true_type{}, S1{}, 1);
-      group(std::true_type{}, S2{}, 2);
-      group(std::true_type{}, S3{}, 3);
-      for (int jj = 4; jj < nj; jj += 4) {
-        group(std::false_type{}, S0{}, jj);
-        group(std::false_type{}, S1{}, jj + 1);
-        group(std::false_type{}, S2{}, jj + 2);
-        group(std::false_type{}, S3{}, jj + 3);
-      }
+    using TNone = std::integral_constant<int, TASK_NONE>;
+    group(std::integral_constant<int, TASK_STORE>{}, S0{}, 0);
+    group(std::integral_constant<int, TASK_LOAD>{}, S1{}, 1);
+    group(TNone{}, S2{}, 2);
+    group(TNone{}, S3{}, 3);
+    for (int jj = 4; jj < nj; jj += 4) {
+      group(TNone{}, S0{}, jj);
+      group(TNone{}, S1{}, jj + 1);
+      group(TNone{}, S2{}, jj + 2);
+      group(TNone{}, S3{}, jj + 3);
     }
     __syncthreads();
   }

@@ -756,7 +756,7 @@ nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long l
   P.fmt = plan->fmt;
   P.tile_frames = M;
   const long long nseg = 1 + (M - 1 + T - 1) / T;
-  P.lds_rows = (int)(M + nseg * extra);
+  P.lds_rows = (int)((M + nseg * extra + 63) / 64 * 64);  // whole loader passes of 64 rows (<= CQ_LDS_ROWS_MAX)
   P.n_ft = (P.g.n_frames + M - 1) / M;
   DeviceGuard guard;
   hipError_t e = guard.enter(plan->device);
