@@ -27,7 +27,10 @@ constexpr int ST_MEL_BLOCKS = 4;  // 32-mel MFMA blocks per pass (128 mels)
 constexpr int CQ_ROWS = 16;
 constexpr int CQ_FRAMES = 256;    // 4 waves x 4 blocks of 16 frames
 constexpr int CQ_KC = 16;         // taps per LDS chunk = taps per bank fragment
-constexpr int CQ_PITCH = 20;
+#ifndef NNA_CQ_PITCH
+#define NNA_CQ_PITCH 20
+#endif
+constexpr int CQ_PITCH = NNA_CQ_PITCH;
 constexpr int CQ_LDS_ROWS_MAX = 512;
 constexpr int CQ_PREFETCH = 4;    // bank fragments in flight per wave
 

@@ -95,17 +95,20 @@ __device__ __forceinline__ void wait_vm(f32x4 (&r)[8]) {
 
 // ---------------------------------------------------------------------------------------
 // Framing loader.  LDS row r of a tile is S-row sigma of waveform b.  A thread fetches 4
-// consecutive columns of one row per pass with ONE 16-byte load: the 4 padded samples
-// i0..i0+3 always map, after mirror reflection at either end of the waveform, into one window
-// of 4 consecutive stored samples, so the load takes that window and a 2-bit-per-element
-// selector (identity 0xE4 in the interior) reorders it when the chunk is written to LDS.
-// Selector 0xFF marks rows that do not exist (zero fill; the load then reads a dummy address so
-// that the number of issued loads is the same on every path).
-// The (pass -> row) descriptors are computed once per tile and kept in registers, so that the
-// per-chunk work in the common interior case is one add and one compare per pass.
+// consecutive columns of one row per pass with ONE 16-byte load.  The 4 padded samples
+// i0..i0+3 map, after mirror reflection at either end of the waveform, into one window of 4
+// consecutive stored samples:
+//   class 0  interior window: load it as it is;
+//   class 1  window entirely inside a reflected zone: it is a stored window read backwards --
+//            load that window, reverse the 4 elements when the chunk is written to LDS (long CQT
+//            kernels pad by tens of hops, so this is the common case at both waveform ends);
+//   class 2  window straddling an end (only when L, hop or the padding are not multiples of 4):
+//            load the covering window and pick each element with a 2-bit selector.
+// The class is decided per wave (ballot), so each chunk takes the cheapest path that serves all
+// 64 lanes.  Rows that do not exist read a dummy window: nobody reads their LDS rows.
+// The (pass -> row) descriptors are computed once per tile and kept in registers.
 // ---------------------------------------------------------------------------------------
-constexpr unsigned SEL_IDENTITY = 0xE4u, SEL_ZERO = 0xFFu;
-constexpr int kNoRow = -0x40000000;  // i0 of a row that does not exist: fails the interior test for any shift
+constexpr unsigned SEL_IDENTITY = 0xE4u;
 
 __device__ __forceinline__ int reflect_clamped(int j, int L) {
   int r = j < 0 ? -j : (j >= L ? 2 * (L - 1) - j : j);
@@ -114,7 +117,7 @@ __device__ __forceinline__ int reflect_clamped(int j, int L) {
 
 template <int NPASS>
 struct RowDesc {
-  const float* xb[NPASS];  // waveform of the row this thread serves in pass p (nullptr: no such row)
+  const float* xb[NPASS];  // waveform of the row this thread serves in pass p
   int i0[NPASS];           // padded-signal sample index of (row, this thread's first column) at shift 0, column 0
 };
 
@@ -131,90 +134,95 @@ __device__ __forceinline__ void build_rowdesc(RowDesc<NPASS>& rd, const FrameGeo
     int sigma;
     tm.decode(row, b, sigma);
     const bool ok = row < rows_used && b < g.B;
-    rd.xb[p] = ok ? g.x + b * g.L : nullptr;
-    rd.i0[p] = ok ? sigma * g.hop + cv * 4 - g.pad : kNoRow;
+    rd.xb[p] = ok ? g.x + b * g.L : g.x;                     // a row nobody reads: any valid window will do
+    rd.i0[p] = ok ? sigma * g.hop + cv * 4 - g.pad : 0;
   }
 }
 
-// `shift` = (first hop-shift of the chunk) * hop + (first column of the chunk).
-// prepare_chunk computes the NPASS load addresses of a chunk (no memory access).  It returns
-// true (uniformly over the wave) if some lane's window touches an end of its waveform or its row
-// does not exist; only then are the selectors `sel` meaningful.
+// State of a requested chunk tile that its LDS write needs.
 template <int NPASS>
-__device__ __forceinline__ bool prepare_chunk(const float* (&ptr)[NPASS], unsigned (&sel)[NPASS], const FrameGeom& g,
+struct TileFix {
+  int cls;              // 0, 1 or 2 (see above), uniform over the wave
+  unsigned rev;         // class 1: bit p set if this lane's window of pass p is read backwards
+  unsigned sel[NPASS];  // class 2: element selectors
+};
+
+// `shift` = (first hop-shift of the chunk) * hop + (first column of the chunk).
+// Computes the NPASS load addresses of a chunk (no memory access) and how to fix the data up.
+template <int NPASS>
+__device__ __forceinline__ void prepare_chunk(const float* (&ptr)[NPASS], TileFix<NPASS>& fx, const FrameGeom& g,
                                               const RowDesc<NPASS>& rd, int shift) {
   const int L = (int)g.L;
-  bool special = false;
+  unsigned rev = 0;
+  bool gen = false;
 #pragma unroll
   for (int p = 0; p < NPASS; ++p) {
     const int i0 = rd.i0[p] + shift;
-    ptr[p] = rd.xb[p] + i0;
-    special |= (unsigned)i0 > (unsigned)(L - 4);
+    int src = i0;
+    if (i0 < 0) src = -i0 - 3;                      // i0..i0+3 all left of sample 0  -> x[-i0-3 .. -i0] reversed
+    else if (i0 > L - 4) src = 2 * (L - 1) - i0 - 3;  // all right of sample L-1    -> x[2(L-1)-i0-3 ..] reversed
+    rev |= (src != i0 ? 1u : 0u) << p;
+    gen |= (unsigned)src > (unsigned)(L - 4);       // not a whole stored window: straddles an end
+    ptr[p] = rd.xb[p] + src;
   }
-  const bool any_special = __builtin_amdgcn_ballot_w64(special) != 0;
-  if (any_special) {
+  fx.rev = rev;
+  fx.cls = __builtin_amdgcn_ballot_w64(rev != 0) != 0 ? 1 : 0;
+  if (__builtin_amdgcn_ballot_w64(gen) != 0) {
+    fx.cls = 2;
 #pragma unroll
     for (int p = 0; p < NPASS; ++p) {
       const int i0 = rd.i0[p] + shift;
-      const float* xb = rd.xb[p];
-      unsigned s = SEL_IDENTITY;
-      if (xb == nullptr) {
-        ptr[p] = g.x;
-        s = SEL_ZERO;
-      } else if ((unsigned)i0 > (unsigned)(L - 4)) {
-        const int i_0 = reflect_clamped(i0, L), i_1 = reflect_clamped(i0 + 1, L);
-        const int i_2 = reflect_clamped(i0 + 2, L), i_3 = reflect_clamped(i0 + 3, L);
-        int w0 = min(min(i_0, i_1), min(i_2, i_3));
-        w0 = min(w0, L - 4);
-        ptr[p] = xb + w0;
-        s = (unsigned)min(i_0 - w0, 3) | ((unsigned)min(i_1 - w0, 3) << 2) | ((unsigned)min(i_2 - w0, 3) << 4) |
-            ((unsigned)min(i_3 - w0, 3) << 6);
-      }
-      sel[p] = s;
+      const int i_0 = reflect_clamped(i0, L), i_1 = reflect_clamped(i0 + 1, L);
+      const int i_2 = reflect_clamped(i0 + 2, L), i_3 = reflect_clamped(i0 + 3, L);
+      int w0 = min(min(i_0, i_1), min(i_2, i_3));
+      w0 = min(w0, L - 4);
+      ptr[p] = rd.xb[p] + w0;
+      fx.sel[p] = (unsigned)min(i_0 - w0, 3) | ((unsigned)min(i_1 - w0, 3) << 2) | ((unsigned)min(i_2 - w0, 3) << 4) |
+                  ((unsigned)min(i_3 - w0, 3) << 6);
     }
   }
-  return any_special;
 }
 
 // Exactly NPASS loads are issued on every path.
 template <int NPASS>
-__device__ __forceinline__ bool issue_chunk(f32x4 (&R)[NPASS], unsigned (&sel)[NPASS], const FrameGeom& g,
+__device__ __forceinline__ void issue_chunk(f32x4 (&R)[NPASS], TileFix<NPASS>& fx, const FrameGeom& g,
                                             const RowDesc<NPASS>& rd, int shift) {
   const float* ptr[NPASS];
-  const bool any_special = prepare_chunk<NPASS>(ptr, sel, g, rd, shift);
+  prepare_chunk<NPASS>(ptr, fx, g, rd, shift);
 #pragma unroll
   for (int p = 0; p < NPASS; ++p) gload16(R[p], ptr[p]);
-  return any_special;
 }
 
 __device__ __forceinline__ float pick4(const f32x4& v, unsigned k) {
   return k == 0 ? v.x : k == 1 ? v.y : k == 2 ? v.z : v.w;
 }
 
+// the value of pass p as it goes to LDS (classes 0 and 1)
+template <int NPASS>
+__device__ __forceinline__ f32x4 fixed_up(const f32x4& v, const TileFix<NPASS>& fx, int p) {
+  if (fx.cls == 0) return v;
+  const bool r = (fx.rev >> p) & 1u;
+  return (f32x4){r ? v.w : v.x, r ? v.z : v.y, r ? v.y : v.z, r ? v.x : v.w};
+}
+
+// whole-tile LDS write (prologue, and class 2 in the main loops)
 template <int KC, int PITCH, int NPASS>
-__device__ __forceinline__ void store_chunk(const f32x4 (&R)[NPASS], const unsigned (&sel)[NPASS], bool special,
-                                            float* lds, int rows_alloc, int tid) {
+__device__ __forceinline__ void store_chunk(const f32x4 (&R)[NPASS], const TileFix<NPASS>& fx, float* lds,
+                                            int rows_alloc, int tid) {
   constexpr int V = KC / 4;
   constexpr int RPP = 256 / V;
   const int cv = tid % V, r0 = tid / V;
   float* dst = lds + r0 * PITCH + cv * 4;
-  if (!special) {  // uniform over the wave: every window is an interior one
 #pragma unroll
-    for (int p = 0; p < NPASS; ++p)
-      if (p * RPP + r0 < rows_alloc) *reinterpret_cast<f32x4*>(dst + p * RPP * PITCH) = R[p];
-  } else {
-#pragma unroll
-    for (int p = 0; p < NPASS; ++p) {
-      f32x4 v = R[p];
-      const unsigned s = sel[p];
-      if (s != SEL_IDENTITY) {
-        if (s == SEL_ZERO)
-          v = (f32x4){0.f, 0.f, 0.f, 0.f};
-        else
-          v = (f32x4){pick4(v, s & 3), pick4(v, (s >> 2) & 3), pick4(v, (s >> 4) & 3), pick4(v, (s >> 6) & 3)};
-      }
-      if (p * RPP + r0 < rows_alloc) *reinterpret_cast<f32x4*>(dst + p * RPP * PITCH) = v;
+  for (int p = 0; p < NPASS; ++p) {
+    f32x4 v;
+    if (fx.cls == 2) {
+      const unsigned s = fx.sel[p];
+      v = (f32x4){pick4(R[p], s & 3), pick4(R[p], (s >> 2) & 3), pick4(R[p], (s >> 4) & 3), pick4(R[p], (s >> 6) & 3)};
+    } else {
+      v = fixed_up<NPASS>(R[p], fx, p);
     }
+    if (p * RPP + r0 < rows_alloc) *reinterpret_cast<f32x4*>(dst + p * RPP * PITCH) = v;
   }
 }
 
@@ -373,11 +381,11 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
   }
   // ---- prologue: chunk 0 into LDS buffer 0, chunk 1 requested, first RING bank groups requested --
   f32x4 R[ST_NPASS];
-  unsigned sel[ST_NPASS];
-  bool special = issue_chunk<ST_NPASS>(R, sel, g, rd, 0);
+  TileFix<ST_NPASS> fx;
+  issue_chunk<ST_NPASS>(R, fx, g, rd, 0);
   wait_vm<0>(R);
-  store_chunk<ST_KC, ST_PITCH, ST_NPASS>(R, sel, special, lds[0], ST_LDS_ROWS, tid);
-  special = issue_chunk<ST_NPASS>(R, sel, g, rd, (1 % n_chunks) * ST_KC);
+  store_chunk<ST_KC, ST_PITCH, ST_NPASS>(R, fx, lds[0], ST_LDS_ROWS, tid);
+  issue_chunk<ST_NPASS>(R, fx, g, rd, (1 % n_chunks) * ST_KC);
 
   // The bank is streamed with scalar-base loads: `bank_s` is uniform, each lane adds its 16 bytes.
   const unsigned lane_off = (unsigned)lane * 16u;
@@ -411,11 +419,10 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
     // instruction behind every other MFMA, so that they cost no MFMA issue time; only the address
     // arithmetic (and the rare edge handling) happens here.
     wait_vm<W_TILE>(R);
-    const bool special_store = special;
-    if (special_store)
-      store_chunk<ST_KC, ST_PITCH, ST_NPASS>(R, sel, true, lds[(it + 1) & 1], ST_LDS_ROWS, tid);
+    const TileFix<ST_NPASS> fx_store = fx;  // how to write the tile now in R; fx moves on to chunk it+2
+    if (fx_store.cls == 2) store_chunk<ST_KC, ST_PITCH, ST_NPASS>(R, fx_store, lds[(it + 1) & 1], ST_LDS_ROWS, tid);
     const float* ptr[ST_NPASS];
-    special = prepare_chunk<ST_NPASS>(ptr, sel, g, rd, ((it + 2) % n_chunks) * ST_KC);
+    prepare_chunk<ST_NPASS>(ptr, fx, g, rd, ((it + 2) % n_chunks) * ST_KC);
     float* const stage_dst = stage_dst0 + ((it + 1) & 1) * (ST_LDS_ROWS * ST_PITCH);
     __builtin_amdgcn_sched_barrier(0);
 
@@ -440,7 +447,8 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
           const int p = m >> 1;
           __builtin_amdgcn_sched_barrier(0);
           if (TASK == TASK_STORE) {
-            if (!special_store) *reinterpret_cast<f32x4*>(stage_dst + p * ST_RPP * ST_PITCH) = R[p];
+            if (fx_store.cls != 2)
+              *reinterpret_cast<f32x4*>(stage_dst + p * ST_RPP * ST_PITCH) = fixed_up<ST_NPASS>(R[p], fx_store, p);
           } else {
             gload16(R[p], ptr[p]);
           }
@@ -640,17 +648,16 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
   __syncthreads();  // the chunk table is complete
 
   f32x4 R[CQ_NPASS];
-  unsigned sel[CQ_NPASS];
-  bool special;
+  TileFix<CQ_NPASS> fx;
   {
     const CqtChunk ck = chunk_at(0);
-    special = issue_chunk<CQ_NPASS>(R, sel, g, rd, ck.jlo * g.hop + ck.c0);
+    issue_chunk<CQ_NPASS>(R, fx, g, rd, ck.jlo * g.hop + ck.c0);
     wait_vm<0>(R);
-    store_chunk<CQ_KC, CQ_PITCH, CQ_NPASS>(R, sel, special, lds0, P.lds_rows, tid);
+    store_chunk<CQ_KC, CQ_PITCH, CQ_NPASS>(R, fx, lds0, P.lds_rows, tid);
   }
   {
     const CqtChunk ck = chunk_at(n_chunks > 1 ? 1 : 0);
-    special = issue_chunk<CQ_NPASS>(R, sel, g, rd, ck.jlo * g.hop + ck.c0);
+    issue_chunk<CQ_NPASS>(R, fx, g, rd, ck.jlo * g.hop + ck.c0);
   }
   // bank fragment pipeline: CQ_PREFETCH requests in flight (the allocation is padded by that many)
   f32x4 bq[CQ_PREFETCH];
@@ -678,12 +685,12 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
     // chunk it+2 are spread over the first two fragment groups (one instruction behind every other
     // MFMA); only the address arithmetic and the rare edge handling happen here.
     wait_vm<W_TILE>(R);
-    const bool special_store = special;
-    if (special_store) store_chunk<CQ_KC, CQ_PITCH, CQ_NPASS>(R, sel, true, nxt, P.lds_rows, tid);
+    const TileFix<CQ_NPASS> fx_store = fx;  // how to write the tile now in R; fx moves on to chunk it+2
+    if (fx_store.cls == 2) store_chunk<CQ_KC, CQ_PITCH, CQ_NPASS>(R, fx_store, nxt, P.lds_rows, tid);
     const float* ptr[CQ_NPASS];
     {
       const CqtChunk ck = chunk_at(it + 2 < n_chunks ? it + 2 : n_chunks - 1);
-      special = prepare_chunk<CQ_NPASS>(ptr, sel, g, rd, ck.jlo * g.hop + ck.c0);
+      prepare_chunk<CQ_NPASS>(ptr, fx, g, rd, ck.jlo * g.hop + ck.c0);
     }
     float* const stage_dst = nxt + stage_off;
     __builtin_amdgcn_sched_barrier(0);
@@ -715,7 +722,8 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
           const int p = m >> 1;  // 0..7 = CQ_NPASS passes
           __builtin_amdgcn_sched_barrier(0);
           if (TASK == TASK_STORE) {
-            if (!special_store && p < n_pass_rows) *reinterpret_cast<f32x4*>(stage_dst + p * CQ_RPP * CQ_PITCH) = R[p];
+            if (fx_store.cls != 2 && p < n_pass_rows)
+              *reinterpret_cast<f32x4*>(stage_dst + p * CQ_RPP * CQ_PITCH) = fixed_up<CQ_NPASS>(R[p], fx_store, p);
           } else {
             gload16(R[p], ptr[p]);
           }
