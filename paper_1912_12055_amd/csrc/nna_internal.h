@@ -66,27 +66,39 @@ struct StftParams {
   int mel_nyq_any;
 };
 
+constexpr int CQ_ITEM_RB = 4;  // row blocks one CQT workgroup can handle (short kernels are grouped)
+
+// One LDS chunk of a CQT work item (48 bytes, read as three 16-byte words).
 struct CqtChunk {
-  int c0;   // first tap column of the chunk (within the hop, or absolute when frames do not overlap)
-  int jlo;  // first hop-shift that has non-zero taps in this chunk
-  int nj;   // number of hop-shifts (bank fragments) in this chunk
-  int pad_;
+  int c0;    // first tap column of the chunk (within the hop, or absolute when frames do not overlap)
+  int jlo;   // first hop-shift of the chunk's LDS rows (that of the item's first, longest row block)
+  int pad0, pad1;
+  int joff[CQ_ITEM_RB];  // first hop-shift of row block r, relative to jlo
+  int nj[CQ_ITEM_RB];    // bank fragments of row block r in this chunk: a multiple of CQ_PREFETCH, 0 = none
+};
+
+// A CQT work item: up to CQ_ITEM_RB consecutive row blocks that share the LDS tiles of the first.
+struct CqtItem {
+  long long frag0;  // first bank fragment of the item
+  int rb_first;
+  int n_rb;
+  int jspan;        // LDS rows per waveform segment beyond the frames, + 1
+  int n_chunks;     // chunks listed for the item (each holds taps of its first row block)
+  int pad0, pad1;
 };
 
 struct CqtParams {
   FrameGeom g;
-  const float4* bank;         // per row block: [fragment][64 lanes] float4, fragments in loop order
-  const long long* rb_frag0;  // [n_rb] first fragment of the row block
-  const CqtChunk* chunks;     // [n_rb][n_chunks]
-  const int* rb_jspan;        // [n_rb] LDS rows added per waveform segment + 1
-  const int* rb_nchunks;      // [n_rb] chunks of the row block that hold taps (listed first in `chunks`)
+  const float4* bank;      // per item: [fragment][64 lanes] float4, fragments in loop order
+  const CqtItem* items;    // [n_items]
+  const CqtChunk* chunks;  // [n_items][n_chunks]
   float* out;
-  int n_rb;
-  int n_chunks;
+  int n_items;
+  int n_chunks;            // stride of `chunks` (largest n_chunks of any item)
   int n_bins;
   int fmt;
-  int lds_rows;               // rows per LDS buffer
-  int tile_frames;            // frames per tile (<= CQ_FRAMES)
+  int lds_rows;            // rows per LDS buffer
+  int tile_frames;         // frames per tile (<= CQ_FRAMES)
   long long n_ft;
 };
 

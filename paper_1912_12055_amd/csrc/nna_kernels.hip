@@ -582,20 +582,22 @@ constexpr int CQ_NPASS = CQ_LDS_ROWS_MAX / CQ_RPP;  // 512 / 64 = 8
 
 __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
   extern __shared__ __attribute__((aligned(16))) float dyn_lds[];
-  // dynamic LDS: this row block's chunk table (read every chunk; kept out of the vector-memory
-  // path so that fetching a descriptor never waits on the streaming loads), then two tile buffers
+  // dynamic LDS: this item's chunk table (read every chunk; kept out of the vector-memory path so
+  // that fetching a descriptor never waits on the streaming loads), then two tile buffers
   int4* s_chunks = reinterpret_cast<int4*>(dyn_lds);
-  float* lds0 = dyn_lds + (size_t)P.n_chunks * 4;
+  float* lds0 = dyn_lds + (size_t)P.n_chunks * (sizeof(CqtChunk) / 4);
   float* lds1 = lds0 + (size_t)P.lds_rows * CQ_PITCH;
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int q = lane >> 4, n = lane & 15;
 
-  // longest kernels first: row block is the slow index
+  // longest kernels first: the work item is the slow index
   const long long bid = blockIdx.x;
-  const int rb = (int)(bid / P.n_ft);
-  const long long ft = bid - (long long)rb * P.n_ft;
+  const int item_id = (int)(bid / P.n_ft);
+  const long long ft = bid - (long long)item_id * P.n_ft;
+  const CqtItem item = P.items[item_id];
+  const int n_rb = item.n_rb;
 
   const FrameGeom& g = P.g;
   const long long f0 = ft * P.tile_frames;
@@ -605,7 +607,7 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
   tm.b0 = f0 / g.T;
   tm.t0 = (int)(f0 - tm.b0 * g.T);
   tm.n0 = (g.T - tm.t0) < m_valid ? (g.T - tm.t0) : m_valid;
-  tm.extra = P.rb_jspan[rb] - 1;
+  tm.extra = item.jspan - 1;
   const int rows_used = tm.frame_row(m_valid - 1) + tm.extra + 1;
   RowDesc<CQ_NPASS> rd;
   build_rowdesc<CQ_KC, CQ_NPASS>(rd, g, tm, rows_used, tid);
@@ -624,41 +626,33 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
     o_off[fb] = (b * P.n_bins) * g.T + t;
   }
 
-  const int n_chunks = P.rb_nchunks[rb];  // >= 1, every listed chunk holds a whole ring of fragments
+  const int n_chunks = item.n_chunks;  // >= 1; every listed chunk starts with >= CQ_PREFETCH fragments
   {
-    const int4* __restrict__ src = reinterpret_cast<const int4*>(P.chunks + (long long)rb * P.n_chunks);
-    for (int i = tid; i < n_chunks; i += 256) s_chunks[i] = src[i];
+    const int4* __restrict__ src = reinterpret_cast<const int4*>(P.chunks + (long long)item_id * P.n_chunks);
+    for (int i = tid; i < n_chunks * 3; i += 256) s_chunks[i] = src[i];
   }
-  auto chunk_at = [&](int i) {
-    const int4 v = s_chunks[i];
-    CqtChunk ck;
-    ck.c0 = __builtin_amdgcn_readfirstlane(v.x);
-    ck.jlo = __builtin_amdgcn_readfirstlane(v.y);
-    ck.nj = __builtin_amdgcn_readfirstlane(v.z);
-    ck.pad_ = 0;
-    return ck;
-  };
   // the bank fragments are streamed with scalar-base loads: uniform base + 16 bytes per lane
   const unsigned lane_off = (unsigned)lane * 16u;
-  const char* bank_s = reinterpret_cast<const char*>(P.bank) + P.rb_frag0[rb] * (64 * 16);
+  const char* bank_s = reinterpret_cast<const char*>(P.bank) + item.frag0 * (64 * 16);
 
-  f32x4 acc[4];
+  f32x4 acc[CQ_ITEM_RB][4];
 #pragma unroll
-  for (int fb = 0; fb < 4; ++fb) acc[fb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int r = 0; r < CQ_ITEM_RB; ++r)
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb) acc[r][fb] = (f32x4){0.f, 0.f, 0.f, 0.f};
   __syncthreads();  // the chunk table is complete
+
+  auto chunk_shift = [&](int i) {  // (first hop-shift) * hop + (first column) of chunk i
+    const int4 v = s_chunks[3 * i];
+    return __builtin_amdgcn_readfirstlane(v.y) * g.hop + __builtin_amdgcn_readfirstlane(v.x);
+  };
 
   f32x4 R[CQ_NPASS];
   TileFix<CQ_NPASS> fx;
-  {
-    const CqtChunk ck = chunk_at(0);
-    issue_chunk<CQ_NPASS>(R, fx, g, rd, ck.jlo * g.hop + ck.c0);
-    wait_vm<0>(R);
-    store_chunk<CQ_KC, CQ_PITCH, CQ_NPASS>(R, fx, lds0, P.lds_rows, tid);
-  }
-  {
-    const CqtChunk ck = chunk_at(n_chunks > 1 ? 1 : 0);
-    issue_chunk<CQ_NPASS>(R, fx, g, rd, ck.jlo * g.hop + ck.c0);
-  }
+  issue_chunk<CQ_NPASS>(R, fx, g, rd, chunk_shift(0));
+  wait_vm<0>(R);
+  store_chunk<CQ_KC, CQ_PITCH, CQ_NPASS>(R, fx, lds0, P.lds_rows, tid);
+  issue_chunk<CQ_NPASS>(R, fx, g, rd, chunk_shift(n_chunks > 1 ? 1 : 0));
   // bank fragment pipeline: CQ_PREFETCH requests in flight (the allocation is padded by that many)
   f32x4 bq[CQ_PREFETCH];
 #pragma unroll
@@ -688,36 +682,37 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
     const TileFix<CQ_NPASS> fx_store = fx;  // how to write the tile now in R; fx moves on to chunk it+2
     if (fx_store.cls == 2) store_chunk<CQ_KC, CQ_PITCH, CQ_NPASS>(R, fx_store, nxt, P.lds_rows, tid);
     const float* ptr[CQ_NPASS];
-    {
-      const CqtChunk ck = chunk_at(it + 2 < n_chunks ? it + 2 : n_chunks - 1);
-      prepare_chunk<CQ_NPASS>(ptr, fx, g, rd, ck.jlo * g.hop + ck.c0);
-    }
+    prepare_chunk<CQ_NPASS>(ptr, fx, g, rd, chunk_shift(it + 2 < n_chunks ? it + 2 : n_chunks - 1));
     float* const stage_dst = nxt + stage_off;
+    // this chunk: per row block r of the item, nj[r] fragments starting joff[r] hop-shifts in
+    const int4 d1 = s_chunks[3 * it + 1], d2 = s_chunks[3 * it + 2];
+    const int joff[CQ_ITEM_RB] = {__builtin_amdgcn_readfirstlane(d1.x), __builtin_amdgcn_readfirstlane(d1.y),
+                                  __builtin_amdgcn_readfirstlane(d1.z), __builtin_amdgcn_readfirstlane(d1.w)};
+    const int njr[CQ_ITEM_RB] = {__builtin_amdgcn_readfirstlane(d2.x), __builtin_amdgcn_readfirstlane(d2.y),
+                                 __builtin_amdgcn_readfirstlane(d2.z), __builtin_amdgcn_readfirstlane(d2.w)};
     __builtin_amdgcn_sched_barrier(0);
 
-    const int nj = chunk_at(it).nj;  // a positive multiple of CQ_PREFETCH
+    // One fragment group: 16 taps, 16 MFMAs on the accumulators of row block R_.  `slot` is the
+    // ring register that holds this group's bank fragment; it is a compile-time constant because
+    // a register with a load in flight must never be copied.  The planner pads every row block's
+    // share of a chunk to a multiple of CQ_PREFETCH groups (zero fragments), so the slots stay
+    // aligned: group jj always lives in slot jj % CQ_PREFETCH.
     f32x4 a_cur[4];
-#pragma unroll
-    for (int fb = 0; fb < 4; ++fb) a_cur[fb] = *reinterpret_cast<const f32x4*>(cur + a_off[fb]);
-
-    // One fragment group: 16 taps, 16 MFMAs.  `slot` is the ring register that holds this
-    // group's bank fragment; it is a compile-time constant because a register with a load in
-    // flight must never be copied.  The planner pads every chunk to a multiple of CQ_PREFETCH
-    // groups (zero fragments), so group jj of any chunk always lives in slot jj % CQ_PREFETCH.
-    auto group = [&](auto task_tag, auto slot_tag, int jj) {
+    auto group = [&](auto rb_tag, auto task_tag, auto slot_tag, const float* base, int jj, int nj) {
+      constexpr int R_ = decltype(rb_tag)::value;
       constexpr int TASK = decltype(task_tag)::value;
       constexpr int slot = decltype(slot_tag)::value;
       const int nxt_off = jj + 1 < nj ? (jj + 1) * CQ_PITCH : 0;
       f32x4 a_nxt[4];
 #pragma unroll
-      for (int fb = 0; fb < 4; ++fb) a_nxt[fb] = *reinterpret_cast<const f32x4*>(cur + a_off[fb] + nxt_off);
+      for (int fb = 0; fb < 4; ++fb) a_nxt[fb] = *reinterpret_cast<const f32x4*>(base + a_off[fb] + nxt_off);
       wait_vm<W_SLOT>(bq[slot]);
       __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);  // the 4 LDS reads go first
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int m = 0; m < 16; ++m) {
         const int e = m >> 2, fb = m & 3;
-        acc[fb] = __builtin_amdgcn_mfma_f32_16x16x4f32(bq[slot][e], a_cur[fb][e], acc[fb], 0, 0, 0);
+        acc[R_][fb] = __builtin_amdgcn_mfma_f32_16x16x4f32(bq[slot][e], a_cur[fb][e], acc[R_][fb], 0, 0, 0);
         if (TASK != TASK_NONE && (m & 1)) {
           const int p = m >> 1;  // 0..7 = CQ_NPASS passes
           __builtin_amdgcn_sched_barrier(0);
@@ -737,22 +732,43 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
 #pragma unroll
       for (int fb = 0; fb < 4; ++fb) a_cur[fb] = a_nxt[fb];
     };
-    static_assert(CQ_PREFETCH == 4 && CQ_NPASS == 8, "the group sequence below is written for a ring of 4 and 8 passes");
+    static_assert(CQ_PREFETCH == 4 && CQ_NPASS == 8 && CQ_ITEM_RB == 4, "the group sequences below assume these");
     using S0 = std::integral_constant<int, 0>;
     using S1 = std::integral_constant<int, 1>;
     using S2 = std::integral_constant<int, 2>;
     using S3 = std::integral_constant<int, 3>;
     using TNone = std::integral_constant<int, TASK_NONE>;
-    group(std::integral_constant<int, TASK_STORE>{}, S0{}, 0);
-    group(std::integral_constant<int, TASK_LOAD>{}, S1{}, 1);
-    group(TNone{}, S2{}, 2);
-    group(TNone{}, S3{}, 3);
-    for (int jj = 4; jj < nj; jj += 4) {
-      group(TNone{}, S0{}, jj);
-      group(TNone{}, S1{}, jj + 1);
-      group(TNone{}, S2{}, jj + 2);
-      group(TNone{}, S3{}, jj + 3);
-    }
+    using TStore = std::integral_constant<int, TASK_STORE>;
+    using TLoad = std::integral_constant<int, TASK_LOAD>;
+    // all fragment groups of row block R_ in this chunk; the item's first row block (always
+    // present, >= 4 groups) carries the staging tasks in its first two groups
+    auto row_block = [&](auto rb_tag) {
+      constexpr int R_ = decltype(rb_tag)::value;
+      const int nj = njr[R_];
+      if (R_ >= n_rb || nj == 0) return;
+      const float* base = cur + joff[R_] * CQ_PITCH;
+#pragma unroll
+      for (int fb = 0; fb < 4; ++fb) a_cur[fb] = *reinterpret_cast<const f32x4*>(base + a_off[fb]);
+      if (R_ == 0) {
+        group(rb_tag, TStore{}, S0{}, base, 0, nj);
+        group(rb_tag, TLoad{}, S1{}, base, 1, nj);
+      } else {
+        group(rb_tag, TNone{}, S0{}, base, 0, nj);
+        group(rb_tag, TNone{}, S1{}, base, 1, nj);
+      }
+      group(rb_tag, TNone{}, S2{}, base, 2, nj);
+      group(rb_tag, TNone{}, S3{}, base, 3, nj);
+      for (int jj = 4; jj < nj; jj += 4) {
+        group(rb_tag, TNone{}, S0{}, base, jj, nj);
+        group(rb_tag, TNone{}, S1{}, base, jj + 1, nj);
+        group(rb_tag, TNone{}, S2{}, base, jj + 2, nj);
+        group(rb_tag, TNone{}, S3{}, base, jj + 3, nj);
+      }
+    };
+    row_block(std::integral_constant<int, 0>{});
+    row_block(std::integral_constant<int, 1>{});
+    row_block(std::integral_constant<int, 2>{});
+    row_block(std::integral_constant<int, 3>{});
     __syncthreads();
   }
 
@@ -761,22 +777,26 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
 #pragma unroll
   for (int i = 0; i < CQ_PREFETCH; ++i) wait_vm<0>(bq[i]);
 
-  const int bin0 = rb * (CQ_ROWS / 2) + 2 * q;
+  const int f = P.fmt;
 #pragma unroll
-  for (int fb = 0; fb < 4; ++fb) {
-    if (!valid[fb]) continue;
-    float* __restrict__ op = P.out + o_off[fb];
-    const float p0 = acc[fb][0] * acc[fb][0] + acc[fb][1] * acc[fb][1];
-    const float p1 = acc[fb][2] * acc[fb][2] + acc[fb][3] * acc[fb][3];
-    const int f = P.fmt;
-    if (bin0 < P.n_bins)
-      op[(long long)bin0 * g.T] = f == NNA_OUT_MAGNITUDE ? format_power<NNA_OUT_MAGNITUDE>(p0)
-                                  : f == NNA_OUT_POWER   ? p0
-                                                         : format_power<NNA_OUT_LOG>(p0);
-    if (bin0 + 1 < P.n_bins)
-      op[(long long)(bin0 + 1) * g.T] = f == NNA_OUT_MAGNITUDE ? format_power<NNA_OUT_MAGNITUDE>(p1)
-                                        : f == NNA_OUT_POWER   ? p1
-                                                               : format_power<NNA_OUT_LOG>(p1);
+  for (int r = 0; r < CQ_ITEM_RB; ++r) {
+    if (r >= n_rb) continue;
+    const int bin0 = (item.rb_first + r) * (CQ_ROWS / 2) + 2 * q;
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb) {
+      if (!valid[fb]) continue;
+      float* __restrict__ op = P.out + o_off[fb];
+      const float p0 = acc[r][fb][0] * acc[r][fb][0] + acc[r][fb][1] * acc[r][fb][1];
+      const float p1 = acc[r][fb][2] * acc[r][fb][2] + acc[r][fb][3] * acc[r][fb][3];
+      if (bin0 < P.n_bins)
+        op[(long long)bin0 * g.T] = f == NNA_OUT_MAGNITUDE ? format_power<NNA_OUT_MAGNITUDE>(p0)
+                                    : f == NNA_OUT_POWER   ? p0
+                                                           : format_power<NNA_OUT_LOG>(p0);
+      if (bin0 + 1 < P.n_bins)
+        op[(long long)(bin0 + 1) * g.T] = f == NNA_OUT_MAGNITUDE ? format_power<NNA_OUT_MAGNITUDE>(p1)
+                                          : f == NNA_OUT_POWER   ? p1
+                                                                 : format_power<NNA_OUT_LOG>(p1);
+    }
   }
 }
 
@@ -809,7 +829,7 @@ hipError_t launch_stft(const StftParams& p, bool mel, hipStream_t stream) {
 }
 
 hipError_t launch_cqt(const CqtParams& p, hipStream_t stream) {
-  const long long blocks = p.n_ft * p.n_rb;
+  const long long blocks = p.n_ft * p.n_items;
   if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   if (p.lds_rows > CQ_LDS_ROWS_MAX) return hipErrorInvalidValue;
   const size_t lds = (size_t)p.n_chunks * sizeof(CqtChunk) + 2ull * p.lds_rows * CQ_PITCH * sizeof(float);

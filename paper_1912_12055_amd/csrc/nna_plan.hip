@@ -47,9 +47,9 @@ struct nna_plan {
   int n_bins = 0, bpo = 0, n_rb = 0;
   double cq_fmin = 0, Q = 0;
   std::vector<long long> Nk, sk;
-  std::vector<long long> h_rb_frag0;
-  std::vector<nna::CqtChunk> h_chunks;
-  std::vector<int> h_rb_jspan, h_rb_nchunks;
+  std::vector<nna::CqtItem> h_items;
+  std::vector<nna::CqtChunk> h_chunks;   // [item][n_chunks]
+  std::vector<int> h_nj_real;            // [item][n_chunks][CQ_ITEM_RB] fragments before ring padding
   int max_jspan = 1;
 
   double exec_flops = 0, alg_flops = 0;
@@ -64,15 +64,14 @@ struct nna_plan {
   unsigned char* d_mel_mask = nullptr;
   float* d_mel_wnyq = nullptr;
   int* d_mel_pass_rt = nullptr;
-  long long* d_rb_frag0 = nullptr;
+  nna::CqtItem* d_items = nullptr;
   nna::CqtChunk* d_chunks = nullptr;
-  int* d_rb_jspan = nullptr;
-  int* d_rb_nchunks = nullptr;
 };
 
 namespace {
 
 using nna::CQ_FRAMES;
+using nna::CQ_ITEM_RB;
 using nna::CQ_KC;
 using nna::CQ_LDS_ROWS_MAX;
 using nna::CQ_PREFETCH;
@@ -348,6 +347,23 @@ struct CqtKernelGen {
 inline long long floor_div(long long a, long long b) { return a >= 0 ? a / b : -((-a + b - 1) / b); }
 inline long long ceil_div(long long a, long long b) { return -floor_div(-a, b); }
 
+// Visit every bank fragment of a CQT plan in the order the kernel consumes them:
+// fn(fragment index, row block, hop-shift j (absolute), c0, is_real)
+template <typename Fn>
+void for_each_cqt_fragment(const nna_plan* p, Fn fn) {
+  for (size_t it = 0; it < p->h_items.size(); ++it) {
+    const nna::CqtItem& item = p->h_items[it];
+    long long f = item.frag0;
+    for (int c = 0; c < item.n_chunks; ++c) {
+      const nna::CqtChunk& ck = p->h_chunks[it * p->n_chunks + c];
+      for (int r = 0; r < item.n_rb; ++r)
+        for (int jj = 0; jj < ck.nj[r]; ++jj, ++f)
+          fn(f, item.rb_first + r, ck.jlo + ck.joff[r] + jj, ck.c0,
+             jj < p->h_nj_real[(it * p->n_chunks + c) * CQ_ITEM_RB + r]);
+    }
+  }
+}
+
 void build_cqt_bank(nna_plan* p) {
   const long long K = p->K;
   p->n_rb = (2 * p->n_bins + CQ_ROWS - 1) / CQ_ROWS;
@@ -370,74 +386,101 @@ void build_cqt_bank(nna_plan* p) {
   for (int rb = 0; rb < p->n_rb; ++rb) span_max = std::max(span_max, e_rb[rb] - s_rb[rb]);
   const long long shifts_max = (ceil_div(span_max, p->hop) + 1 + CQ_PREFETCH - 1) / CQ_PREFETCH * CQ_PREFETCH;
   p->sliding = J >= 1 && p->hop % CQ_KC == 0 && 16 + 2 * (shifts_max - 1) <= CQ_LDS_ROWS_MAX;
-  if (p->sliding) {
-    p->n_chunks = p->hop / CQ_KC;
-  } else {
-    long long most = 1;
-    for (int rb = 0; rb < p->n_rb; ++rb)
-      most = std::max(most, ceil_div(e_rb[rb], CQ_KC) - s_rb[rb] / CQ_KC);
-    p->n_chunks = (int)most;
+  // chunk grid: 16-tap column chunks of the hop (shared LDS rows) or of the whole tap range
+  const int n_grid = p->sliding ? p->hop / CQ_KC : (int)ceil_div(K, CQ_KC);
+  // hop-shifts [jlo, jlo + nj) of row block rb that hold taps in grid chunk c
+  auto shifts_of = [&](int rb, int c, int& jlo, int& nj) {
+    const long long c0 = (long long)c * CQ_KC;
+    if (p->sliding) {
+      // taps j*hop + c0 + [0, KC) intersect [s, e)  <=>  j*hop + c0 + KC > s  and  j*hop + c0 < e
+      long long lo = floor_div(s_rb[rb] - c0 - CQ_KC, p->hop) + 1;
+      long long hi = ceil_div(e_rb[rb] - c0, p->hop);
+      lo = std::max(lo, 0LL);
+      hi = std::min(hi, J);
+      jlo = (int)lo;
+      nj = (int)std::max(0LL, hi - lo);
+    } else {
+      jlo = 0;
+      nj = (c0 + CQ_KC > s_rb[rb] && c0 < e_rb[rb]) ? 1 : 0;
+    }
+    if (nj == 0) jlo = 0;
+  };
+  auto ring_pad = [](int nj) { return (nj + CQ_PREFETCH - 1) / CQ_PREFETCH * CQ_PREFETCH; };
+  // most fragments any chunk of a row block has
+  std::vector<int> rb_nj(p->n_rb, 0);
+  for (int rb = 0; rb < p->n_rb; ++rb)
+    for (int c = 0; c < n_grid; ++c) {
+      int jlo, nj;
+      shifts_of(rb, c, jlo, nj);
+      rb_nj[rb] = std::max(rb_nj[rb], ring_pad(nj));
+    }
+  // Work items: the long kernels get a workgroup per row block; short ones are grouped (they
+  // share the first block's LDS tiles) until a chunk holds about 48 fragments.
+  p->h_items.clear();
+  for (int rb = 0; rb < p->n_rb;) {
+    nna::CqtItem item{};
+    item.rb_first = rb;
+    int sum = 0;
+    do {
+      sum += rb_nj[rb];
+      ++item.n_rb;
+      ++rb;
+    } while (rb < p->n_rb && item.n_rb < CQ_ITEM_RB && sum < 48);
+    p->h_items.push_back(item);
   }
-  p->h_chunks.assign((size_t)p->n_rb * p->n_chunks, nna::CqtChunk{0, 0, 0, 0});
-  p->h_rb_jspan.assign(p->n_rb, 1);
-  p->h_rb_nchunks.assign(p->n_rb, 0);
-  p->h_rb_frag0.assign(p->n_rb, 0);
+  // per item: the chunks that hold taps, and for each the fragments of every row block
+  std::vector<std::vector<nna::CqtChunk>> item_chunks(p->h_items.size());
+  std::vector<std::vector<int>> item_real(p->h_items.size());
   long long frag = 0;
   p->max_jspan = 1;
-  for (int rb = 0; rb < p->n_rb; ++rb) {
-    p->h_rb_frag0[rb] = frag;
-    int jspan = 1;
-    for (int c = 0; c < p->n_chunks; ++c) {
-      nna::CqtChunk ck{0, 0, 0, 0};
-      if (p->sliding) {
-        // taps j*hop + c0 + [0, KC) intersect [s, e)  <=>  j*hop + c0 + KC > s  and  j*hop + c0 < e
-        ck.c0 = c * CQ_KC;
-        long long jlo = floor_div(s_rb[rb] - ck.c0 - CQ_KC, p->hop) + 1;
-        long long jhi = ceil_div(e_rb[rb] - ck.c0, p->hop);
-        jlo = std::max(jlo, 0LL);
-        jhi = std::min(jhi, J);
-        ck.jlo = (int)jlo;
-        ck.nj = (int)std::max(0LL, jhi - jlo);
-        if (ck.nj == 0) ck.jlo = 0;
-      } else {
-        const long long first = s_rb[rb] / CQ_KC;
-        const long long last = ceil_div(e_rb[rb], CQ_KC);
-        ck.c0 = (int)((first + c) * CQ_KC);
-        ck.jlo = 0;
-        ck.nj = (first + c) < last ? 1 : 0;
-        if (ck.nj == 0) ck.c0 = 0;
+  p->n_chunks = 1;
+  for (size_t it = 0; it < p->h_items.size(); ++it) {
+    nna::CqtItem& item = p->h_items[it];
+    item.frag0 = frag;
+    item.jspan = 1;
+    for (int c = 0; c < n_grid; ++c) {
+      int jlo0, nj0;
+      shifts_of(item.rb_first, c, jlo0, nj0);
+      if (nj0 == 0) continue;  // the first (longest) row block has no taps here: nor have the others
+      nna::CqtChunk ck{};
+      ck.c0 = c * CQ_KC;
+      ck.jlo = jlo0;
+      for (int r = 0; r < CQ_ITEM_RB; ++r) {
+        int jlo = 0, nj = 0;
+        if (r < item.n_rb) shifts_of(item.rb_first + r, c, jlo, nj);
+        ck.joff[r] = nj > 0 ? jlo - jlo0 : 0;
+        ck.nj[r] = ring_pad(nj);  // whole rings of CQ_PREFETCH fragments (zero fragments pad)
+        item_real[it].push_back(nj);
+        item.jspan = std::max(item.jspan, ck.joff[r] + ck.nj[r]);
+        frag += ck.nj[r];
       }
-      // the kernel consumes fragments four at a time (its register ring has four fixed slots):
-      // pad with all-zero fragments; pad_ keeps the number of real ones
-      ck.pad_ = ck.nj;
-      ck.nj = (ck.nj + CQ_PREFETCH - 1) / CQ_PREFETCH * CQ_PREFETCH;
-      jspan = std::max(jspan, ck.nj);
-      frag += ck.nj;
-      // only chunks that hold taps are listed (compacted to the front of the row block's table)
-      if (ck.nj > 0) p->h_chunks[(size_t)rb * p->n_chunks + p->h_rb_nchunks[rb]++] = ck;
+      item_chunks[it].push_back(ck);
     }
-    p->h_rb_jspan[rb] = jspan;
-    p->max_jspan = std::max(p->max_jspan, jspan);
+    item.n_chunks = (int)item_chunks[it].size();
+    p->n_chunks = std::max(p->n_chunks, item.n_chunks);  // stride of the chunk table
+    p->max_jspan = std::max(p->max_jspan, item.jspan);
   }
+  p->h_chunks.assign(p->h_items.size() * (size_t)p->n_chunks, nna::CqtChunk{});
+  p->h_nj_real.assign(p->h_items.size() * (size_t)p->n_chunks * CQ_ITEM_RB, 0);
+  for (size_t it = 0; it < p->h_items.size(); ++it)
+    for (size_t c = 0; c < item_chunks[it].size(); ++c) {
+      p->h_chunks[it * p->n_chunks + c] = item_chunks[it][c];
+      for (int r = 0; r < CQ_ITEM_RB; ++r)
+        p->h_nj_real[(it * p->n_chunks + c) * CQ_ITEM_RB + r] = item_real[it][c * CQ_ITEM_RB + r];
+    }
   p->bank_groups = frag;
   p->bank_floats = (size_t)(frag + CQ_PREFETCH) * 64 * 4;
   p->h_bank.assign(p->bank_floats, 0.0f);
   CqtKernelGen gen(p);
-  for (int rb = 0; rb < p->n_rb; ++rb) {
-    long long f = p->h_rb_frag0[rb];
-    for (int c = 0; c < p->h_rb_nchunks[rb]; ++c) {
-      const nna::CqtChunk& ck = p->h_chunks[(size_t)rb * p->n_chunks + c];
-      for (int jj = 0; jj < ck.nj; ++jj, ++f) {
-        if (jj >= ck.pad_) continue;  // zero padding fragment
-        for (int lane = 0; lane < 64; ++lane) {
-          const int q = lane >> 4, r = lane & 15;
-          const long long tap0 = (long long)(ck.jlo + jj) * (p->sliding ? p->hop : 0) + ck.c0 + 4 * q;
-          float* dst = &p->h_bank[((size_t)f * 64 + lane) * 4];
-          for (int e = 0; e < 4; ++e) dst[e] = (float)gen.value(rb * CQ_ROWS + r, tap0 + e);
-        }
-      }
+  for_each_cqt_fragment(p, [&](long long f, int rb, int j, int c0, bool real) {
+    if (!real) return;
+    for (int lane = 0; lane < 64; ++lane) {
+      const int q = lane >> 4, r = lane & 15;
+      const long long tap0 = (long long)j * (p->sliding ? p->hop : 0) + c0 + 4 * q;
+      float* dst = &p->h_bank[((size_t)f * 64 + lane) * 4];
+      for (int e = 0; e < 4; ++e) dst[e] = (float)gen.value(rb * CQ_ROWS + r, tap0 + e);
     }
-  }
+  });
   double sumN = 0;
   for (int k = 0; k < p->n_bins; ++k) sumN += (double)p->Nk[k];
   p->exec_flops = 2.0 * (double)frag * CQ_KC * CQ_ROWS;
@@ -465,10 +508,8 @@ nna_status finish_plan(nna_plan* p, nna_plan** out, const MelDeviceLayout* mel) 
       if (s == NNA_OK) s = upload(&p->d_mel_pass_rt, mel->pass_rt.data(), mel->pass_rt.size() * sizeof(int), "mel pass table");
     }
     if (s == NNA_OK && p->kind == NNA_KIND_CQT) {
-      s = upload(&p->d_rb_frag0, p->h_rb_frag0.data(), p->h_rb_frag0.size() * sizeof(long long), "cqt fragment table");
+      s = upload(&p->d_items, p->h_items.data(), p->h_items.size() * sizeof(nna::CqtItem), "cqt item table");
       if (s == NNA_OK) s = upload(&p->d_chunks, p->h_chunks.data(), p->h_chunks.size() * sizeof(nna::CqtChunk), "cqt chunk table");
-      if (s == NNA_OK) s = upload(&p->d_rb_jspan, p->h_rb_jspan.data(), p->h_rb_jspan.size() * sizeof(int), "cqt span table");
-      if (s == NNA_OK) s = upload(&p->d_rb_nchunks, p->h_rb_nchunks.data(), p->h_rb_nchunks.size() * sizeof(int), "cqt chunk count table");
     }
     if (s != NNA_OK) {
       const std::string keep = g_err;
@@ -745,12 +786,10 @@ nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long l
   std::memset(&P, 0, sizeof(P));
   P.g = make_geom(plan, x_dev, B, L, T);
   P.bank = reinterpret_cast<const float4*>(plan->d_bank);
-  P.rb_frag0 = plan->d_rb_frag0;
+  P.items = plan->d_items;
   P.chunks = plan->d_chunks;
-  P.rb_jspan = plan->d_rb_jspan;
-  P.rb_nchunks = plan->d_rb_nchunks;
   P.out = out_dev;
-  P.n_rb = plan->n_rb;
+  P.n_items = (int)plan->h_items.size();
   P.n_chunks = plan->n_chunks;
   P.n_bins = plan->n_bins;
   P.fmt = plan->fmt;
@@ -789,24 +828,16 @@ nna_status nna_plan_bank(const nna_plan* plan, double* host_out, size_t cap) {
   }
   std::fill(host_out, host_out + rows * K, 0.0);
   if (plan->kind == NNA_KIND_CQT) {
-    for (int rb = 0; rb < plan->n_rb; ++rb) {
-      long long f = plan->h_rb_frag0[rb];
-      for (int c = 0; c < plan->h_rb_nchunks[rb]; ++c) {
-        const nna::CqtChunk& ck = plan->h_chunks[(size_t)rb * plan->n_chunks + c];
-        for (int jj = 0; jj < ck.nj; ++jj, ++f) {
-          if (jj >= ck.pad_) continue;  // zero padding fragment
-          for (int lane = 0; lane < 64; ++lane) {
-            const int q = lane >> 4, r = lane & 15;
-            const long long row = (long long)rb * CQ_ROWS + r;
-            const long long tap0 = (long long)(ck.jlo + jj) * (plan->sliding ? plan->hop : 0) + ck.c0 + 4 * q;
-            for (int e = 0; e < 4; ++e) {
-              const float v = src[((size_t)f * 64 + lane) * 4 + e];
-              if (row < rows && tap0 + e < K) host_out[row * K + tap0 + e] = (double)v;
-            }
-          }
-        }
+    for_each_cqt_fragment(plan, [&](long long f, int rb, int j, int c0, bool real) {
+      if (!real) return;
+      for (int lane = 0; lane < 64; ++lane) {
+        const int q = lane >> 4, r = lane & 15;
+        const long long row = (long long)rb * CQ_ROWS + r;
+        const long long tap0 = (long long)j * (plan->sliding ? plan->hop : 0) + c0 + 4 * q;
+        for (int e = 0; e < 4; ++e)
+          if (row < rows && tap0 + e < K) host_out[row * K + tap0 + e] = (double)src[((size_t)f * 64 + lane) * 4 + e];
       }
-    }
+    });
   } else {
     const long long G = (long long)plan->n_chunks * plan->nj * ST_NKG;
     for (int rt = 0; rt < plan->n_rt; ++rt)
@@ -908,10 +939,8 @@ void nna_plan_destroy(nna_plan* plan) {
       (void)hipFree(plan->d_mel_mask);
       (void)hipFree(plan->d_mel_wnyq);
       (void)hipFree(plan->d_mel_pass_rt);
-      (void)hipFree(plan->d_rb_frag0);
+      (void)hipFree(plan->d_items);
       (void)hipFree(plan->d_chunks);
-      (void)hipFree(plan->d_rb_jspan);
-      (void)hipFree(plan->d_rb_nchunks);
     }
   }
   delete plan;
