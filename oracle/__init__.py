@@ -21,6 +21,7 @@ _LIB = os.path.join(_HERE, "libnna_oracle.so")
 MAGNITUDE, POWER, LOG = 0, 1, 2
 WIN_HANN, WIN_RECT = 0, 1
 MEL_SLANEY, MEL_HTK = 0, 1
+FREQ_DFT, FREQ_LINEAR, FREQ_LOG = 0, 1, 2
 LOG_FLOOR = 1e-10
 
 
@@ -54,6 +55,10 @@ def lib():
         L.orc_window.argtypes = [_I, _LL, _PD]
         L.orc_stft_complex.argtypes = [_PF, _LL, _LL, _I, _I, _I, _I, _PD, _PD]
         L.orc_stft.argtypes = [_PF, _LL, _LL, _I, _I, _I, _I, _I, _PD]
+        L.orc_freq_sigma.restype = _D
+        L.orc_freq_sigma.argtypes = [_I, _LL, _D, _D, _LL, _LL, _D]
+        L.orc_stft_sigma_complex.argtypes = [_PF, _LL, _LL, _I, _I, _I, _I, _LL, _PD, _PD, _PD]
+        L.orc_stft_scaled.argtypes = [_PF, _LL, _LL, _I, _I, _I, _I, _I, _I, _D, _D, _LL, _I, _PD]
         L.orc_hz_to_mel.restype = _D
         L.orc_hz_to_mel.argtypes = [_D, _I]
         L.orc_mel_to_hz.restype = _D
@@ -135,6 +140,39 @@ def stft(x, n_fft=2048, hop=512, window=WIN_HANN, center=True, fmt=MAGNITUDE):
         raise OracleError("signal too short")
     out = np.empty((B, n_fft // 2 + 1, T), dtype=np.float64)
     _check(lib().orc_stft(_pf(x), B, L, n_fft, hop, window, int(center), fmt, _pd(out)), "stft")
+    return out
+
+
+def freq_sigma(scale, k, fmin, fmax, freq_bins, n_fft, sr) -> float:
+    return float(lib().orc_freq_sigma(scale, k, fmin, fmax, freq_bins, n_fft, float(sr)))
+
+
+def stft_sigma_complex(x, sigma, n_fft=2048, hop=512, window=WIN_HANN, center=True):
+    x = _x(x)
+    B, L = x.shape
+    sigma = np.ascontiguousarray(sigma, dtype=np.float64)
+    T = num_frames(L, n_fft, hop, center)
+    if T < 1:
+        raise OracleError("signal too short")
+    re = np.empty((B, sigma.size, T), dtype=np.float64)
+    im = np.empty_like(re)
+    _check(lib().orc_stft_sigma_complex(_pf(x), B, L, n_fft, hop, window, int(center), sigma.size, _pd(sigma),
+                                        _pd(re), _pd(im)), "stft_sigma_complex")
+    return re, im
+
+
+def stft_scaled(x, sr=22050, n_fft=2048, hop=512, window=WIN_HANN, center=True, scale=FREQ_LINEAR, fmin=50.0,
+                fmax=6000.0, freq_bins=0, fmt=MAGNITUDE):
+    x = _x(x)
+    B, L = x.shape
+    if freq_bins <= 0:
+        freq_bins = n_fft // 2 + 1
+    T = num_frames(L, n_fft, hop, center)
+    if T < 1:
+        raise OracleError("signal too short")
+    out = np.empty((B, freq_bins, T), dtype=np.float64)
+    _check(lib().orc_stft_scaled(_pf(x), B, L, sr, n_fft, hop, window, int(center), scale, fmin, fmax, freq_bins,
+                                 fmt, _pd(out)), "stft_scaled")
     return out
 
 

@@ -32,6 +32,9 @@
  *   orc_window                              pinned (closed forms)
  *   orc_stft_complex / orc_stft             pinned (textbook DFT, tone peak,
  *                                           Parseval, impulse support)
+ *   orc_freq_sigma                          pinned (worked values of Sec. II-B)
+ *   orc_stft_sigma_complex / orc_stft_scaled pinned (integer sigma = textbook DFT,
+ *                                           tone peak at the bin's frequency)
  *   orc_hz_to_mel / orc_mel_to_hz           pinned (inverse pair, continuity)
  *   orc_mel_filterbank                      pinned (Table 1 of the paper)
  *   orc_mel                                 pinned (Fig. 2 scenario, linearity)
@@ -63,6 +66,11 @@
 /* windows */
 #define ORC_WIN_HANN 0
 #define ORC_WIN_RECT 1
+
+/* frequency axis of the STFT (Sec. II-B) */
+#define ORC_FREQ_DFT 0
+#define ORC_FREQ_LINEAR 1
+#define ORC_FREQ_LOG 2
 
 /* mel scales */
 #define ORC_MEL_SLANEY 0
@@ -182,6 +190,86 @@ int orc_stft(const float *x, long long B, long long L, int n_fft, int hop, int w
   if (rc == ORC_OK)
     for (long long i = 0; i < n; ++i) out[i] = apply_format(re[i] * re[i] + im[i] * im[i], fmt);
   free(re); free(im);
+  return rc;
+}
+
+/* Normalised frequency sigma(k) of bin k when the DFT's basis frequencies are re-spaced
+ * between f_s and f_e over mu bins (Sec. II-B):
+ *   linear, eq. (linear-frequency-DFT):  sigma(k) = (f_e - f_s) N / (mu s) * k + f_s N / s
+ *   log,    eq. (log-frequency-DFT):     sigma(k) = (f_s N / s) * (f_e / f_s)^(k / mu)
+ * with k = 0..mu-1, as in the worked example of that section (f_s = 50, f_e = 6000,
+ * N = 2048, s = 44100, 1025 bins).  scale 0 gives the plain DFT, sigma(k) = k. */
+double orc_freq_sigma(int scale, long long k, double f_s, double f_e, long long mu, long long N, double s) {
+  if (scale == ORC_FREQ_LINEAR) return (f_e - f_s) * (double)N / ((double)mu * s) * (double)k + f_s * (double)N / s;
+  if (scale == ORC_FREQ_LOG) return f_s * (double)N / s * pow(f_e / f_s, (double)k / (double)mu);
+  return (double)k;
+}
+
+/* STFT with re-spaced basis frequencies, eq. (DFT3) applied to every window:
+ *   Re[b,k,t] =  sum_n w[n] xp_b[t hop + n] cos(2 pi sigma[k] n / N)
+ *   Im[b,k,t] = -sum_n w[n] xp_b[t hop + n] sin(2 pi sigma[k] n / N),   k = 0..n_bins-1,
+ * for any real sigma[k] (no table trick: sigma is not an integer).  re, im: [B, n_bins, T]. */
+int orc_stft_sigma_complex(const float *x, long long B, long long L, int n_fft, int hop, int window,
+                           int center, long long n_bins, const double *sigma, double *re, double *im) {
+  if (!x || !re || !im || !sigma || B < 1 || n_fft < 2 || (n_fft & 1) || hop < 1 || n_bins < 1) return ORC_EINVAL;
+  const long long N = n_fft, pad = center ? N / 2 : 0;
+  if (center && L <= pad) return ORC_EINVAL;
+  const long long T = orc_num_frames(L, N, hop, center);
+  if (T < 1) return ORC_EINVAL;
+  double *w = (double *)malloc(sizeof(double) * N);
+  double *ct = (double *)malloc(sizeof(double) * N * n_bins);
+  double *st = (double *)malloc(sizeof(double) * N * n_bins);
+  if (!w || !ct || !st) { free(w); free(ct); free(st); return ORC_ENOMEM; }
+  if (orc_window(window, N, w) != ORC_OK) { free(w); free(ct); free(st); return ORC_EINVAL; }
+  for (long long k = 0; k < n_bins; ++k)
+    for (long long n = 0; n < N; ++n) {
+      const double a = 2.0 * ORC_PI * sigma[k] * (double)n / (double)N;
+      ct[k * N + n] = cos(a);
+      st[k * N + n] = sin(a);
+    }
+  int fail = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 4)
+  for (long long b = 0; b < B; ++b) {
+    for (long long t = 0; t < T; ++t) {
+      double *frame = (double *)malloc(sizeof(double) * N);
+      if (!frame) { fail = 1; continue; }
+      const float *xb = x + b * L;
+      for (long long n = 0; n < N; ++n) frame[n] = w[n] * padded_sample(xb, L, pad, t * hop + n);
+      for (long long k = 0; k < n_bins; ++k) {
+        double sr = 0.0, si = 0.0;
+        for (long long n = 0; n < N; ++n) {
+          sr += frame[n] * ct[k * N + n];
+          si += frame[n] * st[k * N + n];
+        }
+        re[(b * n_bins + k) * T + t] = sr;
+        im[(b * n_bins + k) * T + t] = -si;
+      }
+      free(frame);
+    }
+  }
+  free(w); free(ct); free(st);
+  return fail ? ORC_ENOMEM : ORC_OK;
+}
+
+/* Spectrogram on a linear or log frequency axis (Sec. II-B; the STFT's freq_scale argument,
+ * Sec. III-A): bins k = 0..freq_bins-1 at sigma(k) between fmin and fmax.  out: [B, freq_bins, T]. */
+int orc_stft_scaled(const float *x, long long B, long long L, int sr, int n_fft, int hop, int window,
+                    int center, int scale, double fmin, double fmax, long long freq_bins, int fmt, double *out) {
+  if (!out || fmt < 0 || fmt > 2 || freq_bins < 1) return ORC_EINVAL;
+  if (scale != ORC_FREQ_LINEAR && scale != ORC_FREQ_LOG) return ORC_EINVAL;
+  if (!(fmax > fmin) || fmin < 0.0 || (scale == ORC_FREQ_LOG && !(fmin > 0.0))) return ORC_EINVAL;
+  const long long T = orc_num_frames(L, n_fft, hop, center);
+  if (T < 1 || B < 1) return ORC_EINVAL;
+  const long long n = B * freq_bins * T;
+  double *sigma = (double *)malloc(sizeof(double) * freq_bins);
+  double *re = (double *)malloc(sizeof(double) * n);
+  double *im = (double *)malloc(sizeof(double) * n);
+  if (!sigma || !re || !im) { free(sigma); free(re); free(im); return ORC_ENOMEM; }
+  for (long long k = 0; k < freq_bins; ++k) sigma[k] = orc_freq_sigma(scale, k, fmin, fmax, freq_bins, n_fft, (double)sr);
+  int rc = orc_stft_sigma_complex(x, B, L, n_fft, hop, window, center, freq_bins, sigma, re, im);
+  if (rc == ORC_OK)
+    for (long long i = 0; i < n; ++i) out[i] = apply_format(re[i] * re[i] + im[i] * im[i], fmt);
+  free(sigma); free(re); free(im);
   return rc;
 }
 
