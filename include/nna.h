@@ -69,6 +69,11 @@ typedef enum {
   NNA_MEL_HTK = 1     /* eq. (mel-o): 2595 log10(1 + f/700) */
 } nna_mel_scale;
 
+typedef enum {
+  NNA_FREQ_LINEAR = 1, /* eq. (linear-frequency-DFT): bins equally spaced in Hz from fmin */
+  NNA_FREQ_LOG = 2     /* eq. (log-frequency-DFT): bins in geometric progression from fmin */
+} nna_freq_scale;
+
 typedef enum { NNA_KIND_STFT = 0, NNA_KIND_MEL = 1, NNA_KIND_CQT = 2 } nna_kind;
 
 /*
@@ -81,6 +86,22 @@ typedef enum { NNA_KIND_STFT = 0, NNA_KIND_MEL = 1, NNA_KIND_CQT = 2 } nna_kind;
  */
 nna_status nna_plan_stft(nna_plan** plan, int sr, int n_fft, int hop, nna_window win, int center,
                          nna_output fmt, int device);
+
+/*
+ * STFT plan on a re-spaced frequency axis (Sec. II-B; the freq_scale / fmin / fmax /
+ * freq_bins arguments of the paper's STFT layer, Sec. III-A).  Bin k = 0..freq_bins-1 has
+ * the normalised frequency
+ *   linear: sigma(k) = (fmax - fmin) N / (freq_bins sr) k + fmin N / sr
+ *   log:    sigma(k) = (fmin N / sr) (fmax / fmin)^(k / freq_bins)
+ * and the bank rows are eq. (DFT3) with the window folded in:
+ * Re_k[n] = w[n] cos(2 pi sigma(k) n / N), Im_k[n] = -w[n] sin(2 pi sigma(k) n / N).
+ * Only the bank differs from nna_plan_stft; the plan runs through nna_stft.
+ *   freq_bins  1..16384, or 0 for n_fft/2 + 1;  0 <= fmin < fmax <= sr/2 (log: fmin > 0).
+ * Output bins = freq_bins.
+ */
+nna_status nna_plan_stft_scaled(nna_plan** plan, int sr, int n_fft, int hop, nna_window win, int center,
+                                nna_output fmt, nna_freq_scale freq_scale, double fmin, double fmax,
+                                int freq_bins, int device);
 
 /*
  * Mel-spectrogram plan (Sec. III-B, Fig. 3): the STFT above followed, inside the same
@@ -110,8 +131,8 @@ nna_status nna_plan_cqt(nna_plan** plan, int sr, int hop, double fmin, int n_bin
 nna_status nna_out_shape(const nna_plan* plan, long long B, long long L, long long* n_bins,
                          long long* n_frames);
 
-/* out_dev[B, n_fft/2+1, T] = STFT of x_dev[B, L] in the plan's output format.
- * The plan must come from nna_plan_stft. */
+/* out_dev[B, F, T] = STFT of x_dev[B, L] in the plan's output format; F = n_fft/2+1 for a
+ * plan from nna_plan_stft, freq_bins for one from nna_plan_stft_scaled. */
 nna_status nna_stft(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
                     void* hip_stream);
 
@@ -149,6 +170,10 @@ nna_status nna_plan_info(const nna_plan* plan, int* kind, long long* bank_rows, 
 
 /* CQT plans only: kernel lengths N_k, k = 0..n_bins-1 (host array of n_bins entries). */
 nna_status nna_plan_cqt_lengths(const nna_plan* plan, long long* host_out, size_t cap);
+
+/* STFT plans only: normalised bin frequencies sigma(k), k = 0..out_bins-1, in units of sr/n_fft
+ * (host array; k itself for a plan from nna_plan_stft). */
+nna_status nna_plan_sigma(const nna_plan* plan, double* host_out, size_t cap);
 
 void nna_plan_destroy(nna_plan* plan); /* NULL is allowed */
 

@@ -19,12 +19,14 @@ NNA_ERR_INVALID_ARG, NNA_ERR_UNSUPPORTED, NNA_ERR_SHAPE, NNA_ERR_ALLOC, NNA_ERR_
 NNA_OUT_MAGNITUDE, NNA_OUT_POWER, NNA_OUT_LOG = 0, 1, 2
 NNA_WIN_HANN, NNA_WIN_RECT = 0, 1
 NNA_MEL_SLANEY, NNA_MEL_HTK = 0, 1
+NNA_FREQ_LINEAR, NNA_FREQ_LOG = 1, 2
 NNA_KIND_STFT, NNA_KIND_MEL, NNA_KIND_CQT = 0, 1, 2
 
 # every symbol include/nna.h declares
 EXPORTS = [
-    "nna_plan_stft", "nna_plan_mel", "nna_plan_cqt", "nna_out_shape", "nna_stft", "nna_mel", "nna_cqt",
-    "nna_plan_bank", "nna_plan_mel_weights", "nna_plan_info", "nna_plan_cqt_lengths", "nna_plan_destroy",
+    "nna_plan_stft", "nna_plan_stft_scaled", "nna_plan_mel", "nna_plan_cqt", "nna_out_shape", "nna_stft", "nna_mel", "nna_cqt",
+    "nna_plan_bank", "nna_plan_mel_weights", "nna_plan_info", "nna_plan_cqt_lengths", "nna_plan_sigma",
+    "nna_plan_destroy",
     "nna_status_str", "nna_last_error",
 ]
 
@@ -52,6 +54,8 @@ def lib():
         L = _c.CDLL(LIB_PATH)
         PP = _c.POINTER(_VP)
         L.nna_plan_stft.argtypes = [PP, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int]
+        L.nna_plan_stft_scaled.argtypes = [PP, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
+                                           _c.c_double, _c.c_double, _c.c_int, _c.c_int]
         L.nna_plan_mel.argtypes = [PP, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_double,
                                    _c.c_double, _c.c_int, _c.c_int, _c.c_double, _c.c_int]
         L.nna_plan_cqt.argtypes = [PP, _c.c_int, _c.c_int, _c.c_double, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
@@ -64,6 +68,7 @@ def lib():
         L.nna_plan_info.argtypes = [_VP, _c.POINTER(_c.c_int), _c.POINTER(_LL), _c.POINTER(_LL), _c.POINTER(_LL),
                                     _c.POINTER(_c.c_double), _c.POINTER(_c.c_double)]
         L.nna_plan_cqt_lengths.argtypes = [_VP, _c.POINTER(_LL), _c.c_size_t]
+        L.nna_plan_sigma.argtypes = [_VP, _c.POINTER(_c.c_double), _c.c_size_t]
         L.nna_plan_destroy.argtypes = [_VP]
         L.nna_plan_destroy.restype = None
         L.nna_status_str.argtypes = [_c.c_int]
@@ -121,6 +126,12 @@ def nna_plan_stft(sr=22050, n_fft=2048, hop=512, win=NNA_WIN_HANN, center=True, 
     return _new_plan(lib().nna_plan_stft, (sr, n_fft, hop, win, int(center), fmt), device)
 
 
+def nna_plan_stft_scaled(sr=22050, n_fft=2048, hop=512, win=NNA_WIN_HANN, center=True, fmt=NNA_OUT_MAGNITUDE,
+                         freq_scale=NNA_FREQ_LINEAR, fmin=50.0, fmax=6000.0, freq_bins=0, device=0) -> Plan:
+    return _new_plan(lib().nna_plan_stft_scaled,
+                     (sr, n_fft, hop, win, int(center), fmt, freq_scale, float(fmin), float(fmax), freq_bins), device)
+
+
 def nna_plan_mel(sr=22050, n_fft=2048, hop=512, win=NNA_WIN_HANN, center=True, n_mels=128, fmin=0.0, fmax=0.0,
                  scale=NNA_MEL_SLANEY, norm_area=True, power=2.0, device=0) -> Plan:
     return _new_plan(lib().nna_plan_mel,
@@ -161,6 +172,13 @@ def nna_plan_cqt_lengths(plan: Plan) -> np.ndarray:
     return out
 
 
+def nna_plan_sigma(plan: Plan) -> np.ndarray:
+    i = plan.info()
+    out = np.empty(i["out_bins"], dtype=np.float64)
+    _check(lib().nna_plan_sigma(plan.handle, out.ctypes.data_as(_c.POINTER(_c.c_double)), out.size))
+    return out
+
+
 def _run(fn, plan: Plan, x, out, stream):
     import torch
 
@@ -184,7 +202,8 @@ def _run(fn, plan: Plan, x, out, stream):
 
 
 def nna_stft(plan: Plan, x, out=None, stream=None):
-    """out[B, n_fft/2+1, T] = STFT of x[B, L] (device tensors; asynchronous on `stream`)."""
+    """out[B, F, T] = STFT of x[B, L] (device tensors; asynchronous on `stream`); F = n_fft/2+1, or freq_bins
+    for a plan from nna_plan_stft_scaled."""
     return _run(lib().nna_stft, plan, x, out, stream)
 
 

@@ -52,7 +52,9 @@ struct StftParams {
   int n_rt;             // row tiles
   int n_chunks;         // LDS chunks per row tile
   int nj;               // hop-shifts per chunk (n_fft/hop when the frames overlap in LDS, else 1)
-  int n_half;           // n_fft / 2: number of (Re,Im) slots that exist
+  int n_half;           // number of (Re,Im) slots that exist (n_fft / 2 for the plain DFT)
+  int packed;           // 1: slot 0 packs the two real bins 0 and n_half (plain DFT); 0: slot s = bin s
+  int out_bins;         // bins per waveform in `out`
   int fmt;              // nna_output (STFT) ; Mel: 1 = magnitude before the filterbank, 2 = power
   long long n_ft;       // frame tiles
   int tile_frames;      // frames per tile (<= ST_FRAMES; smaller only when many short waveforms share a tile)

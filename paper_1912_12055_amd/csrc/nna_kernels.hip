@@ -108,7 +108,6 @@ __device__ __forceinline__ void wait_vm(f32x4 (&r)[8]) {
 // 64 lanes.  Rows that do not exist read a dummy window: nobody reads their LDS rows.
 // The (pass -> row) descriptors are computed once per tile and kept in registers.
 // ---------------------------------------------------------------------------------------
-constexpr unsigned SEL_IDENTITY = 0xE4u;
 
 __device__ __forceinline__ int reflect_clamped(int j, int L) {
   int r = j < 0 ? -j : (j >= L ? 2 * (L - 1) - j : j);
@@ -241,7 +240,7 @@ __device__ __forceinline__ float format_power(float pw) {
 // store instruction writes two 128-byte runs.
 template <int FMT>
 __device__ __forceinline__ void stft_store_tile(const f32x16 (&acc)[ST_RB], float* __restrict__ op, long long T,
-                                                int slot_base, int h, int n_half) {
+                                                int slot_base, int h, int n_half, int packed) {
   float* __restrict__ p = op + (slot_base + 2 * h) * T;
   if (slot_base > 0 && slot_base + ST_ROWS / 2 <= n_half) {
     // interior tile: all 64 slots exist and none is the packed DC/Nyquist slot
@@ -260,7 +259,7 @@ __device__ __forceinline__ void stft_store_tile(const f32x16 (&acc)[ST_RB], floa
         const float re = acc[rb][2 * u], im = acc[rb][2 * u + 1];
         const int k = rb * 16 + 4 * (u >> 1) + (u & 1);
         const int slot = slot_base + 2 * h + k;
-        if (slot == 0) {  // slot 0 packs the two purely real bins: DC and Nyquist
+        if (slot == 0 && packed) {  // slot 0 packs the two purely real bins: DC and Nyquist
           op[0] = format_power<FMT>(re * re);
           op[n_half * T] = format_power<FMT>(im * im);
         } else if (slot < n_half) {
@@ -489,13 +488,13 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
       const int slot_base = rt * (ST_ROWS / 2);
       if constexpr (!MEL) {
         if (valid) {
-          float* __restrict__ op = P.out + (b_lane * (P.n_half + 1)) * g.T + t_lane;
+          float* __restrict__ op = P.out + (b_lane * P.out_bins) * g.T + t_lane;
           if (P.fmt == NNA_OUT_MAGNITUDE)
-            stft_store_tile<NNA_OUT_MAGNITUDE>(acc, op, g.T, slot_base, h, P.n_half);
+            stft_store_tile<NNA_OUT_MAGNITUDE>(acc, op, g.T, slot_base, h, P.n_half, P.packed);
           else if (P.fmt == NNA_OUT_POWER)
-            stft_store_tile<NNA_OUT_POWER>(acc, op, g.T, slot_base, h, P.n_half);
+            stft_store_tile<NNA_OUT_POWER>(acc, op, g.T, slot_base, h, P.n_half, P.packed);
           else
-            stft_store_tile<NNA_OUT_LOG>(acc, op, g.T, slot_base, h, P.n_half);
+            stft_store_tile<NNA_OUT_LOG>(acc, op, g.T, slot_base, h, P.n_half, P.packed);
         }
       } else {
         const unsigned char* __restrict__ maskp = P.mel_mask + ((long long)pass * P.n_rt + rt) * ST_RB;

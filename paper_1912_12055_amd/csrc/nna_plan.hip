@@ -37,8 +37,14 @@ struct nna_plan {
   bool sliding = false;
 
   // STFT / Mel
-  int n_half = 0, n_rt = 0, n_chunks = 0, nj = 1;
+  int n_half = 0, n_rt = 0, n_chunks = 0, nj = 1;  // n_half: (Re, Im) slots of the packed bank
   long long bank_groups = 0;
+  int freq_scale = 0;         // 0: plain DFT bins; else nna_freq_scale (STFT only)
+  int freq_bins = 0;          // re-spaced axis: number of bins
+  std::vector<double> sigma;  // re-spaced axis: normalised frequency of each bin
+
+  // output bins of an STFT plan; a plain DFT packs bins 0 and N/2 (both purely real) into slot 0
+  int stft_bins() const { return freq_scale ? n_half : n_half + 1; }
   // Mel
   int n_mels = 0, mel_power = 2, n_pass = 0, mel_nyq_any = 0;
   std::vector<float> h_melW;  // [n_mels, F] as rounded to float32
@@ -171,10 +177,21 @@ inline int stft_tap(const nna_plan* p, int c, int j, int kg, int h, int e) {
   return j * p->hop + c * ST_KC + kg * ST_KG + 4 * h + e;
 }
 
+// eq. (DFT3) with the window folded in, for a real normalised frequency sigma
+double scaled_value(const nna_plan* p, int pr, int k) {
+  if (k >= p->K) return 0.0;
+  const int slot = pr >> 1, part = pr & 1;
+  if (slot >= p->n_half) return 0.0;
+  // reduce sigma*k modulo N before the multiplication by 2 pi / N: the product is exact in double
+  const double turns = std::fmod(p->sigma[slot] * (double)k, (double)p->K) / (double)p->K;
+  const double w = window_value(p->window, k, p->K);
+  return part == 0 ? w * std::cos(2.0 * kPi * turns) : -w * std::sin(2.0 * kPi * turns);
+}
+
 void build_stft_bank(nna_plan* p) {
   const int N = p->K;
-  p->n_half = N / 2;
-  p->n_rt = (N + ST_ROWS - 1) / ST_ROWS;  // packed rows = 2 * n_half = N
+  p->n_half = p->freq_scale ? p->freq_bins : N / 2;
+  p->n_rt = (2 * p->n_half + ST_ROWS - 1) / ST_ROWS;  // plain DFT: packed rows = 2 * n_half = N
   const int J = (p->hop > 0 && N % p->hop == 0) ? N / p->hop : 0;
   p->sliding = J >= 1 && J <= 32 && p->hop % ST_KC == 0;
   if (p->sliding) {
@@ -200,12 +217,14 @@ void build_stft_bank(nna_plan* p) {
               const int pr = rt * ST_ROWS + rb * 32 + r;
               float* dst = &p->h_bank[((((size_t)rt * G + g) * ST_RB + rb) * 64 + lane) * 4];
               for (int e = 0; e < 4; ++e)
-                dst[e] = (float)stft_packed_value(tab, p->n_half, pr, stft_tap(p, c, j, kg, h, e));
+                dst[e] = (float)(p->freq_scale ? scaled_value(p, pr, stft_tap(p, c, j, kg, h, e))
+                                               : stft_packed_value(tab, p->n_half, pr, stft_tap(p, c, j, kg, h, e)));
             }
         }
   const double k_exec = (double)p->n_chunks * p->nj * ST_KC;
   p->exec_flops = 2.0 * k_exec * (double)p->n_rt * ST_ROWS;
-  p->alg_flops = 2.0 * (double)N * (double)N;  // N non-zero rows (cos 0..N/2, sin 1..N/2-1) x N taps
+  // plain DFT: N non-zero rows (cos 0..N/2, sin 1..N/2-1) x N taps; re-spaced: 2 rows per bin
+  p->alg_flops = p->freq_scale ? 2.0 * (double)N * 2.0 * (double)p->n_half : 2.0 * (double)N * (double)N;
 }
 
 // ---- Mel filterbank (Sec. III-B) ------------------------------------------------------
@@ -603,6 +622,8 @@ nna_status run_stft_like(const nna_plan* plan, int kind, const float* x, long lo
   P.n_chunks = plan->n_chunks;
   P.nj = plan->nj;
   P.n_half = plan->n_half;
+  P.packed = plan->freq_scale ? 0 : 1;
+  P.out_bins = kind == NNA_KIND_MEL ? plan->n_mels : plan->stft_bins();
   P.tile_frames = M;
   P.n_ft = (P.g.n_frames + M - 1) / M;
   if (kind == NNA_KIND_MEL) {
@@ -651,6 +672,49 @@ nna_status nna_plan_stft(nna_plan** plan, int sr, int n_fft, int hop, nna_window
     p->fmt = fmt;
     p->K = n_fft;
     p->pad = center ? n_fft / 2 : 0;
+    build_stft_bank(p);
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return fail(NNA_ERR_ALLOC, "out of host memory while building the DFT bank");
+  }
+  return finish_plan(p, plan, nullptr);
+}
+
+nna_status nna_plan_stft_scaled(nna_plan** plan, int sr, int n_fft, int hop, nna_window win, int center,
+                                nna_output fmt, nna_freq_scale freq_scale, double fmin, double fmax, int freq_bins,
+                                int device) {
+  nna_status s = check_common(plan, sr, hop, win, center, device);
+  if (s != NNA_OK) return s;
+  if ((s = check_stft_args(n_fft)) != NNA_OK) return s;
+  if (fmt != NNA_OUT_MAGNITUDE && fmt != NNA_OUT_POWER && fmt != NNA_OUT_LOG)
+    return fail(NNA_ERR_INVALID_ARG, "unknown output format");
+  if (freq_scale != NNA_FREQ_LINEAR && freq_scale != NNA_FREQ_LOG)
+    return fail(NNA_ERR_INVALID_ARG, "freq_scale must be NNA_FREQ_LINEAR or NNA_FREQ_LOG");
+  if (freq_bins == 0) freq_bins = n_fft / 2 + 1;
+  if (freq_bins < 1 || freq_bins > 16384) return fail(NNA_ERR_INVALID_ARG, "freq_bins must be in [1, 16384]");
+  if (!(fmin >= 0.0) || !(fmax > fmin) || fmax > 0.5 * sr)
+    return fail(NNA_ERR_INVALID_ARG, "need 0 <= fmin < fmax <= sr/2");
+  if (freq_scale == NNA_FREQ_LOG && !(fmin > 0.0))
+    return fail(NNA_ERR_INVALID_ARG, "a log frequency axis needs fmin > 0");
+  nna_plan* p = new (std::nothrow) nna_plan;
+  if (!p) return fail(NNA_ERR_ALLOC, "out of host memory");
+  try {
+    p->kind = NNA_KIND_STFT;
+    p->device = device;
+    p->sr = sr;
+    p->hop = hop;
+    p->center = center;
+    p->window = win;
+    p->fmt = fmt;
+    p->K = n_fft;
+    p->pad = center ? n_fft / 2 : 0;
+    p->freq_scale = freq_scale;
+    p->freq_bins = freq_bins;
+    p->sigma.resize(freq_bins);
+    const double N = n_fft, mu = freq_bins;
+    for (int k = 0; k < freq_bins; ++k)
+      p->sigma[k] = freq_scale == NNA_FREQ_LINEAR ? (fmax - fmin) * N / (mu * sr) * k + fmin * N / sr
+                                                  : fmin * N / sr * std::pow(fmax / fmin, k / mu);
     build_stft_bank(p);
   } catch (const std::bad_alloc&) {
     delete p;
@@ -762,7 +826,7 @@ nna_status nna_out_shape(const nna_plan* plan, long long B, long long L, long lo
   if (B < 1) return fail(NNA_ERR_SHAPE, "B must be >= 1");
   const long long T = frames_of(plan, L);
   if (T < 1) return fail(NNA_ERR_SHAPE, plan->center ? "L must exceed the reflection padding (K/2)" : "L is shorter than one window");
-  if (n_bins) *n_bins = plan->kind == NNA_KIND_STFT ? plan->n_half + 1 : plan->kind == NNA_KIND_MEL ? plan->n_mels : plan->n_bins;
+  if (n_bins) *n_bins = plan->kind == NNA_KIND_STFT ? plan->stft_bins() : plan->kind == NNA_KIND_MEL ? plan->n_mels : plan->n_bins;
   if (n_frames) *n_frames = T;
   return NNA_OK;
 }
@@ -807,7 +871,7 @@ nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long l
 
 nna_status nna_plan_bank(const nna_plan* plan, double* host_out, size_t cap) {
   if (!plan || !host_out) return fail(NNA_ERR_INVALID_ARG, "plan / host_out is NULL");
-  const long long rows = plan->kind == NNA_KIND_CQT ? 2LL * plan->n_bins : 2LL * (plan->n_half + 1);
+  const long long rows = plan->kind == NNA_KIND_CQT ? 2LL * plan->n_bins : 2LL * (plan->freq_scale ? plan->n_half : plan->n_half + 1);
   const long long K = plan->K;
   if ((unsigned long long)cap < (unsigned long long)(rows * K)) return fail(NNA_ERR_INVALID_ARG, "host_out is too small");
   std::vector<float> tmp;
@@ -852,7 +916,7 @@ nna_status nna_plan_bank(const nna_plan* plan, double* host_out, size_t cap) {
                 const int slot = pr >> 1, part = pr & 1;
                 if (slot >= plan->n_half) continue;
                 // packed slot 0 = (Re bin 0, Re bin N/2); slot s = (Re, Im) of bin s
-                const long long row = slot == 0 ? (part == 0 ? 0 : 2LL * plan->n_half) : 2LL * slot + part;
+                const long long row = slot == 0 && !plan->freq_scale ? (part == 0 ? 0 : 2LL * plan->n_half) : 2LL * slot + part;
                 for (int e = 0; e < 4; ++e) {
                   const int k = stft_tap(plan, c, j, kg, h, e);
                   if (k < K) host_out[row * K + k] = (double)src[((((size_t)rt * G + g) * ST_RB + rb) * 64 + lane) * 4 + e];
@@ -913,11 +977,20 @@ nna_status nna_plan_info(const nna_plan* plan, int* kind, long long* bank_rows, 
                          double* executed_flops_per_frame, double* algorithmic_flops_per_frame) {
   if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
   if (kind) *kind = plan->kind;
-  if (bank_rows) *bank_rows = plan->kind == NNA_KIND_CQT ? 2LL * plan->n_bins : 2LL * (plan->n_half + 1);
+  if (bank_rows) *bank_rows = plan->kind == NNA_KIND_CQT ? 2LL * plan->n_bins : 2LL * (plan->freq_scale ? plan->n_half : plan->n_half + 1);
   if (taps) *taps = plan->K;
-  if (out_bins) *out_bins = plan->kind == NNA_KIND_STFT ? plan->n_half + 1 : plan->kind == NNA_KIND_MEL ? plan->n_mels : plan->n_bins;
+  if (out_bins) *out_bins = plan->kind == NNA_KIND_STFT ? plan->stft_bins() : plan->kind == NNA_KIND_MEL ? plan->n_mels : plan->n_bins;
   if (executed_flops_per_frame) *executed_flops_per_frame = plan->exec_flops;
   if (algorithmic_flops_per_frame) *algorithmic_flops_per_frame = plan->alg_flops;
+  return NNA_OK;
+}
+
+nna_status nna_plan_sigma(const nna_plan* plan, double* host_out, size_t cap) {
+  if (!plan || !host_out) return fail(NNA_ERR_INVALID_ARG, "plan / host_out is NULL");
+  if (plan->kind != NNA_KIND_STFT) return fail(NNA_ERR_INVALID_ARG, "not an STFT plan");
+  const int F = plan->stft_bins();
+  if (cap < (size_t)F) return fail(NNA_ERR_INVALID_ARG, "host_out is too small");
+  for (int k = 0; k < F; ++k) host_out[k] = plan->freq_scale ? plan->sigma[k] : (double)k;
   return NNA_OK;
 }
 

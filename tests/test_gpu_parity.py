@@ -124,6 +124,46 @@ def test_stft_tone_closed_form_on_gpu(nb):
     assert np.max(np.abs(got[k0] - 512.0 * A)) < 1e-3 * 512.0 * A
 
 
+SCALED_CASES = [
+    # name, B, L, sr, n_fft, hop, scale, fmin, fmax, bins, center, fmt
+    ("linear axis, bins not a multiple of the row tile", 3, 9000, 22050, 256, 64, 1, 50.0, 6000.0, 100, True, 0),
+    ("linear axis, one partial row tile", 2, 5000, 16000, 128, 32, 1, 0.0, 8000.0, 7, True, 1),
+    ("log axis, seven octaves", 4, 12000, 22050, 512, 128, 2, 55.0, 7040.0, 84, True, 0),
+    ("log axis, hop does not divide n_fft, log output", 2, 7000, 22050, 240, 50, 2, 100.0, 9000.0, 129, False, 2),
+    ("more bins than n_fft/2+1", 2, 6000, 22050, 128, 32, 1, 20.0, 11000.0, 300, True, 0),
+]
+
+
+@pytest.mark.parametrize("case", SCALED_CASES, ids=[c[0] for c in SCALED_CASES])
+def test_scaled_stft_parity_small(nb, case):
+    name, B, L, sr, n_fft, hop, scale, fmin, fmax, bins, center, fmt = case
+    _say(f"scaled stft {name}: B={B} L={L} n_fft={n_fft} hop={hop} scale={scale} bins={bins} fmt={fmt}")
+    x = _rand(B, L, 900 + bins)
+    plan = nb.nna_plan_stft_scaled(sr=sr, n_fft=n_fft, hop=hop, center=center, fmt=fmt, freq_scale=scale, fmin=fmin,
+                                   fmax=fmax, freq_bins=bins, device=0)
+    got = nb.nna_stft(plan, _dev(x)).cpu().numpy()
+    ref = oracle.stft_scaled(x, sr=sr, n_fft=n_fft, hop=hop, center=center, scale=scale, fmin=fmin, fmax=fmax,
+                             freq_bins=bins, fmt=fmt)
+    e = _rel_err(got, ref)
+    _say(f"  rel err {e:.3e}")
+    assert e < TOL
+
+
+def test_scaled_stft_worked_example_full(nb):
+    # the linear axis of Sec. II-B (50..6000 Hz, 1,025 bins, n_fft 2048 @ 44.1 kHz) on workload-4 waveforms
+    _say("scaled stft, worked example of Sec. II-B on 3 x 176400 samples")
+    x = signals.batch(4, [0, 885, 1769])
+    plan = nb.nna_plan_stft_scaled(sr=44100, n_fft=2048, hop=512, freq_scale=nb.NNA_FREQ_LINEAR, fmin=50.0,
+                                   fmax=6000.0, freq_bins=1025, device=0)
+    got = nb.nna_stft(plan, _dev(x)).cpu().numpy()
+    assert got.shape == (3, 1025, 345)
+    ref = oracle.stft_scaled(x, sr=44100, n_fft=2048, hop=512, scale=oracle.FREQ_LINEAR, fmin=50.0, fmax=6000.0,
+                             freq_bins=1025)
+    e = _rel_err(got, ref)
+    _say(f"  rel err {e:.3e}")
+    assert e < TOL
+
+
 def test_stft_rejects_bad_shapes(nb):
     import torch
     plan = nb.nna_plan_stft(n_fft=2048, hop=512, device=0)

@@ -118,6 +118,45 @@ def test_stft_bank_is_windowed_dft_kernels(n_fft, hop, win):
     assert info["executed_flops_per_frame"] >= info["algorithmic_flops_per_frame"]
 
 
+@pytest.mark.parametrize("scale,sr,n_fft,hop,fmin,fmax,bins", [
+    (nb.NNA_FREQ_LINEAR, 44100, 2048, 512, 50.0, 6000.0, 1025),   # the worked example of Sec. II-B
+    (nb.NNA_FREQ_LINEAR, 22050, 256, 64, 0.0, 11025.0, 128),
+    (nb.NNA_FREQ_LOG, 22050, 512, 100, 55.0, 7040.0, 84),
+    (nb.NNA_FREQ_LOG, 16000, 96, 25, 100.0, 8000.0, 7),
+])
+def test_scaled_stft_bank_is_eq_dft3(scale, sr, n_fft, hop, fmin, fmax, bins):
+    p = nb.nna_plan_stft_scaled(sr=sr, n_fft=n_fft, hop=hop, freq_scale=scale, fmin=fmin, fmax=fmax, freq_bins=bins,
+                                device=-1)
+    sig = nb.nna_plan_sigma(p)
+    want = np.array([oracle.freq_sigma(scale, k, fmin, fmax, bins, n_fft, sr) for k in range(bins)])
+    np.testing.assert_allclose(sig, want, rtol=1e-13, atol=1e-13)
+    bank = nb.nna_plan_bank(p)
+    assert bank.shape == (2 * bins, n_fft)
+    n = np.arange(n_fft)
+    w = oracle.window(nb.NNA_WIN_HANN, n_fft)
+    np.testing.assert_allclose(bank[0::2], w * np.cos(2 * np.pi * want[:, None] * n / n_fft), atol=2e-7)
+    np.testing.assert_allclose(bank[1::2], -w * np.sin(2 * np.pi * want[:, None] * n / n_fft), atol=2e-7)
+    info = p.info()
+    assert info["kind"] == nb.NNA_KIND_STFT and info["out_bins"] == bins
+    assert nb.nna_out_shape(p, 3, 5 * n_fft)[0] == bins
+    assert info["algorithmic_flops_per_frame"] == 4.0 * n_fft * bins
+    assert info["executed_flops_per_frame"] >= info["algorithmic_flops_per_frame"]
+
+
+def test_scaled_stft_argument_checking():
+    f = nb.nna_plan_stft_scaled
+    assert _status(f, freq_scale=0, device=-1) == nb.NNA_ERR_INVALID_ARG
+    assert _status(f, freq_scale=nb.NNA_FREQ_LOG, fmin=0.0, device=-1) == nb.NNA_ERR_INVALID_ARG
+    assert _status(f, fmin=500.0, fmax=400.0, device=-1) == nb.NNA_ERR_INVALID_ARG
+    assert _status(f, fmax=12000.0, device=-1) == nb.NNA_ERR_INVALID_ARG  # above sr/2
+    assert _status(f, freq_bins=-1, device=-1) == nb.NNA_ERR_INVALID_ARG
+    assert _status(f, freq_bins=20000, device=-1) == nb.NNA_ERR_INVALID_ARG
+    assert f(freq_bins=0, device=-1).info()["out_bins"] == 1025  # default: n_fft/2 + 1 bins
+    # sigma of a plain plan is the bin index; other kinds have none
+    np.testing.assert_array_equal(nb.nna_plan_sigma(nb.nna_plan_stft(n_fft=64, hop=16, device=-1)), np.arange(33.0))
+    assert _status(nb.nna_plan_sigma, nb.nna_plan_mel(device=-1)) == nb.NNA_ERR_INVALID_ARG
+
+
 @pytest.mark.parametrize("sr,n_fft,n_mels,fmin,fmax,scale,norm", [
     (22050, 2048, 128, 0.0, 0.0, nb.NNA_MEL_SLANEY, True),
     (44100, 2048, 128, 0.0, 22050.0, nb.NNA_MEL_SLANEY, True),
