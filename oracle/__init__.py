@@ -72,6 +72,11 @@ def lib():
         L.orc_cqt_default_taps.argtypes = [_I, _D, _I]
         L.orc_cqt_kernels.argtypes = [_I, _D, _I, _I, _I, _LL, _PD, _PD]
         L.orc_cqt.argtypes = [_PF, _LL, _LL, _I, _I, _D, _I, _I, _I, _I, _LL, _I, _PD]
+        L.orc_lowpass_fir.argtypes = [_I, _D, _PD]
+        L.orc_downsample2.argtypes = [_PD, _LL, _PD, _I, _PD]
+        L.orc_cqt2010_default_taps.restype = _LL
+        L.orc_cqt2010_default_taps.argtypes = [_I, _D, _I, _I]
+        L.orc_cqt2010v2.argtypes = [_PF, _LL, _LL, _I, _I, _D, _I, _I, _I, _LL, _I, _I, _PD]
         _lib = L
     return _lib
 
@@ -241,4 +246,35 @@ def cqt(x, sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, window=
     out = np.empty((B, n_bins, T), dtype=np.float64)
     _check(lib().orc_cqt(_pf(x), B, L, sr, hop, fmin, n_bins, bins_per_octave, window, int(center), n_taps, fmt,
                          _pd(out)), "cqt")
+    return out
+
+
+FIR_TAPS = 257
+
+
+def lowpass_fir(n_taps=FIR_TAPS, cutoff=0.5) -> np.ndarray:
+    h = np.empty(n_taps, dtype=np.float64)
+    _check(lib().orc_lowpass_fir(n_taps, float(cutoff), _pd(h)), "lowpass_fir")
+    return h
+
+
+def downsample2(x, h) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    h = np.ascontiguousarray(h, dtype=np.float64)
+    y = np.empty((x.size + 1) // 2, dtype=np.float64)
+    _check(lib().orc_downsample2(_pd(x), x.size, _pd(h), h.size, _pd(y)), "downsample2")
+    return y
+
+
+def cqt2010_default_taps(sr, fmin, n_bins, bins_per_octave) -> int:
+    return int(lib().orc_cqt2010_default_taps(sr, fmin, n_bins, bins_per_octave))
+
+
+def cqt2010v2(x, sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, window=WIN_HANN, n_taps=0,
+              fir_taps=FIR_TAPS, fmt=MAGNITUDE):
+    x = _x(x)
+    B, L = x.shape
+    out = np.empty((B, n_bins, 1 + L // hop), dtype=np.float64)
+    _check(lib().orc_cqt2010v2(_pf(x), B, L, sr, hop, fmin, n_bins, bins_per_octave, window, n_taps, fir_taps, fmt,
+                               _pd(out)), "cqt2010v2")
     return out

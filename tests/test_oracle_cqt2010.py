@@ -1,0 +1,115 @@
+"""Pins for the downsampling CQT of the CPU oracle (CPU only).
+
+The anti-alias filter and the downsampler are checked against SciPy's own window-method
+design and convolution; the octave recursion against the already pinned one-rate CQT applied,
+octave by octave, to signals downsampled with SciPy; tones against the closed form A/2.
+"""
+import numpy as np
+import pytest
+import scipy.signal
+
+import oracle
+from paper_1912_12055_amd import signals
+
+
+@pytest.mark.parametrize("n", [257, 63, 5])
+def test_fir_is_scipy_window_method_design(n):
+    h = oracle.lowpass_fir(n, 0.5)
+    assert np.allclose(h, scipy.signal.firwin(n, 0.5), atol=1e-15)
+    assert np.allclose(h, h[::-1], atol=1e-17)          # linear phase
+    assert abs(h.sum() - 1.0) < 1e-14                      # unit gain at 0 Hz
+    c = n // 2
+    assert np.all(np.abs(h[c + 2::2]) < 1e-16)             # half-band: every second tap off the centre is zero
+
+
+def test_fir_cuts_at_half_nyquist():
+    # pass band ends 0.4995, stop band starts 0.5005 of Nyquist (Sec. III-C): the response crosses
+    # one half between them; well inside the bands it is flat / more than 50 dB down
+    h = oracle.lowpass_fir(257, 0.5)
+    w, H = scipy.signal.freqz(h, worN=[0.25 * np.pi, 0.45 * np.pi, 0.5 * np.pi, 0.55 * np.pi, 0.75 * np.pi])
+    mag = np.abs(H)
+    assert abs(mag[0] - 1) < 3e-3 and abs(mag[1] - 1) < 3e-3
+    assert abs(mag[2] - 0.5) < 5e-3
+    assert mag[3] < 10 ** (-50 / 20) and mag[4] < 10 ** (-50 / 20)
+
+
+@pytest.mark.parametrize("L,n", [(1000, 63), (1001, 63), (777, 257)])
+def test_downsample2_is_reflect_padded_convolution_keeping_even_samples(L, n):
+    rng = np.random.default_rng(L)
+    x = rng.standard_normal(L)
+    h = oracle.lowpass_fir(n, 0.5)
+    y = oracle.downsample2(x, h)
+    full = scipy.signal.convolve(np.pad(x, n // 2, mode="reflect"), h, mode="valid")
+    assert full.size == L
+    assert y.size == (L + 1) // 2
+    assert np.allclose(y, full[::2], atol=1e-13)
+
+
+def test_downsample2_keeps_low_tones_and_removes_high_ones():
+    sr, L = 16000, 8000
+    h = oracle.lowpass_fir(257, 0.5)
+    n = np.arange(L)
+    low = 0.7 * np.cos(2 * np.pi * 1000.0 * n / sr + 0.3)       # 0.125 of Nyquist
+    y = oracle.downsample2(low, h)
+    assert np.allclose(y[200:-200], low[::2][200:-200], atol=0.7 * 3e-3)  # zero delay, unit gain
+    high = 0.7 * np.cos(2 * np.pi * 6500.0 * n / sr)            # would alias to 1500 Hz
+    y = oracle.downsample2(high, h)
+    assert np.abs(y[200:-200]).max() < 0.7 * 10 ** (-50 / 20)
+
+
+def test_single_octave_is_the_one_rate_cqt():
+    x = signals.batch(1, B=2, L=9000)
+    a = oracle.cqt2010v2(x, sr=16000, hop=128, fmin=1000.0, n_bins=12, bins_per_octave=12)
+    b = oracle.cqt(x, sr=16000, hop=128, fmin=1000.0, n_bins=12, bins_per_octave=12,
+                   n_taps=oracle.cqt2010_default_taps(16000, 1000.0, 12, 12))
+    assert a.shape == b.shape
+    assert np.allclose(a, b, atol=1e-14)
+    assert oracle.cqt2010_default_taps(16000, 1000.0, 12, 12) == oracle.cqt_default_taps(16000, 1000.0, 12)
+
+
+@pytest.mark.parametrize("n_bins,bpo", [(36, 12), (29, 12), (10, 4)])
+def test_each_octave_is_the_one_rate_cqt_of_the_downsampled_signal(n_bins, bpo):
+    # octave a = top-octave kernels on the waveform downsampled a times (by SciPy here), hop / 2^a;
+    # its bins land below those of octave a-1; a partial lowest octave keeps its upper bins
+    sr, hop, fmin, L = 16000, 64, 220.0, 6000
+    x = signals.batch(3, B=2, L=L).astype(np.float32)
+    n_taps = oracle.cqt2010_default_taps(sr, fmin, n_bins, bpo)
+    got = oracle.cqt2010v2(x, sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, n_taps=n_taps, fir_taps=63)
+    T = 1 + L // hop
+    assert got.shape == (2, n_bins, T)
+    h = scipy.signal.firwin(63, 0.5)
+    n_oct = -(-n_bins // bpo)
+    for b in range(2):
+        xa = x[b].astype(np.float64)
+        for a in range(n_oct):
+            hi = n_bins - a * bpo
+            lo = max(0, hi - bpo)
+            # same bins seen from the downsampled rate: frequencies unchanged, sample rate sr / 2^a
+            ref = oracle.cqt(xa.astype(np.float32), sr=sr >> a, hop=hop >> a, fmin=fmin * 2.0 ** (lo / bpo),
+                             n_bins=hi - lo, bins_per_octave=bpo, n_taps=n_taps)
+            # (float32 rounding of the downsampled signal: 6e-8 relative)
+            assert np.allclose(got[b, lo:hi, :], ref[:, :, :T][0], atol=2e-6 * np.abs(ref).max()), (a, lo, hi)
+            xa = scipy.signal.convolve(np.pad(xa, 31, mode="reflect"), h, mode="valid")[::2]
+
+
+def test_tone_reads_half_its_amplitude_in_every_octave():
+    sr, A = 22050, 0.8
+    _, fk = oracle.cqt_lengths(sr, 32.70, 84, 12)
+    for k in (3, 17, 30, 50, 62, 71, 75, 83):
+        x = signals.tone(22050, sr, fk[k], amp=A)[None]
+        out = oracle.cqt2010v2(x, sr=sr, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12)
+        mid = out[0, :, 15:30]
+        assert np.all(mid.argmax(axis=0) == k), k
+        # A/2 up to the filter's pass-band ripple (one pass per octave below the top) and the
+        # rounding of the short kernels' lengths, which detunes them slightly
+        assert np.allclose(mid[k], A / 2, rtol=1e-2), (k, mid[k].mean())
+
+
+def test_rejects_hops_that_do_not_halve_and_short_signals():
+    x = signals.batch(1, B=1, L=9000)
+    with pytest.raises(oracle.OracleError):
+        oracle.cqt2010v2(x, sr=22050, hop=100, n_bins=84)   # 7 octaves need hop % 64 == 0
+    with pytest.raises(oracle.OracleError):
+        oracle.cqt2010v2(x[:, :2000], sr=22050, hop=512, n_bins=84)  # deepest octave shorter than half a kernel
+    with pytest.raises(oracle.OracleError):
+        oracle.cqt2010v2(x, sr=22050, hop=512, n_bins=84, fir_taps=256)  # even tap count has no integer delay
