@@ -74,7 +74,7 @@ typedef enum {
   NNA_FREQ_LOG = 2     /* eq. (log-frequency-DFT): bins in geometric progression from fmin */
 } nna_freq_scale;
 
-typedef enum { NNA_KIND_STFT = 0, NNA_KIND_MEL = 1, NNA_KIND_CQT = 2 } nna_kind;
+typedef enum { NNA_KIND_STFT = 0, NNA_KIND_MEL = 1, NNA_KIND_CQT = 2, NNA_KIND_CQT2010V2 = 3 } nna_kind;
 
 /*
  * STFT plan (Sec. III-A; defaults of the paper's STFT layer: n_fft 2048, hop 512,
@@ -126,6 +126,26 @@ nna_status nna_plan_mel(nna_plan** plan, int sr, int n_fft, int hop, nna_window 
 nna_status nna_plan_cqt(nna_plan** plan, int sr, int hop, double fmin, int n_bins, int bins_per_octave,
                         nna_window win, int center, int n_taps, nna_output fmt, int device);
 
+/*
+ * Constant-Q plan by recursive downsampling with time-domain kernels (Sec. III-C:
+ * "Downsampling", "Constant-Q transform (2010 version)", "CQT with time domain kernels").
+ * The bins are split into octaves from the top; octave a (0 = top) holds bins
+ * [max(0, n_bins - (a+1) b), n_bins - a b).  Octave a is computed from the waveform
+ * downsampled a times by two, with hop / 2^a and the kernels of nna_plan_cqt for the octave's
+ * frequencies times 2^a (one kernel set when n_bins is a multiple of b), so every octave has
+ * the frames of the top one: T = 1 + L / hop, always centred with mirror reflection.
+ * Each downsampling step is y[m] = sum_i h[i] x~[2 m + i - (fir_taps-1)/2], x~ = x mirrored at
+ * both ends, a length-L waveform giving ceil(L/2) samples; h is the window-method low-pass
+ * named in "Downsampling" with its cutoff at half the Nyquist frequency (between the stated
+ * pass-band end 0.4995 and stop-band start 0.5005), Hamming window, unit gain at 0 Hz.
+ *   hop        a multiple of 2^(octaves-1)
+ *   n_taps     0 = next power of two >= the longest top-octave kernel; else even and >= it
+ *   fir_taps   0 = 257; else odd, 3..4095 (the paper gives no tap count)
+ * Output bins = n_bins, lowest frequency first.
+ */
+nna_status nna_plan_cqt2010v2(nna_plan** plan, int sr, int hop, double fmin, int n_bins, int bins_per_octave,
+                              nna_window win, int n_taps, int fir_taps, nna_output fmt, int device);
+
 /* Output shape [B, *n_bins, *n_frames] for a batch of B waveforms of L samples.
  * NNA_ERR_SHAPE if L is too short (center: L <= pad; otherwise L < K) or B < 1. */
 nna_status nna_out_shape(const nna_plan* plan, long long B, long long L, long long* n_bins,
@@ -144,6 +164,24 @@ nna_status nna_mel(const nna_plan* plan, const float* x_dev, long long B, long l
 /* out_dev[B, n_bins, T] = constant-Q spectrogram of x_dev[B, L]; plan from nna_plan_cqt. */
 nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
                    void* hip_stream);
+
+/* Bytes of device workspace nna_cqt2010v2 needs for a batch [B, L]: the downsampled waveforms
+ * of two consecutive octaves (about 3/4 of the input's size; 0 for a single octave). */
+nna_status nna_cqt2010v2_workspace(const nna_plan* plan, long long B, long long L, size_t* bytes);
+
+/* out_dev[B, n_bins, T] = constant-Q spectrogram of x_dev[B, L]; plan from nna_plan_cqt2010v2.
+ * workspace_dev: caller-owned device memory, 16-byte aligned, of at least the size above; its
+ * contents are overwritten and mean nothing afterwards.  Launches 2*octaves - 1 kernels on
+ * hip_stream; nothing is allocated.  NNA_ERR_SHAPE if some octave's waveform is not longer
+ * than the kernels' half length n_taps/2 or shorter than the filter's frame. */
+nna_status nna_cqt2010v2(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
+                         void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* Downsampling CQT plans only: *part = the plan of octave `index` (0 = top; a plan as from
+ * nna_plan_cqt, for nna_plan_bank / nna_plan_info / nna_plan_cqt_lengths), or with index -1 the
+ * filter as the kernel runs it: a bank of 16 rows, row r = the taps h shifted right by 2 r
+ * (16 consecutive output samples per kernel frame).  The parts belong to `plan`. */
+nna_status nna_plan_part(const nna_plan* plan, int index, const nna_plan** part);
 
 /*
  * Inspection: the kernel bank exactly as the GPU holds it (float32 values widened to

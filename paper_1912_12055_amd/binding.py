@@ -20,12 +20,13 @@ NNA_OUT_MAGNITUDE, NNA_OUT_POWER, NNA_OUT_LOG = 0, 1, 2
 NNA_WIN_HANN, NNA_WIN_RECT = 0, 1
 NNA_MEL_SLANEY, NNA_MEL_HTK = 0, 1
 NNA_FREQ_LINEAR, NNA_FREQ_LOG = 1, 2
-NNA_KIND_STFT, NNA_KIND_MEL, NNA_KIND_CQT = 0, 1, 2
+NNA_KIND_STFT, NNA_KIND_MEL, NNA_KIND_CQT, NNA_KIND_CQT2010V2 = 0, 1, 2, 3
 
 # every symbol include/nna.h declares
 EXPORTS = [
-    "nna_plan_stft", "nna_plan_stft_scaled", "nna_plan_mel", "nna_plan_cqt", "nna_out_shape", "nna_stft", "nna_mel", "nna_cqt",
-    "nna_plan_bank", "nna_plan_mel_weights", "nna_plan_info", "nna_plan_cqt_lengths", "nna_plan_sigma",
+    "nna_plan_stft", "nna_plan_stft_scaled", "nna_plan_mel", "nna_plan_cqt", "nna_plan_cqt2010v2", "nna_out_shape", "nna_stft", "nna_mel", "nna_cqt",
+    "nna_plan_bank", "nna_plan_mel_weights", "nna_plan_info", "nna_plan_cqt_lengths", "nna_plan_sigma", "nna_cqt2010v2_workspace",
+    "nna_cqt2010v2", "nna_plan_part",
     "nna_plan_destroy",
     "nna_status_str", "nna_last_error",
 ]
@@ -60,6 +61,11 @@ def lib():
                                    _c.c_double, _c.c_int, _c.c_int, _c.c_double, _c.c_int]
         L.nna_plan_cqt.argtypes = [PP, _c.c_int, _c.c_int, _c.c_double, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
                                    _c.c_int, _c.c_int, _c.c_int]
+        L.nna_plan_cqt2010v2.argtypes = [PP, _c.c_int, _c.c_int, _c.c_double, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
+                                         _c.c_int, _c.c_int, _c.c_int]
+        L.nna_cqt2010v2_workspace.argtypes = [_VP, _LL, _LL, _c.POINTER(_c.c_size_t)]
+        L.nna_cqt2010v2.argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _c.c_size_t, _VP]
+        L.nna_plan_part.argtypes = [_VP, _c.c_int, PP]
         L.nna_out_shape.argtypes = [_VP, _LL, _LL, _c.POINTER(_LL), _c.POINTER(_LL)]
         for name in ("nna_stft", "nna_mel", "nna_cqt"):
             getattr(L, name).argtypes = [_VP, _VP, _LL, _LL, _VP, _VP]
@@ -97,13 +103,14 @@ def _check(status: int):
 class Plan:
     """Owns one nna_plan*; destroyed with the object."""
 
-    def __init__(self, handle: int, device: int):
+    def __init__(self, handle: int, device: int, owner=None):
         self.handle = handle
         self.device = device
+        self.owner = owner  # a part of another plan: that plan owns the handle (and is kept alive here)
 
     def __del__(self):
         h, self.handle = getattr(self, "handle", None), None
-        if h and _lib is not None:
+        if h and _lib is not None and getattr(self, "owner", None) is None:
             _lib.nna_plan_destroy(h)
 
     def info(self) -> dict:
@@ -143,6 +150,25 @@ def nna_plan_cqt(sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, w
                  n_taps=0, fmt=NNA_OUT_MAGNITUDE, device=0) -> Plan:
     return _new_plan(lib().nna_plan_cqt,
                      (sr, hop, float(fmin), n_bins, bins_per_octave, win, int(center), n_taps, fmt), device)
+
+
+def nna_plan_cqt2010v2(sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, win=NNA_WIN_HANN, n_taps=0,
+                       fir_taps=0, fmt=NNA_OUT_MAGNITUDE, device=0) -> Plan:
+    return _new_plan(lib().nna_plan_cqt2010v2,
+                     (sr, hop, float(fmin), n_bins, bins_per_octave, win, n_taps, fir_taps, fmt), device)
+
+
+def nna_plan_part(plan: Plan, index: int) -> Plan:
+    """Octave `index` (0 = top) of a downsampling CQT plan, or its filter bank for index -1."""
+    h = _VP()
+    _check(lib().nna_plan_part(plan.handle, index, _c.byref(h)))
+    return Plan(h.value, plan.device, owner=plan)
+
+
+def nna_cqt2010v2_workspace(plan: Plan, B: int, L: int) -> int:
+    n = _c.c_size_t()
+    _check(lib().nna_cqt2010v2_workspace(plan.handle, B, L, _c.byref(n)))
+    return n.value
 
 
 def nna_out_shape(plan: Plan, B: int, L: int):
@@ -199,6 +225,26 @@ def _run(fn, plan: Plan, x, out, stream):
         stream = torch.cuda.current_stream(x.device).cuda_stream
     _check(fn(plan.handle, x.data_ptr(), B, L, out.data_ptr(), stream))
     return out
+
+
+def nna_cqt2010v2(plan: Plan, x, out=None, workspace=None, stream=None):
+    """out[B, n_bins, T] = constant-Q spectrogram of x[B, L] by recursive downsampling.  `workspace`: a CUDA
+    tensor of at least nna_cqt2010v2_workspace(plan, B, L) bytes (one is made here if None)."""
+    import torch
+
+    if not (isinstance(x, torch.Tensor) and x.is_cuda and x.dim() == 2):
+        raise TypeError("x must be a contiguous float32 CUDA tensor [B, L]")
+    need = nna_cqt2010v2_workspace(plan, x.shape[0], x.shape[1])
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    elif not (workspace.is_cuda and workspace.is_contiguous() and workspace.device == x.device):
+        raise TypeError("workspace must be a contiguous CUDA tensor on x's device")
+    ws_bytes = workspace.numel() * workspace.element_size()
+
+    def fn(handle, xp, B, L, op, st):
+        return lib().nna_cqt2010v2(handle, xp, B, L, op, workspace.data_ptr(), ws_bytes, st)
+
+    return _run(fn, plan, x, out, stream)
 
 
 def nna_stft(plan: Plan, x, out=None, stream=None):

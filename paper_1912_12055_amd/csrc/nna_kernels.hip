@@ -622,7 +622,7 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
     const long long b = valid[fb] ? f / g.T : 0;
     const int t = valid[fb] ? (int)(f - b * g.T) : 0;
     a_off[fb] = (valid[fb] ? tm.frame_row(fi) : 0) * CQ_PITCH + 4 * q;
-    o_off[fb] = (b * P.n_bins) * g.T + t;
+    o_off[fb] = b * P.out_wave_stride + (long long)P.bin_offset * g.T + t;
   }
 
   const int n_chunks = item.n_chunks;  // >= 1; every listed chunk starts with >= CQ_PREFETCH fragments
@@ -776,6 +776,26 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
 #pragma unroll
   for (int i = 0; i < CQ_PREFETCH; ++i) wait_vm<0>(bq[i]);
 
+  if (P.raw) {
+    // real-valued bank of one row block (a decimating FIR filter written as 16 shifted copies):
+    // register i of lane (q, n) is output sample 16 t + 4 q + i of the frame's waveform
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb) {
+      if (!valid[fb]) continue;
+      const long long fr = f0 + wave * 64 + fb * 16 + n;
+      const long long b = fr / g.T;
+      const long long pos = 16 * (fr - b * g.T) + 4 * q;
+      float* __restrict__ op = P.out + b * P.out_wave_stride + pos;
+      if (P.raw_vec && pos + 3 < P.raw_len) {
+        *reinterpret_cast<f32x4*>(op) = acc[0][fb];
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (pos + i < P.raw_len) op[i] = acc[0][fb][i];
+      }
+    }
+    return;
+  }
   const int f = P.fmt;
 #pragma unroll
   for (int r = 0; r < CQ_ITEM_RB; ++r) {

@@ -51,8 +51,17 @@ struct nna_plan {
 
   // CQT
   int n_bins = 0, bpo = 0, n_rb = 0;
+  int k_first = 0;  // bin k sits at fmin 2^((k_first + k) / bpo): non-zero for the octaves of a downsampling plan
   double cq_fmin = 0, Q = 0;
   std::vector<long long> Nk, sk;
+  // any bank the CQT kernel runs: row r has its non-zero taps inside [row_s[r], row_e[r])
+  int conv_rows = 0;
+  std::vector<long long> row_s, row_e;
+  // CQT by recursive downsampling: one CQT sub-plan per octave (0 = top) and the decimating filter
+  std::vector<nna_plan*> octave;
+  nna_plan* fir = nullptr;
+  int fir_taps = 0;
+  std::vector<double> h_fir;
   std::vector<nna::CqtItem> h_items;
   std::vector<nna::CqtChunk> h_chunks;   // [item][n_chunks]
   std::vector<int> h_nj_real;            // [item][n_chunks][CQ_ITEM_RB] fragments before ring padding
@@ -383,17 +392,20 @@ void for_each_cqt_fragment(const nna_plan* p, Fn fn) {
   }
 }
 
-void build_cqt_bank(nna_plan* p) {
+// Lays out, for the CQT kernel, a bank of p->conv_rows rows x p->K taps whose row r is zero
+// outside [row_s[r], row_e[r]); value(row, tap) gives the logical entries.
+template <typename ValueFn>
+void build_conv_bank(nna_plan* p, ValueFn value) {
   const long long K = p->K;
-  p->n_rb = (2 * p->n_bins + CQ_ROWS - 1) / CQ_ROWS;
+  p->n_rb = (p->conv_rows + CQ_ROWS - 1) / CQ_ROWS;
   const long long J = (K % p->hop == 0) ? K / p->hop : 0;
   // tap support [s, e) of every row block
   std::vector<long long> s_rb(p->n_rb), e_rb(p->n_rb);
   for (int rb = 0; rb < p->n_rb; ++rb) {
     long long s = K, e = 0;
-    for (int k = rb * (CQ_ROWS / 2); k < std::min(p->n_bins, (rb + 1) * (CQ_ROWS / 2)); ++k) {
-      s = std::min(s, p->sk[k]);
-      e = std::max(e, p->sk[k] + p->Nk[k]);
+    for (int r = rb * CQ_ROWS; r < std::min(p->conv_rows, (rb + 1) * CQ_ROWS); ++r) {
+      s = std::min(s, p->row_s[r]);
+      e = std::max(e, p->row_e[r]);
     }
     s_rb[rb] = s;
     e_rb[rb] = e;
@@ -490,19 +502,31 @@ void build_cqt_bank(nna_plan* p) {
   p->bank_groups = frag;
   p->bank_floats = (size_t)(frag + CQ_PREFETCH) * 64 * 4;
   p->h_bank.assign(p->bank_floats, 0.0f);
-  CqtKernelGen gen(p);
   for_each_cqt_fragment(p, [&](long long f, int rb, int j, int c0, bool real) {
     if (!real) return;
     for (int lane = 0; lane < 64; ++lane) {
       const int q = lane >> 4, r = lane & 15;
+      const int row = rb * CQ_ROWS + r;
       const long long tap0 = (long long)j * (p->sliding ? p->hop : 0) + c0 + 4 * q;
       float* dst = &p->h_bank[((size_t)f * 64 + lane) * 4];
-      for (int e = 0; e < 4; ++e) dst[e] = (float)gen.value(rb * CQ_ROWS + r, tap0 + e);
+      for (int e = 0; e < 4; ++e) dst[e] = row < p->conv_rows && tap0 + e < K ? (float)value(row, tap0 + e) : 0.0f;
     }
   });
-  double sumN = 0;
-  for (int k = 0; k < p->n_bins; ++k) sumN += (double)p->Nk[k];
   p->exec_flops = 2.0 * (double)frag * CQ_KC * CQ_ROWS;
+}
+
+void build_cqt_bank(nna_plan* p) {
+  p->conv_rows = 2 * p->n_bins;
+  p->row_s.resize(p->conv_rows);
+  p->row_e.resize(p->conv_rows);
+  double sumN = 0;
+  for (int k = 0; k < p->n_bins; ++k) {
+    p->row_s[2 * k] = p->row_s[2 * k + 1] = p->sk[k];
+    p->row_e[2 * k] = p->row_e[2 * k + 1] = p->sk[k] + p->Nk[k];
+    sumN += (double)p->Nk[k];
+  }
+  CqtKernelGen gen(p);
+  build_conv_bank(p, [&](int row, long long tap) { return gen.value(row, tap); });
   p->alg_flops = 4.0 * sumN;
 }
 
@@ -646,6 +670,179 @@ nna_status run_stft_like(const nna_plan* plan, int kind, const float* x, long lo
   return NNA_OK;
 }
 
+nna_status check_cqt_args(double fmin, int n_bins, int bins_per_octave, int n_taps, int fmt, int sr) {
+  if (!(fmin > 0.0)) return fail(NNA_ERR_INVALID_ARG, "fmin must be > 0");
+  if (n_bins < 1 || n_bins > 4096) return fail(NNA_ERR_INVALID_ARG, "n_bins must be in [1, 4096]");
+  if (bins_per_octave < 1 || bins_per_octave > 1024) return fail(NNA_ERR_INVALID_ARG, "bins_per_octave must be in [1, 1024]");
+  if (fmt != NNA_OUT_MAGNITUDE && fmt != NNA_OUT_POWER && fmt != NNA_OUT_LOG)
+    return fail(NNA_ERR_INVALID_ARG, "unknown output format");
+  if (n_taps < 0) return fail(NNA_ERR_INVALID_ARG, "n_taps must be >= 0");
+  const double top = fmin * std::pow(2.0, (double)(n_bins - 1) / bins_per_octave);
+  if (!(top < 0.5 * sr)) return fail(NNA_ERR_INVALID_ARG, "the top CQT bin must lie below sr/2");
+  return NNA_OK;
+}
+
+// CQT plan whose bin k sits at fmin 2^((k_first + k) / bins_per_octave); arguments already checked
+nna_status make_cqt_plan(nna_plan** plan, int sr, int hop, double fmin, int k_first, int n_bins, int bins_per_octave,
+                         int win, int center, int n_taps, int fmt, int device) {
+  nna_plan* p = new (std::nothrow) nna_plan;
+  if (!p) return fail(NNA_ERR_ALLOC, "out of host memory");
+  try {
+    p->kind = NNA_KIND_CQT;
+    p->device = device;
+    p->sr = sr;
+    p->hop = hop;
+    p->center = center;
+    p->window = win;
+    p->fmt = fmt;
+    p->n_bins = n_bins;
+    p->bpo = bins_per_octave;
+    p->k_first = k_first;
+    p->cq_fmin = fmin;
+    p->Q = 1.0 / (std::exp2(1.0 / bins_per_octave) - 1.0);  // eq. (Q)
+    p->Nk.resize(n_bins);
+    p->sk.resize(n_bins);
+    for (int k = 0; k < n_bins; ++k) {
+      const double fk = fmin * std::exp2((double)(k_first + k) / bins_per_octave);
+      p->Nk[k] = (long long)std::ceil(p->Q * (double)sr / fk);  // eq. (N_k), in double
+    }
+    if (p->Nk[0] > (1LL << 24)) {
+      delete p;
+      return fail(NNA_ERR_UNSUPPORTED, "CQT kernels longer than 2^24 taps are not supported");
+    }
+    long long taps = n_taps;
+    if (taps == 0) {
+      taps = 1;
+      while (taps < p->Nk[0]) taps <<= 1;
+      if (taps < 2) taps = 2;
+    }
+    if (taps & 1) {
+      delete p;
+      return fail(NNA_ERR_INVALID_ARG, "n_taps must be even");
+    }
+    if (taps < p->Nk[0]) {
+      char msg[160];
+      std::snprintf(msg, sizeof msg, "n_taps = %lld is shorter than the longest kernel (%lld taps)", taps, p->Nk[0]);
+      delete p;
+      return fail(NNA_ERR_INVALID_ARG, msg);
+    }
+    p->K = (int)taps;
+    p->pad = center ? (int)(taps / 2) : 0;
+    for (int k = 0; k < n_bins; ++k) p->sk[k] = (taps - p->Nk[k]) / 2;
+    build_cqt_bank(p);
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return fail(NNA_ERR_ALLOC, "out of host memory while building the CQT bank");
+  }
+  return finish_plan(p, plan, nullptr);
+}
+
+// Window-method low-pass at half the Nyquist frequency (Sec. III-C, "Downsampling"): the ideal
+// response's samples under a Hamming window, scaled to unit gain at 0 Hz.
+std::vector<double> half_band_taps(int n) {
+  std::vector<double> h(n);
+  double sum = 0;
+  for (int i = 0; i < n; ++i) {
+    const double u = i - 0.5 * (n - 1);
+    const double ideal = u == 0.0 ? 0.5 : std::sin(0.5 * kPi * u) / (kPi * u);  // 0.5 sinc(u / 2)
+    h[i] = ideal * (0.54 - 0.46 * std::cos(2.0 * kPi * i / (n - 1)));
+    sum += h[i];
+  }
+  for (double& v : h) v /= sum;
+  return h;
+}
+
+// The filter + keep-every-second-sample step as a bank for the CQT kernel: a "frame" is 16
+// consecutive output samples y[16 t + r], r = 0..15; it reads input samples 32 t - half + [0, K)
+// and row r holds the filter shifted by 2 r taps (y[m] is centred on x[2 m]).
+constexpr int FIR_HOP = 2 * CQ_ROWS;
+nna_status make_fir_plan(nna_plan** plan, int fir_taps, int device) {
+  nna_plan* p = new (std::nothrow) nna_plan;
+  if (!p) return fail(NNA_ERR_ALLOC, "out of host memory");
+  try {
+    p->kind = NNA_KIND_CQT;
+    p->device = device;
+    p->sr = 1;
+    p->hop = FIR_HOP;
+    p->center = 1;
+    p->window = NNA_WIN_RECT;
+    p->fmt = NNA_OUT_MAGNITUDE;
+    p->fir_taps = fir_taps;
+    p->K = (fir_taps + 2 * (CQ_ROWS - 1) + FIR_HOP - 1) / FIR_HOP * FIR_HOP;
+    p->pad = (fir_taps - 1) / 2;
+    p->h_fir = half_band_taps(fir_taps);
+    p->conv_rows = CQ_ROWS;
+    p->row_s.resize(CQ_ROWS);
+    p->row_e.resize(CQ_ROWS);
+    for (int r = 0; r < CQ_ROWS; ++r) {
+      p->row_s[r] = 2 * r;
+      p->row_e[r] = 2 * r + fir_taps;
+    }
+    build_conv_bank(p, [&](int row, long long tap) {
+      const long long i = tap - 2 * row;
+      return i >= 0 && i < fir_taps ? p->h_fir[i] : 0.0;
+    });
+    p->alg_flops = 2.0 * fir_taps * CQ_ROWS;  // per 16 output samples
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return fail(NNA_ERR_ALLOC, "out of host memory while building the filter bank");
+  }
+  return finish_plan(p, plan, nullptr);
+}
+
+// one launch of the CQT kernel: `sub`'s bank over T frames of each of the B waveforms in x
+nna_status run_conv(const nna_plan* sub, const float* x, long long B, long long L, long long T, float* out,
+                    long long out_wave_stride, int bin_offset, long long raw_len, void* hip_stream) {
+  const int extra = sub->max_jspan - 1;
+  const int M = pick_tile_frames(CQ_FRAMES, T, extra, CQ_LDS_ROWS_MAX);
+  if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
+  nna::CqtParams P;
+  std::memset(&P, 0, sizeof(P));
+  P.g = make_geom(sub, x, B, L, T);
+  P.bank = reinterpret_cast<const float4*>(sub->d_bank);
+  P.items = sub->d_items;
+  P.chunks = sub->d_chunks;
+  P.out = out;
+  P.out_wave_stride = out_wave_stride;
+  P.bin_offset = bin_offset;
+  P.raw = raw_len > 0 ? 1 : 0;
+  P.raw_len = raw_len;
+  P.raw_vec = (raw_len % 4 == 0) && ((reinterpret_cast<uintptr_t>(out) & 15) == 0) ? 1 : 0;
+  P.n_items = (int)sub->h_items.size();
+  P.n_chunks = sub->n_chunks;
+  P.n_bins = sub->n_bins;
+  P.fmt = sub->fmt;
+  P.tile_frames = M;
+  const long long nseg = 1 + (M - 1 + T - 1) / T;
+  P.lds_rows = (int)((M + nseg * extra + 63) / 64 * 64);  // whole loader passes of 64 rows (<= CQ_LDS_ROWS_MAX)
+  P.n_ft = (P.g.n_frames + M - 1) / M;
+  hipError_t e = nna::launch_cqt(P, reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  return NNA_OK;
+}
+
+// octaves of a downsampling plan and the bins [lo, hi) of octave a (0 = top)
+inline int octaves_of(int n_bins, int bpo) { return (n_bins + bpo - 1) / bpo; }
+inline void octave_bins(int n_bins, int bpo, int a, int& lo, int& hi) {
+  hi = n_bins - a * bpo;
+  lo = std::max(0, hi - bpo);
+}
+inline size_t ws_round(long long floats) { return ((size_t)floats * sizeof(float) + 255) / 256 * 256; }
+
+// lengths of the waveform at every octave; false if some octave is too short for its padding
+bool cqt2010_lengths(const nna_plan* plan, long long L, std::vector<long long>& La) {
+  const int n_oct = (int)plan->octave.size();
+  La.assign(n_oct, 0);
+  long long l = L;
+  for (int a = 0; a < n_oct; ++a) {
+    La[a] = l;
+    if (l <= plan->pad) return false;                      // mirror reflection of the CQT kernels
+    if (a + 1 < n_oct && l < plan->fir->K) return false;   // and of the filter's frames
+    l = (l + 1) / 2;
+  }
+  return true;
+}
+
 }  // namespace
 
 // =======================================================================================
@@ -762,68 +959,155 @@ nna_status nna_plan_cqt(nna_plan** plan, int sr, int hop, double fmin, int n_bin
                         nna_window win, int center, int n_taps, nna_output fmt, int device) {
   nna_status s = check_common(plan, sr, hop, win, center, device);
   if (s != NNA_OK) return s;
-  if (!(fmin > 0.0)) return fail(NNA_ERR_INVALID_ARG, "fmin must be > 0");
-  if (n_bins < 1 || n_bins > 4096) return fail(NNA_ERR_INVALID_ARG, "n_bins must be in [1, 4096]");
-  if (bins_per_octave < 1 || bins_per_octave > 1024) return fail(NNA_ERR_INVALID_ARG, "bins_per_octave must be in [1, 1024]");
-  if (fmt != NNA_OUT_MAGNITUDE && fmt != NNA_OUT_POWER && fmt != NNA_OUT_LOG)
-    return fail(NNA_ERR_INVALID_ARG, "unknown output format");
-  if (n_taps < 0) return fail(NNA_ERR_INVALID_ARG, "n_taps must be >= 0");
-  const double top = fmin * std::pow(2.0, (double)(n_bins - 1) / bins_per_octave);
-  if (!(top < 0.5 * sr)) return fail(NNA_ERR_INVALID_ARG, "the top CQT bin must lie below sr/2");
+  if ((s = check_cqt_args(fmin, n_bins, bins_per_octave, n_taps, fmt, sr)) != NNA_OK) return s;
+  return make_cqt_plan(plan, sr, hop, fmin, 0, n_bins, bins_per_octave, win, center, n_taps, fmt, device);
+}
+
+nna_status nna_plan_cqt2010v2(nna_plan** plan, int sr, int hop, double fmin, int n_bins, int bins_per_octave,
+                              nna_window win, int n_taps, int fir_taps, nna_output fmt, int device) {
+  nna_status s = check_common(plan, sr, hop, win, 1, device);
+  if (s != NNA_OK) return s;
+  if ((s = check_cqt_args(fmin, n_bins, bins_per_octave, n_taps, fmt, sr)) != NNA_OK) return s;
+  if (fir_taps == 0) fir_taps = 257;
+  if (fir_taps < 3 || fir_taps > 4095 || !(fir_taps & 1))
+    return fail(NNA_ERR_INVALID_ARG, "fir_taps must be odd and in [3, 4095]");
+  const int n_oct = octaves_of(n_bins, bins_per_octave);
+  if (n_oct > 16) return fail(NNA_ERR_UNSUPPORTED, "more than 16 octaves are not supported");
+  if (hop % (1 << (n_oct - 1)) != 0)
+    return fail(NNA_ERR_INVALID_ARG, "hop must be a multiple of 2^(octaves - 1): every octave halves it");
+  int lo, hi;
+  octave_bins(n_bins, bins_per_octave, 0, lo, hi);
+  if (n_taps == 0) {
+    // next power of two >= the longest kernel of the top octave
+    const double Q = 1.0 / (std::exp2(1.0 / bins_per_octave) - 1.0);
+    const long long n0 = (long long)std::ceil(Q * (double)sr / (fmin * std::exp2((double)lo / bins_per_octave)));
+    long long t = 2;
+    while (t < n0) t <<= 1;
+    if (t > (1LL << 24)) return fail(NNA_ERR_UNSUPPORTED, "CQT kernels longer than 2^24 taps are not supported");
+    n_taps = (int)t;
+  }
   nna_plan* p = new (std::nothrow) nna_plan;
   if (!p) return fail(NNA_ERR_ALLOC, "out of host memory");
-  try {
-    p->kind = NNA_KIND_CQT;
-    p->device = device;
-    p->sr = sr;
-    p->hop = hop;
-    p->center = center;
-    p->window = win;
-    p->fmt = fmt;
-    p->n_bins = n_bins;
-    p->bpo = bins_per_octave;
-    p->cq_fmin = fmin;
-    p->Q = 1.0 / (std::exp2(1.0 / bins_per_octave) - 1.0);  // eq. (Q)
-    p->Nk.resize(n_bins);
-    p->sk.resize(n_bins);
-    for (int k = 0; k < n_bins; ++k) {
-      const double fk = fmin * std::exp2((double)k / bins_per_octave);
-      p->Nk[k] = (long long)std::ceil(p->Q * (double)sr / fk);  // eq. (N_k), in double
-    }
-    if (p->Nk[0] > (1LL << 24)) {
-      delete p;
-      return fail(NNA_ERR_UNSUPPORTED, "CQT kernels longer than 2^24 taps are not supported");
-    }
-    long long taps = n_taps;
-    if (taps == 0) {
-      taps = 1;
-      while (taps < p->Nk[0]) taps <<= 1;
-      if (taps < 2) taps = 2;
-    }
-    if (taps & 1) {
-      delete p;
-      return fail(NNA_ERR_INVALID_ARG, "n_taps must be even");
-    }
-    if (taps < p->Nk[0]) {
-      char msg[160];
-      std::snprintf(msg, sizeof msg, "n_taps = %lld is shorter than the longest kernel (%lld taps)", taps, p->Nk[0]);
-      delete p;
-      return fail(NNA_ERR_INVALID_ARG, msg);
-    }
-    p->K = (int)taps;
-    p->pad = center ? (int)(taps / 2) : 0;
-    for (int k = 0; k < n_bins; ++k) p->sk[k] = (taps - p->Nk[k]) / 2;
-    build_cqt_bank(p);
-  } catch (const std::bad_alloc&) {
-    delete p;
-    return fail(NNA_ERR_ALLOC, "out of host memory while building the CQT bank");
+  p->kind = NNA_KIND_CQT2010V2;
+  p->device = device;
+  p->sr = sr;
+  p->hop = hop;
+  p->center = 1;
+  p->window = win;
+  p->fmt = fmt;
+  p->n_bins = n_bins;
+  p->bpo = bins_per_octave;
+  p->cq_fmin = fmin;
+  p->K = n_taps;
+  p->pad = n_taps / 2;
+  p->fir_taps = fir_taps;
+  // octave a: the bins [lo, hi) one factor 2^a up the frequency axis, hop / 2^a, same taps
+  for (int a = 0; a < n_oct && s == NNA_OK; ++a) {
+    octave_bins(n_bins, bins_per_octave, a, lo, hi);
+    nna_plan* sub = nullptr;
+    s = make_cqt_plan(&sub, sr, hop >> a, fmin, lo + a * bins_per_octave, hi - lo, bins_per_octave, win, 1, n_taps,
+                      fmt, device);
+    if (s == NNA_OK) p->octave.push_back(sub);
   }
-  return finish_plan(p, plan, nullptr);
+  if (s == NNA_OK && n_oct > 1) s = make_fir_plan(&p->fir, fir_taps, device);
+  if (s != NNA_OK) {
+    const std::string keep = g_err;
+    nna_plan_destroy(p);
+    g_err = keep;
+    return s;
+  }
+  // per frame of the output: every octave's kernels once, and hop / 2^(a+1) filter outputs for
+  // each downsampling step a -> a+1 (the filter plan counts flops per 16 outputs)
+  for (int a = 0; a < n_oct; ++a) {
+    p->exec_flops += p->octave[a]->exec_flops;
+    p->alg_flops += p->octave[a]->alg_flops;
+    if (a + 1 < n_oct) {
+      const double frames16 = (double)(hop >> (a + 1)) / CQ_ROWS;
+      p->exec_flops += frames16 * p->fir->exec_flops;
+      p->alg_flops += frames16 * p->fir->alg_flops;
+    }
+  }
+  *plan = p;
+  return NNA_OK;
+}
+
+
+nna_status nna_cqt2010v2_workspace(const nna_plan* plan, long long B, long long L, size_t* bytes) {
+  if (!plan || !bytes) return fail(NNA_ERR_INVALID_ARG, "plan / bytes is NULL");
+  if (plan->kind != NNA_KIND_CQT2010V2) return fail(NNA_ERR_INVALID_ARG, "plan was built for a different transform");
+  if (B < 1 || L < 1) return fail(NNA_ERR_SHAPE, "B and L must be >= 1");
+  const int n_oct = (int)plan->octave.size();
+  const long long L1 = (L + 1) / 2, L2 = (L1 + 1) / 2;
+  *bytes = (n_oct > 1 ? ws_round(B * L1) : 0) + (n_oct > 2 ? ws_round(B * L2) : 0);
+  return NNA_OK;
+}
+
+nna_status nna_cqt2010v2(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
+                         void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+  if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
+  if (plan->kind != NNA_KIND_CQT2010V2) return fail(NNA_ERR_INVALID_ARG, "plan was built for a different transform");
+  if (!x_dev || !out_dev) return fail(NNA_ERR_INVALID_ARG, "x_dev / out_dev is NULL");
+  if (plan->device < 0) return fail(NNA_ERR_UNSUPPORTED, "host-only plan (device = -1) cannot run transforms");
+  if (B < 1) return fail(NNA_ERR_SHAPE, "B must be >= 1");
+  std::vector<long long> La;
+  if (L < 1 || !cqt2010_lengths(plan, L, La))
+    return fail(NNA_ERR_SHAPE, "L is too short: every octave's waveform must exceed the reflection padding");
+  const long long T = 1 + L / plan->hop;
+  if (T > 0x7fffffffLL / 4 || L > 0x7fffffffLL - 4LL * plan->K - 64 || B > 0x7fffffffLL || B > (1LL << 40) / T)
+    return fail(NNA_ERR_SHAPE, "batch too large");
+  size_t need = 0;
+  nna_status s = nna_cqt2010v2_workspace(plan, B, L, &need);
+  if (s != NNA_OK) return s;
+  if (need > 0 && (!workspace_dev || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace_dev) & 15)))
+    return fail(NNA_ERR_INVALID_ARG, "workspace_dev is NULL, misaligned or smaller than nna_cqt2010v2_workspace asks for");
+  const int n_oct = (int)plan->octave.size();
+  float* buf[2] = {static_cast<float*>(workspace_dev), nullptr};
+  if (n_oct > 2) buf[1] = reinterpret_cast<float*>(static_cast<char*>(workspace_dev) + ws_round(B * ((L + 1) / 2)));
+  DeviceGuard guard;
+  hipError_t e = guard.enter(plan->device);
+  if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+  const float* cur = x_dev;
+  for (int a = 0; a < n_oct; ++a) {
+    int lo, hi;
+    octave_bins(plan->n_bins, plan->bpo, a, lo, hi);
+    if ((s = run_conv(plan->octave[a], cur, B, La[a], T, out_dev, (long long)plan->n_bins * T, lo, 0, hip_stream)) != NNA_OK)
+      return s;
+    if (a + 1 < n_oct) {
+      float* dst = buf[a & 1];
+      const long long Ln = La[a + 1];
+      if ((s = run_conv(plan->fir, cur, B, La[a], (Ln + CQ_ROWS - 1) / CQ_ROWS, dst, Ln, 0, Ln, hip_stream)) != NNA_OK)
+        return s;
+      cur = dst;
+    }
+  }
+  return NNA_OK;
+}
+
+nna_status nna_plan_part(const nna_plan* plan, int index, const nna_plan** part) {
+  if (!plan || !part) return fail(NNA_ERR_INVALID_ARG, "plan / part is NULL");
+  *part = nullptr;
+  if (plan->kind != NNA_KIND_CQT2010V2) return fail(NNA_ERR_INVALID_ARG, "not a downsampling CQT plan");
+  if (index == -1) {
+    if (!plan->fir) return fail(NNA_ERR_INVALID_ARG, "a single-octave plan has no filter");
+    *part = plan->fir;
+    return NNA_OK;
+  }
+  if (index < 0 || index >= (int)plan->octave.size()) return fail(NNA_ERR_INVALID_ARG, "no such octave");
+  *part = plan->octave[index];
+  return NNA_OK;
 }
 
 nna_status nna_out_shape(const nna_plan* plan, long long B, long long L, long long* n_bins, long long* n_frames) {
   if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
   if (B < 1) return fail(NNA_ERR_SHAPE, "B must be >= 1");
+  if (plan->kind == NNA_KIND_CQT2010V2) {
+    std::vector<long long> La;
+    if (L < 1 || !cqt2010_lengths(plan, L, La))
+      return fail(NNA_ERR_SHAPE, "L is too short: every octave's waveform must exceed the reflection padding");
+    if (n_bins) *n_bins = plan->n_bins;
+    if (n_frames) *n_frames = 1 + L / plan->hop;
+    return NNA_OK;
+  }
   const long long T = frames_of(plan, L);
   if (T < 1) return fail(NNA_ERR_SHAPE, plan->center ? "L must exceed the reflection padding (K/2)" : "L is shorter than one window");
   if (n_bins) *n_bins = plan->kind == NNA_KIND_STFT ? plan->stft_bins() : plan->kind == NNA_KIND_MEL ? plan->n_mels : plan->n_bins;
@@ -843,35 +1127,16 @@ nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long l
   long long T = 0;
   nna_status s = check_call(plan, NNA_KIND_CQT, x_dev, B, L, out_dev, &T);
   if (s != NNA_OK) return s;
-  const int extra = plan->max_jspan - 1;
-  const int M = pick_tile_frames(CQ_FRAMES, T, extra, CQ_LDS_ROWS_MAX);
-  if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
-  nna::CqtParams P;
-  std::memset(&P, 0, sizeof(P));
-  P.g = make_geom(plan, x_dev, B, L, T);
-  P.bank = reinterpret_cast<const float4*>(plan->d_bank);
-  P.items = plan->d_items;
-  P.chunks = plan->d_chunks;
-  P.out = out_dev;
-  P.n_items = (int)plan->h_items.size();
-  P.n_chunks = plan->n_chunks;
-  P.n_bins = plan->n_bins;
-  P.fmt = plan->fmt;
-  P.tile_frames = M;
-  const long long nseg = 1 + (M - 1 + T - 1) / T;
-  P.lds_rows = (int)((M + nseg * extra + 63) / 64 * 64);  // whole loader passes of 64 rows (<= CQ_LDS_ROWS_MAX)
-  P.n_ft = (P.g.n_frames + M - 1) / M;
   DeviceGuard guard;
   hipError_t e = guard.enter(plan->device);
   if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
-  e = nna::launch_cqt(P, reinterpret_cast<hipStream_t>(hip_stream));
-  if (e != hipSuccess) return fail_hip(e, "kernel launch");
-  return NNA_OK;
+  return run_conv(plan, x_dev, B, L, T, out_dev, (long long)plan->n_bins * T, 0, 0, hip_stream);
 }
 
 nna_status nna_plan_bank(const nna_plan* plan, double* host_out, size_t cap) {
   if (!plan || !host_out) return fail(NNA_ERR_INVALID_ARG, "plan / host_out is NULL");
-  const long long rows = plan->kind == NNA_KIND_CQT ? 2LL * plan->n_bins : 2LL * (plan->freq_scale ? plan->n_half : plan->n_half + 1);
+  if (plan->kind == NNA_KIND_CQT2010V2) return fail(NNA_ERR_INVALID_ARG, "a downsampling CQT plan holds several banks");
+  const long long rows = plan->kind == NNA_KIND_CQT ? (long long)plan->conv_rows : 2LL * (plan->freq_scale ? plan->n_half : plan->n_half + 1);
   const long long K = plan->K;
   if ((unsigned long long)cap < (unsigned long long)(rows * K)) return fail(NNA_ERR_INVALID_ARG, "host_out is too small");
   std::vector<float> tmp;
@@ -977,7 +1242,10 @@ nna_status nna_plan_info(const nna_plan* plan, int* kind, long long* bank_rows, 
                          double* executed_flops_per_frame, double* algorithmic_flops_per_frame) {
   if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
   if (kind) *kind = plan->kind;
-  if (bank_rows) *bank_rows = plan->kind == NNA_KIND_CQT ? 2LL * plan->n_bins : 2LL * (plan->freq_scale ? plan->n_half : plan->n_half + 1);
+  if (bank_rows)
+    *bank_rows = plan->kind == NNA_KIND_CQT2010V2 ? 0
+                 : plan->kind == NNA_KIND_CQT     ? (long long)plan->conv_rows
+                                                  : 2LL * (plan->freq_scale ? plan->n_half : plan->n_half + 1);
   if (taps) *taps = plan->K;
   if (out_bins) *out_bins = plan->kind == NNA_KIND_STFT ? plan->stft_bins() : plan->kind == NNA_KIND_MEL ? plan->n_mels : plan->n_bins;
   if (executed_flops_per_frame) *executed_flops_per_frame = plan->exec_flops;
@@ -1004,6 +1272,8 @@ nna_status nna_plan_cqt_lengths(const nna_plan* plan, long long* host_out, size_
 
 void nna_plan_destroy(nna_plan* plan) {
   if (!plan) return;
+  for (nna_plan* sub : plan->octave) nna_plan_destroy(sub);
+  nna_plan_destroy(plan->fir);
   if (plan->device >= 0) {
     DeviceGuard guard;
     if (guard.enter(plan->device) == hipSuccess) {

@@ -290,6 +290,77 @@ def test_cqt_tone_closed_form_on_gpu(nb):
 
 
 # ---------------------------------------------------------------------------------------
+# CQT by recursive downsampling
+# ---------------------------------------------------------------------------------------
+CQT2010_CASES = [
+    # name, B, L, sr, hop, fmin, n_bins, bpo, n_taps, fir_taps, fmt
+    ("defaults: 7 octaves of 12 bins", 2, 22050, 22050, 512, 32.70, 84, 12, 0, 0, 0),
+    ("partial lowest octave, short filter", 3, 6000, 16000, 64, 220.0, 29, 12, 0, 63, 0),
+    ("single octave: no filter, no workspace", 2, 9000, 16000, 128, 1000.0, 12, 12, 0, 0, 1),
+    ("odd lengths at every octave (scalar stores, unaligned rows)", 2, 22051, 22050, 256, 65.41, 48, 12, 0, 129, 0),
+    ("many short waveforms per tile, log output", 37, 3000, 16000, 32, 500.0, 16, 4, 0, 31, 2),
+    ("24 bins per octave, explicit taps", 2, 30000, 44100, 128, 523.25, 72, 24, 2048, 257, 0),
+]
+
+
+@pytest.mark.parametrize("case", CQT2010_CASES, ids=[c[0] for c in CQT2010_CASES])
+def test_cqt2010v2_parity_small(nb, case):
+    name, B, L, sr, hop, fmin, n_bins, bpo, n_taps, fir_taps, fmt = case
+    _say(f"cqt2010v2 {name}: B={B} L={L} sr={sr} hop={hop} bins={n_bins}/{bpo} taps={n_taps} fir={fir_taps} fmt={fmt}")
+    x = _rand(B, L, 2010 + n_bins)
+    plan = nb.nna_plan_cqt2010v2(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, n_taps=n_taps,
+                                 fir_taps=fir_taps, fmt=fmt, device=0)
+    got = nb.nna_cqt2010v2(plan, _dev(x)).cpu().numpy()
+    ref = oracle.cqt2010v2(x, sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, n_taps=n_taps,
+                           fir_taps=fir_taps or oracle.FIR_TAPS, fmt=fmt)
+    e = _rel_err(got, ref)
+    # every octave against its own peak too: the low octaves of noise are much weaker than the top
+    n_oct = -(-n_bins // bpo)
+    for a in range(n_oct):
+        hi = n_bins - a * bpo
+        lo = max(0, hi - bpo)
+        e = max(e, _rel_err(got[:, lo:hi], ref[:, lo:hi]))
+    _say(f"  rel err {e:.3e}")
+    assert e < TOL
+
+
+def test_cqt2010v2_tone_closed_form_on_gpu(nb):
+    # a tone on bin k reads A/2 in whichever octave k falls (filter ripple and kernel detuning: 1 %)
+    _say("cqt2010v2 closed form tones")
+    sr, A = 22050, 0.6
+    _, fk = oracle.cqt_lengths(sr, 32.70, 84, 12)
+    ks = [3, 30, 50, 71, 83]
+    x = np.stack([signals.tone(22050, sr, fk[k], amp=A) for k in ks])
+    plan = nb.nna_plan_cqt2010v2(sr=sr, device=0)
+    got = nb.nna_cqt2010v2(plan, _dev(x)).cpu().numpy()
+    for i, k in enumerate(ks):
+        mid = got[i, :, 15:30]
+        assert np.all(mid.argmax(axis=0) == k)
+        assert np.allclose(mid[k], A / 2, rtol=1e-2)
+
+
+def test_cqt2010v2_workspace_and_shape_checks(nb):
+    import torch
+    plan = nb.nna_plan_cqt2010v2(sr=22050, device=0)
+    x = torch.zeros((2, 22050), device="cuda:0")
+    need = nb.nna_cqt2010v2_workspace(plan, 2, 22050)
+    assert need >= 4 * 2 * (11025 + 5513)
+    with pytest.raises(nb.NnaError) as e:
+        nb.nna_cqt2010v2(plan, x, workspace=torch.empty(need - 256, dtype=torch.uint8, device="cuda:0"))
+    assert e.value.status == nb.NNA_ERR_INVALID_ARG
+    with pytest.raises(nb.NnaError) as e:
+        nb.nna_cqt2010v2(plan, torch.zeros((2, 4000), device="cuda:0"))  # the deepest octave would have 63 samples
+    assert e.value.status == nb.NNA_ERR_SHAPE
+    with pytest.raises(nb.NnaError):
+        nb.nna_cqt(plan, x)  # wrong entry point for this plan
+    # a caller-owned workspace is enough, and is reusable
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    a = nb.nna_cqt2010v2(plan, x + 0.25, workspace=ws)
+    b = nb.nna_cqt2010v2(plan, x + 0.25, workspace=ws)
+    assert torch.equal(a, b)
+
+
+# ---------------------------------------------------------------------------------------
 # The two 1,770-waveform workloads at full size, in the launch configuration the bench times;
 # the oracle checks a sample of whole waveforms (first, second, middle, last two).
 # ---------------------------------------------------------------------------------------
@@ -356,6 +427,25 @@ def test_cqt_config5_full_sampled(nb):
     xs = signals.batch(5, SAMPLED)
     ref = oracle.cqt(xs, sr=44100, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24, n_taps=65536)
     e = _rel_err(out[SAMPLED].cpu().numpy(), ref)
+    _say(f"  rel err {e:.3e}")
+    assert e < TOL
+    assert torch.isfinite(out).all() and (out >= 0).all()
+
+
+def test_cqt2010v2_config5_full_sampled(nb):
+    import torch
+    _say("cqt2010v2 on config 5's batch (1770 x 176400 @ 44100 Hz, 168 bins, 24 / octave) sampled waveforms")
+    x = _full_batch(5)
+    plan = nb.nna_plan_cqt2010v2(sr=44100, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24, device=0)
+    out = nb.nna_cqt2010v2(plan, x)
+    torch.cuda.synchronize()
+    assert tuple(out.shape) == (1770, 168, 345)
+    xs = signals.batch(5, SAMPLED)
+    ref = oracle.cqt2010v2(xs, sr=44100, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24)
+    got = out[SAMPLED].cpu().numpy()
+    e = _rel_err(got, ref)
+    for a in range(7):
+        e = max(e, _rel_err(got[:, 168 - 24 * (a + 1):168 - 24 * a], ref[:, 168 - 24 * (a + 1):168 - 24 * a]))
     _say(f"  rel err {e:.3e}")
     assert e < TOL
     assert torch.isfinite(out).all() and (out >= 0).all()

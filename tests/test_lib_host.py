@@ -25,7 +25,7 @@ def _status(fn, *a, **k):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "nna.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(nna_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(nna_[a-z0-9_]+)\s*\(", header))
     assert declared == set(nb.EXPORTS)
     L = ctypes.CDLL(nb.LIB_PATH)
     for name in declared:
@@ -202,3 +202,49 @@ def test_cqt_workload_5_plan_facts():
     assert (Nk[0], Nk[-1], Nk.sum()) == (46025, 371, 1604166)
     # zero-tap skipping: executed work stays within 25 % of the non-zero taps
     assert info["executed_flops_per_frame"] < 1.25 * info["algorithmic_flops_per_frame"]
+
+
+@pytest.mark.parametrize("sr,hop,fmin,n_bins,bpo,fir", [(22050, 512, 32.70, 84, 12, 0), (16000, 64, 220.0, 29, 12, 63),
+                                                       (44100, 512, 32.70, 168, 24, 257)])
+def test_cqt2010v2_plan_parts(sr, hop, fmin, n_bins, bpo, fir):
+    p = nb.nna_plan_cqt2010v2(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, fir_taps=fir, device=-1)
+    info = p.info()
+    n_taps = oracle.cqt2010_default_taps(sr, fmin, n_bins, bpo)
+    assert info["kind"] == nb.NNA_KIND_CQT2010V2 and info["out_bins"] == n_bins and info["taps"] == n_taps
+    # the filter: 16 shifted copies of the window-method half-band design
+    h = oracle.lowpass_fir(fir or oracle.FIR_TAPS, 0.5)
+    bank = nb.nna_plan_bank(nb.nna_plan_part(p, -1))
+    assert bank.shape[0] == 16
+    for r in range(16):
+        want = np.zeros(bank.shape[1])
+        want[2 * r:2 * r + h.size] = h
+        np.testing.assert_allclose(bank[r], want, atol=3e-8)
+    # octave a: the kernels of its bins, one factor 2^a up the frequency axis, at the original rate
+    n_oct = -(-n_bins // bpo)
+    for a in range(n_oct):
+        hi = n_bins - a * bpo
+        lo = max(0, hi - bpo)
+        part = nb.nna_plan_part(p, a)
+        kre, kim = oracle.cqt_kernels(sr, fmin * 2.0 ** ((lo + a * bpo) / bpo), hi - lo, bpo, n_taps=n_taps)
+        got = nb.nna_plan_bank(part)
+        assert got.shape == (2 * (hi - lo), n_taps)
+        np.testing.assert_allclose(got[0::2], kre, atol=2e-9)
+        np.testing.assert_allclose(got[1::2], kim, atol=2e-9)
+    assert _status(nb.nna_plan_part, p, n_oct) == nb.NNA_ERR_INVALID_ARG
+    assert nb.nna_out_shape(p, 3, 400 * hop + 5) == (n_bins, 401)
+
+
+def test_cqt2010v2_argument_checking():
+    f = nb.nna_plan_cqt2010v2
+    assert _status(f, hop=100, device=-1) == nb.NNA_ERR_INVALID_ARG       # 7 octaves need hop % 64 == 0
+    assert _status(f, fir_taps=256, device=-1) == nb.NNA_ERR_INVALID_ARG  # even: no integer delay
+    assert _status(f, n_bins=120, device=-1) == nb.NNA_ERR_INVALID_ARG    # top bin above Nyquist
+    assert _status(f, n_taps=128, device=-1) == nb.NNA_ERR_INVALID_ARG    # shorter than the top octave's longest kernel
+    p = f(device=-1)
+    assert _status(nb.nna_out_shape, p, 1, 4000) == nb.NNA_ERR_SHAPE      # deepest octave: 63 samples <= 128
+    assert _status(nb.nna_plan_bank, p) == nb.NNA_ERR_INVALID_ARG         # several banks: ask for a part
+    assert _status(nb.nna_plan_part, nb.nna_plan_cqt(device=-1), 0) == nb.NNA_ERR_INVALID_ARG
+    single = f(fmin=1000.0, n_bins=12, sr=16000, device=-1)
+    assert _status(nb.nna_plan_part, single, -1) == nb.NNA_ERR_INVALID_ARG  # one octave: no filter
+    assert nb.nna_cqt2010v2_workspace(single, 4, 9000) == 0
+    assert nb.nna_cqt2010v2_workspace(p, 4, 22050) >= 4 * 4 * (11025 + 5513)
