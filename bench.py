@@ -48,6 +48,8 @@ def main() -> int:
                          "holds a kernel of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--only", choices=["stft", "mel", "cqt"], default=None,
                     help="time a single transform (profiling aid); the JSON line then covers that one only")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the transforms timed beside the headline step (linear-frequency STFT, downsampling CQT)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (waveforms are independent, so more GPUs would "
@@ -160,6 +162,40 @@ def main() -> int:
         "traffic": traffic.get(dom),
     }
 
+    # Timed beside the step, never part of `value`: the same batch through the STFT on the linear
+    # frequency axis of Sec. II-B's worked example and through the downsampling CQT (Sec. III-C).
+    extras = None
+    if not args.no_extras and not args.only:
+        extras = {}
+        del o_stft, o_mel
+        p_lin = nb.nna_plan_stft_scaled(sr=sr, n_fft=2048, hop=512, freq_scale=nb.NNA_FREQ_LINEAR, fmin=50.0,
+                                        fmax=6000.0, freq_bins=1025, device=0)
+        p_2010 = nb.nna_plan_cqt2010v2(sr=sr, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24, device=0)
+        o_lin = torch.empty((B, 1025, T), dtype=torch.float32, device=dev)
+        ws = torch.empty(max(16, nb.nna_cqt2010v2_workspace(p_2010, B, L)), dtype=torch.uint8, device=dev)
+        for name, fn, plan in (("stft_linear_axis", lambda: nb.nna_stft(p_lin, x4, o_lin), p_lin),
+                               ("cqt2010v2", lambda: nb.nna_cqt2010v2(p_2010, x5, o_cqt, workspace=ws), p_2010)):
+            for _ in range(max(1, args.warmup)):
+                fn()
+            ev = []
+            for _ in range(args.steps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                fn()
+                b.record()
+                ev.append((a, b))
+            torch.cuda.synchronize()
+            ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+            info = plan.info()
+            extras[name] = {
+                "ms": round(ms, 4),
+                "gsamples_per_s": round(B * L / ms / 1e6, 4),
+                "algorithmic_tflops": round(info["algorithmic_flops_per_frame"] * B * T / ms / 1e9, 3),
+                "executed_tflops": round(info["executed_flops_per_frame"] * B * T / ms / 1e9, 3),
+                "mfma_frac": round(info["algorithmic_flops_per_frame"] * B * T / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+            }
+        del o_lin, ws
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -211,6 +247,7 @@ def main() -> int:
         "per_transform": per,
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "extras": extras,
         "setup_s": {"input_generation": round(t_gen, 2), "plans": round(t_plan, 2)},
     }
     print(json.dumps(line))

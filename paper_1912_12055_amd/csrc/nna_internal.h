@@ -76,7 +76,8 @@ struct CqtChunk {
   int jlo;   // first hop-shift of the chunk's LDS rows (that of the item's first, longest row block)
   int pad0, pad1;
   int joff[CQ_ITEM_RB];  // first hop-shift of row block r, relative to jlo
-  int nj[CQ_ITEM_RB];    // bank fragments of row block r in this chunk: a multiple of CQ_PREFETCH, 0 = none
+  int nj[CQ_ITEM_RB];    // low 16 bits: bank fragments of row block r in this chunk, a multiple of CQ_PREFETCH
+                         // (0 = none); high 16 bits: how many of them, from the front, hold taps
 };
 
 // A CQT work item: up to CQ_ITEM_RB consecutive row blocks that share the LDS tiles of the first.

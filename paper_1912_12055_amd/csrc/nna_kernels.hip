@@ -694,10 +694,13 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
     // One fragment group: 16 taps, 16 MFMAs on the accumulators of row block R_.  `slot` is the
     // ring register that holds this group's bank fragment; it is a compile-time constant because
     // a register with a load in flight must never be copied.  The planner pads every row block's
-    // share of a chunk to a multiple of CQ_PREFETCH groups (zero fragments), so the slots stay
-    // aligned: group jj always lives in slot jj % CQ_PREFETCH.
+    // share of a chunk to a multiple of CQ_PREFETCH fragments (zero fragments), so the slots stay
+    // aligned: group jj always lives in slot jj % CQ_PREFETCH.  A padding group (`run` false) keeps
+    // the ring's rhythm -- it waits for its slot and requests the slot's next fragment -- but
+    // issues no MFMA.  The wait and the request stay outside the branch: each ring register is
+    // written by one and the same instruction on every path.
     f32x4 a_cur[4];
-    auto group = [&](auto rb_tag, auto task_tag, auto slot_tag, const float* base, int jj, int nj) {
+    auto group = [&](auto rb_tag, auto task_tag, auto slot_tag, const float* base, int jj, int nj, bool run) {
       constexpr int R_ = decltype(rb_tag)::value;
       constexpr int TASK = decltype(task_tag)::value;
       constexpr int slot = decltype(slot_tag)::value;
@@ -708,20 +711,22 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
       wait_vm<W_SLOT>(bq[slot]);
       __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);  // the 4 LDS reads go first
       __builtin_amdgcn_sched_barrier(0);
+      if (TASK != TASK_NONE || run) {
 #pragma unroll
-      for (int m = 0; m < 16; ++m) {
-        const int e = m >> 2, fb = m & 3;
-        acc[R_][fb] = __builtin_amdgcn_mfma_f32_16x16x4f32(bq[slot][e], a_cur[fb][e], acc[R_][fb], 0, 0, 0);
-        if (TASK != TASK_NONE && (m & 1)) {
-          const int p = m >> 1;  // 0..7 = CQ_NPASS passes
-          __builtin_amdgcn_sched_barrier(0);
-          if (TASK == TASK_STORE) {
-            if (fx_store.cls != 2 && p < n_pass_rows)
-              *reinterpret_cast<f32x4*>(stage_dst + p * CQ_RPP * CQ_PITCH) = fixed_up<CQ_NPASS>(R[p], fx_store, p);
-          } else {
-            gload16(R[p], ptr[p]);
+        for (int m = 0; m < 16; ++m) {
+          const int e = m >> 2, fb = m & 3;
+          acc[R_][fb] = __builtin_amdgcn_mfma_f32_16x16x4f32(bq[slot][e], a_cur[fb][e], acc[R_][fb], 0, 0, 0);
+          if (TASK != TASK_NONE && (m & 1)) {
+            const int p = m >> 1;  // 0..7 = CQ_NPASS passes
+            __builtin_amdgcn_sched_barrier(0);
+            if (TASK == TASK_STORE) {
+              if (fx_store.cls != 2 && p < n_pass_rows)
+                *reinterpret_cast<f32x4*>(stage_dst + p * CQ_RPP * CQ_PITCH) = fixed_up<CQ_NPASS>(R[p], fx_store, p);
+            } else {
+              gload16(R[p], ptr[p]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
           }
-          __builtin_amdgcn_sched_barrier(0);
         }
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -739,29 +744,35 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
     using TNone = std::integral_constant<int, TASK_NONE>;
     using TStore = std::integral_constant<int, TASK_STORE>;
     using TLoad = std::integral_constant<int, TASK_LOAD>;
-    // all fragment groups of row block R_ in this chunk; the item's first row block (always
-    // present, >= 4 groups) carries the staging tasks in its first two groups
+    // all fragment groups of row block R_ in this chunk: nj of them, the first nr real, the rest
+    // padding; the item's first row block (always present, >= 4 groups) carries the staging tasks in
+    // its first two groups
     auto row_block = [&](auto rb_tag) {
       constexpr int R_ = decltype(rb_tag)::value;
-      const int nj = njr[R_];
+      const int nj = njr[R_] & 0xffff, nr = njr[R_] >> 16;
       if (R_ >= n_rb || nj == 0) return;
       const float* base = cur + joff[R_] * CQ_PITCH;
 #pragma unroll
       for (int fb = 0; fb < 4; ++fb) a_cur[fb] = *reinterpret_cast<const f32x4*>(base + a_off[fb]);
+      int jj = 0;
       if (R_ == 0) {
-        group(rb_tag, TStore{}, S0{}, base, 0, nj);
-        group(rb_tag, TLoad{}, S1{}, base, 1, nj);
-      } else {
-        group(rb_tag, TNone{}, S0{}, base, 0, nj);
-        group(rb_tag, TNone{}, S1{}, base, 1, nj);
+        group(rb_tag, TStore{}, S0{}, base, 0, nj, true);
+        group(rb_tag, TLoad{}, S1{}, base, 1, nj, true);
+        group(rb_tag, TNone{}, S2{}, base, 2, nj, 2 < nr);
+        group(rb_tag, TNone{}, S3{}, base, 3, nj, 3 < nr);
+        jj = 4;
       }
-      group(rb_tag, TNone{}, S2{}, base, 2, nj);
-      group(rb_tag, TNone{}, S3{}, base, 3, nj);
-      for (int jj = 4; jj < nj; jj += 4) {
-        group(rb_tag, TNone{}, S0{}, base, jj, nj);
-        group(rb_tag, TNone{}, S1{}, base, jj + 1, nj);
-        group(rb_tag, TNone{}, S2{}, base, jj + 2, nj);
-        group(rb_tag, TNone{}, S3{}, base, jj + 3, nj);
+      for (; jj + 4 <= nr; jj += 4) {
+        group(rb_tag, TNone{}, S0{}, base, jj, nj, true);
+        group(rb_tag, TNone{}, S1{}, base, jj + 1, nj, true);
+        group(rb_tag, TNone{}, S2{}, base, jj + 2, nj, true);
+        group(rb_tag, TNone{}, S3{}, base, jj + 3, nj, true);
+      }
+      if (jj < nj) {  // the last quad: 1..3 real groups, then padding
+        group(rb_tag, TNone{}, S0{}, base, jj, nj, jj < nr);
+        group(rb_tag, TNone{}, S1{}, base, jj + 1, nj, jj + 1 < nr);
+        group(rb_tag, TNone{}, S2{}, base, jj + 2, nj, jj + 2 < nr);
+        group(rb_tag, TNone{}, S3{}, base, jj + 3, nj, false);
       }
     };
     row_block(std::integral_constant<int, 0>{});

@@ -64,7 +64,6 @@ struct nna_plan {
   std::vector<double> h_fir;
   std::vector<nna::CqtItem> h_items;
   std::vector<nna::CqtChunk> h_chunks;   // [item][n_chunks]
-  std::vector<int> h_nj_real;            // [item][n_chunks][CQ_ITEM_RB] fragments before ring padding
   int max_jspan = 1;
 
   double exec_flops = 0, alg_flops = 0;
@@ -385,9 +384,8 @@ void for_each_cqt_fragment(const nna_plan* p, Fn fn) {
     for (int c = 0; c < item.n_chunks; ++c) {
       const nna::CqtChunk& ck = p->h_chunks[it * p->n_chunks + c];
       for (int r = 0; r < item.n_rb; ++r)
-        for (int jj = 0; jj < ck.nj[r]; ++jj, ++f)
-          fn(f, item.rb_first + r, ck.jlo + ck.joff[r] + jj, ck.c0,
-             jj < p->h_nj_real[(it * p->n_chunks + c) * CQ_ITEM_RB + r]);
+        for (int jj = 0; jj < (ck.nj[r] & 0xffff); ++jj, ++f)
+          fn(f, item.rb_first + r, ck.jlo + ck.joff[r] + jj, ck.c0, jj < (ck.nj[r] >> 16));
     }
   }
 }
@@ -461,7 +459,7 @@ void build_conv_bank(nna_plan* p, ValueFn value) {
   }
   // per item: the chunks that hold taps, and for each the fragments of every row block
   std::vector<std::vector<nna::CqtChunk>> item_chunks(p->h_items.size());
-  std::vector<std::vector<int>> item_real(p->h_items.size());
+  long long exec_groups = 0;
   long long frag = 0;
   p->max_jspan = 1;
   p->n_chunks = 1;
@@ -480,10 +478,13 @@ void build_conv_bank(nna_plan* p, ValueFn value) {
         int jlo = 0, nj = 0;
         if (r < item.n_rb) shifts_of(item.rb_first + r, c, jlo, nj);
         ck.joff[r] = nj > 0 ? jlo - jlo0 : 0;
-        ck.nj[r] = ring_pad(nj);  // whole rings of CQ_PREFETCH fragments (zero fragments pad)
-        item_real[it].push_back(nj);
-        item.jspan = std::max(item.jspan, ck.joff[r] + ck.nj[r]);
-        frag += ck.nj[r];
+        const int padded = ring_pad(nj);  // whole rings of CQ_PREFETCH fragments (zero fragments pad)
+        ck.nj[r] = padded | (nj << 16);
+        item.jspan = std::max(item.jspan, ck.joff[r] + padded);
+        frag += padded;
+        // the kernel runs MFMAs for the real fragments only, but always for the first two groups of
+        // the item's first row block, which carry the tile staging
+        exec_groups += r == 0 ? std::max(nj, 2) : nj;
       }
       item_chunks[it].push_back(ck);
     }
@@ -492,12 +493,9 @@ void build_conv_bank(nna_plan* p, ValueFn value) {
     p->max_jspan = std::max(p->max_jspan, item.jspan);
   }
   p->h_chunks.assign(p->h_items.size() * (size_t)p->n_chunks, nna::CqtChunk{});
-  p->h_nj_real.assign(p->h_items.size() * (size_t)p->n_chunks * CQ_ITEM_RB, 0);
   for (size_t it = 0; it < p->h_items.size(); ++it)
     for (size_t c = 0; c < item_chunks[it].size(); ++c) {
       p->h_chunks[it * p->n_chunks + c] = item_chunks[it][c];
-      for (int r = 0; r < CQ_ITEM_RB; ++r)
-        p->h_nj_real[(it * p->n_chunks + c) * CQ_ITEM_RB + r] = item_real[it][c * CQ_ITEM_RB + r];
     }
   p->bank_groups = frag;
   p->bank_floats = (size_t)(frag + CQ_PREFETCH) * 64 * 4;
@@ -512,7 +510,7 @@ void build_conv_bank(nna_plan* p, ValueFn value) {
       for (int e = 0; e < 4; ++e) dst[e] = row < p->conv_rows && tap0 + e < K ? (float)value(row, tap0 + e) : 0.0f;
     }
   });
-  p->exec_flops = 2.0 * (double)frag * CQ_KC * CQ_ROWS;
+  p->exec_flops = 2.0 * (double)exec_groups * CQ_KC * CQ_ROWS;
 }
 
 void build_cqt_bank(nna_plan* p) {
