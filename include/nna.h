@@ -173,14 +173,15 @@ nna_status nna_cqt2010v2_workspace(const nna_plan* plan, long long B, long long 
  * workspace_dev: caller-owned device memory, 16-byte aligned, of at least the size above; its
  * contents are overwritten and mean nothing afterwards.  Launches 2*octaves - 1 kernels on
  * hip_stream; nothing is allocated.  NNA_ERR_SHAPE if some octave's waveform is not longer
- * than the kernels' half length n_taps/2 or shorter than the filter's frame. */
+ * than the kernels' half length n_taps/2 or shorter than the filter's frame (fir_taps + 126
+ * samples, rounded up to a multiple of 128). */
 nna_status nna_cqt2010v2(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
                          void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
 /* Downsampling CQT plans only: *part = the plan of octave `index` (0 = top; a plan as from
  * nna_plan_cqt, for nna_plan_bank / nna_plan_info / nna_plan_cqt_lengths), or with index -1 the
- * filter as the kernel runs it: a bank of 16 rows, row r = the taps h shifted right by 2 r
- * (16 consecutive output samples per kernel frame).  The parts belong to `plan`. */
+ * filter as the kernel runs it: a bank of 64 rows, row r = the taps h shifted right by 2 r
+ * (64 consecutive output samples per kernel frame).  The parts belong to `plan`. */
 nna_status nna_plan_part(const nna_plan* plan, int index, const nna_plan** part);
 
 /*

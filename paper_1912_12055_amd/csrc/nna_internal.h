@@ -98,8 +98,8 @@ struct CqtParams {
   float* out;
   long long out_wave_stride;  // elements of `out` per waveform (all bins x frames; raw: samples)
   int bin_offset;          // spectrogram: bin 0 of this bank is row bin_offset of each waveform's output
-  int raw;                 // 1: the 16 bank rows are 16 consecutive output samples of a real signal
-                           //    (frame t, row r -> out[b][16 t + r]); no magnitude is taken
+  int raw;                 // > 0: the bank's `raw` rows are consecutive output samples of a real signal
+                           //    (frame t, row r -> out[b][raw t + r]); no magnitude is taken
   int raw_vec;             // raw: 16-byte stores are aligned
   long long raw_len;       // raw: output samples per waveform
   int n_items;

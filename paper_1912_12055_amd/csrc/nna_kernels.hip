@@ -788,21 +788,26 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
   for (int i = 0; i < CQ_PREFETCH; ++i) wait_vm<0>(bq[i]);
 
   if (P.raw) {
-    // real-valued bank of one row block (a decimating FIR filter written as 16 shifted copies):
-    // register i of lane (q, n) is output sample 16 t + 4 q + i of the frame's waveform
+    // real-valued bank (a decimating FIR filter written as P.raw shifted copies): register i of
+    // lane (q, n) in row block rb is output sample P.raw t + 16 rb + 4 q + i of the frame's waveform
 #pragma unroll
     for (int fb = 0; fb < 4; ++fb) {
       if (!valid[fb]) continue;
       const long long fr = f0 + wave * 64 + fb * 16 + n;
       const long long b = fr / g.T;
-      const long long pos = 16 * (fr - b * g.T) + 4 * q;
-      float* __restrict__ op = P.out + b * P.out_wave_stride + pos;
-      if (P.raw_vec && pos + 3 < P.raw_len) {
-        *reinterpret_cast<f32x4*>(op) = acc[0][fb];
-      } else {
+      const long long pos0 = (long long)P.raw * (fr - b * g.T) + 4 * q;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (pos + i < P.raw_len) op[i] = acc[0][fb][i];
+      for (int r = 0; r < CQ_ITEM_RB; ++r) {
+        if (r >= n_rb) continue;
+        const long long pos = pos0 + 16 * (item.rb_first + r);
+        float* __restrict__ op = P.out + b * P.out_wave_stride + pos;
+        if (P.raw_vec && pos + 3 < P.raw_len) {
+          *reinterpret_cast<f32x4*>(op) = acc[r][fb];
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (pos + i < P.raw_len) op[i] = acc[r][fb][i];
+        }
       }
     }
     return;

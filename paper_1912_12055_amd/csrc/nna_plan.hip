@@ -1,6 +1,7 @@
 // Host side of the library: argument checking, kernel-bank construction in double precision,
 // permutation of the banks into the order the GPU kernels stream them, and the C ABI itself.
 #include <algorithm>
+#include <climits>
 #include <cmath>
 #include <cstdint>
 #include <cstdio>
@@ -468,22 +469,28 @@ void build_conv_bank(nna_plan* p, ValueFn value) {
     item.frag0 = frag;
     item.jspan = 1;
     for (int c = 0; c < n_grid; ++c) {
-      int jlo0, nj0;
-      shifts_of(item.rb_first, c, jlo0, nj0);
-      if (nj0 == 0) continue;  // the first (longest) row block has no taps here: nor have the others
+      // the chunk is listed if any row block of the item has taps in it; its LDS rows start at the
+      // smallest hop-shift any of them needs
+      int jl[CQ_ITEM_RB] = {0, 0, 0, 0}, nn[CQ_ITEM_RB] = {0, 0, 0, 0};
+      int jmin = INT_MAX;
+      for (int r = 0; r < item.n_rb; ++r) {
+        shifts_of(item.rb_first + r, c, jl[r], nn[r]);
+        if (nn[r] > 0) jmin = std::min(jmin, jl[r]);
+      }
+      if (jmin == INT_MAX) continue;
       nna::CqtChunk ck{};
       ck.c0 = c * CQ_KC;
-      ck.jlo = jlo0;
+      ck.jlo = jmin;
       for (int r = 0; r < CQ_ITEM_RB; ++r) {
-        int jlo = 0, nj = 0;
-        if (r < item.n_rb) shifts_of(item.rb_first + r, c, jlo, nj);
-        ck.joff[r] = nj > 0 ? jlo - jlo0 : 0;
-        const int padded = ring_pad(nj);  // whole rings of CQ_PREFETCH fragments (zero fragments pad)
+        const int nj = nn[r];
+        ck.joff[r] = nj > 0 ? jl[r] - jmin : 0;
+        // whole rings of CQ_PREFETCH fragments (zero fragments pad); the item's first row block always
+        // has one ring, because its first two groups carry the tile staging
+        const int padded = r == 0 ? std::max(ring_pad(nj), CQ_PREFETCH) : ring_pad(nj);
         ck.nj[r] = padded | (nj << 16);
         item.jspan = std::max(item.jspan, ck.joff[r] + padded);
         frag += padded;
-        // the kernel runs MFMAs for the real fragments only, but always for the first two groups of
-        // the item's first row block, which carry the tile staging
+        // the kernel runs MFMAs for the real fragments only, and for those two groups
         exec_groups += r == 0 ? std::max(nj, 2) : nj;
       }
       item_chunks[it].push_back(ck);
@@ -750,10 +757,12 @@ std::vector<double> half_band_taps(int n) {
   return h;
 }
 
-// The filter + keep-every-second-sample step as a bank for the CQT kernel: a "frame" is 16
-// consecutive output samples y[16 t + r], r = 0..15; it reads input samples 32 t - half + [0, K)
-// and row r holds the filter shifted by 2 r taps (y[m] is centred on x[2 m]).
-constexpr int FIR_HOP = 2 * CQ_ROWS;
+// The filter + keep-every-second-sample step as a bank for the CQT kernel: a "frame" is FIR_ROWS
+// consecutive output samples y[FIR_ROWS t + r]; it reads input samples 2 FIR_ROWS t - half + [0, K)
+// and row r holds the filter shifted by 2 r taps (y[m] is centred on x[2 m]).  Four row blocks =
+// one work item, so a workgroup produces 64 samples per frame from one set of LDS tiles.
+constexpr int FIR_ROWS = CQ_ITEM_RB * CQ_ROWS;
+constexpr int FIR_HOP = 2 * FIR_ROWS;
 nna_status make_fir_plan(nna_plan** plan, int fir_taps, int device) {
   nna_plan* p = new (std::nothrow) nna_plan;
   if (!p) return fail(NNA_ERR_ALLOC, "out of host memory");
@@ -766,13 +775,13 @@ nna_status make_fir_plan(nna_plan** plan, int fir_taps, int device) {
     p->window = NNA_WIN_RECT;
     p->fmt = NNA_OUT_MAGNITUDE;
     p->fir_taps = fir_taps;
-    p->K = (fir_taps + 2 * (CQ_ROWS - 1) + FIR_HOP - 1) / FIR_HOP * FIR_HOP;
+    p->K = (fir_taps + 2 * (FIR_ROWS - 1) + FIR_HOP - 1) / FIR_HOP * FIR_HOP;
     p->pad = (fir_taps - 1) / 2;
     p->h_fir = half_band_taps(fir_taps);
-    p->conv_rows = CQ_ROWS;
-    p->row_s.resize(CQ_ROWS);
-    p->row_e.resize(CQ_ROWS);
-    for (int r = 0; r < CQ_ROWS; ++r) {
+    p->conv_rows = FIR_ROWS;
+    p->row_s.resize(FIR_ROWS);
+    p->row_e.resize(FIR_ROWS);
+    for (int r = 0; r < FIR_ROWS; ++r) {
       p->row_s[r] = 2 * r;
       p->row_e[r] = 2 * r + fir_taps;
     }
@@ -780,7 +789,7 @@ nna_status make_fir_plan(nna_plan** plan, int fir_taps, int device) {
       const long long i = tap - 2 * row;
       return i >= 0 && i < fir_taps ? p->h_fir[i] : 0.0;
     });
-    p->alg_flops = 2.0 * fir_taps * CQ_ROWS;  // per 16 output samples
+    p->alg_flops = 2.0 * fir_taps * FIR_ROWS;  // per frame of FIR_ROWS output samples
   } catch (const std::bad_alloc&) {
     delete p;
     return fail(NNA_ERR_ALLOC, "out of host memory while building the filter bank");
@@ -803,7 +812,7 @@ nna_status run_conv(const nna_plan* sub, const float* x, long long B, long long 
   P.out = out;
   P.out_wave_stride = out_wave_stride;
   P.bin_offset = bin_offset;
-  P.raw = raw_len > 0 ? 1 : 0;
+  P.raw = raw_len > 0 ? sub->conv_rows : 0;
   P.raw_len = raw_len;
   P.raw_vec = (raw_len % 4 == 0) && ((reinterpret_cast<uintptr_t>(out) & 15) == 0) ? 1 : 0;
   P.n_items = (int)sub->h_items.size();
@@ -1015,14 +1024,14 @@ nna_status nna_plan_cqt2010v2(nna_plan** plan, int sr, int hop, double fmin, int
     return s;
   }
   // per frame of the output: every octave's kernels once, and hop / 2^(a+1) filter outputs for
-  // each downsampling step a -> a+1 (the filter plan counts flops per 16 outputs)
+  // each downsampling step a -> a+1 (the filter plan counts flops per frame of FIR_ROWS outputs)
   for (int a = 0; a < n_oct; ++a) {
     p->exec_flops += p->octave[a]->exec_flops;
     p->alg_flops += p->octave[a]->alg_flops;
     if (a + 1 < n_oct) {
-      const double frames16 = (double)(hop >> (a + 1)) / CQ_ROWS;
-      p->exec_flops += frames16 * p->fir->exec_flops;
-      p->alg_flops += frames16 * p->fir->alg_flops;
+      const double fir_frames = (double)(hop >> (a + 1)) / FIR_ROWS;
+      p->exec_flops += fir_frames * p->fir->exec_flops;
+      p->alg_flops += fir_frames * p->fir->alg_flops;
     }
   }
   *plan = p;
@@ -1073,7 +1082,7 @@ nna_status nna_cqt2010v2(const nna_plan* plan, const float* x_dev, long long B, 
     if (a + 1 < n_oct) {
       float* dst = buf[a & 1];
       const long long Ln = La[a + 1];
-      if ((s = run_conv(plan->fir, cur, B, La[a], (Ln + CQ_ROWS - 1) / CQ_ROWS, dst, Ln, 0, Ln, hip_stream)) != NNA_OK)
+      if ((s = run_conv(plan->fir, cur, B, La[a], (Ln + FIR_ROWS - 1) / FIR_ROWS, dst, Ln, 0, Ln, hip_stream)) != NNA_OK)
         return s;
       cur = dst;
     }

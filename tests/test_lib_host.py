@@ -211,11 +211,11 @@ def test_cqt2010v2_plan_parts(sr, hop, fmin, n_bins, bpo, fir):
     info = p.info()
     n_taps = oracle.cqt2010_default_taps(sr, fmin, n_bins, bpo)
     assert info["kind"] == nb.NNA_KIND_CQT2010V2 and info["out_bins"] == n_bins and info["taps"] == n_taps
-    # the filter: 16 shifted copies of the window-method half-band design
+    # the filter: 64 shifted copies of the window-method half-band design
     h = oracle.lowpass_fir(fir or oracle.FIR_TAPS, 0.5)
     bank = nb.nna_plan_bank(nb.nna_plan_part(p, -1))
-    assert bank.shape[0] == 16
-    for r in range(16):
+    assert bank.shape[0] == 64
+    for r in range(64):
         want = np.zeros(bank.shape[1])
         want[2 * r:2 * r + h.size] = h
         np.testing.assert_allclose(bank[r], want, atol=3e-8)
