@@ -24,6 +24,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix peak
+PEAK_F16_MFMA_TFLOPS = 2500.0  # MI355X dense fp16 / bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
 
 
@@ -173,8 +174,10 @@ def main() -> int:
         p_2010 = nb.nna_plan_cqt2010v2(sr=sr, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24, device=0)
         o_lin = torch.empty((B, 1025, T), dtype=torch.float32, device=dev)
         ws = torch.empty(max(16, nb.nna_cqt2010v2_workspace(p_2010, B, L)), dtype=torch.uint8, device=dev)
+        p_h = nb.nna_plan_stft_prec(sr=sr, n_fft=2048, hop=512, precision=nb.NNA_PREC_F16, device=0)
         for name, fn, plan in (("stft_linear_axis", lambda: nb.nna_stft(p_lin, x4, o_lin), p_lin),
-                               ("cqt2010v2", lambda: nb.nna_cqt2010v2(p_2010, x5, o_cqt, workspace=ws), p_2010)):
+                               ("cqt2010v2", lambda: nb.nna_cqt2010v2(p_2010, x5, o_cqt, workspace=ws), p_2010),
+                               ("stft_f16_operands", lambda: nb.nna_stft(p_h, x4, o_lin), p_h)):
             for _ in range(max(1, args.warmup)):
                 fn()
             ev = []
@@ -192,7 +195,9 @@ def main() -> int:
                 "gsamples_per_s": round(B * L / ms / 1e6, 4),
                 "algorithmic_tflops": round(info["algorithmic_flops_per_frame"] * B * T / ms / 1e9, 3),
                 "executed_tflops": round(info["executed_flops_per_frame"] * B * T / ms / 1e9, 3),
-                "mfma_frac": round(info["algorithmic_flops_per_frame"] * B * T / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+                "mfma_frac": round(info["algorithmic_flops_per_frame"] * B * T / ms / 1e9
+                                   / (PEAK_F16_MFMA_TFLOPS if name == "stft_f16_operands" else PEAK_FP32_MFMA_TFLOPS), 4),
+                "mfma_peak_tflops": PEAK_F16_MFMA_TFLOPS if name == "stft_f16_operands" else PEAK_FP32_MFMA_TFLOPS,
             }
         del o_lin, ws
 

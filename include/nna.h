@@ -74,6 +74,11 @@ typedef enum {
   NNA_FREQ_LOG = 2     /* eq. (log-frequency-DFT): bins in geometric progression from fmin */
 } nna_freq_scale;
 
+typedef enum {
+  NNA_PREC_F32 = 0, /* float32 operands, float32 accumulation */
+  NNA_PREC_F16 = 1  /* bank and waveform rounded to float16 (to nearest even), float32 accumulation */
+} nna_precision;
+
 typedef enum { NNA_KIND_STFT = 0, NNA_KIND_MEL = 1, NNA_KIND_CQT = 2, NNA_KIND_CQT2010V2 = 3 } nna_kind;
 
 /*
@@ -86,6 +91,17 @@ typedef enum { NNA_KIND_STFT = 0, NNA_KIND_MEL = 1, NNA_KIND_CQT = 2, NNA_KIND_C
  */
 nna_status nna_plan_stft(nna_plan** plan, int sr, int n_fft, int hop, nna_window win, int center,
                          nna_output fmt, int device);
+
+/*
+ * nna_plan_stft with a choice of operand precision.  NNA_PREC_F16 runs the same contraction on
+ * the float16 matrix instructions (16 times the float32 rate): the bank is rounded to float16
+ * when the plan is built, the waveform when it is staged on chip; products are exact and sums
+ * are float32, so the result differs from the float32 plan's by about 1e-5 of the spectrogram's
+ * peak (bar: 1e-3).  It needs hop to divide n_fft at most 32 times and to be a multiple of 32
+ * (NNA_ERR_UNSUPPORTED otherwise).  nna_plan_bank returns the bank as rounded.
+ */
+nna_status nna_plan_stft_prec(nna_plan** plan, int sr, int n_fft, int hop, nna_window win, int center,
+                              nna_output fmt, nna_precision precision, int device);
 
 /*
  * STFT plan on a re-spaced frequency axis (Sec. II-B; the freq_scale / fmin / fmax /

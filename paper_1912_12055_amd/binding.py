@@ -20,11 +20,12 @@ NNA_OUT_MAGNITUDE, NNA_OUT_POWER, NNA_OUT_LOG = 0, 1, 2
 NNA_WIN_HANN, NNA_WIN_RECT = 0, 1
 NNA_MEL_SLANEY, NNA_MEL_HTK = 0, 1
 NNA_FREQ_LINEAR, NNA_FREQ_LOG = 1, 2
+NNA_PREC_F32, NNA_PREC_F16 = 0, 1
 NNA_KIND_STFT, NNA_KIND_MEL, NNA_KIND_CQT, NNA_KIND_CQT2010V2 = 0, 1, 2, 3
 
 # every symbol include/nna.h declares
 EXPORTS = [
-    "nna_plan_stft", "nna_plan_stft_scaled", "nna_plan_mel", "nna_plan_cqt", "nna_plan_cqt2010v2", "nna_out_shape", "nna_stft", "nna_mel", "nna_cqt",
+    "nna_plan_stft", "nna_plan_stft_prec", "nna_plan_stft_scaled", "nna_plan_mel", "nna_plan_cqt", "nna_plan_cqt2010v2", "nna_out_shape", "nna_stft", "nna_mel", "nna_cqt",
     "nna_plan_bank", "nna_plan_mel_weights", "nna_plan_info", "nna_plan_cqt_lengths", "nna_plan_sigma", "nna_cqt2010v2_workspace",
     "nna_cqt2010v2", "nna_plan_part",
     "nna_plan_destroy",
@@ -55,6 +56,8 @@ def lib():
         L = _c.CDLL(LIB_PATH)
         PP = _c.POINTER(_VP)
         L.nna_plan_stft.argtypes = [PP, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int]
+        L.nna_plan_stft_prec.argtypes = [PP, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
+                                         _c.c_int]
         L.nna_plan_stft_scaled.argtypes = [PP, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
                                            _c.c_double, _c.c_double, _c.c_int, _c.c_int]
         L.nna_plan_mel.argtypes = [PP, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_double,
@@ -131,6 +134,11 @@ def _new_plan(fn, args, device):
 def nna_plan_stft(sr=22050, n_fft=2048, hop=512, win=NNA_WIN_HANN, center=True, fmt=NNA_OUT_MAGNITUDE,
                   device=0) -> Plan:
     return _new_plan(lib().nna_plan_stft, (sr, n_fft, hop, win, int(center), fmt), device)
+
+
+def nna_plan_stft_prec(sr=22050, n_fft=2048, hop=512, win=NNA_WIN_HANN, center=True, fmt=NNA_OUT_MAGNITUDE,
+                       precision=NNA_PREC_F16, device=0) -> Plan:
+    return _new_plan(lib().nna_plan_stft_prec, (sr, n_fft, hop, win, int(center), fmt, precision), device)
 
 
 def nna_plan_stft_scaled(sr=22050, n_fft=2048, hop=512, win=NNA_WIN_HANN, center=True, fmt=NNA_OUT_MAGNITUDE,

@@ -23,6 +23,13 @@ constexpr int ST_NKG = ST_KC / ST_KG;
 constexpr int ST_LDS_ROWS = 160;  // LDS rows per buffer (frames + overlap rows)
 constexpr int ST_MEL_BLOCKS = 4;  // 32-mel MFMA blocks per pass (128 mels)
 
+// float16-operand STFT kernel: v_mfma_f32_32x32x16_f16, workgroup tile 256 bank rows x 192 frames.
+constexpr int H_ROWS = 256;
+constexpr int H_FRAMES = 192;
+constexpr int H_KC = 32;          // taps per LDS chunk (two MFMA K-steps of 16)
+constexpr int H_PITCH = 40;       // LDS row pitch in halves (80 bytes: conflict-free 16-byte reads)
+constexpr int H_LB_ROWS = 224;    // LDS rows of the frames tile (frames + overlap rows)
+
 // CQT kernel: v_mfma_f32_16x16x4_f32, workgroup tile 16 bank rows (8 bins) x 256 frames.
 constexpr int CQ_ROWS = 16;
 constexpr int CQ_FRAMES = 256;    // 4 waves x 4 blocks of 16 frames
@@ -66,6 +73,19 @@ struct StftParams {
   int n_mels;
   int n_pass;
   int mel_nyq_any;
+};
+
+struct Stft16Params {
+  FrameGeom g;
+  const _Float16* bank;  // [row tile][chunk][hop-shift][H_ROWS][H_KC] float16
+  float* out;
+  int n_rt;              // row tiles of H_ROWS packed rows
+  int n_chunks;          // LDS chunks per hop
+  int nj;                // hop-shifts (n_fft / hop)
+  int n_half, packed, out_bins, fmt;  // as in StftParams
+  int rt_per_block;      // row tiles one workgroup handles
+  int tile_frames;       // frames per tile (<= H_FRAMES)
+  long long n_ft;
 };
 
 constexpr int CQ_ITEM_RB = 4;  // row blocks one CQT workgroup can handle (short kernels are grouped)
@@ -113,6 +133,7 @@ struct CqtParams {
 
 hipError_t launch_stft(const StftParams& p, bool mel, hipStream_t stream);
 hipError_t launch_cqt(const CqtParams& p, hipStream_t stream);
+hipError_t launch_stft16(const Stft16Params& p, hipStream_t stream);
 hipError_t kernels_init();  // per-process function attributes
 
 }  // namespace nna

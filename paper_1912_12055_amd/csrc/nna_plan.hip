@@ -75,6 +75,12 @@ struct nna_plan {
 
   // device buffers
   float* d_bank = nullptr;
+  // float16-operand STFT: the bank as [row tile][chunk][hop-shift][H_ROWS][H_KC] halves
+  int precision = 0;
+  int n_rt16 = 0;
+  std::vector<_Float16> h_bank16;
+  size_t bank16_halves = 0;
+  _Float16* d_bank16 = nullptr;
   float* d_melw = nullptr;
   unsigned char* d_mel_mask = nullptr;
   float* d_mel_wnyq = nullptr;
@@ -234,6 +240,35 @@ void build_stft_bank(nna_plan* p) {
   p->exec_flops = 2.0 * k_exec * (double)p->n_rt * ST_ROWS;
   // plain DFT: N non-zero rows (cos 0..N/2, sin 1..N/2-1) x N taps; re-spaced: 2 rows per bin
   p->alg_flops = p->freq_scale ? 2.0 * (double)N * 2.0 * (double)p->n_half : 2.0 * (double)N * (double)N;
+}
+
+// float16 copy of the STFT bank for the half-precision kernel: same packed rows, cut into row
+// tiles of H_ROWS; each (row tile, chunk, hop-shift) tile of H_ROWS x H_KC halves is contiguous,
+// in the order the kernel walks them.  Needs the sliding layout.
+bool build_stft_bank_f16(nna_plan* p) {
+  using nna::H_KC;
+  using nna::H_ROWS;
+  const int N = p->K;
+  const int J = (p->hop > 0 && N % p->hop == 0) ? N / p->hop : 0;
+  if (!(J >= 1 && J <= 32 && p->hop % H_KC == 0)) return false;
+  const int n_chunks = p->hop / H_KC;
+  p->n_rt16 = (2 * p->n_half + H_ROWS - 1) / H_ROWS;
+  const size_t tiles = (size_t)p->n_rt16 * n_chunks * J;
+  p->bank16_halves = (tiles + 2) * H_ROWS * H_KC;  // + the two tiles the kernel requests past the end
+  p->h_bank16.assign(p->bank16_halves, (_Float16)0.0f);
+  DftTable tab(N, p->window);
+  for (int rt = 0; rt < p->n_rt16; ++rt)
+    for (int c = 0; c < n_chunks; ++c)
+      for (int j = 0; j < J; ++j) {
+        _Float16* tile = &p->h_bank16[(((size_t)rt * n_chunks + c) * J + j) * H_ROWS * H_KC];
+        for (int r = 0; r < H_ROWS; ++r)
+          for (int e = 0; e < H_KC; ++e) {
+            const int pr = rt * H_ROWS + r, tap = j * p->hop + c * H_KC + e;
+            const double v = p->freq_scale ? scaled_value(p, pr, tap) : stft_packed_value(tab, p->n_half, pr, tap);
+            tile[r * H_KC + e] = (_Float16)(float)v;
+          }
+      }
+  return true;
 }
 
 // ---- Mel filterbank (Sec. III-B) ------------------------------------------------------
@@ -549,6 +584,8 @@ nna_status finish_plan(nna_plan* p, nna_plan** out, const MelDeviceLayout* mel) 
       return fail_hip(g_init_err, "kernel attribute setup");
     }
     nna_status s = upload(&p->d_bank, p->h_bank.data(), p->bank_floats * sizeof(float), "kernel bank");
+    if (s == NNA_OK && p->precision == NNA_PREC_F16)
+      s = upload(&p->d_bank16, p->h_bank16.data(), p->bank16_halves * sizeof(_Float16), "float16 kernel bank");
     if (s == NNA_OK && mel) {
       s = upload(&p->d_melw, mel->frag.data(), mel->frag.size() * sizeof(float), "mel weights");
       if (s == NNA_OK) s = upload(&p->d_mel_mask, mel->mask.data(), mel->mask.size(), "mel mask");
@@ -566,6 +603,7 @@ nna_status finish_plan(nna_plan* p, nna_plan** out, const MelDeviceLayout* mel) 
       return s;
     }
     std::vector<float>().swap(p->h_bank);  // the device copy is the bank from here on
+    std::vector<_Float16>().swap(p->h_bank16);
   }
   *out = p;
   return NNA_OK;
@@ -640,6 +678,31 @@ nna_status run_stft_like(const nna_plan* plan, int kind, const float* x, long lo
   long long T = 0;
   nna_status s = check_call(plan, kind, x, B, L, out, &T);
   if (s != NNA_OK) return s;
+  if (plan->precision == NNA_PREC_F16) {
+    const int M = pick_tile_frames(nna::H_FRAMES, T, plan->nj - 1, nna::H_LB_ROWS);
+    if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
+    nna::Stft16Params P;
+    std::memset(&P, 0, sizeof(P));
+    P.g = make_geom(plan, x, B, L, T);
+    P.bank = plan->d_bank16;
+    P.out = out;
+    P.n_rt = plan->n_rt16;
+    P.n_chunks = plan->hop / nna::H_KC;
+    P.nj = plan->nj;
+    P.n_half = plan->n_half;
+    P.packed = plan->freq_scale ? 0 : 1;
+    P.out_bins = plan->stft_bins();
+    P.fmt = plan->fmt;
+    P.rt_per_block = plan->n_rt16;
+    P.tile_frames = M;
+    P.n_ft = (P.g.n_frames + M - 1) / M;
+    DeviceGuard guard;
+    hipError_t e = guard.enter(plan->device);
+    if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+    e = nna::launch_stft16(P, reinterpret_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    return NNA_OK;
+  }
   const int M = pick_tile_frames(ST_FRAMES, T, plan->nj - 1, ST_LDS_ROWS);
   if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
   nna::StftParams P;
@@ -877,6 +940,45 @@ nna_status nna_plan_stft(nna_plan** plan, int sr, int n_fft, int hop, nna_window
     p->K = n_fft;
     p->pad = center ? n_fft / 2 : 0;
     build_stft_bank(p);
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return fail(NNA_ERR_ALLOC, "out of host memory while building the DFT bank");
+  }
+  return finish_plan(p, plan, nullptr);
+}
+
+nna_status nna_plan_stft_prec(nna_plan** plan, int sr, int n_fft, int hop, nna_window win, int center, nna_output fmt,
+                              nna_precision precision, int device) {
+  if (precision == NNA_PREC_F32) return nna_plan_stft(plan, sr, n_fft, hop, win, center, fmt, device);
+  if (precision != NNA_PREC_F16) {
+    if (plan) *plan = nullptr;
+    return fail(NNA_ERR_INVALID_ARG, "unknown precision");
+  }
+  nna_status s = check_common(plan, sr, hop, win, center, device);
+  if (s != NNA_OK) return s;
+  if ((s = check_stft_args(n_fft)) != NNA_OK) return s;
+  if (fmt != NNA_OUT_MAGNITUDE && fmt != NNA_OUT_POWER && fmt != NNA_OUT_LOG)
+    return fail(NNA_ERR_INVALID_ARG, "unknown output format");
+  nna_plan* p = new (std::nothrow) nna_plan;
+  if (!p) return fail(NNA_ERR_ALLOC, "out of host memory");
+  try {
+    p->kind = NNA_KIND_STFT;
+    p->device = device;
+    p->sr = sr;
+    p->hop = hop;
+    p->center = center;
+    p->window = win;
+    p->fmt = fmt;
+    p->K = n_fft;
+    p->pad = center ? n_fft / 2 : 0;
+    p->precision = NNA_PREC_F16;
+    build_stft_bank(p);
+    if (!build_stft_bank_f16(p)) {
+      delete p;
+      return fail(NNA_ERR_UNSUPPORTED,
+                  "the float16 kernel needs hop to divide n_fft (at most 32 times) and to be a multiple of 32");
+    }
+    p->exec_flops = 2.0 * (double)n_fft * (double)p->n_rt16 * nna::H_ROWS;
   } catch (const std::bad_alloc&) {
     delete p;
     return fail(NNA_ERR_ALLOC, "out of host memory while building the DFT bank");
@@ -1146,6 +1248,38 @@ nna_status nna_plan_bank(const nna_plan* plan, double* host_out, size_t cap) {
   const long long rows = plan->kind == NNA_KIND_CQT ? (long long)plan->conv_rows : 2LL * (plan->freq_scale ? plan->n_half : plan->n_half + 1);
   const long long K = plan->K;
   if ((unsigned long long)cap < (unsigned long long)(rows * K)) return fail(NNA_ERR_INVALID_ARG, "host_out is too small");
+  if (plan->precision == NNA_PREC_F16) {
+    // the float16 bank, un-permuted from [row tile][chunk][hop-shift][H_ROWS][H_KC]
+    std::vector<_Float16> tmp16;
+    const _Float16* src16 = nullptr;
+    try {
+      if (plan->device >= 0) {
+        tmp16.resize(plan->bank16_halves);
+        DeviceGuard guard;
+        hipError_t e = guard.enter(plan->device);
+        if (e == hipSuccess) e = hipMemcpy(tmp16.data(), plan->d_bank16, plan->bank16_halves * sizeof(_Float16), hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return fail_hip(e, "bank read-back");
+        src16 = tmp16.data();
+      } else {
+        src16 = plan->h_bank16.data();
+      }
+    } catch (const std::bad_alloc&) {
+      return fail(NNA_ERR_ALLOC, "out of host memory");
+    }
+    std::fill(host_out, host_out + rows * K, 0.0);
+    const int n_chunks = plan->hop / nna::H_KC, J = plan->nj;
+    for (int rt = 0; rt < plan->n_rt16; ++rt)
+      for (int c = 0; c < n_chunks; ++c)
+        for (int j = 0; j < J; ++j)
+          for (int r = 0; r < nna::H_ROWS; ++r) {
+            const int pr = rt * nna::H_ROWS + r, slot = pr >> 1, part = pr & 1;
+            if (slot >= plan->n_half) continue;
+            const long long row = slot == 0 && !plan->freq_scale ? (part == 0 ? 0 : 2LL * plan->n_half) : 2LL * slot + part;
+            const _Float16* t = src16 + ((((size_t)rt * n_chunks + c) * J + j) * nna::H_ROWS + r) * nna::H_KC;
+            for (int e = 0; e < nna::H_KC; ++e) host_out[row * K + (long long)j * plan->hop + c * nna::H_KC + e] = (double)(float)t[e];
+          }
+    return NNA_OK;
+  }
   std::vector<float> tmp;
   const float* src = nullptr;
   try {
@@ -1285,6 +1419,7 @@ void nna_plan_destroy(nna_plan* plan) {
     DeviceGuard guard;
     if (guard.enter(plan->device) == hipSuccess) {
       (void)hipFree(plan->d_bank);
+      (void)hipFree(plan->d_bank16);
       (void)hipFree(plan->d_melw);
       (void)hipFree(plan->d_mel_mask);
       (void)hipFree(plan->d_mel_wnyq);

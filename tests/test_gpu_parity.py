@@ -290,6 +290,46 @@ def test_cqt_tone_closed_form_on_gpu(nb):
 
 
 # ---------------------------------------------------------------------------------------
+# STFT with float16 operands (float32 accumulation): same bar, 1e-3 of the peak
+# ---------------------------------------------------------------------------------------
+STFT16_CASES = [
+    # name, B, L, n_fft, hop, window, center, fmt
+    ("one tile, one waveform", 1, 8000, 256, 64, 0, True, 0),
+    ("several tiles, ragged tail, tiles span waveforms", 5, 30000, 256, 64, 0, True, 0),
+    ("many short waveforms per tile, power", 37, 700, 256, 64, 0, True, 1),
+    ("single-frame waveforms (T=1)", 9, 40, 64, 64, 0, True, 0),
+    ("hop = n_fft / 2, rect window, no centring", 2, 9000, 512, 256, 1, False, 1),
+    ("L not a multiple of 4 (unaligned rows), log", 3, 22050, 512, 128, 0, True, 2),
+    ("row tiles: 1,025 bins", 2, 12000, 2048, 512, 0, True, 0),
+    ("32 hop-shifts", 2, 9000, 1024, 32, 0, True, 0),
+]
+
+
+@pytest.mark.parametrize("case", STFT16_CASES, ids=[c[0] for c in STFT16_CASES])
+def test_stft_f16_parity_small(nb, case):
+    name, B, L, n_fft, hop, win, center, fmt = case
+    _say(f"stft f16 {name}: B={B} L={L} n_fft={n_fft} hop={hop} win={win} center={center} fmt={fmt}")
+    x = _rand(B, L, 1600 + n_fft + hop)
+    plan = nb.nna_plan_stft_prec(n_fft=n_fft, hop=hop, win=win, center=center, fmt=fmt, precision=nb.NNA_PREC_F16,
+                                 device=0)
+    got = nb.nna_stft(plan, _dev(x)).cpu().numpy()
+    ref = oracle.stft(x, n_fft=n_fft, hop=hop, window=win, center=center, fmt=fmt)
+    if fmt == 2:
+        # ln amplifies the error of small powers without bound: compare the magnitudes it encodes
+        got, ref = np.exp(0.5 * got.astype(np.float64)), np.exp(0.5 * ref)
+    e = _rel_err(got, ref)
+    _say(f"  rel err {e:.3e}")
+    assert e < TOL
+
+
+def test_stft_f16_unsupported_shapes(nb):
+    for n_fft, hop in ((96, 25), (240, 48), (2048, 16)):
+        with pytest.raises(nb.NnaError) as e:
+            nb.nna_plan_stft_prec(n_fft=n_fft, hop=hop, precision=nb.NNA_PREC_F16, device=0)
+        assert e.value.status == nb.NNA_ERR_UNSUPPORTED
+
+
+# ---------------------------------------------------------------------------------------
 # CQT by recursive downsampling
 # ---------------------------------------------------------------------------------------
 CQT2010_CASES = [
@@ -449,3 +489,18 @@ def test_cqt2010v2_config5_full_sampled(nb):
     _say(f"  rel err {e:.3e}")
     assert e < TOL
     assert torch.isfinite(out).all() and (out >= 0).all()
+
+
+def test_stft_f16_config4_full_sampled(nb, batch4):
+    import torch
+    _say("stft f16 config 4 (1770 x 176400 @ 44100 Hz) sampled waveforms")
+    plan = nb.nna_plan_stft_prec(sr=44100, n_fft=2048, hop=512, precision=nb.NNA_PREC_F16, device=0)
+    out = nb.nna_stft(plan, batch4)
+    torch.cuda.synchronize()
+    assert tuple(out.shape) == (1770, 1025, 345)
+    xs = signals.batch(4, SAMPLED)
+    ref = oracle.stft(xs, n_fft=2048, hop=512)
+    e = _rel_err(out[SAMPLED].cpu().numpy(), ref)
+    _say(f"  rel err {e:.3e}")
+    assert e < TOL
+    assert torch.isfinite(out).all()
