@@ -20,6 +20,8 @@
 // spectrogram's peak (the parity bar is 1e-3).
 #include "nna_device.h"
 
+#include <type_traits>
+
 namespace nna {
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -50,6 +52,11 @@ __device__ __forceinline__ void store_chunk_f16(const f32x4 (&R)[NPASS], const T
   }
 }
 
+// NJ = hop-shifts per chunk (n_fft / hop) when it is one the kernel is specialised for, else 0:
+// with NJ known the steps of a chunk are unrolled into one loop body, which keeps the
+// accumulators in place (with a run-time step loop the compiler peels the steps that load or
+// store the B tile and shuffles all accumulators between the copies).
+template <int NJ>
 __global__ __launch_bounds__(256, 1) void stft16_kernel(const Stft16Params P) {
   __shared__ __attribute__((aligned(16))) _Float16 ldsA[2][H_ROWS * H_PITCH];
   __shared__ __attribute__((aligned(16))) _Float16 ldsB[2][H_LB_ROWS * H_PITCH];
@@ -101,15 +108,7 @@ __global__ __launch_bounds__(256, 1) void stft16_kernel(const Stft16Params P) {
 
   const int nj = P.nj, n_chunks = P.n_chunks;
   const int steps_per_rt = n_chunks * nj;
-  const int total = (rt_end - rt_begin) * steps_per_rt;
-
-  f32x16 acc[H_JT][4];  // [frame sub-tile][row sub-tile]
-#pragma unroll
-  for (int jt = 0; jt < H_JT; ++jt)
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[jt][i][r] = 0.f;
+  if (rt_end <= rt_begin) return;
 
   // bank tiles of this row group are consecutive in memory: [row tile][chunk][shift][256 rows][32 taps]
   const _Float16* a_src = P.bank + ((long long)rt_begin * steps_per_rt) * (H_ROWS * H_KC) + tid * H_KC;
@@ -136,80 +135,93 @@ __global__ __launch_bounds__(256, 1) void stft16_kernel(const Stft16Params P) {
   }
   __syncthreads();
 
-  int j = 0, c = 0, rt = rt_begin, cc = 0;  // hop-shift, chunk of the row tile, row tile, chunks done
-  bool b_pending = false;
-  for (int s = 0; s < total; ++s) {
-    // the A tile requested one step ago (for step s+1) is taken over; the one for step s+2 is requested
+  int s = 0, cc = 0;  // steps and chunks done so far (they select the LDS buffers)
+  for (int rt = rt_begin; rt < rt_end; ++rt) {
+    f32x16 acc[H_JT][4];  // [frame sub-tile][row sub-tile]
 #pragma unroll
-    for (int q = 0; q < 4; ++q) pa[q] = ga[q];
+    for (int jt = 0; jt < H_JT; ++jt)
 #pragma unroll
-    for (int q = 0; q < 4; ++q) ga[q] = *reinterpret_cast<const f32x4*>(a_src + q * 8);
-    a_src += H_ROWS * H_KC;
-    // first step of a chunk: request the B tile of the next chunk (the bank tail is padded, and
-    // the chunk after the last wraps to column 0: always in bounds)
-    if (j == 0) {
-      const float* ptr[H_NPASS];
-      prepare_chunk<H_NPASS>(ptr, fxB, g, rd, ((c + 1) % n_chunks) * H_KC);
+      for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int p = 0; p < H_NPASS; ++p) gB[p] = *reinterpret_cast<const f32x4_u*>(ptr[p]);
-      b_pending = true;
-    }
+        for (int r = 0; r < 16; ++r) acc[jt][i][r] = 0.f;
 
-    // ---- 24 MFMAs: two 16-tap halves of the chunk x 3 x 4 tiles ----
-    const _Float16* A = &ldsA[s & 1][0] + a_off;
-    const _Float16* Bt = &ldsB[cc & 1][0] + j * H_PITCH;
+    // one step: hop-shift j of chunk c.  B_LOAD: request the B tile of the next chunk (first step of
+    // a chunk); B_STORE: write it to the other B buffer (one step later when there is one).
+    auto step = [&](auto load_tag, auto store_tag, int c, int j) {
+      constexpr bool B_LOAD = decltype(load_tag)::value;
+      constexpr bool B_STORE = decltype(store_tag)::value;
+      // the A tile requested one step ago (for step s+1) is taken over; the one for step s+2 is requested
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      f16x8 af[4], bf[H_JT];
+      for (int q = 0; q < 4; ++q) pa[q] = ga[q];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const f16x8*>(A + i * 32 * H_PITCH + ks * 16);
+      for (int q = 0; q < 4; ++q) ga[q] = *reinterpret_cast<const f32x4*>(a_src + q * 8);
+      a_src += H_ROWS * H_KC;
+      if (B_LOAD) {
+        // (the bank tail is padded, and the chunk after the last wraps to column 0: always in bounds)
+        const float* ptr[H_NPASS];
+        prepare_chunk<H_NPASS>(ptr, fxB, g, rd, ((c + 1) % n_chunks) * H_KC);
 #pragma unroll
-      for (int jt = 0; jt < H_JT; ++jt) bf[jt] = *reinterpret_cast<const f16x8*>(Bt + b_off[jt] + ks * 16);
-#pragma unroll
-      for (int jt = 0; jt < H_JT; ++jt)
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          acc[jt][i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[jt], acc[jt][i], 0, 0, 0);
-    }
+        for (int p = 0; p < H_NPASS; ++p) gB[p] = *reinterpret_cast<const f32x4_u*>(ptr[p]);
+      }
 
-    // ---- stage: A tile of step s+1; the B tile of the next chunk one step after it was requested ----
-    {
-      _Float16* a_dst = a_dst0 + ((s + 1) & 1) * (H_ROWS * H_PITCH);
+      // ---- 24 MFMAs: two 16-tap halves of the chunk x 3 x 4 tiles ----
+      const _Float16* A = &ldsA[s & 1][0] + a_off;
+      const _Float16* Bt = &ldsB[cc & 1][0] + j * H_PITCH;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) *reinterpret_cast<f32x4*>(a_dst + q * 8) = pa[q];
-    }
-    if (b_pending && (j == 1 || nj == 1)) {
-      store_chunk_f16<H_NPASS>(gB, fxB, ldsB[(cc + 1) & 1], tid);
-      b_pending = false;
-    }
-
-    if (++j == nj) {
-      j = 0;
-      ++cc;
-      if (++c == n_chunks) {
-        // ---- epilogue of row tile rt ----
-        c = 0;
-        const int slot_base = rt * (H_ROWS / 2) + wr * 64;
+      for (int ks = 0; ks < 2; ++ks) {
+        f16x8 af[4], bf[H_JT];
 #pragma unroll
-        for (int jt = 0; jt < H_JT; ++jt) {
-          if (valid[jt]) {
-            float* __restrict__ op = P.out + o_off[jt];
-            if (P.fmt == NNA_OUT_MAGNITUDE)
-              stft_store_tile<NNA_OUT_MAGNITUDE>(acc[jt], op, g.T, slot_base, h, P.n_half, P.packed);
-            else if (P.fmt == NNA_OUT_POWER)
-              stft_store_tile<NNA_OUT_POWER>(acc[jt], op, g.T, slot_base, h, P.n_half, P.packed);
-            else
-              stft_store_tile<NNA_OUT_LOG>(acc[jt], op, g.T, slot_base, h, P.n_half, P.packed);
-          }
+        for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const f16x8*>(A + i * 32 * H_PITCH + ks * 16);
+#pragma unroll
+        for (int jt = 0; jt < H_JT; ++jt) bf[jt] = *reinterpret_cast<const f16x8*>(Bt + b_off[jt] + ks * 16);
+#pragma unroll
+        for (int jt = 0; jt < H_JT; ++jt)
 #pragma unroll
           for (int i = 0; i < 4; ++i)
+            acc[jt][i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[jt], acc[jt][i], 0, 0, 0);
+      }
+
+      // ---- stage the A tile of step s+1 (and the B tile) ----
+      {
+        _Float16* a_dst = a_dst0 + ((s + 1) & 1) * (H_ROWS * H_PITCH);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[jt][i][r] = 0.f;
-        }
-        ++rt;
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<f32x4*>(a_dst + q * 8) = pa[q];
+      }
+      if (B_STORE) store_chunk_f16<H_NPASS>(gB, fxB, ldsB[(cc + 1) & 1], tid);
+      __syncthreads();
+      ++s;
+    };
+    using Yes = std::true_type;
+    using No = std::false_type;
+    for (int c = 0; c < n_chunks; ++c, ++cc) {
+      if constexpr (NJ == 1) {
+        step(Yes{}, Yes{}, c, 0);
+      } else if constexpr (NJ >= 2) {
+        step(Yes{}, No{}, c, 0);
+        step(No{}, Yes{}, c, 1);
+#pragma unroll
+        for (int j = 2; j < NJ; ++j) step(No{}, No{}, c, j);
+      } else {
+        step(Yes{}, No{}, c, 0);
+        step(No{}, Yes{}, c, 1);
+        for (int j = 2; j < nj; ++j) step(No{}, No{}, c, j);
       }
     }
-    __syncthreads();
+
+    // ---- epilogue of row tile rt ----
+    const int slot_base = rt * (H_ROWS / 2) + wr * 64;
+#pragma unroll
+    for (int jt = 0; jt < H_JT; ++jt) {
+      if (valid[jt]) {
+        float* __restrict__ op = P.out + o_off[jt];
+        if (P.fmt == NNA_OUT_MAGNITUDE)
+          stft_store_tile<NNA_OUT_MAGNITUDE>(acc[jt], op, g.T, slot_base, h, P.n_half, P.packed);
+        else if (P.fmt == NNA_OUT_POWER)
+          stft_store_tile<NNA_OUT_POWER>(acc[jt], op, g.T, slot_base, h, P.n_half, P.packed);
+        else
+          stft_store_tile<NNA_OUT_LOG>(acc[jt], op, g.T, slot_base, h, P.n_half, P.packed);
+      }
+    }
   }
 }
 
@@ -218,7 +230,13 @@ hipError_t launch_stft16(const Stft16Params& p, hipStream_t stream) {
   const long long blocks = p.n_ft * n_rg;
   if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   if (p.tile_frames > H_FRAMES || p.nj < 1) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(stft16_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  switch (p.nj) {
+    case 1: hipLaunchKernelGGL(stft16_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, stream, p); break;
+    case 2: hipLaunchKernelGGL(stft16_kernel<2>, dim3((unsigned)blocks), dim3(256), 0, stream, p); break;
+    case 4: hipLaunchKernelGGL(stft16_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, stream, p); break;
+    case 8: hipLaunchKernelGGL(stft16_kernel<8>, dim3((unsigned)blocks), dim3(256), 0, stream, p); break;
+    default: hipLaunchKernelGGL(stft16_kernel<0>, dim3((unsigned)blocks), dim3(256), 0, stream, p); break;
+  }
   return hipGetLastError();
 }
 
