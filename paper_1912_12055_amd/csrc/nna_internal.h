@@ -78,6 +78,7 @@ struct StftParams {
 struct Stft16Params {
   FrameGeom g;
   const _Float16* bank;  // [row tile][chunk][hop-shift][H_ROWS][H_KC] float16
+  const _Float16* bank_s;  // the same bank in MFMA-fragment streaming order, or NULL (see stft16s_kernel)
   float* out;
   int n_rt;              // row tiles of H_ROWS packed rows
   int n_chunks;          // LDS chunks per hop

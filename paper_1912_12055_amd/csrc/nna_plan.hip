@@ -81,6 +81,11 @@ struct nna_plan {
   std::vector<_Float16> h_bank16;
   size_t bank16_halves = 0;
   _Float16* d_bank16 = nullptr;
+  // the same values in the order a wave of the streamed-bank kernel consumes them:
+  // [row tile][chunk][hop-shift][K-step][row half][fragment][64 lanes][8 halves]
+  std::vector<_Float16> h_bank16s;
+  size_t bank16s_halves = 0;
+  _Float16* d_bank16s = nullptr;
   float* d_melw = nullptr;
   unsigned char* d_mel_mask = nullptr;
   float* d_mel_wnyq = nullptr;
@@ -268,6 +273,24 @@ bool build_stft_bank_f16(nna_plan* p) {
             tile[r * H_KC + e] = (_Float16)(float)v;
           }
       }
+  if (J == 2 || J == 4 || J == 8) {
+    // streaming order: lane (n = lane % 32, h = lane / 32) of fragment i in row half wr holds row
+    // wr*128 + i*32 + n of the tile, taps ks*16 + 8h .. + 8 of the chunk
+    const size_t ksteps = tiles * 2;
+    p->bank16s_halves = (ksteps + 4) * (size_t)H_ROWS * 16;  // + the ring's requests past the end
+    p->h_bank16s.assign(p->bank16s_halves, (_Float16)0.0f);
+    for (size_t t = 0; t < tiles; ++t) {
+      const _Float16* tile = &p->h_bank16[t * H_ROWS * H_KC];
+      for (int ks = 0; ks < 2; ++ks)
+        for (int wr = 0; wr < 2; ++wr)
+          for (int i = 0; i < 4; ++i)
+            for (int lane = 0; lane < 64; ++lane) {
+              const int n = lane & 31, h = lane >> 5, row = wr * 128 + i * 32 + n;
+              _Float16* dst = &p->h_bank16s[((((t * 2 + ks) * 2 + wr) * 4 + i) * 64 + lane) * 8];
+              for (int e = 0; e < 8; ++e) dst[e] = tile[row * H_KC + ks * 16 + 8 * h + e];
+            }
+    }
+  }
   return true;
 }
 
@@ -586,6 +609,8 @@ nna_status finish_plan(nna_plan* p, nna_plan** out, const MelDeviceLayout* mel) 
     nna_status s = upload(&p->d_bank, p->h_bank.data(), p->bank_floats * sizeof(float), "kernel bank");
     if (s == NNA_OK && p->precision == NNA_PREC_F16)
       s = upload(&p->d_bank16, p->h_bank16.data(), p->bank16_halves * sizeof(_Float16), "float16 kernel bank");
+    if (s == NNA_OK && p->precision == NNA_PREC_F16 && p->bank16s_halves)
+      s = upload(&p->d_bank16s, p->h_bank16s.data(), p->bank16s_halves * sizeof(_Float16), "float16 kernel bank (streaming order)");
     if (s == NNA_OK && mel) {
       s = upload(&p->d_melw, mel->frag.data(), mel->frag.size() * sizeof(float), "mel weights");
       if (s == NNA_OK) s = upload(&p->d_mel_mask, mel->mask.data(), mel->mask.size(), "mel mask");
@@ -604,6 +629,7 @@ nna_status finish_plan(nna_plan* p, nna_plan** out, const MelDeviceLayout* mel) 
     }
     std::vector<float>().swap(p->h_bank);  // the device copy is the bank from here on
     std::vector<_Float16>().swap(p->h_bank16);
+    std::vector<_Float16>().swap(p->h_bank16s);
   }
   *out = p;
   return NNA_OK;
@@ -685,6 +711,7 @@ nna_status run_stft_like(const nna_plan* plan, int kind, const float* x, long lo
     std::memset(&P, 0, sizeof(P));
     P.g = make_geom(plan, x, B, L, T);
     P.bank = plan->d_bank16;
+    P.bank_s = plan->d_bank16s;
     P.out = out;
     P.n_rt = plan->n_rt16;
     P.n_chunks = plan->hop / nna::H_KC;
@@ -1420,6 +1447,7 @@ void nna_plan_destroy(nna_plan* plan) {
     if (guard.enter(plan->device) == hipSuccess) {
       (void)hipFree(plan->d_bank);
       (void)hipFree(plan->d_bank16);
+      (void)hipFree(plan->d_bank16s);
       (void)hipFree(plan->d_melw);
       (void)hipFree(plan->d_mel_mask);
       (void)hipFree(plan->d_mel_wnyq);

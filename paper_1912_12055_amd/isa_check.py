@@ -130,15 +130,21 @@ def check_kernel(lines) -> list:
     return sorted(bad.items())
 
 
+KERNEL_SOURCES = ("nna_kernels.hip", "nna_kernels_f16.hip")
+
+
 def compile_to_asm(extra_flags=()) -> str:
+    """Device assembly of every kernel source file, concatenated."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     flags = [f for f in _build.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    text = []
     with tempfile.TemporaryDirectory() as d:
-        out = os.path.join(d, "kernels.s")
-        cmd = [hipcc, *flags, *extra_flags, "-S", "--cuda-device-only", "-o", out,
-               os.path.join(_build.CSRC, "nna_kernels.hip")]
-        subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
-        return open(out).read()
+        for src in KERNEL_SOURCES:
+            out = os.path.join(d, src + ".s")
+            cmd = [hipcc, *flags, *extra_flags, "-S", "--cuda-device-only", "-o", out, os.path.join(_build.CSRC, src)]
+            subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+            text.append(open(out).read())
+    return "\n".join(text)
 
 
 def check_all(asm_text: str) -> dict:

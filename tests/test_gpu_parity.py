@@ -302,6 +302,7 @@ STFT16_CASES = [
     ("L not a multiple of 4 (unaligned rows), log", 3, 22050, 512, 128, 0, True, 2),
     ("row tiles: 1,025 bins", 2, 12000, 2048, 512, 0, True, 0),
     ("32 hop-shifts", 2, 9000, 1024, 32, 0, True, 0),
+    ("8 hop-shifts, three row tiles", 4, 20000, 768, 96, 0, True, 0),
 ]
 
 
