@@ -230,7 +230,8 @@ __global__ __launch_bounds__(256, 1) void stft16_kernel(const Stft16Params P) {
 //
 // Measured on the kernel above: with one wave per SIMD nothing hides the latency of the LDS
 // reads, and every 24 MFMAs end in a barrier -- the matrix pipe was busy 35 % of the time while
-// the LDS was active 19 %.  Here only the frames go through LDS.  Each wave streams its own bank
+// the LDS was active 19 %.  (Past about half-busy matrix pipes the chip is power-limited on this
+// kernel: the shader clock falls from 2.4 to 1.65-1.8 GHz and throughput stays near 0.9 PFLOP/s.)  Here only the frames go through LDS.  Each wave streams its own bank
 // fragments straight from the L2 into a ring of registers, four K-steps (16 taps each) ahead,
 // with the same hand-scheduled loads as the float32 kernels: the bank is stored in the order
 // [row tile][chunk][hop-shift][K-step][row half][4 fragments][64 lanes] x 16 bytes, so a wave
@@ -347,15 +348,20 @@ __global__ __launch_bounds__(256, 1) void stft16s_kernel(const Stft16Params P) {
       const _Float16* Bt = &ldsB[it & 1][0];
       __builtin_amdgcn_sched_barrier(0);
 
+      f16x8 bf[H_JT];  // frames fragments of the K-step about to run
+#pragma unroll
+      for (int jt = 0; jt < H_JT; ++jt) bf[jt] = *reinterpret_cast<const f16x8*>(Bt + b_off[jt]);
       // one K-step: 16 taps, 12 MFMAs (3 frame sub-tiles x 4 row sub-tiles)
       auto kstep = [&](auto task_tag, auto g_tag) {
         constexpr int TASK = decltype(task_tag)::value;
         constexpr int G = decltype(g_tag)::value;
-        constexpr int sl = G % HS_RING, j = G / 2, ks = G % 2;
-        f16x8 bf[H_JT];
+        constexpr int sl = G % HS_RING;
+        // the frames fragments of the next K-step are read from LDS while this one's MFMAs run
+        constexpr int G1 = G + 1 < KSTEPS ? G + 1 : G;
+        f16x8 bf_nxt[H_JT];
 #pragma unroll
         for (int jt = 0; jt < H_JT; ++jt)
-          bf[jt] = *reinterpret_cast<const f16x8*>(Bt + b_off[jt] + j * H_PITCH + ks * 16);
+          bf_nxt[jt] = *reinterpret_cast<const f16x8*>(Bt + b_off[jt] + (G1 / 2) * H_PITCH + (G1 % 2) * 16);
         wait_vm<W_SLOT>(bq[sl][0], bq[sl][1], bq[sl][2], bq[sl][3]);
         __builtin_amdgcn_sched_group_barrier(0x100, H_JT, 0);  // the LDS reads go first
         __builtin_amdgcn_sched_barrier(0);
@@ -389,6 +395,8 @@ __global__ __launch_bounds__(256, 1) void stft16s_kernel(const Stft16Params P) {
           }
         }
         bank_s += KSTEP_BYTES;
+#pragma unroll
+        for (int jt = 0; jt < H_JT; ++jt) bf[jt] = bf_nxt[jt];
       };
       kstep(std::integral_constant<int, TASK_STORE>{}, std::integral_constant<int, 0>{});
       kstep(std::integral_constant<int, TASK_LOAD>{}, std::integral_constant<int, 1>{});
