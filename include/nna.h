@@ -79,7 +79,13 @@ typedef enum {
   NNA_PREC_F16 = 1  /* bank and waveform rounded to float16 (to nearest even), float32 accumulation */
 } nna_precision;
 
-typedef enum { NNA_KIND_STFT = 0, NNA_KIND_MEL = 1, NNA_KIND_CQT = 2, NNA_KIND_CQT2010V2 = 3 } nna_kind;
+typedef enum {
+  NNA_KIND_STFT = 0,
+  NNA_KIND_MEL = 1,
+  NNA_KIND_CQT = 2,
+  NNA_KIND_CQT2010V2 = 3,
+  NNA_KIND_CQT1992 = 4
+} nna_kind;
 
 /*
  * STFT plan (Sec. III-A; defaults of the paper's STFT layer: n_fft 2048, hop 512,
@@ -162,6 +168,25 @@ nna_status nna_plan_cqt(nna_plan** plan, int sr, int hop, double fmin, int n_bin
 nna_status nna_plan_cqt2010v2(nna_plan** plan, int sr, int hop, double fmin, int n_bins, int bins_per_octave,
                               nna_window win, int n_taps, int fir_taps, nna_output fmt, int device);
 
+/*
+ * Constant-Q plan with frequency-domain kernels (Sec. III-C "CQT using neural networks",
+ * eqs. (Parseval), (CQT1992), Fig. 5; the paper's CQT1992 layer).  Two stages, run in one kernel:
+ *   1. the un-windowed STFT X_t[k], k = 0..n_fft/2, of the waveform (the DFT bank of nna_plan_stft
+ *      with a rectangular window; the constant-Q window lives in the kernels);
+ *   2. X_cq[q, t] = (1/n_fft) sum_{k=0}^{n_fft/2} X_t[k] Y[q, k], followed by the output format.
+ * Y[q, .] is the kernel of bin q -- that of nna_plan_cqt, centred in n_fft taps -- taken to the
+ * frequency domain: Y[q, k] = conj(DFT(conj(kernel_q))[k]), the reading under which eq. (CQT1992)'s
+ * two sides agree when k runs over all n_fft bins.  Only the half k <= n_fft/2 is kept, as in the
+ * paper, so the result approximates nna_cqt's (to about 1e-4 of the peak for 12 bins per octave well
+ * below the Nyquist frequency, a few 1e-3 for 6 bins per octave reaching 0.8 of it); no
+ * sparsity threshold is applied to Y.  Cost per frame is that of an STFT with n_fft taps, for every
+ * 64 constant-Q bins: the paper itself calls this form inefficient and offers it for research.
+ *   n_fft  0 = the smallest power of two >= the longest kernel; else a power of two >= it, <= 65536
+ * Output bins = n_bins; frames as for nna_plan_cqt with n_taps = n_fft.
+ */
+nna_status nna_plan_cqt1992(nna_plan** plan, int sr, int hop, double fmin, int n_bins, int bins_per_octave,
+                            nna_window win, int center, int n_fft, nna_output fmt, int device);
+
 /* Output shape [B, *n_bins, *n_frames] for a batch of B waveforms of L samples.
  * NNA_ERR_SHAPE if L is too short (center: L <= pad; otherwise L < K) or B < 1. */
 nna_status nna_out_shape(const nna_plan* plan, long long B, long long L, long long* n_bins,
@@ -180,6 +205,11 @@ nna_status nna_mel(const nna_plan* plan, const float* x_dev, long long B, long l
 /* out_dev[B, n_bins, T] = constant-Q spectrogram of x_dev[B, L]; plan from nna_plan_cqt. */
 nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
                    void* hip_stream);
+
+/* out_dev[B, n_bins, T] = constant-Q spectrogram of x_dev[B, L]; plan from nna_plan_cqt1992.
+ * The STFT itself is never written to memory. */
+nna_status nna_cqt1992(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
+                       void* hip_stream);
 
 /* Bytes of device workspace nna_cqt2010v2 needs for a batch [B, L]: the downsampled waveforms
  * of two consecutive octaves (about 3/4 of the input's size; 0 for a single octave). */
@@ -213,17 +243,24 @@ nna_status nna_plan_bank(const nna_plan* plan, double* host_out, size_t cap);
 /* Mel plans only: the filterbank W[n_mels, n_fft/2+1] as the GPU holds it. */
 nna_status nna_plan_mel_weights(const nna_plan* plan, double* host_out, size_t cap);
 
+/* Plans from nna_plan_cqt1992 only: the spectral kernels as the GPU holds them (float32 widened to
+ * double, the factor 1/n_fft included), host_out[2 n_bins, n_fft/2+1] with row 2q = Re Y[q, .]/n_fft
+ * and row 2q+1 = Im Y[q, .]/n_fft.  nna_plan_bank returns the plan's DFT bank, nna_plan_cqt_lengths
+ * its kernel lengths. */
+nna_status nna_plan_spectral_kernels(const nna_plan* plan, double* host_out, size_t cap);
+
 /*
  * Plan facts, each written if its pointer is non-NULL: kind, logical bank rows, taps K,
  * output bins, flops the kernels execute per frame (multiply-add = 2, zero-padded
  * taps they do not skip included) and algorithmic flops per frame (non-zero taps only:
- * 2*K*rows_nonzero for the DFT bank, 4*sum_k N_k for the CQT, plus 2*nnz(W) for Mel).
+ * 2*K*rows_nonzero for the DFT bank, 4*sum_k N_k for the CQT, plus 2*nnz(W) for Mel;
+ * nna_plan_cqt1992: the DFT plus 8 per (constant-Q bin, kept DFT bin)).
  */
 nna_status nna_plan_info(const nna_plan* plan, int* kind, long long* bank_rows, long long* taps,
                          long long* out_bins, double* executed_flops_per_frame,
                          double* algorithmic_flops_per_frame);
 
-/* CQT plans only: kernel lengths N_k, k = 0..n_bins-1 (host array of n_bins entries). */
+/* CQT plans (nna_plan_cqt, nna_plan_cqt1992) only: kernel lengths N_k, k = 0..n_bins-1 (host array of n_bins entries). */
 nna_status nna_plan_cqt_lengths(const nna_plan* plan, long long* host_out, size_t cap);
 
 /* STFT plans only: normalised bin frequencies sigma(k), k = 0..out_bins-1, in units of sr/n_fft

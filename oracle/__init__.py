@@ -278,3 +278,46 @@ def cqt2010v2(x, sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, w
     _check(lib().orc_cqt2010v2(_pf(x), B, L, sr, hop, fmin, n_bins, bins_per_octave, window, n_taps, fir_taps, fmt,
                                _pd(out)), "cqt2010v2")
     return out
+
+
+def cqt1992_spectral_kernels(sr, fmin, n_bins, bins_per_octave, window=WIN_HANN, n_fft=0):
+    """Frequency-domain constant-Q kernels Y[k_cq, k], k = 0..n_fft/2 (Sec. III-C, "CQT using neural
+    networks", eq. (CQT1992), Fig. 4 right): each time-domain kernel of ``cqt_kernels`` (centred in
+    n_fft taps) taken to the frequency domain by an FFT, of which the half k <= n_fft/2 is kept.
+
+    Reading: eq. (Parseval) as printed has neither a conjugate nor an index reversal, which a product of
+    two complex spectra needs.  The identity used is  sum_n a[n] kappa[n] = (1/N) sum_k A[k] conj(B[k])
+    with B = DFT(conj(kappa)); kappa = w exp(-2 pi i Q n / N_k) / sum(w) is the kernel of eq. (CQT), so
+    conj(kappa) has a positive frequency and B lives in the kept half.  Returned: Y = conj(B).
+    """
+    if n_fft <= 0:
+        n_fft = cqt_default_taps(sr, fmin, bins_per_octave)
+    kre, kim = cqt_kernels(sr, fmin, n_bins, bins_per_octave, window=window, n_taps=n_fft)
+    B = np.fft.fft(kre - 1j * kim, axis=1)
+    return np.conj(B[:, :n_fft // 2 + 1])
+
+
+def cqt1992(x, sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, window=WIN_HANN, center=True,
+            n_fft=0, fmt=MAGNITUDE):
+    """Constant-Q spectrogram with frequency-domain kernels (Sec. III-C, eq. (CQT1992), Fig. 5), in the
+    paper's order: (1) the un-windowed STFT of the waveform with n_fft = the kernels' padded length
+    (the CQT window lives in the kernels), bins 0..n_fft/2; (2) every time step multiplied with the
+    spectral kernels, X_cq[k_cq, t] = (1/n_fft) sum_k X_t[k] Y[k_cq, k]; (3) element-wise magnitude.
+    The sum runs over the kept half of the spectrum only, which makes this the approximation of the
+    time-domain CQT that the paper says it is.  out: [B, n_bins, T].
+    """
+    x = _x(x)
+    if n_fft <= 0:
+        n_fft = cqt_default_taps(sr, fmin, bins_per_octave)
+    Y = cqt1992_spectral_kernels(sr, fmin, n_bins, bins_per_octave, window=window, n_fft=n_fft)
+    re, im = stft_complex(x, n_fft=n_fft, hop=hop, window=WIN_RECT, center=center)
+    X = re + 1j * im                                    # [B, F, T]
+    Xcq = np.einsum("qk,bkt->bqt", Y, X) / float(n_fft)  # [B, n_bins, T]
+    pw = Xcq.real ** 2 + Xcq.imag ** 2
+    if fmt == MAGNITUDE:
+        return np.sqrt(pw)
+    if fmt == POWER:
+        return pw
+    if fmt == LOG:
+        return np.log(np.maximum(pw, LOG_FLOOR))
+    raise OracleError("unknown output format")

@@ -21,13 +21,13 @@ NNA_WIN_HANN, NNA_WIN_RECT = 0, 1
 NNA_MEL_SLANEY, NNA_MEL_HTK = 0, 1
 NNA_FREQ_LINEAR, NNA_FREQ_LOG = 1, 2
 NNA_PREC_F32, NNA_PREC_F16 = 0, 1
-NNA_KIND_STFT, NNA_KIND_MEL, NNA_KIND_CQT, NNA_KIND_CQT2010V2 = 0, 1, 2, 3
+NNA_KIND_STFT, NNA_KIND_MEL, NNA_KIND_CQT, NNA_KIND_CQT2010V2, NNA_KIND_CQT1992 = 0, 1, 2, 3, 4
 
 # every symbol include/nna.h declares
 EXPORTS = [
     "nna_plan_stft", "nna_plan_stft_prec", "nna_plan_stft_scaled", "nna_plan_mel", "nna_plan_cqt", "nna_plan_cqt2010v2", "nna_out_shape", "nna_stft", "nna_mel", "nna_cqt",
     "nna_plan_bank", "nna_plan_mel_weights", "nna_plan_info", "nna_plan_cqt_lengths", "nna_plan_sigma", "nna_cqt2010v2_workspace",
-    "nna_cqt2010v2", "nna_plan_part",
+    "nna_cqt2010v2", "nna_plan_part", "nna_plan_cqt1992", "nna_cqt1992", "nna_plan_spectral_kernels",
     "nna_plan_destroy",
     "nna_status_str", "nna_last_error",
 ]
@@ -53,6 +53,13 @@ def lib():
             raise FileNotFoundError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_1912_12055_amd.build` "
                 "(there is no CPU fallback)")
+        # PyTorch ships a HIP runtime of its own.  Loading it first makes the library's dependency on
+        # the runtime resolve to that copy, so the process holds one runtime; loaded the other way
+        # round, the second copy finds no device.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = _c.CDLL(LIB_PATH)
         PP = _c.POINTER(_VP)
         L.nna_plan_stft.argtypes = [PP, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int]
@@ -66,11 +73,14 @@ def lib():
                                    _c.c_int, _c.c_int, _c.c_int]
         L.nna_plan_cqt2010v2.argtypes = [PP, _c.c_int, _c.c_int, _c.c_double, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
                                          _c.c_int, _c.c_int, _c.c_int]
+        L.nna_plan_cqt1992.argtypes = [PP, _c.c_int, _c.c_int, _c.c_double, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
+                                       _c.c_int, _c.c_int, _c.c_int]
+        L.nna_plan_spectral_kernels.argtypes = [_VP, _c.POINTER(_c.c_double), _c.c_size_t]
         L.nna_cqt2010v2_workspace.argtypes = [_VP, _LL, _LL, _c.POINTER(_c.c_size_t)]
         L.nna_cqt2010v2.argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _c.c_size_t, _VP]
         L.nna_plan_part.argtypes = [_VP, _c.c_int, PP]
         L.nna_out_shape.argtypes = [_VP, _LL, _LL, _c.POINTER(_LL), _c.POINTER(_LL)]
-        for name in ("nna_stft", "nna_mel", "nna_cqt"):
+        for name in ("nna_stft", "nna_mel", "nna_cqt", "nna_cqt1992"):
             getattr(L, name).argtypes = [_VP, _VP, _LL, _LL, _VP, _VP]
         L.nna_plan_bank.argtypes = [_VP, _c.POINTER(_c.c_double), _c.c_size_t]
         L.nna_plan_mel_weights.argtypes = [_VP, _c.POINTER(_c.c_double), _c.c_size_t]
@@ -164,6 +174,20 @@ def nna_plan_cqt2010v2(sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave
                        fir_taps=0, fmt=NNA_OUT_MAGNITUDE, device=0) -> Plan:
     return _new_plan(lib().nna_plan_cqt2010v2,
                      (sr, hop, float(fmin), n_bins, bins_per_octave, win, n_taps, fir_taps, fmt), device)
+
+
+def nna_plan_cqt1992(sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, win=NNA_WIN_HANN, center=True,
+                     n_fft=0, fmt=NNA_OUT_MAGNITUDE, device=0) -> Plan:
+    return _new_plan(lib().nna_plan_cqt1992,
+                     (sr, hop, float(fmin), n_bins, bins_per_octave, win, int(center), n_fft, fmt), device)
+
+
+def nna_plan_spectral_kernels(plan: Plan) -> np.ndarray:
+    """Complex [n_bins, n_fft/2+1]: the spectral kernels of a plan from nna_plan_cqt1992, divided by n_fft."""
+    i = plan.info()
+    out = np.empty((2 * i["out_bins"], i["taps"] // 2 + 1), dtype=np.float64)
+    _check(lib().nna_plan_spectral_kernels(plan.handle, out.ctypes.data_as(_c.POINTER(_c.c_double)), out.size))
+    return out[0::2] + 1j * out[1::2]
 
 
 def nna_plan_part(plan: Plan, index: int) -> Plan:
@@ -264,6 +288,11 @@ def nna_stft(plan: Plan, x, out=None, stream=None):
 def nna_mel(plan: Plan, x, out=None, stream=None):
     """out[B, n_mels, T] = Mel spectrogram of x[B, L]."""
     return _run(lib().nna_mel, plan, x, out, stream)
+
+
+def nna_cqt1992(plan: Plan, x, out=None, stream=None):
+    """out[B, n_bins, T] = constant-Q spectrogram of x[B, L] with frequency-domain kernels."""
+    return _run(lib().nna_cqt1992, plan, x, out, stream)
 
 
 def nna_cqt(plan: Plan, x, out=None, stream=None):

@@ -22,6 +22,11 @@ constexpr int ST_KG = 8;          // taps per bank fragment (float4 per lane, tw
 constexpr int ST_NKG = ST_KC / ST_KG;
 constexpr int ST_LDS_ROWS = 160;  // LDS rows per buffer (frames + overlap rows)
 constexpr int ST_MEL_BLOCKS = 4;  // 32-mel MFMA blocks per pass (128 mels)
+// what the STFT kernel does with a finished row tile
+constexpr int ST_MODE_STFT = 0;   // per-bin epilogue, output written per row tile
+constexpr int ST_MODE_MEL = 1;    // power (or magnitude) of the row tile x filterbank slice -> 128 mel accumulators
+constexpr int ST_MODE_LIN = 2;    // the (Re, Im) rows themselves x a real matrix slice -> 128 output rows = 64
+                                  // complex bins (constant-Q transform with frequency-domain kernels)
 
 // float16-operand STFT kernel: v_mfma_f32_32x32x16_f16, workgroup tile 256 bank rows x 192 frames.
 constexpr int H_ROWS = 256;
@@ -66,7 +71,7 @@ struct StftParams {
   long long n_ft;       // frame tiles
   int tile_frames;      // frames per tile (<= ST_FRAMES; smaller only when many short waveforms share a tile)
   // Mel only
-  const float4* melw;   // [pass][row tile][ST_RB][ST_MEL_BLOCKS][2][64 lanes] float4
+  const float4* melw;   // [pass][row tile][ST_RB][ST_MEL_BLOCKS][2][64 lanes] float4 (ST_MODE_LIN: [4] in place of [2])
   const unsigned char* mel_mask;  // [pass][row tile][ST_RB]: bit mb set if that 32-mel block is non-zero
   const float* mel_wnyq;          // [n_mels] weight of the Nyquist bin
   const int* mel_pass_rt;         // [pass][2]: first row tile, one past the last
@@ -132,7 +137,7 @@ struct CqtParams {
   long long n_ft;
 };
 
-hipError_t launch_stft(const StftParams& p, bool mel, hipStream_t stream);
+hipError_t launch_stft(const StftParams& p, int mode, hipStream_t stream);
 hipError_t launch_cqt(const CqtParams& p, hipStream_t stream);
 hipError_t launch_stft16(const Stft16Params& p, hipStream_t stream);
 hipError_t kernels_init();  // per-process function attributes

@@ -41,9 +41,12 @@ constexpr int ST_RG = 4;         // row tiles one STFT workgroup handles (amorti
 constexpr int ST_RING_STFT = 4;  // bank fragment groups in flight per wave
 constexpr int ST_RING_MEL = 2;   // fewer in the Mel variant: its 64 extra accumulators need the registers
 
-template <bool MEL, int RING>
+// MODE (ST_MODE_*): what follows the contraction of a row tile.
+template <int MODE, int RING>
 __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
   static_assert(ST_NKG % RING == 0, "ring depth must divide the fragment groups per LDS row");
+  constexpr bool MEL = MODE != ST_MODE_STFT;  // a second contraction follows every row tile
+  constexpr bool LIN = MODE == ST_MODE_LIN;
   __shared__ __attribute__((aligned(16))) float lds[2][ST_LDS_ROWS * ST_PITCH];
 
   const int tid = threadIdx.x;
@@ -249,6 +252,30 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
         }
       } else {
         const unsigned char* __restrict__ maskp = P.mel_mask + ((long long)pass * P.n_rt + rt) * ST_RB;
+        if constexpr (LIN) {
+          // Accumulator register r of lane (h, n) is packed row 32 rb + 8 (r/4) + 4 h + r%4 of the row
+          // tile for frame n: as the B operand of MFMA number r it meets, in lane (h, m), the weight
+          // of output row m for that packed row.  16 MFMAs contract the 32 rows of block rb.
+          const float4* __restrict__ wp =
+              P.melw + (((long long)pass * P.n_rt + rt) * ST_RB) * (ST_MEL_BLOCKS * 4 * 64) + lane;
+#pragma unroll
+          for (int rb = 0; rb < ST_RB; ++rb) {
+            const unsigned mask = maskp[rb];
+#pragma unroll
+            for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb) {
+              if (mask & (1u << mb)) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                  const float4 w = wp[((rb * ST_MEL_BLOCKS + mb) * 4 + v) * 64];
+                  macc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w.x, acc[rb][4 * v + 0], macc[mb], 0, 0, 0);
+                  macc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w.y, acc[rb][4 * v + 1], macc[mb], 0, 0, 0);
+                  macc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w.z, acc[rb][4 * v + 2], macc[mb], 0, 0, 0);
+                  macc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w.w, acc[rb][4 * v + 3], macc[mb], 0, 0, 0);
+                }
+              }
+            }
+          }
+        } else {
         const float4* __restrict__ wp =
             P.melw + (((long long)pass * P.n_rt + rt) * ST_RB) * (ST_MEL_BLOCKS * 2 * 64) + lane;
 #pragma unroll
@@ -282,6 +309,7 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
             }
           }
         }
+        }
       }
 #pragma unroll
       for (int rb = 0; rb < ST_RB; ++rb)
@@ -299,7 +327,24 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
 #pragma unroll
   for (int s = 0; s < RING; ++s) wait_vm<0>(bq[s][0], bq[s][1], bq[s][2], bq[s][3]);
 
-  if constexpr (MEL) {
+  if constexpr (LIN) {
+    // output rows 2q, 2q+1 = (Re, Im) of complex bin q sit in adjacent registers of one lane
+    float* __restrict__ op = P.out + (b_lane * P.out_bins) * g.T + t_lane;
+    const int f = P.fmt;
+#pragma unroll
+    for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb) {
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        const int bin = (pass * (32 * ST_MEL_BLOCKS) + mb * 32 + 8 * (r >> 2) + 4 * h + (r & 3)) >> 1;
+        if (valid && bin < P.out_bins) {
+          const float pw = macc[mb][r] * macc[mb][r] + macc[mb][r + 1] * macc[mb][r + 1];
+          op[(long long)bin * g.T] = f == NNA_OUT_MAGNITUDE ? format_power<NNA_OUT_MAGNITUDE>(pw)
+                                     : f == NNA_OUT_POWER   ? pw
+                                                            : format_power<NNA_OUT_LOG>(pw);
+        }
+      }
+    }
+  } else if constexpr (MEL) {
     // Nyquist-bin term (its power lives in lane n of the first lane half) and the store.
     float nyq_n = 0.f;
     if (P.mel_nyq_any) nyq_n = __shfl(nyq, n, 64);
@@ -597,8 +642,9 @@ hipError_t kernels_init() {
                              (int)CQ_DYN_LDS_MAX);
 }
 
-hipError_t launch_stft(const StftParams& p, bool mel, hipStream_t stream) {
+hipError_t launch_stft(const StftParams& p, int mode, hipStream_t stream) {
   long long blocks;
+  const bool mel = mode != ST_MODE_STFT;
   if (mel) {
     blocks = p.n_ft * p.n_pass;
   } else {
@@ -607,10 +653,12 @@ hipError_t launch_stft(const StftParams& p, bool mel, hipStream_t stream) {
     blocks = 8 * groups * 64 * ((p.n_rt + ST_RG - 1) / ST_RG);
   }
   if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  if (mel)
-    hipLaunchKernelGGL((stft_kernel<true, ST_RING_MEL>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  if (mode == ST_MODE_LIN)
+    hipLaunchKernelGGL((stft_kernel<ST_MODE_LIN, ST_RING_MEL>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  else if (mode == ST_MODE_MEL)
+    hipLaunchKernelGGL((stft_kernel<ST_MODE_MEL, ST_RING_MEL>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   else
-    hipLaunchKernelGGL((stft_kernel<false, ST_RING_STFT>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL((stft_kernel<ST_MODE_STFT, ST_RING_STFT>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 

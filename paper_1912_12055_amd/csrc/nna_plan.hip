@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <climits>
 #include <cmath>
+#include <complex>
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
@@ -49,6 +50,11 @@ struct nna_plan {
   // Mel
   int n_mels = 0, mel_power = 2, n_pass = 0, mel_nyq_any = 0;
   std::vector<float> h_melW;  // [n_mels, F] as rounded to float32
+  // CQT with frequency-domain kernels: the real matrix that takes the packed (Re, Im) rows of one
+  // STFT frame to the (Re, Im) rows of the constant-Q bins, [2 n_bins, 2 n_half], float32 as uploaded
+  std::vector<float> h_linW;
+  int cq_window = 0;
+  size_t lin_frag_floats = 0;
 
   // CQT
   int n_bins = 0, bpo = 0, n_rb = 0;
@@ -407,6 +413,116 @@ MelDeviceLayout layout_mel(nna_plan* p) {
   return out;
 }
 
+// ---- CQT with frequency-domain kernels (Sec. III-C, eq. (CQT1992)) -----------------------
+// In-place radix-2 decimation-in-time FFT, forward sign, n a power of two.
+void fft_pow2(std::vector<std::complex<double>>& a) {
+  const size_t n = a.size();
+  for (size_t i = 1, j = 0; i < n; ++i) {
+    size_t bit = n >> 1;
+    for (; j & bit; bit >>= 1) j ^= bit;
+    j ^= bit;
+    if (i < j) std::swap(a[i], a[j]);
+  }
+  std::vector<std::complex<double>> tw(n / 2);
+  for (size_t k = 0; k < n / 2; ++k) tw[k] = std::polar(1.0, -2.0 * kPi * (double)k / (double)n);
+  for (size_t len = 2; len <= n; len <<= 1) {
+    const size_t half = len >> 1, step = n / len;
+    for (size_t i = 0; i < n; i += len)
+      for (size_t k = 0; k < half; ++k) {
+        const std::complex<double> u = a[i + k], v = a[i + k + half] * tw[k * step];
+        a[i + k] = u + v;
+        a[i + k + half] = u - v;
+      }
+  }
+}
+
+// The spectral kernels and the real matrix the kernel multiplies with.  kappa_q[n] = window(N_q)[n]
+// exp(-2 pi i Q n / N_q) / sum(window) is the kernel of eq. (CQT), centred in K taps.  With
+// B_q = DFT(conj(kappa_q)) (a positive-frequency signal, so B_q lives in bins 0..K/2) Parseval gives
+//   sum_n x[n] kappa_q[n] = (1/K) sum_k X[k] conj(B_q[k]),
+// and eq. (CQT1992) keeps k = 0..K/2.  Y[q, k] = conj(B_q[k]).  In real arithmetic, per bin k:
+//   Re X_cq += (Xr Yr - Xi Yi)/K,   Im X_cq += (Xr Yi + Xi Yr)/K.
+// Packed STFT rows: 2s = Re X[s], 2s+1 = Im X[s]; slot 0 holds the two purely real bins 0 and K/2.
+void build_cqt1992_matrix(nna_plan* p) {
+  const int K = p->K, n_half = p->n_half, R = 2 * p->n_bins, C = 2 * n_half;
+  p->h_linW.assign((size_t)R * C, 0.0f);
+  std::vector<std::complex<double>> a(K);
+  const double inv = 1.0 / (double)K;
+  for (int q = 0; q < p->n_bins; ++q) {
+    std::fill(a.begin(), a.end(), std::complex<double>(0.0, 0.0));
+    double wsum = 0;
+    for (long long n = 0; n < p->Nk[q]; ++n) wsum += window_value(p->cq_window, n, p->Nk[q]);
+    for (long long n = 0; n < p->Nk[q]; ++n) {
+      const double w = window_value(p->cq_window, n, p->Nk[q]) / wsum;
+      a[p->sk[q] + n] = std::polar(w, 2.0 * kPi * p->Q * (double)n / (double)p->Nk[q]);  // conj(kappa)
+    }
+    fft_pow2(a);
+    float* re_row = &p->h_linW[(size_t)(2 * q) * C];
+    float* im_row = &p->h_linW[(size_t)(2 * q + 1) * C];
+    for (int s = 0; s <= n_half; ++s) {
+      const double yr = a[s].real() * inv, yi = -a[s].imag() * inv;  // Y = conj(B), with the 1/K folded in
+      if (s == 0 || s == n_half) {  // purely real STFT bins: packed rows 0 and 1
+        re_row[s == 0 ? 0 : 1] = (float)yr;
+        im_row[s == 0 ? 0 : 1] = (float)yi;
+      } else {
+        re_row[2 * s] = (float)yr;
+        re_row[2 * s + 1] = (float)(-yi);
+        im_row[2 * s] = (float)yi;
+        im_row[2 * s + 1] = (float)yr;
+      }
+    }
+  }
+}
+
+// index of (pass, row tile, row block, out block, quad v, lane, element e) in the fragment array of
+// the second contraction, and the matrix entry it holds: output row pass*128 + mb*32 + lane%32,
+// packed row rt*128 + rb*32 + 8 v + 4 (lane/32) + e
+inline size_t lin_frag_index(const nna_plan* p, int pass, int rt, int rb, int mb, int v, int lane, int e) {
+  return ((((((size_t)pass * p->n_rt + rt) * ST_RB + rb) * ST_MEL_BLOCKS + mb) * 4 + v) * 64 + lane) * 4 + e;
+}
+
+MelDeviceLayout layout_cqt1992(nna_plan* p) {
+  MelDeviceLayout out;
+  const int R = 2 * p->n_bins, C = 2 * p->n_half;
+  const int per_pass = 32 * ST_MEL_BLOCKS;
+  p->n_pass = (R + per_pass - 1) / per_pass;
+  p->lin_frag_floats = (size_t)p->n_pass * p->n_rt * ST_RB * ST_MEL_BLOCKS * 4 * 64 * 4;
+  out.frag.assign(p->lin_frag_floats, 0.0f);
+  out.mask.assign((size_t)p->n_pass * p->n_rt * ST_RB, 0);
+  out.wnyq.assign(1, 0.0f);
+  out.pass_rt.assign((size_t)p->n_pass * 2, 0);
+  p->mel_nyq_any = 0;
+  double exec_blocks = 0;
+  for (int pass = 0; pass < p->n_pass; ++pass) {
+    // the paper applies no threshold to the spectral kernels: every row tile is visited
+    out.pass_rt[2 * pass] = 0;
+    out.pass_rt[2 * pass + 1] = p->n_rt;
+    for (int rt = 0; rt < p->n_rt; ++rt)
+      for (int rb = 0; rb < ST_RB; ++rb)
+        for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb) {
+          bool any = false;
+          for (int v = 0; v < 4; ++v)
+            for (int lane = 0; lane < 64; ++lane)
+              for (int e = 0; e < 4; ++e) {
+                const int row = pass * per_pass + mb * 32 + (lane & 31);
+                const int col = rt * ST_ROWS + rb * 32 + 8 * v + 4 * (lane >> 5) + e;
+                const float w = row < R && col < C ? p->h_linW[(size_t)row * C + col] : 0.0f;
+                out.frag[lin_frag_index(p, pass, rt, rb, mb, v, lane, e)] = w;
+                any = any || w != 0.0f;
+              }
+          if (any) {
+            out.mask[((size_t)pass * p->n_rt + rt) * ST_RB + rb] |= (unsigned char)(1u << mb);
+            exec_blocks += 1;
+          }
+        }
+  }
+  const double k_exec = (double)p->n_chunks * p->nj * ST_KC;
+  p->exec_flops = p->n_pass * 2.0 * k_exec * ST_ROWS * p->n_rt + exec_blocks * 2.0 * 32 * 32;
+  // the DFT of a frame (K non-zero rows x K taps) + one complex multiply-add per (bin, kept DFT bin)
+  p->alg_flops = 2.0 * (double)p->K * (double)p->K + 8.0 * (double)p->n_bins * (double)(p->n_half + 1);
+  return out;
+}
+
 // ---- CQT bank (Sec. III-C) ------------------------------------------------------------
 struct CqtKernelGen {
   const nna_plan* p;
@@ -742,7 +858,7 @@ nna_status run_stft_like(const nna_plan* plan, int kind, const float* x, long lo
   P.nj = plan->nj;
   P.n_half = plan->n_half;
   P.packed = plan->freq_scale ? 0 : 1;
-  P.out_bins = kind == NNA_KIND_MEL ? plan->n_mels : plan->stft_bins();
+  P.out_bins = kind == NNA_KIND_MEL ? plan->n_mels : kind == NNA_KIND_CQT1992 ? plan->n_bins : plan->stft_bins();
   P.tile_frames = M;
   P.n_ft = (P.g.n_frames + M - 1) / M;
   if (kind == NNA_KIND_MEL) {
@@ -754,13 +870,22 @@ nna_status run_stft_like(const nna_plan* plan, int kind, const float* x, long lo
     P.n_mels = plan->n_mels;
     P.n_pass = plan->n_pass;
     P.mel_nyq_any = plan->mel_nyq_any;
+  } else if (kind == NNA_KIND_CQT1992) {
+    P.fmt = plan->fmt;
+    P.melw = reinterpret_cast<const float4*>(plan->d_melw);
+    P.mel_mask = plan->d_mel_mask;
+    P.mel_wnyq = plan->d_mel_wnyq;
+    P.mel_pass_rt = plan->d_mel_pass_rt;
+    P.n_mels = 2 * plan->n_bins;
+    P.n_pass = plan->n_pass;
   } else {
     P.fmt = plan->fmt;
   }
   DeviceGuard guard;
   hipError_t e = guard.enter(plan->device);
   if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
-  e = nna::launch_stft(P, kind == NNA_KIND_MEL, reinterpret_cast<hipStream_t>(stream));
+  const int mode = kind == NNA_KIND_MEL ? nna::ST_MODE_MEL : kind == NNA_KIND_CQT1992 ? nna::ST_MODE_LIN : nna::ST_MODE_STFT;
+  e = nna::launch_stft(P, mode, reinterpret_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail_hip(e, "kernel launch");
   return NNA_OK;
 }
@@ -1168,6 +1293,111 @@ nna_status nna_plan_cqt2010v2(nna_plan** plan, int sr, int hop, double fmin, int
 }
 
 
+nna_status nna_plan_cqt1992(nna_plan** plan, int sr, int hop, double fmin, int n_bins, int bins_per_octave,
+                            nna_window win, int center, int n_fft, nna_output fmt, int device) {
+  nna_status s = check_common(plan, sr, hop, win, center, device);
+  if (s != NNA_OK) return s;
+  if ((s = check_cqt_args(fmin, n_bins, bins_per_octave, n_fft, fmt, sr)) != NNA_OK) return s;
+  nna_plan* p = new (std::nothrow) nna_plan;
+  if (!p) return fail(NNA_ERR_ALLOC, "out of host memory");
+  MelDeviceLayout lin;
+  try {
+    p->kind = NNA_KIND_CQT1992;
+    p->device = device;
+    p->sr = sr;
+    p->hop = hop;
+    p->center = center;
+    p->window = NNA_WIN_RECT;  // the STFT stage is un-windowed: the window lives in the CQT kernels
+    p->cq_window = win;
+    p->fmt = fmt;
+    p->n_bins = n_bins;
+    p->bpo = bins_per_octave;
+    p->cq_fmin = fmin;
+    p->Q = 1.0 / (std::exp2(1.0 / bins_per_octave) - 1.0);  // eq. (Q)
+    p->Nk.resize(n_bins);
+    p->sk.resize(n_bins);
+    for (int k = 0; k < n_bins; ++k)
+      p->Nk[k] = (long long)std::ceil(p->Q * (double)sr / (fmin * std::exp2((double)k / bins_per_octave)));  // eq. (N_k)
+    long long N = n_fft;
+    if (N == 0) {
+      N = 8;
+      while (N < p->Nk[0] && N < (1LL << 30)) N <<= 1;
+    }
+    if (N < 8 || (N & (N - 1))) {
+      delete p;
+      return fail(NNA_ERR_INVALID_ARG, "n_fft must be a power of two >= 8 (0 picks the smallest that holds the longest kernel)");
+    }
+    if (N < p->Nk[0]) {
+      char msg[160];
+      std::snprintf(msg, sizeof msg, "n_fft = %lld is shorter than the longest kernel (%lld taps)", N, p->Nk[0]);
+      delete p;
+      return fail(NNA_ERR_INVALID_ARG, msg);
+    }
+    if (N > 65536) {
+      delete p;
+      return fail(NNA_ERR_UNSUPPORTED, "the DFT bank of n_fft above 65,536 (17 GB at 65,536) is not supported");
+    }
+    p->K = (int)N;
+    p->pad = center ? (int)(N / 2) : 0;
+    for (int k = 0; k < n_bins; ++k) p->sk[k] = (N - p->Nk[k]) / 2;
+    build_stft_bank(p);
+    build_cqt1992_matrix(p);
+    lin = layout_cqt1992(p);
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return fail(NNA_ERR_ALLOC, "out of host memory while building the DFT bank and the spectral kernels");
+  }
+  return finish_plan(p, plan, &lin);
+}
+
+nna_status nna_cqt1992(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev, void* hip_stream) {
+  return run_stft_like(plan, NNA_KIND_CQT1992, x_dev, B, L, out_dev, hip_stream);
+}
+
+nna_status nna_plan_spectral_kernels(const nna_plan* plan, double* host_out, size_t cap) {
+  if (!plan || !host_out) return fail(NNA_ERR_INVALID_ARG, "plan / host_out is NULL");
+  if (plan->kind != NNA_KIND_CQT1992) return fail(NNA_ERR_INVALID_ARG, "not a plan from nna_plan_cqt1992");
+  const size_t F = (size_t)plan->n_half + 1, R = 2 * (size_t)plan->n_bins, C = 2 * (size_t)plan->n_half;
+  if (cap < R * F) return fail(NNA_ERR_INVALID_ARG, "host_out is too small");
+  std::vector<float> W;  // the matrix [R, C] as the GPU holds it
+  try {
+    if (plan->device < 0) {
+      W = plan->h_linW;
+    } else {
+      std::vector<float> frag(plan->lin_frag_floats);
+      {
+        DeviceGuard guard;
+        hipError_t e = guard.enter(plan->device);
+        if (e == hipSuccess) e = hipMemcpy(frag.data(), plan->d_melw, frag.size() * sizeof(float), hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return fail_hip(e, "spectral kernel read-back");
+      }
+      W.assign(R * C, 0.0f);
+      const int per_pass = 32 * ST_MEL_BLOCKS;
+      for (int pass = 0; pass < plan->n_pass; ++pass)
+        for (int rt = 0; rt < plan->n_rt; ++rt)
+          for (int rb = 0; rb < ST_RB; ++rb)
+            for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb)
+              for (int v = 0; v < 4; ++v)
+                for (int lane = 0; lane < 64; ++lane)
+                  for (int e = 0; e < 4; ++e) {
+                    const size_t row = (size_t)pass * per_pass + mb * 32 + (lane & 31);
+                    const size_t col = (size_t)rt * ST_ROWS + rb * 32 + 8 * v + 4 * (lane >> 5) + e;
+                    if (row < R && col < C) W[row * C + col] = frag[lin_frag_index(plan, pass, rt, rb, mb, v, lane, e)];
+                  }
+    }
+  } catch (const std::bad_alloc&) {
+    return fail(NNA_ERR_ALLOC, "out of host memory");
+  }
+  // un-pack: bins 0 and K/2 sit in packed columns 0 and 1, bin s in columns 2s (its Re weight)
+  for (size_t q = 0; q < (size_t)plan->n_bins; ++q)
+    for (size_t s2 = 0; s2 < F; ++s2) {
+      const size_t col = s2 == 0 ? 0 : s2 == F - 1 ? 1 : 2 * s2;
+      host_out[(2 * q) * F + s2] = (double)W[(2 * q) * C + col];
+      host_out[(2 * q + 1) * F + s2] = (double)W[(2 * q + 1) * C + col];
+    }
+  return NNA_OK;
+}
+
 nna_status nna_cqt2010v2_workspace(const nna_plan* plan, long long B, long long L, size_t* bytes) {
   if (!plan || !bytes) return fail(NNA_ERR_INVALID_ARG, "plan / bytes is NULL");
   if (plan->kind != NNA_KIND_CQT2010V2) return fail(NNA_ERR_INVALID_ARG, "plan was built for a different transform");
@@ -1432,7 +1662,7 @@ nna_status nna_plan_sigma(const nna_plan* plan, double* host_out, size_t cap) {
 
 nna_status nna_plan_cqt_lengths(const nna_plan* plan, long long* host_out, size_t cap) {
   if (!plan || !host_out) return fail(NNA_ERR_INVALID_ARG, "plan / host_out is NULL");
-  if (plan->kind != NNA_KIND_CQT) return fail(NNA_ERR_INVALID_ARG, "not a CQT plan");
+  if (plan->kind != NNA_KIND_CQT && plan->kind != NNA_KIND_CQT1992) return fail(NNA_ERR_INVALID_ARG, "not a CQT plan");
   if (cap < (size_t)plan->n_bins) return fail(NNA_ERR_INVALID_ARG, "host_out is too small");
   for (int k = 0; k < plan->n_bins; ++k) host_out[k] = plan->Nk[k];
   return NNA_OK;

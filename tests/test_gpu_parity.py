@@ -402,6 +402,81 @@ def test_cqt2010v2_workspace_and_shape_checks(nb):
 
 
 # ---------------------------------------------------------------------------------------
+# CQT with frequency-domain kernels (un-windowed STFT x spectral kernels, one kernel)
+# ---------------------------------------------------------------------------------------
+CQT1992_CASES = [
+    # name, B, L, sr, hop, fmin, n_bins, bpo, n_fft, win, center, fmt
+    ("36 bins, 2048 taps, one pass", 2, 9000, 22050, 256, 220.0, 36, 12, 0, 0, True, 0),
+    ("70 bins: two passes of 64, ragged, tiles span waveforms", 5, 9000, 8000, 64, 55.0, 70, 12, 0, 0, True, 0),
+    ("odd bin count, power output, padded n_fft", 2, 12000, 8000, 128, 300.0, 13, 6, 1024, 0, True, 1),
+    ("hop does not divide n_fft", 2, 6000, 8000, 100, 220.0, 30, 12, 1024, 0, True, 0),
+    ("rect kernels, no centring, log output", 2, 7000, 8000, 128, 500.0, 6, 3, 128, 1, False, 2),
+    ("short waveforms, many per tile", 40, 1100, 8000, 128, 220.0, 24, 12, 1024, 0, True, 0),
+    ("150 bins: three passes, 4096 taps", 2, 20000, 22050, 512, 110.0, 150, 24, 0, 0, True, 0),
+    ("8192 taps, 16 hop-shifts", 1, 30000, 22050, 512, 65.41, 40, 12, 0, 0, True, 0),
+]
+
+
+@pytest.mark.parametrize("case", CQT1992_CASES, ids=[c[0] for c in CQT1992_CASES])
+def test_cqt1992_parity_small(nb, case):
+    name, B, L, sr, hop, fmin, n_bins, bpo, n_fft, win, center, fmt = case
+    _say(f"cqt1992 {name}: B={B} L={L} sr={sr} hop={hop} bins={n_bins}/{bpo} n_fft={n_fft}")
+    x = _rand(B, L, 700 + n_bins)
+    plan = nb.nna_plan_cqt1992(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, win=win,
+                               center=center, n_fft=n_fft, fmt=fmt, device=0)
+    got = nb.nna_cqt1992(plan, _dev(x)).cpu().numpy()
+    ref = oracle.cqt1992(x, sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, window=win, center=center,
+                         n_fft=n_fft, fmt=fmt)
+    if fmt == 2:
+        # log output: compare where the power is above -60 dB of the peak (below, float32 rounding of a
+        # near-zero power is amplified without bound by the logarithm)
+        pw = oracle.cqt1992(x, sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, window=win,
+                            center=center, n_fft=n_fft, fmt=1)
+        keep = pw > 1e-6 * pw.max()
+        e = np.abs(got - ref)[keep].max()
+    else:
+        e = _rel_err(got, ref)
+    _say(f"  rel err {e:.3e}")
+    assert e < TOL and e < 5e-5
+
+
+def test_cqt1992_device_kernels_equal_host_kernels(nb):
+    _say("cqt1992 spectral kernels and DFT bank read-back")
+    kw = dict(sr=8000, hop=64, fmin=55.0, n_bins=70, bins_per_octave=12)
+    host, dev = nb.nna_plan_cqt1992(device=-1, **kw), nb.nna_plan_cqt1992(device=0, **kw)
+    np.testing.assert_array_equal(nb.nna_plan_spectral_kernels(host), nb.nna_plan_spectral_kernels(dev))
+    np.testing.assert_array_equal(nb.nna_plan_bank(host), nb.nna_plan_bank(dev))
+
+
+def test_cqt1992_tone_closed_form_and_time_domain_cqt_on_gpu(nb):
+    # a tone of exactly Q cycles per kernel reads A/2; and the whole output stays within the dropped
+    # half's share (1e-4 of the peak for this set-up) of the time-domain kernels' result
+    _say("cqt1992 tone closed form")
+    sr, fmin, n_bins, bpo, hop, A = 22050, 220.0, 36, 12, 256, 0.6
+    Nk, _ = oracle.cqt_lengths(sr, fmin, n_bins, bpo)
+    q = 17
+    f = oracle.cqt_Q(bpo) * sr / Nk[q]
+    x = signals.tone(4 * 2048, sr, f, amp=A, phase=1.1)[None, :]
+    kw = dict(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, device=0)
+    got = nb.nna_cqt1992(nb.nna_plan_cqt1992(**kw), _dev(x)).cpu().numpy()[0]
+    mid = got[:, got.shape[1] // 2]
+    assert int(np.argmax(mid)) == q and abs(mid[q] - A / 2) < 1e-4 * A
+    time_domain = nb.nna_cqt(nb.nna_plan_cqt(**kw), _dev(x)).cpu().numpy()[0]
+    assert np.abs(got - time_domain).max() < 2e-4 * time_domain.max()
+
+
+def test_cqt1992_rejects_wrong_plan_and_short_input(nb):
+    _say("cqt1992 error paths")
+    plan = nb.nna_plan_cqt1992(sr=8000, hop=64, fmin=220.0, n_bins=24, device=0)
+    with pytest.raises(nb.NnaError) as ei:
+        nb.nna_cqt1992(plan, _dev(_rand(1, 400, 1)))  # L <= n_fft / 2
+    assert ei.value.status == nb.NNA_ERR_SHAPE
+    with pytest.raises(nb.NnaError) as ei:
+        nb.nna_cqt(plan, _dev(_rand(1, 4000, 1)))
+    assert ei.value.status == nb.NNA_ERR_INVALID_ARG
+
+
+# ---------------------------------------------------------------------------------------
 # The two 1,770-waveform workloads at full size, in the launch configuration the bench times;
 # the oracle checks a sample of whole waveforms (first, second, middle, last two).
 # ---------------------------------------------------------------------------------------

@@ -248,3 +248,38 @@ def test_cqt2010v2_argument_checking():
     assert _status(nb.nna_plan_part, single, -1) == nb.NNA_ERR_INVALID_ARG  # one octave: no filter
     assert nb.nna_cqt2010v2_workspace(single, 4, 9000) == 0
     assert nb.nna_cqt2010v2_workspace(p, 4, 22050) >= 4 * 4 * (11025 + 5513)
+
+
+@pytest.mark.parametrize("sr,hop,fmin,n_bins,bpo,n_fft", [(22050, 256, 220.0, 36, 12, 0), (8000, 64, 110.0, 60, 12, 4096),
+                                                          (1000, 16, 100.0, 5, 3, 0)])
+def test_cqt1992_plan_holds_the_dft_bank_and_the_oracles_spectral_kernels(sr, hop, fmin, n_bins, bpo, n_fft):
+    p = nb.nna_plan_cqt1992(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, n_fft=n_fft, device=-1)
+    info = p.info()
+    N = n_fft or oracle.cqt_default_taps(sr, fmin, bpo)
+    assert (info["kind"], info["taps"], info["out_bins"], info["bank_rows"]) == (nb.NNA_KIND_CQT1992, N, n_bins, N + 2)
+    np.testing.assert_array_equal(nb.nna_plan_cqt_lengths(p), oracle.cqt_lengths(sr, fmin, n_bins, bpo)[0])
+    # stage 2: Y / n_fft, float32-rounded
+    want = oracle.cqt1992_spectral_kernels(sr, fmin, n_bins, bpo, n_fft=N) / N
+    got = nb.nna_plan_spectral_kernels(p)
+    assert got.shape == want.shape
+    np.testing.assert_allclose(got, want, atol=2e-7 * np.abs(want).max())
+    # stage 1: the un-windowed DFT kernels of eq. (DFT2)
+    bank = nb.nna_plan_bank(p)
+    n = np.arange(N)
+    for k in (0, 1, N // 4 + 1, N // 2):
+        np.testing.assert_allclose(bank[2 * k], np.cos(2 * np.pi * k * n / N), atol=1e-6)
+        np.testing.assert_allclose(bank[2 * k + 1], -np.sin(2 * np.pi * k * n / N), atol=1e-6)
+    assert nb.nna_out_shape(p, 3, 5 * N) == (n_bins, 1 + 5 * N // hop)
+    assert info["algorithmic_flops_per_frame"] == 2.0 * N * N + 8.0 * n_bins * (N // 2 + 1)
+
+
+def test_cqt1992_argument_checking():
+    kw = dict(sr=22050, hop=256, fmin=220.0, n_bins=36, bins_per_octave=12, device=-1)
+    assert _status(nb.nna_plan_cqt1992, **kw) == nb.NNA_OK
+    assert _status(nb.nna_plan_cqt1992, n_fft=1024, **kw) == nb.NNA_ERR_INVALID_ARG  # longest kernel: 1,686 taps
+    assert "longest kernel" in nb.nna_last_error()
+    assert _status(nb.nna_plan_cqt1992, n_fft=3000, **kw) == nb.NNA_ERR_INVALID_ARG  # not a power of two
+    assert _status(nb.nna_plan_cqt1992, n_fft=1 << 17, **kw) == nb.NNA_ERR_UNSUPPORTED
+    assert _status(nb.nna_plan_cqt1992, **{**kw, "n_bins": 80}) == nb.NNA_ERR_INVALID_ARG  # top bin above sr/2
+    p = nb.nna_plan_cqt(sr=22050, hop=256, fmin=220.0, n_bins=36, device=-1)
+    assert _status(nb.nna_plan_spectral_kernels, p) == nb.NNA_ERR_INVALID_ARG
