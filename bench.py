@@ -154,7 +154,7 @@ def main() -> int:
         }
     dom = max(names, key=lambda n: per[n]["ms"])
     roofline = {
-        "kernel": {"stft": "stft_kernel<false>", "mel": "stft_kernel<true>", "cqt": "cqt_kernel"}[dom],
+        "kernel": {"stft": "stft_kernel<0, 4>", "mel": "stft_kernel<1, 2>", "cqt": "cqt_kernel"}[dom],
         "bound": "mfma",
         "achieved": per[dom]["algorithmic_tflops"],
         "peak": PEAK_FP32_MFMA_TFLOPS,
@@ -164,7 +164,8 @@ def main() -> int:
     }
 
     # Timed beside the step, never part of `value`: the same batch through the STFT on the linear
-    # frequency axis of Sec. II-B's worked example and through the downsampling CQT (Sec. III-C).
+    # frequency axis of Sec. II-B's worked example, through the downsampling CQT (Sec. III-C) and through
+    # the STFT with float16 operands; and the CQT with frequency-domain kernels on a smaller batch.
     extras = None
     if not args.no_extras and not args.only:
         extras = {}
@@ -175,9 +176,19 @@ def main() -> int:
         o_lin = torch.empty((B, 1025, T), dtype=torch.float32, device=dev)
         ws = torch.empty(max(16, nb.nna_cqt2010v2_workspace(p_2010, B, L)), dtype=torch.uint8, device=dev)
         p_h = nb.nna_plan_stft_prec(sr=sr, n_fft=2048, hop=512, precision=nb.NNA_PREC_F16, device=0)
-        for name, fn, plan in (("stft_linear_axis", lambda: nb.nna_stft(p_lin, x4, o_lin), p_lin),
-                               ("cqt2010v2", lambda: nb.nna_cqt2010v2(p_2010, x5, o_cqt, workspace=ws), p_2010),
-                               ("stft_f16_operands", lambda: nb.nna_stft(p_h, x4, o_lin), p_h)):
+        # the CQT with frequency-domain kernels costs an STFT of n_fft = 16,384 per 64 bins: timed on the
+        # smaller CQT workload's waveforms (220,500 samples @ 22,050 Hz, 84 bins, 12 per octave), 152 of
+        # them, which makes 1,024 workgroups (two per compute unit, twice over)
+        B3 = 152
+        x3 = torch.from_numpy(signals.batch(3, list(range(B3)), workers=16)).to(dev)
+        p_1992 = nb.nna_plan_cqt1992(sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, device=0)
+        o_1992 = torch.empty((B3, 84, 1 + 220500 // 512), dtype=torch.float32, device=dev)
+        full = (B * L, B * T)
+        for name, fn, plan, (n_samples, n_frames) in (
+                ("stft_linear_axis", lambda: nb.nna_stft(p_lin, x4, o_lin), p_lin, full),
+                ("cqt2010v2", lambda: nb.nna_cqt2010v2(p_2010, x5, o_cqt, workspace=ws), p_2010, full),
+                ("stft_f16_operands", lambda: nb.nna_stft(p_h, x4, o_lin), p_h, full),
+                ("cqt1992_152x220500", lambda: nb.nna_cqt1992(p_1992, x3, o_1992), p_1992, (B3 * 220500, B3 * 431))):
             for _ in range(max(1, args.warmup)):
                 fn()
             ev = []
@@ -192,14 +203,14 @@ def main() -> int:
             info = plan.info()
             extras[name] = {
                 "ms": round(ms, 4),
-                "gsamples_per_s": round(B * L / ms / 1e6, 4),
-                "algorithmic_tflops": round(info["algorithmic_flops_per_frame"] * B * T / ms / 1e9, 3),
-                "executed_tflops": round(info["executed_flops_per_frame"] * B * T / ms / 1e9, 3),
-                "mfma_frac": round(info["algorithmic_flops_per_frame"] * B * T / ms / 1e9
+                "gsamples_per_s": round(n_samples / ms / 1e6, 4),
+                "algorithmic_tflops": round(info["algorithmic_flops_per_frame"] * n_frames / ms / 1e9, 3),
+                "executed_tflops": round(info["executed_flops_per_frame"] * n_frames / ms / 1e9, 3),
+                "mfma_frac": round(info["algorithmic_flops_per_frame"] * n_frames / ms / 1e9
                                    / (PEAK_F16_MFMA_TFLOPS if name == "stft_f16_operands" else PEAK_FP32_MFMA_TFLOPS), 4),
                 "mfma_peak_tflops": PEAK_F16_MFMA_TFLOPS if name == "stft_f16_operands" else PEAK_FP32_MFMA_TFLOPS,
             }
-        del o_lin, ws
+        del o_lin, ws, x3, o_1992
 
     cpu = None
     if not args.no_cpu_baseline:
