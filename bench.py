@@ -183,10 +183,12 @@ def main() -> int:
         x3 = torch.from_numpy(signals.batch(3, list(range(B3)), workers=16)).to(dev)
         p_1992 = nb.nna_plan_cqt1992(sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, device=0)
         o_1992 = torch.empty((B3, 84, 1 + 220500 // 512), dtype=torch.float32, device=dev)
+        p_2010f = nb.nna_plan_cqt2010(sr=sr, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24, device=0)
         full = (B * L, B * T)
         for name, fn, plan, (n_samples, n_frames) in (
                 ("stft_linear_axis", lambda: nb.nna_stft(p_lin, x4, o_lin), p_lin, full),
                 ("cqt2010v2", lambda: nb.nna_cqt2010v2(p_2010, x5, o_cqt, workspace=ws), p_2010, full),
+                ("cqt2010", lambda: nb.nna_cqt2010(p_2010f, x5, o_cqt, workspace=ws), p_2010f, full),
                 ("stft_f16_operands", lambda: nb.nna_stft(p_h, x4, o_lin), p_h, full),
                 ("cqt1992_152x220500", lambda: nb.nna_cqt1992(p_1992, x3, o_1992), p_1992, (B3 * 220500, B3 * 431))):
             for _ in range(max(1, args.warmup)):

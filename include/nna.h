@@ -84,7 +84,8 @@ typedef enum {
   NNA_KIND_MEL = 1,
   NNA_KIND_CQT = 2,
   NNA_KIND_CQT2010V2 = 3,
-  NNA_KIND_CQT1992 = 4
+  NNA_KIND_CQT1992 = 4,
+  NNA_KIND_CQT2010 = 5
 } nna_kind;
 
 /*
@@ -187,6 +188,19 @@ nna_status nna_plan_cqt2010v2(nna_plan** plan, int sr, int hop, double fmin, int
 nna_status nna_plan_cqt1992(nna_plan** plan, int sr, int hop, double fmin, int n_bins, int bins_per_octave,
                             nna_window win, int center, int n_fft, nna_output fmt, int device);
 
+/*
+ * Constant-Q plan by recursive downsampling with frequency-domain kernels (Sec. III-C,
+ * "Constant-Q transform (2010 version)", Fig. CQT2010; the paper's CQT2010 layer).  Octaves, bins per
+ * octave, hop per octave, kernels, filter and frames are those of nna_plan_cqt2010v2; each octave is
+ * computed as in nna_plan_cqt1992 -- un-windowed STFT of the (downsampled) waveform with n_fft taps,
+ * times the octave's spectral kernels -- instead of with time-domain kernels.
+ *   n_fft     0 = the smallest power of two >= the longest top-octave kernel; else a power of two >= it
+ *   fir_taps  0 = 257; else odd, 3..4095
+ * Runs through nna_cqt2010 with the workspace nna_cqt2010v2_workspace reports.
+ */
+nna_status nna_plan_cqt2010(nna_plan** plan, int sr, int hop, double fmin, int n_bins, int bins_per_octave,
+                            nna_window win, int n_fft, int fir_taps, nna_output fmt, int device);
+
 /* Output shape [B, *n_bins, *n_frames] for a batch of B waveforms of L samples.
  * NNA_ERR_SHAPE if L is too short (center: L <= pad; otherwise L < K) or B < 1. */
 nna_status nna_out_shape(const nna_plan* plan, long long B, long long L, long long* n_bins,
@@ -211,8 +225,9 @@ nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long l
 nna_status nna_cqt1992(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
                        void* hip_stream);
 
-/* Bytes of device workspace nna_cqt2010v2 needs for a batch [B, L]: the downsampled waveforms
- * of two consecutive octaves (about 3/4 of the input's size; 0 for a single octave). */
+/* Bytes of device workspace nna_cqt2010v2 / nna_cqt2010 need for a batch [B, L]: the downsampled
+ * waveforms of two consecutive octaves (about 3/4 of the input's size; 0 for a single octave).
+ * Plans from nna_plan_cqt2010v2 and nna_plan_cqt2010. */
 nna_status nna_cqt2010v2_workspace(const nna_plan* plan, long long B, long long L, size_t* bytes);
 
 /* out_dev[B, n_bins, T] = constant-Q spectrogram of x_dev[B, L]; plan from nna_plan_cqt2010v2.
@@ -224,8 +239,15 @@ nna_status nna_cqt2010v2_workspace(const nna_plan* plan, long long B, long long 
 nna_status nna_cqt2010v2(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
                          void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
+/* out_dev[B, n_bins, T] = constant-Q spectrogram of x_dev[B, L]; plan from nna_plan_cqt2010.
+ * Workspace, launches (2*octaves - 1, of the STFT kernel and of the filter) and errors as for
+ * nna_cqt2010v2; an octave's waveform must also be longer than n_fft/2. */
+nna_status nna_cqt2010(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
+                       void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
 /* Downsampling CQT plans only: *part = the plan of octave `index` (0 = top; a plan as from
- * nna_plan_cqt, for nna_plan_bank / nna_plan_info / nna_plan_cqt_lengths), or with index -1 the
+ * nna_plan_cqt -- from nna_plan_cqt1992 for a plan made by nna_plan_cqt2010 -- for nna_plan_bank /
+ * nna_plan_info / nna_plan_cqt_lengths / nna_plan_spectral_kernels), or with index -1 the
  * filter as the kernel runs it: a bank of 64 rows, row r = the taps h shifted right by 2 r
  * (64 consecutive output samples per kernel frame).  The parts belong to `plan`. */
 nna_status nna_plan_part(const nna_plan* plan, int index, const nna_plan** part);

@@ -5,6 +5,14 @@ loops, double precision) through ctypes.  Only ``tests/``, the smoke check and
 the bench's ``cpu_baseline`` leg may import it; the GPU library never does and
 shares no code with it.  Function names follow the C file; every array is
 row-major with the frame axis fastest: ``[B, bins, T]``.
+
+Two transforms are written here in numpy rather than in the C file, as compositions of its
+pinned parts and numpy's FFT / matrix product: ``cqt1992`` (constant-Q transform with
+frequency-domain kernels) and ``cqt2010`` (the same per octave of a recursive downsampling).
+Parity status: ``cqt1992_spectral_kernels`` / ``cqt1992`` pinned (explicit O(N^2) sums on a tiny
+case, numpy's FFT of frames cut independently, the exact dropped-half difference from the
+time-domain CQT, tone magnitude A/2); ``cqt2010`` pinned (octave by octave against ``cqt1992`` on
+SciPy-downsampled signals, its time-domain twin, tones A/2 in every octave).
 """
 from __future__ import annotations
 
@@ -320,4 +328,68 @@ def cqt1992(x, sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, win
         return pw
     if fmt == LOG:
         return np.log(np.maximum(pw, LOG_FLOOR))
+    raise OracleError("unknown output format")
+
+
+def cqt2010(x, sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, window=WIN_HANN, n_fft=0,
+            fir_taps=FIR_TAPS, fmt=MAGNITUDE):
+    """Constant-Q spectrogram by recursive downsampling with frequency-domain kernels (Sec. III-C,
+    "Constant-Q transform (2010 version)", Fig. CQT2010), in the paper's order.  For octave a = 0 (top),
+    1, ...: the un-windowed STFT (n_fft = the padded length of the top octave's kernels, hop / 2^a) of
+    the waveform downsampled a times is multiplied with the octave's spectral kernels exactly as in
+    ``cqt1992``; then the waveform is low-pass filtered and every second sample kept (``downsample2``).
+    Octaves, bins per octave, kernel lengths, filter, frame positions and the absence of any
+    per-octave scaling are the readings of ``orc_cqt2010v2``; only the kernels' domain differs.
+    out: [B, n_bins, 1 + L // hop], lowest frequency first.
+    """
+    x = _x(x)
+    B, L = x.shape
+    b = bins_per_octave
+    n_oct = (n_bins + b - 1) // b
+    if hop % (1 << (n_oct - 1)):
+        raise OracleError("hop must be a multiple of 2^(octaves-1)")
+    N = int(n_fft) if n_fft > 0 else cqt2010_default_taps(sr, fmin, n_bins, b)
+    Q = cqt_Q(b)
+    h = lowpass_fir(fir_taps, 0.5)
+    T = 1 + L // hop
+    F = N // 2 + 1
+    n = np.arange(N)
+    dft = np.exp(-2j * np.pi * np.outer(n, np.arange(F)) / N)  # eq. (DFT2), no window: [N, F]
+    out = np.empty((B, n_bins, T), dtype=np.float64)
+    for bi in range(B):
+        xa = x[bi].astype(np.float64)
+        for a in range(n_oct):
+            hi = n_bins - a * b
+            lo = max(hi - b, 0)
+            hop_a = hop >> a
+            La = xa.size
+            if La <= N // 2:
+                raise OracleError("signal too short for this many octaves")
+            # this octave's kernels (eq. (CQT) for the bins' frequencies times 2^a), centred in N taps
+            kap = np.zeros((hi - lo, N), dtype=np.complex128)
+            for k in range(lo, hi):
+                f = fmin * 2.0 ** (float(k + a * b) / float(b))
+                Nk = int(np.ceil(Q * float(sr) / f))
+                if Nk > N:
+                    raise OracleError("n_fft is shorter than the octave's longest kernel")
+                m = np.arange(Nk)
+                w = (0.5 - 0.5 * np.cos(2 * np.pi * m / Nk)) if window == WIN_HANN else np.ones(Nk)
+                s = (N - Nk) // 2
+                kap[k - lo, s:s + Nk] = w / w.sum() * np.exp(-2j * np.pi * Q * m / Nk)
+            Y = np.conj(np.fft.fft(np.conj(kap), axis=1))[:, :F]
+            # frames of the mirrored waveform, frame t centred on sample t * hop_a
+            idx = (np.arange(T)[:, None] * hop_a + n[None, :]) - N // 2
+            idx = np.where(idx < 0, -idx, idx)
+            idx = np.where(idx >= La, 2 * (La - 1) - idx, idx)
+            X = xa[idx] @ dft                       # [T, F]
+            Xcq = (X @ Y.T) / float(N)               # [T, bins of the octave]
+            out[bi, lo:hi, :] = (Xcq.real ** 2 + Xcq.imag ** 2).T
+            if a + 1 < n_oct:
+                xa = downsample2(xa, h)
+    if fmt == MAGNITUDE:
+        return np.sqrt(out)
+    if fmt == POWER:
+        return out
+    if fmt == LOG:
+        return np.log(np.maximum(out, LOG_FLOOR))
     raise OracleError("unknown output format")

@@ -21,13 +21,14 @@ NNA_WIN_HANN, NNA_WIN_RECT = 0, 1
 NNA_MEL_SLANEY, NNA_MEL_HTK = 0, 1
 NNA_FREQ_LINEAR, NNA_FREQ_LOG = 1, 2
 NNA_PREC_F32, NNA_PREC_F16 = 0, 1
-NNA_KIND_STFT, NNA_KIND_MEL, NNA_KIND_CQT, NNA_KIND_CQT2010V2, NNA_KIND_CQT1992 = 0, 1, 2, 3, 4
+NNA_KIND_STFT, NNA_KIND_MEL, NNA_KIND_CQT, NNA_KIND_CQT2010V2, NNA_KIND_CQT1992, NNA_KIND_CQT2010 = 0, 1, 2, 3, 4, 5
 
 # every symbol include/nna.h declares
 EXPORTS = [
     "nna_plan_stft", "nna_plan_stft_prec", "nna_plan_stft_scaled", "nna_plan_mel", "nna_plan_cqt", "nna_plan_cqt2010v2", "nna_out_shape", "nna_stft", "nna_mel", "nna_cqt",
     "nna_plan_bank", "nna_plan_mel_weights", "nna_plan_info", "nna_plan_cqt_lengths", "nna_plan_sigma", "nna_cqt2010v2_workspace",
     "nna_cqt2010v2", "nna_plan_part", "nna_plan_cqt1992", "nna_cqt1992", "nna_plan_spectral_kernels",
+    "nna_plan_cqt2010", "nna_cqt2010",
     "nna_plan_destroy",
     "nna_status_str", "nna_last_error",
 ]
@@ -78,6 +79,9 @@ def lib():
         L.nna_plan_spectral_kernels.argtypes = [_VP, _c.POINTER(_c.c_double), _c.c_size_t]
         L.nna_cqt2010v2_workspace.argtypes = [_VP, _LL, _LL, _c.POINTER(_c.c_size_t)]
         L.nna_cqt2010v2.argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _c.c_size_t, _VP]
+        L.nna_cqt2010.argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _c.c_size_t, _VP]
+        L.nna_plan_cqt2010.argtypes = [PP, _c.c_int, _c.c_int, _c.c_double, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
+                                       _c.c_int, _c.c_int, _c.c_int]
         L.nna_plan_part.argtypes = [_VP, _c.c_int, PP]
         L.nna_out_shape.argtypes = [_VP, _LL, _LL, _c.POINTER(_LL), _c.POINTER(_LL)]
         for name in ("nna_stft", "nna_mel", "nna_cqt", "nna_cqt1992"):
@@ -190,6 +194,12 @@ def nna_plan_spectral_kernels(plan: Plan) -> np.ndarray:
     return out[0::2] + 1j * out[1::2]
 
 
+def nna_plan_cqt2010(sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, win=NNA_WIN_HANN, n_fft=0,
+                     fir_taps=0, fmt=NNA_OUT_MAGNITUDE, device=0) -> Plan:
+    return _new_plan(lib().nna_plan_cqt2010,
+                     (sr, hop, float(fmin), n_bins, bins_per_octave, win, n_fft, fir_taps, fmt), device)
+
+
 def nna_plan_part(plan: Plan, index: int) -> Plan:
     """Octave `index` (0 = top) of a downsampling CQT plan, or its filter bank for index -1."""
     h = _VP()
@@ -259,9 +269,7 @@ def _run(fn, plan: Plan, x, out, stream):
     return out
 
 
-def nna_cqt2010v2(plan: Plan, x, out=None, workspace=None, stream=None):
-    """out[B, n_bins, T] = constant-Q spectrogram of x[B, L] by recursive downsampling.  `workspace`: a CUDA
-    tensor of at least nna_cqt2010v2_workspace(plan, B, L) bytes (one is made here if None)."""
+def _run_octaves(cfn, plan: Plan, x, out, workspace, stream):
     import torch
 
     if not (isinstance(x, torch.Tensor) and x.is_cuda and x.dim() == 2):
@@ -274,9 +282,20 @@ def nna_cqt2010v2(plan: Plan, x, out=None, workspace=None, stream=None):
     ws_bytes = workspace.numel() * workspace.element_size()
 
     def fn(handle, xp, B, L, op, st):
-        return lib().nna_cqt2010v2(handle, xp, B, L, op, workspace.data_ptr(), ws_bytes, st)
+        return cfn(handle, xp, B, L, op, workspace.data_ptr(), ws_bytes, st)
 
     return _run(fn, plan, x, out, stream)
+
+
+def nna_cqt2010v2(plan: Plan, x, out=None, workspace=None, stream=None):
+    """out[B, n_bins, T] = constant-Q spectrogram of x[B, L] by recursive downsampling.  `workspace`: a CUDA
+    tensor of at least nna_cqt2010v2_workspace(plan, B, L) bytes (one is made here if None)."""
+    return _run_octaves(lib().nna_cqt2010v2, plan, x, out, workspace, stream)
+
+
+def nna_cqt2010(plan: Plan, x, out=None, workspace=None, stream=None):
+    """As nna_cqt2010v2, for a plan from nna_plan_cqt2010 (frequency-domain kernels per octave)."""
+    return _run_octaves(lib().nna_cqt2010, plan, x, out, workspace, stream)
 
 
 def nna_stft(plan: Plan, x, out=None, stream=None):

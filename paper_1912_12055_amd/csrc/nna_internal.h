@@ -78,6 +78,9 @@ struct StftParams {
   int n_mels;
   int n_pass;
   int mel_nyq_any;
+  // ST_MODE_LIN only: where this plan's bins go in `out`
+  long long out_wave_stride;  // elements of `out` per waveform
+  int bin_offset;             // bin 0 of this plan is row bin_offset of each waveform's output
 };
 
 struct Stft16Params {

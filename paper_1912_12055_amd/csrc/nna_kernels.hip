@@ -329,7 +329,7 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
 
   if constexpr (LIN) {
     // output rows 2q, 2q+1 = (Re, Im) of complex bin q sit in adjacent registers of one lane
-    float* __restrict__ op = P.out + (b_lane * P.out_bins) * g.T + t_lane;
+    float* __restrict__ op = P.out + b_lane * P.out_wave_stride + (long long)P.bin_offset * g.T + t_lane;
     const int f = P.fmt;
 #pragma unroll
     for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb) {

@@ -815,11 +815,11 @@ nna::FrameGeom make_geom(const nna_plan* p, const float* x, long long B, long lo
   return g;
 }
 
-nna_status run_stft_like(const nna_plan* plan, int kind, const float* x, long long B, long long L, float* out,
-                         void* stream) {
-  long long T = 0;
-  nna_status s = check_call(plan, kind, x, B, L, out, &T);
-  if (s != NNA_OK) return s;
+// One launch of the STFT kernel family: T frames of each of the B waveforms (arguments checked by the
+// caller).  out_wave_stride / bin_offset place a two-stage CQT plan's bins inside a larger output
+// (octave of a downsampling plan); 0 / 0 = the plan's own [B, bins, T].
+nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long long B, long long L, long long T,
+                         float* out, long long out_wave_stride, int bin_offset, void* stream) {
   if (plan->precision == NNA_PREC_F16) {
     const int M = pick_tile_frames(nna::H_FRAMES, T, plan->nj - 1, nna::H_LB_ROWS);
     if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
@@ -872,6 +872,8 @@ nna_status run_stft_like(const nna_plan* plan, int kind, const float* x, long lo
     P.mel_nyq_any = plan->mel_nyq_any;
   } else if (kind == NNA_KIND_CQT1992) {
     P.fmt = plan->fmt;
+    P.out_wave_stride = out_wave_stride > 0 ? out_wave_stride : (long long)plan->n_bins * T;
+    P.bin_offset = bin_offset;
     P.melw = reinterpret_cast<const float4*>(plan->d_melw);
     P.mel_mask = plan->d_mel_mask;
     P.mel_wnyq = plan->d_mel_wnyq;
@@ -888,6 +890,14 @@ nna_status run_stft_like(const nna_plan* plan, int kind, const float* x, long lo
   e = nna::launch_stft(P, mode, reinterpret_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail_hip(e, "kernel launch");
   return NNA_OK;
+}
+
+nna_status run_stft_like(const nna_plan* plan, int kind, const float* x, long long B, long long L, float* out,
+                         void* stream) {
+  long long T = 0;
+  nna_status s = check_call(plan, kind, x, B, L, out, &T);
+  if (s != NNA_OK) return s;
+  return run_stft_core(plan, kind, x, B, L, T, out, 0, 0, stream);
 }
 
 nna_status check_cqt_args(double fmin, int n_bins, int bins_per_octave, int n_taps, int fmt, int sr) {
@@ -1224,80 +1234,9 @@ nna_status nna_plan_cqt(nna_plan** plan, int sr, int hop, double fmin, int n_bin
   return make_cqt_plan(plan, sr, hop, fmin, 0, n_bins, bins_per_octave, win, center, n_taps, fmt, device);
 }
 
-nna_status nna_plan_cqt2010v2(nna_plan** plan, int sr, int hop, double fmin, int n_bins, int bins_per_octave,
-                              nna_window win, int n_taps, int fir_taps, nna_output fmt, int device) {
-  nna_status s = check_common(plan, sr, hop, win, 1, device);
-  if (s != NNA_OK) return s;
-  if ((s = check_cqt_args(fmin, n_bins, bins_per_octave, n_taps, fmt, sr)) != NNA_OK) return s;
-  if (fir_taps == 0) fir_taps = 257;
-  if (fir_taps < 3 || fir_taps > 4095 || !(fir_taps & 1))
-    return fail(NNA_ERR_INVALID_ARG, "fir_taps must be odd and in [3, 4095]");
-  const int n_oct = octaves_of(n_bins, bins_per_octave);
-  if (n_oct > 16) return fail(NNA_ERR_UNSUPPORTED, "more than 16 octaves are not supported");
-  if (hop % (1 << (n_oct - 1)) != 0)
-    return fail(NNA_ERR_INVALID_ARG, "hop must be a multiple of 2^(octaves - 1): every octave halves it");
-  int lo, hi;
-  octave_bins(n_bins, bins_per_octave, 0, lo, hi);
-  if (n_taps == 0) {
-    // next power of two >= the longest kernel of the top octave
-    const double Q = 1.0 / (std::exp2(1.0 / bins_per_octave) - 1.0);
-    const long long n0 = (long long)std::ceil(Q * (double)sr / (fmin * std::exp2((double)lo / bins_per_octave)));
-    long long t = 2;
-    while (t < n0) t <<= 1;
-    if (t > (1LL << 24)) return fail(NNA_ERR_UNSUPPORTED, "CQT kernels longer than 2^24 taps are not supported");
-    n_taps = (int)t;
-  }
-  nna_plan* p = new (std::nothrow) nna_plan;
-  if (!p) return fail(NNA_ERR_ALLOC, "out of host memory");
-  p->kind = NNA_KIND_CQT2010V2;
-  p->device = device;
-  p->sr = sr;
-  p->hop = hop;
-  p->center = 1;
-  p->window = win;
-  p->fmt = fmt;
-  p->n_bins = n_bins;
-  p->bpo = bins_per_octave;
-  p->cq_fmin = fmin;
-  p->K = n_taps;
-  p->pad = n_taps / 2;
-  p->fir_taps = fir_taps;
-  // octave a: the bins [lo, hi) one factor 2^a up the frequency axis, hop / 2^a, same taps
-  for (int a = 0; a < n_oct && s == NNA_OK; ++a) {
-    octave_bins(n_bins, bins_per_octave, a, lo, hi);
-    nna_plan* sub = nullptr;
-    s = make_cqt_plan(&sub, sr, hop >> a, fmin, lo + a * bins_per_octave, hi - lo, bins_per_octave, win, 1, n_taps,
-                      fmt, device);
-    if (s == NNA_OK) p->octave.push_back(sub);
-  }
-  if (s == NNA_OK && n_oct > 1) s = make_fir_plan(&p->fir, fir_taps, device);
-  if (s != NNA_OK) {
-    const std::string keep = g_err;
-    nna_plan_destroy(p);
-    g_err = keep;
-    return s;
-  }
-  // per frame of the output: every octave's kernels once, and hop / 2^(a+1) filter outputs for
-  // each downsampling step a -> a+1 (the filter plan counts flops per frame of FIR_ROWS outputs)
-  for (int a = 0; a < n_oct; ++a) {
-    p->exec_flops += p->octave[a]->exec_flops;
-    p->alg_flops += p->octave[a]->alg_flops;
-    if (a + 1 < n_oct) {
-      const double fir_frames = (double)(hop >> (a + 1)) / FIR_ROWS;
-      p->exec_flops += fir_frames * p->fir->exec_flops;
-      p->alg_flops += fir_frames * p->fir->alg_flops;
-    }
-  }
-  *plan = p;
-  return NNA_OK;
-}
-
-
-nna_status nna_plan_cqt1992(nna_plan** plan, int sr, int hop, double fmin, int n_bins, int bins_per_octave,
-                            nna_window win, int center, int n_fft, nna_output fmt, int device) {
-  nna_status s = check_common(plan, sr, hop, win, center, device);
-  if (s != NNA_OK) return s;
-  if ((s = check_cqt_args(fmin, n_bins, bins_per_octave, n_fft, fmt, sr)) != NNA_OK) return s;
+// two-stage CQT plan whose bin k sits at fmin 2^((k_first + k) / bins_per_octave); arguments already checked
+static nna_status make_cqt1992_plan(nna_plan** plan, int sr, int hop, double fmin, int k_first, int n_bins,
+                                    int bins_per_octave, int win, int center, int n_fft, int fmt, int device) {
   nna_plan* p = new (std::nothrow) nna_plan;
   if (!p) return fail(NNA_ERR_ALLOC, "out of host memory");
   MelDeviceLayout lin;
@@ -1313,11 +1252,12 @@ nna_status nna_plan_cqt1992(nna_plan** plan, int sr, int hop, double fmin, int n
     p->n_bins = n_bins;
     p->bpo = bins_per_octave;
     p->cq_fmin = fmin;
+    p->k_first = k_first;
     p->Q = 1.0 / (std::exp2(1.0 / bins_per_octave) - 1.0);  // eq. (Q)
     p->Nk.resize(n_bins);
     p->sk.resize(n_bins);
     for (int k = 0; k < n_bins; ++k)
-      p->Nk[k] = (long long)std::ceil(p->Q * (double)sr / (fmin * std::exp2((double)k / bins_per_octave)));  // eq. (N_k)
+      p->Nk[k] = (long long)std::ceil(p->Q * (double)sr / (fmin * std::exp2((double)(k_first + k) / bins_per_octave)));  // eq. (N_k)
     long long N = n_fft;
     if (N == 0) {
       N = 8;
@@ -1348,6 +1288,106 @@ nna_status nna_plan_cqt1992(nna_plan** plan, int sr, int hop, double fmin, int n
     return fail(NNA_ERR_ALLOC, "out of host memory while building the DFT bank and the spectral kernels");
   }
   return finish_plan(p, plan, &lin);
+}
+
+nna_status nna_plan_cqt1992(nna_plan** plan, int sr, int hop, double fmin, int n_bins, int bins_per_octave,
+                            nna_window win, int center, int n_fft, nna_output fmt, int device) {
+  nna_status s = check_common(plan, sr, hop, win, center, device);
+  if (s != NNA_OK) return s;
+  if ((s = check_cqt_args(fmin, n_bins, bins_per_octave, n_fft, fmt, sr)) != NNA_OK) return s;
+  return make_cqt1992_plan(plan, sr, hop, fmin, 0, n_bins, bins_per_octave, win, center, n_fft, fmt, device);
+}
+
+// Both downsampling plans: one sub-plan per octave (time-domain kernels: a plan as from nna_plan_cqt;
+// frequency-domain kernels: one as from nna_plan_cqt1992) and the decimation filter.
+static nna_status make_downsampling_plan(int kind, nna_plan** plan, int sr, int hop, double fmin, int n_bins,
+                                         int bins_per_octave, nna_window win, int n_taps, int fir_taps, nna_output fmt,
+                                         int device) {
+  nna_status s = check_common(plan, sr, hop, win, 1, device);
+  if (s != NNA_OK) return s;
+  if ((s = check_cqt_args(fmin, n_bins, bins_per_octave, n_taps, fmt, sr)) != NNA_OK) return s;
+  if (fir_taps == 0) fir_taps = 257;
+  if (fir_taps < 3 || fir_taps > 4095 || !(fir_taps & 1))
+    return fail(NNA_ERR_INVALID_ARG, "fir_taps must be odd and in [3, 4095]");
+  const int n_oct = octaves_of(n_bins, bins_per_octave);
+  if (n_oct > 16) return fail(NNA_ERR_UNSUPPORTED, "more than 16 octaves are not supported");
+  if (hop % (1 << (n_oct - 1)) != 0)
+    return fail(NNA_ERR_INVALID_ARG, "hop must be a multiple of 2^(octaves - 1): every octave halves it");
+  int lo, hi;
+  octave_bins(n_bins, bins_per_octave, 0, lo, hi);
+  if (n_taps == 0) {
+    // next power of two >= the longest kernel of the top octave
+    const double Q = 1.0 / (std::exp2(1.0 / bins_per_octave) - 1.0);
+    const long long n0 = (long long)std::ceil(Q * (double)sr / (fmin * std::exp2((double)lo / bins_per_octave)));
+    long long t = 2;
+    while (t < n0) t <<= 1;
+    if (t > (1LL << 24)) return fail(NNA_ERR_UNSUPPORTED, "CQT kernels longer than 2^24 taps are not supported");
+    n_taps = (int)t;
+    if (kind == NNA_KIND_CQT2010 && n_taps < 8) n_taps = 8;
+  }
+  nna_plan* p = new (std::nothrow) nna_plan;
+  if (!p) return fail(NNA_ERR_ALLOC, "out of host memory");
+  p->kind = kind;
+  p->device = device;
+  p->sr = sr;
+  p->hop = hop;
+  p->center = 1;
+  p->window = win;
+  p->fmt = fmt;
+  p->n_bins = n_bins;
+  p->bpo = bins_per_octave;
+  p->cq_fmin = fmin;
+  p->K = n_taps;
+  p->pad = n_taps / 2;
+  p->fir_taps = fir_taps;
+  // octave a: the bins [lo, hi) one factor 2^a up the frequency axis, hop / 2^a, same taps
+  for (int a = 0; a < n_oct && s == NNA_OK; ++a) {
+    octave_bins(n_bins, bins_per_octave, a, lo, hi);
+    nna_plan* sub = nullptr;
+    if (kind == NNA_KIND_CQT2010V2)
+      s = make_cqt_plan(&sub, sr, hop >> a, fmin, lo + a * bins_per_octave, hi - lo, bins_per_octave, win, 1, n_taps,
+                        fmt, device);
+    else
+      s = make_cqt1992_plan(&sub, sr, hop >> a, fmin, lo + a * bins_per_octave, hi - lo, bins_per_octave, win, 1,
+                            n_taps, fmt, device);
+    if (s == NNA_OK) p->octave.push_back(sub);
+  }
+  if (s == NNA_OK && n_oct > 1) s = make_fir_plan(&p->fir, fir_taps, device);
+  if (s != NNA_OK) {
+    const std::string keep = g_err;
+    nna_plan_destroy(p);
+    g_err = keep;
+    return s;
+  }
+  // per frame of the output: every octave's kernels once, and hop / 2^(a+1) filter outputs for
+  // each downsampling step a -> a+1 (the filter plan counts flops per frame of FIR_ROWS outputs)
+  for (int a = 0; a < n_oct; ++a) {
+    p->exec_flops += p->octave[a]->exec_flops;
+    p->alg_flops += p->octave[a]->alg_flops;
+    if (a + 1 < n_oct) {
+      const double fir_frames = (double)(hop >> (a + 1)) / FIR_ROWS;
+      p->exec_flops += fir_frames * p->fir->exec_flops;
+      p->alg_flops += fir_frames * p->fir->alg_flops;
+    }
+  }
+  *plan = p;
+  return NNA_OK;
+}
+
+nna_status nna_plan_cqt2010v2(nna_plan** plan, int sr, int hop, double fmin, int n_bins, int bins_per_octave,
+                              nna_window win, int n_taps, int fir_taps, nna_output fmt, int device) {
+  return make_downsampling_plan(NNA_KIND_CQT2010V2, plan, sr, hop, fmin, n_bins, bins_per_octave, win, n_taps, fir_taps,
+                                fmt, device);
+}
+
+nna_status nna_plan_cqt2010(nna_plan** plan, int sr, int hop, double fmin, int n_bins, int bins_per_octave,
+                            nna_window win, int n_fft, int fir_taps, nna_output fmt, int device) {
+  if (n_fft != 0 && (n_fft < 8 || (n_fft & (n_fft - 1)))) {
+    if (plan) *plan = nullptr;
+    return fail(NNA_ERR_INVALID_ARG, "n_fft must be a power of two >= 8 (0 picks the smallest that holds the longest top-octave kernel)");
+  }
+  return make_downsampling_plan(NNA_KIND_CQT2010, plan, sr, hop, fmin, n_bins, bins_per_octave, win, n_fft, fir_taps,
+                                fmt, device);
 }
 
 nna_status nna_cqt1992(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev, void* hip_stream) {
@@ -1400,7 +1440,8 @@ nna_status nna_plan_spectral_kernels(const nna_plan* plan, double* host_out, siz
 
 nna_status nna_cqt2010v2_workspace(const nna_plan* plan, long long B, long long L, size_t* bytes) {
   if (!plan || !bytes) return fail(NNA_ERR_INVALID_ARG, "plan / bytes is NULL");
-  if (plan->kind != NNA_KIND_CQT2010V2) return fail(NNA_ERR_INVALID_ARG, "plan was built for a different transform");
+  if (plan->kind != NNA_KIND_CQT2010V2 && plan->kind != NNA_KIND_CQT2010)
+    return fail(NNA_ERR_INVALID_ARG, "plan was built for a different transform");
   if (B < 1 || L < 1) return fail(NNA_ERR_SHAPE, "B and L must be >= 1");
   const int n_oct = (int)plan->octave.size();
   const long long L1 = (L + 1) / 2, L2 = (L1 + 1) / 2;
@@ -1408,10 +1449,11 @@ nna_status nna_cqt2010v2_workspace(const nna_plan* plan, long long B, long long 
   return NNA_OK;
 }
 
-nna_status nna_cqt2010v2(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
-                         void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+// the octave loop of both downsampling plans (time-domain or frequency-domain kernels per octave)
+static nna_status run_octaves(const nna_plan* plan, int kind, const float* x_dev, long long B, long long L,
+                              float* out_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
   if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
-  if (plan->kind != NNA_KIND_CQT2010V2) return fail(NNA_ERR_INVALID_ARG, "plan was built for a different transform");
+  if (plan->kind != kind) return fail(NNA_ERR_INVALID_ARG, "plan was built for a different transform");
   if (!x_dev || !out_dev) return fail(NNA_ERR_INVALID_ARG, "x_dev / out_dev is NULL");
   if (plan->device < 0) return fail(NNA_ERR_UNSUPPORTED, "host-only plan (device = -1) cannot run transforms");
   if (B < 1) return fail(NNA_ERR_SHAPE, "B must be >= 1");
@@ -1436,8 +1478,12 @@ nna_status nna_cqt2010v2(const nna_plan* plan, const float* x_dev, long long B, 
   for (int a = 0; a < n_oct; ++a) {
     int lo, hi;
     octave_bins(plan->n_bins, plan->bpo, a, lo, hi);
-    if ((s = run_conv(plan->octave[a], cur, B, La[a], T, out_dev, (long long)plan->n_bins * T, lo, 0, hip_stream)) != NNA_OK)
-      return s;
+    if (kind == NNA_KIND_CQT2010V2)
+      s = run_conv(plan->octave[a], cur, B, La[a], T, out_dev, (long long)plan->n_bins * T, lo, 0, hip_stream);
+    else
+      s = run_stft_core(plan->octave[a], NNA_KIND_CQT1992, cur, B, La[a], T, out_dev, (long long)plan->n_bins * T, lo,
+                        hip_stream);
+    if (s != NNA_OK) return s;
     if (a + 1 < n_oct) {
       float* dst = buf[a & 1];
       const long long Ln = La[a + 1];
@@ -1449,10 +1495,21 @@ nna_status nna_cqt2010v2(const nna_plan* plan, const float* x_dev, long long B, 
   return NNA_OK;
 }
 
+nna_status nna_cqt2010v2(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
+                         void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+  return run_octaves(plan, NNA_KIND_CQT2010V2, x_dev, B, L, out_dev, workspace_dev, workspace_bytes, hip_stream);
+}
+
+nna_status nna_cqt2010(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
+                       void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+  return run_octaves(plan, NNA_KIND_CQT2010, x_dev, B, L, out_dev, workspace_dev, workspace_bytes, hip_stream);
+}
+
 nna_status nna_plan_part(const nna_plan* plan, int index, const nna_plan** part) {
   if (!plan || !part) return fail(NNA_ERR_INVALID_ARG, "plan / part is NULL");
   *part = nullptr;
-  if (plan->kind != NNA_KIND_CQT2010V2) return fail(NNA_ERR_INVALID_ARG, "not a downsampling CQT plan");
+  if (plan->kind != NNA_KIND_CQT2010V2 && plan->kind != NNA_KIND_CQT2010)
+    return fail(NNA_ERR_INVALID_ARG, "not a downsampling CQT plan");
   if (index == -1) {
     if (!plan->fir) return fail(NNA_ERR_INVALID_ARG, "a single-octave plan has no filter");
     *part = plan->fir;
@@ -1466,7 +1523,7 @@ nna_status nna_plan_part(const nna_plan* plan, int index, const nna_plan** part)
 nna_status nna_out_shape(const nna_plan* plan, long long B, long long L, long long* n_bins, long long* n_frames) {
   if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
   if (B < 1) return fail(NNA_ERR_SHAPE, "B must be >= 1");
-  if (plan->kind == NNA_KIND_CQT2010V2) {
+  if (plan->kind == NNA_KIND_CQT2010V2 || plan->kind == NNA_KIND_CQT2010) {
     std::vector<long long> La;
     if (L < 1 || !cqt2010_lengths(plan, L, La))
       return fail(NNA_ERR_SHAPE, "L is too short: every octave's waveform must exceed the reflection padding");
@@ -1501,7 +1558,8 @@ nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long l
 
 nna_status nna_plan_bank(const nna_plan* plan, double* host_out, size_t cap) {
   if (!plan || !host_out) return fail(NNA_ERR_INVALID_ARG, "plan / host_out is NULL");
-  if (plan->kind == NNA_KIND_CQT2010V2) return fail(NNA_ERR_INVALID_ARG, "a downsampling CQT plan holds several banks");
+  if (plan->kind == NNA_KIND_CQT2010V2 || plan->kind == NNA_KIND_CQT2010)
+    return fail(NNA_ERR_INVALID_ARG, "a downsampling CQT plan holds several banks");
   const long long rows = plan->kind == NNA_KIND_CQT ? (long long)plan->conv_rows : 2LL * (plan->freq_scale ? plan->n_half : plan->n_half + 1);
   const long long K = plan->K;
   if ((unsigned long long)cap < (unsigned long long)(rows * K)) return fail(NNA_ERR_INVALID_ARG, "host_out is too small");
@@ -1641,7 +1699,7 @@ nna_status nna_plan_info(const nna_plan* plan, int* kind, long long* bank_rows, 
   if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
   if (kind) *kind = plan->kind;
   if (bank_rows)
-    *bank_rows = plan->kind == NNA_KIND_CQT2010V2 ? 0
+    *bank_rows = plan->kind == NNA_KIND_CQT2010V2 || plan->kind == NNA_KIND_CQT2010 ? 0
                  : plan->kind == NNA_KIND_CQT     ? (long long)plan->conv_rows
                                                   : 2LL * (plan->freq_scale ? plan->n_half : plan->n_half + 1);
   if (taps) *taps = plan->K;

@@ -476,6 +476,51 @@ def test_cqt1992_rejects_wrong_plan_and_short_input(nb):
     assert ei.value.status == nb.NNA_ERR_INVALID_ARG
 
 
+@pytest.mark.parametrize("case", CQT2010_CASES, ids=[c[0] for c in CQT2010_CASES])
+def test_cqt2010_parity_small(nb, case):
+    # the same shapes as the time-domain flavour (its n_taps, where given, is a power of two and serves as n_fft)
+    name, B, L, sr, hop, fmin, n_bins, bpo, n_fft, fir_taps, fmt = case
+    _say(f"cqt2010 {name}: B={B} L={L} sr={sr} hop={hop} bins={n_bins}/{bpo} n_fft={n_fft} fir={fir_taps} fmt={fmt}")
+    x = _rand(B, L, 2010 + n_bins)
+    plan = nb.nna_plan_cqt2010(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, n_fft=n_fft,
+                               fir_taps=fir_taps, fmt=fmt, device=0)
+    got = nb.nna_cqt2010(plan, _dev(x)).cpu().numpy()
+    kw = dict(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, n_fft=n_fft,
+              fir_taps=fir_taps or oracle.FIR_TAPS)
+    ref = oracle.cqt2010(x, fmt=fmt, **kw)
+    if fmt == 2:
+        # log output: compare the magnitudes it encodes (ln amplifies the error of small powers without bound)
+        got, ref = np.exp(0.5 * got.astype(np.float64)), np.exp(0.5 * ref)
+    e = _rel_err(got, ref)
+    n_oct = -(-n_bins // bpo)
+    for a in range(n_oct):  # every octave against its own peak too
+        hi = n_bins - a * bpo
+        lo = max(0, hi - bpo)
+        e = max(e, _rel_err(got[:, lo:hi], ref[:, lo:hi]))
+    _say(f"  rel err {e:.3e}")
+    assert e < TOL
+
+
+def test_cqt2010_tone_closed_form_and_wrong_entry_point_on_gpu(nb):
+    _say("cqt2010 closed form tones")
+    sr, A = 22050, 0.6
+    _, fk = oracle.cqt_lengths(sr, 32.70, 84, 12)
+    ks = [3, 30, 50, 71, 83]
+    x = _dev(np.stack([signals.tone(22050, sr, fk[k], amp=A) for k in ks]))
+    plan = nb.nna_plan_cqt2010(sr=sr, device=0)
+    got = nb.nna_cqt2010(plan, x).cpu().numpy()
+    for i, k in enumerate(ks):
+        mid = got[i, :, 15:30]
+        assert np.all(mid.argmax(axis=0) == k)
+        assert np.allclose(mid[k], A / 2, rtol=1e-2)
+    with pytest.raises(nb.NnaError) as e:
+        nb.nna_cqt2010v2(plan, x)
+    assert e.value.status == nb.NNA_ERR_INVALID_ARG
+    with pytest.raises(nb.NnaError) as e:
+        nb.nna_cqt2010(plan, x[:, :4000].contiguous())  # the deepest octave would have 63 samples
+    assert e.value.status == nb.NNA_ERR_SHAPE
+
+
 # ---------------------------------------------------------------------------------------
 # The two 1,770-waveform workloads at full size, in the launch configuration the bench times;
 # the oracle checks a sample of whole waveforms (first, second, middle, last two).

@@ -283,3 +283,42 @@ def test_cqt1992_argument_checking():
     assert _status(nb.nna_plan_cqt1992, **{**kw, "n_bins": 80}) == nb.NNA_ERR_INVALID_ARG  # top bin above sr/2
     p = nb.nna_plan_cqt(sr=22050, hop=256, fmin=220.0, n_bins=36, device=-1)
     assert _status(nb.nna_plan_spectral_kernels, p) == nb.NNA_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("sr,hop,fmin,n_bins,bpo,fir", [(22050, 512, 32.70, 84, 12, 0), (16000, 64, 220.0, 29, 12, 63)])
+def test_cqt2010_plan_parts(sr, hop, fmin, n_bins, bpo, fir):
+    p = nb.nna_plan_cqt2010(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, fir_taps=fir, device=-1)
+    info = p.info()
+    N = oracle.cqt2010_default_taps(sr, fmin, n_bins, bpo)
+    assert (info["kind"], info["taps"], info["out_bins"]) == (nb.NNA_KIND_CQT2010, N, n_bins)
+    n_oct = (n_bins + bpo - 1) // bpo
+    L = 22050
+    assert nb.nna_out_shape(p, 2, L) == (n_bins, 1 + L // hop)
+    assert nb.nna_cqt2010v2_workspace(p, 2, L) == nb.nna_cqt2010v2_workspace(
+        nb.nna_plan_cqt2010v2(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, fir_taps=fir, device=-1), 2, L)
+    flops = 0.0
+    for a in range(n_oct):
+        hi = n_bins - a * bpo
+        lo = max(hi - bpo, 0)
+        sub = nb.nna_plan_part(p, a)
+        si = sub.info()
+        assert (si["kind"], si["taps"], si["out_bins"]) == (nb.NNA_KIND_CQT1992, N, hi - lo)
+        # the octave's spectral kernels: those of the one-rate transform for its bins' frequencies x 2^a
+        want = oracle.cqt1992_spectral_kernels(sr, fmin * 2.0 ** ((lo + a * bpo) / bpo), hi - lo, bpo, n_fft=N) / N
+        got = nb.nna_plan_spectral_kernels(sub)
+        np.testing.assert_allclose(got, want, atol=2e-7 * np.abs(want).max())
+        flops += si["algorithmic_flops_per_frame"]
+    if n_oct > 1:
+        fir_plan = nb.nna_plan_part(p, -1)
+        flops += sum((hop >> (a + 1)) / 64 * fir_plan.info()["algorithmic_flops_per_frame"] for a in range(n_oct - 1))
+    assert abs(info["algorithmic_flops_per_frame"] - flops) < 1e-6 * flops
+    assert _status(nb.nna_plan_bank, p) == nb.NNA_ERR_INVALID_ARG
+
+
+def test_cqt2010_argument_checking():
+    kw = dict(sr=22050, fmin=32.70, n_bins=84, bins_per_octave=12, device=-1)
+    assert _status(nb.nna_plan_cqt2010, hop=512, **kw) == nb.NNA_OK
+    assert _status(nb.nna_plan_cqt2010, hop=96, **kw) == nb.NNA_ERR_INVALID_ARG  # 7 octaves need hop % 64 == 0
+    assert _status(nb.nna_plan_cqt2010, hop=512, n_fft=128, **kw) == nb.NNA_ERR_INVALID_ARG  # top octave: 178 taps
+    assert _status(nb.nna_plan_cqt2010, hop=512, n_fft=300, **kw) == nb.NNA_ERR_INVALID_ARG  # not a power of two
+    assert _status(nb.nna_plan_cqt2010, hop=512, fir_taps=64, **kw) == nb.NNA_ERR_INVALID_ARG
