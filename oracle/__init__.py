@@ -393,3 +393,83 @@ def cqt2010(x, sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, win
     if fmt == LOG:
         return np.log(np.maximum(out, LOG_FLOOR))
     raise OracleError("unknown output format")
+
+
+# ---------------------------------------------------------------------------------------
+# Trainable Fourier kernels (Sec. IV-C, "Trainable Transformation Kernels"): the STFT layer with an
+# arbitrary kernel bank, and the gradients of a scalar loss through it.
+# ---------------------------------------------------------------------------------------
+def _frame_index(L, K, hop, center):
+    """[T, K] index of the stored sample behind tap n of frame t (mirror reflection when centred)."""
+    T = num_frames(L, K, hop, center)
+    if T < 1:
+        raise OracleError("signal too short")
+    pad = K // 2 if center else 0
+    idx = np.arange(T)[:, None] * hop + np.arange(K)[None, :] - pad
+    idx = np.where(idx < 0, -idx, idx)
+    idx = np.where(idx >= L, 2 * (L - 1) - idx, idx)
+    return idx
+
+
+def stft_bank(x, W, hop=512, center=True, fmt=MAGNITUDE):
+    """The STFT layer with a given kernel bank (Sec. III-A with the kernels as weights, Sec. IV-C):
+    W[2F, K], row 2k = real-part kernel and row 2k+1 = imaginary-part kernel of bin k (window folded
+    in, as eq. (DFT2) initialises them).  C[b, r, t] = sum_n W[r, n] xp_b[t hop + n] (the strided
+    convolution of Sec. III-A with its kernel flip folded away), out[b, k, t] = the format applied to
+    C[b, 2k, t]^2 + C[b, 2k+1, t]^2.  out: [B, F, T]."""
+    x = _x(x).astype(np.float64)
+    W = np.ascontiguousarray(W, dtype=np.float64)
+    K = W.shape[1]
+    idx = _frame_index(x.shape[1], K, hop, center)
+    out = []
+    for b in range(x.shape[0]):
+        C = x[b][idx] @ W.T                      # [T, 2F]
+        pw = C[:, 0::2] ** 2 + C[:, 1::2] ** 2   # [T, F]
+        out.append(pw.T)
+    pw = np.stack(out)
+    if fmt == MAGNITUDE:
+        return np.sqrt(pw)
+    if fmt == POWER:
+        return pw
+    if fmt == LOG:
+        return np.log(np.maximum(pw, LOG_FLOOR))
+    raise OracleError("unknown output format")
+
+
+def stft_bank_backward(x, W, gout, hop=512, center=True, fmt=MAGNITUDE):
+    """Gradients of a scalar loss through ``stft_bank`` by the chain rule, given gout = dLoss/dout
+    [B, F, T]: returns (gW [2F, K], gx [B, L]).
+
+    With P = Re^2 + Im^2:  magnitude: d out/d Re = Re / sqrt(P) (0 where P = 0);  power: 2 Re;
+    log: 2 Re / P where P exceeds the floor, else 0 -- and likewise for Im.  G[b, r, t] = dLoss/dC.
+    gW[r, n] = sum_{b,t} G[b, r, t] xp_b[t hop + n];   gx_b[j] = sum over all (t, n) whose padded
+    sample t hop + n mirrors onto j of sum_r W[r, n] G[b, r, t] (the transposed strided convolution,
+    with the reflection padding folded back)."""
+    x = _x(x).astype(np.float64)
+    W = np.ascontiguousarray(W, dtype=np.float64)
+    gout = np.ascontiguousarray(gout, dtype=np.float64)
+    B, L = x.shape
+    K = W.shape[1]
+    idx = _frame_index(L, K, hop, center)
+    gW = np.zeros_like(W)
+    gx = np.zeros_like(x)
+    for b in range(B):
+        X = x[b][idx]                            # [T, K]
+        C = X @ W.T                              # [T, 2F]
+        re, im = C[:, 0::2], C[:, 1::2]
+        pw = re ** 2 + im ** 2
+        g = gout[b].T                            # [T, F]
+        if fmt == MAGNITUDE:
+            s = np.where(pw > 0, g / np.sqrt(np.where(pw > 0, pw, 1.0)), 0.0)
+        elif fmt == POWER:
+            s = 2.0 * g
+        elif fmt == LOG:
+            s = np.where(pw > LOG_FLOOR, 2.0 * g / np.where(pw > LOG_FLOOR, pw, 1.0), 0.0)
+        else:
+            raise OracleError("unknown output format")
+        G = np.empty_like(C)
+        G[:, 0::2] = s * re
+        G[:, 1::2] = s * im
+        gW += G.T @ X
+        np.add.at(gx[b], idx, G @ W)
+    return gW, gx

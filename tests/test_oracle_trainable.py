@@ -1,0 +1,112 @@
+"""Pins for the oracle's STFT layer with a given kernel bank and its gradients (CPU only).
+
+Sec. IV-C ("Trainable Transformation Kernels").  The forward is pinned to the already pinned
+windowed-DFT oracle through a bank written out here from eq. (DFT2); the gradients to central
+finite differences of that forward (float64, so a correct derivative agrees to ~1e-8) and to closed
+forms of one-frame cases.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1912_12055_amd import signals
+
+
+def _dft_bank(N, window=True):
+    n = np.arange(N)
+    w = 0.5 - 0.5 * np.cos(2 * np.pi * n / N) if window else np.ones(N)
+    W = np.empty((N + 2, N))
+    for k in range(N // 2 + 1):
+        W[2 * k] = w * np.cos(2 * np.pi * k * n / N)
+        W[2 * k + 1] = -w * np.sin(2 * np.pi * k * n / N)
+    W[1] = 0.0      # sin(0) and sin(pi n): identically zero rows (floating point leaves 1e-16 in the latter)
+    W[N + 1] = 0.0
+    return W
+
+
+@pytest.mark.parametrize("fmt", [oracle.MAGNITUDE, oracle.POWER, oracle.LOG])
+@pytest.mark.parametrize("center", [True, False])
+def test_forward_with_the_dft_bank_is_the_stft(fmt, center):
+    x = signals.batch(1, B=2, L=700)
+    got = oracle.stft_bank(x, _dft_bank(64), hop=16, center=center, fmt=fmt)
+    ref = oracle.stft(x, n_fft=64, hop=16, center=center, fmt=fmt)
+    np.testing.assert_allclose(got, ref, rtol=1e-9, atol=1e-12)
+
+
+@pytest.mark.parametrize("fmt", [oracle.MAGNITUDE, oracle.POWER, oracle.LOG])
+@pytest.mark.parametrize("center,hop", [(True, 8), (False, 8), (True, 5)])
+def test_gradients_against_central_differences(fmt, center, hop):
+    rng = np.random.default_rng(7 + fmt)
+    K, F, B, L = 16, 5, 2, 61
+    W = rng.standard_normal((2 * F, K))
+    x = rng.standard_normal((B, L)).astype(np.float32)
+    out = oracle.stft_bank(x, W, hop=hop, center=center, fmt=fmt)
+    gout = rng.standard_normal(out.shape)
+
+    def loss(Wv, xv):
+        return float(np.sum(gout * _forward64(xv, Wv, hop, center, fmt)))
+
+    gW, gx = oracle.stft_bank_backward(x, W, gout, hop=hop, center=center, fmt=fmt)
+    assert gW.shape == W.shape and gx.shape == x.shape
+    eps = 1e-6
+    x64 = x.astype(np.float64)
+    for _ in range(25):
+        r, n = rng.integers(2 * F), rng.integers(K)
+        Wp, Wm = W.copy(), W.copy()
+        Wp[r, n] += eps
+        Wm[r, n] -= eps
+        num = (loss(Wp, x64) - loss(Wm, x64)) / (2 * eps)
+        assert abs(num - gW[r, n]) < 1e-6 * max(1.0, abs(num)), (r, n, num, gW[r, n])
+    for _ in range(25):
+        b, j = rng.integers(B), rng.integers(L)
+        xp, xm = x64.copy(), x64.copy()
+        xp[b, j] += eps
+        xm[b, j] -= eps
+        num = (loss(W, xp) - loss(W, xm)) / (2 * eps)
+        assert abs(num - gx[b, j]) < 1e-6 * max(1.0, abs(num)), (b, j, num, gx[b, j])
+
+
+def _forward64(x64, W, hop, center, fmt):
+    """The layer's definition written out with loops for float64 input (the oracle's entry point takes
+    float32 waveforms, which would swamp a 1e-6 perturbation)."""
+    B, L = x64.shape
+    K = W.shape[1]
+    pad = K // 2 if center else 0
+    T = 1 + (L + 2 * pad - K) // hop
+    out = np.empty((B, W.shape[0] // 2, T))
+    for b in range(B):
+        for t in range(T):
+            fr = np.empty(K)
+            for n in range(K):
+                j = t * hop + n - pad
+                j = -j if j < 0 else (2 * (L - 1) - j if j >= L else j)
+                fr[n] = x64[b, j]
+            C = W @ fr
+            pw = C[0::2] ** 2 + C[1::2] ** 2
+            out[b, :, t] = np.sqrt(pw) if fmt == oracle.MAGNITUDE else pw if fmt == oracle.POWER else np.log(np.maximum(pw, oracle.LOG_FLOOR))
+    return out
+
+
+def test_one_frame_power_closed_form():
+    # one frame, no padding, power output, loss = sum of the output: gW[r] = 2 C[r] x, gx = 2 W^T C
+    rng = np.random.default_rng(3)
+    K, F = 12, 4
+    W = rng.standard_normal((2 * F, K))
+    x = rng.standard_normal((1, K)).astype(np.float32)
+    gW, gx = oracle.stft_bank_backward(x, W, np.ones((1, F, 1)), hop=4, center=False, fmt=oracle.POWER)
+    C = W @ x[0].astype(np.float64)
+    np.testing.assert_allclose(gW, 2 * np.outer(C, x[0]), rtol=1e-12)
+    np.testing.assert_allclose(gx[0], 2 * W.T @ C, rtol=1e-12)
+
+
+def test_zero_sine_rows_of_the_dft_bank_get_no_gradient():
+    # bins 0 and N/2 of eq. (DFT2) have identically zero sine kernels: Im = 0 there, and
+    # d|X|/dIm = Im/|X| = 0, so those two rows stay zero under training (magnitude and power)
+    N = 32
+    x = signals.batch(1, B=2, L=300)
+    W = _dft_bank(N)
+    for fmt in (oracle.MAGNITUDE, oracle.POWER):
+        gout = np.random.default_rng(fmt).standard_normal((2, N // 2 + 1, 1 + 300 // 8))
+        gW, _ = oracle.stft_bank_backward(x, W, gout, hop=8, fmt=fmt)
+        assert np.all(gW[1] == 0) and np.all(gW[N + 1] == 0)
+        assert np.abs(gW[0]).max() > 0 and np.abs(gW[N]).max() > 0
