@@ -25,7 +25,7 @@
  *   - Transform calls allocate nothing, do not synchronise and return as soon as the
  *     kernel is enqueued on `hip_stream` (a hipStream_t cast to void*; NULL = the
  *     default stream).  Plans are immutable after creation and may be shared
- *     between threads.
+ *     between threads (the one exception, nna_plan_set_bank, says so).
  *   - Every function returns an nna_status; on failure nothing is enqueued, an
  *     output plan pointer is set to NULL and nna_last_error() describes the problem
  *     (thread-local text).  Nothing throws or aborts across this boundary.
@@ -244,6 +244,49 @@ nna_status nna_cqt2010v2(const nna_plan* plan, const float* x_dev, long long B, 
  * nna_cqt2010v2; an octave's waveform must also be longer than n_fft/2. */
 nna_status nna_cqt2010(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
                        void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Trainable Fourier kernels (Sec. IV-C, "Trainable Transformation Kernels"): the STFT layer's kernel
+ * bank as a parameter that a training loop reads, updates and differentiates through.  Plans from
+ * nna_plan_stft and nna_plan_stft_scaled (float32).  The bank's logical layout is the layer's weight
+ * W[2 F, K], float32 row-major on the device: row 2k = real-part kernel, row 2k+1 = imaginary-part
+ * kernel of bin k, K = n_fft taps, F = the plan's output bins.  For a plan from nna_plan_stft rows 1
+ * and 2F-1 (the sine kernels of bins 0 and n_fft/2, identically zero in eq. (DFT2)) are not
+ * parameters: they read as zero, writes to them are ignored and their gradient is zero -- which is
+ * also what training would give, since d|X|/dIm = Im/|X| vanishes where Im is zero.
+ *
+ * nna_plan_trainable  makes a plan trainable: allocates a second, row-major device copy of its bank
+ *                     (the only allocation of this group; synchronises).  Idempotent.
+ * nna_plan_get_bank   w_dev[2F, K] = the current bank.
+ * nna_plan_set_bank   the bank = w_dev[2F, K] (after an optimiser step).  The plan is modified: no
+ *                     transform using it may be in flight on another stream.  Kernels written here
+ *                     need not be DFT kernels; nna_stft then computes out = format(C[2k]^2 + C[2k+1]^2),
+ *                     C[r, t] = sum_n W[r, n] xp[t hop + n].
+ * nna_stft_backward   given gout_dev[B, F, T] = dLoss/d(output of nna_stft for x_dev), writes
+ *                     gw_dev[2F, K] = dLoss/dW and/or gx_dev[B, L] = dLoss/dx (either may be NULL):
+ *                       G[r, f]  = dLoss/dC: gout times the output format's derivative -- magnitude
+ *                                  Re/|X| (0 where |X| = 0), power 2 Re, log 2 Re/P where the power P
+ *                                  exceeds the logarithm's floor (else 0); likewise Im;
+ *                       gw[r, n] = sum over all frames f of G[r, f] xp[f hop + n];
+ *                       gx[j]    = sum over all (t, n) whose padded sample t hop + n mirrors onto j
+ *                                  of sum_r W[r, n] G[r, t].
+ *                     Both outputs are overwritten (zeroed, then accumulated with float atomic adds:
+ *                     the last bits may differ between runs).  workspace_dev: caller-owned device
+ *                     memory, 256-byte aligned, of nna_stft_backward_workspace bytes (G itself:
+ *                     128-row-padded bank rows x frames x 4 bytes); nothing is allocated, four to
+ *                     six kernels are enqueued on hip_stream.  The forward pass is recomputed inside,
+ *                     so nothing needs to be kept from nna_stft.
+ * Errors: NNA_ERR_INVALID_ARG for a plan of another kind or one not made trainable, NULL pointers, a
+ * small or misaligned workspace; NNA_ERR_UNSUPPORTED for float16 or host-only plans; NNA_ERR_SHAPE as
+ * for nna_stft.
+ */
+nna_status nna_plan_trainable(nna_plan* plan);
+nna_status nna_plan_get_bank(const nna_plan* plan, float* w_dev, void* hip_stream);
+nna_status nna_plan_set_bank(nna_plan* plan, const float* w_dev, void* hip_stream);
+nna_status nna_stft_backward_workspace(const nna_plan* plan, long long B, long long L, size_t* bytes);
+nna_status nna_stft_backward(const nna_plan* plan, const float* x_dev, long long B, long long L,
+                             const float* gout_dev, float* gw_dev, float* gx_dev, void* workspace_dev,
+                             size_t workspace_bytes, void* hip_stream);
 
 /* Downsampling CQT plans only: *part = the plan of octave `index` (0 = top; a plan as from
  * nna_plan_cqt -- from nna_plan_cqt1992 for a plan made by nna_plan_cqt2010 -- for nna_plan_bank /

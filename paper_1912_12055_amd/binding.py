@@ -29,6 +29,7 @@ EXPORTS = [
     "nna_plan_bank", "nna_plan_mel_weights", "nna_plan_info", "nna_plan_cqt_lengths", "nna_plan_sigma", "nna_cqt2010v2_workspace",
     "nna_cqt2010v2", "nna_plan_part", "nna_plan_cqt1992", "nna_cqt1992", "nna_plan_spectral_kernels",
     "nna_plan_cqt2010", "nna_cqt2010",
+    "nna_plan_trainable", "nna_plan_get_bank", "nna_plan_set_bank", "nna_stft_backward_workspace", "nna_stft_backward",
     "nna_plan_destroy",
     "nna_status_str", "nna_last_error",
 ]
@@ -83,6 +84,11 @@ def lib():
         L.nna_plan_cqt2010.argtypes = [PP, _c.c_int, _c.c_int, _c.c_double, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
                                        _c.c_int, _c.c_int, _c.c_int]
         L.nna_plan_part.argtypes = [_VP, _c.c_int, PP]
+        L.nna_plan_trainable.argtypes = [_VP]
+        L.nna_plan_get_bank.argtypes = [_VP, _VP, _VP]
+        L.nna_plan_set_bank.argtypes = [_VP, _VP, _VP]
+        L.nna_stft_backward_workspace.argtypes = [_VP, _LL, _LL, _c.POINTER(_c.c_size_t)]
+        L.nna_stft_backward.argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _VP, _VP, _c.c_size_t, _VP]
         L.nna_out_shape.argtypes = [_VP, _LL, _LL, _c.POINTER(_LL), _c.POINTER(_LL)]
         for name in ("nna_stft", "nna_mel", "nna_cqt", "nna_cqt1992"):
             getattr(L, name).argtypes = [_VP, _VP, _LL, _LL, _VP, _VP]
@@ -317,3 +323,71 @@ def nna_cqt1992(plan: Plan, x, out=None, stream=None):
 def nna_cqt(plan: Plan, x, out=None, stream=None):
     """out[B, n_bins, T] = constant-Q spectrogram of x[B, L]."""
     return _run(lib().nna_cqt, plan, x, out, stream)
+
+
+# ---- trainable Fourier kernels -------------------------------------------------------------------
+def nna_plan_trainable(plan: Plan) -> Plan:
+    _check(lib().nna_plan_trainable(plan.handle))
+    return plan
+
+
+def _bank_shape(plan: Plan):
+    i = plan.info()
+    return (2 * i["out_bins"], i["taps"])
+
+
+def _stream_of(t, stream):
+    import torch
+
+    return torch.cuda.current_stream(t.device).cuda_stream if stream is None else stream
+
+
+def nna_plan_get_bank(plan: Plan, out=None, stream=None):
+    """W[2F, K]: the plan's kernel bank as a float32 CUDA tensor (logical layout)."""
+    import torch
+
+    shape = _bank_shape(plan)
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float32, device=f"cuda:{plan.device}")
+    elif not (out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and tuple(out.shape) == shape):
+        raise TypeError(f"out must be a contiguous float32 CUDA tensor of shape {shape}")
+    _check(lib().nna_plan_get_bank(plan.handle, out.data_ptr(), _stream_of(out, stream)))
+    return out
+
+
+def nna_plan_set_bank(plan: Plan, W, stream=None):
+    shape = _bank_shape(plan)
+    if not (W.is_cuda and W.dtype.is_floating_point and W.element_size() == 4 and W.is_contiguous()
+            and tuple(W.shape) == shape and W.device.index == plan.device):
+        raise TypeError(f"W must be a contiguous float32 CUDA tensor of shape {shape} on the plan's device")
+    _check(lib().nna_plan_set_bank(plan.handle, W.data_ptr(), _stream_of(W, stream)))
+
+
+def nna_stft_backward_workspace(plan: Plan, B: int, L: int) -> int:
+    n = _c.c_size_t()
+    _check(lib().nna_stft_backward_workspace(plan.handle, B, L, _c.byref(n)))
+    return n.value
+
+
+def nna_stft_backward(plan: Plan, x, gout, want_gw=True, want_gx=True, workspace=None, stream=None):
+    """(gW[2F, K] or None, gx[B, L] or None) = gradients of a loss through nna_stft(plan, x), given
+    gout[B, F, T] = dLoss/dout.  `workspace`: a CUDA tensor of nna_stft_backward_workspace bytes (made here if None)."""
+    import torch
+
+    if not (isinstance(x, torch.Tensor) and x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.dim() == 2):
+        raise TypeError("x must be a contiguous float32 CUDA tensor [B, L]")
+    B, L = x.shape
+    bins, frames = nna_out_shape(plan, B, L)
+    if not (gout.is_cuda and gout.dtype == torch.float32 and gout.is_contiguous()
+            and tuple(gout.shape) == (B, bins, frames) and gout.device == x.device):
+        raise TypeError(f"gout must be a contiguous float32 CUDA tensor of shape {(B, bins, frames)}")
+    need = nna_stft_backward_workspace(plan, B, L)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    gw = torch.empty(_bank_shape(plan), dtype=torch.float32, device=x.device) if want_gw else None
+    gx = torch.empty_like(x) if want_gx else None
+    _check(lib().nna_stft_backward(plan.handle, x.data_ptr(), B, L, gout.data_ptr(),
+                                   gw.data_ptr() if want_gw else None, gx.data_ptr() if want_gx else None,
+                                   workspace.data_ptr(), ws_bytes, _stream_of(x, stream)))
+    return gw, gx

@@ -262,5 +262,44 @@ __device__ __forceinline__ void stft_store_tile(const f32x16 (&acc)[ST_RB], floa
   }
 }
 
+// Backward pass: the finished row tile turned into G = dLoss/dC for the same 64 (Re, Im) slots x this
+// wave's 32 frames.  `gp` points at (waveform, bin 0, frame) of the upstream gradient for this lane,
+// `Gp` at (packed row 0, global frame) of the G buffer.  With P = Re^2 + Im^2 and g the upstream
+// gradient of the bin: magnitude  g Re / sqrt(P)  (0 where P = 0), power  2 g Re, log  2 g Re / P
+// where P exceeds the floor inside the logarithm (else 0); likewise for Im.  The packed slot 0 holds
+// two real bins (0 and n_half), each with P = its own square.  Slots past n_half are written as zeros.
+template <int FMT>
+__device__ __forceinline__ float grad_scale(float g, float pw) {
+  if constexpr (FMT == NNA_OUT_MAGNITUDE)
+    return pw > 0.f ? g * __builtin_amdgcn_rsqf(pw) : 0.f;
+  else if constexpr (FMT == NNA_OUT_POWER)
+    return 2.f * g;
+  else
+    return pw > 1e-10f ? 2.f * g / pw : 0.f;
+}
+
+template <int FMT>
+__device__ __forceinline__ void stft_grad_tile(const f32x16 (&acc)[ST_RB], const float* __restrict__ gp, long long T,
+                                               float* __restrict__ Gp, long long gpitch, int slot_base, int h,
+                                               int n_half, int packed) {
+#pragma unroll
+  for (int rb = 0; rb < ST_RB; ++rb)
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const float re = acc[rb][2 * u], im = acc[rb][2 * u + 1];
+      const int slot = slot_base + 2 * h + rb * 16 + 4 * (u >> 1) + (u & 1);
+      float gr = 0.f, gi = 0.f;
+      if (slot == 0 && packed) {
+        gr = grad_scale<FMT>(gp[0], re * re) * re;
+        gi = grad_scale<FMT>(gp[n_half * T], im * im) * im;
+      } else if (slot < n_half) {
+        const float s = grad_scale<FMT>(gp[slot * T], re * re + im * im);
+        gr = s * re;
+        gi = s * im;
+      }
+      Gp[(long long)(2 * slot) * gpitch] = gr;
+      Gp[(long long)(2 * slot + 1) * gpitch] = gi;
+    }
+}
 
 }  // namespace nna

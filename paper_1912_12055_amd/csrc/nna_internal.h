@@ -25,6 +25,7 @@ constexpr int ST_MEL_BLOCKS = 4;  // 32-mel MFMA blocks per pass (128 mels)
 // what the STFT kernel does with a finished row tile
 constexpr int ST_MODE_STFT = 0;   // per-bin epilogue, output written per row tile
 constexpr int ST_MODE_MEL = 1;    // power (or magnitude) of the row tile x filterbank slice -> 128 mel accumulators
+constexpr int ST_MODE_GRAD = 3;   // backward pass: dLoss/d(row tile) from the upstream gradient, written to a buffer
 constexpr int ST_MODE_LIN = 2;    // the (Re, Im) rows themselves x a real matrix slice -> 128 output rows = 64
                                   // complex bins (constant-Q transform with frequency-domain kernels)
 
@@ -78,6 +79,12 @@ struct StftParams {
   int n_mels;
   int n_pass;
   int mel_nyq_any;
+  // ST_MODE_GRAD (backward pass): nothing is written to `out`; instead the gradient
+  // of the loss with respect to the contraction's result, G[packed row][global frame], is written
+  // from the upstream gradient gout[B, out_bins, T] (fmt selects the derivative of the output format)
+  const float* gout;
+  float* gbuf;
+  long long gpitch;           // elements per row of gbuf
   // ST_MODE_LIN only: where this plan's bins go in `out`
   long long out_wave_stride;  // elements of `out` per waveform
   int bin_offset;             // bin 0 of this plan is row bin_offset of each waveform's output
@@ -140,7 +147,42 @@ struct CqtParams {
   long long n_ft;
 };
 
+// ---- backward pass of the STFT layer (trainable kernel banks) --------------------------------
+constexpr int BW_MT = 128;   // output tile rows per workgroup
+constexpr int BW_NT = 128;   // output tile columns per workgroup
+constexpr int BW_KC = 32;    // contraction chunk staged in LDS
+
+struct BwParams {
+  FrameGeom g;           // the batch (x may be NULL when only the waveform gradient is wanted)
+  const float* gbuf;     // G[rows_pad][gpitch]: dLoss/dC, packed bank rows x global frames, zero padded
+  long long gpitch;      // multiple of BW_MT
+  const float* wrm;      // packed bank, row-major [rows_pad][kp], zero padded
+  int kp;                // row pitch of wrm (multiple of BW_NT)
+  int rows_pad;          // multiple of BW_MT
+  int n_half, packed;    // as in StftParams: maps packed rows to the logical rows of gw
+  int K;                 // taps
+  float* gw;             // [logical rows][K], zeroed; partial sums are added atomically
+  float* gx;             // [B][L], zeroed; overlapping frames and mirrored samples are added atomically
+  int n_split;           // bank gradient: workgroups that share one output tile (split contraction)
+  long long chunks_per_split;
+};
+
+// logical <-> streaming order of an STFT bank on the device
+struct BankPermuteParams {
+  float* bank;           // fragment order [row tile][group][ST_RB][64][4]
+  float* wrm;            // row-major packed [rows_pad][kp]
+  float* logical;        // [logical rows][K] (caller's tensor)
+  int n_rt, n_chunks, nj, hop, K, kp, n_half, packed;
+};
+
 hipError_t launch_stft(const StftParams& p, int mode, hipStream_t stream);
+hipError_t launch_fill_zero(float* p, long long n, hipStream_t stream);
+hipError_t launch_fill_zero_cols(float* p, long long rows, long long pitch, long long c0, long long c1, hipStream_t stream);
+hipError_t launch_bank_from_logical(const BankPermuteParams& p, hipStream_t stream);  // logical -> bank, wrm
+hipError_t launch_bank_to_rowmajor(const BankPermuteParams& p, hipStream_t stream);   // bank -> wrm
+hipError_t launch_bank_to_logical(const BankPermuteParams& p, hipStream_t stream);    // wrm -> logical
+hipError_t launch_bw_bank(const BwParams& p, hipStream_t stream);      // gw += G x frames
+hipError_t launch_bw_wave(const BwParams& p, hipStream_t stream);      // gx += transposed convolution
 hipError_t launch_cqt(const CqtParams& p, hipStream_t stream);
 hipError_t launch_stft16(const Stft16Params& p, hipStream_t stream);
 hipError_t kernels_init();  // per-process function attributes

@@ -45,8 +45,9 @@ constexpr int ST_RING_MEL = 2;   // fewer in the Mel variant: its 64 extra accum
 template <int MODE, int RING>
 __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
   static_assert(ST_NKG % RING == 0, "ring depth must divide the fragment groups per LDS row");
-  constexpr bool MEL = MODE != ST_MODE_STFT;  // a second contraction follows every row tile
+  constexpr bool MEL = MODE == ST_MODE_MEL || MODE == ST_MODE_LIN;  // a second contraction follows every row tile
   constexpr bool LIN = MODE == ST_MODE_LIN;
+  constexpr bool GRAD = MODE == ST_MODE_GRAD;  // backward pass: the row tile becomes dLoss/dC
   __shared__ __attribute__((aligned(16))) float lds[2][ST_LDS_ROWS * ST_PITCH];
 
   const int tid = threadIdx.x;
@@ -240,7 +241,18 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
       // ---- epilogue of row tile rt ---------------------------------------------------
       c = 0;
       const int slot_base = rt * (ST_ROWS / 2);
-      if constexpr (!MEL) {
+      if constexpr (GRAD) {
+        if (valid) {
+          const float* __restrict__ gp = P.gout + (b_lane * P.out_bins) * g.T + t_lane;
+          float* __restrict__ Gp = P.gbuf + f_lane;
+          if (P.fmt == NNA_OUT_MAGNITUDE)
+            stft_grad_tile<NNA_OUT_MAGNITUDE>(acc, gp, g.T, Gp, P.gpitch, slot_base, h, P.n_half, P.packed);
+          else if (P.fmt == NNA_OUT_POWER)
+            stft_grad_tile<NNA_OUT_POWER>(acc, gp, g.T, Gp, P.gpitch, slot_base, h, P.n_half, P.packed);
+          else
+            stft_grad_tile<NNA_OUT_LOG>(acc, gp, g.T, Gp, P.gpitch, slot_base, h, P.n_half, P.packed);
+        }
+      } else if constexpr (!MEL) {
         if (valid) {
           float* __restrict__ op = P.out + (b_lane * P.out_bins) * g.T + t_lane;
           if (P.fmt == NNA_OUT_MAGNITUDE)
@@ -644,7 +656,7 @@ hipError_t kernels_init() {
 
 hipError_t launch_stft(const StftParams& p, int mode, hipStream_t stream) {
   long long blocks;
-  const bool mel = mode != ST_MODE_STFT;
+  const bool mel = mode == ST_MODE_MEL || mode == ST_MODE_LIN;
   if (mel) {
     blocks = p.n_ft * p.n_pass;
   } else {
@@ -657,6 +669,8 @@ hipError_t launch_stft(const StftParams& p, int mode, hipStream_t stream) {
     hipLaunchKernelGGL((stft_kernel<ST_MODE_LIN, ST_RING_MEL>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   else if (mode == ST_MODE_MEL)
     hipLaunchKernelGGL((stft_kernel<ST_MODE_MEL, ST_RING_MEL>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  else if (mode == ST_MODE_GRAD)
+    hipLaunchKernelGGL((stft_kernel<ST_MODE_GRAD, ST_RING_STFT>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   else
     hipLaunchKernelGGL((stft_kernel<ST_MODE_STFT, ST_RING_STFT>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   return hipGetLastError();

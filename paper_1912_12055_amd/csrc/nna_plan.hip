@@ -92,6 +92,10 @@ struct nna_plan {
   std::vector<_Float16> h_bank16s;
   size_t bank16s_halves = 0;
   _Float16* d_bank16s = nullptr;
+  // trainable STFT plans: the packed bank once more, row-major [rows_pad][kp] (zero padded), for the
+  // backward pass's waveform gradient; kept in step with d_bank by nna_plan_set_bank
+  float* d_wrm = nullptr;
+  int kp = 0, rows_pad = 0;
   float* d_melw = nullptr;
   unsigned char* d_mel_mask = nullptr;
   float* d_mel_wnyq = nullptr;
@@ -1556,6 +1560,177 @@ nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long l
   return run_conv(plan, x_dev, B, L, T, out_dev, (long long)plan->n_bins * T, 0, 0, hip_stream);
 }
 
+// ---- trainable Fourier kernels (Sec. IV-C) ----------------------------------------------------
+static nna_status check_trainable_kind(const nna_plan* plan) {
+  if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
+  if (plan->kind != NNA_KIND_STFT) return fail(NNA_ERR_INVALID_ARG, "only STFT plans have trainable kernels");
+  if (plan->precision != NNA_PREC_F32) return fail(NNA_ERR_UNSUPPORTED, "trainable kernels need a float32 plan");
+  if (plan->device < 0) return fail(NNA_ERR_UNSUPPORTED, "host-only plan (device = -1)");
+  return NNA_OK;
+}
+
+static nna::BankPermuteParams permute_params(const nna_plan* plan, float* logical) {
+  nna::BankPermuteParams q;
+  q.bank = plan->d_bank;
+  q.wrm = plan->d_wrm;
+  q.logical = logical;
+  q.n_rt = plan->n_rt;
+  q.n_chunks = plan->n_chunks;
+  q.nj = plan->nj;
+  q.hop = plan->hop;
+  q.K = plan->K;
+  q.kp = plan->kp;
+  q.n_half = plan->n_half;
+  q.packed = plan->freq_scale ? 0 : 1;
+  return q;
+}
+
+nna_status nna_plan_trainable(nna_plan* plan) {
+  nna_status s = check_trainable_kind(plan);
+  if (s != NNA_OK) return s;
+  if (plan->d_wrm) return NNA_OK;
+  DeviceGuard guard;
+  hipError_t e = guard.enter(plan->device);
+  if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+  plan->rows_pad = plan->n_rt * ST_ROWS;
+  plan->kp = (plan->K + nna::BW_NT - 1) / nna::BW_NT * nna::BW_NT;
+  const size_t bytes = (size_t)plan->rows_pad * plan->kp * sizeof(float);
+  if ((s = upload(&plan->d_wrm, nullptr, bytes, "row-major kernel bank")) != NNA_OK) return s;
+  e = hipMemset(plan->d_wrm, 0, bytes);
+  if (e == hipSuccess) e = nna::launch_bank_to_rowmajor(permute_params(plan, nullptr), nullptr);
+  if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+  if (e != hipSuccess) {
+    (void)hipFree(plan->d_wrm);
+    plan->d_wrm = nullptr;
+    return fail_hip(e, "row-major kernel bank");
+  }
+  return NNA_OK;
+}
+
+static nna_status check_trainable(const nna_plan* plan) {
+  nna_status s = check_trainable_kind(plan);
+  if (s != NNA_OK) return s;
+  if (!plan->d_wrm) return fail(NNA_ERR_INVALID_ARG, "call nna_plan_trainable on the plan first");
+  return NNA_OK;
+}
+
+nna_status nna_plan_get_bank(const nna_plan* plan, float* w_dev, void* hip_stream) {
+  nna_status s = check_trainable(plan);
+  if (s != NNA_OK) return s;
+  if (!w_dev) return fail(NNA_ERR_INVALID_ARG, "w_dev is NULL");
+  DeviceGuard guard;
+  hipError_t e = guard.enter(plan->device);
+  if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+  e = nna::launch_bank_to_logical(permute_params(plan, w_dev), reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  return NNA_OK;
+}
+
+nna_status nna_plan_set_bank(nna_plan* plan, const float* w_dev, void* hip_stream) {
+  nna_status s = check_trainable(plan);
+  if (s != NNA_OK) return s;
+  if (!w_dev) return fail(NNA_ERR_INVALID_ARG, "w_dev is NULL");
+  DeviceGuard guard;
+  hipError_t e = guard.enter(plan->device);
+  if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+  e = nna::launch_bank_from_logical(permute_params(plan, const_cast<float*>(w_dev)), reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  return NNA_OK;
+}
+
+static long long bw_gpitch(long long n_frames) { return (n_frames + nna::BW_MT - 1) / nna::BW_MT * nna::BW_MT; }
+
+nna_status nna_stft_backward_workspace(const nna_plan* plan, long long B, long long L, size_t* bytes) {
+  nna_status s = check_trainable(plan);
+  if (s != NNA_OK) return s;
+  if (!bytes) return fail(NNA_ERR_INVALID_ARG, "bytes is NULL");
+  if (B < 1) return fail(NNA_ERR_SHAPE, "B must be >= 1");
+  const long long T = frames_of(plan, L);
+  if (T < 1) return fail(NNA_ERR_SHAPE, plan->center ? "L must exceed the reflection padding (K/2)" : "L is shorter than one window");
+  *bytes = (size_t)plan->rows_pad * (size_t)bw_gpitch(B * T) * sizeof(float);
+  return NNA_OK;
+}
+
+nna_status nna_stft_backward(const nna_plan* plan, const float* x_dev, long long B, long long L, const float* gout_dev,
+                             float* gw_dev, float* gx_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+  nna_status s = check_trainable(plan);
+  if (s != NNA_OK) return s;
+  if (!gout_dev) return fail(NNA_ERR_INVALID_ARG, "gout_dev is NULL");
+  if (!gw_dev && !gx_dev) return fail(NNA_ERR_INVALID_ARG, "gw_dev and gx_dev are both NULL: nothing to compute");
+  long long T = 0;
+  // (check_call wants an output pointer; the gradient buffers play that part)
+  if ((s = check_call(plan, NNA_KIND_STFT, x_dev, B, L, gw_dev ? gw_dev : gx_dev, &T)) != NNA_OK) return s;
+  size_t need = 0;
+  if ((s = nna_stft_backward_workspace(plan, B, L, &need)) != NNA_OK) return s;
+  if (!workspace_dev || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace_dev) & 255))
+    return fail(NNA_ERR_INVALID_ARG, "workspace_dev is NULL, not 256-byte aligned or smaller than nna_stft_backward_workspace asks for");
+  const int M = pick_tile_frames(ST_FRAMES, T, plan->nj - 1, ST_LDS_ROWS);
+  if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  DeviceGuard guard;
+  hipError_t e = guard.enter(plan->device);
+  if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+
+  float* gbuf = static_cast<float*>(workspace_dev);
+  const long long n_frames = B * T, gpitch = bw_gpitch(n_frames);
+  const int packed = plan->freq_scale ? 0 : 1;
+  // 1. G = dLoss/dC: the forward contraction again, its epilogue turned into the output format's derivative
+  e = nna::launch_fill_zero_cols(gbuf, plan->rows_pad, gpitch, n_frames, gpitch, stream);
+  if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  nna::StftParams P;
+  std::memset(&P, 0, sizeof(P));
+  P.g = make_geom(plan, x_dev, B, L, T);
+  P.bank = reinterpret_cast<const float4*>(plan->d_bank);
+  P.n_rt = plan->n_rt;
+  P.n_chunks = plan->n_chunks;
+  P.nj = plan->nj;
+  P.n_half = plan->n_half;
+  P.packed = packed;
+  P.out_bins = plan->stft_bins();
+  P.fmt = plan->fmt;
+  P.tile_frames = M;
+  P.n_ft = (n_frames + M - 1) / M;
+  P.gout = gout_dev;
+  P.gbuf = gbuf;
+  P.gpitch = gpitch;
+  e = nna::launch_stft(P, nna::ST_MODE_GRAD, stream);
+  if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  // 2. the two contractions with G
+  nna::BwParams Q;
+  std::memset(&Q, 0, sizeof(Q));
+  Q.g = P.g;
+  Q.gbuf = gbuf;
+  Q.gpitch = gpitch;
+  Q.wrm = plan->d_wrm;
+  Q.kp = plan->kp;
+  Q.rows_pad = plan->rows_pad;
+  Q.n_half = plan->n_half;
+  Q.packed = packed;
+  Q.K = plan->K;
+  Q.gw = gw_dev;
+  Q.gx = gx_dev;
+  if (gw_dev) {
+    e = nna::launch_fill_zero(gw_dev, 2LL * plan->stft_bins() * plan->K, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    // split the contraction over the frames so that about 1,024 workgroups exist (two per compute
+    // unit, twice over), each with at least 64 chunks to amortise its start-up
+    const long long tiles = (long long)(plan->rows_pad / nna::BW_MT) * (plan->kp / nna::BW_NT);
+    const long long chunks = gpitch / nna::BW_KC;
+    long long split = std::max(1LL, std::min((1024 + tiles - 1) / tiles, chunks / 64));
+    Q.chunks_per_split = (chunks + split - 1) / split;
+    Q.n_split = (int)((chunks + Q.chunks_per_split - 1) / Q.chunks_per_split);
+    e = nna::launch_bw_bank(Q, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  }
+  if (gx_dev) {
+    e = nna::launch_fill_zero(gx_dev, B * L, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    e = nna::launch_bw_wave(Q, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  }
+  return NNA_OK;
+}
+
 nna_status nna_plan_bank(const nna_plan* plan, double* host_out, size_t cap) {
   if (!plan || !host_out) return fail(NNA_ERR_INVALID_ARG, "plan / host_out is NULL");
   if (plan->kind == NNA_KIND_CQT2010V2 || plan->kind == NNA_KIND_CQT2010)
@@ -1736,6 +1911,7 @@ void nna_plan_destroy(nna_plan* plan) {
       (void)hipFree(plan->d_bank);
       (void)hipFree(plan->d_bank16);
       (void)hipFree(plan->d_bank16s);
+      (void)hipFree(plan->d_wrm);
       (void)hipFree(plan->d_melw);
       (void)hipFree(plan->d_mel_mask);
       (void)hipFree(plan->d_mel_wnyq);

@@ -1,0 +1,368 @@
+// Backward pass of the STFT layer with trainable Fourier kernels (arXiv 1912.12055, Sec. IV-C
+// "Trainable Transformation Kernels") on gfx950 / CDNA4.
+//
+// Forward:  C[r, f] = sum_n W[r, n] xp[f hop + n]  (r = packed bank row, f = global frame), then the
+// output format per (Re, Im) pair.  Given the upstream gradient, the STFT kernel's gradient mode
+// first writes G = dLoss/dC[packed row][global frame].  The two contractions here finish the job:
+//
+//   bank gradient      gW[r, n]  = sum_f G[r, f] xp[f hop + n]              (rows x taps, over frames)
+//   waveform gradient  D[f, n]   = sum_r G[r, f] W[r, n], then gx[mirror(f hop + n)] += D[f, n]
+//                                                              (frames x taps, over bank rows)
+//
+// Both are dense GEMMs on v_mfma_f32_32x32x2_f32 with one kernel: a 128 x 128 output tile per
+// workgroup (4 waves in a 2 x 2 grid, 64 x 64 = four 32 x 32 accumulators each), the contraction
+// staged through LDS in chunks of 32 (double buffered, one barrier per chunk), two workgroups per
+// compute unit.  The B operand is always stored k-major in LDS ([k][column], read with 4-byte LDS
+// loads: at the float32 MFMA rate LDS bandwidth is nowhere near a limit); the A operand is m-major
+// for the bank gradient (G rows are contiguous along the contraction index) and k-major for the
+// waveform gradient (G rows are contiguous along the output index).  Lanes of an accumulator
+// register run along the output's contiguous axis (taps) in both, so the final atomic adds go out
+// in 128-byte runs.  The bank gradient's B operand is the frames matrix, never built: the framing
+// loader of the forward kernels gathers 32 frames x 128 taps per chunk, reflection included.
+//
+// Sums that meet in memory -- the split contraction of the bank gradient, the overlapping frames
+// and mirrored edge samples of the waveform gradient -- are combined with float atomic adds on
+// buffers the caller of these launchers has zeroed, so their order (and with it the last bits of
+// the result) may vary from run to run.
+#include "nna_device.h"
+
+namespace nna {
+
+typedef f32x4 f32x4_u __attribute__((aligned(4)));
+
+constexpr int BW_PA_M = BW_KC + 4;   // LDS pitch of an m-major A tile (conflict-free 16-byte reads)
+constexpr int BW_PK = BW_NT + 4;     // LDS pitch of a k-major tile
+constexpr int BW_MODE_BANK = 0, BW_MODE_WAVE = 1;
+
+__global__ void fill_zero_kernel(float* __restrict__ p, long long n) {
+  const long long stride = (long long)gridDim.x * blockDim.x;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.f;
+}
+
+// columns [c0, c1) of every row of a [rows][pitch] array
+__global__ void fill_zero_cols_kernel(float* __restrict__ p, long long rows, long long pitch, long long c0, long long c1) {
+  const long long w = c1 - c0, n = rows * w;
+  const long long stride = (long long)gridDim.x * blockDim.x;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+    const long long r = i / w;
+    p[r * pitch + c0 + (i - r * w)] = 0.f;
+  }
+}
+
+// ---- logical <-> streaming order of the STFT bank ----------------------------------------------
+// fragment element -> (packed row, tap); the order is that of the forward kernel's bank stream:
+// [row tile][chunk][hop-shift][fragment group][row block][lane] x float4
+struct FragPos {
+  int pr, tap;
+};
+__device__ __forceinline__ FragPos frag_pos(const BankPermuteParams& P, long long i4, int e) {
+  const int lane = (int)(i4 & 63), rb = (int)((i4 >> 6) & 3);
+  const long long G = (long long)P.n_chunks * P.nj * ST_NKG;
+  const long long gi = (i4 >> 8) % G;
+  const int rt = (int)((i4 >> 8) / G);
+  const int kg = (int)(gi % ST_NKG), j = (int)((gi / ST_NKG) % P.nj), c = (int)(gi / ((long long)ST_NKG * P.nj));
+  FragPos fp;
+  fp.pr = rt * ST_ROWS + rb * 32 + (lane & 31);
+  fp.tap = j * P.hop + c * ST_KC + kg * ST_KG + 4 * (lane >> 5) + e;
+  return fp;
+}
+// packed row -> row of the logical [2 bins][K] bank
+__device__ __forceinline__ int logical_row(int pr, int n_half, int packed) {
+  return packed ? (pr == 0 ? 0 : pr == 1 ? 2 * n_half : pr) : pr;
+}
+
+__global__ void bank_from_logical_kernel(const BankPermuteParams P, long long n4) {
+  const long long i4 = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i4 >= n4) return;
+  f32x4 v;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const FragPos fp = frag_pos(P, i4, e);
+    float x = 0.f;
+    if ((fp.pr >> 1) < P.n_half && fp.tap < P.K) {
+      x = P.logical[(long long)logical_row(fp.pr, P.n_half, P.packed) * P.K + fp.tap];
+      P.wrm[(long long)fp.pr * P.kp + fp.tap] = x;
+    }
+    v[e] = x;
+  }
+  reinterpret_cast<f32x4*>(P.bank)[i4] = v;
+}
+
+__global__ void bank_to_rowmajor_kernel(const BankPermuteParams P, long long n4) {
+  const long long i4 = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i4 >= n4) return;
+  const f32x4 v = reinterpret_cast<const f32x4*>(P.bank)[i4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const FragPos fp = frag_pos(P, i4, e);
+    if ((fp.pr >> 1) < P.n_half && fp.tap < P.K) P.wrm[(long long)fp.pr * P.kp + fp.tap] = v[e];
+  }
+}
+
+__global__ void bank_to_logical_kernel(const BankPermuteParams P, long long n) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int lrow = (int)(i / P.K), tap = (int)(i - (long long)lrow * P.K);
+  int pr = lrow;
+  bool zero = false;
+  if (P.packed) {
+    if (lrow == 0) pr = 0;
+    else if (lrow == 2 * P.n_half) pr = 1;
+    else if (lrow == 1 || lrow == 2 * P.n_half + 1) zero = true;  // the two identically-zero sine rows
+  }
+  P.logical[i] = zero ? 0.f : P.wrm[(long long)pr * P.kp + tap];
+}
+
+// ---- the contraction kernel --------------------------------------------------------------------
+template <int MODE>
+__global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
+  constexpr int A_FLOATS = MODE == BW_MODE_BANK ? BW_MT * BW_PA_M : BW_KC * BW_PK;
+  constexpr int B_FLOATS = BW_KC * BW_PK;
+  __shared__ __attribute__((aligned(16))) float ldsA[2][A_FLOATS];
+  __shared__ __attribute__((aligned(16))) float ldsB[2][B_FLOATS];
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int h = lane >> 5, r32 = lane & 31;
+
+  const int n_nt = P.kp / BW_NT;
+  long long m0, c_begin, c_end;
+  int n0;
+  if constexpr (MODE == BW_MODE_BANK) {
+    const int n_mt = P.rows_pad / BW_MT;
+    const long long tiles = (long long)n_mt * n_nt;
+    const long long split = blockIdx.x / tiles;
+    const int tile = (int)(blockIdx.x - split * tiles);
+    m0 = (long long)(tile / n_nt) * BW_MT;
+    n0 = (tile % n_nt) * BW_NT;
+    const long long n_chunks = P.gpitch / BW_KC;
+    c_begin = split * P.chunks_per_split;
+    c_end = c_begin + P.chunks_per_split < n_chunks ? c_begin + P.chunks_per_split : n_chunks;
+  } else {
+    // the tap tiles of one frame tile are neighbours: they share its G columns in the L2
+    m0 = (long long)(blockIdx.x / n_nt) * BW_MT;
+    n0 = (int)(blockIdx.x % n_nt) * BW_NT;
+    c_begin = 0;
+    c_end = P.rows_pad / BW_KC;
+  }
+  if (c_begin >= c_end) return;
+
+  const FrameGeom& g = P.g;
+  f32x4 ra[4], rb[4];
+  TileFix<4> fx;
+
+  // global -> registers for contraction chunk c
+  auto fetch = [&](long long c) {
+    if constexpr (MODE == BW_MODE_BANK) {
+      const long long f0 = c * BW_KC;
+      // A: G[m0 + row][f0 + 4 c4], row = tid/8 + 32 p
+      const float* ap = P.gbuf + (m0 + (tid >> 3)) * P.gpitch + f0 + 4 * (tid & 7);
+#pragma unroll
+      for (int p = 0; p < 4; ++p) ra[p] = *reinterpret_cast<const f32x4*>(ap + (long long)(32 * p) * P.gpitch);
+      // B: taps n0.. of the 32 frames f0.., gathered from the mirrored waveforms (one LDS row per frame)
+      TileMap tm;
+      tm.T = g.T;
+      tm.b0 = f0 / g.T;
+      tm.t0 = (int)(f0 - tm.b0 * g.T);
+      tm.n0 = (g.T - tm.t0) < BW_KC ? (g.T - tm.t0) : BW_KC;
+      tm.extra = 0;
+      const long long left = g.n_frames - f0;
+      const int rows_used = left < 0 ? 0 : left < BW_KC ? (int)left : BW_KC;
+      RowDesc<4> rd;
+      build_rowdesc<BW_NT, 4>(rd, g, tm, rows_used, tid);
+      const float* ptr[4];
+      prepare_chunk<4>(ptr, fx, g, rd, n0);
+#pragma unroll
+      for (int p = 0; p < 4; ++p) rb[p] = *reinterpret_cast<const f32x4_u*>(ptr[p]);
+    } else {
+      const long long k0 = c * BW_KC;
+      // A: G[k0 + k][m0 + 4 c4], k = tid/32 + 8 p;  B: wrm[k0 + k][n0 + 4 c4]
+      const float* ap = P.gbuf + (k0 + (tid >> 5)) * P.gpitch + m0 + 4 * (tid & 31);
+      const float* bp = P.wrm + (k0 + (tid >> 5)) * P.kp + n0 + 4 * (tid & 31);
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        ra[p] = *reinterpret_cast<const f32x4*>(ap + (long long)(8 * p) * P.gpitch);
+        rb[p] = *reinterpret_cast<const f32x4*>(bp + (long long)(8 * p) * P.kp);
+      }
+    }
+  };
+  // registers -> LDS buffer
+  auto stage = [&](int buf) {
+    if constexpr (MODE == BW_MODE_BANK) {
+      float* a = &ldsA[buf][(tid >> 3) * BW_PA_M + 4 * (tid & 7)];
+#pragma unroll
+      for (int p = 0; p < 4; ++p) *reinterpret_cast<f32x4*>(a + 32 * p * BW_PA_M) = ra[p];
+      store_chunk<BW_NT, BW_PK, 4>(rb, fx, ldsB[buf], BW_KC, tid);
+    } else {
+      float* a = &ldsA[buf][(tid >> 5) * BW_PK + 4 * (tid & 31)];
+      float* b = &ldsB[buf][(tid >> 5) * BW_PK + 4 * (tid & 31)];
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        *reinterpret_cast<f32x4*>(a + 8 * p * BW_PK) = ra[p];
+        *reinterpret_cast<f32x4*>(b + 8 * p * BW_PK) = rb[p];
+      }
+    }
+  };
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+  fetch(c_begin);
+  stage(0);
+  __syncthreads();
+
+  for (long long c = c_begin; c < c_end; ++c) {
+    const int buf = (int)((c - c_begin) & 1);
+    const bool more = c + 1 < c_end;
+    if (more) fetch(c + 1);
+    const float* A = ldsA[buf];
+    const float* B = ldsB[buf];
+#pragma unroll
+    for (int kg = 0; kg < BW_KC / 8; ++kg) {
+      // lane (h, r32) holds contraction indices 8 kg + 4 h + e, e = 0..3, of row / column r32
+      f32x4 a[2], b[2];
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi) {
+        if constexpr (MODE == BW_MODE_BANK) {
+          a[mi] = *reinterpret_cast<const f32x4*>(A + (wm * 64 + mi * 32 + r32) * BW_PA_M + 8 * kg + 4 * h);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) a[mi][e] = A[(8 * kg + 4 * h + e) * BW_PK + wm * 64 + mi * 32 + r32];
+        }
+      }
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) b[ni][e] = B[(8 * kg + 4 * h + e) * BW_PK + wn * 64 + ni * 32 + r32];
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < 2; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][e], b[ni][e], acc[mi][ni], 0, 0, 0);
+    }
+    if (more) stage(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: accumulator register r of lane (h, r32) is output row 8 (r/4) + 4 h + r%4, column r32
+  if constexpr (MODE == BW_MODE_BANK) {
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni) {
+        const int tap = n0 + wn * 64 + ni * 32 + r32;
+        if (tap >= P.K) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int pr = (int)m0 + wm * 64 + mi * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+          if ((pr >> 1) < P.n_half)
+            unsafeAtomicAdd(P.gw + (long long)logical_row(pr, P.n_half, P.packed) * P.K + tap, acc[mi][ni][r]);
+        }
+      }
+  } else {
+    const int L = (int)g.L;
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        // four consecutive frames per register quad
+        long long f = m0 + wm * 64 + mi * 32 + 8 * q + 4 * h;
+        long long b = f / g.T;
+        int t = (int)(f - b * g.T);
+#pragma unroll
+        for (int i = 0; i < 4; ++i, ++f) {
+          if (f < g.n_frames) {
+            float* __restrict__ row = P.gx + b * g.L;
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+              const int tap = n0 + wn * 64 + ni * 32 + r32;
+              if (tap < P.K) {
+                int j = t * g.hop + tap - g.pad;
+                j = j < 0 ? -j : (j >= L ? 2 * (L - 1) - j : j);  // mirror padding folded back
+                unsafeAtomicAdd(row + j, acc[mi][ni][4 * q + i]);
+              }
+            }
+          }
+          if (++t == g.T) {
+            t = 0;
+            ++b;
+          }
+        }
+      }
+  }
+}
+
+// ---- launchers ---------------------------------------------------------------------------------
+static unsigned grid_for(long long n, int block) {
+  long long b = (n + block - 1) / block;
+  return (unsigned)(b < 1 ? 1 : b > 65535LL * 16 ? 65535LL * 16 : b);
+}
+
+hipError_t launch_fill_zero(float* p, long long n, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(grid_for(n, 256 * 8)), dim3(256), 0, stream, p, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_zero_cols(float* p, long long rows, long long pitch, long long c0, long long c1, hipStream_t stream) {
+  if (rows <= 0 || c1 <= c0) return hipSuccess;
+  hipLaunchKernelGGL(fill_zero_cols_kernel, dim3(grid_for(rows * (c1 - c0), 256)), dim3(256), 0, stream, p, rows, pitch, c0, c1);
+  return hipGetLastError();
+}
+
+static long long bank_float4s(const BankPermuteParams& p) {
+  return (long long)p.n_rt * p.n_chunks * p.nj * ST_NKG * ST_RB * 64;
+}
+
+hipError_t launch_bank_from_logical(const BankPermuteParams& p, hipStream_t stream) {
+  const long long n4 = bank_float4s(p);
+  if (n4 > 0x7fffffffLL * 256) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(bank_from_logical_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, stream, p, n4);
+  return hipGetLastError();
+}
+
+hipError_t launch_bank_to_rowmajor(const BankPermuteParams& p, hipStream_t stream) {
+  const long long n4 = bank_float4s(p);
+  if (n4 > 0x7fffffffLL * 256) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(bank_to_rowmajor_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, stream, p, n4);
+  return hipGetLastError();
+}
+
+hipError_t launch_bank_to_logical(const BankPermuteParams& p, hipStream_t stream) {
+  const long long rows = 2LL * (p.packed ? p.n_half + 1 : p.n_half);
+  const long long n = rows * p.K;
+  hipLaunchKernelGGL(bank_to_logical_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p, n);
+  return hipGetLastError();
+}
+
+static bool bw_shapes_ok(const BwParams& p) {
+  return p.rows_pad > 0 && p.rows_pad % BW_MT == 0 && p.kp > 0 && p.kp % BW_NT == 0 && p.gpitch > 0 &&
+         p.gpitch % BW_MT == 0 && p.gpitch >= p.g.n_frames && p.K <= p.kp && 2 * p.n_half <= p.rows_pad;
+}
+
+hipError_t launch_bw_bank(const BwParams& p, hipStream_t stream) {
+  if (!bw_shapes_ok(p) || p.n_split < 1 || p.chunks_per_split < 1) return hipErrorInvalidValue;
+  if (p.chunks_per_split * p.n_split < p.gpitch / BW_KC) return hipErrorInvalidValue;
+  const long long blocks = (long long)(p.rows_pad / BW_MT) * (p.kp / BW_NT) * p.n_split;
+  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((bw_gemm_kernel<BW_MODE_BANK>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_bw_wave(const BwParams& p, hipStream_t stream) {
+  if (!bw_shapes_ok(p)) return hipErrorInvalidValue;
+  const long long blocks = (p.gpitch / BW_MT) * (p.kp / BW_NT);
+  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((bw_gemm_kernel<BW_MODE_WAVE>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  return hipGetLastError();
+}
+
+}  // namespace nna

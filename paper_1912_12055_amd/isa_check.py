@@ -130,7 +130,7 @@ def check_kernel(lines) -> list:
     return sorted(bad.items())
 
 
-KERNEL_SOURCES = ("nna_kernels.hip", "nna_kernels_f16.hip")
+KERNEL_SOURCES = ("nna_kernels.hip", "nna_kernels_f16.hip", "nna_train.hip")
 
 
 def compile_to_asm(extra_flags=()) -> str:
