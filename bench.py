@@ -213,6 +213,32 @@ def main() -> int:
                 "mfma_peak_tflops": PEAK_F16_MFMA_TFLOPS if name == "stft_f16_operands" else PEAK_FP32_MFMA_TFLOPS,
             }
         del o_lin, ws, x3, o_1992
+        # backward pass of the STFT layer (trainable kernels): dLoss/dW and dLoss/dx for the same batch.
+        # Algorithmic work: the forward contraction again (2 N^2 per frame) + the bank gradient (2 N^2)
+        # + the waveform gradient (2 N^2) = 6 N^2 flop per frame.
+        p_tr = nb.nna_plan_trainable(nb.nna_plan_stft(sr=sr, n_fft=2048, hop=512, device=0))
+        gout = torch.ones((B, 1025, T), dtype=torch.float32, device=dev)
+        ws_bw = torch.empty(nb.nna_stft_backward_workspace(p_tr, B, L), dtype=torch.uint8, device=dev)
+        for _ in range(max(1, args.warmup)):
+            nb.nna_stft_backward(p_tr, x4, gout, workspace=ws_bw)
+        ev = []
+        for _ in range(args.steps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            nb.nna_stft_backward(p_tr, x4, gout, workspace=ws_bw)
+            b.record()
+            ev.append((a, b))
+        torch.cuda.synchronize()
+        ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+        alg = 3 * p_tr.info()["algorithmic_flops_per_frame"] * B * T
+        extras["stft_backward"] = {
+            "ms": round(ms, 4),
+            "gsamples_per_s": round(B * L / ms / 1e6, 4),
+            "algorithmic_tflops": round(alg / ms / 1e9, 3),
+            "mfma_frac": round(alg / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+            "mfma_peak_tflops": PEAK_FP32_MFMA_TFLOPS,
+        }
+        del gout, ws_bw
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -83,8 +83,8 @@ struct StftParams {
   // of the loss with respect to the contraction's result, G[packed row][global frame], is written
   // from the upstream gradient gout[B, out_bins, T] (fmt selects the derivative of the output format)
   const float* gout;
-  float* gbuf;
-  long long gpitch;           // elements per row of gbuf
+  float* gbuf;                // [frame / 32][n_rt * ST_ROWS packed rows][frame % 32]
+  long long gpitch;           // elements between consecutive rows of gbuf (32)
   // ST_MODE_LIN only: where this plan's bins go in `out`
   long long out_wave_stride;  // elements of `out` per waveform
   int bin_offset;             // bin 0 of this plan is row bin_offset of each waveform's output
@@ -154,8 +154,9 @@ constexpr int BW_KC = 32;    // contraction chunk staged in LDS
 
 struct BwParams {
   FrameGeom g;           // the batch (x may be NULL when only the waveform gradient is wanted)
-  const float* gbuf;     // G[rows_pad][gpitch]: dLoss/dC, packed bank rows x global frames, zero padded
-  long long gpitch;      // multiple of BW_MT
+  const float* gbuf;     // G = dLoss/dC in blocks of 32 frames, [gpitch / 32][rows_pad][32], zero padded: a
+                         // 128-row x 32-frame operand tile is one contiguous 16 KB run
+  long long gpitch;      // frames, padded to a multiple of BW_MT
   const float* wrm;      // packed bank, row-major [rows_pad][kp], zero padded
   int kp;                // row pitch of wrm (multiple of BW_NT)
   int rows_pad;          // multiple of BW_MT
@@ -177,7 +178,7 @@ struct BankPermuteParams {
 
 hipError_t launch_stft(const StftParams& p, int mode, hipStream_t stream);
 hipError_t launch_fill_zero(float* p, long long n, hipStream_t stream);
-hipError_t launch_fill_zero_cols(float* p, long long rows, long long pitch, long long c0, long long c1, hipStream_t stream);
+hipError_t launch_fill_zero_frames(float* gbuf, long long rows_pad, long long f0, long long f1, hipStream_t stream);
 hipError_t launch_bank_from_logical(const BankPermuteParams& p, hipStream_t stream);  // logical -> bank, wrm
 hipError_t launch_bank_to_rowmajor(const BankPermuteParams& p, hipStream_t stream);   // bank -> wrm
 hipError_t launch_bank_to_logical(const BankPermuteParams& p, hipStream_t stream);    // wrm -> logical

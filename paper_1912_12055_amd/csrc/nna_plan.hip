@@ -1675,7 +1675,7 @@ nna_status nna_stft_backward(const nna_plan* plan, const float* x_dev, long long
   const long long n_frames = B * T, gpitch = bw_gpitch(n_frames);
   const int packed = plan->freq_scale ? 0 : 1;
   // 1. G = dLoss/dC: the forward contraction again, its epilogue turned into the output format's derivative
-  e = nna::launch_fill_zero_cols(gbuf, plan->rows_pad, gpitch, n_frames, gpitch, stream);
+  e = nna::launch_fill_zero_frames(gbuf, plan->rows_pad, n_frames, gpitch, stream);
   if (e != hipSuccess) return fail_hip(e, "kernel launch");
   nna::StftParams P;
   std::memset(&P, 0, sizeof(P));
@@ -1692,7 +1692,7 @@ nna_status nna_stft_backward(const nna_plan* plan, const float* x_dev, long long
   P.n_ft = (n_frames + M - 1) / M;
   P.gout = gout_dev;
   P.gbuf = gbuf;
-  P.gpitch = gpitch;
+  P.gpitch = 32;  // G is stored in blocks of 32 frames: [frame / 32][packed row][frame % 32]
   e = nna::launch_stft(P, nna::ST_MODE_GRAD, stream);
   if (e != hipSuccess) return fail_hip(e, "kernel launch");
   // 2. the two contractions with G

@@ -39,13 +39,13 @@ __global__ void fill_zero_kernel(float* __restrict__ p, long long n) {
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.f;
 }
 
-// columns [c0, c1) of every row of a [rows][pitch] array
-__global__ void fill_zero_cols_kernel(float* __restrict__ p, long long rows, long long pitch, long long c0, long long c1) {
-  const long long w = c1 - c0, n = rows * w;
+// frames [f0, f1) of every row of the blocked G buffer [frame / 32][rows_pad][frame % 32]
+__global__ void fill_zero_frames_kernel(float* __restrict__ p, long long rows_pad, long long f0, long long f1) {
+  const long long w = f1 - f0, n = rows_pad * w;
   const long long stride = (long long)gridDim.x * blockDim.x;
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
-    const long long r = i / w;
-    p[r * pitch + c0 + (i - r * w)] = 0.f;
+    const long long r = i / w, f = f0 + (i - r * w);
+    p[(f >> 5) * (rows_pad * 32) + r * 32 + (f & 31)] = 0.f;
   }
 }
 
@@ -133,7 +133,11 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
     const int n_mt = P.rows_pad / BW_MT;
     const long long tiles = (long long)n_mt * n_nt;
     const long long split = blockIdx.x / tiles;
-    const int tile = (int)(blockIdx.x - split * tiles);
+    int tile = (int)(blockIdx.x - split * tiles);
+    // Workgroup ids are dealt round-robin to the 8 XCDs, each with an L2 of its own.  Give every XCD a
+    // contiguous run of tiles in row-major order: it then reads only its own rows of G (the large
+    // operand) instead of all of them.
+    if (tiles % 8 == 0) tile = (tile & 7) * (int)(tiles / 8) + (tile >> 3);
     m0 = (long long)(tile / n_nt) * BW_MT;
     n0 = (tile % n_nt) * BW_NT;
     const long long n_chunks = P.gpitch / BW_KC;
@@ -152,37 +156,71 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
   f32x4 ra[4], rb[4];
   TileFix<4> fx;
 
+  // Bank gradient: this thread stages taps n0 + 4 (tid % 32) .. + 3 of frame (chunk start) + tid/32 + 8 p,
+  // p = 0..3.  The frames' (waveform, frame-in-waveform) pairs are stepped from chunk to chunk
+  // (BW_KC frames on) instead of being divided out every time.
+  long long fb[4];
+  int ft[4];
+  bool fast = false;                        // how the chunk now in rb goes to LDS
+  const bool long_waves = g.T >= BW_KC;     // a step of BW_KC frames crosses at most one waveform boundary
+  if constexpr (MODE == BW_MODE_BANK) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const long long f = c_begin * BW_KC + (tid >> 5) + 8 * p;
+      fb[p] = f / g.T;
+      ft[p] = (int)(f - fb[p] * g.T);
+    }
+  }
+
   // global -> registers for contraction chunk c
   auto fetch = [&](long long c) {
     if constexpr (MODE == BW_MODE_BANK) {
-      const long long f0 = c * BW_KC;
-      // A: G[m0 + row][f0 + 4 c4], row = tid/8 + 32 p
-      const float* ap = P.gbuf + (m0 + (tid >> 3)) * P.gpitch + f0 + 4 * (tid & 7);
+      // A: G[m0 + row][32 c + 4 c4], row = tid/8 + 32 p: the tile is one contiguous run of frame block c
+      const float* ap = P.gbuf + c * ((long long)P.rows_pad * 32) + (m0 + (tid >> 3)) * 32 + 4 * (tid & 7);
 #pragma unroll
-      for (int p = 0; p < 4; ++p) ra[p] = *reinterpret_cast<const f32x4*>(ap + (long long)(32 * p) * P.gpitch);
+      for (int p = 0; p < 4; ++p) ra[p] = *reinterpret_cast<const f32x4*>(ap + 32 * 32 * p);
       // B: taps n0.. of the 32 frames f0.., gathered from the mirrored waveforms (one LDS row per frame)
-      TileMap tm;
-      tm.T = g.T;
-      tm.b0 = f0 / g.T;
-      tm.t0 = (int)(f0 - tm.b0 * g.T);
-      tm.n0 = (g.T - tm.t0) < BW_KC ? (g.T - tm.t0) : BW_KC;
-      tm.extra = 0;
-      const long long left = g.n_frames - f0;
-      const int rows_used = left < 0 ? 0 : left < BW_KC ? (int)left : BW_KC;
+      // Almost every window lies inside its waveform: then the four samples are loaded as they are
+      // stored.  Only a wave that touches a mirrored edge takes the forward kernels' general loader.
       RowDesc<4> rd;
-      build_rowdesc<BW_NT, 4>(rd, g, tm, rows_used, tid);
-      const float* ptr[4];
-      prepare_chunk<4>(ptr, fx, g, rd, n0);
+      bool interior = true;
 #pragma unroll
-      for (int p = 0; p < 4; ++p) rb[p] = *reinterpret_cast<const f32x4_u*>(ptr[p]);
+      for (int p = 0; p < 4; ++p) {
+        const bool ok = fb[p] < g.B;  // frames past the last one read a dummy window: their G is zero
+        rd.xb[p] = ok ? g.x + fb[p] * g.L : g.x;
+        rd.i0[p] = ok ? ft[p] * g.hop + 4 * (tid & 31) - g.pad + n0 : 0;
+        interior = interior && (unsigned)rd.i0[p] <= (unsigned)((int)g.L - 4);
+        ft[p] += BW_KC;  // on to the next chunk
+        if (long_waves) {
+          const bool wrap = ft[p] >= g.T;
+          ft[p] -= wrap ? g.T : 0;
+          fb[p] += wrap ? 1 : 0;
+        } else {
+          while (ft[p] >= g.T) {
+            ft[p] -= g.T;
+            ++fb[p];
+          }
+        }
+      }
+      fast = __builtin_amdgcn_ballot_w64(!interior) == 0;
+      if (fast) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) rb[p] = *reinterpret_cast<const f32x4_u*>(rd.xb[p] + rd.i0[p]);
+      } else {
+        const float* ptr[4];
+        prepare_chunk<4>(ptr, fx, g, rd, 0);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) rb[p] = *reinterpret_cast<const f32x4_u*>(ptr[p]);
+      }
     } else {
       const long long k0 = c * BW_KC;
-      // A: G[k0 + k][m0 + 4 c4], k = tid/32 + 8 p;  B: wrm[k0 + k][n0 + 4 c4]
-      const float* ap = P.gbuf + (k0 + (tid >> 5)) * P.gpitch + m0 + 4 * (tid & 31);
+      // A: G[k0 + k][m0 + 4 c4], k = tid/32 + 8 p (frame block m0/32 + c4/8);  B: wrm[k0 + k][n0 + 4 c4]
+      const float* ap = P.gbuf + ((m0 >> 5) + ((tid & 31) >> 3)) * ((long long)P.rows_pad * 32) +
+                        (k0 + (tid >> 5)) * 32 + 4 * (tid & 7);
       const float* bp = P.wrm + (k0 + (tid >> 5)) * P.kp + n0 + 4 * (tid & 31);
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
-        ra[p] = *reinterpret_cast<const f32x4*>(ap + (long long)(8 * p) * P.gpitch);
+        ra[p] = *reinterpret_cast<const f32x4*>(ap + 8 * p * 32);
         rb[p] = *reinterpret_cast<const f32x4*>(bp + (long long)(8 * p) * P.kp);
       }
     }
@@ -193,7 +231,13 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
       float* a = &ldsA[buf][(tid >> 3) * BW_PA_M + 4 * (tid & 7)];
 #pragma unroll
       for (int p = 0; p < 4; ++p) *reinterpret_cast<f32x4*>(a + 32 * p * BW_PA_M) = ra[p];
-      store_chunk<BW_NT, BW_PK, 4>(rb, fx, ldsB[buf], BW_KC, tid);
+      if (fast) {
+        float* b = &ldsB[buf][(tid >> 5) * BW_PK + 4 * (tid & 31)];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) *reinterpret_cast<f32x4*>(b + 8 * p * BW_PK) = rb[p];
+      } else {
+        store_chunk<BW_NT, BW_PK, 4>(rb, fx, ldsB[buf], BW_KC, tid);
+      }
     } else {
       float* a = &ldsA[buf][(tid >> 5) * BW_PK + 4 * (tid & 31)];
       float* b = &ldsB[buf][(tid >> 5) * BW_PK + 4 * (tid & 31)];
@@ -213,42 +257,66 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
+  // lane (h, r32) holds contraction indices 8 kg + 4 h + e, e = 0..3, of row / column r32
+  auto load_frags = [&](const float* A, const float* B, int kg, f32x4 (&a)[2], f32x4 (&b)[2]) {
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi) {
+      if constexpr (MODE == BW_MODE_BANK) {
+        a[mi] = *reinterpret_cast<const f32x4*>(A + (wm * 64 + mi * 32 + r32) * BW_PA_M + 8 * kg + 4 * h);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) a[mi][e] = A[(8 * kg + 4 * h + e) * BW_PK + wm * 64 + mi * 32 + r32];
+      }
+    }
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) b[ni][e] = B[(8 * kg + 4 * h + e) * BW_PK + wn * 64 + ni * 32 + r32];
+  };
+  auto mfma_group = [&](const f32x4 (&a)[2], const f32x4 (&b)[2]) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][e], b[ni][e], acc[mi][ni], 0, 0, 0);
+  };
+
+  // Pipeline: while chunk c is multiplied out of one LDS buffer, chunk c+1 (requested one iteration
+  // earlier) is written to the other and chunk c+2 is requested; within a chunk the operand fragments
+  // of the next group of 8 are read from LDS while the current 16 MFMAs run.
   fetch(c_begin);
   stage(0);
+  if (c_begin + 1 < c_end) fetch(c_begin + 1);
   __syncthreads();
 
   for (long long c = c_begin; c < c_end; ++c) {
     const int buf = (int)((c - c_begin) & 1);
-    const bool more = c + 1 < c_end;
-    if (more) fetch(c + 1);
     const float* A = ldsA[buf];
     const float* B = ldsB[buf];
-#pragma unroll
-    for (int kg = 0; kg < BW_KC / 8; ++kg) {
-      // lane (h, r32) holds contraction indices 8 kg + 4 h + e, e = 0..3, of row / column r32
-      f32x4 a[2], b[2];
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi) {
-        if constexpr (MODE == BW_MODE_BANK) {
-          a[mi] = *reinterpret_cast<const f32x4*>(A + (wm * 64 + mi * 32 + r32) * BW_PA_M + 8 * kg + 4 * h);
-        } else {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) a[mi][e] = A[(8 * kg + 4 * h + e) * BW_PK + wm * 64 + mi * 32 + r32];
-        }
-      }
-#pragma unroll
-      for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) b[ni][e] = B[(8 * kg + 4 * h + e) * BW_PK + wn * 64 + ni * 32 + r32];
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-          for (int ni = 0; ni < 2; ++ni)
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][e], b[ni][e], acc[mi][ni], 0, 0, 0);
-    }
-    if (more) stage(buf ^ 1);
+    static_assert(BW_KC == 32, "four fragment groups per chunk");
+    // The scheduling barriers pin the order: each group's LDS reads go out ahead of the previous
+    // group's 16 MFMAs (left alone, the compiler sinks every read to just before its first use and
+    // the matrix pipe idles for the LDS latency every four MFMAs), and the LDS writes of chunk c+1
+    // and the global requests for chunk c+2 sit behind reads that are already on their way, with a
+    // whole MFMA group to hide them.
+    f32x4 a0[2], b0[2], a1[2], b1[2];
+    load_frags(A, B, 0, a0, b0);
+    load_frags(A, B, 1, a1, b1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_group(a0, b0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(A, B, 2, a0, b0);
+    if (c + 1 < c_end) stage(buf ^ 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_group(a1, b1);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(A, B, 3, a1, b1);
+    if (c + 2 < c_end) fetch(c + 2);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_group(a0, b0);
+    mfma_group(a1, b1);
     __syncthreads();
   }
 
@@ -312,9 +380,9 @@ hipError_t launch_fill_zero(float* p, long long n, hipStream_t stream) {
   return hipGetLastError();
 }
 
-hipError_t launch_fill_zero_cols(float* p, long long rows, long long pitch, long long c0, long long c1, hipStream_t stream) {
-  if (rows <= 0 || c1 <= c0) return hipSuccess;
-  hipLaunchKernelGGL(fill_zero_cols_kernel, dim3(grid_for(rows * (c1 - c0), 256)), dim3(256), 0, stream, p, rows, pitch, c0, c1);
+hipError_t launch_fill_zero_frames(float* gbuf, long long rows_pad, long long f0, long long f1, hipStream_t stream) {
+  if (rows_pad <= 0 || f1 <= f0) return hipSuccess;
+  hipLaunchKernelGGL(fill_zero_frames_kernel, dim3(grid_for(rows_pad * (f1 - f0), 256)), dim3(256), 0, stream, gbuf, rows_pad, f0, f1);
   return hipGetLastError();
 }
 
