@@ -130,7 +130,9 @@ def check_kernel(lines) -> list:
     return sorted(bad.items())
 
 
-KERNEL_SOURCES = ("nna_kernels.hip", "nna_kernels_f16.hip", "nna_train.hip")
+# the files whose kernels issue loads through inline asm (nna_train.hip leaves its loads to the compiler,
+# which tracks them itself)
+KERNEL_SOURCES = ("nna_kernels.hip", "nna_kernels_f16.hip")
 
 
 def compile_to_asm(extra_flags=()) -> str:
