@@ -80,6 +80,7 @@ def lib():
         L.orc_cqt_default_taps.argtypes = [_I, _D, _I]
         L.orc_cqt_kernels.argtypes = [_I, _D, _I, _I, _I, _LL, _PD, _PD]
         L.orc_cqt.argtypes = [_PF, _LL, _LL, _I, _I, _D, _I, _I, _I, _I, _LL, _I, _PD]
+        L.orc_cqt_complex.argtypes = [_PF, _LL, _LL, _I, _I, _D, _I, _I, _I, _I, _LL, _PD, _PD]
         L.orc_lowpass_fir.argtypes = [_I, _D, _PD]
         L.orc_downsample2.argtypes = [_PD, _LL, _PD, _I, _PD]
         L.orc_cqt2010_default_taps.restype = _LL
@@ -255,6 +256,23 @@ def cqt(x, sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, window=
     _check(lib().orc_cqt(_pf(x), B, L, sr, hop, fmin, n_bins, bins_per_octave, window, int(center), n_taps, fmt,
                          _pd(out)), "cqt")
     return out
+
+
+def cqt_complex(x, sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, window=WIN_HANN, center=True,
+                n_taps=0):
+    """(re, im) of the constant-Q transform, each [B, n_bins, T]."""
+    x = _x(x)
+    B, L = x.shape
+    if n_taps <= 0:
+        n_taps = cqt_default_taps(sr, fmin, bins_per_octave)
+    T = num_frames(L, n_taps, hop, center)
+    if T < 1:
+        raise OracleError("signal too short")
+    re = np.empty((B, n_bins, T), dtype=np.float64)
+    im = np.empty_like(re)
+    _check(lib().orc_cqt_complex(_pf(x), B, L, sr, hop, fmin, n_bins, bins_per_octave, window, int(center), n_taps,
+                                 _pd(re), _pd(im)), "cqt_complex")
+    return re, im
 
 
 FIR_TAPS = 257

@@ -39,7 +39,7 @@
  *   orc_mel_filterbank                      pinned (Table 1 of the paper)
  *   orc_mel                                 pinned (Fig. 2 scenario, linearity)
  *   orc_cqt_lengths / orc_cqt_kernels       pinned (lengths quoted in Sec. III-C)
- *   orc_cqt                                 pinned (tone magnitude A/2, argmax)
+ *   orc_cqt_complex / orc_cqt               pinned (tone magnitude A/2, argmax; phase of a tone)
  *   orc_lowpass_fir / orc_downsample2       pinned (SciPy's window-method design and
  *                                           convolution; tap count and window are this
  *                                           build's choice: the paper gives neither)
@@ -420,13 +420,13 @@ int orc_cqt_kernels(int sr, double fmin, int n_bins, int bins_per_octave, int wi
   return ORC_OK;
 }
 
-/* Constant-Q spectrogram by direct inner products (eq. (CQT) per bin and frame; the
- * "naive" loop of Sec. III-C):
+/* Constant-Q transform by direct inner products (eq. (CQT) per bin and frame; the "naive" loop of
+ * Sec. III-C), complex result:
  *   X[b,k,t] = sum_{n<N_k} xp_b[t hop + s_k + n] w_k[n] exp(-2 pi i Q n / N_k) / sum(w_k)
- * with xp padded by n_taps/2 when center.  out: [B, n_bins, T], formatted like orc_stft. */
-int orc_cqt(const float *x, long long B, long long L, int sr, int hop, double fmin, int n_bins,
-            int bins_per_octave, int window, int center, long long n_taps, int fmt, double *out) {
-  if (!x || !out || B < 1 || hop < 1 || fmt < 0 || fmt > 2) return ORC_EINVAL;
+ * with xp padded by n_taps/2 when center.  re, im: [B, n_bins, T]. */
+int orc_cqt_complex(const float *x, long long B, long long L, int sr, int hop, double fmin, int n_bins,
+                    int bins_per_octave, int window, int center, long long n_taps, double *re, double *im) {
+  if (!x || !re || !im || B < 1 || hop < 1) return ORC_EINVAL;
   if (window != ORC_WIN_HANN && window != ORC_WIN_RECT) return ORC_EINVAL;
   if (n_taps <= 0) n_taps = orc_cqt_default_taps(sr, fmin, bins_per_octave);
   if (n_taps < 2 || (n_taps & 1)) return ORC_EINVAL;
@@ -464,12 +464,31 @@ int orc_cqt(const float *x, long long B, long long L, int sr, int hop, double fm
           sr_ += v * yre[off[k] + n];
           si_ += v * yim[off[k] + n];
         }
-        out[(b * n_bins + k) * T + t] = apply_format(sr_ * sr_ + si_ * si_, fmt);
+        re[(b * n_bins + k) * T + t] = sr_;
+        im[(b * n_bins + k) * T + t] = si_;
       }
     }
   }
   free(Nk); free(off); free(yre); free(yim);
   return ORC_OK;
+}
+
+/* Constant-Q spectrogram: the transform above, formatted like orc_stft.  out: [B, n_bins, T]. */
+int orc_cqt(const float *x, long long B, long long L, int sr, int hop, double fmin, int n_bins,
+            int bins_per_octave, int window, int center, long long n_taps, int fmt, double *out) {
+  if (!out || fmt < 0 || fmt > 2 || B < 1 || hop < 1) return ORC_EINVAL;
+  if (n_taps <= 0) n_taps = orc_cqt_default_taps(sr, fmin, bins_per_octave);
+  const long long T = orc_num_frames(L, n_taps, hop, center);
+  if (T < 1) return ORC_EINVAL;
+  const long long n = B * (long long)n_bins * T;
+  double *re = (double *)malloc(sizeof(double) * n);
+  double *im = (double *)malloc(sizeof(double) * n);
+  if (!re || !im) { free(re); free(im); return ORC_ENOMEM; }
+  int rc = orc_cqt_complex(x, B, L, sr, hop, fmin, n_bins, bins_per_octave, window, center, n_taps, re, im);
+  if (rc == ORC_OK)
+    for (long long i = 0; i < n; ++i) out[i] = apply_format(re[i] * re[i] + im[i] * im[i], fmt);
+  free(re); free(im);
+  return rc;
 }
 
 /* ---------------------------------------------------------------------------------------

@@ -141,3 +141,22 @@ def test_default_taps_and_bad_args():
         oracle.cqt(np.zeros(8000, np.float32))  # pad 8192 >= L
     with pytest.raises(oracle.OracleError):
         oracle.cqt(x, n_taps=8192)  # shorter than the longest kernel
+
+
+@pytest.mark.parametrize("k,phase", [(5, 0.4), (40, -1.3), (83, 2.6)])
+def test_complex_result_carries_the_tone_phase(k, phase):
+    # x[n] = A cos(2 pi Q n' / N_k + phase) with n' counted from the kernel's first tap: the kernel
+    # exp(-2 pi i Q n' / N_k) w / sum(w) then returns (A/2) exp(+i phase) (+ the conjugate term 2Q bins away)
+    sr, fmin, nb, b, taps, hop, A = 22050, 32.70, 84, 12, 16384, 512, 0.8
+    Nk, _ = oracle.cqt_lengths(sr, fmin, nb, b)
+    L = 3 * taps
+    t = 10  # a mid-signal frame: padded start t*hop, kernel k starts s_k taps later
+    s_k = (taps - Nk[k]) // 2
+    n = np.arange(L)
+    first = t * hop + s_k - taps // 2  # stored-sample index of the kernel's first tap in frame t
+    x = (A * np.cos(2 * np.pi * oracle.cqt_Q(b) * (n - first) / Nk[k] + phase)).astype(np.float32)
+    re, im = oracle.cqt_complex(x, sr=sr, hop=hop, fmin=fmin, n_bins=nb, bins_per_octave=b, n_taps=taps)
+    z = re[0, k, t] + 1j * im[0, k, t]
+    assert abs(z - A / 2 * np.exp(1j * phase)) < 2e-5 * A
+    mag = oracle.cqt(x, sr=sr, hop=hop, fmin=fmin, n_bins=nb, bins_per_octave=b, n_taps=taps)
+    np.testing.assert_allclose(np.hypot(re, im), mag, rtol=1e-12, atol=1e-15)

@@ -188,3 +188,15 @@ def test_rejects_bad_arguments():
         oracle.stft(x, n_fft=63, hop=16)  # odd window
     with pytest.raises(oracle.OracleError):
         oracle.stft(x, n_fft=256, hop=64, center=False)  # shorter than one window
+
+
+def test_complex_result_carries_the_tone_phase():
+    # one un-centred frame of A cos(2 pi k0 n / N + phi): X[k0] = (A/2) sum(w) exp(+i phi) for the
+    # periodic Hann window (its spectrum vanishes 2 k0 bins away), eq. (DFT2)'s sign convention
+    N, k0, A = 256, 19, 0.7
+    for phi in (0.0, 0.9, -2.2):
+        n = np.arange(N)
+        x = (A * np.cos(2 * np.pi * k0 * n / N + phi)).astype(np.float32)
+        re, im = oracle.stft_complex(x, n_fft=N, hop=N, center=False)
+        z = re[0, k0, 0] + 1j * im[0, k0, 0]
+        assert abs(z - A / 2 * (N / 2) * np.exp(1j * phi)) < 1e-5 * N
