@@ -56,7 +56,11 @@ typedef enum {
 typedef enum {
   NNA_OUT_MAGNITUDE = 0, /* sqrt(Re^2 + Im^2) */
   NNA_OUT_POWER = 1,     /* Re^2 + Im^2 */
-  NNA_OUT_LOG = 2        /* ln(max(Re^2 + Im^2, 1e-10)): log compression, Fig. 1 caption */
+  NNA_OUT_LOG = 2,       /* ln(max(Re^2 + Im^2, 1e-10)): log compression, Fig. 1 caption */
+  /* The transform itself, before the magnitude is taken (the output_format argument of the paper's
+   * CQT layer, Sec. III-C): nna_stft (float32 plans) and nna_cqt only. */
+  NNA_OUT_COMPLEX = 3,   /* out[B, 2 bins, T]: row 2k = Re, row 2k+1 = Im of bin k (eq. (DFT2)'s signs: Im = -sum x sin) */
+  NNA_OUT_PHASE = 4      /* atan2(Im, Re) in [-pi, pi] */
 } nna_output;
 
 typedef enum {
@@ -92,7 +96,7 @@ typedef enum {
  * STFT plan (Sec. III-A; defaults of the paper's STFT layer: n_fft 2048, hop 512,
  * Hann, center, reflect).  Bank: rows Re_k[n] = w[n] cos(2 pi k n / N) and
  * Im_k[n] = -w[n] sin(2 pi k n / N), k = 0..N/2 (eq. (DFT2) with the window folded
- * into the kernels).  Output bins F = n_fft/2 + 1.
+ * into the kernels).  Output bins F = n_fft/2 + 1 (2F output rows for NNA_OUT_COMPLEX).
  *   sr     sample rate in Hz (kept for reporting; the DFT bank does not depend on it)
  *   n_fft  even, >= 8;  hop >= 1;  center 0/1;  device: HIP device index or -1.
  */
@@ -253,7 +257,8 @@ nna_status nna_cqt2010(const nna_plan* plan, const float* x_dev, long long B, lo
  * kernel of bin k, K = n_fft taps, F = the plan's output bins.  For a plan from nna_plan_stft rows 1
  * and 2F-1 (the sine kernels of bins 0 and n_fft/2, identically zero in eq. (DFT2)) are not
  * parameters: they read as zero, writes to them are ignored and their gradient is zero -- which is
- * also what training would give, since d|X|/dIm = Im/|X| vanishes where Im is zero.
+ * also what training would give, since d|X|/dIm = Im/|X| vanishes where Im is zero.  (With
+ * NNA_OUT_COMPLEX the output rows these two kernels would produce are identically zero.)
  *
  * nna_plan_trainable  makes a plan trainable: allocates a second, row-major device copy of its bank
  *                     (the only allocation of this group; synchronises).  Idempotent.

@@ -27,6 +27,7 @@ _SRC = os.path.join(_HERE, "nna_oracle.c")
 _LIB = os.path.join(_HERE, "libnna_oracle.so")
 
 MAGNITUDE, POWER, LOG = 0, 1, 2
+COMPLEX, PHASE = 3, 4  # the transform before the magnitude: (Re, Im) row pairs [B, 2 bins, T]; atan2(Im, Re)
 WIN_HANN, WIN_RECT = 0, 1
 MEL_SLANEY, MEL_HTK = 0, 1
 FREQ_DFT, FREQ_LINEAR, FREQ_LOG = 0, 1, 2
@@ -429,6 +430,14 @@ def _frame_index(L, K, hop, center):
     return idx
 
 
+def interleave(re, im):
+    """[B, 2 bins, T] with row 2k = re[:, k], row 2k+1 = im[:, k]: the layout of the complex output format."""
+    out = np.empty((re.shape[0], 2 * re.shape[1], re.shape[2]), dtype=np.float64)
+    out[:, 0::2] = re
+    out[:, 1::2] = im
+    return out
+
+
 def stft_bank(x, W, hop=512, center=True, fmt=MAGNITUDE):
     """The STFT layer with a given kernel bank (Sec. III-A with the kernels as weights, Sec. IV-C):
     W[2F, K], row 2k = real-part kernel and row 2k+1 = imaginary-part kernel of bin k (window folded
@@ -442,9 +451,15 @@ def stft_bank(x, W, hop=512, center=True, fmt=MAGNITUDE):
     out = []
     for b in range(x.shape[0]):
         C = x[b][idx] @ W.T                      # [T, 2F]
-        pw = C[:, 0::2] ** 2 + C[:, 1::2] ** 2   # [T, F]
-        out.append(pw.T)
+        if fmt == COMPLEX:
+            out.append(C.T)
+        elif fmt == PHASE:
+            out.append(np.arctan2(C[:, 1::2], C[:, 0::2]).T)
+        else:
+            out.append((C[:, 0::2] ** 2 + C[:, 1::2] ** 2).T)   # [F, T]
     pw = np.stack(out)
+    if fmt in (COMPLEX, PHASE):
+        return pw
     if fmt == MAGNITUDE:
         return np.sqrt(pw)
     if fmt == POWER:
@@ -459,7 +474,8 @@ def stft_bank_backward(x, W, gout, hop=512, center=True, fmt=MAGNITUDE):
     [B, F, T]: returns (gW [2F, K], gx [B, L]).
 
     With P = Re^2 + Im^2:  magnitude: d out/d Re = Re / sqrt(P) (0 where P = 0);  power: 2 Re;
-    log: 2 Re / P where P exceeds the floor, else 0 -- and likewise for Im.  G[b, r, t] = dLoss/dC.
+    log: 2 Re / P where P exceeds the floor, else 0 -- and likewise for Im;  complex (gout [B, 2F, T]):
+    the output is C itself;  phase: d atan2(Im, Re) = (Re dIm - Im dRe) / P.  G[b, r, t] = dLoss/dC.
     gW[r, n] = sum_{b,t} G[b, r, t] xp_b[t hop + n];   gx_b[j] = sum over all (t, n) whose padded
     sample t hop + n mirrors onto j of sum_r W[r, n] G[b, r, t] (the transposed strided convolution,
     with the reflection padding folded back)."""
@@ -476,7 +492,20 @@ def stft_bank_backward(x, W, gout, hop=512, center=True, fmt=MAGNITUDE):
         C = X @ W.T                              # [T, 2F]
         re, im = C[:, 0::2], C[:, 1::2]
         pw = re ** 2 + im ** 2
-        g = gout[b].T                            # [T, F]
+        g = gout[b].T                            # [T, F]  ([T, 2F] for the complex format)
+        if fmt == COMPLEX:
+            G = g
+            gW += G.T @ X
+            np.add.at(gx[b], idx, G @ W)
+            continue
+        if fmt == PHASE:
+            s = np.where(pw > 0, g / np.where(pw > 0, pw, 1.0), 0.0)
+            G = np.empty_like(C)
+            G[:, 0::2] = -s * im
+            G[:, 1::2] = s * re
+            gW += G.T @ X
+            np.add.at(gx[b], idx, G @ W)
+            continue
         if fmt == MAGNITUDE:
             s = np.where(pw > 0, g / np.sqrt(np.where(pw > 0, pw, 1.0)), 0.0)
         elif fmt == POWER:

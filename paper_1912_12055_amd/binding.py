@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libnna.so")
 
 NNA_OK = 0
 NNA_ERR_INVALID_ARG, NNA_ERR_UNSUPPORTED, NNA_ERR_SHAPE, NNA_ERR_ALLOC, NNA_ERR_HIP = 1, 2, 3, 4, 5
-NNA_OUT_MAGNITUDE, NNA_OUT_POWER, NNA_OUT_LOG = 0, 1, 2
+NNA_OUT_MAGNITUDE, NNA_OUT_POWER, NNA_OUT_LOG, NNA_OUT_COMPLEX, NNA_OUT_PHASE = 0, 1, 2, 3, 4
 NNA_WIN_HANN, NNA_WIN_RECT = 0, 1
 NNA_MEL_SLANEY, NNA_MEL_HTK = 0, 1
 NNA_FREQ_LINEAR, NNA_FREQ_LOG = 1, 2
@@ -241,14 +241,15 @@ def nna_plan_mel_weights(plan: Plan) -> np.ndarray:
 
 def nna_plan_cqt_lengths(plan: Plan) -> np.ndarray:
     i = plan.info()
-    out = np.empty(i["out_bins"], dtype=np.int64)
+    # (out_bins counts (Re, Im) row pairs twice for a complex-output CQT plan; the plan's bank has 2 rows per bin)
+    out = np.empty(i["out_bins"] if i["kind"] == NNA_KIND_CQT1992 else i["bank_rows"] // 2, dtype=np.int64)
     _check(lib().nna_plan_cqt_lengths(plan.handle, out.ctypes.data_as(_c.POINTER(_LL)), out.size))
     return out
 
 
 def nna_plan_sigma(plan: Plan) -> np.ndarray:
     i = plan.info()
-    out = np.empty(i["out_bins"], dtype=np.float64)
+    out = np.empty(i["bank_rows"] // 2, dtype=np.float64)
     _check(lib().nna_plan_sigma(plan.handle, out.ctypes.data_as(_c.POINTER(_c.c_double)), out.size))
     return out
 
@@ -333,7 +334,7 @@ def nna_plan_trainable(plan: Plan) -> Plan:
 
 def _bank_shape(plan: Plan):
     i = plan.info()
-    return (2 * i["out_bins"], i["taps"])
+    return (i["bank_rows"], i["taps"])
 
 
 def _stream_of(t, stream):

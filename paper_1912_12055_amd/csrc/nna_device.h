@@ -262,12 +262,45 @@ __device__ __forceinline__ void stft_store_tile(const f32x16 (&acc)[ST_RB], floa
   }
 }
 
+// Output of one finished row tile before the magnitude is taken: NNA_OUT_COMPLEX writes rows 2k = Re,
+// 2k+1 = Im of bin k (`op` points at (waveform, row 0, frame)); NNA_OUT_PHASE writes atan2(Im, Re).
+template <int FMT>
+__device__ __forceinline__ void stft_store_tile_complex(const f32x16 (&acc)[ST_RB], float* __restrict__ op, long long T,
+                                                        int slot_base, int h, int n_half, int packed) {
+#pragma unroll
+  for (int rb = 0; rb < ST_RB; ++rb)
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const float re = acc[rb][2 * u], im = acc[rb][2 * u + 1];
+      const int slot = slot_base + 2 * h + rb * 16 + 4 * (u >> 1) + (u & 1);
+      if (slot == 0 && packed) {  // the two purely real bins 0 and n_half
+        if constexpr (FMT == NNA_OUT_COMPLEX) {
+          op[0] = re;
+          op[T] = 0.f;
+          op[(2LL * n_half) * T] = im;
+          op[(2LL * n_half + 1) * T] = 0.f;
+        } else {
+          op[0] = atan2f(0.f, re);
+          op[(long long)n_half * T] = atan2f(0.f, im);
+        }
+      } else if (slot < n_half) {
+        if constexpr (FMT == NNA_OUT_COMPLEX) {
+          op[(2LL * slot) * T] = re;
+          op[(2LL * slot + 1) * T] = im;
+        } else {
+          op[(long long)slot * T] = atan2f(im, re);
+        }
+      }
+    }
+}
+
 // Backward pass: the finished row tile turned into G = dLoss/dC for the same 64 (Re, Im) slots x this
 // wave's 32 frames.  `gp` points at (waveform, bin 0, frame) of the upstream gradient for this lane,
 // `Gp` at (packed row 0, global frame) of the G buffer.  With P = Re^2 + Im^2 and g the upstream
 // gradient of the bin: magnitude  g Re / sqrt(P)  (0 where P = 0), power  2 g Re, log  2 g Re / P
 // where P exceeds the floor inside the logarithm (else 0); likewise for Im.  The packed slot 0 holds
 // two real bins (0 and n_half), each with P = its own square.  Slots past n_half are written as zeros.
+// NNA_OUT_COMPLEX: the output is C itself; NNA_OUT_PHASE: d atan2(Im, Re) = (Re dIm - Im dRe) / P.
 template <int FMT>
 __device__ __forceinline__ float grad_scale(float g, float pw) {
   if constexpr (FMT == NNA_OUT_MAGNITUDE)
@@ -289,7 +322,24 @@ __device__ __forceinline__ void stft_grad_tile(const f32x16 (&acc)[ST_RB], const
       const float re = acc[rb][2 * u], im = acc[rb][2 * u + 1];
       const int slot = slot_base + 2 * h + rb * 16 + 4 * (u >> 1) + (u & 1);
       float gr = 0.f, gi = 0.f;
-      if (slot == 0 && packed) {
+      if constexpr (FMT == NNA_OUT_COMPLEX) {
+        // the output is C itself (rows 2k, 2k+1 of the upstream gradient)
+        if (slot == 0 && packed) {
+          gr = gp[0];
+          gi = gp[(2LL * n_half) * T];
+        } else if (slot < n_half) {
+          gr = gp[(2LL * slot) * T];
+          gi = gp[(2LL * slot + 1) * T];
+        }
+      } else if constexpr (FMT == NNA_OUT_PHASE) {
+        // d atan2(Im, Re) = (Re dIm - Im dRe) / P; the phase of the two real bins is piecewise constant
+        if (!(slot == 0 && packed) && slot < n_half) {
+          const float pw = re * re + im * im;
+          const float s = pw > 0.f ? gp[slot * T] / pw : 0.f;
+          gr = -s * im;
+          gi = s * re;
+        }
+      } else if (slot == 0 && packed) {
         gr = grad_scale<FMT>(gp[0], re * re) * re;
         gi = grad_scale<FMT>(gp[n_half * T], im * im) * im;
       } else if (slot < n_half) {

@@ -48,6 +48,7 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
   constexpr bool MEL = MODE == ST_MODE_MEL || MODE == ST_MODE_LIN;  // a second contraction follows every row tile
   constexpr bool LIN = MODE == ST_MODE_LIN;
   constexpr bool GRAD = MODE == ST_MODE_GRAD;  // backward pass: the row tile becomes dLoss/dC
+  constexpr bool CPLX = MODE == ST_MODE_CPLX;  // complex or phase output
   __shared__ __attribute__((aligned(16))) float lds[2][ST_LDS_ROWS * ST_PITCH];
 
   const int tid = threadIdx.x;
@@ -250,8 +251,20 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
             stft_grad_tile<NNA_OUT_MAGNITUDE>(acc, gp, g.T, Gp, P.gpitch, slot_base, h, P.n_half, P.packed);
           else if (P.fmt == NNA_OUT_POWER)
             stft_grad_tile<NNA_OUT_POWER>(acc, gp, g.T, Gp, P.gpitch, slot_base, h, P.n_half, P.packed);
-          else
+          else if (P.fmt == NNA_OUT_LOG)
             stft_grad_tile<NNA_OUT_LOG>(acc, gp, g.T, Gp, P.gpitch, slot_base, h, P.n_half, P.packed);
+          else if (P.fmt == NNA_OUT_COMPLEX)
+            stft_grad_tile<NNA_OUT_COMPLEX>(acc, gp, g.T, Gp, P.gpitch, slot_base, h, P.n_half, P.packed);
+          else
+            stft_grad_tile<NNA_OUT_PHASE>(acc, gp, g.T, Gp, P.gpitch, slot_base, h, P.n_half, P.packed);
+        }
+      } else if constexpr (CPLX) {
+        if (valid) {
+          float* __restrict__ op = P.out + (b_lane * P.out_bins) * g.T + t_lane;
+          if (P.fmt == NNA_OUT_COMPLEX)
+            stft_store_tile_complex<NNA_OUT_COMPLEX>(acc, op, g.T, slot_base, h, P.n_half, P.packed);
+          else
+            stft_store_tile_complex<NNA_OUT_PHASE>(acc, op, g.T, slot_base, h, P.n_half, P.packed);
         }
       } else if constexpr (!MEL) {
         if (valid) {
@@ -630,6 +643,22 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
     for (int fb = 0; fb < 4; ++fb) {
       if (!valid[fb]) continue;
       float* __restrict__ op = P.out + o_off[fb];
+      if (f == NNA_OUT_COMPLEX) {  // rows 2k = Re, 2k+1 = Im of bin k
+        if (bin0 < P.n_bins) {
+          op[(2LL * bin0) * g.T] = acc[r][fb][0];
+          op[(2LL * bin0 + 1) * g.T] = acc[r][fb][1];
+        }
+        if (bin0 + 1 < P.n_bins) {
+          op[(2LL * bin0 + 2) * g.T] = acc[r][fb][2];
+          op[(2LL * bin0 + 3) * g.T] = acc[r][fb][3];
+        }
+        continue;
+      }
+      if (f == NNA_OUT_PHASE) {
+        if (bin0 < P.n_bins) op[(long long)bin0 * g.T] = atan2f(acc[r][fb][1], acc[r][fb][0]);
+        if (bin0 + 1 < P.n_bins) op[(long long)(bin0 + 1) * g.T] = atan2f(acc[r][fb][3], acc[r][fb][2]);
+        continue;
+      }
       const float p0 = acc[r][fb][0] * acc[r][fb][0] + acc[r][fb][1] * acc[r][fb][1];
       const float p1 = acc[r][fb][2] * acc[r][fb][2] + acc[r][fb][3] * acc[r][fb][3];
       if (bin0 < P.n_bins)
@@ -672,6 +701,8 @@ hipError_t launch_stft(const StftParams& p, int mode, hipStream_t stream) {
     hipLaunchKernelGGL((stft_kernel<ST_MODE_MEL, ST_RING_MEL>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   else if (mode == ST_MODE_GRAD)
     hipLaunchKernelGGL((stft_kernel<ST_MODE_GRAD, ST_RING_STFT>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  else if (mode == ST_MODE_CPLX)
+    hipLaunchKernelGGL((stft_kernel<ST_MODE_CPLX, ST_RING_STFT>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   else
     hipLaunchKernelGGL((stft_kernel<ST_MODE_STFT, ST_RING_STFT>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   return hipGetLastError();

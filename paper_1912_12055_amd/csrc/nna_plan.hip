@@ -47,6 +47,11 @@ struct nna_plan {
 
   // output bins of an STFT plan; a plain DFT packs bins 0 and N/2 (both purely real) into slot 0
   int stft_bins() const { return freq_scale ? n_half : n_half + 1; }
+  // rows of the output per waveform: the complex format writes (Re, Im) row pairs
+  int out_rows() const {
+    const int bins = kind == NNA_KIND_STFT ? stft_bins() : kind == NNA_KIND_MEL ? n_mels : n_bins;
+    return fmt == NNA_OUT_COMPLEX ? 2 * bins : bins;
+  }
   // Mel
   int n_mels = 0, mel_power = 2, n_pass = 0, mel_nyq_any = 0;
   std::vector<float> h_melW;  // [n_mels, F] as rounded to float32
@@ -765,6 +770,16 @@ nna_status check_common(nna_plan** plan, int sr, int hop, int win, int center, i
   return check_device(device);
 }
 
+// magnitude / power / log everywhere; the complex and phase outputs where `allow_complex`
+nna_status check_fmt(int fmt, bool allow_complex) {
+  if (fmt == NNA_OUT_MAGNITUDE || fmt == NNA_OUT_POWER || fmt == NNA_OUT_LOG) return NNA_OK;
+  if (fmt == NNA_OUT_COMPLEX || fmt == NNA_OUT_PHASE) {
+    if (allow_complex) return NNA_OK;
+    return fail(NNA_ERR_UNSUPPORTED, "the complex and phase outputs exist for nna_stft (float32) and nna_cqt only");
+  }
+  return fail(NNA_ERR_INVALID_ARG, "unknown output format");
+}
+
 nna_status check_stft_args(int n_fft) {
   if (n_fft < 8 || (n_fft & 1)) return fail(NNA_ERR_INVALID_ARG, "n_fft must be even and >= 8");
   if (n_fft > (1 << 20)) return fail(NNA_ERR_UNSUPPORTED, "n_fft above 2^20 is not supported");
@@ -862,7 +877,7 @@ nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long lo
   P.nj = plan->nj;
   P.n_half = plan->n_half;
   P.packed = plan->freq_scale ? 0 : 1;
-  P.out_bins = kind == NNA_KIND_MEL ? plan->n_mels : kind == NNA_KIND_CQT1992 ? plan->n_bins : plan->stft_bins();
+  P.out_bins = kind == NNA_KIND_MEL ? plan->n_mels : kind == NNA_KIND_CQT1992 ? plan->n_bins : plan->out_rows();
   P.tile_frames = M;
   P.n_ft = (P.g.n_frames + M - 1) / M;
   if (kind == NNA_KIND_MEL) {
@@ -890,7 +905,10 @@ nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long lo
   DeviceGuard guard;
   hipError_t e = guard.enter(plan->device);
   if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
-  const int mode = kind == NNA_KIND_MEL ? nna::ST_MODE_MEL : kind == NNA_KIND_CQT1992 ? nna::ST_MODE_LIN : nna::ST_MODE_STFT;
+  const int mode = kind == NNA_KIND_MEL       ? nna::ST_MODE_MEL
+                   : kind == NNA_KIND_CQT1992 ? nna::ST_MODE_LIN
+                   : (plan->fmt == NNA_OUT_COMPLEX || plan->fmt == NNA_OUT_PHASE) ? nna::ST_MODE_CPLX
+                                                                                  : nna::ST_MODE_STFT;
   e = nna::launch_stft(P, mode, reinterpret_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail_hip(e, "kernel launch");
   return NNA_OK;
@@ -904,12 +922,12 @@ nna_status run_stft_like(const nna_plan* plan, int kind, const float* x, long lo
   return run_stft_core(plan, kind, x, B, L, T, out, 0, 0, stream);
 }
 
-nna_status check_cqt_args(double fmin, int n_bins, int bins_per_octave, int n_taps, int fmt, int sr) {
+nna_status check_cqt_args(double fmin, int n_bins, int bins_per_octave, int n_taps, int fmt, int sr,
+                          bool allow_complex = false) {
   if (!(fmin > 0.0)) return fail(NNA_ERR_INVALID_ARG, "fmin must be > 0");
   if (n_bins < 1 || n_bins > 4096) return fail(NNA_ERR_INVALID_ARG, "n_bins must be in [1, 4096]");
   if (bins_per_octave < 1 || bins_per_octave > 1024) return fail(NNA_ERR_INVALID_ARG, "bins_per_octave must be in [1, 1024]");
-  if (fmt != NNA_OUT_MAGNITUDE && fmt != NNA_OUT_POWER && fmt != NNA_OUT_LOG)
-    return fail(NNA_ERR_INVALID_ARG, "unknown output format");
+  if (nna_status sf = check_fmt(fmt, allow_complex); sf != NNA_OK) return sf;
   if (n_taps < 0) return fail(NNA_ERR_INVALID_ARG, "n_taps must be >= 0");
   const double top = fmin * std::pow(2.0, (double)(n_bins - 1) / bins_per_octave);
   if (!(top < 0.5 * sr)) return fail(NNA_ERR_INVALID_ARG, "the top CQT bin must lie below sr/2");
@@ -1091,8 +1109,7 @@ nna_status nna_plan_stft(nna_plan** plan, int sr, int n_fft, int hop, nna_window
   nna_status s = check_common(plan, sr, hop, win, center, device);
   if (s != NNA_OK) return s;
   if ((s = check_stft_args(n_fft)) != NNA_OK) return s;
-  if (fmt != NNA_OUT_MAGNITUDE && fmt != NNA_OUT_POWER && fmt != NNA_OUT_LOG)
-    return fail(NNA_ERR_INVALID_ARG, "unknown output format");
+  if ((s = check_fmt(fmt, true)) != NNA_OK) return s;
   nna_plan* p = new (std::nothrow) nna_plan;
   if (!p) return fail(NNA_ERR_ALLOC, "out of host memory");
   try {
@@ -1123,8 +1140,7 @@ nna_status nna_plan_stft_prec(nna_plan** plan, int sr, int n_fft, int hop, nna_w
   nna_status s = check_common(plan, sr, hop, win, center, device);
   if (s != NNA_OK) return s;
   if ((s = check_stft_args(n_fft)) != NNA_OK) return s;
-  if (fmt != NNA_OUT_MAGNITUDE && fmt != NNA_OUT_POWER && fmt != NNA_OUT_LOG)
-    return fail(NNA_ERR_INVALID_ARG, "unknown output format");
+  if ((s = check_fmt(fmt, false)) != NNA_OK) return s;
   nna_plan* p = new (std::nothrow) nna_plan;
   if (!p) return fail(NNA_ERR_ALLOC, "out of host memory");
   try {
@@ -1158,8 +1174,7 @@ nna_status nna_plan_stft_scaled(nna_plan** plan, int sr, int n_fft, int hop, nna
   nna_status s = check_common(plan, sr, hop, win, center, device);
   if (s != NNA_OK) return s;
   if ((s = check_stft_args(n_fft)) != NNA_OK) return s;
-  if (fmt != NNA_OUT_MAGNITUDE && fmt != NNA_OUT_POWER && fmt != NNA_OUT_LOG)
-    return fail(NNA_ERR_INVALID_ARG, "unknown output format");
+  if ((s = check_fmt(fmt, true)) != NNA_OK) return s;
   if (freq_scale != NNA_FREQ_LINEAR && freq_scale != NNA_FREQ_LOG)
     return fail(NNA_ERR_INVALID_ARG, "freq_scale must be NNA_FREQ_LINEAR or NNA_FREQ_LOG");
   if (freq_bins == 0) freq_bins = n_fft / 2 + 1;
@@ -1234,7 +1249,7 @@ nna_status nna_plan_cqt(nna_plan** plan, int sr, int hop, double fmin, int n_bin
                         nna_window win, int center, int n_taps, nna_output fmt, int device) {
   nna_status s = check_common(plan, sr, hop, win, center, device);
   if (s != NNA_OK) return s;
-  if ((s = check_cqt_args(fmin, n_bins, bins_per_octave, n_taps, fmt, sr)) != NNA_OK) return s;
+  if ((s = check_cqt_args(fmin, n_bins, bins_per_octave, n_taps, fmt, sr, true)) != NNA_OK) return s;
   return make_cqt_plan(plan, sr, hop, fmin, 0, n_bins, bins_per_octave, win, center, n_taps, fmt, device);
 }
 
@@ -1537,7 +1552,7 @@ nna_status nna_out_shape(const nna_plan* plan, long long B, long long L, long lo
   }
   const long long T = frames_of(plan, L);
   if (T < 1) return fail(NNA_ERR_SHAPE, plan->center ? "L must exceed the reflection padding (K/2)" : "L is shorter than one window");
-  if (n_bins) *n_bins = plan->kind == NNA_KIND_STFT ? plan->stft_bins() : plan->kind == NNA_KIND_MEL ? plan->n_mels : plan->n_bins;
+  if (n_bins) *n_bins = plan->out_rows();
   if (n_frames) *n_frames = T;
   return NNA_OK;
 }
@@ -1557,7 +1572,7 @@ nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long l
   DeviceGuard guard;
   hipError_t e = guard.enter(plan->device);
   if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
-  return run_conv(plan, x_dev, B, L, T, out_dev, (long long)plan->n_bins * T, 0, 0, hip_stream);
+  return run_conv(plan, x_dev, B, L, T, out_dev, (long long)plan->out_rows() * T, 0, 0, hip_stream);
 }
 
 // ---- trainable Fourier kernels (Sec. IV-C) ----------------------------------------------------
@@ -1686,7 +1701,7 @@ nna_status nna_stft_backward(const nna_plan* plan, const float* x_dev, long long
   P.nj = plan->nj;
   P.n_half = plan->n_half;
   P.packed = packed;
-  P.out_bins = plan->stft_bins();
+  P.out_bins = plan->out_rows();
   P.fmt = plan->fmt;
   P.tile_frames = M;
   P.n_ft = (n_frames + M - 1) / M;
@@ -1878,7 +1893,7 @@ nna_status nna_plan_info(const nna_plan* plan, int* kind, long long* bank_rows, 
                  : plan->kind == NNA_KIND_CQT     ? (long long)plan->conv_rows
                                                   : 2LL * (plan->freq_scale ? plan->n_half : plan->n_half + 1);
   if (taps) *taps = plan->K;
-  if (out_bins) *out_bins = plan->kind == NNA_KIND_STFT ? plan->stft_bins() : plan->kind == NNA_KIND_MEL ? plan->n_mels : plan->n_bins;
+  if (out_bins) *out_bins = plan->out_rows();
   if (executed_flops_per_frame) *executed_flops_per_frame = plan->exec_flops;
   if (algorithmic_flops_per_frame) *algorithmic_flops_per_frame = plan->alg_flops;
   return NNA_OK;

@@ -176,6 +176,59 @@ def test_stft_rejects_bad_shapes(nb):
     assert nb.lib().nna_stft(mel.handle, x.data_ptr(), 1, 4096, out.data_ptr(), None) == nb.NNA_ERR_INVALID_ARG
 
 
+def _phase_err(got, ref_re, ref_im):
+    """largest phase difference (modulo 2 pi) over the bins whose magnitude is above 1e-3 of the peak: below
+    that the float32 rounding of (Re, Im) turns into an arbitrary angle"""
+    mag = np.hypot(ref_re, ref_im)
+    keep = mag > 1e-3 * mag.max()
+    d = np.angle(np.exp(1j * (np.asarray(got, dtype=np.float64) - np.arctan2(ref_im, ref_re))))
+    return np.abs(d[keep]).max()
+
+
+COMPLEX_STFT_CASES = [
+    # name, B, L, n_fft, hop, window, center
+    ("several tiles, ragged tail, tiles span waveforms", 5, 30000, 256, 64, 0, True),
+    ("no centring, rect window", 2, 9000, 512, 128, 1, False),
+    ("hop does not divide n_fft", 3, 5000, 96, 25, 0, True),
+    ("n_fft = 2048, hop 512", 2, 20000, 2048, 512, 0, True),
+]
+
+
+@pytest.mark.parametrize("case", COMPLEX_STFT_CASES, ids=[c[0] for c in COMPLEX_STFT_CASES])
+def test_stft_complex_and_phase_output(nb, case):
+    name, B, L, n_fft, hop, win, center = case
+    _say(f"stft complex/phase {name}: B={B} L={L} n_fft={n_fft} hop={hop} win={win} center={center}")
+    x = _rand(B, L, 4000 + n_fft)
+    re, im = oracle.stft_complex(x, n_fft=n_fft, hop=hop, window=win, center=center)
+    plan = nb.nna_plan_stft(n_fft=n_fft, hop=hop, win=win, center=center, fmt=nb.NNA_OUT_COMPLEX, device=0)
+    got = nb.nna_stft(plan, _dev(x)).cpu().numpy()
+    e = _rel_err(got, oracle.interleave(re, im))
+    assert not got[:, 1].any() and not got[:, -1].any()  # Im of bins 0 and N/2
+    plan = nb.nna_plan_stft(n_fft=n_fft, hop=hop, win=win, center=center, fmt=nb.NNA_OUT_PHASE, device=0)
+    ph = nb.nna_stft(plan, _dev(x)).cpu().numpy()
+    assert ph.shape == re.shape and np.abs(ph).max() <= np.pi + 1e-6
+    ep = _phase_err(ph[:, 1:-1], re[:, 1:-1], im[:, 1:-1])
+    # bins 0 and N/2 are real: phase 0 or +-pi by the sign of Re
+    for k in (0, -1):
+        strong = np.abs(re[:, k]) > 1e-3 * np.abs(re).max()
+        want_pi = re[:, k] < 0
+        assert np.all((np.abs(ph[:, k]) > 3.0)[strong] == want_pi[strong])
+    _say(f"  complex rel err {e:.3e}, phase err {ep:.3e} rad")
+    assert e < TOL and e < 5e-5 and ep < 1e-3
+
+
+def test_scaled_stft_complex_output(nb):
+    _say("scaled stft complex")
+    x = _rand(3, 9000, 4100)
+    sig = np.array([oracle.freq_sigma(oracle.FREQ_LOG, k, 100.0, 3500.0, 37, 512, 8000) for k in range(37)])
+    re, im = oracle.stft_sigma_complex(x, sig, n_fft=512, hop=128)
+    plan = nb.nna_plan_stft_scaled(sr=8000, n_fft=512, hop=128, fmt=nb.NNA_OUT_COMPLEX, freq_scale=nb.NNA_FREQ_LOG,
+                                   fmin=100.0, fmax=3500.0, freq_bins=37, device=0)
+    e = _rel_err(nb.nna_stft(plan, _dev(x)).cpu().numpy(), oracle.interleave(re, im))
+    _say(f"  rel err {e:.3e}")
+    assert e < TOL and e < 5e-5
+
+
 # ---------------------------------------------------------------------------------------
 # Mel
 # ---------------------------------------------------------------------------------------
@@ -254,6 +307,21 @@ def test_cqt_parity_small(nb, case):
     e = _rel_err(got, ref)
     _say(f"  rel err {e:.3e}")
     assert e < TOL and e < 5e-5
+
+
+@pytest.mark.parametrize("case", [CQT_CASES[1], CQT_CASES[2], CQT_CASES[3], CQT_CASES[6]], ids=lambda c: c[0])
+def test_cqt_complex_and_phase_output(nb, case):
+    name, B, L, sr, hop, fmin, n_bins, bpo, taps, win, center, _ = case
+    _say(f"cqt complex/phase {name}: B={B} L={L} sr={sr} hop={hop} bins={n_bins}/{bpo} taps={taps}")
+    x = _rand(B, L, 300 + n_bins)
+    kw = dict(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, center=center, n_taps=taps)
+    re, im = oracle.cqt_complex(x, window=win, **kw)
+    got = nb.nna_cqt(nb.nna_plan_cqt(win=win, fmt=nb.NNA_OUT_COMPLEX, device=0, **kw), _dev(x)).cpu().numpy()
+    e = _rel_err(got, oracle.interleave(re, im))
+    ph = nb.nna_cqt(nb.nna_plan_cqt(win=win, fmt=nb.NNA_OUT_PHASE, device=0, **kw), _dev(x)).cpu().numpy()
+    ep = _phase_err(ph, re, im)
+    _say(f"  complex rel err {e:.3e}, phase err {ep:.3e} rad")
+    assert e < TOL and e < 5e-5 and ep < 1e-3
 
 
 def test_cqt_device_bank_equals_host_bank(nb):

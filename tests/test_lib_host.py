@@ -42,7 +42,7 @@ def test_plan_argument_checking():
     assert _status(nb.nna_plan_stft, n_fft=6, device=-1) == nb.NNA_ERR_INVALID_ARG
     assert _status(nb.nna_plan_stft, hop=0, device=-1) == nb.NNA_ERR_INVALID_ARG
     assert _status(nb.nna_plan_stft, win=7, device=-1) == nb.NNA_ERR_INVALID_ARG
-    assert _status(nb.nna_plan_stft, fmt=3, device=-1) == nb.NNA_ERR_INVALID_ARG
+    assert _status(nb.nna_plan_stft, fmt=5, device=-1) == nb.NNA_ERR_INVALID_ARG
     assert _status(nb.nna_plan_stft, device=-2) == nb.NNA_ERR_INVALID_ARG
     assert _status(nb.nna_plan_mel, fmax=12000.0, device=-1) == nb.NNA_ERR_INVALID_ARG  # above sr/2
     assert _status(nb.nna_plan_mel, fmin=500.0, fmax=400.0, device=-1) == nb.NNA_ERR_INVALID_ARG
@@ -322,3 +322,18 @@ def test_cqt2010_argument_checking():
     assert _status(nb.nna_plan_cqt2010, hop=512, n_fft=128, **kw) == nb.NNA_ERR_INVALID_ARG  # top octave: 178 taps
     assert _status(nb.nna_plan_cqt2010, hop=512, n_fft=300, **kw) == nb.NNA_ERR_INVALID_ARG  # not a power of two
     assert _status(nb.nna_plan_cqt2010, hop=512, fir_taps=64, **kw) == nb.NNA_ERR_INVALID_ARG
+
+
+def test_complex_and_phase_formats_shapes_and_where_they_exist():
+    p = nb.nna_plan_stft(n_fft=256, hop=64, fmt=nb.NNA_OUT_COMPLEX, device=-1)
+    assert nb.nna_out_shape(p, 2, 1000) == (2 * 129, 16) and p.info()["out_bins"] == 258
+    p = nb.nna_plan_stft(n_fft=256, hop=64, fmt=nb.NNA_OUT_PHASE, device=-1)
+    assert nb.nna_out_shape(p, 2, 1000) == (129, 16)
+    p = nb.nna_plan_stft_scaled(n_fft=256, hop=64, fmt=nb.NNA_OUT_COMPLEX, freq_bins=40, device=-1)
+    assert nb.nna_out_shape(p, 1, 1000) == (80, 16)
+    p = nb.nna_plan_cqt(sr=8000, hop=64, fmin=220.0, n_bins=24, fmt=nb.NNA_OUT_COMPLEX, device=-1)
+    assert nb.nna_out_shape(p, 1, 4000)[0] == 48 and nb.nna_plan_cqt_lengths(p).size == 24
+    for fn, kw in ((nb.nna_plan_cqt2010v2, {}), (nb.nna_plan_cqt2010, {}), (nb.nna_plan_cqt1992, dict(fmin=220.0, n_bins=24)),
+                   (nb.nna_plan_stft_prec, dict(precision=nb.NNA_PREC_F16))):
+        assert _status(fn, fmt=nb.NNA_OUT_COMPLEX, device=-1, **kw) == nb.NNA_ERR_UNSUPPORTED, fn
+    assert _status(nb.nna_plan_stft, fmt=5, device=-1) == nb.NNA_ERR_INVALID_ARG

@@ -33,7 +33,17 @@ def test_forward_with_the_dft_bank_is_the_stft(fmt, center):
     np.testing.assert_allclose(got, ref, rtol=1e-9, atol=1e-12)
 
 
-@pytest.mark.parametrize("fmt", [oracle.MAGNITUDE, oracle.POWER, oracle.LOG])
+def test_complex_and_phase_forward_with_the_dft_bank():
+    x = signals.batch(1, B=2, L=700)
+    re, im = oracle.stft_complex(x, n_fft=64, hop=16)
+    got = oracle.stft_bank(x, _dft_bank(64), hop=16, fmt=oracle.COMPLEX)
+    np.testing.assert_allclose(got, oracle.interleave(re, im), atol=1e-11)
+    ph = oracle.stft_bank(x, _dft_bank(64), hop=16, fmt=oracle.PHASE)
+    d = np.angle(np.exp(1j * (ph - np.arctan2(im, re))))  # compared modulo 2 pi
+    assert np.abs(d[:, 1:-1]).max() < 1e-9  # (bins 0 and N/2 are real: their phase is 0 or +-pi)
+
+
+@pytest.mark.parametrize("fmt", [oracle.MAGNITUDE, oracle.POWER, oracle.LOG, oracle.COMPLEX, oracle.PHASE])
 @pytest.mark.parametrize("center,hop", [(True, 8), (False, 8), (True, 5)])
 def test_gradients_against_central_differences(fmt, center, hop):
     rng = np.random.default_rng(7 + fmt)
@@ -74,6 +84,7 @@ def _forward64(x64, W, hop, center, fmt):
     pad = K // 2 if center else 0
     T = 1 + (L + 2 * pad - K) // hop
     out = np.empty((B, W.shape[0] // 2, T))
+    outc = np.empty((B, W.shape[0], T))
     for b in range(B):
         for t in range(T):
             fr = np.empty(K)
@@ -83,8 +94,13 @@ def _forward64(x64, W, hop, center, fmt):
                 fr[n] = x64[b, j]
             C = W @ fr
             pw = C[0::2] ** 2 + C[1::2] ** 2
-            out[b, :, t] = np.sqrt(pw) if fmt == oracle.MAGNITUDE else pw if fmt == oracle.POWER else np.log(np.maximum(pw, oracle.LOG_FLOOR))
-    return out
+            if fmt == oracle.COMPLEX:
+                outc[b, :, t] = C
+            elif fmt == oracle.PHASE:
+                out[b, :, t] = np.arctan2(C[1::2], C[0::2])
+            else:
+                out[b, :, t] = np.sqrt(pw) if fmt == oracle.MAGNITUDE else pw if fmt == oracle.POWER else np.log(np.maximum(pw, oracle.LOG_FLOOR))
+    return outc if fmt == oracle.COMPLEX else out
 
 
 def test_one_frame_power_closed_form():
