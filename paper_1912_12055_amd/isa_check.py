@@ -4,8 +4,10 @@ The kernels request their streaming loads through inline asm and wait for them w
 ``s_waitcnt vmcnt(N)``; the compiler therefore does not know which registers have a load in
 flight.  It is free to copy, spill or reuse such a register, and any of those would read or
 clobber data that has not landed yet.  This module compiles the kernels to assembly and scans
-every kernel's control-flow graph: between a ``global_load`` and the ``s_waitcnt vmcnt`` that
-retires it no other instruction, on any path, may name the load's destination registers.
+every kernel's control-flow graph: between a ``global_load`` issued from an inline-asm block and
+the ``s_waitcnt vmcnt`` that retires it no other instruction, on any path, may name the load's
+destination registers.  Loads, stores and atomics the compiler issues itself are counted (they share
+the counter) but their registers are the compiler's business.
 """
 from __future__ import annotations
 
@@ -32,11 +34,28 @@ def _regs(text: str) -> set:
 _MAX_VARIANTS = 256
 
 
-def _step(pending: tuple, lineno: int, t: str, op: str, bad: dict) -> tuple:
+def _norm(pending: tuple) -> tuple:
+    """Canonical form of an in-flight list: entries older than the oldest one that owns registers
+    protect nothing, and the counter holds at most 63 requests (the machine stalls the issue of a
+    64th until the oldest has retired)."""
+    i = 0
+    while i < len(pending) and not pending[i]:
+        i += 1
+    pending = pending[i:]
+    return pending[-63:]
+
+
+def _step(pending: tuple, lineno: int, t: str, op: str, bad: dict, in_asm: bool = True) -> tuple:
+    return _norm(_step_raw(pending, lineno, t, op, bad, in_asm))
+
+
+def _step_raw(pending: tuple, lineno: int, t: str, op: str, bad: dict, in_asm: bool) -> tuple:
     """Apply one instruction to one in-flight list (tuple of frozenset(dst regs), oldest first).
 
-    Stores also count in vmcnt; leaving them out of the model only makes it stricter (a wait then
-    retires fewer loads in the model than on the machine)."""
+    Stores and atomics without return count in vmcnt on this target too and retire in issue order with
+    the loads (the compiler's own wait insertion relies on it): they enter the list with no
+    destination registers, so that a compiler-placed ``vmcnt(N)`` behind a run of stores retires the
+    loads it is meant to."""
     if op == "s_waitcnt":
         m = re.search(r"vmcnt\((\d+)\)", t)
         if m:
@@ -52,12 +71,16 @@ def _step(pending: tuple, lineno: int, t: str, op: str, bad: dict) -> tuple:
         for rs in pending:
             if rs & (src | dst):
                 bad.setdefault(lineno, f"{t}   [touches v{sorted(rs & (src | dst))}, destination of a load in flight]")
-        return pending + (frozenset(dst),)
+        # a load the compiler issued itself is tracked by the compiler (it may, for instance, load one
+        # register from both arms of a divergent branch): it only takes its place in the count
+        return pending + (frozenset(dst) if in_asm else frozenset(),)
     touched = _regs(t)
     for rs in pending:
         if rs & touched:
             bad.setdefault(lineno, f"{t}   [v{sorted(rs & touched)} is the destination of a load in flight]")
             break
+    if op.startswith(("global_store", "buffer_store", "global_atomic", "buffer_atomic")):
+        return pending + (frozenset(),)
     return pending
 
 
@@ -67,9 +90,15 @@ def check_kernel(lines) -> list:
     The kernel is split into basic blocks; the set of possible in-flight load lists is propagated
     along every control-flow edge to a fixed point (loads retire in order, so a list is trimmed to
     its N youngest entries by ``s_waitcnt vmcnt(N)``)."""
-    insts = []  # (lineno, text, op)
+    insts = []  # (lineno, text, op, inside an inline-asm block)
     labels = {}
+    in_asm = False
+    marked = any("#ASMSTART" in raw for raw in lines)  # hand-written snippets carry no markers: all asm
     for i, raw in enumerate(lines, 1):
+        if "#ASMSTART" in raw:
+            in_asm = True
+        elif "#ASMEND" in raw:
+            in_asm = False
         t = raw.split(";")[0].strip()
         if not t:
             continue
@@ -78,12 +107,12 @@ def check_kernel(lines) -> list:
             continue
         if t.startswith("."):
             continue
-        insts.append((i, t, t.split()[0]))
+        insts.append((i, t, t.split()[0], in_asm or not marked))
     if not insts:
         return []
     # basic block leaders
     leaders = {0} | set(labels.values())
-    for k, (_, t, op) in enumerate(insts):
+    for k, (_, t, op, _a) in enumerate(insts):
         if op.startswith("s_cbranch") or op in ("s_branch", "s_endpgm", "s_setpc_b64"):
             leaders.add(k + 1)
     leaders = sorted(x for x in leaders if x < len(insts))
@@ -93,7 +122,7 @@ def check_kernel(lines) -> list:
         block_of[start] = (start, end)
     succs = {}
     for start, (s0, e0) in block_of.items():
-        _, t, op = insts[e0 - 1]
+        _, t, op, _a = insts[e0 - 1]
         out = []
         if op == "s_endpgm":
             pass
@@ -108,16 +137,19 @@ def check_kernel(lines) -> list:
         succs[start] = out
     bad = {}
     entry_states = {0: {()}}
+    simulated = {}  # block -> entry states already pushed through it
     work = [0]
     while work:
         start = work.pop()
         s0, e0 = block_of[start]
         outs = set()
-        for pend in entry_states[start]:
+        fresh = entry_states[start] - simulated.setdefault(start, set())
+        simulated[start] |= fresh
+        for pend in fresh:
             cur = pend
             for k in range(s0, e0):
-                ln, t, op = insts[k]
-                cur = _step(cur, ln, t, op, bad)
+                ln, t, op, a = insts[k]
+                cur = _step(cur, ln, t, op, bad, a)
             outs.add(cur)
         for nxt in succs[start]:
             have = entry_states.setdefault(nxt, set())

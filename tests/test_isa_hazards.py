@@ -28,6 +28,27 @@ def test_scanner_accepts_ordered_waits():
     assert bad == []
 
 
+def test_scanner_counts_stores_in_vmcnt():
+    # a compiler-placed wait behind two stores: vmcnt(2) retires the load
+    ok = isa_check.check_kernel([
+        "global_load_dword v10, v[0:1], off",
+        "global_store_dword v[2:3], v5, off",
+        "global_store_dword v[2:3], v6, off offset:4",
+        "s_waitcnt vmcnt(2)",
+        "v_add_f32_e32 v7, v10, v10",
+        "s_endpgm",
+    ])
+    assert ok == []
+    bad = isa_check.check_kernel([
+        "global_load_dword v10, v[0:1], off",
+        "global_store_dword v[2:3], v5, off",
+        "s_waitcnt vmcnt(2)",
+        "v_add_f32_e32 v7, v10, v10",
+        "s_endpgm",
+    ])
+    assert [b[0] for b in bad] == [4]
+
+
 def test_compiled_kernels_have_no_in_flight_register_hazard():
     res = isa_check.check_all(isa_check.compile_to_asm())
     assert len(res) >= 3  # STFT, Mel and CQT kernels
