@@ -520,3 +520,27 @@ def stft_bank_backward(x, W, gout, hop=512, center=True, fmt=MAGNITUDE):
         gW += G.T @ X
         np.add.at(gx[b], idx, G @ W)
     return gW, gx
+
+
+def mel_bank(x, W, Wmel, hop=512, center=True, power=2.0):
+    """The Mel-spectrogram layer with given weights (Sec. III-B, Fig. 3, with both stages as weights,
+    Sec. IV-C): the STFT layer of ``stft_bank`` with kernel bank W[2F, K], then the fully connected
+    layer Wmel[n_mels, F] applied per time step to |X|^power (power 1 or 2).  out: [B, n_mels, T]."""
+    fmt = POWER if power == 2.0 else MAGNITUDE
+    P = stft_bank(x, W, hop=hop, center=center, fmt=fmt)           # [B, F, T]
+    return np.einsum("mk,bkt->bmt", np.asarray(Wmel, dtype=np.float64), P)
+
+
+def mel_bank_backward(x, W, Wmel, gout, hop=512, center=True, power=2.0):
+    """Gradients of a scalar loss through ``mel_bank`` given gout = dLoss/dout [B, n_mels, T]:
+    (gWmel [n_mels, F], gW [2F, K], gx [B, L]).  gWmel[m, k] = sum_{b,t} gout[b, m, t] P[b, k, t];
+    the gradient reaching the STFT layer's output is gP[b, k, t] = sum_m Wmel[m, k] gout[b, m, t],
+    which ``stft_bank_backward`` carries on to the kernel bank and the waveform."""
+    fmt = POWER if power == 2.0 else MAGNITUDE
+    Wmel = np.asarray(Wmel, dtype=np.float64)
+    gout = np.asarray(gout, dtype=np.float64)
+    P = stft_bank(x, W, hop=hop, center=center, fmt=fmt)
+    gWmel = np.einsum("bmt,bkt->mk", gout, P)
+    gP = np.einsum("mk,bmt->bkt", Wmel, gout)
+    gW, gx = stft_bank_backward(x, W, gP, hop=hop, center=center, fmt=fmt)
+    return gWmel, gW, gx

@@ -126,3 +126,53 @@ def test_zero_sine_rows_of_the_dft_bank_get_no_gradient():
         gW, _ = oracle.stft_bank_backward(x, W, gout, hop=8, fmt=fmt)
         assert np.all(gW[1] == 0) and np.all(gW[N + 1] == 0)
         assert np.abs(gW[0]).max() > 0 and np.abs(gW[N]).max() > 0
+
+
+# ---------------------------------------------------------------------------------------
+# the Mel layer with both stages as weights
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("power", [1.0, 2.0])
+def test_mel_forward_with_the_dft_bank_and_the_filterbank_is_the_mel_spectrogram(power):
+    x = signals.batch(2, B=2, L=900)
+    Wmel, _ = oracle.mel_filterbank(8000, 64, 10, fmin=0.0, fmax=4000.0)
+    got = oracle.mel_bank(x, _dft_bank(64), Wmel, hop=16, power=power)
+    ref = oracle.mel(x, sr=8000, n_fft=64, hop=16, n_mels=10, fmin=0.0, fmax=4000.0, power=power)
+    np.testing.assert_allclose(got, ref, rtol=1e-9, atol=1e-12)
+
+
+@pytest.mark.parametrize("power", [1.0, 2.0])
+def test_mel_gradients_against_central_differences(power):
+    rng = np.random.default_rng(17)
+    K, F, M, B, L, hop = 16, 5, 3, 2, 61, 8
+    W = rng.standard_normal((2 * F, K))
+    Wmel = rng.standard_normal((M, F))
+    x = rng.standard_normal((B, L)).astype(np.float32)
+    x64 = x.astype(np.float64)
+    fmt = oracle.POWER if power == 2.0 else oracle.MAGNITUDE
+
+    def fwd(Wv, Wm, xv):
+        return np.einsum("mk,bkt->bmt", Wm, _forward64(xv, Wv, hop, True, fmt))
+
+    gout = rng.standard_normal(fwd(W, Wmel, x64).shape)
+    gWmel, gW, gx = oracle.mel_bank_backward(x, W, Wmel, gout, hop=hop, power=power)
+    eps = 1e-6
+
+    def num(f):
+        return (f(+eps) - f(-eps)) / (2 * eps)
+
+    for _ in range(15):
+        m, k = rng.integers(M), rng.integers(F)
+        def f(e):
+            Wm = Wmel.copy(); Wm[m, k] += e
+            return float(np.sum(gout * fwd(W, Wm, x64)))
+        assert abs(num(f) - gWmel[m, k]) < 1e-6 * max(1.0, abs(gWmel[m, k]))
+        r, n = rng.integers(2 * F), rng.integers(K)
+        def f(e):
+            Wv = W.copy(); Wv[r, n] += e
+            return float(np.sum(gout * fwd(Wv, Wmel, x64)))
+        assert abs(num(f) - gW[r, n]) < 1e-6 * max(1.0, abs(gW[r, n]))
+        b, j = rng.integers(B), rng.integers(L)
+        def f(e):
+            xv = x64.copy(); xv[b, j] += e
+            return float(np.sum(gout * fwd(W, Wmel, xv)))
+        assert abs(num(f) - gx[b, j]) < 1e-6 * max(1.0, abs(gx[b, j]))
