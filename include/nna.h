@@ -252,7 +252,7 @@ nna_status nna_cqt2010(const nna_plan* plan, const float* x_dev, long long B, lo
 /*
  * Trainable Fourier kernels (Sec. IV-C, "Trainable Transformation Kernels"): the STFT layer's kernel
  * bank as a parameter that a training loop reads, updates and differentiates through.  Plans from
- * nna_plan_stft and nna_plan_stft_scaled (float32).  The bank's logical layout is the layer's weight
+ * nna_plan_stft and nna_plan_stft_scaled (float32; for nna_plan_mel see the next group).  The bank's logical layout is the layer's weight
  * W[2 F, K], float32 row-major on the device: row 2k = real-part kernel, row 2k+1 = imaginary-part
  * kernel of bin k, K = n_fft taps, F = the plan's output bins.  For a plan from nna_plan_stft rows 1
  * and 2F-1 (the sine kernels of bins 0 and n_fft/2, identically zero in eq. (DFT2)) are not
@@ -292,6 +292,31 @@ nna_status nna_stft_backward_workspace(const nna_plan* plan, long long B, long l
 nna_status nna_stft_backward(const nna_plan* plan, const float* x_dev, long long B, long long L,
                              const float* gout_dev, float* gw_dev, float* gx_dev, void* workspace_dev,
                              size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Trainable Mel layer (Sec. IV-C; the trainable_mel / trainable_STFT arguments of the paper's
+ * MelSpectrogram layer, Sec. III-B): both stages of a plan from nna_plan_mel as parameters.
+ * nna_plan_trainable also accepts Mel plans; nna_plan_get_bank / nna_plan_set_bank then address the
+ * STFT stage's kernels W[2F, K] as above, and
+ *   nna_plan_get_mel_weights / nna_plan_set_mel_weights   the filterbank Wmel[n_mels, F], float32
+ *                      row-major on the device, F = n_fft/2 + 1.  Once a Mel plan is trainable its
+ *                      filters are treated as dense (a trained filter is no triangle any more), which
+ *                      costs nna_mel about 3 % more multiply-adds.
+ *   nna_mel_backward   given gout_dev[B, n_mels, T] = dLoss/d(output of nna_mel for x_dev), writes any of
+ *                        gmelw_dev[n_mels, F] = sum_{b,t} gout[b, m, t] P[b, k, t],  P = |X|^power,
+ *                        gw_dev[2F, K] and gx_dev[B, L]: the gradient gP[b, k, t] = sum_m Wmel[m, k]
+ *                        gout[b, m, t] reaching the STFT stage, carried on as in nna_stft_backward
+ *                        (format power or magnitude according to the plan's `power`).
+ *                      NULL pointers are skipped (at least one must be given).  workspace_dev: 256-byte
+ *                      aligned, nna_mel_backward_workspace bytes (the spectrogram P, gP and the STFT
+ *                      stage's G).  Outputs are overwritten; atomics as in nna_stft_backward.
+ */
+nna_status nna_plan_get_mel_weights(const nna_plan* plan, float* w_dev, void* hip_stream);
+nna_status nna_plan_set_mel_weights(nna_plan* plan, const float* w_dev, void* hip_stream);
+nna_status nna_mel_backward_workspace(const nna_plan* plan, long long B, long long L, size_t* bytes);
+nna_status nna_mel_backward(const nna_plan* plan, const float* x_dev, long long B, long long L, const float* gout_dev,
+                            float* gmelw_dev, float* gw_dev, float* gx_dev, void* workspace_dev,
+                            size_t workspace_bytes, void* hip_stream);
 
 /* Downsampling CQT plans only: *part = the plan of octave `index` (0 = top; a plan as from
  * nna_plan_cqt -- from nna_plan_cqt1992 for a plan made by nna_plan_cqt2010 -- for nna_plan_bank /

@@ -29,6 +29,7 @@ EXPORTS = [
     "nna_plan_bank", "nna_plan_mel_weights", "nna_plan_info", "nna_plan_cqt_lengths", "nna_plan_sigma", "nna_cqt2010v2_workspace",
     "nna_cqt2010v2", "nna_plan_part", "nna_plan_cqt1992", "nna_cqt1992", "nna_plan_spectral_kernels",
     "nna_plan_cqt2010", "nna_cqt2010",
+    "nna_plan_get_mel_weights", "nna_plan_set_mel_weights", "nna_mel_backward_workspace", "nna_mel_backward",
     "nna_plan_trainable", "nna_plan_get_bank", "nna_plan_set_bank", "nna_stft_backward_workspace", "nna_stft_backward",
     "nna_plan_destroy",
     "nna_status_str", "nna_last_error",
@@ -84,6 +85,10 @@ def lib():
         L.nna_plan_cqt2010.argtypes = [PP, _c.c_int, _c.c_int, _c.c_double, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
                                        _c.c_int, _c.c_int, _c.c_int]
         L.nna_plan_part.argtypes = [_VP, _c.c_int, PP]
+        L.nna_plan_get_mel_weights.argtypes = [_VP, _VP, _VP]
+        L.nna_plan_set_mel_weights.argtypes = [_VP, _VP, _VP]
+        L.nna_mel_backward_workspace.argtypes = [_VP, _LL, _LL, _c.POINTER(_c.c_size_t)]
+        L.nna_mel_backward.argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _VP, _VP, _VP, _c.c_size_t, _VP]
         L.nna_plan_trainable.argtypes = [_VP]
         L.nna_plan_get_bank.argtypes = [_VP, _VP, _VP]
         L.nna_plan_set_bank.argtypes = [_VP, _VP, _VP]
@@ -392,3 +397,57 @@ def nna_stft_backward(plan: Plan, x, gout, want_gw=True, want_gx=True, workspace
                                    gw.data_ptr() if want_gw else None, gx.data_ptr() if want_gx else None,
                                    workspace.data_ptr(), ws_bytes, _stream_of(x, stream)))
     return gw, gx
+
+
+def _mel_shape(plan: Plan):
+    i = plan.info()
+    return (i["out_bins"], i["bank_rows"] // 2)
+
+
+def nna_plan_get_mel_weights(plan: Plan, stream=None):
+    """Wmel[n_mels, F]: the filterbank of a trainable Mel plan as a float32 CUDA tensor."""
+    import torch
+
+    out = torch.empty(_mel_shape(plan), dtype=torch.float32, device=f"cuda:{plan.device}")
+    _check(lib().nna_plan_get_mel_weights(plan.handle, out.data_ptr(), _stream_of(out, stream)))
+    return out
+
+
+def nna_plan_set_mel_weights(plan: Plan, W, stream=None):
+    shape = _mel_shape(plan)
+    if not (W.is_cuda and W.element_size() == 4 and W.dtype.is_floating_point and W.is_contiguous()
+            and tuple(W.shape) == shape and W.device.index == plan.device):
+        raise TypeError(f"W must be a contiguous float32 CUDA tensor of shape {shape} on the plan's device")
+    _check(lib().nna_plan_set_mel_weights(plan.handle, W.data_ptr(), _stream_of(W, stream)))
+
+
+def nna_mel_backward_workspace(plan: Plan, B: int, L: int) -> int:
+    n = _c.c_size_t()
+    _check(lib().nna_mel_backward_workspace(plan.handle, B, L, _c.byref(n)))
+    return n.value
+
+
+def nna_mel_backward(plan: Plan, x, gout, want_gmelw=True, want_gw=True, want_gx=True, workspace=None, stream=None):
+    """(gWmel[n_mels, F], gW[2F, K], gx[B, L]) (None where not wanted) = gradients of a loss through
+    nna_mel(plan, x), given gout[B, n_mels, T] = dLoss/dout."""
+    import torch
+
+    if not (isinstance(x, torch.Tensor) and x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.dim() == 2):
+        raise TypeError("x must be a contiguous float32 CUDA tensor [B, L]")
+    B, L = x.shape
+    bins, frames = nna_out_shape(plan, B, L)
+    if not (gout.is_cuda and gout.dtype == torch.float32 and gout.is_contiguous()
+            and tuple(gout.shape) == (B, bins, frames) and gout.device == x.device):
+        raise TypeError(f"gout must be a contiguous float32 CUDA tensor of shape {(B, bins, frames)}")
+    need = nna_mel_backward_workspace(plan, B, L)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    gm = torch.empty(_mel_shape(plan), dtype=torch.float32, device=x.device) if want_gmelw else None
+    gw = torch.empty(_bank_shape(plan), dtype=torch.float32, device=x.device) if want_gw else None
+    gx = torch.empty_like(x) if want_gx else None
+    _check(lib().nna_mel_backward(plan.handle, x.data_ptr(), B, L, gout.data_ptr(),
+                                  gm.data_ptr() if want_gmelw else None, gw.data_ptr() if want_gw else None,
+                                  gx.data_ptr() if want_gx else None, workspace.data_ptr(), ws_bytes,
+                                  _stream_of(x, stream)))
+    return gm, gw, gx

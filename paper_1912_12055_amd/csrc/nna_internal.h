@@ -177,7 +177,25 @@ struct BankPermuteParams {
   int n_rt, n_chunks, nj, hop, K, kp, n_half, packed;
 };
 
+// The Mel layer's two small contractions of the backward pass (per waveform b, frames t contiguous):
+//   gP[b, k, t]   = sum_m W[m, k] g[b, m, t]        (gradient reaching the STFT's output)
+//   gW[m, k]     += sum_{b,t} g[b, m, t] P[b, k, t]   (gradient of the filterbank)
+struct MelBwParams {
+  const float* g;        // upstream gradient [B][n_mels][T]
+  const float* wrm;      // filterbank, row-major [mels_pad][fp], zero padded (fp a multiple of BW_MT)
+  const float* P;        // |X|^power [B][F][T]                      (filterbank gradient)
+  float* gP;             // [B][F][T]                                (gradient to the STFT output)
+  float* gW;             // [n_mels][F], zeroed; partial sums are added atomically
+  long long B;
+  int T, F, n_mels, fp, mels_pad;
+  int b_per_split;       // filterbank gradient: waveforms per workgroup
+};
+
 hipError_t launch_stft(const StftParams& p, int mode, hipStream_t stream);
+hipError_t launch_mel_bw_spec(const MelBwParams& p, hipStream_t stream);    // gP
+hipError_t launch_mel_bw_weights(const MelBwParams& p, hipStream_t stream); // gW
+hipError_t launch_mel_from_logical(const float* w, float* frag, float* wnyq, float* wrm, int n_mels, int n_half, int n_rt,
+                                   int n_pass, int fp, hipStream_t stream);
 hipError_t launch_fill_zero(float* p, long long n, hipStream_t stream);
 hipError_t launch_fill_zero_frames(float* gbuf, long long rows_pad, long long f0, long long f1, hipStream_t stream);
 hipError_t launch_bank_from_logical(const BankPermuteParams& p, hipStream_t stream);  // logical -> bank, wrm

@@ -101,6 +101,9 @@ struct nna_plan {
   // backward pass's waveform gradient; kept in step with d_bank by nna_plan_set_bank
   float* d_wrm = nullptr;
   int kp = 0, rows_pad = 0;
+  // trainable Mel plans: the filterbank row-major [mels_pad][fp], zero padded
+  float* d_melw_rm = nullptr;
+  int fp = 0, mels_pad = 0;
   float* d_melw = nullptr;
   unsigned char* d_mel_mask = nullptr;
   float* d_mel_wnyq = nullptr;
@@ -1578,7 +1581,8 @@ nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long l
 // ---- trainable Fourier kernels (Sec. IV-C) ----------------------------------------------------
 static nna_status check_trainable_kind(const nna_plan* plan) {
   if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
-  if (plan->kind != NNA_KIND_STFT) return fail(NNA_ERR_INVALID_ARG, "only STFT plans have trainable kernels");
+  if (plan->kind != NNA_KIND_STFT && plan->kind != NNA_KIND_MEL)
+    return fail(NNA_ERR_INVALID_ARG, "only STFT and Mel plans have trainable kernels");
   if (plan->precision != NNA_PREC_F32) return fail(NNA_ERR_UNSUPPORTED, "trainable kernels need a float32 plan");
   if (plan->device < 0) return fail(NNA_ERR_UNSUPPORTED, "host-only plan (device = -1)");
   return NNA_OK;
@@ -1618,6 +1622,38 @@ nna_status nna_plan_trainable(nna_plan* plan) {
     (void)hipFree(plan->d_wrm);
     plan->d_wrm = nullptr;
     return fail_hip(e, "row-major kernel bank");
+  }
+  if (plan->kind == NNA_KIND_MEL) {
+    // Trained filters are no longer triangles: from here on every 32 x 16 weight block is multiplied
+    // and every pass sweeps all row tiles.  The filterbank gets its row-major copy.
+    const int F = plan->n_half + 1;
+    plan->fp = (F + nna::BW_MT - 1) / nna::BW_MT * nna::BW_MT;
+    plan->mels_pad = (plan->n_mels + nna::BW_KC - 1) / nna::BW_KC * nna::BW_KC;
+    std::vector<unsigned char> mask((size_t)plan->n_pass * plan->n_rt * ST_RB, (unsigned char)((1u << ST_MEL_BLOCKS) - 1));
+    std::vector<int> pass_rt((size_t)plan->n_pass * 2);
+    for (int p = 0; p < plan->n_pass; ++p) {
+      pass_rt[2 * p] = 0;
+      pass_rt[2 * p + 1] = plan->n_rt;
+    }
+    std::vector<float> rm((size_t)plan->mels_pad * plan->fp, 0.0f);
+    for (int m = 0; m < plan->n_mels; ++m)
+      for (int k = 0; k < F; ++k) rm[(size_t)m * plan->fp + k] = plan->h_melW[(size_t)m * F + k];
+    s = upload(&plan->d_melw_rm, rm.data(), rm.size() * sizeof(float), "row-major filterbank");
+    if (s == NNA_OK) {
+      e = hipMemcpy(plan->d_mel_mask, mask.data(), mask.size(), hipMemcpyHostToDevice);
+      if (e == hipSuccess) e = hipMemcpy(plan->d_mel_pass_rt, pass_rt.data(), pass_rt.size() * sizeof(int), hipMemcpyHostToDevice);
+      if (e != hipSuccess) s = fail_hip(e, "filterbank tables");
+    }
+    if (s != NNA_OK) {
+      (void)hipFree(plan->d_wrm);
+      (void)hipFree(plan->d_melw_rm);
+      plan->d_wrm = plan->d_melw_rm = nullptr;
+      return s;
+    }
+    plan->mel_nyq_any = 1;
+    const double k_exec = (double)plan->n_chunks * plan->nj * ST_KC;
+    plan->exec_flops = plan->n_pass * (2.0 * k_exec * ST_ROWS * plan->n_rt + (double)plan->n_rt * ST_RB * ST_MEL_BLOCKS * 2.0 * 32 * 16);
+    plan->alg_flops = 2.0 * (double)plan->K * (double)plan->K + 2.0 * (double)plan->n_mels * F;
   }
   return NNA_OK;
 }
@@ -1666,19 +1702,11 @@ nna_status nna_stft_backward_workspace(const nna_plan* plan, long long B, long l
   return NNA_OK;
 }
 
-nna_status nna_stft_backward(const nna_plan* plan, const float* x_dev, long long B, long long L, const float* gout_dev,
-                             float* gw_dev, float* gx_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
-  nna_status s = check_trainable(plan);
-  if (s != NNA_OK) return s;
-  if (!gout_dev) return fail(NNA_ERR_INVALID_ARG, "gout_dev is NULL");
-  if (!gw_dev && !gx_dev) return fail(NNA_ERR_INVALID_ARG, "gw_dev and gx_dev are both NULL: nothing to compute");
-  long long T = 0;
-  // (check_call wants an output pointer; the gradient buffers play that part)
-  if ((s = check_call(plan, NNA_KIND_STFT, x_dev, B, L, gw_dev ? gw_dev : gx_dev, &T)) != NNA_OK) return s;
-  size_t need = 0;
-  if ((s = nna_stft_backward_workspace(plan, B, L, &need)) != NNA_OK) return s;
-  if (!workspace_dev || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace_dev) & 255))
-    return fail(NNA_ERR_INVALID_ARG, "workspace_dev is NULL, not 256-byte aligned or smaller than nna_stft_backward_workspace asks for");
+// The backward pass of the STFT stage: gout[B, out_bins, T] is the gradient with respect to the stage's
+// output in format `fmt`; gbuf holds G (rows_pad x padded frames floats).  Arguments already checked.
+static nna_status stft_backward_core(const nna_plan* plan, const float* x_dev, long long B, long long L, long long T,
+                                     const float* gout_dev, int fmt, int out_bins, float* gw_dev, float* gx_dev,
+                                     float* gbuf, void* hip_stream) {
   const int M = pick_tile_frames(ST_FRAMES, T, plan->nj - 1, ST_LDS_ROWS);
   if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
@@ -1686,7 +1714,6 @@ nna_status nna_stft_backward(const nna_plan* plan, const float* x_dev, long long
   hipError_t e = guard.enter(plan->device);
   if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
 
-  float* gbuf = static_cast<float*>(workspace_dev);
   const long long n_frames = B * T, gpitch = bw_gpitch(n_frames);
   const int packed = plan->freq_scale ? 0 : 1;
   // 1. G = dLoss/dC: the forward contraction again, its epilogue turned into the output format's derivative
@@ -1701,8 +1728,8 @@ nna_status nna_stft_backward(const nna_plan* plan, const float* x_dev, long long
   P.nj = plan->nj;
   P.n_half = plan->n_half;
   P.packed = packed;
-  P.out_bins = plan->out_rows();
-  P.fmt = plan->fmt;
+  P.out_bins = out_bins;
+  P.fmt = fmt;
   P.tile_frames = M;
   P.n_ft = (n_frames + M - 1) / M;
   P.gout = gout_dev;
@@ -1742,6 +1769,146 @@ nna_status nna_stft_backward(const nna_plan* plan, const float* x_dev, long long
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
     e = nna::launch_bw_wave(Q, stream);
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  }
+  return NNA_OK;
+}
+
+nna_status nna_stft_backward(const nna_plan* plan, const float* x_dev, long long B, long long L, const float* gout_dev,
+                             float* gw_dev, float* gx_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+  nna_status s = check_trainable(plan);
+  if (s != NNA_OK) return s;
+  if (plan->kind != NNA_KIND_STFT) return fail(NNA_ERR_INVALID_ARG, "plan was built for a different transform");
+  if (!gout_dev) return fail(NNA_ERR_INVALID_ARG, "gout_dev is NULL");
+  if (!gw_dev && !gx_dev) return fail(NNA_ERR_INVALID_ARG, "gw_dev and gx_dev are both NULL: nothing to compute");
+  long long T = 0;
+  // (check_call wants an output pointer; the gradient buffers play that part)
+  if ((s = check_call(plan, NNA_KIND_STFT, x_dev, B, L, gw_dev ? gw_dev : gx_dev, &T)) != NNA_OK) return s;
+  size_t need = 0;
+  if ((s = nna_stft_backward_workspace(plan, B, L, &need)) != NNA_OK) return s;
+  if (!workspace_dev || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace_dev) & 255))
+    return fail(NNA_ERR_INVALID_ARG, "workspace_dev is NULL, not 256-byte aligned or smaller than nna_stft_backward_workspace asks for");
+  return stft_backward_core(plan, x_dev, B, L, T, gout_dev, plan->fmt, plan->out_rows(), gw_dev, gx_dev,
+                            static_cast<float*>(workspace_dev), hip_stream);
+}
+
+// ---- trainable Mel layer -----------------------------------------------------------------------
+static nna_status check_trainable_mel(const nna_plan* plan) {
+  nna_status s = check_trainable(plan);
+  if (s != NNA_OK) return s;
+  if (plan->kind != NNA_KIND_MEL) return fail(NNA_ERR_INVALID_ARG, "not a Mel plan");
+  return NNA_OK;
+}
+
+nna_status nna_plan_get_mel_weights(const nna_plan* plan, float* w_dev, void* hip_stream) {
+  nna_status s = check_trainable_mel(plan);
+  if (s != NNA_OK) return s;
+  if (!w_dev) return fail(NNA_ERR_INVALID_ARG, "w_dev is NULL");
+  DeviceGuard guard;
+  hipError_t e = guard.enter(plan->device);
+  if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+  const size_t F = plan->n_half + 1;
+  e = hipMemcpy2DAsync(w_dev, F * sizeof(float), plan->d_melw_rm, (size_t)plan->fp * sizeof(float), F * sizeof(float),
+                       plan->n_mels, hipMemcpyDeviceToDevice, reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail_hip(e, "filterbank copy");
+  return NNA_OK;
+}
+
+nna_status nna_plan_set_mel_weights(nna_plan* plan, const float* w_dev, void* hip_stream) {
+  nna_status s = check_trainable_mel(plan);
+  if (s != NNA_OK) return s;
+  if (!w_dev) return fail(NNA_ERR_INVALID_ARG, "w_dev is NULL");
+  DeviceGuard guard;
+  hipError_t e = guard.enter(plan->device);
+  if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+  e = nna::launch_mel_from_logical(w_dev, plan->d_melw, plan->d_mel_wnyq, plan->d_melw_rm, plan->n_mels, plan->n_half,
+                                   plan->n_rt, plan->n_pass, plan->fp, reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  return NNA_OK;
+}
+
+static size_t ws256(size_t bytes) { return (bytes + 255) / 256 * 256; }
+
+nna_status nna_mel_backward_workspace(const nna_plan* plan, long long B, long long L, size_t* bytes) {
+  nna_status s = check_trainable_mel(plan);
+  if (s != NNA_OK) return s;
+  if (!bytes) return fail(NNA_ERR_INVALID_ARG, "bytes is NULL");
+  if (B < 1) return fail(NNA_ERR_SHAPE, "B must be >= 1");
+  const long long T = frames_of(plan, L);
+  if (T < 1) return fail(NNA_ERR_SHAPE, plan->center ? "L must exceed the reflection padding (K/2)" : "L is shorter than one window");
+  const size_t spec = ws256((size_t)B * (plan->n_half + 1) * T * sizeof(float));
+  *bytes = 2 * spec + (size_t)plan->rows_pad * (size_t)bw_gpitch(B * T) * sizeof(float);
+  return NNA_OK;
+}
+
+nna_status nna_mel_backward(const nna_plan* plan, const float* x_dev, long long B, long long L, const float* gout_dev,
+                            float* gmelw_dev, float* gw_dev, float* gx_dev, void* workspace_dev, size_t workspace_bytes,
+                            void* hip_stream) {
+  nna_status s = check_trainable_mel(plan);
+  if (s != NNA_OK) return s;
+  if (!gout_dev) return fail(NNA_ERR_INVALID_ARG, "gout_dev is NULL");
+  if (!gmelw_dev && !gw_dev && !gx_dev) return fail(NNA_ERR_INVALID_ARG, "all three gradient pointers are NULL: nothing to compute");
+  long long T = 0;
+  float* any_out = gmelw_dev ? gmelw_dev : gw_dev ? gw_dev : gx_dev;
+  if ((s = check_call(plan, NNA_KIND_MEL, x_dev, B, L, any_out, &T)) != NNA_OK) return s;
+  size_t need = 0;
+  if ((s = nna_mel_backward_workspace(plan, B, L, &need)) != NNA_OK) return s;
+  if (!workspace_dev || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace_dev) & 255))
+    return fail(NNA_ERR_INVALID_ARG, "workspace_dev is NULL, not 256-byte aligned or smaller than nna_mel_backward_workspace asks for");
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  const int F = plan->n_half + 1;
+  const size_t spec = ws256((size_t)B * F * T * sizeof(float));
+  float* pbuf = static_cast<float*>(workspace_dev);
+  float* gpbuf = reinterpret_cast<float*>(static_cast<char*>(workspace_dev) + spec);
+  float* gbuf = reinterpret_cast<float*>(static_cast<char*>(workspace_dev) + 2 * spec);
+  const int fmt = plan->mel_power == 2 ? NNA_OUT_POWER : NNA_OUT_MAGNITUDE;  // what the filterbank is applied to
+  DeviceGuard guard;
+  hipError_t e = guard.enter(plan->device);
+  if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+  nna::MelBwParams Q;
+  std::memset(&Q, 0, sizeof(Q));
+  Q.g = gout_dev;
+  Q.wrm = plan->d_melw_rm;
+  Q.P = pbuf;
+  Q.gP = gpbuf;
+  Q.gW = gmelw_dev;
+  Q.B = B;
+  Q.T = (int)T;
+  Q.F = F;
+  Q.n_mels = plan->n_mels;
+  Q.fp = plan->fp;
+  Q.mels_pad = plan->mels_pad;
+  if (gmelw_dev) {
+    // filterbank gradient: the spectrogram the filterbank saw (the STFT stage again, written out), times gout
+    const int M = pick_tile_frames(ST_FRAMES, T, plan->nj - 1, ST_LDS_ROWS);
+    if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
+    nna::StftParams P;
+    std::memset(&P, 0, sizeof(P));
+    P.g = make_geom(plan, x_dev, B, L, T);
+    P.bank = reinterpret_cast<const float4*>(plan->d_bank);
+    P.out = pbuf;
+    P.n_rt = plan->n_rt;
+    P.n_chunks = plan->n_chunks;
+    P.nj = plan->nj;
+    P.n_half = plan->n_half;
+    P.packed = 1;
+    P.out_bins = F;
+    P.fmt = fmt;
+    P.tile_frames = M;
+    P.n_ft = (P.g.n_frames + M - 1) / M;
+    e = nna::launch_stft(P, nna::ST_MODE_STFT, stream);
+    if (e == hipSuccess) e = nna::launch_fill_zero(gmelw_dev, (long long)plan->n_mels * F, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    // about 1,024 workgroups share the output tiles
+    const long long tiles = (long long)((plan->n_mels + nna::BW_MT - 1) / nna::BW_MT) * (plan->fp / nna::BW_NT);
+    const long long splits = std::max(1LL, std::min(B, (1024 + tiles - 1) / tiles));
+    Q.b_per_split = (int)((B + splits - 1) / splits);
+    e = nna::launch_mel_bw_weights(Q, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  }
+  if (gw_dev || gx_dev) {
+    e = nna::launch_mel_bw_spec(Q, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    return stft_backward_core(plan, x_dev, B, L, T, gpbuf, fmt, F, gw_dev, gx_dev, gbuf, hip_stream);
   }
   return NNA_OK;
 }
@@ -1927,6 +2094,7 @@ void nna_plan_destroy(nna_plan* plan) {
       (void)hipFree(plan->d_bank16);
       (void)hipFree(plan->d_bank16s);
       (void)hipFree(plan->d_wrm);
+      (void)hipFree(plan->d_melw_rm);
       (void)hipFree(plan->d_melw);
       (void)hipFree(plan->d_mel_mask);
       (void)hipFree(plan->d_mel_wnyq);

@@ -26,6 +26,8 @@
 // the result) may vary from run to run.
 #include "nna_device.h"
 
+#include <algorithm>
+
 namespace nna {
 
 typedef f32x4 f32x4_u __attribute__((aligned(4)));
@@ -368,6 +370,185 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
   }
 }
 
+// ---- the Mel layer's backward contractions ------------------------------------------------------
+// Four consecutive elements c..c+3 of a row of `lim` elements (zero beyond it, or if the row does not
+// exist); rows of the caller's arrays start at any 4-byte boundary.
+__device__ __forceinline__ f32x4 load4_guarded(const float* row, int c, int lim) {
+  f32x4 v = {0.f, 0.f, 0.f, 0.f};
+  if (row) {
+    if (c + 3 < lim) {
+      v = *reinterpret_cast<const f32x4_u*>(row + c);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (c + i < lim) v[i] = row[c + i];
+    }
+  }
+  return v;
+}
+
+constexpr int MEL_BW_SPEC = 0, MEL_BW_WEIGHTS = 1;
+
+// Same 128 x 128 tile, wave grid and MFMA as bw_gemm_kernel; these two contractions are small
+// (2 n_mels F flop per frame each, 3 % of the STFT's) and bound by reading / writing the [B, F, T]
+// arrays, so the chunk loop is the plain one: load, barrier, write LDS, barrier, multiply.
+//   MEL_BW_SPEC:    C[k, t] (one waveform)  A = W[m][k] (k-major: row = contraction index), B = g[b][m][t] (k-major)
+//   MEL_BW_WEIGHTS: C[m, k]                 A = g[b][m][t], B = P[b][k][t] (both: row = output index, contraction contiguous)
+template <int MODE>
+__global__ __launch_bounds__(256, 2) void mel_bw_kernel(const MelBwParams P) {
+  constexpr int TILE_FLOATS = MODE == MEL_BW_SPEC ? BW_KC * BW_PK : BW_MT * BW_PA_M;
+  __shared__ __attribute__((aligned(16))) float ldsA[TILE_FLOATS];
+  __shared__ __attribute__((aligned(16))) float ldsB[TILE_FLOATS];
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int h = lane >> 5, r32 = lane & 31;
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+  auto multiply = [&]() {
+#pragma unroll
+    for (int kg = 0; kg < BW_KC / 8; ++kg) {
+      f32x4 a[2], b[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        if constexpr (MODE == MEL_BW_SPEC) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            a[i][e] = ldsA[(8 * kg + 4 * h + e) * BW_PK + wm * 64 + i * 32 + r32];
+            b[i][e] = ldsB[(8 * kg + 4 * h + e) * BW_PK + wn * 64 + i * 32 + r32];
+          }
+        } else {
+          a[i] = *reinterpret_cast<const f32x4*>(ldsA + (wm * 64 + i * 32 + r32) * BW_PA_M + 8 * kg + 4 * h);
+          b[i] = *reinterpret_cast<const f32x4*>(ldsB + (wn * 64 + i * 32 + r32) * BW_PA_M + 8 * kg + 4 * h);
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < 2; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][e], b[ni][e], acc[mi][ni], 0, 0, 0);
+    }
+  };
+
+  if constexpr (MODE == MEL_BW_SPEC) {
+    const int n_mt = P.fp / BW_MT, n_nt = (P.T + BW_NT - 1) / BW_NT;
+    const long long b = blockIdx.x / (n_mt * n_nt);
+    const int tile = (int)(blockIdx.x - b * (n_mt * n_nt));
+    const int k0 = (tile / n_nt) * BW_MT, t0 = (tile % n_nt) * BW_NT;  // bins, frames of this tile
+    const float* gb = P.g + b * (long long)P.n_mels * P.T;
+    for (int m0 = 0; m0 < P.mels_pad; m0 += BW_KC) {
+      f32x4 ra[4], rb[4];
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const int m = m0 + (tid >> 5) + 8 * p;  // contraction index: the mel
+        ra[p] = *reinterpret_cast<const f32x4*>(P.wrm + (long long)m * P.fp + k0 + 4 * (tid & 31));
+        rb[p] = load4_guarded(m < P.n_mels ? gb + (long long)m * P.T : nullptr, t0 + 4 * (tid & 31), P.T);
+      }
+      __syncthreads();
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        *reinterpret_cast<f32x4*>(ldsA + ((tid >> 5) + 8 * p) * BW_PK + 4 * (tid & 31)) = ra[p];
+        *reinterpret_cast<f32x4*>(ldsB + ((tid >> 5) + 8 * p) * BW_PK + 4 * (tid & 31)) = rb[p];
+      }
+      __syncthreads();
+      multiply();
+    }
+    float* __restrict__ ob = P.gP + b * (long long)P.F * P.T;
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni) {
+        const int t = t0 + wn * 64 + ni * 32 + r32;
+        if (t >= P.T) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int k = k0 + wm * 64 + mi * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+          if (k < P.F) ob[(long long)k * P.T + t] = acc[mi][ni][r];
+        }
+      }
+  } else {
+    const int n_nt = P.fp / BW_NT, n_mt = (P.n_mels + BW_MT - 1) / BW_MT;
+    const long long split = blockIdx.x / (n_mt * n_nt);
+    const int tile = (int)(blockIdx.x - split * (n_mt * n_nt));
+    const int m0 = (tile / n_nt) * BW_MT, k0 = (tile % n_nt) * BW_NT;  // mels, bins of this tile
+    const long long b_begin = split * P.b_per_split;
+    const long long b_end = b_begin + P.b_per_split < P.B ? b_begin + P.b_per_split : P.B;
+    for (long long b = b_begin; b < b_end; ++b) {
+      const float* gb = P.g + b * (long long)P.n_mels * P.T;
+      const float* pb = P.P + b * (long long)P.F * P.T;
+      for (int t0 = 0; t0 < P.T; t0 += BW_KC) {
+        f32x4 ra[4], rb[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const int row = (tid >> 3) + 32 * p;  // output index: mel (A), bin (B); contraction = frames
+          ra[p] = load4_guarded(m0 + row < P.n_mels ? gb + (long long)(m0 + row) * P.T : nullptr, t0 + 4 * (tid & 7), P.T);
+          rb[p] = load4_guarded(k0 + row < P.F ? pb + (long long)(k0 + row) * P.T : nullptr, t0 + 4 * (tid & 7), P.T);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          *reinterpret_cast<f32x4*>(ldsA + ((tid >> 3) + 32 * p) * BW_PA_M + 4 * (tid & 7)) = ra[p];
+          *reinterpret_cast<f32x4*>(ldsB + ((tid >> 3) + 32 * p) * BW_PA_M + 4 * (tid & 7)) = rb[p];
+        }
+        __syncthreads();
+        multiply();
+      }
+    }
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni) {
+        const int k = k0 + wn * 64 + ni * 32 + r32;
+        if (k >= P.F) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = m0 + wm * 64 + mi * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+          if (m < P.n_mels) unsafeAtomicAdd(P.gW + (long long)m * P.F + k, acc[mi][ni][r]);
+        }
+      }
+  }
+}
+
+// The filterbank from its logical layout W[n_mels][n_half + 1] into the forward kernel's fragment
+// order [pass][row tile][row block][32-mel block][2][64 lanes] x float4 (lane (h, m) of quad v, element
+// e holds mel pass*128 + mb*32 + m, bin rt*64 + rb*16 + 4 ((4 v + e) / 2) + 2 h + (4 v + e) % 2), the
+// Nyquist-bin weights and the zero-padded row-major copy the backward pass reads.
+__global__ void mel_from_logical_kernel(const float* __restrict__ w, float* __restrict__ frag, float* __restrict__ wnyq,
+                                        float* __restrict__ wrm, int n_mels, int n_half, int n_rt, int n_pass, int fp,
+                                        long long n4) {
+  const long long i4 = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int F = n_half + 1;
+  if (i4 < (long long)n_mels * F) {  // row-major copy and Nyquist weights ride along on the first threads
+    const int m = (int)(i4 / F), k = (int)(i4 - (long long)m * F);
+    const float x = w[i4];
+    wrm[(long long)m * fp + k] = x;
+    if (k == n_half) wnyq[m] = x;
+  }
+  if (i4 >= n4) return;
+  const int lane = (int)(i4 & 63), v = (int)((i4 >> 6) & 1), mb = (int)((i4 >> 7) % ST_MEL_BLOCKS);
+  const long long rest = (i4 >> 7) / ST_MEL_BLOCKS;  // (pass * n_rt + rt) * ST_RB + rb
+  const int rb = (int)(rest % ST_RB), rt = (int)((rest / ST_RB) % n_rt), pass = (int)(rest / ST_RB / n_rt);
+  const int hh = lane >> 5, mel = pass * (32 * ST_MEL_BLOCKS) + mb * 32 + (lane & 31);
+  f32x4 out;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int idx8 = v * 4 + e, bin = rt * (ST_ROWS / 2) + rb * 16 + 4 * (idx8 >> 1) + 2 * hh + (idx8 & 1);
+    out[e] = (mel < n_mels && bin < n_half) ? w[(long long)mel * F + bin] : 0.f;
+  }
+  reinterpret_cast<f32x4*>(frag)[i4] = out;
+  (void)n_pass;
+}
+
 // ---- launchers ---------------------------------------------------------------------------------
 static unsigned grid_for(long long n, int block) {
   long long b = (n + block - 1) / block;
@@ -430,6 +611,32 @@ hipError_t launch_bw_wave(const BwParams& p, hipStream_t stream) {
   const long long blocks = (p.gpitch / BW_MT) * (p.kp / BW_NT);
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL((bw_gemm_kernel<BW_MODE_WAVE>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_mel_bw_spec(const MelBwParams& p, hipStream_t stream) {
+  if (p.fp <= 0 || p.fp % BW_MT || p.mels_pad % BW_KC || p.mels_pad < p.n_mels || p.F > p.fp || p.T < 1) return hipErrorInvalidValue;
+  const long long blocks = p.B * (p.fp / BW_MT) * ((p.T + BW_NT - 1) / BW_NT);
+  if (blocks < 1 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((mel_bw_kernel<MEL_BW_SPEC>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_mel_bw_weights(const MelBwParams& p, hipStream_t stream) {
+  if (p.fp <= 0 || p.fp % BW_NT || p.F > p.fp || p.T < 1 || p.b_per_split < 1) return hipErrorInvalidValue;
+  const long long splits = (p.B + p.b_per_split - 1) / p.b_per_split;
+  const long long blocks = splits * ((p.n_mels + BW_MT - 1) / BW_MT) * (p.fp / BW_NT);
+  if (blocks < 1 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((mel_bw_kernel<MEL_BW_WEIGHTS>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_mel_from_logical(const float* w, float* frag, float* wnyq, float* wrm, int n_mels, int n_half, int n_rt,
+                                   int n_pass, int fp, hipStream_t stream) {
+  const long long n4 = (long long)n_pass * n_rt * ST_RB * ST_MEL_BLOCKS * 2 * 64;
+  const long long n = std::max(n4, (long long)n_mels * (n_half + 1));
+  hipLaunchKernelGGL(mel_from_logical_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, w, frag, wnyq, wrm,
+                     n_mels, n_half, n_rt, n_pass, fp, n4);
   return hipGetLastError();
 }
 

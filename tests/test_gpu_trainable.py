@@ -87,7 +87,10 @@ def test_not_trainable_plans_are_refused(nb):
         nb.nna_plan_get_bank(plan)
     assert e.value.status == nb.NNA_ERR_INVALID_ARG and "nna_plan_trainable" in e.value.message
     with pytest.raises(nb.NnaError) as e:
-        nb.nna_plan_trainable(nb.nna_plan_mel(n_fft=256, hop=64, n_mels=20, device=0))
+        nb.nna_plan_trainable(nb.nna_plan_cqt(sr=8000, hop=64, fmin=220.0, n_bins=24, device=0))
+    assert e.value.status == nb.NNA_ERR_INVALID_ARG
+    with pytest.raises(nb.NnaError) as e:
+        nb.nna_plan_get_mel_weights(nb.nna_plan_trainable(nb.nna_plan_stft(n_fft=256, hop=64, device=0)))
     assert e.value.status == nb.NNA_ERR_INVALID_ARG
     with pytest.raises(nb.NnaError) as e:
         nb.nna_plan_trainable(nb.nna_plan_stft_prec(n_fft=256, hop=64, precision=nb.NNA_PREC_F16, device=0))
@@ -185,6 +188,90 @@ def test_gradient_step_lowers_a_loss(nb):
     l1, _ = loss_and_grad()
     _say(f"  loss {l0:.4e} -> {l1:.4e}")
     assert l1 < l0
+
+
+MEL_BACKWARD_CASES = [
+    # name, B, L, sr, n_fft, hop, n_mels, scale, power, trained
+    ("40 slaney mels, filterbank as built", 2, 9000, 8000, 256, 64, 40, 0, 2.0, False),
+    ("trained stages, ragged, tiles span waveforms", 5, 20000, 8000, 256, 64, 40, 0, 2.0, True),
+    ("magnitude (power 1), htk", 3, 7000, 8000, 256, 64, 20, 1, 1.0, True),
+    ("200 mels (two passes), many short waveforms", 23, 900, 22050, 512, 128, 200, 0, 2.0, True),
+    ("n_fft 2048, hop 512, 128 mels (the workloads' layer)", 2, 30000, 44100, 2048, 512, 128, 0, 2.0, True),
+    ("hop does not divide n_fft, L not a multiple of 4", 2, 5001, 8000, 96, 25, 7, 0, 2.0, True),
+]
+
+
+@pytest.mark.parametrize("case", MEL_BACKWARD_CASES, ids=[c[0] for c in MEL_BACKWARD_CASES])
+def test_mel_backward_parity_small(nb, case):
+    name, B, L, sr, n_fft, hop, n_mels, scale, power, trained = case
+    _say(f"mel backward {name}: B={B} L={L} sr={sr} n_fft={n_fft} hop={hop} mels={n_mels} scale={scale} power={power}")
+    rng = np.random.default_rng(1300 + n_fft + n_mels)
+    x = _rand(B, L, 1301 + n_mels)
+    plan = nb.nna_plan_mel(sr=sr, n_fft=n_fft, hop=hop, n_mels=n_mels, scale=scale, power=power, device=0)
+    before = nb.nna_mel(plan, _dev(x)).cpu().numpy()
+    nb.nna_plan_trainable(plan)
+    # the dense treatment of the filters changes nothing while they are still triangles
+    np.testing.assert_allclose(nb.nna_mel(plan, _dev(x)).cpu().numpy(), before, rtol=1e-5, atol=1e-6 * before.max())
+    np.testing.assert_array_equal(nb.nna_plan_get_mel_weights(plan).cpu().numpy().astype(np.float64),
+                                  nb.nna_plan_mel_weights(plan))
+    if trained:
+        W0 = nb.nna_plan_get_bank(plan).cpu().numpy()
+        nb.nna_plan_set_bank(plan, _dev((W0 + 0.05 * rng.standard_normal(W0.shape)).astype(np.float32)))
+        M0 = nb.nna_plan_get_mel_weights(plan).cpu().numpy()
+        M1 = (M0 + 0.1 * M0.max() * rng.standard_normal(M0.shape)).astype(np.float32)
+        nb.nna_plan_set_mel_weights(plan, _dev(M1))
+        np.testing.assert_array_equal(nb.nna_plan_get_mel_weights(plan).cpu().numpy(), M1)
+        np.testing.assert_array_equal(nb.nna_plan_mel_weights(plan), M1.astype(np.float64))
+    W = nb.nna_plan_get_bank(plan).cpu().numpy().astype(np.float64)
+    Wmel = nb.nna_plan_get_mel_weights(plan).cpu().numpy().astype(np.float64)
+    out = nb.nna_mel(plan, _dev(x)).cpu().numpy()
+    e_out = _peak_err(out, oracle.mel_bank(x, W, Wmel, hop=hop, power=power))
+    gout = rng.standard_normal(out.shape).astype(np.float32)
+    gm, gw, gx = nb.nna_mel_backward(plan, _dev(x), _dev(gout))
+    ref_gm, ref_gw, ref_gx = oracle.mel_bank_backward(x, W, Wmel, gout, hop=hop, power=power)
+    ref_gw[1] = 0.0  # the two sine kernels that are not parameters
+    ref_gw[-1] = 0.0
+    e_m, e_w, e_x = _peak_err(gm.cpu().numpy(), ref_gm), _peak_err(gw.cpu().numpy(), ref_gw), _peak_err(gx.cpu().numpy(), ref_gx)
+    _say(f"  forward {e_out:.3e}, filterbank gradient {e_m:.3e}, bank gradient {e_w:.3e}, waveform gradient {e_x:.3e}")
+    assert e_out < TOL and e_m < TOL and e_w < TOL and e_x < TOL
+    # any subset of the three
+    gm2, n1, n2 = nb.nna_mel_backward(plan, _dev(x), _dev(gout), want_gw=False, want_gx=False)
+    assert n1 is None and n2 is None and _peak_err(gm2.cpu().numpy(), ref_gm) < TOL
+    n0, n1, gx2 = nb.nna_mel_backward(plan, _dev(x), _dev(gout), want_gmelw=False, want_gw=False)
+    assert n0 is None and n1 is None and _peak_err(gx2.cpu().numpy(), ref_gx) < TOL
+
+
+def test_mel_backward_config4_full_sampled(nb):
+    # as for the STFT layer: the full 1,770-waveform launch, upstream gradient on five waveforms
+    import torch
+    _say("mel backward config 4 (1770 x 176400 @ 44100 Hz, 128 mels) sampled waveforms")
+    wl = signals.WORKLOADS[4]
+    B, L = wl["B"], wl["L"]
+    x = torch.empty((B, L), dtype=torch.float32, device="cuda:0")
+    for s in range(0, B, 128):
+        idx = list(range(s, min(B, s + 128)))
+        x[s:s + len(idx)] = torch.from_numpy(signals.batch(4, idx)).to("cuda:0")
+    sampled = [0, 1, 885, 1768, 1769]
+    plan = nb.nna_plan_trainable(nb.nna_plan_mel(sr=44100, n_fft=2048, hop=512, n_mels=128, fmin=0.0, fmax=22050.0, device=0))
+    W = nb.nna_plan_get_bank(plan).cpu().numpy().astype(np.float64)
+    Wmel = nb.nna_plan_get_mel_weights(plan).cpu().numpy().astype(np.float64)
+    T = 1 + L // 512
+    gs = np.random.default_rng(45).standard_normal((len(sampled), 128, T)).astype(np.float32)
+    gout = torch.zeros((B, 128, T), dtype=torch.float32, device="cuda:0")
+    gout[sampled] = torch.from_numpy(gs).to("cuda:0")
+    gm, gw, gx = nb.nna_mel_backward(plan, x, gout)
+    torch.cuda.synchronize()
+    xs = signals.batch(4, sampled)
+    ref_gm, ref_gw, ref_gx = oracle.mel_bank_backward(xs, W, Wmel, gs, hop=512, power=2.0)
+    ref_gw[1] = 0.0
+    ref_gw[-1] = 0.0
+    e_m, e_w = _peak_err(gm.cpu().numpy(), ref_gm), _peak_err(gw.cpu().numpy(), ref_gw)
+    e_x = _peak_err(gx[sampled].cpu().numpy(), ref_gx)
+    _say(f"  filterbank gradient {e_m:.3e}, bank gradient {e_w:.3e}, waveform gradient {e_x:.3e}")
+    assert e_m < TOL and e_w < TOL and e_x < TOL
+    rest = torch.ones(B, dtype=torch.bool, device="cuda:0")
+    rest[sampled] = False
+    assert not gx[rest].any()
 
 
 def test_backward_config4_full_sampled(nb):
