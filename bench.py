@@ -238,7 +238,32 @@ def main() -> int:
             "mfma_frac": round(alg / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
             "mfma_peak_tflops": PEAK_FP32_MFMA_TFLOPS,
         }
-        del gout, ws_bw
+        del gout, ws_bw, p_tr
+        # backward pass of the Mel layer (filterbank, kernel-bank and waveform gradients): the three
+        # contractions above plus the Mel stage's two small ones (2 n_mels F flop per frame each)
+        p_trm = nb.nna_plan_trainable(nb.nna_plan_mel(sr=sr, n_fft=2048, hop=512, n_mels=128, fmin=0.0, fmax=22050.0, device=0))
+        gmel = torch.ones((B, 128, T), dtype=torch.float32, device=dev)
+        ws_bw = torch.empty(nb.nna_mel_backward_workspace(p_trm, B, L), dtype=torch.uint8, device=dev)
+        for _ in range(max(1, args.warmup)):
+            nb.nna_mel_backward(p_trm, x4, gmel, workspace=ws_bw)
+        ev = []
+        for _ in range(args.steps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            nb.nna_mel_backward(p_trm, x4, gmel, workspace=ws_bw)
+            b.record()
+            ev.append((a, b))
+        torch.cuda.synchronize()
+        ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+        alg = (3 * 2.0 * 2048 * 2048 + 2 * 2.0 * 128 * 1025) * B * T
+        extras["mel_backward"] = {
+            "ms": round(ms, 4),
+            "gsamples_per_s": round(B * L / ms / 1e6, 4),
+            "algorithmic_tflops": round(alg / ms / 1e9, 3),
+            "mfma_frac": round(alg / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+            "mfma_peak_tflops": PEAK_FP32_MFMA_TFLOPS,
+        }
+        del gmel, ws_bw
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -314,7 +314,7 @@ __device__ __forceinline__ float grad_scale(float g, float pw) {
 template <int FMT>
 __device__ __forceinline__ void stft_grad_tile(const f32x16 (&acc)[ST_RB], const float* __restrict__ gp, long long T,
                                                float* __restrict__ Gp, long long gpitch, int slot_base, int h,
-                                               int n_half, int packed) {
+                                               int n_half, int packed, float* __restrict__ pp = nullptr) {
 #pragma unroll
   for (int rb = 0; rb < ST_RB; ++rb)
 #pragma unroll
@@ -342,10 +342,16 @@ __device__ __forceinline__ void stft_grad_tile(const f32x16 (&acc)[ST_RB], const
       } else if (slot == 0 && packed) {
         gr = grad_scale<FMT>(gp[0], re * re) * re;
         gi = grad_scale<FMT>(gp[n_half * T], im * im) * im;
+        if (pp) {  // the stage's own output, for a caller that needs it next to the gradient
+          pp[0] = format_power<FMT>(re * re);
+          pp[n_half * T] = format_power<FMT>(im * im);
+        }
       } else if (slot < n_half) {
-        const float s = grad_scale<FMT>(gp[slot * T], re * re + im * im);
+        const float pw = re * re + im * im;
+        const float s = grad_scale<FMT>(gp[slot * T], pw);
         gr = s * re;
         gi = s * im;
+        if (pp) pp[slot * T] = format_power<FMT>(pw);
       }
       Gp[(long long)(2 * slot) * gpitch] = gr;
       Gp[(long long)(2 * slot + 1) * gpitch] = gi;

@@ -84,6 +84,7 @@ struct StftParams {
   // of the loss with respect to the contraction's result, G[packed row][global frame], is written
   // from the upstream gradient gout[B, out_bins, T] (fmt selects the derivative of the output format)
   const float* gout;
+  float* pout;                // optional (magnitude / power formats): the stage's output [B, out_bins, T] as well
   float* gbuf;                // [frame / 32][n_rt * ST_ROWS packed rows][frame % 32]
   long long gpitch;           // elements between consecutive rows of gbuf (32)
   // ST_MODE_LIN only: where this plan's bins go in `out`

@@ -247,10 +247,11 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
           const float* __restrict__ gp = P.gout + (b_lane * P.out_bins) * g.T + t_lane;
           // G is stored in blocks of 32 frames: [frame / 32][packed row][frame % 32]
           float* __restrict__ Gp = P.gbuf + (f_lane >> 5) * ((long long)P.n_rt * ST_ROWS * 32) + (f_lane & 31);
+          float* __restrict__ pp = P.pout ? P.pout + (b_lane * P.out_bins) * g.T + t_lane : nullptr;
           if (P.fmt == NNA_OUT_MAGNITUDE)
-            stft_grad_tile<NNA_OUT_MAGNITUDE>(acc, gp, g.T, Gp, P.gpitch, slot_base, h, P.n_half, P.packed);
+            stft_grad_tile<NNA_OUT_MAGNITUDE>(acc, gp, g.T, Gp, P.gpitch, slot_base, h, P.n_half, P.packed, pp);
           else if (P.fmt == NNA_OUT_POWER)
-            stft_grad_tile<NNA_OUT_POWER>(acc, gp, g.T, Gp, P.gpitch, slot_base, h, P.n_half, P.packed);
+            stft_grad_tile<NNA_OUT_POWER>(acc, gp, g.T, Gp, P.gpitch, slot_base, h, P.n_half, P.packed, pp);
           else if (P.fmt == NNA_OUT_LOG)
             stft_grad_tile<NNA_OUT_LOG>(acc, gp, g.T, Gp, P.gpitch, slot_base, h, P.n_half, P.packed);
           else if (P.fmt == NNA_OUT_COMPLEX)

@@ -1704,9 +1704,11 @@ nna_status nna_stft_backward_workspace(const nna_plan* plan, long long B, long l
 
 // The backward pass of the STFT stage: gout[B, out_bins, T] is the gradient with respect to the stage's
 // output in format `fmt`; gbuf holds G (rows_pad x padded frames floats).  Arguments already checked.
+// pout (optional, magnitude / power formats): the stage's own output is written there on the way.
+// With gw_dev and gx_dev both NULL only G (and pout) are produced.
 static nna_status stft_backward_core(const nna_plan* plan, const float* x_dev, long long B, long long L, long long T,
                                      const float* gout_dev, int fmt, int out_bins, float* gw_dev, float* gx_dev,
-                                     float* gbuf, void* hip_stream) {
+                                     float* gbuf, void* hip_stream, float* pout = nullptr) {
   const int M = pick_tile_frames(ST_FRAMES, T, plan->nj - 1, ST_LDS_ROWS);
   if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
@@ -1733,6 +1735,7 @@ static nna_status stft_backward_core(const nna_plan* plan, const float* x_dev, l
   P.tile_frames = M;
   P.n_ft = (n_frames + M - 1) / M;
   P.gout = gout_dev;
+  P.pout = pout;
   P.gbuf = gbuf;
   P.gpitch = 32;  // G is stored in blocks of 32 frames: [frame / 32][packed row][frame % 32]
   e = nna::launch_stft(P, nna::ST_MODE_GRAD, stream);
@@ -1877,26 +1880,16 @@ nna_status nna_mel_backward(const nna_plan* plan, const float* x_dev, long long 
   Q.n_mels = plan->n_mels;
   Q.fp = plan->fp;
   Q.mels_pad = plan->mels_pad;
+  // 1. gP, the gradient reaching the STFT stage's output;  2. the STFT stage's backward pass, whose
+  // recomputed contraction also writes the spectrogram P the filterbank saw when its gradient is
+  // wanted;  3. filterbank gradient = gout x P.
+  e = nna::launch_mel_bw_spec(Q, stream);
+  if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  if ((s = stft_backward_core(plan, x_dev, B, L, T, gpbuf, fmt, F, gw_dev, gx_dev, gbuf, hip_stream,
+                              gmelw_dev ? pbuf : nullptr)) != NNA_OK)
+    return s;
   if (gmelw_dev) {
-    // filterbank gradient: the spectrogram the filterbank saw (the STFT stage again, written out), times gout
-    const int M = pick_tile_frames(ST_FRAMES, T, plan->nj - 1, ST_LDS_ROWS);
-    if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
-    nna::StftParams P;
-    std::memset(&P, 0, sizeof(P));
-    P.g = make_geom(plan, x_dev, B, L, T);
-    P.bank = reinterpret_cast<const float4*>(plan->d_bank);
-    P.out = pbuf;
-    P.n_rt = plan->n_rt;
-    P.n_chunks = plan->n_chunks;
-    P.nj = plan->nj;
-    P.n_half = plan->n_half;
-    P.packed = 1;
-    P.out_bins = F;
-    P.fmt = fmt;
-    P.tile_frames = M;
-    P.n_ft = (P.g.n_frames + M - 1) / M;
-    e = nna::launch_stft(P, nna::ST_MODE_STFT, stream);
-    if (e == hipSuccess) e = nna::launch_fill_zero(gmelw_dev, (long long)plan->n_mels * F, stream);
+    e = nna::launch_fill_zero(gmelw_dev, (long long)plan->n_mels * F, stream);
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
     // about 1,024 workgroups share the output tiles
     const long long tiles = (long long)((plan->n_mels + nna::BW_MT - 1) / nna::BW_MT) * (plan->fp / nna::BW_NT);
@@ -1904,11 +1897,6 @@ nna_status nna_mel_backward(const nna_plan* plan, const float* x_dev, long long 
     Q.b_per_split = (int)((B + splits - 1) / splits);
     e = nna::launch_mel_bw_weights(Q, stream);
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
-  }
-  if (gw_dev || gx_dev) {
-    e = nna::launch_mel_bw_spec(Q, stream);
-    if (e != hipSuccess) return fail_hip(e, "kernel launch");
-    return stft_backward_core(plan, x_dev, B, L, T, gpbuf, fmt, F, gw_dev, gx_dev, gbuf, hip_stream);
   }
   return NNA_OK;
 }
