@@ -176,6 +176,23 @@ def test_stft_rejects_bad_shapes(nb):
     assert nb.lib().nna_stft(mel.handle, x.data_ptr(), 1, 4096, out.data_ptr(), None) == nb.NNA_ERR_INVALID_ARG
 
 
+def test_size_limits_are_errors_not_launches(nb):
+    # empty batches and sizes beyond the kernels' 32-bit sample / frame indices are refused before anything
+    # is enqueued (the pointers are never touched: small buffers stand in for the impossible ones)
+    import torch
+    L_ = nb.lib()
+    x = torch.zeros((1, 4096), device="cuda:0")
+    out = torch.empty((1, 1025, 9), device="cuda:0")
+    for plan, fn in ((nb.nna_plan_stft(device=0), L_.nna_stft), (nb.nna_plan_mel(device=0), L_.nna_mel),
+                     (nb.nna_plan_cqt(sr=8000, hop=128, fmin=220.0, n_bins=24, n_taps=1024, device=0), L_.nna_cqt)):
+        for B, L in ((0, 4096), (-3, 4096), (1 << 41, 4096), (1, (1 << 31) + 8), (1 << 31, 1 << 20)):
+            assert fn(plan.handle, x.data_ptr(), B, L, out.data_ptr(), None) == nb.NNA_ERR_SHAPE, (B, L)
+            assert nb.nna_last_error()
+        assert fn(plan.handle, None, 1, 4096, out.data_ptr(), None) == nb.NNA_ERR_INVALID_ARG
+        assert fn(plan.handle, x.data_ptr(), 1, 4096, None, None) == nb.NNA_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+
+
 def _phase_err(got, ref_re, ref_im):
     """largest phase difference (modulo 2 pi) over the bins whose magnitude is above 1e-3 of the peak: below
     that the float32 rounding of (Re, Im) turns into an arbitrary angle"""
@@ -693,3 +710,65 @@ def test_stft_f16_config4_full_sampled(nb, batch4):
     _say(f"  rel err {e:.3e}")
     assert e < TOL
     assert torch.isfinite(out).all()
+
+
+# ---------------------------------------------------------------------------------------
+# One waveform as long as the library accepts (sample indices just below 2^31): frames sampled at
+# the start, across the signal and at the mirrored end, each against the oracle run on a slice.
+# ---------------------------------------------------------------------------------------
+def _check_long_signal(nb, plan, run, oracle_fn, K, hop, L, x):
+    import torch
+    out = run(plan, x)
+    torch.cuda.synchronize()
+    T = 1 + L // hop
+    assert out.shape[0] == 1 and out.shape[2] == T
+    worst = 0.0
+    span = 8 * K  # samples per slice, a multiple of hop
+    # the first frames (left mirror), slices inside, the last frames (right mirror)
+    head = x[0, :span].cpu().numpy()[None, :]
+    ref = oracle_fn(head, True)[0]
+    n = (span - K) // hop  # frames of the slice that do not reach past its right end
+    worst = max(worst, np.abs(out[0, :, :n].cpu().numpy() - ref[:, :n]).max() / ref.max())
+    for frac in (0.13, 0.5, 0.77, 0.999):
+        t0 = int(frac * (T - 2 * span // hop))
+        s0 = t0 * hop - K // 2  # frame t0 starts here in the un-padded signal
+        sl = x[0, s0:s0 + span].cpu().numpy()[None, :]
+        ref = oracle_fn(sl, False)[0]  # frame j of the slice = frame t0 + j
+        got = out[0, :, t0:t0 + ref.shape[1]].cpu().numpy()
+        worst = max(worst, np.abs(got - ref).max() / ref.max())
+    s0 = (L - span) // hop * hop  # a slice that ends where the signal ends, starting on a frame boundary
+    tail = x[0, s0:].cpu().numpy()[None, :]
+    ref = oracle_fn(tail, True)[0]
+    skip = (K // 2 + hop - 1) // hop  # its first frames see its own artificial left mirror
+    got = out[0, :, s0 // hop + skip:].cpu().numpy()
+    assert got.shape[1] == ref.shape[1] - skip
+    worst = max(worst, np.abs(got - ref[:, skip:]).max() / ref.max())
+    return worst
+
+
+def test_stft_longest_accepted_waveform(nb):
+    import torch
+    n_fft, hop = 2048, 512
+    L = ((1 << 31) - 1 - 4 * n_fft - 64) // 4 * 4  # the largest multiple of 4 the library takes
+    _say(f"stft, one waveform of {L} samples")
+    x = (torch.rand((1, L), device="cuda:0") - 0.5)
+    plan = nb.nna_plan_stft(n_fft=n_fft, hop=hop, device=0)
+    e = _check_long_signal(nb, plan, nb.nna_stft, lambda s, c: oracle.stft(s, n_fft=n_fft, hop=hop, center=c), n_fft, hop, L, x)
+    _say(f"  rel err {e:.3e}")
+    assert e < TOL
+    # eight samples more are refused (nothing is launched, the pointers are not touched)
+    assert nb.lib().nna_stft(plan.handle, x.data_ptr(), 1, L + 8, x.data_ptr(), None) == nb.NNA_ERR_SHAPE
+
+
+def test_cqt_longest_accepted_waveform(nb):
+    import torch
+    sr, hop, fmin, n_bins, taps = 8000, 128, 220.0, 24, 1024
+    L = ((1 << 31) - 1 - 4 * taps - 64) // 4 * 4
+    _say(f"cqt, one waveform of {L} samples")
+    x = (torch.rand((1, L), device="cuda:0") - 0.5)
+    plan = nb.nna_plan_cqt(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, n_taps=taps, device=0)
+    e = _check_long_signal(nb, plan, nb.nna_cqt,
+                           lambda s, c: oracle.cqt(s, sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, n_taps=taps, center=c),
+                           taps, hop, L, x)
+    _say(f"  rel err {e:.3e}")
+    assert e < TOL
