@@ -63,9 +63,11 @@ typedef enum {
   NNA_OUT_PHASE = 4      /* atan2(Im, Re) in [-pi, pi] */
 } nna_output;
 
-typedef enum {
-  NNA_WIN_HANN = 0, /* periodic Hann, w[n] = 1/2 - 1/2 cos(2 pi n / N) */
-  NNA_WIN_RECT = 1
+typedef enum {       /* Sec. III-A names Hann, Hamming and Blackman; all in their periodic form */
+  NNA_WIN_HANN = 0,     /* w[n] = 1/2 - 1/2 cos(2 pi n / N) */
+  NNA_WIN_RECT = 1,
+  NNA_WIN_HAMMING = 2,  /* 0.54 - 0.46 cos(2 pi n / N) */
+  NNA_WIN_BLACKMAN = 3  /* 0.42 - 0.5 cos(2 pi n / N) + 0.08 cos(4 pi n / N) */
 } nna_window;
 
 typedef enum {

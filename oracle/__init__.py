@@ -28,7 +28,7 @@ _LIB = os.path.join(_HERE, "libnna_oracle.so")
 
 MAGNITUDE, POWER, LOG = 0, 1, 2
 COMPLEX, PHASE = 3, 4  # the transform before the magnitude: (Re, Im) row pairs [B, 2 bins, T]; atan2(Im, Re)
-WIN_HANN, WIN_RECT = 0, 1
+WIN_HANN, WIN_RECT, WIN_HAMMING, WIN_BLACKMAN = 0, 1, 2, 3
 MEL_SLANEY, MEL_HTK = 0, 1
 FREQ_DFT, FREQ_LINEAR, FREQ_LOG = 0, 1, 2
 LOG_FLOOR = 1e-10
@@ -133,6 +133,9 @@ def window(kind: int, N: int) -> np.ndarray:
     w = np.empty(N, dtype=np.float64)
     _check(lib().orc_window(kind, N, _pd(w)), "window")
     return w
+
+
+_window_values = window  # (most functions below have an argument of that name)
 
 
 def stft_complex(x, n_fft=2048, hop=512, window=WIN_HANN, center=True):
@@ -392,7 +395,7 @@ def cqt2010(x, sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, win
                 if Nk > N:
                     raise OracleError("n_fft is shorter than the octave's longest kernel")
                 m = np.arange(Nk)
-                w = (0.5 - 0.5 * np.cos(2 * np.pi * m / Nk)) if window == WIN_HANN else np.ones(Nk)
+                w = _window_values(window, Nk)
                 s = (N - Nk) // 2
                 kap[k - lo, s:s + Nk] = w / w.sum() * np.exp(-2j * np.pi * Q * m / Nk)
             Y = np.conj(np.fft.fft(np.conj(kap), axis=1))[:, :F]

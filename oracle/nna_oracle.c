@@ -15,7 +15,8 @@
  * an OpenMP "parallel for" over independent (waveform, frame) pairs.
  *
  * Readings taken where the paper is silent (all listed in the design notes):
- *   - 'hann' is the periodic Hann window  w[n] = 1/2 - 1/2 cos(2 pi n / N).
+ *   - 'hann' is the periodic Hann window  w[n] = 1/2 - 1/2 cos(2 pi n / N); the Hamming and
+ *     Blackman windows the paper also names are taken in the same periodic form.
  *   - center=True pads by N/2 on both sides by mirror reflection that does not
  *     repeat the edge sample; frame t then starts at padded index t*hop.
  *   - number of frames T = 1 + floor((L + 2*pad - N) / hop).
@@ -71,6 +72,8 @@
 /* windows */
 #define ORC_WIN_HANN 0
 #define ORC_WIN_RECT 1
+#define ORC_WIN_HAMMING 2
+#define ORC_WIN_BLACKMAN 3
 
 /* frequency axis of the STFT (Sec. II-B) */
 #define ORC_FREQ_DFT 0
@@ -105,17 +108,23 @@ long long orc_num_frames(long long L, long long N, long long hop, int center) {
   return 1 + (padded - N) / hop;
 }
 
-/* Window of length N (Sec. III-A, window paragraph). */
-int orc_window(int kind, long long N, double *w) {
-  if (N < 1 || !w) return ORC_EINVAL;
-  for (long long n = 0; n < N; ++n) {
-    if (kind == ORC_WIN_HANN)
-      w[n] = 0.5 - 0.5 * cos(2.0 * ORC_PI * (double)n / (double)N);
-    else if (kind == ORC_WIN_RECT)
-      w[n] = 1.0;
-    else
-      return ORC_EINVAL;
+/* Sample n of the length-N window (Sec. III-A, window paragraph: Hann, Hamming and Blackman are the
+ * types it names), in the periodic form that suits a DFT of the same length: the textbook cosine
+ * sums with 2 pi n / N (not N - 1) as their argument. */
+static int window_known(int kind) { return kind >= ORC_WIN_HANN && kind <= ORC_WIN_BLACKMAN; }
+static double window_at(int kind, long long n, long long N) {
+  const double a = 2.0 * ORC_PI * (double)n / (double)N;
+  switch (kind) {
+    case ORC_WIN_HANN: return 0.5 - 0.5 * cos(a);
+    case ORC_WIN_HAMMING: return 0.54 - 0.46 * cos(a);
+    case ORC_WIN_BLACKMAN: return 0.42 - 0.5 * cos(a) + 0.08 * cos(2.0 * a);
+    default: return 1.0;
   }
+}
+
+int orc_window(int kind, long long N, double *w) {
+  if (N < 1 || !w || !window_known(kind)) return ORC_EINVAL;
+  for (long long n = 0; n < N; ++n) w[n] = window_at(kind, n, N);
   return ORC_OK;
 }
 
@@ -382,7 +391,7 @@ long long orc_cqt_default_taps(int sr, double fmin, int bins_per_octave) {
 
 /* one tap of kernel k: window(N_k)[n] * exp(-2 pi i Q n / N_k) / sum(window) */
 static void cqt_tap(int window, double Q, long long Nk, double wsum, long long n, double *re, double *im) {
-  const double w = (window == ORC_WIN_HANN) ? 0.5 - 0.5 * cos(2.0 * ORC_PI * (double)n / (double)Nk) : 1.0;
+  const double w = window_at(window, n, Nk);
   const double ph = 2.0 * ORC_PI * Q * (double)n / (double)Nk;
   *re = w * cos(ph) / wsum;
   *im = -w * sin(ph) / wsum;
@@ -391,7 +400,7 @@ static void cqt_tap(int window, double Q, long long Nk, double wsum, long long n
 static double window_sum(int window, long long Nk) {
   double s = 0.0;
   for (long long n = 0; n < Nk; ++n)
-    s += (window == ORC_WIN_HANN) ? 0.5 - 0.5 * cos(2.0 * ORC_PI * (double)n / (double)Nk) : 1.0;
+    s += window_at(window, n, Nk);
   return s;
 }
 
@@ -401,7 +410,7 @@ static double window_sum(int window, long long Nk) {
 int orc_cqt_kernels(int sr, double fmin, int n_bins, int bins_per_octave, int window,
                     long long n_taps, double *kre, double *kim) {
   if (!kre || !kim || n_taps < 1) return ORC_EINVAL;
-  if (window != ORC_WIN_HANN && window != ORC_WIN_RECT) return ORC_EINVAL;
+  if (!window_known(window)) return ORC_EINVAL;
   long long *Nk = (long long *)malloc(sizeof(long long) * n_bins);
   if (!Nk) return ORC_ENOMEM;
   int rc = orc_cqt_lengths(sr, fmin, n_bins, bins_per_octave, Nk, NULL);
@@ -427,7 +436,7 @@ int orc_cqt_kernels(int sr, double fmin, int n_bins, int bins_per_octave, int wi
 int orc_cqt_complex(const float *x, long long B, long long L, int sr, int hop, double fmin, int n_bins,
                     int bins_per_octave, int window, int center, long long n_taps, double *re, double *im) {
   if (!x || !re || !im || B < 1 || hop < 1) return ORC_EINVAL;
-  if (window != ORC_WIN_HANN && window != ORC_WIN_RECT) return ORC_EINVAL;
+  if (!window_known(window)) return ORC_EINVAL;
   if (n_taps <= 0) n_taps = orc_cqt_default_taps(sr, fmin, bins_per_octave);
   if (n_taps < 2 || (n_taps & 1)) return ORC_EINVAL;
   const long long pad = center ? n_taps / 2 : 0;
@@ -571,7 +580,7 @@ long long orc_cqt2010_default_taps(int sr, double fmin, int n_bins, int bins_per
 int orc_cqt2010v2(const float *x, long long B, long long L, int sr, int hop, double fmin, int n_bins,
                   int bins_per_octave, int window, long long n_taps, int fir_taps, int fmt, double *out) {
   if (!x || !out || B < 1 || hop < 1 || fmt < 0 || fmt > 2 || n_bins < 1 || bins_per_octave < 1) return ORC_EINVAL;
-  if (window != ORC_WIN_HANN && window != ORC_WIN_RECT) return ORC_EINVAL;
+  if (!window_known(window)) return ORC_EINVAL;
   if (sr < 1 || fmin <= 0.0 || fir_taps < 3 || !(fir_taps & 1)) return ORC_EINVAL;
   const int b = bins_per_octave, n_oct = cqt2010_octaves(n_bins, b);
   if (n_oct > 30 || hop % (1 << (n_oct - 1)) != 0) return ORC_EINVAL; /* every octave needs an integer hop */

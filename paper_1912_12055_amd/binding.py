@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libnna.so")
 NNA_OK = 0
 NNA_ERR_INVALID_ARG, NNA_ERR_UNSUPPORTED, NNA_ERR_SHAPE, NNA_ERR_ALLOC, NNA_ERR_HIP = 1, 2, 3, 4, 5
 NNA_OUT_MAGNITUDE, NNA_OUT_POWER, NNA_OUT_LOG, NNA_OUT_COMPLEX, NNA_OUT_PHASE = 0, 1, 2, 3, 4
-NNA_WIN_HANN, NNA_WIN_RECT = 0, 1
+NNA_WIN_HANN, NNA_WIN_RECT, NNA_WIN_HAMMING, NNA_WIN_BLACKMAN = 0, 1, 2, 3
 NNA_MEL_SLANEY, NNA_MEL_HTK = 0, 1
 NNA_FREQ_LINEAR, NNA_FREQ_LOG = 1, 2
 NNA_PREC_F32, NNA_PREC_F16 = 0, 1

@@ -130,8 +130,13 @@ using nna::ST_RB;
 using nna::ST_ROWS;
 
 double window_value(int win, long long n, long long N) {
-  if (win == NNA_WIN_RECT) return 1.0;
-  return 0.5 - 0.5 * std::cos(2.0 * kPi * (double)n / (double)N);  // periodic Hann
+  const double a = 2.0 * kPi * (double)n / (double)N;  // periodic forms: the argument runs over n / N
+  switch (win) {
+    case NNA_WIN_RECT: return 1.0;
+    case NNA_WIN_HAMMING: return 0.54 - 0.46 * std::cos(a);
+    case NNA_WIN_BLACKMAN: return 0.42 - 0.5 * std::cos(a) + 0.08 * std::cos(2.0 * a);
+    default: return 0.5 - 0.5 * std::cos(a);  // Hann
+  }
 }
 
 // ---- device helpers -----------------------------------------------------------------
@@ -768,7 +773,7 @@ nna_status check_common(nna_plan** plan, int sr, int hop, int win, int center, i
   *plan = nullptr;
   if (sr < 1) return fail(NNA_ERR_INVALID_ARG, "sr must be >= 1");
   if (hop < 1) return fail(NNA_ERR_INVALID_ARG, "hop must be >= 1");
-  if (win != NNA_WIN_HANN && win != NNA_WIN_RECT) return fail(NNA_ERR_INVALID_ARG, "unknown window");
+  if (win < NNA_WIN_HANN || win > NNA_WIN_BLACKMAN) return fail(NNA_ERR_INVALID_ARG, "unknown window");
   if (center != 0 && center != 1) return fail(NNA_ERR_INVALID_ARG, "center must be 0 or 1");
   return check_device(device);
 }

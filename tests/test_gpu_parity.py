@@ -72,6 +72,8 @@ STFT_CASES = [
     ("n_fft = 4096, hop 512 (8 shifts)", 2, 40000, 4096, 512, 0, True, 0),
     ("32 hop-shifts", 2, 20000, 1024, 32, 0, True, 0),
     ("log output", 2, 9000, 256, 64, 0, True, 2),
+    ("Hamming window", 2, 9000, 256, 64, 2, True, 0),
+    ("Blackman window, power", 3, 12000, 512, 128, 3, True, 1),
 ]
 
 
@@ -308,6 +310,8 @@ CQT_CASES = [
     ("rect window, no centring", 2, 7000, 8000, 128, 500.0, 6, 3, 128, 1, False, 0),
     ("short waveforms, many per tile", 40, 1100, 8000, 128, 220.0, 24, 12, 1024, 0, True, 0),
     ("36 bins per octave", 2, 30000, 22050, 256, 110.0, 100, 36, 0, 0, True, 0),
+    ("Hamming-windowed kernels", 2, 6000, 8000, 128, 220.0, 24, 12, 1024, 2, True, 0),
+    ("Blackman-windowed kernels", 2, 6000, 8000, 128, 220.0, 24, 12, 1024, 3, True, 0),
 ]
 
 

@@ -94,6 +94,7 @@ def test_out_shape_rejects_short_signals():
 
 
 @pytest.mark.parametrize("n_fft,hop,win", [(2048, 512, nb.NNA_WIN_HANN), (256, 64, nb.NNA_WIN_HANN),
+                                           (256, 64, nb.NNA_WIN_HAMMING), (512, 128, nb.NNA_WIN_BLACKMAN),
                                             (96, 25, nb.NNA_WIN_HANN), (200, 50, nb.NNA_WIN_RECT),
                                             (130, 130, nb.NNA_WIN_HANN)])
 def test_stft_bank_is_windowed_dft_kernels(n_fft, hop, win):

@@ -200,3 +200,24 @@ def test_complex_result_carries_the_tone_phase():
         re, im = oracle.stft_complex(x, n_fft=N, hop=N, center=False)
         z = re[0, k0, 0] + 1j * im[0, k0, 0]
         assert abs(z - A / 2 * (N / 2) * np.exp(1j * phi)) < 1e-5 * N
+
+
+def test_hamming_and_blackman_windows_are_the_periodic_textbook_forms():
+    # against SciPy's generator of DFT-even ("periodic") windows, and two closed forms
+    import scipy.signal
+    for N in (8, 64, 2048):
+        np.testing.assert_allclose(oracle.window(oracle.WIN_HAMMING, N), scipy.signal.get_window("hamming", N, fftbins=True), atol=1e-14)
+        np.testing.assert_allclose(oracle.window(oracle.WIN_BLACKMAN, N), scipy.signal.get_window("blackman", N, fftbins=True), atol=1e-14)
+        np.testing.assert_allclose(oracle.window(oracle.WIN_HANN, N), scipy.signal.get_window("hann", N, fftbins=True), atol=1e-14)
+    assert abs(oracle.window(oracle.WIN_HAMMING, 64)[0] - 0.08) < 1e-15
+    assert abs(oracle.window(oracle.WIN_BLACKMAN, 64).sum() - 0.42 * 64) < 1e-12  # the cosines sum to zero over a period
+
+
+@pytest.mark.parametrize("win,coef", [(oracle.WIN_HAMMING, 0.54), (oracle.WIN_BLACKMAN, 0.42)])
+def test_tone_peak_under_hamming_and_blackman(win, coef):
+    # a tone on bin k0 reads A sum(w) / 2 = A coef N / 2 (these windows' spectra vanish 2 k0 bins away too)
+    N, k0, A = 256, 31, 0.9
+    x = signals.tone(N, N, k0, amp=A, phase=0.3)  # sr = N: frequency k0 is bin k0
+    out = oracle.stft(x, n_fft=N, hop=N, window=win, center=False)[0, :, 0]
+    assert int(np.argmax(out)) == k0
+    assert abs(out[k0] - A * coef * N / 2) < 1e-5 * N
