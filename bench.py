@@ -263,7 +263,33 @@ def main() -> int:
             "mfma_frac": round(alg / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
             "mfma_peak_tflops": PEAK_FP32_MFMA_TFLOPS,
         }
-        del gmel, ws_bw
+        del gmel, ws_bw, p_trm
+        # backward pass of the constant-Q layer with trainable time-domain kernels: the forward contraction
+        # again, the bank gradient and the waveform gradient, 4 sum(N_k) flop per frame each
+        p_trc = nb.nna_plan_trainable(nb.nna_plan_cqt(sr=sr, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24,
+                                                      n_taps=65536, device=0))
+        gcq = torch.ones((B, 168, T), dtype=torch.float32, device=dev)
+        ws_bw = torch.empty(nb.nna_cqt_backward_workspace(p_trc, B, L), dtype=torch.uint8, device=dev)
+        for _ in range(max(1, args.warmup)):
+            nb.nna_cqt_backward(p_trc, x5, gcq, workspace=ws_bw)
+        ev = []
+        for _ in range(args.steps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            nb.nna_cqt_backward(p_trc, x5, gcq, workspace=ws_bw)
+            b.record()
+            ev.append((a, b))
+        torch.cuda.synchronize()
+        ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+        alg = 3 * p_trc.info()["algorithmic_flops_per_frame"] * B * T
+        extras["cqt_backward"] = {
+            "ms": round(ms, 4),
+            "gsamples_per_s": round(B * L / ms / 1e6, 4),
+            "algorithmic_tflops": round(alg / ms / 1e9, 3),
+            "mfma_frac": round(alg / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+            "mfma_peak_tflops": PEAK_FP32_MFMA_TFLOPS,
+        }
+        del gcq, ws_bw, p_trc
 
     cpu = None
     if not args.no_cpu_baseline:

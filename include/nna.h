@@ -296,6 +296,27 @@ nna_status nna_stft_backward(const nna_plan* plan, const float* x_dev, long long
                              size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Trainable constant-Q kernels (Sec. IV-C; the `trainable` argument of the paper's CQT layers, Sec.
+ * III-C): nna_plan_trainable also accepts plans from nna_plan_cqt.  The bank's logical layout is
+ * W[2 n_bins, n_taps], float32 row-major on the device: row 2k = real part, row 2k+1 = imaginary part of
+ * the kernel eq. (CQT) multiplies the signal with, w_k[n] exp(-2 pi i Q n / N_k) / sum(w_k) (row 2k+1
+ * starts out as the negative sine).  The parameters are the taps inside each kernel's support [s_k, s_k + N_k); the zeros
+ * that centre the kernel among n_taps are structure, not parameters (the kernel that multiplies only
+ * stored taps depends on it): they read as zero, writes to them are ignored, their gradient is zero.
+ *   nna_plan_get_bank / nna_plan_set_bank   as above, with w_dev[2 n_bins, n_taps].
+ *   nna_cqt_backward   given gout_dev[B, n_bins, T] ([B, 2 n_bins, T] for NNA_OUT_COMPLEX) = dLoss/d(output
+ *                      of nna_cqt for x_dev), writes gw_dev[2 n_bins, n_taps] and/or gx_dev[B, L] with
+ *                      the definitions given for nna_stft_backward (phase: d atan2(Im, Re) =
+ *                      (Re dIm - Im dRe)/P; complex: G = gout).  workspace_dev: 256-byte aligned,
+ *                      nna_cqt_backward_workspace bytes (G: 128-row-padded bank rows x padded frames x 4).
+ *                      Outputs are overwritten; atomics and errors as in nna_stft_backward.
+ */
+nna_status nna_cqt_backward_workspace(const nna_plan* plan, long long B, long long L, size_t* bytes);
+nna_status nna_cqt_backward(const nna_plan* plan, const float* x_dev, long long B, long long L,
+                            const float* gout_dev, float* gw_dev, float* gx_dev, void* workspace_dev,
+                            size_t workspace_bytes, void* hip_stream);
+
+/*
  * Trainable Mel layer (Sec. IV-C; the trainable_mel / trainable_STFT arguments of the paper's
  * MelSpectrogram layer, Sec. III-B): both stages of a plan from nna_plan_mel as parameters.
  * nna_plan_trainable also accepts Mel plans; nna_plan_get_bank / nna_plan_set_bank then address the

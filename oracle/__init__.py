@@ -547,3 +547,31 @@ def mel_bank_backward(x, W, Wmel, gout, hop=512, center=True, power=2.0):
     gP = np.einsum("mk,bmt->bkt", Wmel, gout)
     gW, gx = stft_bank_backward(x, W, gP, hop=hop, center=center, fmt=fmt)
     return gWmel, gW, gx
+
+
+def cqt_bank(sr=22050, fmin=32.70, n_bins=84, bins_per_octave=12, window=WIN_HANN, n_taps=0):
+    """The constant-Q kernels of Sec. III-C ("CQT with time domain kernels") as the weight of a
+    convolution layer (Sec. IV-C): W[2 n_bins, n_taps], row 2k / 2k+1 = real / imaginary part of the
+    kernel w_k[n] exp(-2 pi i Q n / N_k) / sum(w_k) that eq. (CQT) multiplies the signal with, so that
+    ``stft_bank(x, W)`` is eq. (CQT) for every frame; and the support mask
+    [2 n_bins, n_taps] (True on taps s_k .. s_k + N_k - 1 of bin k's rows: the window's extent,
+    whether or not the window value there is zero)."""
+    kre, kim = cqt_kernels(sr, fmin, n_bins, bins_per_octave, window, n_taps)
+    taps = kre.shape[1]
+    Nk, _ = cqt_lengths(sr, fmin, n_bins, bins_per_octave)
+    W = np.empty((2 * n_bins, taps), dtype=np.float64)
+    W[0::2] = kre
+    W[1::2] = kim
+    mask = np.zeros(W.shape, dtype=bool)
+    for k in range(n_bins):
+        s = (taps - int(Nk[k])) // 2
+        mask[2 * k:2 * k + 2, s:s + int(Nk[k])] = True
+    return W, mask
+
+
+def cqt_bank_backward(x, W, mask, gout, hop=512, center=True, fmt=MAGNITUDE):
+    """Gradients through the constant-Q layer with kernel bank W (``stft_bank`` with W from
+    ``cqt_bank``): the chain rule of ``stft_bank_backward``; the taps outside ``mask`` are the zeros
+    that centre each kernel, not parameters, so their gradient is dropped.  (gW, gx)."""
+    gW, gx = stft_bank_backward(x, W, gout, hop=hop, center=center, fmt=fmt)
+    return np.where(mask, gW, 0.0), gx

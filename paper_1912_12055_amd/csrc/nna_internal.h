@@ -147,6 +147,11 @@ struct CqtParams {
   int lds_rows;            // rows per LDS buffer
   int tile_frames;         // frames per tile (<= CQ_FRAMES)
   long long n_ft;
+  // backward pass (gbuf != NULL): the epilogue writes G = dLoss/dC instead of the spectrogram
+  const float* gout;       // upstream gradient [B][out rows][T]
+  long long gout_wave_stride;
+  float* gbuf;             // G in blocks of 32 frames, [frames / 32][rows_pad][32]
+  int rows_pad;
 };
 
 // ---- backward pass of the STFT layer (trainable kernel banks) --------------------------------
@@ -168,6 +173,26 @@ struct BwParams {
   float* gx;             // [B][L], zeroed; overlapping frames and mirrored samples are added atomically
   int n_split;           // bank gradient: workgroups that share one output tile (split contraction)
   long long chunks_per_split;
+  // Banks whose rows are zero outside a tap range (constant-Q kernels, rows ordered longest first);
+  // all NULL / 0 for a dense bank.
+  const int2* tiles;     // bank gradient: the (row tile, tap tile) pairs that hold taps; NULL: every pair
+  int n_tiles;
+  const int* row_lo;     // bank gradient: row r is a parameter on taps [row_lo[r], row_hi[r]) only
+  const int* row_hi;
+  int nt_lo, nt_cnt;     // waveform gradient: only tap tiles nt_lo .. nt_lo + nt_cnt - 1 hold taps (0: all)
+  const int* nt_chunks;  // waveform gradient: contraction chunks (rows / BW_KC) tap tile nt needs; NULL: all
+};
+
+// constant-Q bank of a trainable plan: the caller's [rows][K] tensor <-> streaming order / row-major copy
+struct CqtBankParams {
+  float* bank;           // streaming order, n_bank floats
+  const int* map;        // per float of `bank`: index into the caller's tensor, or -1 (structural zero)
+  long long n_bank;
+  float* wrm;            // row-major [rows_pad][kp], zero outside each row's support
+  const int* row_lo;     // [rows]
+  const int* row_hi;
+  float* logical;        // caller's tensor [rows][K]
+  int rows, K, kp;
 };
 
 // logical <-> streaming order of an STFT bank on the device
@@ -205,6 +230,8 @@ hipError_t launch_bank_to_logical(const BankPermuteParams& p, hipStream_t stream
 hipError_t launch_bw_bank(const BwParams& p, hipStream_t stream);      // gw += G x frames
 hipError_t launch_bw_wave(const BwParams& p, hipStream_t stream);      // gx += transposed convolution
 hipError_t launch_cqt(const CqtParams& p, hipStream_t stream);
+hipError_t launch_cqt_bank_from_logical(const CqtBankParams& p, hipStream_t stream);  // bank and wrm <- logical
+hipError_t launch_cqt_bank_to_logical(const CqtBankParams& p, hipStream_t stream);    // logical <- wrm
 hipError_t launch_stft16(const Stft16Params& p, hipStream_t stream);
 hipError_t kernels_init();  // per-process function attributes
 

@@ -402,6 +402,9 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
 constexpr int CQ_RPP = 256 / (CQ_KC / 4);            // LDS rows written per loader pass (64)
 constexpr int CQ_NPASS = CQ_LDS_ROWS_MAX / CQ_RPP;  // 512 / 64 = 8
 
+// GRAD: instead of the spectrogram the kernel writes G = dLoss/dC, the derivative of the output format
+// applied to the upstream gradient, in the blocked layout the backward contractions read.
+template <bool GRAD>
 __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
   extern __shared__ __attribute__((aligned(16))) float dyn_lds[];
   // dynamic LDS: this item's chunk table (read every chunk; kept out of the vector-memory path so
@@ -610,7 +613,7 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
 #pragma unroll
   for (int i = 0; i < CQ_PREFETCH; ++i) wait_vm<0>(bq[i]);
 
-  if (P.raw) {
+  if (!GRAD && P.raw) {
     // real-valued bank (a decimating FIR filter written as P.raw shifted copies): register i of
     // lane (q, n) in row block rb is output sample P.raw t + 16 rb + 4 q + i of the frame's waveform
 #pragma unroll
@@ -636,6 +639,48 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
     return;
   }
   const int f = P.fmt;
+  if constexpr (GRAD) {
+    // lane (q, n), registers 0..3 of row block rb: (Re, Im) of bins 8 rb + 2 q and + 1, frame n of the
+    // wave's frame block fb.  G[frame / 32][row][frame % 32], row = 2 bin (Re), 2 bin + 1 (Im).
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb) {
+      if (!valid[fb]) continue;
+      const long long fr = f0 + wave * 64 + fb * 16 + n;
+      const long long b = fr / g.T;
+      const float* __restrict__ gp = P.gout + b * P.gout_wave_stride + (fr - b * g.T);
+      float* __restrict__ Gp = P.gbuf + (fr >> 5) * ((long long)P.rows_pad * 32) + (fr & 31);
+#pragma unroll
+      for (int r = 0; r < CQ_ITEM_RB; ++r) {
+        if (r >= n_rb) continue;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int bin = (item.rb_first + r) * (CQ_ROWS / 2) + 2 * q + u;
+          if (bin >= P.n_bins) continue;
+          const float re = acc[r][fb][2 * u], im = acc[r][fb][2 * u + 1];
+          const float pw = re * re + im * im;
+          float gr, gi;
+          if (f == NNA_OUT_COMPLEX) {
+            gr = gp[(2LL * bin) * g.T];
+            gi = gp[(2LL * bin + 1) * g.T];
+          } else if (f == NNA_OUT_PHASE) {  // d atan2(Im, Re) = (Re dIm - Im dRe) / P
+            const float s = pw > 0.f ? gp[(long long)bin * g.T] / pw : 0.f;
+            gr = -s * im;
+            gi = s * re;
+          } else {
+            const float go = gp[(long long)bin * g.T];
+            const float s = f == NNA_OUT_MAGNITUDE ? grad_scale<NNA_OUT_MAGNITUDE>(go, pw)
+                            : f == NNA_OUT_POWER   ? grad_scale<NNA_OUT_POWER>(go, pw)
+                                                   : grad_scale<NNA_OUT_LOG>(go, pw);
+            gr = s * re;
+            gi = s * im;
+          }
+          Gp[(2LL * bin) * 32] = gr;
+          Gp[(2LL * bin + 1) * 32] = gi;
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int r = 0; r < CQ_ITEM_RB; ++r) {
     if (r >= n_rb) continue;
@@ -681,7 +726,10 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
 static constexpr size_t CQ_DYN_LDS_MAX = 160 * 1024;
 
 hipError_t kernels_init() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(cqt_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(cqt_kernel<false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)CQ_DYN_LDS_MAX);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(cqt_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize,
                              (int)CQ_DYN_LDS_MAX);
 }
 
@@ -715,7 +763,12 @@ hipError_t launch_cqt(const CqtParams& p, hipStream_t stream) {
   if (p.lds_rows > CQ_LDS_ROWS_MAX) return hipErrorInvalidValue;
   const size_t lds = (size_t)p.n_chunks * sizeof(CqtChunk) + 2ull * p.lds_rows * CQ_PITCH * sizeof(float);
   if (lds > CQ_DYN_LDS_MAX) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(cqt_kernel, dim3((unsigned)blocks), dim3(256), lds, stream, p);
+  if (p.gbuf) {
+    if (!p.gout || p.raw || p.rows_pad < 2 * p.n_bins) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(cqt_kernel<true>, dim3((unsigned)blocks), dim3(256), lds, stream, p);
+  } else {
+    hipLaunchKernelGGL(cqt_kernel<false>, dim3((unsigned)blocks), dim3(256), lds, stream, p);
+  }
   return hipGetLastError();
 }
 

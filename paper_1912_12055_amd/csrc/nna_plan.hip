@@ -110,6 +110,16 @@ struct nna_plan {
   int* d_mel_pass_rt = nullptr;
   nna::CqtItem* d_items = nullptr;
   nna::CqtChunk* d_chunks = nullptr;
+  // trainable CQT plans: index map caller's tensor -> streaming order, each row's tap support, and the
+  // tables that let the backward contractions skip what lies outside every support
+  int* d_cq_map = nullptr;
+  int* d_row_lo = nullptr;
+  int* d_row_hi = nullptr;
+  int2* d_bw_tiles = nullptr;
+  int n_bw_tiles = 0;
+  int* d_nt_chunks = nullptr;
+  int nt_lo = 0, nt_cnt = 0;
+  double bw_bank_flops = 0, bw_wave_flops = 0;  // per frame, as executed by the two backward contractions
 };
 
 namespace {
@@ -1586,8 +1596,8 @@ nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long l
 // ---- trainable Fourier kernels (Sec. IV-C) ----------------------------------------------------
 static nna_status check_trainable_kind(const nna_plan* plan) {
   if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
-  if (plan->kind != NNA_KIND_STFT && plan->kind != NNA_KIND_MEL)
-    return fail(NNA_ERR_INVALID_ARG, "only STFT and Mel plans have trainable kernels");
+  if (plan->kind != NNA_KIND_STFT && plan->kind != NNA_KIND_MEL && plan->kind != NNA_KIND_CQT)
+    return fail(NNA_ERR_INVALID_ARG, "only plans from nna_plan_stft, nna_plan_stft_scaled, nna_plan_mel and nna_plan_cqt have trainable kernels");
   if (plan->precision != NNA_PREC_F32) return fail(NNA_ERR_UNSUPPORTED, "trainable kernels need a float32 plan");
   if (plan->device < 0) return fail(NNA_ERR_UNSUPPORTED, "host-only plan (device = -1)");
   return NNA_OK;
@@ -1609,6 +1619,121 @@ static nna::BankPermuteParams permute_params(const nna_plan* plan, float* logica
   return q;
 }
 
+static nna::CqtBankParams cqt_bank_params(const nna_plan* plan, float* logical) {
+  nna::CqtBankParams q;
+  q.bank = plan->d_bank;
+  q.map = plan->d_cq_map;
+  q.n_bank = (long long)plan->bank_floats;
+  q.wrm = plan->d_wrm;
+  q.row_lo = plan->d_row_lo;
+  q.row_hi = plan->d_row_hi;
+  q.logical = logical;
+  q.rows = plan->conv_rows;
+  q.K = plan->K;
+  q.kp = plan->kp;
+  return q;
+}
+
+// A constant-Q plan becomes trainable (device current): the parameters are the taps inside each kernel's
+// support [s_k, s_k + N_k); the zeros that centre a kernel among n_taps stay zeros.
+static nna_status make_cqt_trainable(nna_plan* plan) {
+  const int rows = plan->conv_rows;
+  const long long K = plan->K;
+  if ((long long)rows * K > 0x7fffffffLL) return fail(NNA_ERR_UNSUPPORTED, "bank of more than 2^31 - 1 entries");
+  const int rows_pad = (rows + nna::BW_MT - 1) / nna::BW_MT * nna::BW_MT;
+  const int kp = (int)((K + nna::BW_NT - 1) / nna::BW_NT * nna::BW_NT);
+  const int n_nt = kp / nna::BW_NT;
+  std::vector<int> map, lo(rows_pad, 0), hi(rows_pad, 0), nt_chunks(n_nt, 0);
+  std::vector<int2> tiles;
+  std::vector<float> logical;
+  try {
+    // streaming order <- [row][tap]: the inverse of the layout build_conv_bank writes
+    map.assign(plan->bank_floats, -1);
+    for_each_cqt_fragment(plan, [&](long long f, int rb, int j, int c0, bool real) {
+      if (!real) return;
+      for (int lane = 0; lane < 64; ++lane) {
+        const int q = lane >> 4, row = rb * CQ_ROWS + (lane & 15);
+        const long long tap0 = (long long)j * (plan->sliding ? plan->hop : 0) + c0 + 4 * q;
+        for (int e = 0; e < 4; ++e)
+          if (row < rows && tap0 + e >= plan->row_s[row] && tap0 + e < plan->row_e[row])
+            map[((size_t)f * 64 + lane) * 4 + e] = (int)(row * K + tap0 + e);
+      }
+    });
+    for (int r = 0; r < rows; ++r) {
+      lo[r] = (int)plan->row_s[r];
+      hi[r] = (int)plan->row_e[r];
+    }
+    // bank gradient: output tiles (128 rows x 128 taps) that hold a parameter
+    double bank_tiles = 0;
+    for (int mt = 0; mt < rows_pad / nna::BW_MT; ++mt) {
+      long long s = K, e = 0;
+      for (int r = mt * nna::BW_MT; r < std::min(rows, (mt + 1) * nna::BW_MT); ++r) {
+        s = std::min(s, plan->row_s[r]);
+        e = std::max(e, plan->row_e[r]);
+      }
+      for (long long nt = s / nna::BW_NT; nt * nna::BW_NT < e; ++nt) tiles.push_back(make_int2(mt, (int)nt));
+    }
+    bank_tiles = (double)tiles.size();
+    // waveform gradient: tap tiles that hold a parameter, and how many rows (in chunks of 32) each needs
+    int nt_first = n_nt, nt_last = -1;
+    double wave_chunks = 0;
+    for (int nt = 0; nt < n_nt; ++nt) {
+      int r_max = 0;
+      for (int r = 0; r < rows; ++r)
+        if (plan->row_s[r] < (long long)(nt + 1) * nna::BW_NT && plan->row_e[r] > (long long)nt * nna::BW_NT) r_max = r + 1;
+      nt_chunks[nt] = (r_max + nna::BW_KC - 1) / nna::BW_KC;
+      if (r_max > 0) {
+        nt_first = std::min(nt_first, nt);
+        nt_last = nt;
+        wave_chunks += nt_chunks[nt];
+      }
+    }
+    if (nt_last < 0 || tiles.empty()) return fail(NNA_ERR_UNSUPPORTED, "the bank has no taps");
+    plan->nt_lo = nt_first;
+    plan->nt_cnt = nt_last - nt_first + 1;
+    plan->n_bw_tiles = (int)tiles.size();
+    plan->bw_bank_flops = 2.0 * bank_tiles * nna::BW_MT * nna::BW_NT;
+    plan->bw_wave_flops = 2.0 * wave_chunks * nna::BW_KC * nna::BW_NT;
+    // the bank as the caller's tensor: the values the plan was built with
+    logical.assign((size_t)rows * K, 0.0f);
+    CqtKernelGen gen(plan);
+    for (int r = 0; r < rows; ++r)
+      for (long long n = plan->row_s[r]; n < plan->row_e[r]; ++n) logical[(size_t)r * K + n] = (float)gen.value(r, n);
+  } catch (const std::bad_alloc&) {
+    return fail(NNA_ERR_ALLOC, "out of host memory");
+  }
+  plan->rows_pad = rows_pad;
+  plan->kp = kp;
+  float* d_logical = nullptr;
+  const size_t wrm_bytes = (size_t)rows_pad * kp * sizeof(float);
+  nna_status s = upload(&plan->d_wrm, nullptr, wrm_bytes, "row-major kernel bank");
+  if (s == NNA_OK) s = upload(&plan->d_cq_map, map.data(), map.size() * sizeof(int), "bank index map");
+  if (s == NNA_OK) s = upload(&plan->d_row_lo, lo.data(), lo.size() * sizeof(int), "row supports");
+  if (s == NNA_OK) s = upload(&plan->d_row_hi, hi.data(), hi.size() * sizeof(int), "row supports");
+  if (s == NNA_OK) s = upload(&plan->d_bw_tiles, tiles.data(), tiles.size() * sizeof(int2), "gradient tile list");
+  if (s == NNA_OK) s = upload(&plan->d_nt_chunks, nt_chunks.data(), nt_chunks.size() * sizeof(int), "tap tile table");
+  if (s == NNA_OK) s = upload(&d_logical, logical.data(), logical.size() * sizeof(float), "kernel bank");
+  if (s == NNA_OK) {
+    hipError_t e = hipMemset(plan->d_wrm, 0, wrm_bytes);
+    if (e == hipSuccess) e = nna::launch_cqt_bank_from_logical(cqt_bank_params(plan, d_logical), nullptr);
+    if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+    if (e != hipSuccess) s = fail_hip(e, "row-major kernel bank");
+  }
+  (void)hipFree(d_logical);
+  if (s != NNA_OK) {
+    (void)hipFree(plan->d_wrm);
+    (void)hipFree(plan->d_cq_map);
+    (void)hipFree(plan->d_row_lo);
+    (void)hipFree(plan->d_row_hi);
+    (void)hipFree(plan->d_bw_tiles);
+    (void)hipFree(plan->d_nt_chunks);
+    plan->d_wrm = nullptr;
+    plan->d_cq_map = plan->d_row_lo = plan->d_row_hi = plan->d_nt_chunks = nullptr;
+    plan->d_bw_tiles = nullptr;
+  }
+  return s;
+}
+
 nna_status nna_plan_trainable(nna_plan* plan) {
   nna_status s = check_trainable_kind(plan);
   if (s != NNA_OK) return s;
@@ -1616,6 +1741,7 @@ nna_status nna_plan_trainable(nna_plan* plan) {
   DeviceGuard guard;
   hipError_t e = guard.enter(plan->device);
   if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+  if (plan->kind == NNA_KIND_CQT) return make_cqt_trainable(plan);
   plan->rows_pad = plan->n_rt * ST_ROWS;
   plan->kp = (plan->K + nna::BW_NT - 1) / nna::BW_NT * nna::BW_NT;
   const size_t bytes = (size_t)plan->rows_pad * plan->kp * sizeof(float);
@@ -1677,7 +1803,10 @@ nna_status nna_plan_get_bank(const nna_plan* plan, float* w_dev, void* hip_strea
   DeviceGuard guard;
   hipError_t e = guard.enter(plan->device);
   if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
-  e = nna::launch_bank_to_logical(permute_params(plan, w_dev), reinterpret_cast<hipStream_t>(hip_stream));
+  if (plan->kind == NNA_KIND_CQT)
+    e = nna::launch_cqt_bank_to_logical(cqt_bank_params(plan, w_dev), reinterpret_cast<hipStream_t>(hip_stream));
+  else
+    e = nna::launch_bank_to_logical(permute_params(plan, w_dev), reinterpret_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail_hip(e, "kernel launch");
   return NNA_OK;
 }
@@ -1689,7 +1818,10 @@ nna_status nna_plan_set_bank(nna_plan* plan, const float* w_dev, void* hip_strea
   DeviceGuard guard;
   hipError_t e = guard.enter(plan->device);
   if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
-  e = nna::launch_bank_from_logical(permute_params(plan, const_cast<float*>(w_dev)), reinterpret_cast<hipStream_t>(hip_stream));
+  if (plan->kind == NNA_KIND_CQT)
+    e = nna::launch_cqt_bank_from_logical(cqt_bank_params(plan, const_cast<float*>(w_dev)), reinterpret_cast<hipStream_t>(hip_stream));
+  else
+    e = nna::launch_bank_from_logical(permute_params(plan, const_cast<float*>(w_dev)), reinterpret_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail_hip(e, "kernel launch");
   return NNA_OK;
 }
@@ -1797,6 +1929,108 @@ nna_status nna_stft_backward(const nna_plan* plan, const float* x_dev, long long
     return fail(NNA_ERR_INVALID_ARG, "workspace_dev is NULL, not 256-byte aligned or smaller than nna_stft_backward_workspace asks for");
   return stft_backward_core(plan, x_dev, B, L, T, gout_dev, plan->fmt, plan->out_rows(), gw_dev, gx_dev,
                             static_cast<float*>(workspace_dev), hip_stream);
+}
+
+// ---- trainable constant-Q kernels (time-domain kernels at one rate) ------------------------------
+nna_status nna_cqt_backward_workspace(const nna_plan* plan, long long B, long long L, size_t* bytes) {
+  nna_status s = check_trainable(plan);
+  if (s != NNA_OK) return s;
+  if (plan->kind != NNA_KIND_CQT) return fail(NNA_ERR_INVALID_ARG, "plan was built for a different transform");
+  if (!bytes) return fail(NNA_ERR_INVALID_ARG, "bytes is NULL");
+  if (B < 1) return fail(NNA_ERR_SHAPE, "B must be >= 1");
+  const long long T = frames_of(plan, L);
+  if (T < 1) return fail(NNA_ERR_SHAPE, plan->center ? "L must exceed the reflection padding (K/2)" : "L is shorter than one window");
+  *bytes = (size_t)plan->rows_pad * (size_t)bw_gpitch(B * T) * sizeof(float);
+  return NNA_OK;
+}
+
+nna_status nna_cqt_backward(const nna_plan* plan, const float* x_dev, long long B, long long L, const float* gout_dev,
+                            float* gw_dev, float* gx_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+  nna_status s = check_trainable(plan);
+  if (s != NNA_OK) return s;
+  if (plan->kind != NNA_KIND_CQT) return fail(NNA_ERR_INVALID_ARG, "plan was built for a different transform");
+  if (!gout_dev) return fail(NNA_ERR_INVALID_ARG, "gout_dev is NULL");
+  if (!gw_dev && !gx_dev) return fail(NNA_ERR_INVALID_ARG, "gw_dev and gx_dev are both NULL: nothing to compute");
+  long long T = 0;
+  if ((s = check_call(plan, NNA_KIND_CQT, x_dev, B, L, gw_dev ? gw_dev : gx_dev, &T)) != NNA_OK) return s;
+  size_t need = 0;
+  if ((s = nna_cqt_backward_workspace(plan, B, L, &need)) != NNA_OK) return s;
+  if (!workspace_dev || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace_dev) & 255))
+    return fail(NNA_ERR_INVALID_ARG, "workspace_dev is NULL, not 256-byte aligned or smaller than nna_cqt_backward_workspace asks for");
+  const int extra = plan->max_jspan - 1;
+  const int M = pick_tile_frames(CQ_FRAMES, T, extra, CQ_LDS_ROWS_MAX);
+  if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  DeviceGuard guard;
+  hipError_t e = guard.enter(plan->device);
+  if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+
+  float* gbuf = static_cast<float*>(workspace_dev);
+  const long long n_frames = B * T, gpitch = bw_gpitch(n_frames);
+  // 1. G = dLoss/dC: the forward contraction again with the derivative of the output format as its
+  //    epilogue.  The kernel writes the rows of existing bins and frames; the padding stays zero.
+  e = nna::launch_fill_zero(gbuf, (long long)plan->rows_pad * gpitch, stream);
+  if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  nna::CqtParams P;
+  std::memset(&P, 0, sizeof(P));
+  P.g = make_geom(plan, x_dev, B, L, T);
+  P.bank = reinterpret_cast<const float4*>(plan->d_bank);
+  P.items = plan->d_items;
+  P.chunks = plan->d_chunks;
+  P.n_items = (int)plan->h_items.size();
+  P.n_chunks = plan->n_chunks;
+  P.n_bins = plan->n_bins;
+  P.fmt = plan->fmt;
+  P.tile_frames = M;
+  const long long nseg = 1 + (M - 1 + T - 1) / T;
+  P.lds_rows = (int)((M + nseg * extra + 63) / 64 * 64);
+  P.n_ft = (n_frames + M - 1) / M;
+  P.gout = gout_dev;
+  P.gout_wave_stride = (long long)plan->out_rows() * T;
+  P.gbuf = gbuf;
+  P.rows_pad = plan->rows_pad;
+  e = nna::launch_cqt(P, stream);
+  if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  // 2. the two contractions with G, restricted to the tiles that hold taps
+  nna::BwParams Q;
+  std::memset(&Q, 0, sizeof(Q));
+  Q.g = P.g;
+  Q.gbuf = gbuf;
+  Q.gpitch = gpitch;
+  Q.wrm = plan->d_wrm;
+  Q.kp = plan->kp;
+  Q.rows_pad = plan->rows_pad;
+  Q.n_half = plan->n_bins;
+  Q.packed = 0;
+  Q.K = plan->K;
+  Q.gw = gw_dev;
+  Q.gx = gx_dev;
+  Q.tiles = plan->d_bw_tiles;
+  Q.n_tiles = plan->n_bw_tiles;
+  Q.row_lo = plan->d_row_lo;
+  Q.row_hi = plan->d_row_hi;
+  Q.nt_lo = plan->nt_lo;
+  Q.nt_cnt = plan->nt_cnt;
+  Q.nt_chunks = plan->d_nt_chunks;
+  if (gw_dev) {
+    e = nna::launch_fill_zero(gw_dev, (long long)plan->conv_rows * plan->K, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    const long long chunks = gpitch / nna::BW_KC;
+    // the tile count is whatever the supports give: aim at eight rounds of the 512 resident workgroups, so
+    // that a partly filled last round costs little
+    long long split = std::max(1LL, std::min((4096 + (long long)Q.n_tiles - 1) / Q.n_tiles, chunks / 64));
+    Q.chunks_per_split = (chunks + split - 1) / split;
+    Q.n_split = (int)((chunks + Q.chunks_per_split - 1) / Q.chunks_per_split);
+    e = nna::launch_bw_bank(Q, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  }
+  if (gx_dev) {
+    e = nna::launch_fill_zero(gx_dev, B * L, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    e = nna::launch_bw_wave(Q, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  }
+  return NNA_OK;
 }
 
 // ---- trainable Mel layer -----------------------------------------------------------------------
@@ -2094,6 +2328,11 @@ void nna_plan_destroy(nna_plan* plan) {
       (void)hipFree(plan->d_mel_pass_rt);
       (void)hipFree(plan->d_items);
       (void)hipFree(plan->d_chunks);
+      (void)hipFree(plan->d_cq_map);
+      (void)hipFree(plan->d_row_lo);
+      (void)hipFree(plan->d_row_hi);
+      (void)hipFree(plan->d_bw_tiles);
+      (void)hipFree(plan->d_nt_chunks);
     }
   }
   delete plan;

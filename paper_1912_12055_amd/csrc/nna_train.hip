@@ -133,24 +133,32 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
   int n0;
   if constexpr (MODE == BW_MODE_BANK) {
     const int n_mt = P.rows_pad / BW_MT;
-    const long long tiles = (long long)n_mt * n_nt;
+    const long long tiles = P.tiles ? P.n_tiles : (long long)n_mt * n_nt;
     const long long split = blockIdx.x / tiles;
     int tile = (int)(blockIdx.x - split * tiles);
     // Workgroup ids are dealt round-robin to the 8 XCDs, each with an L2 of its own.  Give every XCD a
     // contiguous run of tiles in row-major order: it then reads only its own rows of G (the large
     // operand) instead of all of them.
     if (tiles % 8 == 0) tile = (tile & 7) * (int)(tiles / 8) + (tile >> 3);
-    m0 = (long long)(tile / n_nt) * BW_MT;
-    n0 = (tile % n_nt) * BW_NT;
+    if (P.tiles) {
+      const int2 t = P.tiles[tile];
+      m0 = (long long)t.x * BW_MT;
+      n0 = t.y * BW_NT;
+    } else {
+      m0 = (long long)(tile / n_nt) * BW_MT;
+      n0 = (tile % n_nt) * BW_NT;
+    }
     const long long n_chunks = P.gpitch / BW_KC;
     c_begin = split * P.chunks_per_split;
     c_end = c_begin + P.chunks_per_split < n_chunks ? c_begin + P.chunks_per_split : n_chunks;
   } else {
     // the tap tiles of one frame tile are neighbours: they share its G columns in the L2
-    m0 = (long long)(blockIdx.x / n_nt) * BW_MT;
-    n0 = (int)(blockIdx.x % n_nt) * BW_NT;
+    const int cnt = P.nt_cnt > 0 ? P.nt_cnt : n_nt;
+    const int nt = P.nt_lo + (int)(blockIdx.x % cnt);
+    m0 = (long long)(blockIdx.x / cnt) * BW_MT;
+    n0 = nt * BW_NT;
     c_begin = 0;
-    c_end = P.rows_pad / BW_KC;
+    c_end = P.nt_chunks ? P.nt_chunks[nt] : P.rows_pad / BW_KC;  // rows past that are zero on this tap tile
   }
   if (c_begin >= c_end) return;
 
@@ -333,7 +341,7 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int pr = (int)m0 + wm * 64 + mi * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-          if ((pr >> 1) < P.n_half)
+          if ((pr >> 1) < P.n_half && (!P.row_lo || (tap >= P.row_lo[pr] && tap < P.row_hi[pr])))
             unsafeAtomicAdd(P.gw + (long long)logical_row(pr, P.n_half, P.packed) * P.K + tap, acc[mi][ni][r]);
         }
       }
@@ -561,6 +569,42 @@ hipError_t launch_fill_zero(float* p, long long n, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// constant-Q bank of a trainable plan: the streaming-order bank through the plan's index map, and the
+// row-major copy with everything outside a row's support forced to zero
+__global__ void cqt_bank_from_logical_kernel(const CqtBankParams P) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i < P.n_bank) {
+    const int src = P.map[i];
+    P.bank[i] = src >= 0 ? P.logical[src] : 0.f;
+  }
+  if (i < (long long)P.rows * P.K) {
+    const int row = (int)(i / P.K), k = (int)(i - (long long)row * P.K);
+    P.wrm[(long long)row * P.kp + k] = (k >= P.row_lo[row] && k < P.row_hi[row]) ? P.logical[i] : 0.f;
+  }
+}
+
+__global__ void cqt_bank_to_logical_kernel(const CqtBankParams P) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i < (long long)P.rows * P.K) {
+    const int row = (int)(i / P.K), k = (int)(i - (long long)row * P.K);
+    P.logical[i] = P.wrm[(long long)row * P.kp + k];
+  }
+}
+
+hipError_t launch_cqt_bank_from_logical(const CqtBankParams& p, hipStream_t stream) {
+  const long long n = std::max(p.n_bank, (long long)p.rows * p.K);
+  if (n < 1 || (n + 255) / 256 > 0x7fffffffLL || (long long)p.rows * p.K > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(cqt_bank_from_logical_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_cqt_bank_to_logical(const CqtBankParams& p, hipStream_t stream) {
+  const long long n = (long long)p.rows * p.K;
+  if (n < 1 || (n + 255) / 256 > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(cqt_bank_to_logical_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p);
+  return hipGetLastError();
+}
+
 hipError_t launch_fill_zero_frames(float* gbuf, long long rows_pad, long long f0, long long f1, hipStream_t stream) {
   if (rows_pad <= 0 || f1 <= f0) return hipSuccess;
   hipLaunchKernelGGL(fill_zero_frames_kernel, dim3(grid_for(rows_pad * (f1 - f0), 256)), dim3(256), 0, stream, gbuf, rows_pad, f0, f1);
@@ -600,7 +644,9 @@ static bool bw_shapes_ok(const BwParams& p) {
 hipError_t launch_bw_bank(const BwParams& p, hipStream_t stream) {
   if (!bw_shapes_ok(p) || p.n_split < 1 || p.chunks_per_split < 1) return hipErrorInvalidValue;
   if (p.chunks_per_split * p.n_split < p.gpitch / BW_KC) return hipErrorInvalidValue;
-  const long long blocks = (long long)(p.rows_pad / BW_MT) * (p.kp / BW_NT) * p.n_split;
+  if ((p.tiles && p.n_tiles < 1) || (!p.row_lo != !p.row_hi)) return hipErrorInvalidValue;
+  const long long tiles = p.tiles ? p.n_tiles : (long long)(p.rows_pad / BW_MT) * (p.kp / BW_NT);
+  const long long blocks = tiles * p.n_split;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL((bw_gemm_kernel<BW_MODE_BANK>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   return hipGetLastError();
@@ -608,7 +654,8 @@ hipError_t launch_bw_bank(const BwParams& p, hipStream_t stream) {
 
 hipError_t launch_bw_wave(const BwParams& p, hipStream_t stream) {
   if (!bw_shapes_ok(p)) return hipErrorInvalidValue;
-  const long long blocks = (p.gpitch / BW_MT) * (p.kp / BW_NT);
+  if (p.nt_cnt < 0 || p.nt_lo < 0 || p.nt_lo + p.nt_cnt > p.kp / BW_NT || (p.nt_cnt == 0 && p.nt_lo != 0)) return hipErrorInvalidValue;
+  const long long blocks = (p.gpitch / BW_MT) * (p.nt_cnt > 0 ? p.nt_cnt : p.kp / BW_NT);
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL((bw_gemm_kernel<BW_MODE_WAVE>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   return hipGetLastError();

@@ -305,3 +305,115 @@ def test_backward_config4_full_sampled(nb):
     rest = torch.ones(B, dtype=torch.bool, device="cuda:0")
     rest[sampled] = False
     assert not gx[rest].any()
+
+
+# ---- trainable constant-Q kernels ------------------------------------------------------------------
+# (name, sr, fmin, n_bins, bins/octave, hop, n_taps, B, L, output format)
+CQT_BACKWARD_CASES = [
+    ("one-row-tile-magnitude", 8000, 220.0, 30, 12, 64, 0, 3, 5000, oracle.MAGNITUDE),
+    ("power", 8000, 220.0, 30, 12, 64, 0, 3, 5000, oracle.POWER),
+    ("log", 8000, 220.0, 30, 12, 64, 0, 2, 3000, oracle.LOG),
+    ("complex", 8000, 220.0, 30, 12, 64, 0, 2, 3000, oracle.COMPLEX),
+    ("phase", 8000, 220.0, 30, 12, 64, 0, 2, 3000, oracle.PHASE),
+    ("hop-not-dividing-the-taps", 8000, 220.0, 24, 12, 100, 0, 2, 3100, oracle.MAGNITUDE),
+    ("odd-bins-ragged-taps", 8000, 300.0, 19, 8, 32, 600, 2, 2000, oracle.MAGNITUDE),
+    ("two-row-tiles-84-bins", 22050, 32.70, 84, 12, 512, 0, 2, 12000, oracle.MAGNITUDE),
+    ("three-row-tiles-short-waveforms", 16000, 100.0, 150, 24, 256, 0, 40, 5000, oracle.POWER),
+]
+
+
+def _cqt_plan(nb, sr, fmin, n_bins, bpo, hop, n_taps, fmt):
+    return nb.nna_plan_trainable(nb.nna_plan_cqt(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo,
+                                                 n_taps=n_taps, fmt=fmt, device=0))
+
+
+def test_cqt_get_bank_is_the_oracles_bank_and_set_bank_masks(nb):
+    import torch
+    _say("cqt trainable: get / set bank")
+    sr, fmin, n_bins, bpo, hop = 8000, 220.0, 30, 12, 64
+    plan = _cqt_plan(nb, sr, fmin, n_bins, bpo, hop, 0, oracle.MAGNITUDE)
+    W0, mask = oracle.cqt_bank(sr, fmin, n_bins, bpo)
+    W = nb.nna_plan_get_bank(plan).cpu().numpy()
+    assert W.shape == W0.shape and not W[~mask].any()
+    assert np.abs(W - W0).max() <= 1e-7 * np.abs(W0).max()
+    x = _rand(3, 5000, 2)
+    # making the plan trainable rewrote the streaming-order bank through the index map: same transform
+    ref = oracle.cqt(x, sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo)
+    assert _peak_err(nb.nna_cqt(plan, _dev(x)).cpu().numpy(), ref) < 1e-5
+    # a bank that is no constant-Q bank any more, also written outside the supports: those writes are dropped
+    rng = np.random.default_rng(3)
+    Wn = (W + 0.3 * np.abs(W).max() * rng.standard_normal(W.shape)).astype(np.float32)
+    nb.nna_plan_set_bank(plan, _dev(Wn))
+    Wm = np.where(mask, Wn, np.float32(0))
+    assert np.array_equal(nb.nna_plan_get_bank(plan).cpu().numpy(), Wm)
+    ref = oracle.stft_bank(x, Wm, hop=hop)
+    assert _peak_err(nb.nna_cqt(plan, _dev(x)).cpu().numpy(), ref) < 1e-5
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("case", CQT_BACKWARD_CASES, ids=[c[0] for c in CQT_BACKWARD_CASES])
+def test_cqt_backward_parity_small(nb, case):
+    import torch
+    name, sr, fmin, n_bins, bpo, hop, n_taps, B, L, fmt = case
+    _say(f"cqt backward {name}: sr={sr} bins={n_bins} hop={hop} taps={n_taps} B={B} L={L} fmt={fmt}")
+    plan = _cqt_plan(nb, sr, fmin, n_bins, bpo, hop, n_taps, fmt)
+    _, mask = oracle.cqt_bank(sr, fmin, n_bins, bpo, n_taps=n_taps)
+    rng = np.random.default_rng(11)
+    W = nb.nna_plan_get_bank(plan).cpu().numpy()
+    W = np.where(mask, W * (1.0 + 0.2 * rng.standard_normal(W.shape)), 0).astype(np.float32)  # no longer the initial bank
+    nb.nna_plan_set_bank(plan, _dev(W))
+    x = _rand(B, L, 12)
+    out = nb.nna_cqt(plan, _dev(x))
+    ref_out = oracle.stft_bank(x, W, hop=hop, fmt=fmt)
+    gout = rng.standard_normal(ref_out.shape).astype(np.float32)
+    ref_gw, ref_gx = oracle.cqt_bank_backward(x, W, mask, gout, hop=hop, fmt=fmt)
+    gw, gx = nb.nna_cqt_backward(plan, _dev(x), _dev(gout))
+    torch.cuda.synchronize()
+    if fmt != oracle.PHASE:
+        assert _peak_err(out.cpu().numpy(), ref_out) < TOL
+    gw = gw.cpu().numpy()
+    assert not gw[~mask].any()
+    e_w, e_x = _peak_err(gw, ref_gw), _peak_err(gx.cpu().numpy(), ref_gx)
+    _say(f"  bank gradient {e_w:.3e}, waveform gradient {e_x:.3e}")
+    assert e_w < TOL and e_x < TOL
+    # either gradient alone
+    gw1, none = nb.nna_cqt_backward(plan, _dev(x), _dev(gout), want_gx=False)
+    assert none is None and _peak_err(gw1.cpu().numpy(), ref_gw) < TOL
+    none, gx1 = nb.nna_cqt_backward(plan, _dev(x), _dev(gout), want_gw=False)
+    assert none is None and _peak_err(gx1.cpu().numpy(), ref_gx) < TOL
+
+
+def test_cqt_backward_config5_full_sampled(nb):
+    # the 1,770-waveform batch with the 168-bin, 65,536-tap bank; the upstream gradient is non-zero on
+    # three waveforms only (see the STFT case above)
+    import torch
+    _say("cqt backward config 5 (1770 x 176400 @ 44100 Hz, 168 bins) sampled waveforms")
+    wl = signals.WORKLOADS[5]
+    B, L = wl["B"], wl["L"]
+    x = torch.empty((B, L), dtype=torch.float32, device="cuda:0")
+    for s in range(0, B, 128):
+        idx = list(range(s, min(B, s + 128)))
+        x[s:s + len(idx)] = torch.from_numpy(signals.batch(5, idx)).to("cuda:0")
+    sampled = [0, 885, 1769]
+    plan = _cqt_plan(nb, 44100, 32.70, 168, 24, 512, 0, oracle.MAGNITUDE)
+    _, mask = oracle.cqt_bank(44100, 32.70, 168, 24)
+    W = nb.nna_plan_get_bank(plan).cpu().numpy().astype(np.float64)
+    T = 1 + L // 512
+    rng = np.random.default_rng(55)
+    gs = rng.standard_normal((len(sampled), 168, T)).astype(np.float32)
+    gout = torch.zeros((B, 168, T), dtype=torch.float32, device="cuda:0")
+    gout[sampled] = torch.from_numpy(gs).to("cuda:0")
+    gw, gx = nb.nna_cqt_backward(plan, x, gout)
+    torch.cuda.synchronize()
+    _say("  gpu done; oracle on the sampled waveforms")
+    xs = signals.batch(5, sampled)
+    ref_gw, ref_gx = oracle.cqt_bank_backward(xs, W, mask, gs, hop=512)
+    gw = gw.cpu().numpy()
+    assert not gw[~mask].any()
+    e_w = _peak_err(gw, ref_gw)
+    e_x = _peak_err(gx[sampled].cpu().numpy(), ref_gx)
+    _say(f"  bank gradient {e_w:.3e}, waveform gradient {e_x:.3e}")
+    assert e_w < TOL and e_x < TOL
+    rest = torch.ones(B, dtype=torch.bool, device="cuda:0")
+    rest[sampled] = False
+    assert not gx[rest].any()

@@ -176,3 +176,54 @@ def test_mel_gradients_against_central_differences(power):
             xv = x64.copy(); xv[b, j] += e
             return float(np.sum(gout * fwd(W, Wmel, xv)))
         assert abs(num(f) - gx[b, j]) < 1e-6 * max(1.0, abs(gx[b, j]))
+
+
+# ---- constant-Q kernels as a layer's weight --------------------------------------------------------
+CQ = dict(sr=8000, fmin=220.0, n_bins=20, bins_per_octave=6)
+
+
+def test_forward_with_the_cqt_bank_is_the_constant_q_transform():
+    # ties cqt_bank (rows = Re, -Im of the kernels; supports) to the pinned constant-Q oracle
+    x = signals.batch(3, B=2, L=2600)
+    W, mask = oracle.cqt_bank(**CQ)
+    taps = W.shape[1]
+    assert taps == oracle.cqt_default_taps(CQ["sr"], CQ["fmin"], CQ["bins_per_octave"])
+    re, im = oracle.cqt_complex(x, hop=64, **CQ)
+    got = oracle.stft_bank(x, W, hop=64, fmt=oracle.COMPLEX)
+    np.testing.assert_allclose(got, oracle.interleave(re, im), atol=1e-12)
+    np.testing.assert_allclose(oracle.stft_bank(x, W, hop=64), oracle.cqt(x, hop=64, **CQ), rtol=1e-9, atol=1e-13)
+    # supports: N_k taps per row, centred with the spare zero on the right; nothing outside them
+    Nk, _ = oracle.cqt_lengths(CQ["sr"], CQ["fmin"], CQ["n_bins"], CQ["bins_per_octave"])
+    assert np.array_equal(mask.sum(axis=1), np.repeat(Nk, 2))
+    assert not W[~mask].any()
+    for k in (0, 7, 19):
+        first = int(np.argmax(mask[2 * k]))
+        assert first == (taps - Nk[k]) // 2 and mask[2 * k, first:first + Nk[k]].all()
+    # the real-part kernel's second tap is non-zero, and it is the first one inside the support that is
+    # (a periodic Hann window starts at zero)
+    assert W[0, (taps - Nk[0]) // 2] == 0.0 and W[0, (taps - Nk[0]) // 2 + 1] != 0.0
+
+
+@pytest.mark.parametrize("fmt", [oracle.MAGNITUDE, oracle.LOG, oracle.PHASE])
+def test_cqt_bank_gradient_is_the_masked_central_difference(fmt):
+    rng = np.random.default_rng(5)
+    x = signals.batch(3, B=2, L=2600)
+    W, mask = oracle.cqt_bank(**CQ)
+    W = W + 1e-4 * rng.standard_normal(W.shape) * mask        # no longer the initial kernels
+    out = oracle.stft_bank(x, W, hop=64, fmt=fmt)
+    gout = rng.standard_normal(out.shape)
+    gW, gx = oracle.cqt_bank_backward(x, W, mask, gout, hop=64, fmt=fmt)
+    full, gx_full = oracle.stft_bank_backward(x, W, gout, hop=64, fmt=fmt)
+    assert np.array_equal(gx, gx_full)
+    # outside the supports the unmasked derivative is far from zero: the mask is what removes it
+    assert not gW[~mask].any() and np.abs(full[~mask]).max() > 0.1 * np.abs(full).max()
+    loss = lambda Wv: float((oracle.stft_bank(x, Wv, hop=64, fmt=fmt) * gout).sum())
+    rows, cols = np.nonzero(mask)
+    for i in rng.choice(len(rows), 12, replace=False):
+        r, c = rows[i], cols[i]
+        h = 1e-6
+        Wp, Wm = W.copy(), W.copy()
+        Wp[r, c] += h
+        Wm[r, c] -= h
+        fd = (loss(Wp) - loss(Wm)) / (2 * h)
+        assert abs(fd - gW[r, c]) <= 1e-5 * max(1.0, np.abs(gW).max()), (r, c, fd, gW[r, c])
