@@ -175,12 +175,18 @@ struct BwParams {
   long long chunks_per_split;
   // Banks whose rows are zero outside a tap range (constant-Q kernels, rows ordered longest first);
   // all NULL / 0 for a dense bank.
-  const int2* tiles;     // bank gradient: the (row tile, tap tile) pairs that hold taps; NULL: every pair
+  const int2* tiles;     // bank gradient: the output tiles that hold taps, x = row tile | (32-row blocks of it that
+                         // hold taps here) << 16, y = tap tile; NULL: every tile, all four blocks
   int n_tiles;
   const int* row_lo;     // bank gradient: row r is a parameter on taps [row_lo[r], row_hi[r]) only
   const int* row_hi;
-  int nt_lo, nt_cnt;     // waveform gradient: only tap tiles nt_lo .. nt_lo + nt_cnt - 1 hold taps (0: all)
-  const int* nt_chunks;  // waveform gradient: contraction chunks (rows / BW_KC) tap tile nt needs; NULL: all
+  // waveform gradient, gathered over the hop-shifts (see cq_wave_kernel): shift_rng[ct][kc], ct = 128-column
+  // tile of the hop, kc = chunk of BW_KC rows: first and last shift on which those rows hold taps (x > y: none)
+  const int2* shift_rng;
+  int n_kc;              // row chunks listed per column tile
+  int n_shift;           // hop-shifts: ceil(K / hop)
+  int n_ct;              // column tiles of the hop: ceil(hop / BW_NT)
+  long long n_qt;        // hop-row tiles of a waveform's padded signal: ceil((T + n_shift - 1) / BW_MT)
 };
 
 // constant-Q bank of a trainable plan: the caller's [rows][K] tensor <-> streaming order / row-major copy

@@ -117,9 +117,8 @@ struct nna_plan {
   int* d_row_hi = nullptr;
   int2* d_bw_tiles = nullptr;
   int n_bw_tiles = 0;
-  int* d_nt_chunks = nullptr;
-  int nt_lo = 0, nt_cnt = 0;
-  double bw_bank_flops = 0, bw_wave_flops = 0;  // per frame, as executed by the two backward contractions
+  int2* d_shift_rng = nullptr;
+  int n_shift = 0, n_ct = 0, n_kc = 0;
 };
 
 namespace {
@@ -1644,6 +1643,7 @@ static nna_status make_cqt_trainable(nna_plan* plan) {
   const int kp = (int)((K + nna::BW_NT - 1) / nna::BW_NT * nna::BW_NT);
   const int n_nt = kp / nna::BW_NT;
   std::vector<int> map, lo(rows_pad, 0), hi(rows_pad, 0), nt_chunks(n_nt, 0);
+  std::vector<int2> shift_rng;
   std::vector<int2> tiles;
   std::vector<float> logical;
   try {
@@ -1664,36 +1664,51 @@ static nna_status make_cqt_trainable(nna_plan* plan) {
       hi[r] = (int)plan->row_e[r];
     }
     // bank gradient: output tiles (128 rows x 128 taps) that hold a parameter
-    double bank_tiles = 0;
     for (int mt = 0; mt < rows_pad / nna::BW_MT; ++mt) {
       long long s = K, e = 0;
       for (int r = mt * nna::BW_MT; r < std::min(rows, (mt + 1) * nna::BW_MT); ++r) {
         s = std::min(s, plan->row_s[r]);
         e = std::max(e, plan->row_e[r]);
       }
-      for (long long nt = s / nna::BW_NT; nt * nna::BW_NT < e; ++nt) tiles.push_back(make_int2(mt, (int)nt));
+      for (long long nt = s / nna::BW_NT; nt * nna::BW_NT < e; ++nt) {
+        // 32-row blocks of the tile with taps on this tap tile (rows are ordered longest first: a prefix)
+        int alive = 0;
+        for (int r = mt * nna::BW_MT; r < std::min(rows, (mt + 1) * nna::BW_MT); ++r)
+          if (plan->row_s[r] < (nt + 1) * nna::BW_NT && plan->row_e[r] > nt * nna::BW_NT) alive = (r - mt * nna::BW_MT) / 32 + 1;
+        tiles.push_back(make_int2(mt | (alive << 16), (int)nt));
+      }
     }
-    bank_tiles = (double)tiles.size();
-    // waveform gradient: tap tiles that hold a parameter, and how many rows (in chunks of 32) each needs
-    int nt_first = n_nt, nt_last = -1;
-    double wave_chunks = 0;
+    // waveform gradient: how many rows (in chunks of 32; rows are ordered longest first) hold taps on each
+    // 128-tap tile, and from that, per 128-column tile of the hop, the running count over the hop-shifts
     for (int nt = 0; nt < n_nt; ++nt) {
       int r_max = 0;
       for (int r = 0; r < rows; ++r)
         if (plan->row_s[r] < (long long)(nt + 1) * nna::BW_NT && plan->row_e[r] > (long long)nt * nna::BW_NT) r_max = r + 1;
       nt_chunks[nt] = (r_max + nna::BW_KC - 1) / nna::BW_KC;
-      if (r_max > 0) {
-        nt_first = std::min(nt_first, nt);
-        nt_last = nt;
-        wave_chunks += nt_chunks[nt];
-      }
     }
-    if (nt_last < 0 || tiles.empty()) return fail(NNA_ERR_UNSUPPORTED, "the bank has no taps");
-    plan->nt_lo = nt_first;
-    plan->nt_cnt = nt_last - nt_first + 1;
+    if (tiles.empty()) return fail(NNA_ERR_UNSUPPORTED, "the bank has no taps");
+    const int J = (int)((K + plan->hop - 1) / plan->hop), n_ct = (plan->hop + nna::BW_NT - 1) / nna::BW_NT;
+    int n_kc = 0;
+    for (int nt = 0; nt < n_nt; ++nt) n_kc = std::max(n_kc, nt_chunks[nt]);
+    shift_rng.assign((size_t)n_ct * n_kc, make_int2(1, 0));
+    for (int ct = 0; ct < n_ct; ++ct)
+      for (int j = 0; j < J; ++j) {
+        const long long tb = (long long)j * plan->hop + (long long)ct * nna::BW_NT;
+        int chunks = 0;
+        if (tb < K) {
+          const long long last = std::min({tb + nna::BW_NT - 1, (long long)(j + 1) * plan->hop - 1, K - 1});
+          for (long long nt = tb / nna::BW_NT; nt <= last / nna::BW_NT; ++nt) chunks = std::max(chunks, nt_chunks[nt]);
+        }
+        for (int kc = 0; kc < chunks; ++kc) {
+          int2& r = shift_rng[(size_t)ct * n_kc + kc];
+          if (r.x > r.y) r = make_int2(j, j);
+          r.y = j;
+        }
+      }
+    plan->n_kc = n_kc;
+    plan->n_shift = J;
+    plan->n_ct = n_ct;
     plan->n_bw_tiles = (int)tiles.size();
-    plan->bw_bank_flops = 2.0 * bank_tiles * nna::BW_MT * nna::BW_NT;
-    plan->bw_wave_flops = 2.0 * wave_chunks * nna::BW_KC * nna::BW_NT;
     // the bank as the caller's tensor: the values the plan was built with
     logical.assign((size_t)rows * K, 0.0f);
     CqtKernelGen gen(plan);
@@ -1711,7 +1726,7 @@ static nna_status make_cqt_trainable(nna_plan* plan) {
   if (s == NNA_OK) s = upload(&plan->d_row_lo, lo.data(), lo.size() * sizeof(int), "row supports");
   if (s == NNA_OK) s = upload(&plan->d_row_hi, hi.data(), hi.size() * sizeof(int), "row supports");
   if (s == NNA_OK) s = upload(&plan->d_bw_tiles, tiles.data(), tiles.size() * sizeof(int2), "gradient tile list");
-  if (s == NNA_OK) s = upload(&plan->d_nt_chunks, nt_chunks.data(), nt_chunks.size() * sizeof(int), "tap tile table");
+  if (s == NNA_OK) s = upload(&plan->d_shift_rng, shift_rng.data(), shift_rng.size() * sizeof(int2), "hop-shift table");
   if (s == NNA_OK) s = upload(&d_logical, logical.data(), logical.size() * sizeof(float), "kernel bank");
   if (s == NNA_OK) {
     hipError_t e = hipMemset(plan->d_wrm, 0, wrm_bytes);
@@ -1726,9 +1741,10 @@ static nna_status make_cqt_trainable(nna_plan* plan) {
     (void)hipFree(plan->d_row_lo);
     (void)hipFree(plan->d_row_hi);
     (void)hipFree(plan->d_bw_tiles);
-    (void)hipFree(plan->d_nt_chunks);
+    (void)hipFree(plan->d_shift_rng);
     plan->d_wrm = nullptr;
-    plan->d_cq_map = plan->d_row_lo = plan->d_row_hi = plan->d_nt_chunks = nullptr;
+    plan->d_cq_map = plan->d_row_lo = plan->d_row_hi = nullptr;
+    plan->d_shift_rng = nullptr;
     plan->d_bw_tiles = nullptr;
   }
   return s;
@@ -2009,9 +2025,11 @@ nna_status nna_cqt_backward(const nna_plan* plan, const float* x_dev, long long 
   Q.n_tiles = plan->n_bw_tiles;
   Q.row_lo = plan->d_row_lo;
   Q.row_hi = plan->d_row_hi;
-  Q.nt_lo = plan->nt_lo;
-  Q.nt_cnt = plan->nt_cnt;
-  Q.nt_chunks = plan->d_nt_chunks;
+  Q.shift_rng = plan->d_shift_rng;
+  Q.n_kc = plan->n_kc;
+  Q.n_shift = plan->n_shift;
+  Q.n_ct = plan->n_ct;
+  Q.n_qt = (T + plan->n_shift - 1 + nna::BW_MT - 1) / nna::BW_MT;
   if (gw_dev) {
     e = nna::launch_fill_zero(gw_dev, (long long)plan->conv_rows * plan->K, stream);
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
@@ -2332,7 +2350,7 @@ void nna_plan_destroy(nna_plan* plan) {
       (void)hipFree(plan->d_row_lo);
       (void)hipFree(plan->d_row_hi);
       (void)hipFree(plan->d_bw_tiles);
-      (void)hipFree(plan->d_nt_chunks);
+      (void)hipFree(plan->d_shift_rng);
     }
   }
   delete plan;

@@ -116,7 +116,26 @@ __global__ void bank_to_logical_kernel(const BankPermuteParams P, long long n) {
 }
 
 // ---- the contraction kernel --------------------------------------------------------------------
-template <int MODE>
+// Frames t .. t+3 (of T; zero outside) of row `row` of the blocked G buffer [frame / 32][rows_pad][frame % 32];
+// fb0 = global index of the waveform's frame 0, blk = rows_pad * 32.
+__device__ __forceinline__ f32x4 load_g4(const float* __restrict__ gbuf, long long blk, int row, long long fb0, int t, int T) {
+  f32x4 v = {0.f, 0.f, 0.f, 0.f};
+  if (t >= 0 && t + 3 < T) {
+    const long long f = fb0 + t;
+    const int off = (int)(f & 31);
+    if (off <= 28) return *reinterpret_cast<const f32x4_u*>(gbuf + (f >> 5) * blk + row * 32 + off);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = gbuf[((f + i) >> 5) * blk + row * 32 + ((f + i) & 31)];
+  } else if (t + 3 >= 0 && t < T) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (t + i >= 0 && t + i < T) v[i] = gbuf[((fb0 + t + i) >> 5) * blk + row * 32 + ((fb0 + t + i) & 31)];
+  }
+  return v;
+}
+
+// SPARSE: the bank's rows are zero outside a tap range each (P.tiles, P.row_lo / row_hi are given); bank gradient only
+template <int MODE, bool SPARSE>
 __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
   constexpr int A_FLOATS = MODE == BW_MODE_BANK ? BW_MT * BW_PA_M : BW_KC * BW_PK;
   constexpr int B_FLOATS = BW_KC * BW_PK;
@@ -131,19 +150,25 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
   const int n_nt = P.kp / BW_NT;
   long long m0, c_begin, c_end;
   int n0;
+  // Bank gradient: the four waves split the tile's taps (32 each) and every wave sweeps the tile's four
+  // 32-row blocks, of which the first `alive` hold taps here (rows are ordered longest kernel first; a
+  // dense bank has all four): the blocks past that are neither read from LDS nor multiplied, and the
+  // waves stay balanced whatever `alive` is.  Waveform gradient: 2 x 2 waves of 64 x 64.
+  int alive_rt = 4;
   if constexpr (MODE == BW_MODE_BANK) {
     const int n_mt = P.rows_pad / BW_MT;
-    const long long tiles = P.tiles ? P.n_tiles : (long long)n_mt * n_nt;
+    const long long tiles = SPARSE ? P.n_tiles : (long long)n_mt * n_nt;
     const long long split = blockIdx.x / tiles;
     int tile = (int)(blockIdx.x - split * tiles);
     // Workgroup ids are dealt round-robin to the 8 XCDs, each with an L2 of its own.  Give every XCD a
     // contiguous run of tiles in row-major order: it then reads only its own rows of G (the large
     // operand) instead of all of them.
     if (tiles % 8 == 0) tile = (tile & 7) * (int)(tiles / 8) + (tile >> 3);
-    if (P.tiles) {
+    if constexpr (SPARSE) {
       const int2 t = P.tiles[tile];
-      m0 = (long long)t.x * BW_MT;
+      m0 = (long long)(t.x & 0xffff) * BW_MT;
       n0 = t.y * BW_NT;
+      alive_rt = t.x >> 16;
     } else {
       m0 = (long long)(tile / n_nt) * BW_MT;
       n0 = (tile % n_nt) * BW_NT;
@@ -153,14 +178,13 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
     c_end = c_begin + P.chunks_per_split < n_chunks ? c_begin + P.chunks_per_split : n_chunks;
   } else {
     // the tap tiles of one frame tile are neighbours: they share its G columns in the L2
-    const int cnt = P.nt_cnt > 0 ? P.nt_cnt : n_nt;
-    const int nt = P.nt_lo + (int)(blockIdx.x % cnt);
-    m0 = (long long)(blockIdx.x / cnt) * BW_MT;
-    n0 = nt * BW_NT;
+    m0 = (long long)(blockIdx.x / n_nt) * BW_MT;
+    n0 = (int)(blockIdx.x % n_nt) * BW_NT;
     c_begin = 0;
-    c_end = P.nt_chunks ? P.nt_chunks[nt] : P.rows_pad / BW_KC;  // rows past that are zero on this tap tile
+    c_end = P.rows_pad / BW_KC;
   }
   if (c_begin >= c_end) return;
+  const int alive = SPARSE ? alive_rt : 4;
 
   const FrameGeom& g = P.g;
   f32x4 ra[4], rb[4];
@@ -259,38 +283,49 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
     }
   };
 
-  f32x16 acc[2][2];
+  // bank gradient: acc[s] = row block s x this wave's 32 taps; waveform gradient: acc[2 mi + ni]
+  f32x16 acc[4];
 #pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
+  for (int s = 0; s < 4; ++s)
 #pragma unroll
-    for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+    for (int r = 0; r < 16; ++r) acc[s][r] = 0.f;
 
   // lane (h, r32) holds contraction indices 8 kg + 4 h + e, e = 0..3, of row / column r32
-  auto load_frags = [&](const float* A, const float* B, int kg, f32x4 (&a)[2], f32x4 (&b)[2]) {
+  constexpr int NA = MODE == BW_MODE_BANK ? 4 : 2, NB = MODE == BW_MODE_BANK ? 1 : 2;
+  auto load_frags = [&](const float* A, const float* B, int kg, f32x4 (&a)[NA], f32x4 (&b)[NB]) {
+    if constexpr (MODE == BW_MODE_BANK) {
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi) {
-      if constexpr (MODE == BW_MODE_BANK) {
-        a[mi] = *reinterpret_cast<const f32x4*>(A + (wm * 64 + mi * 32 + r32) * BW_PA_M + 8 * kg + 4 * h);
-      } else {
+      for (int s = 0; s < 4; ++s)
+        if (s < alive) a[s] = *reinterpret_cast<const f32x4*>(A + (s * 32 + r32) * BW_PA_M + 8 * kg + 4 * h);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) a[mi][e] = A[(8 * kg + 4 * h + e) * BW_PK + wm * 64 + mi * 32 + r32];
-      }
-    }
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) b[ni][e] = B[(8 * kg + 4 * h + e) * BW_PK + wn * 64 + ni * 32 + r32];
-  };
-  auto mfma_group = [&](const f32x4 (&a)[2], const f32x4 (&b)[2]) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
+      for (int e = 0; e < 4; ++e) b[0][e] = B[(8 * kg + 4 * h + e) * BW_PK + wave * 32 + r32];
+    } else {
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][e], b[ni][e], acc[mi][ni], 0, 0, 0);
+        for (int e = 0; e < 4; ++e) a[mi][e] = A[(8 * kg + 4 * h + e) * BW_PK + wm * 64 + mi * 32 + r32];
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) b[ni][e] = B[(8 * kg + 4 * h + e) * BW_PK + wn * 64 + ni * 32 + r32];
+    }
+  };
+  auto mfma_group = [&](const f32x4 (&a)[NA], const f32x4 (&b)[NB]) {
+    if constexpr (MODE == BW_MODE_BANK) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          if (s < alive) acc[s] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s][e], b[0][e], acc[s], 0, 0, 0);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < 2; ++ni)
+            acc[2 * mi + ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][e], b[ni][e], acc[2 * mi + ni], 0, 0, 0);
+    }
   };
 
   // Pipeline: while chunk c is multiplied out of one LDS buffer, chunk c+1 (requested one iteration
@@ -311,7 +346,7 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
     // the matrix pipe idles for the LDS latency every four MFMAs), and the LDS writes of chunk c+1
     // and the global requests for chunk c+2 sit behind reads that are already on their way, with a
     // whole MFMA group to hide them.
-    f32x4 a0[2], b0[2], a1[2], b1[2];
+    f32x4 a0[NA], b0[NB], a1[NA], b1[NB];
     load_frags(A, B, 0, a0, b0);
     load_frags(A, B, 1, a1, b1);
     __builtin_amdgcn_sched_barrier(0);
@@ -332,19 +367,19 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
 
   // ---- epilogue: accumulator register r of lane (h, r32) is output row 8 (r/4) + 4 h + r%4, column r32
   if constexpr (MODE == BW_MODE_BANK) {
+    const int tap = n0 + wave * 32 + r32;
+    if (tap < P.K) {
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-      for (int ni = 0; ni < 2; ++ni) {
-        const int tap = n0 + wn * 64 + ni * 32 + r32;
-        if (tap >= P.K) continue;
+      for (int s = 0; s < 4; ++s) {
+        if (s >= alive) continue;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int pr = (int)m0 + wm * 64 + mi * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-          if ((pr >> 1) < P.n_half && (!P.row_lo || (tap >= P.row_lo[pr] && tap < P.row_hi[pr])))
-            unsafeAtomicAdd(P.gw + (long long)logical_row(pr, P.n_half, P.packed) * P.K + tap, acc[mi][ni][r]);
+          const int pr = (int)m0 + s * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+          if ((pr >> 1) < P.n_half && (!SPARSE || (tap >= P.row_lo[pr] && tap < P.row_hi[pr])))
+            unsafeAtomicAdd(P.gw + (long long)logical_row(pr, P.n_half, P.packed) * P.K + tap, acc[s][r]);
         }
       }
+    }
   } else {
     const int L = (int)g.L;
 #pragma unroll
@@ -365,7 +400,7 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
               if (tap < P.K) {
                 int j = t * g.hop + tap - g.pad;
                 j = j < 0 ? -j : (j >= L ? 2 * (L - 1) - j : j);  // mirror padding folded back
-                unsafeAtomicAdd(row + j, acc[mi][ni][4 * q + i]);
+                unsafeAtomicAdd(row + j, acc[2 * mi + ni][4 * q + i]);
               }
             }
           }
@@ -373,6 +408,174 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
             t = 0;
             ++b;
           }
+        }
+      }
+  }
+}
+
+// ---- waveform gradient of a bank with per-row supports -----------------------------------------
+// Long constant-Q kernels span hundreds of hop-shifts; a tile of frames x taps (as above) would add
+// every product to memory atomically and re-read G for every shift.  Here the output is tiled by
+// (hop-row q, column c) of a waveform's padded signal, sample q hop + c, and the shifts are gathered
+// inside the workgroup:
+//   out[q, c] = sum_r sum_j G[r, q - j] W[r, j hop + c],
+// a contraction over (row r, shift j) pairs whose A operand is G read j frames back.  Rows go in chunks
+// of BW_KC, the outer loop; for one chunk the frames q0 - j .. q0 - j + 127 of all its shifts form
+// one window of G that stays in LDS while only W tiles stream.  Each padded sample is written once
+// (the atomic add only folds the mirrored samples onto the waveform).
+constexpr int CW_SEG = BW_MT;             // shifts served by one window
+constexpr int CW_WIN = BW_MT + CW_SEG;    // frames in the window (128 tile rows + up to 127 shifts, rounded up)
+constexpr int CW_PA = CW_WIN + 4;         // its LDS pitch
+
+__global__ __launch_bounds__(256, 2) void cq_wave_kernel(const BwParams P) {
+  __shared__ __attribute__((aligned(16))) float ldsA[BW_KC * CW_PA];
+  __shared__ __attribute__((aligned(16))) float ldsB[2][BW_KC * BW_PK];
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int h = lane >> 5, r32 = lane & 31;
+  const FrameGeom& g = P.g;
+  const int T = g.T;
+
+  // the column tiles of one (waveform, row tile) are neighbours: they share its G frames in the L2
+  const long long bq = blockIdx.x / P.n_ct;
+  const int ct = (int)(blockIdx.x - bq * P.n_ct), n0 = ct * BW_NT;
+  const long long gb = bq / P.n_qt;
+  const int q0 = (int)(bq - gb * P.n_qt) * BW_MT;
+  // shifts j with a frame q - j inside [0, T) for some row q of the tile
+  const int j_lo = q0 - (T - 1) > 0 ? q0 - (T - 1) : 0;
+  const int j_hi = q0 + BW_MT - 1 < P.n_shift - 1 ? q0 + BW_MT - 1 : P.n_shift - 1;
+
+  f32x16 acc[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[s][r] = 0.f;
+
+  f32x4 rb0[4], rb1[4];  // W tiles in flight: requested two shifts ahead of their use
+  const int c4 = 4 * (tid & 31);
+  // W[k0 + tid/32 + 8 p][j hop + n0 + c4 ..]; columns past the hop belong to the next shift: zero
+  auto fetch_b = [&](f32x4 (&rb)[4], int k0, int j) {
+    const long long tb = (long long)j * g.hop + n0;
+    const bool whole = n0 + BW_NT <= g.hop && tb + BW_NT <= P.kp;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const float* bp = P.wrm + (long long)(k0 + (tid >> 5) + 8 * p) * P.kp + tb + c4;
+      if (whole) {
+        rb[p] = *reinterpret_cast<const f32x4_u*>(bp);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) rb[p][i] = (n0 + c4 + i < g.hop && tb + c4 + i < P.kp) ? bp[i] : 0.f;
+      }
+    }
+  };
+  auto stage_b = [&](const f32x4 (&rb)[4], int buf) {
+    float* b = &ldsB[buf][(tid >> 5) * BW_PK + c4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) *reinterpret_cast<f32x4*>(b + 8 * p * BW_PK) = rb[p];
+  };
+  // lane (h, r32) holds contraction indices 8 kg + 4 h + e of tile row / column r32; `w` = window index of tile row 0
+  // A 32-row block of the tile whose frames q - j all fall outside the waveform on this shift has a zero A
+  // operand (the first and last row tiles of a waveform are half such blocks): it is skipped.
+  bool live[2];
+  auto load_frags = [&](const float* B, int w, int kg, f32x4 (&a)[2], f32x4 (&b)[2]) {
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+      if (live[mi]) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) a[mi][e] = ldsA[(8 * kg + 4 * h + e) * CW_PA + w + wm * 64 + mi * 32 + r32];
+      }
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) b[ni][e] = B[(8 * kg + 4 * h + e) * BW_PK + wn * 64 + ni * 32 + r32];
+  };
+  auto mfma_group = [&](const f32x4 (&a)[2], const f32x4 (&b)[2]) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+        if (live[mi]) {
+#pragma unroll
+          for (int ni = 0; ni < 2; ++ni)
+            acc[2 * mi + ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][e], b[ni][e], acc[2 * mi + ni], 0, 0, 0);
+        }
+  };
+
+  int buf = 0;
+  for (int kc = 0; kc < P.n_kc; ++kc) {
+    const int2 rng = P.shift_rng[ct * P.n_kc + kc];  // shifts on which rows k0 .. k0 + 31 hold taps
+    const int ja = rng.x > j_lo ? rng.x : j_lo, jb = rng.y < j_hi ? rng.y : j_hi;
+    const int k0 = kc * BW_KC;
+    for (int js = ja; js <= jb; js += CW_SEG) {
+      const int je = js + CW_SEG - 1 < jb ? js + CW_SEG - 1 : jb;
+      __syncthreads();  // every wave is done with the previous window and W tiles
+      // window: frames q0 - je .. q0 - je + CW_WIN - 1 of rows k0 .. k0 + 31 (zero outside the waveform)
+      {
+        const int row = tid >> 3;
+#pragma unroll
+        for (int i = 0; i < CW_WIN / 32; ++i) {
+          const int w = 4 * (tid & 7) + 32 * i;
+          *reinterpret_cast<f32x4*>(&ldsA[row * CW_PA + w]) =
+              load_g4(P.gbuf, (long long)P.rows_pad * 32, k0 + row, gb * T, q0 - je + w, T);
+        }
+      }
+      fetch_b(rb0, k0, js);
+      if (js < je) fetch_b(rb1, k0, js + 1);
+      // one shift: its W tile (requested two shifts ago) goes to LDS, the tile two shifts on is requested
+      auto step = [&](int j, f32x4 (&rb)[4]) {
+        stage_b(rb, buf);
+        __syncthreads();
+        if (j + 2 <= je) fetch_b(rb, k0, j + 2);
+        const float* B = ldsB[buf];
+        buf ^= 1;
+        const int w = je - j;
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+          const int t_first = q0 + wm * 64 + mi * 32 - j;  // frame of the block's first row
+          live[mi] = t_first + 31 >= 0 && t_first < T;
+        }
+        if (!live[0] && !live[1]) return;
+        f32x4 a0[2], b0[2], a1[2], b1[2];
+        load_frags(B, w, 0, a0, b0);
+        load_frags(B, w, 1, a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_group(a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(B, w, 2, a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_group(a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(B, w, 3, a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_group(a0, b0);
+        mfma_group(a1, b1);
+      };
+      for (int j = js; j <= je; j += 2) {
+        step(j, rb0);
+        if (j + 1 <= je) step(j + 1, rb1);
+      }
+    }
+  }
+
+  // register r of lane (h, r32): hop-row q0 + wm 64 + mi 32 + 8 (r/4) + 4 h + r%4, column n0 + wn 64 + ni 32 + r32
+  const int L = (int)g.L;
+  const long long ext = (long long)(T - 1) * g.hop + P.K;  // samples of the padded signal that frames cover
+  float* __restrict__ xrow = P.gx + gb * g.L;
+#pragma unroll
+  for (int ni = 0; ni < 2; ++ni) {
+    const int col = n0 + wn * 64 + ni * 32 + r32;
+    if (col >= g.hop) continue;
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const long long pos = (long long)(q0 + wm * 64 + mi * 32 + 8 * (r >> 2) + 4 * h + (r & 3)) * g.hop + col;
+        if (pos < ext) {
+          long long j = pos - g.pad;
+          j = j < 0 ? -j : (j >= L ? 2 * (L - 1) - j : j);  // mirror padding folded back
+          unsafeAtomicAdd(xrow + j, acc[2 * mi + ni][r]);
         }
       }
   }
@@ -644,20 +847,32 @@ static bool bw_shapes_ok(const BwParams& p) {
 hipError_t launch_bw_bank(const BwParams& p, hipStream_t stream) {
   if (!bw_shapes_ok(p) || p.n_split < 1 || p.chunks_per_split < 1) return hipErrorInvalidValue;
   if (p.chunks_per_split * p.n_split < p.gpitch / BW_KC) return hipErrorInvalidValue;
-  if ((p.tiles && p.n_tiles < 1) || (!p.row_lo != !p.row_hi)) return hipErrorInvalidValue;
-  const long long tiles = p.tiles ? p.n_tiles : (long long)(p.rows_pad / BW_MT) * (p.kp / BW_NT);
+  const bool sparse = p.tiles != nullptr;
+  if (sparse && (p.n_tiles < 1 || !p.row_lo || !p.row_hi)) return hipErrorInvalidValue;
+  const long long tiles = sparse ? p.n_tiles : (long long)(p.rows_pad / BW_MT) * (p.kp / BW_NT);
   const long long blocks = tiles * p.n_split;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((bw_gemm_kernel<BW_MODE_BANK>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  if (sparse)
+    hipLaunchKernelGGL((bw_gemm_kernel<BW_MODE_BANK, true>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  else
+    hipLaunchKernelGGL((bw_gemm_kernel<BW_MODE_BANK, false>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 
 hipError_t launch_bw_wave(const BwParams& p, hipStream_t stream) {
   if (!bw_shapes_ok(p)) return hipErrorInvalidValue;
-  if (p.nt_cnt < 0 || p.nt_lo < 0 || p.nt_lo + p.nt_cnt > p.kp / BW_NT || (p.nt_cnt == 0 && p.nt_lo != 0)) return hipErrorInvalidValue;
-  const long long blocks = (p.gpitch / BW_MT) * (p.nt_cnt > 0 ? p.nt_cnt : p.kp / BW_NT);
+  if (p.shift_rng) {
+    if (p.n_shift < 1 || p.n_kc < 1 || p.n_kc > p.rows_pad / BW_KC || p.n_ct != (p.g.hop + BW_NT - 1) / BW_NT ||
+        p.n_qt != (p.g.T + p.n_shift - 1 + BW_MT - 1) / BW_MT || (long long)p.n_shift * p.g.hop < p.K)
+      return hipErrorInvalidValue;
+    const long long blocks = p.g.B * p.n_qt * p.n_ct;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(cq_wave_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    return hipGetLastError();
+  }
+  const long long blocks = (p.gpitch / BW_MT) * (p.kp / BW_NT);
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((bw_gemm_kernel<BW_MODE_WAVE>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  hipLaunchKernelGGL((bw_gemm_kernel<BW_MODE_WAVE, false>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 

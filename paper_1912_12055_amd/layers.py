@@ -169,29 +169,56 @@ def _cqt_bins(sr, fmin, fmax, n_bins, bins_per_octave):
     return int(math.ceil(bins_per_octave * math.log2(fmax / fmin)))  # fmax replaces n_bins, as in the paper's layers
 
 
-class _Cqt(torch.nn.Module):
+class _CqtFn(torch.autograd.Function):
+    """nna_cqt with nna_cqt_backward as its derivative (kernels W and waveform x)."""
+
+    @staticmethod
+    def forward(ctx, x, W, layer):
+        ctx.layer = layer
+        ctx.save_for_backward(x)
+        return nb.nna_cqt(layer.plan, x)
+
+    @staticmethod
+    def backward(ctx, gout):
+        (x,) = ctx.saved_tensors
+        need_x, need_w = ctx.needs_input_grad[0], ctx.needs_input_grad[1]
+        gw, gx = nb.nna_cqt_backward(ctx.layer.plan, x, gout.contiguous(), want_gw=need_w, want_gx=need_x)
+        return gx, gw, None
+
+
+class _Cqt(_Trainable):
     def __init__(self, trainable):
         super().__init__()
         if trainable:
-            raise NotImplementedError("trainable constant-Q kernels are not implemented")
+            raise NotImplementedError("trainable kernels: only CQT1992v2 (time-domain kernels at one rate)")
 
 
 class CQT1992v2(_Cqt):
-    """Sec. III-C "CQT with time domain kernels": one rate, full-length kernels (the paper's default CQT)."""
+    """Sec. III-C "CQT with time domain kernels": one rate, full-length kernels (the paper's default CQT).
+    ``trainable=True`` makes the kernels ``self.cqt_kernels`` [2 n_bins, n_taps] a parameter (rows 2k / 2k+1 =
+    real / imaginary part of bin k's kernel; the taps outside a kernel's own length stay zero)."""
 
     def __init__(self, sr=22050, hop_length=512, fmin=32.70, fmax=None, n_bins=84, bins_per_octave=12, norm=1,
                  window="hann", center=True, pad_mode="reflect", trainable=False, output_format="Magnitude",
                  device="cuda:0"):
-        super().__init__(trainable)
+        super().__init__(False)
         _check_pad(center, pad_mode)
         if norm != 1:
             raise ValueError("norm: only the L1 normalisation (1) is implemented")
         self.plan = nb.nna_plan_cqt(sr=sr, hop=hop_length, fmin=fmin, n_bins=_cqt_bins(sr, fmin, fmax, n_bins, bins_per_octave),
                                     bins_per_octave=bins_per_octave, win=_window(window), center=center,
                                     fmt=_format(output_format), device=_device_index(device))
+        self.trainable = bool(trainable)
+        if self.trainable:
+            nb.nna_plan_trainable(self.plan)
+            self.cqt_kernels = torch.nn.Parameter(nb.nna_plan_get_bank(self.plan))
 
     def forward(self, x):
-        return nb.nna_cqt(self.plan, _as_batch(x))
+        x = _as_batch(x)
+        if not self.trainable:
+            return nb.nna_cqt(self.plan, x)
+        self._sync(self.cqt_kernels, nb.nna_plan_set_bank, "bank")
+        return _CqtFn.apply(x, self.cqt_kernels, self)
 
 
 class CQT1992(_Cqt):

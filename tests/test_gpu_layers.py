@@ -50,7 +50,7 @@ def test_layers_with_the_papers_defaults_match_the_oracle(layers):
     assert _err(layers.CQT1992v2(output_format="Complex")(xd), oracle.interleave(re, im)) < TOL
     assert layers.STFT()(xd[0]).shape == (1, 1025, 44)  # a single waveform
     with pytest.raises(NotImplementedError):
-        layers.CQT1992v2(trainable=True)
+        layers.CQT2010v2(trainable=True)
     with pytest.raises(ValueError):
         layers.STFT(pad_mode="constant")
 
@@ -105,3 +105,34 @@ def test_optimiser_steps_tune_the_kernels_and_the_filterbank(layers):
         losses.append(float(loss.detach()))
     _say(f"  mel loss {losses[0]:.4e} -> {losses[-1]:.4e}")
     assert losses[-1] < 0.8 * losses[0] and mel.wsin_wcos.grad is None
+
+
+def test_autograd_and_an_optimiser_on_the_trainable_cqt_layer(layers):
+    import torch
+    _say("layers: CQT1992v2(trainable=True)")
+    cfg = dict(sr=8000, fmin=220.0, n_bins=30, bins_per_octave=12)
+    layer = layers.CQT1992v2(hop_length=64, trainable=True, **cfg)
+    x = signals.batch(3, B=3, L=5000, sr=8000)
+    xd = torch.from_numpy(x).cuda().requires_grad_(True)
+    out = layer(xd)
+    gout = np.random.default_rng(2).standard_normal(tuple(out.shape)).astype(np.float32)
+    (out * torch.from_numpy(gout).cuda()).sum().backward()
+    W = layer.cqt_kernels.detach().cpu().numpy().astype(np.float64)
+    _, mask = oracle.cqt_bank(**cfg)
+    ref_gw, ref_gx = oracle.cqt_bank_backward(x, W, mask, gout, hop=64)
+    assert _err(layer.cqt_kernels.grad, ref_gw) < TOL and _err(xd.grad, ref_gx) < TOL
+    # a few optimiser steps towards a scaled copy of the initial transform; the zeros that centre the kernels stay zeros
+    target = 0.5 * layer(xd.detach()).detach()
+    opt = torch.optim.Adam(layer.parameters(), lr=1e-4)
+    losses = []
+    for _ in range(6):
+        opt.zero_grad()
+        loss = ((layer(xd.detach()) - target) ** 2).mean()
+        loss.backward()
+        opt.step()
+        losses.append(float(loss.detach()))
+    _say(f"  cqt loss {losses[0]:.4e} -> {losses[-1]:.4e}")
+    assert losses[-1] < 0.8 * losses[0]
+    layer(xd.detach())
+    from paper_1912_12055_amd import binding as nb
+    assert not nb.nna_plan_get_bank(layer.plan).cpu().numpy()[~mask].any()

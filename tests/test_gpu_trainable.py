@@ -87,7 +87,10 @@ def test_not_trainable_plans_are_refused(nb):
         nb.nna_plan_get_bank(plan)
     assert e.value.status == nb.NNA_ERR_INVALID_ARG and "nna_plan_trainable" in e.value.message
     with pytest.raises(nb.NnaError) as e:
-        nb.nna_plan_trainable(nb.nna_plan_cqt(sr=8000, hop=64, fmin=220.0, n_bins=24, device=0))
+        nb.nna_plan_trainable(nb.nna_plan_cqt2010v2(sr=8000, hop=64, fmin=220.0, n_bins=24, device=0))
+    assert e.value.status == nb.NNA_ERR_INVALID_ARG
+    with pytest.raises(nb.NnaError) as e:  # the constant-Q backward pass wants a constant-Q plan
+        nb.nna_cqt_backward_workspace(nb.nna_plan_trainable(nb.nna_plan_stft(n_fft=256, hop=64, device=0)), 2, 1000)
     assert e.value.status == nb.NNA_ERR_INVALID_ARG
     with pytest.raises(nb.NnaError) as e:
         nb.nna_plan_get_mel_weights(nb.nna_plan_trainable(nb.nna_plan_stft(n_fft=256, hop=64, device=0)))
