@@ -149,8 +149,20 @@ double window_value(int win, long long n, long long N) {
 }
 
 // ---- device helpers -----------------------------------------------------------------
-std::once_flag g_init_flag;
-hipError_t g_init_err = hipSuccess;
+// The kernels' dynamic-LDS attribute is a per-device setting: set once on every device a plan is built for
+// (that device current).
+std::mutex g_init_mutex;
+std::vector<char> g_init_done;
+hipError_t ensure_kernels_init(int device) {
+  std::lock_guard<std::mutex> lock(g_init_mutex);
+  if ((int)g_init_done.size() <= device) g_init_done.resize(device + 1, 0);
+  if (!g_init_done[device]) {
+    const hipError_t e = nna::kernels_init();
+    if (e != hipSuccess) return e;
+    g_init_done[device] = 1;
+  }
+  return hipSuccess;
+}
 
 template <typename T>
 nna_status upload(T** dst, const void* src, size_t bytes, const char* what) {
@@ -743,10 +755,10 @@ nna_status finish_plan(nna_plan* p, nna_plan** out, const MelDeviceLayout* mel) 
       delete p;
       return fail_hip(e, "hipSetDevice");
     }
-    std::call_once(g_init_flag, [] { g_init_err = nna::kernels_init(); });
-    if (g_init_err != hipSuccess) {
+    e = ensure_kernels_init(p->device);
+    if (e != hipSuccess) {
       delete p;
-      return fail_hip(g_init_err, "kernel attribute setup");
+      return fail_hip(e, "kernel attribute setup");
     }
     nna_status s = upload(&p->d_bank, p->h_bank.data(), p->bank_floats * sizeof(float), "kernel bank");
     if (s == NNA_OK && p->precision == NNA_PREC_F16)

@@ -104,3 +104,26 @@ def impulse(L: int, at: int, amp: float = 1.0) -> np.ndarray:
 def tone(L: int, sr: float, f: float, amp: float = 1.0, phase: float = 0.0) -> np.ndarray:
     t = np.arange(L, dtype=np.float64) / sr
     return (amp * np.cos(2.0 * np.pi * f * t + phase)).astype(np.float32)
+
+
+def validation_signals(L: int = 22050, sr: int = 22050) -> np.ndarray:
+    """float32 [4, L]: the kinds of input the paper checks its output on (Sec. IV-B) -- a linear sine
+    sweep, a logarithmic sine sweep, an impulse train, and, standing in for the recorded piano scale, a
+    chromatic scale of decaying harmonic tones.  Deterministic; generation only."""
+    t = np.arange(L, dtype=np.float64) / float(sr)
+    dur = L / float(sr)
+    f0, f1 = 50.0, 0.45 * sr
+    lin = np.sin(2.0 * np.pi * (f0 * t + 0.5 * (f1 - f0) / dur * t * t))
+    k = np.log(f1 / f0) / dur
+    log = np.sin(2.0 * np.pi * f0 * (np.exp(k * t) - 1.0) / k)
+    imp = np.zeros(L)
+    imp[L // 8::L // 4] = 1.0
+    scale = np.zeros(L)
+    n_notes = 12
+    seg = L // n_notes
+    for i in range(n_notes):
+        f = 220.0 * 2.0 ** (i / 12.0)
+        tt = t[:seg]
+        note = sum(np.sin(2.0 * np.pi * f * h * tt) / h for h in (1, 2, 3, 4) if f * h < 0.5 * sr)
+        scale[i * seg:(i + 1) * seg] = 0.25 * note * np.exp(-3.0 * tt)
+    return np.stack([0.5 * lin, 0.5 * log, imp, scale]).astype(np.float32)

@@ -776,3 +776,33 @@ def test_cqt_longest_accepted_waveform(nb):
                            taps, hop, L, x)
     _say(f"  rel err {e:.3e}")
     assert e < TOL
+
+
+# ---- the paper's own validation inputs (Sec. IV-B) ------------------------------------------------
+def test_sweeps_impulses_and_a_chromatic_scale_through_every_layer(nb):
+    # the paper compares its layers with a reference implementation on sine sweeps, an impulse tone and
+    # a piano scale; here the same kinds of input go through every layer against the oracle, per signal
+    _say("validation signals (linear sweep, log sweep, impulses, chromatic scale) through all layers")
+    sr = 22050
+    x = signals.validation_signals(L=22050, sr=sr)
+    xd = _dev(x)
+    cq = dict(sr=sr, hop=256, fmin=110.0, n_bins=72, bins_per_octave=12)
+    layers = [
+        ("stft", nb.nna_stft(nb.nna_plan_stft(sr=sr, n_fft=1024, hop=256, device=0), xd),
+         oracle.stft(x, n_fft=1024, hop=256)),
+        ("log-frequency stft", nb.nna_stft(nb.nna_plan_stft_scaled(sr=sr, n_fft=1024, hop=256, freq_scale=nb.NNA_FREQ_LOG,
+                                                                   fmin=60.0, fmax=8000.0, freq_bins=256, device=0), xd),
+         oracle.stft_scaled(x, sr=sr, n_fft=1024, hop=256, scale=oracle.FREQ_LOG, fmin=60.0, fmax=8000.0, freq_bins=256)),
+        ("mel", nb.nna_mel(nb.nna_plan_mel(sr=sr, n_fft=1024, hop=256, n_mels=96, device=0), xd),
+         oracle.mel(x, sr=sr, n_fft=1024, hop=256, n_mels=96)),
+        ("cqt1992v2", nb.nna_cqt(nb.nna_plan_cqt(device=0, **cq), xd), oracle.cqt(x, **cq)),
+        ("cqt2010v2", nb.nna_cqt2010v2(nb.nna_plan_cqt2010v2(device=0, **cq), xd), oracle.cqt2010v2(x, **cq)),
+        ("cqt1992", nb.nna_cqt1992(nb.nna_plan_cqt1992(device=0, **cq), xd), oracle.cqt1992(x, **cq)),
+        ("cqt2010", nb.nna_cqt2010(nb.nna_plan_cqt2010(device=0, **cq), xd), oracle.cqt2010(x, **cq)),
+    ]
+    for name, got, ref in layers:
+        got = got.cpu().numpy().astype(np.float64)
+        assert got.shape == ref.shape, name
+        errs = [np.abs(got[b] - ref[b]).max() / np.abs(ref[b]).max() for b in range(ref.shape[0])]
+        _say(f"  {name}: " + ", ".join(f"{e:.2e}" for e in errs))
+        assert max(errs) < TOL, (name, errs)

@@ -221,3 +221,22 @@ def test_tone_peak_under_hamming_and_blackman(win, coef):
     out = oracle.stft(x, n_fft=N, hop=N, window=win, center=False)[0, :, 0]
     assert int(np.argmax(out)) == k0
     assert abs(out[k0] - A * coef * N / 2) < 1e-5 * N
+
+
+def test_validation_signals_sweep_tracks_its_frequency_and_impulse_is_flat():
+    # Sec. IV-B's inputs: the linear sweep's peak bin follows its instantaneous frequency, and an impulse
+    # n0 samples into a frame gives |X_k| = w[n0] for every bin (the DFT of a shifted impulse has unit modulus)
+    sr, L, N, hop = 22050, 22050, 1024, 256
+    x = signals.validation_signals(L=L, sr=sr)
+    S = oracle.stft(x, n_fft=N, hop=hop)
+    f0, f1, dur = 50.0, 0.45 * sr, L / sr
+    for t in range(4, S.shape[2] - 4):
+        f_inst = f0 + (f1 - f0) * (t * hop / sr) / dur
+        assert abs(int(np.argmax(S[0, :, t])) - f_inst * N / sr) <= 1.5, t
+    pos = L // 8                                   # the first impulse
+    w = 0.5 - 0.5 * np.cos(2 * np.pi * np.arange(N) / N)
+    for t in range(S.shape[2]):
+        n0 = pos - (t * hop - N // 2)              # its offset inside frame t
+        others = [p for p in range(L // 8, L, L // 4) if p != pos and 0 <= p - (t * hop - N // 2) < N]
+        if 0 <= n0 < N and not others and t * hop - N // 2 >= 0 and t * hop + N // 2 <= L:
+            np.testing.assert_allclose(S[2, :, t], w[n0], atol=1e-12)
