@@ -212,7 +212,29 @@ def main() -> int:
                                    / (PEAK_F16_MFMA_TFLOPS if name == "stft_f16_operands" else PEAK_FP32_MFMA_TFLOPS), 4),
                 "mfma_peak_tflops": PEAK_F16_MFMA_TFLOPS if name == "stft_f16_operands" else PEAK_FP32_MFMA_TFLOPS,
             }
-        del o_lin, ws, x3, o_1992
+        # Mel and the power spectrogram it is computed from, both written by one launch (one contraction)
+        p_mel2 = nb.nna_plan_mel(sr=sr, n_fft=2048, hop=512, n_mels=128, fmin=0.0, fmax=22050.0, device=0)
+        o_mel2 = torch.empty((B, 128, T), dtype=torch.float32, device=dev)
+        for _ in range(max(1, args.warmup)):
+            nb.nna_mel_with_stft(p_mel2, x4, o_mel2, o_lin)
+        ev = []
+        for _ in range(args.steps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            nb.nna_mel_with_stft(p_mel2, x4, o_mel2, o_lin)
+            b.record()
+            ev.append((a, b))
+        torch.cuda.synchronize()
+        ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+        alg = p_mel2.info()["algorithmic_flops_per_frame"] * B * T
+        extras["mel_with_stft"] = {
+            "ms": round(ms, 4),
+            "gsamples_per_s": round(B * L / ms / 1e6, 4),
+            "algorithmic_tflops": round(alg / ms / 1e9, 3),
+            "mfma_frac": round(alg / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+            "mfma_peak_tflops": PEAK_FP32_MFMA_TFLOPS,
+        }
+        del o_lin, ws, x3, o_1992, o_mel2, p_mel2
         # backward pass of the STFT layer (trainable kernels): dLoss/dW and dLoss/dx for the same batch.
         # Algorithmic work: the forward contraction again (2 N^2 per frame) + the bank gradient (2 N^2)
         # + the waveform gradient (2 N^2) = 6 N^2 flop per frame.

@@ -222,6 +222,14 @@ nna_status nna_stft(const nna_plan* plan, const float* x_dev, long long B, long 
 nna_status nna_mel(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
                    void* hip_stream);
 
+/* nna_mel that also hands out the spectrogram its filterbank is applied to (Fig. 3: the STFT layer's
+ * output feeding the Mel layer), from the one contraction: mel_dev[B, n_mels, T] as nna_mel writes it and
+ * spec_dev[B, n_fft/2+1, T] = |X|^power (power 2: the power spectrogram; power 1: the magnitude).  For a
+ * caller that wants both, this is one kernel launch of nna_mel's cost plus the spectrogram's stores.
+ * Plan from nna_plan_mel (float32); errors as nna_mel, NNA_ERR_INVALID_ARG for a NULL spec_dev. */
+nna_status nna_mel_with_stft(const nna_plan* plan, const float* x_dev, long long B, long long L,
+                             float* mel_dev, float* spec_dev, void* hip_stream);
+
 /* out_dev[B, n_bins, T] = constant-Q spectrogram of x_dev[B, L]; plan from nna_plan_cqt. */
 nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
                    void* hip_stream);

@@ -31,7 +31,7 @@ EXPORTS = [
     "nna_plan_cqt2010", "nna_cqt2010",
     "nna_plan_get_mel_weights", "nna_plan_set_mel_weights", "nna_mel_backward_workspace", "nna_mel_backward",
     "nna_plan_trainable", "nna_plan_get_bank", "nna_plan_set_bank", "nna_stft_backward_workspace", "nna_stft_backward",
-    "nna_cqt_backward_workspace", "nna_cqt_backward",
+    "nna_cqt_backward_workspace", "nna_cqt_backward", "nna_mel_with_stft",
     "nna_plan_destroy",
     "nna_status_str", "nna_last_error",
 ]
@@ -97,6 +97,7 @@ def lib():
         L.nna_stft_backward.argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _VP, _VP, _c.c_size_t, _VP]
         L.nna_cqt_backward_workspace.argtypes = [_VP, _LL, _LL, _c.POINTER(_c.c_size_t)]
         L.nna_cqt_backward.argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _VP, _VP, _c.c_size_t, _VP]
+        L.nna_mel_with_stft.argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _VP]
         L.nna_out_shape.argtypes = [_VP, _LL, _LL, _c.POINTER(_LL), _c.POINTER(_LL)]
         for name in ("nna_stft", "nna_mel", "nna_cqt", "nna_cqt1992"):
             getattr(L, name).argtypes = [_VP, _VP, _LL, _LL, _VP, _VP]
@@ -322,6 +323,30 @@ def nna_stft(plan: Plan, x, out=None, stream=None):
 def nna_mel(plan: Plan, x, out=None, stream=None):
     """out[B, n_mels, T] = Mel spectrogram of x[B, L]."""
     return _run(lib().nna_mel, plan, x, out, stream)
+
+
+def nna_mel_with_stft(plan: Plan, x, out=None, spec=None, stream=None):
+    """(mel[B, n_mels, T], spec[B, n_fft/2+1, T]) from one contraction: the Mel spectrogram and the |X|^power
+    spectrogram its filterbank is applied to."""
+    import torch
+
+    F = plan.info()["bank_rows"] // 2
+    cfn = lib().nna_mel_with_stft
+    holder = {}
+
+    def fn(handle, xp, B, L, op, st):
+        T = nna_out_shape(plan, B, L)[1]
+        sp = spec
+        if sp is None:
+            sp = torch.empty((B, F, T), dtype=torch.float32, device=x.device)
+        elif not (sp.is_cuda and sp.dtype == torch.float32 and sp.is_contiguous() and tuple(sp.shape) == (B, F, T)
+                  and sp.device == x.device):
+            raise TypeError(f"spec must be a contiguous float32 CUDA tensor of shape {(B, F, T)}")
+        holder["spec"] = sp
+        return cfn(handle, xp, B, L, op, sp.data_ptr(), st)
+
+    mel = _run(fn, plan, x, out, stream)
+    return mel, holder["spec"]
 
 
 def nna_cqt1992(plan: Plan, x, out=None, stream=None):

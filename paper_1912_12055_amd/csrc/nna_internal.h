@@ -27,6 +27,7 @@ constexpr int ST_MODE_STFT = 0;   // per-bin epilogue, output written per row ti
 constexpr int ST_MODE_MEL = 1;    // power (or magnitude) of the row tile x filterbank slice -> 128 mel accumulators
 constexpr int ST_MODE_GRAD = 3;   // backward pass: dLoss/d(row tile) from the upstream gradient, written to a buffer
 constexpr int ST_MODE_CPLX = 4;   // the row tile itself (Re, Im rows) or its phase is the output
+constexpr int ST_MODE_MELSPEC = 5;  // ST_MODE_MEL that also writes the spectrogram the filterbank is applied to (to `pout`)
 constexpr int ST_MODE_LIN = 2;    // the (Re, Im) rows themselves x a real matrix slice -> 128 output rows = 64
                                   // complex bins (constant-Q transform with frequency-domain kernels)
 

@@ -45,7 +45,8 @@ constexpr int ST_RING_MEL = 2;   // fewer in the Mel variant: its 64 extra accum
 template <int MODE, int RING>
 __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
   static_assert(ST_NKG % RING == 0, "ring depth must divide the fragment groups per LDS row");
-  constexpr bool MEL = MODE == ST_MODE_MEL || MODE == ST_MODE_LIN;  // a second contraction follows every row tile
+  constexpr bool MEL = MODE == ST_MODE_MEL || MODE == ST_MODE_LIN || MODE == ST_MODE_MELSPEC;  // a second contraction follows every row tile
+  constexpr bool SPEC = MODE == ST_MODE_MELSPEC;  // ... and the spectrogram itself is an output too
   constexpr bool LIN = MODE == ST_MODE_LIN;
   constexpr bool GRAD = MODE == ST_MODE_GRAD;  // backward pass: the row tile becomes dLoss/dC
   constexpr bool CPLX = MODE == ST_MODE_CPLX;  // complex or phase output
@@ -63,6 +64,10 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
     pass = (int)(blockIdx.x % P.n_pass);
     rt_begin = P.mel_pass_rt[2 * pass];
     rt_end = P.mel_pass_rt[2 * pass + 1];
+    if (SPEC && pass == 0) {  // the spectrogram needs every row tile, also those no filter touches
+      rt_begin = 0;
+      rt_end = P.n_rt;
+    }
   } else {
     // XCD-aware order: workgroup ids are dealt round-robin to the 8 XCDs.  Each XCD walks its
     // own contiguous range of frame tiles in groups of 64; inside a group the row group (ST_RG
@@ -303,6 +308,15 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
             }
           }
         } else {
+        if constexpr (SPEC) {
+          if (valid && pass == 0) {
+            float* __restrict__ sp = P.pout + (b_lane * (P.n_half + 1)) * g.T + t_lane;
+            if (P.fmt == 1)
+              stft_store_tile<NNA_OUT_MAGNITUDE>(acc, sp, g.T, slot_base, h, P.n_half, P.packed);
+            else
+              stft_store_tile<NNA_OUT_POWER>(acc, sp, g.T, slot_base, h, P.n_half, P.packed);
+          }
+        }
         const float4* __restrict__ wp =
             P.melw + (((long long)pass * P.n_rt + rt) * ST_RB) * (ST_MEL_BLOCKS * 2 * 64) + lane;
 #pragma unroll
@@ -735,7 +749,8 @@ hipError_t kernels_init() {
 
 hipError_t launch_stft(const StftParams& p, int mode, hipStream_t stream) {
   long long blocks;
-  const bool mel = mode == ST_MODE_MEL || mode == ST_MODE_LIN;
+  const bool mel = mode == ST_MODE_MEL || mode == ST_MODE_LIN || mode == ST_MODE_MELSPEC;
+  if (mode == ST_MODE_MELSPEC && !p.pout) return hipErrorInvalidValue;
   if (mel) {
     blocks = p.n_ft * p.n_pass;
   } else {
@@ -748,6 +763,8 @@ hipError_t launch_stft(const StftParams& p, int mode, hipStream_t stream) {
     hipLaunchKernelGGL((stft_kernel<ST_MODE_LIN, ST_RING_MEL>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   else if (mode == ST_MODE_MEL)
     hipLaunchKernelGGL((stft_kernel<ST_MODE_MEL, ST_RING_MEL>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  else if (mode == ST_MODE_MELSPEC)
+    hipLaunchKernelGGL((stft_kernel<ST_MODE_MELSPEC, ST_RING_MEL>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   else if (mode == ST_MODE_GRAD)
     hipLaunchKernelGGL((stft_kernel<ST_MODE_GRAD, ST_RING_STFT>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   else if (mode == ST_MODE_CPLX)

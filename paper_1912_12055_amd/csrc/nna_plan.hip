@@ -867,7 +867,7 @@ nna::FrameGeom make_geom(const nna_plan* p, const float* x, long long B, long lo
 // caller).  out_wave_stride / bin_offset place a two-stage CQT plan's bins inside a larger output
 // (octave of a downsampling plan); 0 / 0 = the plan's own [B, bins, T].
 nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long long B, long long L, long long T,
-                         float* out, long long out_wave_stride, int bin_offset, void* stream) {
+                         float* out, long long out_wave_stride, int bin_offset, void* stream, float* spec_out = nullptr) {
   if (plan->precision == NNA_PREC_F16) {
     const int M = pick_tile_frames(nna::H_FRAMES, T, plan->nj - 1, nna::H_LB_ROWS);
     if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
@@ -934,7 +934,8 @@ nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long lo
   DeviceGuard guard;
   hipError_t e = guard.enter(plan->device);
   if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
-  const int mode = kind == NNA_KIND_MEL       ? nna::ST_MODE_MEL
+  P.pout = spec_out;
+  const int mode = kind == NNA_KIND_MEL       ? (spec_out ? nna::ST_MODE_MELSPEC : nna::ST_MODE_MEL)
                    : kind == NNA_KIND_CQT1992 ? nna::ST_MODE_LIN
                    : (plan->fmt == NNA_OUT_COMPLEX || plan->fmt == NNA_OUT_PHASE) ? nna::ST_MODE_CPLX
                                                                                   : nna::ST_MODE_STFT;
@@ -1592,6 +1593,16 @@ nna_status nna_stft(const nna_plan* plan, const float* x_dev, long long B, long 
 
 nna_status nna_mel(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev, void* hip_stream) {
   return run_stft_like(plan, NNA_KIND_MEL, x_dev, B, L, out_dev, hip_stream);
+}
+
+nna_status nna_mel_with_stft(const nna_plan* plan, const float* x_dev, long long B, long long L, float* mel_dev,
+                             float* spec_dev, void* hip_stream) {
+  if (!spec_dev) return fail(NNA_ERR_INVALID_ARG, "spec_dev is NULL");
+  long long T = 0;
+  nna_status s = check_call(plan, NNA_KIND_MEL, x_dev, B, L, mel_dev, &T);
+  if (s != NNA_OK) return s;
+  if (plan->precision != NNA_PREC_F32) return fail(NNA_ERR_UNSUPPORTED, "float32 plans only");
+  return run_stft_core(plan, NNA_KIND_MEL, x_dev, B, L, T, mel_dev, 0, 0, hip_stream, spec_dev);
 }
 
 nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev, void* hip_stream) {

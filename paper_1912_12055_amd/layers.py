@@ -153,8 +153,14 @@ class MelSpectrogram(_Trainable):
             self.mel_basis = torch.nn.Parameter(nb.nna_plan_get_mel_weights(self.plan), requires_grad=bool(trainable_mel))
             self.wsin_wcos = torch.nn.Parameter(nb.nna_plan_get_bank(self.plan), requires_grad=bool(trainable_STFT))
 
-    def forward(self, x):
+    def forward(self, x, return_spectrogram=False):
+        """``return_spectrogram=True`` returns (mel, |X|^power) from the one launch (not differentiable)."""
         x = _as_batch(x)
+        if self.trainable:
+            self._sync(self.wsin_wcos, nb.nna_plan_set_bank, "bank")
+            self._sync(self.mel_basis, nb.nna_plan_set_mel_weights, "mel")
+        if return_spectrogram:
+            return nb.nna_mel_with_stft(self.plan, x.detach())
         if not self.trainable:
             return nb.nna_mel(self.plan, x)
         self._sync(self.wsin_wcos, nb.nna_plan_set_bank, "bank")

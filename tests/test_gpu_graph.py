@@ -37,6 +37,8 @@ def test_forward_and_backward_calls_replay_from_a_graph(nb):
     p_fd = nb.nna_plan_cqt2010(sr=16000, hop=128, fmin=110.0, n_bins=48, device=0)
     outs = {k: torch.empty((B,) + nb.nna_out_shape(p, B, L), device=dev)
             for k, p in (("stft", p_stft), ("mel", p_mel), ("cqt", p_cqt), ("v2", p_v2), ("fd", p_fd))}
+    outs["mel2"] = torch.empty_like(outs["mel"])
+    outs["spec"] = torch.empty_like(outs["stft"])
     ws_v2 = torch.empty(max(16, nb.nna_cqt2010v2_workspace(p_v2, B, L)), dtype=torch.uint8, device=dev)
     ws_fd = torch.empty(max(16, nb.nna_cqt2010v2_workspace(p_fd, B, L)), dtype=torch.uint8, device=dev)
     ws_bw = torch.empty(nb.nna_stft_backward_workspace(p_stft, B, L), dtype=torch.uint8, device=dev)
@@ -52,6 +54,7 @@ def test_forward_and_backward_calls_replay_from_a_graph(nb):
     def run_all():
         nb.nna_stft(p_stft, x, outs["stft"])
         nb.nna_mel(p_mel, x, outs["mel"])
+        nb.nna_mel_with_stft(p_mel, x, outs["mel2"], outs["spec"])
         nb.nna_cqt(p_cqt, x, outs["cqt"])
         nb.nna_cqt2010v2(p_v2, x, outs["v2"], workspace=ws_v2)
         nb.nna_cqt2010(p_fd, x, outs["fd"], workspace=ws_fd)

@@ -49,6 +49,8 @@ def test_layers_with_the_papers_defaults_match_the_oracle(layers):
     re, im = oracle.cqt_complex(x)
     assert _err(layers.CQT1992v2(output_format="Complex")(xd), oracle.interleave(re, im)) < TOL
     assert layers.STFT()(xd[0]).shape == (1, 1025, 44)  # a single waveform
+    mel, spec = layers.MelSpectrogram()(xd, return_spectrogram=True)
+    assert _err(mel, oracle.mel(x)) < TOL and _err(spec, oracle.stft(x, fmt=oracle.POWER)) < TOL
     with pytest.raises(NotImplementedError):
         layers.CQT2010v2(trainable=True)
     with pytest.raises(ValueError):

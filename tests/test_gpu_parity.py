@@ -663,6 +663,15 @@ def test_mel_config4_full_sampled(nb, batch4):
     _say(f"  rel err {e:.3e}")
     assert e < TOL
     assert torch.isfinite(out).all() and (out >= 0).all()
+    # the same batch through the launch that also writes the power spectrogram: the same Mel output, bit for
+    # bit, and the spectrogram the oracle's STFT gives
+    _say("mel + spectrogram in one launch, config 4")
+    mel2, spec = nb.nna_mel_with_stft(plan, batch4)
+    torch.cuda.synchronize()
+    assert torch.equal(mel2, out)
+    e = _rel_err(spec[SAMPLED].cpu().numpy(), oracle.stft(xs, n_fft=2048, hop=512, fmt=oracle.POWER))
+    _say(f"  spectrogram rel err {e:.3e}")
+    assert e < TOL and torch.isfinite(spec).all()
 
 
 def test_cqt_config5_full_sampled(nb):
@@ -806,3 +815,32 @@ def test_sweeps_impulses_and_a_chromatic_scale_through_every_layer(nb):
         errs = [np.abs(got[b] - ref[b]).max() / np.abs(ref[b]).max() for b in range(ref.shape[0])]
         _say(f"  {name}: " + ", ".join(f"{e:.2e}" for e in errs))
         assert max(errs) < TOL, (name, errs)
+
+
+# ---- Mel and its spectrogram from one launch --------------------------------------------------------
+MEL_STFT_CASES = [
+    # name, B, L, sr, n_fft, hop, n_mels, fmin, fmax, power
+    ("power, 128 mels", 3, 20000, 22050, 2048, 512, 128, 0.0, 0.0, 2.0),
+    ("magnitude, filters that stop below Nyquist (upper row tiles untouched by them)", 2, 9000, 22050, 1024, 256, 40, 100.0, 3000.0, 1.0),
+    ("more than 128 mels: two passes", 2, 12000, 22050, 2048, 512, 200, 0.0, 0.0, 2.0),
+    ("many short waveforms, ragged tiles", 37, 1500, 8000, 256, 64, 20, 0.0, 0.0, 2.0),
+]
+
+
+@pytest.mark.parametrize("case", MEL_STFT_CASES, ids=[c[0] for c in MEL_STFT_CASES])
+def test_mel_with_stft_parity(nb, case):
+    name, B, L, sr, n_fft, hop, n_mels, fmin, fmax, power = case
+    _say(f"mel + spectrogram in one launch: {name}")
+    x = signals.batch(2, B=B, L=L, sr=sr)
+    plan = nb.nna_plan_mel(sr=sr, n_fft=n_fft, hop=hop, n_mels=n_mels, fmin=fmin, fmax=fmax, power=power, device=0)
+    mel, spec = nb.nna_mel_with_stft(plan, _dev(x))
+    ref_mel = oracle.mel(x, sr=sr, n_fft=n_fft, hop=hop, n_mels=n_mels, fmin=fmin, fmax=fmax, power=power)
+    ref_spec = oracle.stft(x, n_fft=n_fft, hop=hop, fmt=oracle.POWER if power == 2.0 else oracle.MAGNITUDE)
+    e_m, e_s = _rel_err(mel.cpu().numpy(), ref_mel), _rel_err(spec.cpu().numpy(), ref_spec)
+    _say(f"  mel {e_m:.2e}, spectrogram {e_s:.2e}")
+    assert e_m < TOL and e_s < TOL
+    # the Mel output is the one nna_mel writes, bit for bit
+    import torch
+    assert torch.equal(mel, nb.nna_mel(plan, _dev(x)))
+    with pytest.raises(nb.NnaError):
+        nb.nna_mel_with_stft(nb.nna_plan_stft(n_fft=n_fft, hop=hop, device=0), _dev(x))
