@@ -47,7 +47,10 @@ constexpr int CQ_KC = 16;         // taps per LDS chunk = taps per bank fragment
 #endif
 constexpr int CQ_PITCH = NNA_CQ_PITCH;
 constexpr int CQ_LDS_ROWS_MAX = 512;
-constexpr int CQ_PREFETCH = 4;    // bank fragments in flight per wave
+#ifndef NNA_CQ_PREFETCH
+#define NNA_CQ_PREFETCH 4
+#endif
+constexpr int CQ_PREFETCH = NNA_CQ_PREFETCH;  // bank fragments in flight per wave
 
 // How frames map onto the batch of waveforms.
 struct FrameGeom {

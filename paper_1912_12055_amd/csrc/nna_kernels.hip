@@ -17,6 +17,7 @@
 #include "nna_device.h"
 
 #include <type_traits>
+#include <utility>
 
 namespace nna {
 
@@ -416,6 +417,12 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
 constexpr int CQ_RPP = 256 / (CQ_KC / 4);            // LDS rows written per loader pass (64)
 constexpr int CQ_NPASS = CQ_LDS_ROWS_MAX / CQ_RPP;  // 512 / 64 = 8
 
+// fn(integral_constant<int, 0>), fn(integral_constant<int, 1>), ...: a loop whose index is a compile-time constant
+template <typename F, int... S>
+__device__ __forceinline__ void for_each_index(F&& fn, std::integer_sequence<int, S...>) {
+  (fn(std::integral_constant<int, S>{}), ...);
+}
+
 // GRAD: instead of the spectrogram the kernel writes G = dLoss/dC, the derivative of the output format
 // applied to the upstream gradient, in the blocked layout the backward contractions read.
 template <bool GRAD>
@@ -576,16 +583,12 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
 #pragma unroll
       for (int fb = 0; fb < 4; ++fb) a_cur[fb] = a_nxt[fb];
     };
-    static_assert(CQ_PREFETCH == 4 && CQ_NPASS == 8 && CQ_ITEM_RB == 4, "the group sequences below assume these");
-    using S0 = std::integral_constant<int, 0>;
-    using S1 = std::integral_constant<int, 1>;
-    using S2 = std::integral_constant<int, 2>;
-    using S3 = std::integral_constant<int, 3>;
+    static_assert(CQ_PREFETCH >= 2 && CQ_NPASS == 8 && CQ_ITEM_RB == 4, "the group sequences below assume these");
     using TNone = std::integral_constant<int, TASK_NONE>;
     using TStore = std::integral_constant<int, TASK_STORE>;
     using TLoad = std::integral_constant<int, TASK_LOAD>;
     // all fragment groups of row block R_ in this chunk: nj of them, the first nr real, the rest
-    // padding; the item's first row block (always present, >= 4 groups) carries the staging tasks in
+    // padding; the item's first row block (always present, >= one ring of groups) carries the staging tasks in
     // its first two groups
     auto row_block = [&](auto rb_tag) {
       constexpr int R_ = decltype(rb_tag)::value;
@@ -594,26 +597,25 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
       const float* base = cur + joff[R_] * CQ_PITCH;
 #pragma unroll
       for (int fb = 0; fb < 4; ++fb) a_cur[fb] = *reinterpret_cast<const f32x4*>(base + a_off[fb]);
+      // the ring's slots in order, each with its compile-time index
+      auto ring = [&](auto&& fn) { for_each_index(fn, std::make_integer_sequence<int, CQ_PREFETCH>{}); };
       int jj = 0;
       if (R_ == 0) {
-        group(rb_tag, TStore{}, S0{}, base, 0, nj, true);
-        group(rb_tag, TLoad{}, S1{}, base, 1, nj, true);
-        group(rb_tag, TNone{}, S2{}, base, 2, nj, 2 < nr);
-        group(rb_tag, TNone{}, S3{}, base, 3, nj, 3 < nr);
-        jj = 4;
+        ring([&](auto s) {
+          constexpr int S = decltype(s)::value;
+          if constexpr (S == 0)
+            group(rb_tag, TStore{}, s, base, 0, nj, true);
+          else if constexpr (S == 1)
+            group(rb_tag, TLoad{}, s, base, 1, nj, true);
+          else
+            group(rb_tag, TNone{}, s, base, S, nj, S < nr);
+        });
+        jj = CQ_PREFETCH;
       }
-      for (; jj + 4 <= nr; jj += 4) {
-        group(rb_tag, TNone{}, S0{}, base, jj, nj, true);
-        group(rb_tag, TNone{}, S1{}, base, jj + 1, nj, true);
-        group(rb_tag, TNone{}, S2{}, base, jj + 2, nj, true);
-        group(rb_tag, TNone{}, S3{}, base, jj + 3, nj, true);
-      }
-      if (jj < nj) {  // the last quad: 1..3 real groups, then padding
-        group(rb_tag, TNone{}, S0{}, base, jj, nj, jj < nr);
-        group(rb_tag, TNone{}, S1{}, base, jj + 1, nj, jj + 1 < nr);
-        group(rb_tag, TNone{}, S2{}, base, jj + 2, nj, jj + 2 < nr);
-        group(rb_tag, TNone{}, S3{}, base, jj + 3, nj, false);
-      }
+      for (; jj + CQ_PREFETCH <= nr; jj += CQ_PREFETCH)
+        ring([&](auto s) { group(rb_tag, TNone{}, s, base, jj + decltype(s)::value, nj, true); });
+      if (jj < nj)  // the last ring: some real groups, then padding
+        ring([&](auto s) { group(rb_tag, TNone{}, s, base, jj + decltype(s)::value, nj, jj + decltype(s)::value < nr); });
     };
     row_block(std::integral_constant<int, 0>{});
     row_block(std::integral_constant<int, 1>{});

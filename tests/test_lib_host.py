@@ -338,3 +338,14 @@ def test_complex_and_phase_formats_shapes_and_where_they_exist():
                    (nb.nna_plan_stft_prec, dict(precision=nb.NNA_PREC_F16))):
         assert _status(fn, fmt=nb.NNA_OUT_COMPLEX, device=-1, **kw) == nb.NNA_ERR_UNSUPPORTED, fn
     assert _status(nb.nna_plan_stft, fmt=5, device=-1) == nb.NNA_ERR_INVALID_ARG
+
+
+def test_bench_refuses_more_than_one_gpu_and_has_no_cpu_fallback():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr and not r.stdout.strip()
+    import torch
+    if not torch.cuda.is_available():
+        r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")], capture_output=True, text=True)
+        assert r.returncode != 0 and "no CPU fallback" in r.stderr and not r.stdout.strip()
