@@ -322,12 +322,14 @@ CQT_BACKWARD_CASES = [
     ("odd-bins-ragged-taps", 8000, 300.0, 19, 8, 32, 600, 2, 2000, oracle.MAGNITUDE),
     ("two-row-tiles-84-bins", 22050, 32.70, 84, 12, 512, 0, 2, 12000, oracle.MAGNITUDE),
     ("three-row-tiles-short-waveforms", 16000, 100.0, 150, 24, 256, 0, 40, 5000, oracle.POWER),
+    ("512-hop-shifts-several-windows-per-row-chunk", 8000, 100.0, 12, 12, 4, 0, 2, 3000, oracle.MAGNITUDE),
+    ("no-centring", 8000, 220.0, 30, 12, 64, 0, 3, 5000, oracle.MAGNITUDE, False),
 ]
 
 
-def _cqt_plan(nb, sr, fmin, n_bins, bpo, hop, n_taps, fmt):
+def _cqt_plan(nb, sr, fmin, n_bins, bpo, hop, n_taps, fmt, center=True):
     return nb.nna_plan_trainable(nb.nna_plan_cqt(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo,
-                                                 n_taps=n_taps, fmt=fmt, device=0))
+                                                 n_taps=n_taps, fmt=fmt, center=center, device=0))
 
 
 def test_cqt_get_bank_is_the_oracles_bank_and_set_bank_masks(nb):
@@ -357,9 +359,10 @@ def test_cqt_get_bank_is_the_oracles_bank_and_set_bank_masks(nb):
 @pytest.mark.parametrize("case", CQT_BACKWARD_CASES, ids=[c[0] for c in CQT_BACKWARD_CASES])
 def test_cqt_backward_parity_small(nb, case):
     import torch
-    name, sr, fmin, n_bins, bpo, hop, n_taps, B, L, fmt = case
+    name, sr, fmin, n_bins, bpo, hop, n_taps, B, L, fmt = case[:10]
+    center = case[10] if len(case) > 10 else True
     _say(f"cqt backward {name}: sr={sr} bins={n_bins} hop={hop} taps={n_taps} B={B} L={L} fmt={fmt}")
-    plan = _cqt_plan(nb, sr, fmin, n_bins, bpo, hop, n_taps, fmt)
+    plan = _cqt_plan(nb, sr, fmin, n_bins, bpo, hop, n_taps, fmt, center)
     _, mask = oracle.cqt_bank(sr, fmin, n_bins, bpo, n_taps=n_taps)
     rng = np.random.default_rng(11)
     W = nb.nna_plan_get_bank(plan).cpu().numpy()
@@ -367,9 +370,9 @@ def test_cqt_backward_parity_small(nb, case):
     nb.nna_plan_set_bank(plan, _dev(W))
     x = _rand(B, L, 12)
     out = nb.nna_cqt(plan, _dev(x))
-    ref_out = oracle.stft_bank(x, W, hop=hop, fmt=fmt)
+    ref_out = oracle.stft_bank(x, W, hop=hop, center=center, fmt=fmt)
     gout = rng.standard_normal(ref_out.shape).astype(np.float32)
-    ref_gw, ref_gx = oracle.cqt_bank_backward(x, W, mask, gout, hop=hop, fmt=fmt)
+    ref_gw, ref_gx = oracle.cqt_bank_backward(x, W, mask, gout, hop=hop, center=center, fmt=fmt)
     gw, gx = nb.nna_cqt_backward(plan, _dev(x), _dev(gout))
     torch.cuda.synchronize()
     if fmt != oracle.PHASE:
