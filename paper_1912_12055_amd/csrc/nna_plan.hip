@@ -1701,6 +1701,8 @@ static nna_status make_cqt_trainable(nna_plan* plan) {
         tiles.push_back(make_int2(mt | (alive << 16), (int)nt));
       }
     }
+    // heaviest tiles first (a tile's time goes with its live row blocks): the light ones fill the launch's tail
+    std::stable_sort(tiles.begin(), tiles.end(), [](const int2& a, const int2& b) { return (a.x >> 16) > (b.x >> 16); });
     // waveform gradient: how many rows (in chunks of 32; rows are ordered longest first) hold taps on each
     // 128-tap tile, and from that, per 128-column tile of the hop, the running count over the hop-shifts
     for (int nt = 0; nt < n_nt; ++nt) {

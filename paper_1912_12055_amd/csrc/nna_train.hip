@@ -212,7 +212,8 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
       // A: G[m0 + row][32 c + 4 c4], row = tid/8 + 32 p: the tile is one contiguous run of frame block c
       const float* ap = P.gbuf + c * ((long long)P.rows_pad * 32) + (m0 + (tid >> 3)) * 32 + 4 * (tid & 7);
 #pragma unroll
-      for (int p = 0; p < 4; ++p) ra[p] = *reinterpret_cast<const f32x4*>(ap + 32 * 32 * p);
+      for (int p = 0; p < 4; ++p)
+        if (p < alive) ra[p] = *reinterpret_cast<const f32x4*>(ap + 32 * 32 * p);  // pass p = row block p
       // B: taps n0.. of the 32 frames f0.., gathered from the mirrored waveforms (one LDS row per frame)
       // Almost every window lies inside its waveform: then the four samples are loaded as they are
       // stored.  Only a wave that touches a mirrored edge takes the forward kernels' general loader.
@@ -264,7 +265,8 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
     if constexpr (MODE == BW_MODE_BANK) {
       float* a = &ldsA[buf][(tid >> 3) * BW_PA_M + 4 * (tid & 7)];
 #pragma unroll
-      for (int p = 0; p < 4; ++p) *reinterpret_cast<f32x4*>(a + 32 * p * BW_PA_M) = ra[p];
+      for (int p = 0; p < 4; ++p)
+        if (p < alive) *reinterpret_cast<f32x4*>(a + 32 * p * BW_PA_M) = ra[p];
       if (fast) {
         float* b = &ldsB[buf][(tid >> 5) * BW_PK + 4 * (tid & 31)];
 #pragma unroll
