@@ -1,5 +1,5 @@
-// Backward pass of the STFT layer with trainable Fourier kernels (arXiv 1912.12055, Sec. IV-C
-// "Trainable Transformation Kernels") on gfx950 / CDNA4.
+// Backward pass of the layers with trainable kernels -- STFT, Mel, one-rate constant-Q -- (arXiv
+// 1912.12055, Sec. IV-C "Trainable Transformation Kernels") on gfx950 / CDNA4.
 //
 // Forward:  C[r, f] = sum_n W[r, n] xp[f hop + n]  (r = packed bank row, f = global frame), then the
 // output format per (Re, Im) pair.  Given the upstream gradient, the STFT kernel's gradient mode
@@ -10,7 +10,8 @@
 //                                                              (frames x taps, over bank rows)
 //
 // Both are dense GEMMs on v_mfma_f32_32x32x2_f32 with one kernel: a 128 x 128 output tile per
-// workgroup (4 waves in a 2 x 2 grid, 64 x 64 = four 32 x 32 accumulators each), the contraction
+// workgroup (4 waves, four 32 x 32 accumulators each: 2 x 2 waves of 64 x 64 for the waveform gradient,
+// 4 waves of 128 rows x 32 taps for the bank gradient), the contraction
 // staged through LDS in chunks of 32 (double buffered, one barrier per chunk), two workgroups per
 // compute unit.  The B operand is always stored k-major in LDS ([k][column], read with 4-byte LDS
 // loads: at the float32 MFMA rate LDS bandwidth is nowhere near a limit); the A operand is m-major
@@ -19,6 +20,10 @@
 // register run along the output's contiguous axis (taps) in both, so the final atomic adds go out
 // in 128-byte runs.  The bank gradient's B operand is the frames matrix, never built: the framing
 // loader of the forward kernels gathers 32 frames x 128 taps per chunk, reflection included.
+//
+// A constant-Q bank (rows zero outside a tap range each, hundreds of hop-shifts) uses the same bank-gradient
+// kernel restricted to the output tiles and 32-row blocks that hold taps, and a waveform-gradient kernel of
+// its own (cq_wave_kernel, below).  The Mel layer's two small contractions are at the end of the file.
 //
 // Sums that meet in memory -- the split contraction of the bank gradient, the overlapping frames
 // and mirrored edge samples of the waveform gradient -- are combined with float atomic adds on
