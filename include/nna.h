@@ -171,6 +171,9 @@ nna_status nna_plan_cqt(nna_plan** plan, int sr, int hop, double fmin, int n_bin
  *   n_taps     0 = next power of two >= the longest top-octave kernel; else even and >= it
  *   fir_taps   0 = 257; else odd, 3..4095 (the paper gives no tap count)
  * Output bins = n_bins, lowest frequency first.
+ * Waveform length: with l_0 = L, l_(a+1) = ceil(l_a / 2), every octave needs l_a > n_taps/2 (its mirror
+ * reflection) and every octave but the lowest l_a >= fir_taps + 126 rounded up to a multiple of 128 (one
+ * whole frame of the filter stage, 64 outputs: 384 samples for 257 taps); else NNA_ERR_SHAPE.
  */
 nna_status nna_plan_cqt2010v2(nna_plan** plan, int sr, int hop, double fmin, int n_bins, int bins_per_octave,
                               nna_window win, int n_taps, int fir_taps, nna_output fmt, int device);

@@ -1508,7 +1508,7 @@ static nna_status run_octaves(const nna_plan* plan, int kind, const float* x_dev
   if (B < 1) return fail(NNA_ERR_SHAPE, "B must be >= 1");
   std::vector<long long> La;
   if (L < 1 || !cqt2010_lengths(plan, L, La))
-    return fail(NNA_ERR_SHAPE, "L is too short: every octave's waveform must exceed the reflection padding");
+    return fail(NNA_ERR_SHAPE, "L is too short: every octave's waveform must exceed the reflection padding, and all but the lowest hold one frame of the decimation filter");
   const long long T = 1 + L / plan->hop;
   if (T > 0x7fffffffLL / 4 || L > 0x7fffffffLL - 4LL * plan->K - 64 || B > 0x7fffffffLL || B > (1LL << 40) / T)
     return fail(NNA_ERR_SHAPE, "batch too large");
@@ -1575,7 +1575,7 @@ nna_status nna_out_shape(const nna_plan* plan, long long B, long long L, long lo
   if (plan->kind == NNA_KIND_CQT2010V2 || plan->kind == NNA_KIND_CQT2010) {
     std::vector<long long> La;
     if (L < 1 || !cqt2010_lengths(plan, L, La))
-      return fail(NNA_ERR_SHAPE, "L is too short: every octave's waveform must exceed the reflection padding");
+      return fail(NNA_ERR_SHAPE, "L is too short: every octave's waveform must exceed the reflection padding, and all but the lowest hold one frame of the decimation filter");
     if (n_bins) *n_bins = plan->n_bins;
     if (n_frames) *n_frames = 1 + L / plan->hop;
     return NNA_OK;
