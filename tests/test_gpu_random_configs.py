@@ -175,3 +175,69 @@ def test_random_backward(nb, seed):
         got = got.cpu().numpy().astype(np.float64)
         e = np.abs(got - ref).max() / np.abs(ref).max()
         assert e < (1e-2 if fmt in (2, 4) else TOL), (name, e)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_cqt_and_mel_backward(nb, seed):
+    import torch
+    rng = np.random.default_rng([17, seed])
+    # constant-Q layer with trainable kernels
+    sr = int(rng.choice([8000, 16000]))
+    bpo = int(rng.choice([6, 12, 17]))
+    n_bins = int(rng.integers(3, 4 * bpo))
+    top = 0.4 * sr
+    fmin = float(top / 2.0 ** ((n_bins - 1) / bpo) * rng.uniform(0.6, 1.0))
+    hop = int(rng.choice([4, 16, 25, 32, 64, 100, 128, 256]))
+    center = bool(rng.integers(0, 2))
+    fmt = int(rng.integers(0, 5))
+    taps = oracle.cqt_default_taps(sr, fmin, bpo)
+    if rng.integers(0, 2):
+        Nk, _ = oracle.cqt_lengths(sr, fmin, n_bins, bpo)
+        taps = int(Nk[0]) + int(Nk[0]) % 2 + 2 * int(rng.integers(0, 40))   # ragged, even, >= the longest kernel
+    B = int(rng.choice([1, 2, 6]))
+    L = (taps // 2 + 1 if center else taps) + int(rng.integers(0, 30)) * hop + int(rng.integers(0, hop))
+    _say(f"random cqt backward seed={seed}: sr={sr} fmin={fmin:.1f} bins={n_bins} bpo={bpo} hop={hop} taps={taps} "
+         f"center={center} fmt={fmt} B={B} L={L}")
+    x = _wave(rng, B, L)
+    plan = nb.nna_plan_trainable(nb.nna_plan_cqt(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo,
+                                                 n_taps=taps, center=center, fmt=fmt, device=0))
+    _, mask = oracle.cqt_bank(sr, fmin, n_bins, bpo, n_taps=taps)
+    W = nb.nna_plan_get_bank(plan).cpu().numpy()
+    W = np.where(mask, W * (1.0 + 0.1 * rng.standard_normal(W.shape)), 0).astype(np.float32)
+    nb.nna_plan_set_bank(plan, _dev(W))
+    gout = rng.standard_normal(oracle.stft_bank(x, W, hop=hop, center=center, fmt=fmt).shape).astype(np.float32)
+    ref_gw, ref_gx = oracle.cqt_bank_backward(x, W, mask, gout, hop=hop, center=center, fmt=fmt)
+    gw, gx = nb.nna_cqt_backward(plan, _dev(x), _dev(gout))
+    torch.cuda.synchronize()
+    tol = 1e-2 if fmt in (2, 4) else TOL   # log and phase divide by the power: ill-conditioned where it is small
+    for got, ref, name in ((gw, ref_gw, "bank"), (gx, ref_gx, "waveform")):
+        got = got.cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(got))
+        e = np.abs(got - ref).max() / np.abs(ref).max()
+        assert e < tol, (name, e)
+    assert not gw.cpu().numpy()[~mask].any()
+
+    # Mel layer with both stages trainable
+    n_fft = int(rng.choice([128, 200, 256, 512]))
+    hop = int(rng.choice([d for d in (16, 25, 32, 64, 128) if d <= n_fft]))
+    n_mels = int(rng.choice([8, 20, 40]))
+    n_mels = min(n_mels, n_fft // 8)
+    power = float(rng.choice([1.0, 2.0]))
+    L = n_fft + int(rng.integers(1, 30)) * hop + int(rng.integers(0, hop))
+    _say(f"  mel backward: n_fft={n_fft} hop={hop} n_mels={n_mels} power={power} B={B} L={L}")
+    x = _wave(rng, B, L)
+    plan = nb.nna_plan_trainable(nb.nna_plan_mel(sr=sr, n_fft=n_fft, hop=hop, n_mels=n_mels, power=power, device=0))
+    W = nb.nna_plan_get_bank(plan).cpu().numpy()
+    Wm = nb.nna_plan_get_mel_weights(plan).cpu().numpy()
+    Wm = (Wm + 0.05 * Wm.max() * rng.random(Wm.shape)).astype(np.float32)   # dense, no longer triangles
+    nb.nna_plan_set_mel_weights(plan, _dev(Wm))
+    gout = rng.standard_normal(oracle.mel_bank(x, W, Wm, hop=hop, power=power).shape).astype(np.float32)
+    ref = oracle.mel_bank_backward(x, W, Wm, gout, hop=hop, power=power)
+    ref[1][1] = 0.0
+    ref[1][-1] = 0.0
+    got = nb.nna_mel_backward(plan, _dev(x), _dev(gout))
+    torch.cuda.synchronize()
+    for g, r, name in zip(got, ref, ("filterbank", "bank", "waveform")):
+        g = g.cpu().numpy().astype(np.float64)
+        e = np.abs(g - r).max() / np.abs(r).max()
+        assert np.all(np.isfinite(g)) and e < TOL, (name, e)
