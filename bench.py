@@ -154,7 +154,7 @@ def main() -> int:
         }
     dom = max(names, key=lambda n: per[n]["ms"])
     roofline = {
-        "kernel": {"stft": "stft_kernel<0, 4>", "mel": "stft_kernel<1, 2>", "cqt": "cqt_kernel<false>"}[dom],
+        "kernel": {"stft": "stft_kernel<0, 4, 4>", "mel": "stft_kernel<1, 2, 4>", "cqt": "cqt_kernel<false>"}[dom],
         "bound": "mfma",
         "achieved": per[dom]["algorithmic_tflops"],
         "peak": PEAK_FP32_MFMA_TFLOPS,

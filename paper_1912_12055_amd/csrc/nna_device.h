@@ -74,6 +74,10 @@ __device__ __forceinline__ void wait_vm(f32x4 (&r)[5]) {
   asm volatile("s_waitcnt vmcnt(%5)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]) : "n"(N));
 }
 template <int N>
+__device__ __forceinline__ void wait_vm(f32x4 (&r)[6]) {
+  asm volatile("s_waitcnt vmcnt(%6)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]) : "n"(N));
+}
+template <int N>
 __device__ __forceinline__ void wait_vm(f32x4 (&r)[7]) {
   asm volatile("s_waitcnt vmcnt(%7)"
                : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6])

@@ -21,7 +21,9 @@ constexpr int ST_PITCH = 36;      // LDS row pitch in floats (KC + 4: conflict-f
 constexpr int ST_KG = 8;          // taps per bank fragment (float4 per lane, two lane halves)
 constexpr int ST_NKG = ST_KC / ST_KG;
 constexpr int ST_LDS_ROWS = 160;  // LDS rows per buffer (frames + overlap rows)
+constexpr int ST_LDS_ROWS_WIDE = 192;  // ... of the one-workgroup-per-CU variant (ST_MODE_LIN with six output blocks)
 constexpr int ST_MEL_BLOCKS = 4;  // 32-mel MFMA blocks per pass (128 mels)
+constexpr int ST_LIN_BLOCKS_MAX = 6;  // ST_MODE_LIN: 4 or 6 output blocks per pass (6 when that saves a pass)
 // what the STFT kernel does with a finished row tile
 constexpr int ST_MODE_STFT = 0;   // per-bin epilogue, output written per row tile
 constexpr int ST_MODE_MEL = 1;    // power (or magnitude) of the row tile x filterbank slice -> 128 mel accumulators
@@ -77,7 +79,8 @@ struct StftParams {
   long long n_ft;       // frame tiles
   int tile_frames;      // frames per tile (<= ST_FRAMES; smaller only when many short waveforms share a tile)
   // Mel only
-  const float4* melw;   // [pass][row tile][ST_RB][ST_MEL_BLOCKS][2][64 lanes] float4 (ST_MODE_LIN: [4] in place of [2])
+  const float4* melw;   // [pass][row tile][ST_RB][ST_MEL_BLOCKS][2][64 lanes] float4 (ST_MODE_LIN: [lin_blocks][4])
+  int lin_blocks;       // ST_MODE_LIN: 32-row output blocks per pass, 4 or 6
   const unsigned char* mel_mask;  // [pass][row tile][ST_RB]: bit mb set if that 32-mel block is non-zero
   const float* mel_wnyq;          // [n_mels] weight of the Nyquist bin
   const int* mel_pass_rt;         // [pass][2]: first row tile, one past the last

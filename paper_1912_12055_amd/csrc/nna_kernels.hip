@@ -37,21 +37,25 @@ namespace nna {
 // fragments (requested RING groups earlier) and re-requesting its ring slot afterwards.
 // ---------------------------------------------------------------------------------------
 constexpr int ST_RPP = 256 / (ST_KC / 4);          // LDS rows written per loader pass (32)
-constexpr int ST_NPASS = ST_LDS_ROWS / ST_RPP;     // 160 / 32 = 5
 constexpr int ST_RG = 4;         // row tiles one STFT workgroup handles (amortises its start-up, re-uses its frames)
 constexpr int ST_RING_STFT = 4;  // bank fragment groups in flight per wave
 constexpr int ST_RING_MEL = 2;   // fewer in the Mel variant: its 64 extra accumulators need the registers
 
 // MODE (ST_MODE_*): what follows the contraction of a row tile.
-template <int MODE, int RING>
-__global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
+// LIN_NB (ST_MODE_LIN only): 32-row blocks of the second contraction's output per pass.
+template <int MODE, int RING, int LIN_NB = ST_MEL_BLOCKS>
+__global__ __launch_bounds__(256, LIN_NB > 4 ? 1 : 2) void stft_kernel(const StftParams P) {
   static_assert(ST_NKG % RING == 0, "ring depth must divide the fragment groups per LDS row");
   constexpr bool MEL = MODE == ST_MODE_MEL || MODE == ST_MODE_LIN || MODE == ST_MODE_MELSPEC;  // a second contraction follows every row tile
   constexpr bool SPEC = MODE == ST_MODE_MELSPEC;  // ... and the spectrogram itself is an output too
   constexpr bool LIN = MODE == ST_MODE_LIN;
   constexpr bool GRAD = MODE == ST_MODE_GRAD;  // backward pass: the row tile becomes dLoss/dC
   constexpr bool CPLX = MODE == ST_MODE_CPLX;  // complex or phase output
-  __shared__ __attribute__((aligned(16))) float lds[2][ST_LDS_ROWS * ST_PITCH];
+  // The six-block variant runs one workgroup per compute unit: its tile may hold more overlap rows (a tile of
+  // 128 frames across two waveforms with 32 hop-shifts needs 190).
+  constexpr int LDS_ROWS = LIN_NB > 4 ? ST_LDS_ROWS_WIDE : ST_LDS_ROWS;
+  constexpr int NPASS = LDS_ROWS / ST_RPP;
+  __shared__ __attribute__((aligned(16))) float lds[2][LDS_ROWS * ST_PITCH];
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
@@ -112,8 +116,8 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
   const int total = (rt_end - rt_begin) * n_chunks;
   if (total <= 0) return;
 
-  RowDesc<ST_NPASS> rd;
-  build_rowdesc<ST_KC, ST_NPASS>(rd, g, tm, rows_used, tid);
+  RowDesc<NPASS> rd;
+  build_rowdesc<ST_KC, NPASS>(rd, g, tm, rows_used, tid);
 
   // this lane's frame
   const int fi_lane = wave * 32 + n;
@@ -132,21 +136,22 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
 
-  f32x16 macc[MEL ? ST_MEL_BLOCKS : 1];
+  constexpr int NB = LIN ? LIN_NB : ST_MEL_BLOCKS;  // 32-row blocks of the second contraction's output
+  f32x16 macc[MEL ? NB : 1];
   float nyq = 0.f;
   if constexpr (MEL) {
 #pragma unroll
-    for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb)
+    for (int mb = 0; mb < NB; ++mb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) macc[mb][r] = 0.f;
   }
   // ---- prologue: chunk 0 into LDS buffer 0, chunk 1 requested, first RING bank groups requested --
-  f32x4 R[ST_NPASS];
-  TileFix<ST_NPASS> fx;
-  issue_chunk<ST_NPASS>(R, fx, g, rd, 0);
+  f32x4 R[NPASS];
+  TileFix<NPASS> fx;
+  issue_chunk<NPASS>(R, fx, g, rd, 0);
   wait_vm<0>(R);
-  store_chunk<ST_KC, ST_PITCH, ST_NPASS>(R, fx, lds[0], ST_LDS_ROWS, tid);
-  issue_chunk<ST_NPASS>(R, fx, g, rd, (1 % n_chunks) * ST_KC);
+  store_chunk<ST_KC, ST_PITCH, NPASS>(R, fx, lds[0], LDS_ROWS, tid);
+  issue_chunk<NPASS>(R, fx, g, rd, (1 % n_chunks) * ST_KC);
 
   // The bank is streamed with scalar-base loads: `bank_s` is uniform, each lane adds its 16 bytes.
   const unsigned lane_off = (unsigned)lane * 16u;
@@ -180,11 +185,11 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
     // instruction behind every other MFMA, so that they cost no MFMA issue time; only the address
     // arithmetic (and the rare edge handling) happens here.
     wait_vm<W_TILE>(R);
-    const TileFix<ST_NPASS> fx_store = fx;  // how to write the tile now in R; fx moves on to chunk it+2
-    if (fx_store.cls == 2) store_chunk<ST_KC, ST_PITCH, ST_NPASS>(R, fx_store, lds[(it + 1) & 1], ST_LDS_ROWS, tid);
-    const float* ptr[ST_NPASS];
-    prepare_chunk<ST_NPASS>(ptr, fx, g, rd, ((it + 2) % n_chunks) * ST_KC);
-    float* const stage_dst = stage_dst0 + ((it + 1) & 1) * (ST_LDS_ROWS * ST_PITCH);
+    const TileFix<NPASS> fx_store = fx;  // how to write the tile now in R; fx moves on to chunk it+2
+    if (fx_store.cls == 2) store_chunk<ST_KC, ST_PITCH, NPASS>(R, fx_store, lds[(it + 1) & 1], LDS_ROWS, tid);
+    const float* ptr[NPASS];
+    prepare_chunk<NPASS>(ptr, fx, g, rd, ((it + 2) % n_chunks) * ST_KC);
+    float* const stage_dst = stage_dst0 + ((it + 1) & 1) * (LDS_ROWS * ST_PITCH);
     __builtin_amdgcn_sched_barrier(0);
 
     const float* A = lds[it & 1] + a_off;
@@ -204,12 +209,12 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
       for (int m = 0; m < 16; ++m) {
         const int e = m >> 2, rb = m & 3;
         acc[rb] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][rb][e], a_cur[e], acc[rb], 0, 0, 0);
-        if (TASK != TASK_NONE && (m & 1) && (m >> 1) < ST_NPASS) {
+        if (TASK != TASK_NONE && (m & 1) && (m >> 1) < NPASS) {
           const int p = m >> 1;
           __builtin_amdgcn_sched_barrier(0);
           if (TASK == TASK_STORE) {
             if (fx_store.cls != 2)
-              *reinterpret_cast<f32x4*>(stage_dst + p * ST_RPP * ST_PITCH) = fixed_up<ST_NPASS>(R[p], fx_store, p);
+              *reinterpret_cast<f32x4*>(stage_dst + p * ST_RPP * ST_PITCH) = fixed_up<NPASS>(R[p], fx_store, p);
           } else {
             gload16(R[p], ptr[p]);
           }
@@ -290,16 +295,16 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
           // tile for frame n: as the B operand of MFMA number r it meets, in lane (h, m), the weight
           // of output row m for that packed row.  16 MFMAs contract the 32 rows of block rb.
           const float4* __restrict__ wp =
-              P.melw + (((long long)pass * P.n_rt + rt) * ST_RB) * (ST_MEL_BLOCKS * 4 * 64) + lane;
+              P.melw + (((long long)pass * P.n_rt + rt) * ST_RB) * (NB * 4 * 64) + lane;
 #pragma unroll
           for (int rb = 0; rb < ST_RB; ++rb) {
             const unsigned mask = maskp[rb];
 #pragma unroll
-            for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb) {
+            for (int mb = 0; mb < NB; ++mb) {
               if (mask & (1u << mb)) {
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                  const float4 w = wp[((rb * ST_MEL_BLOCKS + mb) * 4 + v) * 64];
+                  const float4 w = wp[((rb * NB + mb) * 4 + v) * 64];
                   macc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w.x, acc[rb][4 * v + 0], macc[mb], 0, 0, 0);
                   macc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w.y, acc[rb][4 * v + 1], macc[mb], 0, 0, 0);
                   macc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w.z, acc[rb][4 * v + 2], macc[mb], 0, 0, 0);
@@ -374,10 +379,10 @@ __global__ __launch_bounds__(256, 2) void stft_kernel(const StftParams P) {
     float* __restrict__ op = P.out + b_lane * P.out_wave_stride + (long long)P.bin_offset * g.T + t_lane;
     const int f = P.fmt;
 #pragma unroll
-    for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb) {
+    for (int mb = 0; mb < NB; ++mb) {
 #pragma unroll
       for (int r = 0; r < 16; r += 2) {
-        const int bin = (pass * (32 * ST_MEL_BLOCKS) + mb * 32 + 8 * (r >> 2) + 4 * h + (r & 3)) >> 1;
+        const int bin = (pass * (32 * NB) + mb * 32 + 8 * (r >> 2) + 4 * h + (r & 3)) >> 1;
         if (valid && bin < P.out_bins) {
           const float pw = macc[mb][r] * macc[mb][r] + macc[mb][r + 1] * macc[mb][r + 1];
           op[(long long)bin * g.T] = f == NNA_OUT_MAGNITUDE ? format_power<NNA_OUT_MAGNITUDE>(pw)
@@ -762,7 +767,11 @@ hipError_t launch_stft(const StftParams& p, int mode, hipStream_t stream) {
   }
   if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   if (mode == ST_MODE_LIN)
-    hipLaunchKernelGGL((stft_kernel<ST_MODE_LIN, ST_RING_MEL>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    // six output blocks (a pass saved when 128 < output rows <= 192 ...): their registers come out of the ring
+    if (p.lin_blocks == 6)
+      hipLaunchKernelGGL((stft_kernel<ST_MODE_LIN, ST_RING_STFT, 6>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    else
+      hipLaunchKernelGGL((stft_kernel<ST_MODE_LIN, ST_RING_MEL, 4>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   else if (mode == ST_MODE_MEL)
     hipLaunchKernelGGL((stft_kernel<ST_MODE_MEL, ST_RING_MEL>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   else if (mode == ST_MODE_MELSPEC)

@@ -60,6 +60,7 @@ struct nna_plan {
   std::vector<float> h_linW;
   int cq_window = 0;
   size_t lin_frag_floats = 0;
+  int lin_blocks = 4;  // 32-row output blocks per pass of the second contraction (4 or 6)
 
   // CQT
   int n_bins = 0, bpo = 0, n_rb = 0;
@@ -516,15 +517,18 @@ void build_cqt1992_matrix(nna_plan* p) {
 // the second contraction, and the matrix entry it holds: output row pass*128 + mb*32 + lane%32,
 // packed row rt*128 + rb*32 + 8 v + 4 (lane/32) + e
 inline size_t lin_frag_index(const nna_plan* p, int pass, int rt, int rb, int mb, int v, int lane, int e) {
-  return ((((((size_t)pass * p->n_rt + rt) * ST_RB + rb) * ST_MEL_BLOCKS + mb) * 4 + v) * 64 + lane) * 4 + e;
+  return ((((((size_t)pass * p->n_rt + rt) * ST_RB + rb) * p->lin_blocks + mb) * 4 + v) * 64 + lane) * 4 + e;
 }
 
 MelDeviceLayout layout_cqt1992(nna_plan* p) {
   MelDeviceLayout out;
   const int R = 2 * p->n_bins, C = 2 * p->n_half;
-  const int per_pass = 32 * ST_MEL_BLOCKS;
+  // every pass repeats the whole first stage: six output blocks per pass (fewer registers left for the
+  // bank ring) when that saves one, e.g. the 168 rows of 84 bins in one pass instead of two
+  p->lin_blocks = (R + 191) / 192 < (R + 127) / 128 ? 6 : 4;
+  const int per_pass = 32 * p->lin_blocks;
   p->n_pass = (R + per_pass - 1) / per_pass;
-  p->lin_frag_floats = (size_t)p->n_pass * p->n_rt * ST_RB * ST_MEL_BLOCKS * 4 * 64 * 4;
+  p->lin_frag_floats = (size_t)p->n_pass * p->n_rt * ST_RB * p->lin_blocks * 4 * 64 * 4;
   out.frag.assign(p->lin_frag_floats, 0.0f);
   out.mask.assign((size_t)p->n_pass * p->n_rt * ST_RB, 0);
   out.wnyq.assign(1, 0.0f);
@@ -537,7 +541,7 @@ MelDeviceLayout layout_cqt1992(nna_plan* p) {
     out.pass_rt[2 * pass + 1] = p->n_rt;
     for (int rt = 0; rt < p->n_rt; ++rt)
       for (int rb = 0; rb < ST_RB; ++rb)
-        for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb) {
+        for (int mb = 0; mb < p->lin_blocks; ++mb) {
           bool any = false;
           for (int v = 0; v < 4; ++v)
             for (int lane = 0; lane < 64; ++lane)
@@ -894,7 +898,8 @@ nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long lo
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
     return NNA_OK;
   }
-  const int M = pick_tile_frames(ST_FRAMES, T, plan->nj - 1, ST_LDS_ROWS);
+  const int lds_rows = kind == NNA_KIND_CQT1992 && plan->lin_blocks == 6 ? nna::ST_LDS_ROWS_WIDE : ST_LDS_ROWS;
+  const int M = pick_tile_frames(ST_FRAMES, T, plan->nj - 1, lds_rows);
   if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
   nna::StftParams P;
   std::memset(&P, 0, sizeof(P));
@@ -928,6 +933,7 @@ nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long lo
     P.mel_pass_rt = plan->d_mel_pass_rt;
     P.n_mels = 2 * plan->n_bins;
     P.n_pass = plan->n_pass;
+    P.lin_blocks = plan->lin_blocks;
   } else {
     P.fmt = plan->fmt;
   }
@@ -1461,11 +1467,11 @@ nna_status nna_plan_spectral_kernels(const nna_plan* plan, double* host_out, siz
         if (e != hipSuccess) return fail_hip(e, "spectral kernel read-back");
       }
       W.assign(R * C, 0.0f);
-      const int per_pass = 32 * ST_MEL_BLOCKS;
+      const int per_pass = 32 * plan->lin_blocks;
       for (int pass = 0; pass < plan->n_pass; ++pass)
         for (int rt = 0; rt < plan->n_rt; ++rt)
           for (int rb = 0; rb < ST_RB; ++rb)
-            for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb)
+            for (int mb = 0; mb < plan->lin_blocks; ++mb)
               for (int v = 0; v < 4; ++v)
                 for (int lane = 0; lane < 64; ++lane)
                   for (int e = 0; e < 4; ++e) {

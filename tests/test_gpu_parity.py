@@ -496,12 +496,13 @@ def test_cqt2010v2_workspace_and_shape_checks(nb):
 CQT1992_CASES = [
     # name, B, L, sr, hop, fmin, n_bins, bpo, n_fft, win, center, fmt
     ("36 bins, 2048 taps, one pass", 2, 9000, 22050, 256, 220.0, 36, 12, 0, 0, True, 0),
-    ("70 bins: two passes of 64, ragged, tiles span waveforms", 5, 9000, 8000, 64, 55.0, 70, 12, 0, 0, True, 0),
+    ("70 bins: one pass of six 32-row blocks, ragged, tiles span waveforms", 5, 9000, 8000, 64, 55.0, 70, 12, 0, 0, True, 0),
+    ("100 bins: two passes of four blocks", 3, 9000, 16000, 64, 200.0, 100, 24, 0, 0, True, 0),
     ("odd bin count, power output, padded n_fft", 2, 12000, 8000, 128, 300.0, 13, 6, 1024, 0, True, 1),
     ("hop does not divide n_fft", 2, 6000, 8000, 100, 220.0, 30, 12, 1024, 0, True, 0),
     ("rect kernels, no centring, log output", 2, 7000, 8000, 128, 500.0, 6, 3, 128, 1, False, 2),
     ("short waveforms, many per tile", 40, 1100, 8000, 128, 220.0, 24, 12, 1024, 0, True, 0),
-    ("150 bins: three passes, 4096 taps", 2, 20000, 22050, 512, 110.0, 150, 24, 0, 0, True, 0),
+    ("150 bins: two passes of six blocks, 4096 taps", 2, 20000, 22050, 512, 110.0, 150, 24, 0, 0, True, 0),
     ("8192 taps, 16 hop-shifts", 1, 30000, 22050, 512, 65.41, 40, 12, 0, 0, True, 0),
 ]
 
