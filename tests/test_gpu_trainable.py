@@ -423,3 +423,31 @@ def test_cqt_backward_config5_full_sampled(nb):
     rest = torch.ones(B, dtype=torch.bool, device="cuda:0")
     rest[sampled] = False
     assert not gx[rest].any()
+
+
+def test_destroying_plans_returns_their_device_memory(nb):
+    # every buffer a plan owns (banks, row-major copies, index maps, tables) goes back when the plan is destroyed:
+    # building and dropping the same plans again and again does not eat into the free memory
+    import gc
+    import torch
+    _say("plan destroy frees device memory")
+
+    def one_round():
+        plans = [nb.nna_plan_trainable(nb.nna_plan_cqt(sr=22050, hop=512, fmin=32.70, n_bins=84, n_taps=16384, device=0)),
+                 nb.nna_plan_trainable(nb.nna_plan_mel(n_fft=2048, hop=512, n_mels=128, device=0)),
+                 nb.nna_plan_trainable(nb.nna_plan_stft(n_fft=2048, hop=512, device=0)),
+                 nb.nna_plan_cqt2010(device=0), nb.nna_plan_cqt2010v2(device=0),
+                 nb.nna_plan_cqt1992(fmin=220.0, n_bins=36, device=0),
+                 nb.nna_plan_stft_prec(n_fft=2048, hop=512, precision=nb.NNA_PREC_F16, device=0)]
+        torch.cuda.synchronize()
+        held = torch.cuda.mem_get_info()[0]
+        del plans
+        gc.collect()
+        torch.cuda.synchronize()
+        return held, torch.cuda.mem_get_info()[0]
+
+    held1, free1 = one_round()
+    assert free1 - held1 > 50e6          # the plans did hold device memory, and dropping them gave it back
+    for _ in range(3):
+        _, free_n = one_round()
+    assert free1 - free_n < 8e6, (free1, free_n)
