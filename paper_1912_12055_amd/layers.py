@@ -279,3 +279,7 @@ class CQT2010(_Cqt2010):
     """Sec. III-C "Constant-Q transform (2010 version)": recursive downsampling, frequency-domain kernels."""
     _plan_fn = staticmethod(nb.nna_plan_cqt2010)
     _run_fn = staticmethod(nb.nna_cqt2010)
+
+
+# The constant-Q layer the paper recommends (fastest on a GPU, best output: Sec. IV-A, IV-B) under the plain name.
+CQT = CQT1992v2
