@@ -13,6 +13,14 @@ Parity status: ``cqt1992_spectral_kernels`` / ``cqt1992`` pinned (explicit O(N^2
 case, numpy's FFT of frames cut independently, the exact dropped-half difference from the
 time-domain CQT, tone magnitude A/2); ``cqt2010`` pinned (octave by octave against ``cqt1992`` on
 SciPy-downsampled signals, its time-domain twin, tones A/2 in every octave).
+
+Also in numpy: the layers with their kernels as weights and the gradients through them (Sec. IV-C).
+Parity status: ``stft_bank`` pinned (equals the windowed-DFT oracle for a bank written out from eq. (DFT2));
+``stft_bank_backward`` pinned (central differences of that forward in float64, one-frame closed forms);
+``mel_bank`` / ``mel_bank_backward`` pinned (the Mel oracle for the initial weights; central differences);
+``cqt_bank`` pinned (``stft_bank`` with it equals the constant-Q oracle, real and imaginary parts; supports
+equal the kernel lengths); ``cqt_bank_backward`` pinned (central differences inside the supports, exact
+zeros outside).
 """
 from __future__ import annotations
 
