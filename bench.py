@@ -162,10 +162,26 @@ def main() -> int:
         "frac": per[dom]["mfma_frac"],
         "traffic": traffic.get(dom),
     }
+    # the kernel of the step that sits furthest below its roof
+    low = min(names, key=lambda n: per[n]["mfma_frac"])
+    kernel_names = {"stft": "stft_kernel<0, 4, 4>", "mel": "stft_kernel<1, 2, 4>", "cqt": "cqt_kernel<false>"}
+    roofline_min = {"kernel": kernel_names[low], "frac": per[low]["mfma_frac"],
+                    "frac_executed": per[low]["mfma_frac_executed"]}
 
     # Timed beside the step, never part of `value`: the same batch through the STFT on the linear
     # frequency axis of Sec. II-B's worked example, through the downsampling CQT (Sec. III-C) and through
     # the STFT with float16 operands; and the CQT with frequency-domain kernels on a smaller batch.
+    # the waveforms the cpu_baseline leg will run the oracle on: keep the GPU's results for them, so that
+    # the oracle's outputs are compared with them afterwards (outside every timed region)
+    n_cpu = min(B, 96)
+    cpu_idx = sorted({int(i) for i in np.linspace(0, B - 1, n_cpu)})
+    gpu_sample = {}
+    if not args.no_cpu_baseline:
+        for n in names:
+            legs[n][0]()
+        torch.cuda.synchronize()
+        gpu_sample = {n: legs[n][2][cpu_idx].cpu().numpy() for n in names}
+
     extras = None
     if not args.no_extras and not args.only:
         extras = {}
@@ -316,23 +332,29 @@ def main() -> int:
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        n_cpu = min(B, 96)
-        idx = sorted({int(i) for i in np.linspace(0, B - 1, n_cpu)})
+        idx = cpu_idx
         n_cpu = len(idx)
         xs4 = signals.batch(4, idx)
         xs5 = signals.batch(5, idx)
+        ref = {}
         t0 = time.perf_counter()
         done = 0
         if "stft" in names:
-            oracle.stft(xs4, n_fft=2048, hop=512)
+            ref["stft"] = oracle.stft(xs4, n_fft=2048, hop=512)
             done += 1
         if "mel" in names:
-            oracle.mel(xs4, sr=sr, n_fft=2048, hop=512, n_mels=128, fmin=0.0, fmax=22050.0)
+            ref["mel"] = oracle.mel(xs4, sr=sr, n_fft=2048, hop=512, n_mels=128, fmin=0.0, fmax=22050.0)
             done += 1
         if "cqt" in names:
-            oracle.cqt(xs5, sr=sr, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24, n_taps=65536)
+            ref["cqt"] = oracle.cqt(xs5, sr=sr, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24, n_taps=65536)
             done += 1
         t_cpu = time.perf_counter() - t0
+        # parity of this very run: per waveform max |gpu - oracle| / max |oracle|, the worst over the sample
+        for n in names:
+            got = gpu_sample[n].astype(np.float64)
+            per[n]["max_rel_err"] = float(max(
+                np.abs(got[i] - ref[n][i]).max() / np.abs(ref[n][i]).max() for i in range(n_cpu)))
+            per[n]["max_rel_err_waveforms"] = n_cpu
         cpu = {
             "value": round(done * n_cpu * L / t_cpu / 1e9, 6),
             "unit": "GSamples/s",
@@ -363,6 +385,7 @@ def main() -> int:
         },
         "per_transform": per,
         "roofline": roofline,
+        "roofline_min": roofline_min,
         "cpu_baseline": cpu,
         "extras": extras,
         "setup_s": {"input_generation": round(t_gen, 2), "plans": round(t_plan, 2)},

@@ -26,9 +26,15 @@
  *     kernel is enqueued on `hip_stream` (a hipStream_t cast to void*; NULL = the
  *     default stream).  Plans are immutable after creation and may be shared
  *     between threads (the one exception, nna_plan_set_bank, says so).
- *   - Every function returns an nna_status; on failure nothing is enqueued, an
- *     output plan pointer is set to NULL and nna_last_error() describes the problem
- *     (thread-local text).  Nothing throws or aborts across this boundary.
+ *   - Every function returns an nna_status; on failure an output plan pointer is set
+ *     to NULL and nna_last_error() describes the problem (thread-local text).  All
+ *     argument, shape, capacity and workspace checks are made before anything is
+ *     enqueued, so a call that fails them leaves the stream and the outputs alone.
+ *     The calls that enqueue several kernels (nna_cqt2010v2, nna_cqt2010 and the
+ *     *_backward calls) can still fail with NNA_ERR_HIP when the runtime itself
+ *     rejects one of the later launches; the earlier kernels of that call are then
+ *     already enqueued and the outputs and workspace hold unspecified values.
+ *     Nothing throws or aborts across this boundary.
  *   - There is no CPU fallback: on a machine without a usable GPU plan creation for
  *     device >= 0 fails with NNA_ERR_HIP.  device == -1 builds a host-only plan that
  *     can be inspected (nna_out_shape, nna_plan_bank, nna_plan_info) but not run.
@@ -211,7 +217,7 @@ nna_status nna_plan_cqt2010(nna_plan** plan, int sr, int hop, double fmin, int n
                             nna_window win, int n_fft, int fir_taps, nna_output fmt, int device);
 
 /* Output shape [B, *n_bins, *n_frames] for a batch of B waveforms of L samples.
- * NNA_ERR_SHAPE if L is too short (center: L <= pad; otherwise L < K) or B < 1. */
+ * NNA_ERR_SHAPE if L is too short (center: L <= pad; otherwise L < K; in any case L < 4) or B < 1. */
 nna_status nna_out_shape(const nna_plan* plan, long long B, long long L, long long* n_bins,
                          long long* n_frames);
 

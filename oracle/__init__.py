@@ -20,7 +20,9 @@ Parity status: ``stft_bank`` pinned (equals the windowed-DFT oracle for a bank w
 ``mel_bank`` / ``mel_bank_backward`` pinned (the Mel oracle for the initial weights; central differences);
 ``cqt_bank`` pinned (``stft_bank`` with it equals the constant-Q oracle, real and imaginary parts; supports
 equal the kernel lengths); ``cqt_bank_backward`` pinned (central differences inside the supports, exact
-zeros outside).
+zeros outside); ``dft_bank_parameter_mask`` / ``stft_dft_bank_backward`` pinned (the masked rows are exactly
+the rows of eq. (DFT2)'s bank, written out in the test, that are zero for every tap; the unmasked gradient
+there is already zero for the magnitude-type outputs).
 """
 from __future__ import annotations
 
@@ -533,6 +535,26 @@ def stft_bank_backward(x, W, gout, hop=512, center=True, fmt=MAGNITUDE):
     return gW, gx
 
 
+def dft_bank_parameter_mask(n_fft: int) -> np.ndarray:
+    """Which entries of the STFT layer's weight W[2F, K] (F = n_fft/2 + 1, K = n_fft) are parameters
+    when the layer is initialised from eq. (DFT2): everything except rows 1 and 2F-1, the sine kernels
+    of bins 0 and n_fft/2.  Those two are sin(0 n) and sin(pi n), identically zero for integer n, so the
+    layer has no kernel there to train (Sec. IV-C trains the kernels eq. (DFT2) gives it): they stay
+    zero, and their gradient is reported as zero.  [2F, K] bool."""
+    F = n_fft // 2 + 1
+    mask = np.ones((2 * F, n_fft), dtype=bool)
+    mask[1] = False
+    mask[2 * F - 1] = False
+    return mask
+
+
+def stft_dft_bank_backward(x, W, gout, hop=512, center=True, fmt=MAGNITUDE):
+    """``stft_bank_backward`` for a bank that started as eq. (DFT2)'s kernels: the gradient of the two
+    structurally zero sine rows (``dft_bank_parameter_mask``) is dropped.  (gW, gx)."""
+    gW, gx = stft_bank_backward(x, W, gout, hop=hop, center=center, fmt=fmt)
+    return np.where(dft_bank_parameter_mask(np.asarray(W).shape[1]), gW, 0.0), gx
+
+
 def mel_bank(x, W, Wmel, hop=512, center=True, power=2.0):
     """The Mel-spectrogram layer with given weights (Sec. III-B, Fig. 3, with both stages as weights,
     Sec. IV-C): the STFT layer of ``stft_bank`` with kernel bank W[2F, K], then the fully connected
@@ -542,9 +564,10 @@ def mel_bank(x, W, Wmel, hop=512, center=True, power=2.0):
     return np.einsum("mk,bkt->bmt", np.asarray(Wmel, dtype=np.float64), P)
 
 
-def mel_bank_backward(x, W, Wmel, gout, hop=512, center=True, power=2.0):
+def mel_bank_backward(x, W, Wmel, gout, hop=512, center=True, power=2.0, dft_rows=False):
     """Gradients of a scalar loss through ``mel_bank`` given gout = dLoss/dout [B, n_mels, T]:
-    (gWmel [n_mels, F], gW [2F, K], gx [B, L]).  gWmel[m, k] = sum_{b,t} gout[b, m, t] P[b, k, t];
+    (gWmel [n_mels, F], gW [2F, K], gx [B, L]).  dft_rows: the bank started as eq. (DFT2)'s kernels, so
+    the two structurally zero sine rows are not parameters (``dft_bank_parameter_mask``).  gWmel[m, k] = sum_{b,t} gout[b, m, t] P[b, k, t];
     the gradient reaching the STFT layer's output is gP[b, k, t] = sum_m Wmel[m, k] gout[b, m, t],
     which ``stft_bank_backward`` carries on to the kernel bank and the waveform."""
     fmt = POWER if power == 2.0 else MAGNITUDE
@@ -554,6 +577,8 @@ def mel_bank_backward(x, W, Wmel, gout, hop=512, center=True, power=2.0):
     gWmel = np.einsum("bmt,bkt->mk", gout, P)
     gP = np.einsum("mk,bmt->bkt", Wmel, gout)
     gW, gx = stft_bank_backward(x, W, gP, hop=hop, center=center, fmt=fmt)
+    if dft_rows:
+        gW = np.where(dft_bank_parameter_mask(np.asarray(W).shape[1]), gW, 0.0)
     return gWmel, gW, gx
 
 

@@ -114,6 +114,7 @@ struct Stft16Params {
 };
 
 constexpr int CQ_ITEM_RB = 4;  // row blocks one CQT workgroup can handle (short kernels are grouped)
+constexpr int CQ_TABLE_CAP = 512;  // chunk descriptors of a work item held in LDS at a time (a power of two; 24 KB)
 
 // One LDS chunk of a CQT work item (48 bytes, read as three 16-byte words).
 struct CqtChunk {
@@ -230,6 +231,11 @@ struct MelBwParams {
   int b_per_split;       // filterbank gradient: waveforms per workgroup
 };
 
+// The launchers report hipGetLastError() right after their launch.  That call also returns (and clears) an
+// error some earlier, unrelated call of this thread left behind -- PyTorch shares the runtime -- so every
+// launcher first clears whatever is pending: the status it returns is then its own launch's.
+inline void clear_stale_error() { (void)hipGetLastError(); }
+
 hipError_t launch_stft(const StftParams& p, int mode, hipStream_t stream);
 hipError_t launch_mel_bw_spec(const MelBwParams& p, hipStream_t stream);    // gP
 hipError_t launch_mel_bw_weights(const MelBwParams& p, hipStream_t stream); // gW
@@ -243,6 +249,7 @@ hipError_t launch_bank_to_logical(const BankPermuteParams& p, hipStream_t stream
 hipError_t launch_bw_bank(const BwParams& p, hipStream_t stream);      // gw += G x frames
 hipError_t launch_bw_wave(const BwParams& p, hipStream_t stream);      // gx += transposed convolution
 hipError_t launch_cqt(const CqtParams& p, hipStream_t stream);
+size_t cqt_launch_lds_bytes(int n_chunks, int lds_rows);  // dynamic LDS launch_cqt asks for (limit: 160 KB)
 hipError_t launch_cqt_bank_from_logical(const CqtBankParams& p, hipStream_t stream);  // bank and wrm <- logical
 hipError_t launch_cqt_bank_to_logical(const CqtBankParams& p, hipStream_t stream);    // logical <- wrm
 hipError_t launch_stft16(const Stft16Params& p, hipStream_t stream);

@@ -435,8 +435,12 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
   extern __shared__ __attribute__((aligned(16))) float dyn_lds[];
   // dynamic LDS: this item's chunk table (read every chunk; kept out of the vector-memory path so
   // that fetching a descriptor never waits on the streaming loads), then two tile buffers
+  // A table longer than CQ_TABLE_CAP chunks (kernels of tens of thousands of taps whose frames do not
+  // share LDS rows) is kept as a ring of CQ_TABLE_CAP entries, refilled half a ring at a time.
   int4* s_chunks = reinterpret_cast<int4*>(dyn_lds);
-  float* lds0 = dyn_lds + (size_t)P.n_chunks * (sizeof(CqtChunk) / 4);
+  const int tbl_n = P.n_chunks < CQ_TABLE_CAP ? P.n_chunks : CQ_TABLE_CAP;  // entries held in LDS
+  const int tbl_mask = P.n_chunks <= CQ_TABLE_CAP ? 0x7fffffff : CQ_TABLE_CAP - 1;
+  float* lds0 = dyn_lds + (size_t)tbl_n * (sizeof(CqtChunk) / 4);
   float* lds1 = lds0 + (size_t)P.lds_rows * CQ_PITCH;
 
   const int tid = threadIdx.x;
@@ -478,10 +482,8 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
   }
 
   const int n_chunks = item.n_chunks;  // >= 1; every listed chunk starts with >= CQ_PREFETCH fragments
-  {
-    const int4* __restrict__ src = reinterpret_cast<const int4*>(P.chunks + (long long)item_id * P.n_chunks);
-    for (int i = tid; i < n_chunks * 3; i += 256) s_chunks[i] = src[i];
-  }
+  const int4* __restrict__ tbl_src = reinterpret_cast<const int4*>(P.chunks + (long long)item_id * P.n_chunks);
+  for (int i = tid; i < (n_chunks < tbl_n ? n_chunks : tbl_n) * 3; i += 256) s_chunks[i] = tbl_src[i];
   // the bank fragments are streamed with scalar-base loads: uniform base + 16 bytes per lane
   const unsigned lane_off = (unsigned)lane * 16u;
   const char* bank_s = reinterpret_cast<const char*>(P.bank) + item.frag0 * (64 * 16);
@@ -494,7 +496,7 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
   __syncthreads();  // the chunk table is complete
 
   auto chunk_shift = [&](int i) {  // (first hop-shift) * hop + (first column) of chunk i
-    const int4 v = s_chunks[3 * i];
+    const int4 v = s_chunks[3 * (i & tbl_mask)];
     return __builtin_amdgcn_readfirstlane(v.y) * g.hop + __builtin_amdgcn_readfirstlane(v.x);
   };
 
@@ -536,7 +538,7 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
     prepare_chunk<CQ_NPASS>(ptr, fx, g, rd, chunk_shift(it + 2 < n_chunks ? it + 2 : n_chunks - 1));
     float* const stage_dst = nxt + stage_off;
     // this chunk: per row block r of the item, nj[r] fragments starting joff[r] hop-shifts in
-    const int4 d1 = s_chunks[3 * it + 1], d2 = s_chunks[3 * it + 2];
+    const int4 d1 = s_chunks[3 * (it & tbl_mask) + 1], d2 = s_chunks[3 * (it & tbl_mask) + 2];
     const int joff[CQ_ITEM_RB] = {__builtin_amdgcn_readfirstlane(d1.x), __builtin_amdgcn_readfirstlane(d1.y),
                                   __builtin_amdgcn_readfirstlane(d1.z), __builtin_amdgcn_readfirstlane(d1.w)};
     const int njr[CQ_ITEM_RB] = {__builtin_amdgcn_readfirstlane(d2.x), __builtin_amdgcn_readfirstlane(d2.y),
@@ -626,6 +628,15 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
     row_block(std::integral_constant<int, 1>{});
     row_block(std::integral_constant<int, 2>{});
     row_block(std::integral_constant<int, 3>{});
+    // Ring refill: every wave is inside iteration `it` (the barrier below separates iterations) and reads
+    // entries it .. it+2 only, so entries [it - CAP/2, it) are dead; their slots take entries
+    // [it + CAP/2, it + CAP), first read CAP/2 - 2 iterations from now.
+    if (tbl_mask != 0x7fffffff && it >= CQ_TABLE_CAP / 2 && (it & (CQ_TABLE_CAP / 2 - 1)) == 0) {
+      const int first = it + CQ_TABLE_CAP / 2;
+      int count = n_chunks - first;
+      count = count < CQ_TABLE_CAP / 2 ? count : CQ_TABLE_CAP / 2;
+      for (int i = tid; i < count * 3; i += 256) s_chunks[3 * (first & tbl_mask) + i] = tbl_src[3 * first + i];
+    }
     __syncthreads();
   }
 
@@ -746,6 +757,11 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
 // LDS per workgroup is 160 KB
 static constexpr size_t CQ_DYN_LDS_MAX = 160 * 1024;
 
+size_t cqt_launch_lds_bytes(int n_chunks, int lds_rows) {
+  const int tbl_n = n_chunks < CQ_TABLE_CAP ? n_chunks : CQ_TABLE_CAP;
+  return (size_t)tbl_n * sizeof(CqtChunk) + 2ull * lds_rows * CQ_PITCH * sizeof(float);
+}
+
 hipError_t kernels_init() {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(cqt_kernel<false>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)CQ_DYN_LDS_MAX);
@@ -755,6 +771,7 @@ hipError_t kernels_init() {
 }
 
 hipError_t launch_stft(const StftParams& p, int mode, hipStream_t stream) {
+  clear_stale_error();
   long long blocks;
   const bool mel = mode == ST_MODE_MEL || mode == ST_MODE_LIN || mode == ST_MODE_MELSPEC;
   if (mode == ST_MODE_MELSPEC && !p.pout) return hipErrorInvalidValue;
@@ -786,10 +803,11 @@ hipError_t launch_stft(const StftParams& p, int mode, hipStream_t stream) {
 }
 
 hipError_t launch_cqt(const CqtParams& p, hipStream_t stream) {
+  clear_stale_error();
   const long long blocks = p.n_ft * p.n_items;
   if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   if (p.lds_rows > CQ_LDS_ROWS_MAX) return hipErrorInvalidValue;
-  const size_t lds = (size_t)p.n_chunks * sizeof(CqtChunk) + 2ull * p.lds_rows * CQ_PITCH * sizeof(float);
+  const size_t lds = cqt_launch_lds_bytes(p.n_chunks, p.lds_rows);
   if (lds > CQ_DYN_LDS_MAX) return hipErrorInvalidValue;
   if (p.gbuf) {
     if (!p.gout || p.raw || p.rows_pad < 2 * p.n_bins) return hipErrorInvalidValue;

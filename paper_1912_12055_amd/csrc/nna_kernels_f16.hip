@@ -444,6 +444,7 @@ __global__ __launch_bounds__(256, 1) void stft16s_kernel(const Stft16Params P) {
 }
 
 hipError_t launch_stft16(const Stft16Params& p, hipStream_t stream) {
+  clear_stale_error();
   const long long n_rg = (p.n_rt + p.rt_per_block - 1) / p.rt_per_block;
   const long long blocks = p.n_ft * n_rg;
   if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;

@@ -845,6 +845,8 @@ nna_status check_call(const nna_plan* plan, int kind, const float* x, long long 
   if (!x || !out) return fail(NNA_ERR_INVALID_ARG, "x_dev / out_dev is NULL");
   if (plan->device < 0) return fail(NNA_ERR_UNSUPPORTED, "host-only plan (device = -1) cannot run transforms");
   if (B < 1) return fail(NNA_ERR_SHAPE, "B must be >= 1");
+  // the framing loader fetches windows of four consecutive stored samples
+  if (L < 4) return fail(NNA_ERR_SHAPE, "L must be at least 4 samples");
   const long long T = frames_of(plan, L);
   if (T < 1) return fail(NNA_ERR_SHAPE, plan->center ? "L must exceed the reflection padding (K/2)" : "L is shorter than one window");
   // the kernels index samples of one waveform with 32-bit integers (padded index < L + 2K)
@@ -1120,13 +1122,13 @@ inline void octave_bins(int n_bins, int bpo, int a, int& lo, int& hi) {
 inline size_t ws_round(long long floats) { return ((size_t)floats * sizeof(float) + 255) / 256 * 256; }
 
 // lengths of the waveform at every octave; false if some octave is too short for its padding
-bool cqt2010_lengths(const nna_plan* plan, long long L, std::vector<long long>& La) {
+constexpr int MAX_OCTAVES = 16;
+bool cqt2010_lengths(const nna_plan* plan, long long L, long long (&La)[MAX_OCTAVES]) {
   const int n_oct = (int)plan->octave.size();
-  La.assign(n_oct, 0);
   long long l = L;
   for (int a = 0; a < n_oct; ++a) {
     La[a] = l;
-    if (l <= plan->pad) return false;                      // mirror reflection of the CQT kernels
+    if (l < 4 || l <= plan->pad) return false;             // mirror reflection of the CQT kernels
     if (a + 1 < n_oct && l < plan->fir->K) return false;   // and of the filter's frames
     l = (l + 1) / 2;
   }
@@ -1365,7 +1367,7 @@ static nna_status make_downsampling_plan(int kind, nna_plan** plan, int sr, int 
   if (fir_taps < 3 || fir_taps > 4095 || !(fir_taps & 1))
     return fail(NNA_ERR_INVALID_ARG, "fir_taps must be odd and in [3, 4095]");
   const int n_oct = octaves_of(n_bins, bins_per_octave);
-  if (n_oct > 16) return fail(NNA_ERR_UNSUPPORTED, "more than 16 octaves are not supported");
+  if (n_oct > MAX_OCTAVES) return fail(NNA_ERR_UNSUPPORTED, "more than 16 octaves are not supported");
   if (hop % (1 << (n_oct - 1)) != 0)
     return fail(NNA_ERR_INVALID_ARG, "hop must be a multiple of 2^(octaves - 1): every octave halves it");
   int lo, hi;
@@ -1512,7 +1514,7 @@ static nna_status run_octaves(const nna_plan* plan, int kind, const float* x_dev
   if (!x_dev || !out_dev) return fail(NNA_ERR_INVALID_ARG, "x_dev / out_dev is NULL");
   if (plan->device < 0) return fail(NNA_ERR_UNSUPPORTED, "host-only plan (device = -1) cannot run transforms");
   if (B < 1) return fail(NNA_ERR_SHAPE, "B must be >= 1");
-  std::vector<long long> La;
+  long long La[MAX_OCTAVES];
   if (L < 1 || !cqt2010_lengths(plan, L, La))
     return fail(NNA_ERR_SHAPE, "L is too short: every octave's waveform must exceed the reflection padding, and all but the lowest hold one frame of the decimation filter");
   const long long T = 1 + L / plan->hop;
@@ -1524,6 +1526,17 @@ static nna_status run_octaves(const nna_plan* plan, int kind, const float* x_dev
   if (need > 0 && (!workspace_dev || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace_dev) & 15)))
     return fail(NNA_ERR_INVALID_ARG, "workspace_dev is NULL, misaligned or smaller than nna_cqt2010v2_workspace asks for");
   const int n_oct = (int)plan->octave.size();
+  // every launch of the call must fit before the first one is enqueued
+  for (int a = 0; a < n_oct; ++a) {
+    const nna_plan* sub = plan->octave[a];
+    const int lds_rows = sub->kind == NNA_KIND_CQT1992 && sub->lin_blocks == 6 ? nna::ST_LDS_ROWS_WIDE : ST_LDS_ROWS;
+    const int M = kind == NNA_KIND_CQT2010V2 ? pick_tile_frames(CQ_FRAMES, T, sub->max_jspan - 1, CQ_LDS_ROWS_MAX)
+                                             : pick_tile_frames(ST_FRAMES, T, sub->nj - 1, lds_rows);
+    const int Mf = a + 1 < n_oct ? pick_tile_frames(CQ_FRAMES, (La[a + 1] + FIR_ROWS - 1) / FIR_ROWS,
+                                                    plan->fir->max_jspan - 1, CQ_LDS_ROWS_MAX)
+                                 : 1;
+    if (M < 1 || Mf < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
+  }
   float* buf[2] = {static_cast<float*>(workspace_dev), nullptr};
   if (n_oct > 2) buf[1] = reinterpret_cast<float*>(static_cast<char*>(workspace_dev) + ws_round(B * ((L + 1) / 2)));
   DeviceGuard guard;
@@ -1579,13 +1592,14 @@ nna_status nna_out_shape(const nna_plan* plan, long long B, long long L, long lo
   if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
   if (B < 1) return fail(NNA_ERR_SHAPE, "B must be >= 1");
   if (plan->kind == NNA_KIND_CQT2010V2 || plan->kind == NNA_KIND_CQT2010) {
-    std::vector<long long> La;
+    long long La[MAX_OCTAVES];
     if (L < 1 || !cqt2010_lengths(plan, L, La))
       return fail(NNA_ERR_SHAPE, "L is too short: every octave's waveform must exceed the reflection padding, and all but the lowest hold one frame of the decimation filter");
     if (n_bins) *n_bins = plan->n_bins;
     if (n_frames) *n_frames = 1 + L / plan->hop;
     return NNA_OK;
   }
+  if (L < 4) return fail(NNA_ERR_SHAPE, "L must be at least 4 samples");
   const long long T = frames_of(plan, L);
   if (T < 1) return fail(NNA_ERR_SHAPE, plan->center ? "L must exceed the reflection padding (K/2)" : "L is shorter than one window");
   if (n_bins) *n_bins = plan->out_rows();

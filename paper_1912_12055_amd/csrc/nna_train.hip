@@ -774,6 +774,7 @@ static unsigned grid_for(long long n, int block) {
 }
 
 hipError_t launch_fill_zero(float* p, long long n, hipStream_t stream) {
+  clear_stale_error();
   if (n <= 0) return hipSuccess;
   hipLaunchKernelGGL(fill_zero_kernel, dim3(grid_for(n, 256 * 8)), dim3(256), 0, stream, p, n);
   return hipGetLastError();
@@ -802,6 +803,7 @@ __global__ void cqt_bank_to_logical_kernel(const CqtBankParams P) {
 }
 
 hipError_t launch_cqt_bank_from_logical(const CqtBankParams& p, hipStream_t stream) {
+  clear_stale_error();
   const long long n = std::max(p.n_bank, (long long)p.rows * p.K);
   if (n < 1 || (n + 255) / 256 > 0x7fffffffLL || (long long)p.rows * p.K > 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(cqt_bank_from_logical_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p);
@@ -809,6 +811,7 @@ hipError_t launch_cqt_bank_from_logical(const CqtBankParams& p, hipStream_t stre
 }
 
 hipError_t launch_cqt_bank_to_logical(const CqtBankParams& p, hipStream_t stream) {
+  clear_stale_error();
   const long long n = (long long)p.rows * p.K;
   if (n < 1 || (n + 255) / 256 > 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(cqt_bank_to_logical_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p);
@@ -816,6 +819,7 @@ hipError_t launch_cqt_bank_to_logical(const CqtBankParams& p, hipStream_t stream
 }
 
 hipError_t launch_fill_zero_frames(float* gbuf, long long rows_pad, long long f0, long long f1, hipStream_t stream) {
+  clear_stale_error();
   if (rows_pad <= 0 || f1 <= f0) return hipSuccess;
   hipLaunchKernelGGL(fill_zero_frames_kernel, dim3(grid_for(rows_pad * (f1 - f0), 256)), dim3(256), 0, stream, gbuf, rows_pad, f0, f1);
   return hipGetLastError();
@@ -826,6 +830,7 @@ static long long bank_float4s(const BankPermuteParams& p) {
 }
 
 hipError_t launch_bank_from_logical(const BankPermuteParams& p, hipStream_t stream) {
+  clear_stale_error();
   const long long n4 = bank_float4s(p);
   if (n4 > 0x7fffffffLL * 256) return hipErrorInvalidValue;
   hipLaunchKernelGGL(bank_from_logical_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, stream, p, n4);
@@ -833,6 +838,7 @@ hipError_t launch_bank_from_logical(const BankPermuteParams& p, hipStream_t stre
 }
 
 hipError_t launch_bank_to_rowmajor(const BankPermuteParams& p, hipStream_t stream) {
+  clear_stale_error();
   const long long n4 = bank_float4s(p);
   if (n4 > 0x7fffffffLL * 256) return hipErrorInvalidValue;
   hipLaunchKernelGGL(bank_to_rowmajor_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, stream, p, n4);
@@ -840,6 +846,7 @@ hipError_t launch_bank_to_rowmajor(const BankPermuteParams& p, hipStream_t strea
 }
 
 hipError_t launch_bank_to_logical(const BankPermuteParams& p, hipStream_t stream) {
+  clear_stale_error();
   const long long rows = 2LL * (p.packed ? p.n_half + 1 : p.n_half);
   const long long n = rows * p.K;
   hipLaunchKernelGGL(bank_to_logical_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p, n);
@@ -852,6 +859,7 @@ static bool bw_shapes_ok(const BwParams& p) {
 }
 
 hipError_t launch_bw_bank(const BwParams& p, hipStream_t stream) {
+  clear_stale_error();
   if (!bw_shapes_ok(p) || p.n_split < 1 || p.chunks_per_split < 1) return hipErrorInvalidValue;
   if (p.chunks_per_split * p.n_split < p.gpitch / BW_KC) return hipErrorInvalidValue;
   const bool sparse = p.tiles != nullptr;
@@ -867,6 +875,7 @@ hipError_t launch_bw_bank(const BwParams& p, hipStream_t stream) {
 }
 
 hipError_t launch_bw_wave(const BwParams& p, hipStream_t stream) {
+  clear_stale_error();
   if (!bw_shapes_ok(p)) return hipErrorInvalidValue;
   if (p.shift_rng) {
     if (p.n_shift < 1 || p.n_kc < 1 || p.n_kc > p.rows_pad / BW_KC || p.n_ct != (p.g.hop + BW_NT - 1) / BW_NT ||
@@ -884,6 +893,7 @@ hipError_t launch_bw_wave(const BwParams& p, hipStream_t stream) {
 }
 
 hipError_t launch_mel_bw_spec(const MelBwParams& p, hipStream_t stream) {
+  clear_stale_error();
   if (p.fp <= 0 || p.fp % BW_MT || p.mels_pad % BW_KC || p.mels_pad < p.n_mels || p.F > p.fp || p.T < 1) return hipErrorInvalidValue;
   const long long blocks = p.B * (p.fp / BW_MT) * ((p.T + BW_NT - 1) / BW_NT);
   if (blocks < 1 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -892,6 +902,7 @@ hipError_t launch_mel_bw_spec(const MelBwParams& p, hipStream_t stream) {
 }
 
 hipError_t launch_mel_bw_weights(const MelBwParams& p, hipStream_t stream) {
+  clear_stale_error();
   if (p.fp <= 0 || p.fp % BW_NT || p.F > p.fp || p.T < 1 || p.b_per_split < 1) return hipErrorInvalidValue;
   const long long splits = (p.B + p.b_per_split - 1) / p.b_per_split;
   const long long blocks = splits * ((p.n_mels + BW_MT - 1) / BW_MT) * (p.fp / BW_NT);
@@ -902,6 +913,7 @@ hipError_t launch_mel_bw_weights(const MelBwParams& p, hipStream_t stream) {
 
 hipError_t launch_mel_from_logical(const float* w, float* frag, float* wnyq, float* wrm, int n_mels, int n_half, int n_rt,
                                    int n_pass, int fp, hipStream_t stream) {
+  clear_stale_error();
   const long long n4 = (long long)n_pass * n_rt * ST_RB * ST_MEL_BLOCKS * 2 * 64;
   const long long n = std::max(n4, (long long)n_mels * (n_half + 1));
   hipLaunchKernelGGL(mel_from_logical_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, w, frag, wnyq, wrm,

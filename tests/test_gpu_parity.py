@@ -12,6 +12,7 @@ import pytest
 
 import oracle
 from paper_1912_12055_amd import signals
+from tile_sample import sampled_waveforms
 
 pytestmark = pytest.mark.gpu
 
@@ -312,6 +313,10 @@ CQT_CASES = [
     ("36 bins per octave", 2, 30000, 22050, 256, 110.0, 100, 36, 0, 0, True, 0),
     ("Hamming-windowed kernels", 2, 6000, 8000, 128, 220.0, 24, 12, 1024, 2, True, 0),
     ("Blackman-windowed kernels", 2, 6000, 8000, 128, 220.0, 24, 12, 1024, 3, True, 0),
+    # hop 441 does not divide 65,536 taps: one chunk per 16 taps of a 46,025-tap kernel, 2,878 chunk
+    # descriptors per work item -- more than the kernel keeps in LDS at a time (ring of 512)
+    ("46,025-tap kernels whose frames do not overlap in LDS", 2, 40000, 44100, 441, 32.70, 30, 24, 0, 0, True, 0),
+    ("the same, chunk count just past one ring refill", 1, 9000, 44100, 441, 130.0, 6, 24, 0, 0, True, 1),
 ]
 
 
@@ -612,10 +617,12 @@ def test_cqt2010_tone_closed_form_and_wrong_entry_point_on_gpu(nb):
 
 
 # ---------------------------------------------------------------------------------------
-# The two 1,770-waveform workloads at full size, in the launch configuration the bench times;
-# the oracle checks a sample of whole waveforms (first, second, middle, last two).
+# The two 1,770-waveform workloads at full size, in the launch configuration the bench times.
+# Every output (and workspace) starts out as NaN, so an element no workgroup writes stays NaN and fails
+# the finiteness check over all 1,770 waveforms; the oracle checks whole waveforms chosen from the kernel's
+# own tile walk (tests/tile_sample.py): every XCD's range, a group boundary and the partial last group.
 # ---------------------------------------------------------------------------------------
-SAMPLED = [0, 1, 885, 1768, 1769]
+SAMPLED = sampled_waveforms(1770, 345)
 
 
 def _full_batch(cfg_id):
@@ -629,77 +636,106 @@ def _full_batch(cfg_id):
     return x
 
 
+def _poisoned(*shape):
+    import torch
+    return torch.full(shape, float("nan"), dtype=torch.float32, device="cuda:0")
+
+
+def _poisoned_bytes(n):
+    import torch
+    return torch.full(((max(n, 16) + 3) // 4,), float("nan"), dtype=torch.float32, device="cuda:0").view(torch.uint8)
+
+
 @pytest.fixture(scope="module")
 def batch4():
     return _full_batch(4)
 
 
+def test_sample_covers_every_xcd_range():
+    # 4,771 tiles of 128 frames, 597 per XCD: each XCD's range holds at least three sampled waveforms
+    assert len(SAMPLED) >= 24 + 5 and SAMPLED[0] == 0 and SAMPLED[-1] == 1769
+    n_ft = -(-1770 * 345 // 128)
+    per = -(-n_ft // 8)
+    for xcd in range(8):
+        lo, hi = xcd * per * 128 // 345, min(1769, (min(n_ft, (xcd + 1) * per) * 128 - 1) // 345)
+        assert sum(lo <= b <= hi for b in SAMPLED) >= 3, (xcd, lo, hi)
+
+
 def test_stft_config4_full_sampled(nb, batch4):
     import torch
-    _say("stft config 4 (1770 x 176400 @ 44100 Hz) sampled waveforms")
+    _say(f"stft config 4 (1770 x 176400 @ 44100 Hz), {len(SAMPLED)} sampled waveforms")
     plan = nb.nna_plan_stft(sr=44100, n_fft=2048, hop=512, device=0)
-    out = nb.nna_stft(plan, batch4)
+    out = nb.nna_stft(plan, batch4, out=_poisoned(1770, 1025, 345))
     torch.cuda.synchronize()
-    assert tuple(out.shape) == (1770, 1025, 345)
+    assert torch.isfinite(out).all() and (out >= 0).all()  # every element was written
     xs = signals.batch(4, SAMPLED)
     ref = oracle.stft(xs, n_fft=2048, hop=512)
     got = out[SAMPLED].cpu().numpy()
     e = _rel_err(got, ref)
     _say(f"  rel err {e:.3e}")
     assert e < TOL
-    # property that holds for every waveform: Parseval per frame, from the power output
-    assert torch.isfinite(out).all()
+    # every waveform, no oracle needed: the batch cut into three launches of other sizes (other tile walks:
+    # 1,595 / 1,591 / 1,588 tiles instead of 4,771) gives the same bits
+    for lo, hi in ((0, 590), (590, 1180), (1180, 1770)):
+        part = nb.nna_stft(plan, batch4[lo:hi], out=_poisoned(hi - lo, 1025, 345))
+        assert torch.equal(part, out[lo:hi]), (lo, hi)
 
 
 def test_mel_config4_full_sampled(nb, batch4):
     import torch
-    _say("mel config 4 (1770 x 176400 @ 44100 Hz, 128 mels) sampled waveforms")
+    _say(f"mel config 4 (1770 x 176400 @ 44100 Hz, 128 mels), {len(SAMPLED)} sampled waveforms")
     plan = nb.nna_plan_mel(sr=44100, n_fft=2048, hop=512, n_mels=128, fmin=0.0, fmax=22050.0, device=0)
-    out = nb.nna_mel(plan, batch4)
+    out = nb.nna_mel(plan, batch4, out=_poisoned(1770, 128, 345))
     torch.cuda.synchronize()
-    assert tuple(out.shape) == (1770, 128, 345)
+    assert torch.isfinite(out).all() and (out >= 0).all()
     xs = signals.batch(4, SAMPLED)
     ref = oracle.mel(xs, sr=44100, n_fft=2048, hop=512, n_mels=128, fmin=0.0, fmax=22050.0)
     e = _rel_err(out[SAMPLED].cpu().numpy(), ref)
     _say(f"  rel err {e:.3e}")
     assert e < TOL
-    assert torch.isfinite(out).all() and (out >= 0).all()
+    for lo, hi in ((0, 590), (590, 1770)):
+        part = nb.nna_mel(plan, batch4[lo:hi], out=_poisoned(hi - lo, 128, 345))
+        assert torch.equal(part, out[lo:hi]), (lo, hi)
     # the same batch through the launch that also writes the power spectrogram: the same Mel output, bit for
     # bit, and the spectrogram the oracle's STFT gives
     _say("mel + spectrogram in one launch, config 4")
-    mel2, spec = nb.nna_mel_with_stft(plan, batch4)
+    mel2, spec = nb.nna_mel_with_stft(plan, batch4, out=_poisoned(1770, 128, 345), spec=_poisoned(1770, 1025, 345))
     torch.cuda.synchronize()
     assert torch.equal(mel2, out)
+    assert torch.isfinite(spec).all()
     e = _rel_err(spec[SAMPLED].cpu().numpy(), oracle.stft(xs, n_fft=2048, hop=512, fmt=oracle.POWER))
     _say(f"  spectrogram rel err {e:.3e}")
-    assert e < TOL and torch.isfinite(spec).all()
+    assert e < TOL
 
 
 def test_cqt_config5_full_sampled(nb):
     import torch
-    _say("cqt config 5 (1770 x 176400 @ 44100 Hz, 168 bins, 65536 taps) sampled waveforms")
+    _say(f"cqt config 5 (1770 x 176400 @ 44100 Hz, 168 bins, 65536 taps), {len(SAMPLED)} sampled waveforms")
     x = _full_batch(5)
     plan = nb.nna_plan_cqt(sr=44100, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24, n_taps=0, device=0)
     assert plan.info()["taps"] == 65536
-    out = nb.nna_cqt(plan, x)
+    out = nb.nna_cqt(plan, x, out=_poisoned(1770, 168, 345))
     torch.cuda.synchronize()
-    assert tuple(out.shape) == (1770, 168, 345)
+    assert torch.isfinite(out).all() and (out >= 0).all()
     xs = signals.batch(5, SAMPLED)
     ref = oracle.cqt(xs, sr=44100, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24, n_taps=65536)
     e = _rel_err(out[SAMPLED].cpu().numpy(), ref)
     _say(f"  rel err {e:.3e}")
     assert e < TOL
-    assert torch.isfinite(out).all() and (out >= 0).all()
+    for lo, hi in ((0, 590), (590, 1770)):
+        part = nb.nna_cqt(plan, x[lo:hi], out=_poisoned(hi - lo, 168, 345))
+        assert torch.equal(part, out[lo:hi]), (lo, hi)
 
 
 def test_cqt2010v2_config5_full_sampled(nb):
     import torch
-    _say("cqt2010v2 on config 5's batch (1770 x 176400 @ 44100 Hz, 168 bins, 24 / octave) sampled waveforms")
+    _say(f"cqt2010v2 on config 5's batch (1770 x 176400 @ 44100 Hz, 168 bins, 24 / octave), {len(SAMPLED)} sampled waveforms")
     x = _full_batch(5)
     plan = nb.nna_plan_cqt2010v2(sr=44100, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24, device=0)
-    out = nb.nna_cqt2010v2(plan, x)
+    ws = _poisoned_bytes(nb.nna_cqt2010v2_workspace(plan, 1770, 176400))
+    out = nb.nna_cqt2010v2(plan, x, out=_poisoned(1770, 168, 345), workspace=ws)
     torch.cuda.synchronize()
-    assert tuple(out.shape) == (1770, 168, 345)
+    assert torch.isfinite(out).all() and (out >= 0).all()
     xs = signals.batch(5, SAMPLED)
     ref = oracle.cqt2010v2(xs, sr=44100, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24)
     got = out[SAMPLED].cpu().numpy()
@@ -708,22 +744,20 @@ def test_cqt2010v2_config5_full_sampled(nb):
         e = max(e, _rel_err(got[:, 168 - 24 * (a + 1):168 - 24 * a], ref[:, 168 - 24 * (a + 1):168 - 24 * a]))
     _say(f"  rel err {e:.3e}")
     assert e < TOL
-    assert torch.isfinite(out).all() and (out >= 0).all()
 
 
 def test_stft_f16_config4_full_sampled(nb, batch4):
     import torch
-    _say("stft f16 config 4 (1770 x 176400 @ 44100 Hz) sampled waveforms")
+    _say(f"stft f16 config 4 (1770 x 176400 @ 44100 Hz), {len(SAMPLED)} sampled waveforms")
     plan = nb.nna_plan_stft_prec(sr=44100, n_fft=2048, hop=512, precision=nb.NNA_PREC_F16, device=0)
-    out = nb.nna_stft(plan, batch4)
+    out = nb.nna_stft(plan, batch4, out=_poisoned(1770, 1025, 345))
     torch.cuda.synchronize()
-    assert tuple(out.shape) == (1770, 1025, 345)
+    assert torch.isfinite(out).all() and (out >= 0).all()
     xs = signals.batch(4, SAMPLED)
     ref = oracle.stft(xs, n_fft=2048, hop=512)
     e = _rel_err(out[SAMPLED].cpu().numpy(), ref)
     _say(f"  rel err {e:.3e}")
     assert e < TOL
-    assert torch.isfinite(out).all()
 
 
 # ---------------------------------------------------------------------------------------
@@ -732,10 +766,13 @@ def test_stft_f16_config4_full_sampled(nb, batch4):
 # ---------------------------------------------------------------------------------------
 def _check_long_signal(nb, plan, run, oracle_fn, K, hop, L, x):
     import torch
-    out = run(plan, x)
-    torch.cuda.synchronize()
     T = 1 + L // hop
+    bins = nb.nna_out_shape(plan, 1, L)[0]
+    out = run(plan, x, out=_poisoned(1, bins, T))  # NaN wherever no workgroup writes
+    torch.cuda.synchronize()
     assert out.shape[0] == 1 and out.shape[2] == T
+    for lo in range(0, bins, 128):  # in slices: the comparison's temporaries stay small
+        assert torch.isfinite(out[:, lo:lo + 128]).all()
     worst = 0.0
     span = 8 * K  # samples per slice, a multiple of hop
     # the first frames (left mirror), slices inside, the last frames (right mirror)

@@ -166,9 +166,7 @@ def test_random_backward(nb, seed):
     W = nb.nna_plan_get_bank(plan).cpu().numpy()            # rows 1 and 2F-1 read back as zero
     out_shape = oracle.stft_bank(x, W, hop=hop, center=center, fmt=fmt).shape
     gout = rng.standard_normal(out_shape).astype(np.float32)
-    ref_gw, ref_gx = oracle.stft_bank_backward(x, W, gout, hop=hop, center=center, fmt=fmt)
-    ref_gw[1] = 0.0
-    ref_gw[-1] = 0.0
+    ref_gw, ref_gx = oracle.stft_dft_bank_backward(x, W, gout, hop=hop, center=center, fmt=fmt)
     gw, gx = nb.nna_stft_backward(plan, _dev(x), _dev(gout))
     torch.cuda.synchronize()
     for got, ref, name in ((gw, ref_gw, "bank"), (gx, ref_gx, "waveform")):

@@ -13,6 +13,10 @@ import pytest
 
 import oracle
 from paper_1912_12055_amd import signals
+from tile_sample import sampled_waveforms
+
+# full-size backward tests: a third of the forward tests' sample (tests/tile_sample.py), both ends included
+SAMPLED_BW = sorted(set(sampled_waveforms(1770, 345)[::3]) | {0, 1769})
 
 pytestmark = pytest.mark.gpu
 
@@ -148,14 +152,10 @@ def test_backward_parity_small(nb, case):
         e_out = _peak_err(out, ref_out)
     gout = rng.standard_normal(out.shape).astype(np.float32)
     gw, gx = nb.nna_stft_backward(plan, _dev(x), _dev(gout))
-    ref_gw, ref_gx = oracle.stft_bank_backward(x, W, gout, hop=hop, center=center, fmt=fmt)
-    if not scaled:
-        # The sine kernels of bins 0 and n_fft/2 are not parameters of a plain-DFT plan: they are fixed at
-        # zero.  For the magnitude-type outputs the oracle's gradient for them is zero as well; for the
-        # complex output (whose rows 1 and 2F-1 the library defines as identically zero) the oracle, which
-        # treats them as free parameters that happen to be zero, reports one.
-        ref_gw[1] = 0.0
-        ref_gw[-1] = 0.0
+    # The sine kernels of bins 0 and n_fft/2 are not parameters of a plain-DFT plan (they are fixed at
+    # zero): the oracle's variant for banks that start as eq. (DFT2)'s kernels drops their gradient.
+    backward = oracle.stft_bank_backward if scaled else oracle.stft_dft_bank_backward
+    ref_gw, ref_gx = backward(x, W, gout, hop=hop, center=center, fmt=fmt)
     e_w, e_x = _peak_err(gw.cpu().numpy(), ref_gw), _peak_err(gx.cpu().numpy(), ref_gx)
     _say(f"  forward {e_out:.3e}, bank gradient {e_w:.3e}, waveform gradient {e_x:.3e}")
     assert e_out < TOL and e_w < TOL and e_x < TOL
@@ -231,9 +231,7 @@ def test_mel_backward_parity_small(nb, case):
     e_out = _peak_err(out, oracle.mel_bank(x, W, Wmel, hop=hop, power=power))
     gout = rng.standard_normal(out.shape).astype(np.float32)
     gm, gw, gx = nb.nna_mel_backward(plan, _dev(x), _dev(gout))
-    ref_gm, ref_gw, ref_gx = oracle.mel_bank_backward(x, W, Wmel, gout, hop=hop, power=power)
-    ref_gw[1] = 0.0  # the two sine kernels that are not parameters
-    ref_gw[-1] = 0.0
+    ref_gm, ref_gw, ref_gx = oracle.mel_bank_backward(x, W, Wmel, gout, hop=hop, power=power, dft_rows=True)
     e_m, e_w, e_x = _peak_err(gm.cpu().numpy(), ref_gm), _peak_err(gw.cpu().numpy(), ref_gw), _peak_err(gx.cpu().numpy(), ref_gx)
     _say(f"  forward {e_out:.3e}, filterbank gradient {e_m:.3e}, bank gradient {e_w:.3e}, waveform gradient {e_x:.3e}")
     assert e_out < TOL and e_m < TOL and e_w < TOL and e_x < TOL
@@ -245,7 +243,7 @@ def test_mel_backward_parity_small(nb, case):
 
 
 def test_mel_backward_config4_full_sampled(nb):
-    # as for the STFT layer: the full 1,770-waveform launch, upstream gradient on five waveforms
+    # as for the STFT layer: the full 1,770-waveform launch, upstream gradient on a dozen waveforms
     import torch
     _say("mel backward config 4 (1770 x 176400 @ 44100 Hz, 128 mels) sampled waveforms")
     wl = signals.WORKLOADS[4]
@@ -254,7 +252,7 @@ def test_mel_backward_config4_full_sampled(nb):
     for s in range(0, B, 128):
         idx = list(range(s, min(B, s + 128)))
         x[s:s + len(idx)] = torch.from_numpy(signals.batch(4, idx)).to("cuda:0")
-    sampled = [0, 1, 885, 1768, 1769]
+    sampled = SAMPLED_BW
     plan = nb.nna_plan_trainable(nb.nna_plan_mel(sr=44100, n_fft=2048, hop=512, n_mels=128, fmin=0.0, fmax=22050.0, device=0))
     W = nb.nna_plan_get_bank(plan).cpu().numpy().astype(np.float64)
     Wmel = nb.nna_plan_get_mel_weights(plan).cpu().numpy().astype(np.float64)
@@ -265,9 +263,7 @@ def test_mel_backward_config4_full_sampled(nb):
     gm, gw, gx = nb.nna_mel_backward(plan, x, gout)
     torch.cuda.synchronize()
     xs = signals.batch(4, sampled)
-    ref_gm, ref_gw, ref_gx = oracle.mel_bank_backward(xs, W, Wmel, gs, hop=512, power=2.0)
-    ref_gw[1] = 0.0
-    ref_gw[-1] = 0.0
+    ref_gm, ref_gw, ref_gx = oracle.mel_bank_backward(xs, W, Wmel, gs, hop=512, power=2.0, dft_rows=True)
     e_m, e_w = _peak_err(gm.cpu().numpy(), ref_gm), _peak_err(gw.cpu().numpy(), ref_gw)
     e_x = _peak_err(gx[sampled].cpu().numpy(), ref_gx)
     _say(f"  filterbank gradient {e_m:.3e}, bank gradient {e_w:.3e}, waveform gradient {e_x:.3e}")
@@ -279,7 +275,7 @@ def test_mel_backward_config4_full_sampled(nb):
 
 def test_backward_config4_full_sampled(nb):
     # the 1,770-waveform batch in the launch configuration the bench times; the upstream gradient is
-    # non-zero on five waveforms only, so the bank gradient is the oracle's over those five while the
+    # non-zero on a dozen waveforms (spread over every XCD's tile range) only, so the bank gradient is the oracle's over those five while the
     # kernels still sweep every frame, and every other waveform's gradient must be exactly zero
     import torch
     _say("stft backward config 4 (1770 x 176400 @ 44100 Hz) sampled waveforms")
@@ -289,7 +285,7 @@ def test_backward_config4_full_sampled(nb):
     for s in range(0, B, 128):
         idx = list(range(s, min(B, s + 128)))
         x[s:s + len(idx)] = torch.from_numpy(signals.batch(4, idx)).to("cuda:0")
-    sampled = [0, 1, 885, 1768, 1769]
+    sampled = SAMPLED_BW
     plan = nb.nna_plan_trainable(nb.nna_plan_stft(sr=44100, n_fft=2048, hop=512, device=0))
     W = nb.nna_plan_get_bank(plan).cpu().numpy().astype(np.float64)
     T = 1 + L // 512
@@ -391,7 +387,7 @@ def test_cqt_backward_parity_small(nb, case):
 
 def test_cqt_backward_config5_full_sampled(nb):
     # the 1,770-waveform batch with the 168-bin, 65,536-tap bank; the upstream gradient is non-zero on
-    # three waveforms only (see the STFT case above)
+    # seven waveforms only (see the STFT case above)
     import torch
     _say("cqt backward config 5 (1770 x 176400 @ 44100 Hz, 168 bins) sampled waveforms")
     wl = signals.WORKLOADS[5]
@@ -400,7 +396,7 @@ def test_cqt_backward_config5_full_sampled(nb):
     for s in range(0, B, 128):
         idx = list(range(s, min(B, s + 128)))
         x[s:s + len(idx)] = torch.from_numpy(signals.batch(5, idx)).to("cuda:0")
-    sampled = [0, 885, 1769]
+    sampled = SAMPLED_BW[::2] + [1769]
     plan = _cqt_plan(nb, 44100, 32.70, 168, 24, 512, 0, oracle.MAGNITUDE)
     _, mask = oracle.cqt_bank(44100, 32.70, 168, 24)
     W = nb.nna_plan_get_bank(plan).cpu().numpy().astype(np.float64)

@@ -179,6 +179,7 @@ def test_mel_weights_match_oracle_filterbank(sr, n_fft, n_mels, fmin, fmax, scal
     (8000, 128, 220.0, 24, 12, 1024),
     (8000, 100, 220.0, 30, 12, 1000),     # hop does not divide the taps: non-overlapping LDS mode
     (8000, 48, 300.0, 13, 6, 0),          # default taps, hop not a multiple of 16
+    (44100, 441, 32.70, 26, 24, 0),       # non-overlapping mode with 46,025-tap kernels (65,536 taps): 2,878 chunks
 ])
 def test_cqt_bank_matches_oracle_kernels(sr, hop, fmin, nbins, bpo, taps):
     p = nb.nna_plan_cqt(sr=sr, hop=hop, fmin=fmin, n_bins=nbins, bins_per_octave=bpo, n_taps=taps, device=-1)
@@ -349,3 +350,14 @@ def test_bench_refuses_more_than_one_gpu_and_has_no_cpu_fallback():
     if not torch.cuda.is_available():
         r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")], capture_output=True, text=True)
         assert r.returncode != 0 and "no CPU fallback" in r.stderr and not r.stdout.strip()
+
+
+def test_waveforms_shorter_than_four_samples_are_refused():
+    # a 4-tap constant-Q bank pads by 2, so L = 3 would have a mirror image; the loader's 16-byte windows
+    # need four stored samples
+    p = nb.nna_plan_cqt(sr=10, hop=1, fmin=4.0, n_bins=1, bins_per_octave=1, device=-1)
+    assert p.info()["taps"] == 4
+    with pytest.raises(nb.NnaError) as e:
+        nb.nna_out_shape(p, 1, 3)
+    assert e.value.status == nb.NNA_ERR_SHAPE
+    assert nb.nna_out_shape(p, 1, 4) == (1, 5)

@@ -128,6 +128,55 @@ def test_zero_sine_rows_of_the_dft_bank_get_no_gradient():
         assert np.abs(gW[0]).max() > 0 and np.abs(gW[N]).max() > 0
 
 
+def test_dft_bank_parameter_mask_marks_exactly_the_identically_zero_kernels():
+    # eq. (DFT2) written out here, without the clean-up _dft_bank applies: a row is structurally zero when
+    # its exact value sin(2 pi k n / N) vanishes for every integer n, i.e. k n / N is a multiple of 1/2 for
+    # all n -- only k = 0 and k = N/2.  Numerically those rows hold at most rounding noise (< 1e-12) while
+    # every other row has entries of order one.
+    for N in (16, 64, 250):
+        n = np.arange(N)
+        w = 0.5 - 0.5 * np.cos(2 * np.pi * n / N)
+        rows = []
+        for k in range(N // 2 + 1):
+            rows.append(w * np.cos(2 * np.pi * k * n / N))
+            rows.append(-w * np.sin(2 * np.pi * k * n / N))
+        W = np.array(rows)
+        structurally_zero = np.abs(W).max(axis=1) < 1e-12
+        mask = oracle.dft_bank_parameter_mask(N)
+        assert mask.shape == W.shape and mask.dtype == bool
+        assert np.array_equal(~mask.any(axis=1), structurally_zero)
+        assert np.array_equal(mask.all(axis=1), ~structurally_zero)
+        assert list(np.nonzero(structurally_zero)[0]) == [1, N + 1]
+
+
+def test_masked_dft_bank_gradient_differs_from_the_plain_one_only_on_the_masked_rows():
+    # complex output: the plain chain rule reports a gradient for the two zero rows (their outputs are free
+    # to move); the masked variant drops exactly that and nothing else
+    N = 32
+    x = signals.batch(1, B=2, L=300)
+    W = _dft_bank(N)
+    gout = np.random.default_rng(11).standard_normal((2, N + 2, 1 + 300 // 8))
+    full, gx_full = oracle.stft_bank_backward(x, W, gout, hop=8, fmt=oracle.COMPLEX)
+    gW, gx = oracle.stft_dft_bank_backward(x, W, gout, hop=8, fmt=oracle.COMPLEX)
+    assert np.array_equal(gx, gx_full)
+    keep = np.ones(N + 2, dtype=bool)
+    keep[[1, N + 1]] = False
+    assert np.array_equal(gW[keep], full[keep])
+    assert not gW[~keep].any() and np.abs(full[~keep]).max() > 0.1 * np.abs(full).max()
+    # magnitude-type outputs: nothing to drop (test_zero_sine_rows_of_the_dft_bank_get_no_gradient)
+    g2 = np.random.default_rng(12).standard_normal((2, N // 2 + 1, 1 + 300 // 8))
+    a, _ = oracle.stft_bank_backward(x, W, g2, hop=8, fmt=oracle.MAGNITUDE)
+    b, _ = oracle.stft_dft_bank_backward(x, W, g2, hop=8, fmt=oracle.MAGNITUDE)
+    assert np.array_equal(a, b)
+    # and through the Mel layer
+    Wmel = np.abs(np.random.default_rng(13).standard_normal((5, N // 2 + 1)))
+    gm = np.random.default_rng(14).standard_normal((2, 5, 1 + 300 // 8))
+    m0 = oracle.mel_bank_backward(x, W, Wmel, gm, hop=8)
+    m1 = oracle.mel_bank_backward(x, W, Wmel, gm, hop=8, dft_rows=True)
+    assert np.array_equal(m0[0], m1[0]) and np.array_equal(m0[2], m1[2])
+    assert np.array_equal(m0[1][keep], m1[1][keep]) and not m1[1][~keep].any()
+
+
 # ---------------------------------------------------------------------------------------
 # the Mel layer with both stages as weights
 # ---------------------------------------------------------------------------------------
