@@ -262,6 +262,19 @@ nna_status nna_cqt2010v2_workspace(const nna_plan* plan, long long B, long long 
 nna_status nna_cqt2010v2(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
                          void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
+/* nna_cqt2010v2 for callers that cannot allocate device memory for the workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Same plan, kernels and result as
+ * nna_cqt2010v2; the downsampled waveforms go to a workspace of NNA_STATIC_SCRATCH_BYTES that is part of the
+ * library's device image (every GPU the library runs on holds it until the process ends), so the call
+ * itself allocates and frees nothing, on the host or the device.  NNA_ERR_SHAPE, with the sizes in
+ * nna_last_error(), if the batch needs more than that (nna_cqt2010v2_workspace tells how much: about
+ * 3 B L bytes, e.g. 126 waveforms of 176,400 samples).  All calls on one GPU share the one workspace, whose
+ * contents mean nothing between calls (each call overwrites what it reads): two calls that overlap in
+ * time on the same GPU -- from two streams or two threads -- race, and must be ordered by the caller. */
+#define NNA_STATIC_SCRATCH_BYTES (64u << 20)
+nna_status nna_cqt2010v2_static(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
+                                void* hip_stream);
+
 /* out_dev[B, n_bins, T] = constant-Q spectrogram of x_dev[B, L]; plan from nna_plan_cqt2010.
  * Workspace, launches (2*octaves - 1, of the STFT kernel and of the filter) and errors as for
  * nna_cqt2010v2; an octave's waveform must also be longer than n_fft/2. */

@@ -31,7 +31,7 @@ EXPORTS = [
     "nna_plan_cqt2010", "nna_cqt2010",
     "nna_plan_get_mel_weights", "nna_plan_set_mel_weights", "nna_mel_backward_workspace", "nna_mel_backward",
     "nna_plan_trainable", "nna_plan_get_bank", "nna_plan_set_bank", "nna_stft_backward_workspace", "nna_stft_backward",
-    "nna_cqt_backward_workspace", "nna_cqt_backward", "nna_mel_with_stft",
+    "nna_cqt_backward_workspace", "nna_cqt_backward", "nna_mel_with_stft", "nna_cqt2010v2_static",
     "nna_plan_destroy",
     "nna_status_str", "nna_last_error",
 ]
@@ -99,7 +99,7 @@ def lib():
         L.nna_cqt_backward.argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _VP, _VP, _c.c_size_t, _VP]
         L.nna_mel_with_stft.argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _VP]
         L.nna_out_shape.argtypes = [_VP, _LL, _LL, _c.POINTER(_LL), _c.POINTER(_LL)]
-        for name in ("nna_stft", "nna_mel", "nna_cqt", "nna_cqt1992"):
+        for name in ("nna_stft", "nna_mel", "nna_cqt", "nna_cqt1992", "nna_cqt2010v2_static"):
             getattr(L, name).argtypes = [_VP, _VP, _LL, _LL, _VP, _VP]
         L.nna_plan_bank.argtypes = [_VP, _c.POINTER(_c.c_double), _c.c_size_t]
         L.nna_plan_mel_weights.argtypes = [_VP, _c.POINTER(_c.c_double), _c.c_size_t]
@@ -307,6 +307,14 @@ def nna_cqt2010v2(plan: Plan, x, out=None, workspace=None, stream=None):
     """out[B, n_bins, T] = constant-Q spectrogram of x[B, L] by recursive downsampling.  `workspace`: a CUDA
     tensor of at least nna_cqt2010v2_workspace(plan, B, L) bytes (one is made here if None)."""
     return _run_octaves(lib().nna_cqt2010v2, plan, x, out, workspace, stream)
+
+
+NNA_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def nna_cqt2010v2_static(plan: Plan, x, out=None, stream=None):
+    """nna_cqt2010v2 with the library's own static workspace: the call allocates nothing (pass `out`)."""
+    return _run(lib().nna_cqt2010v2_static, plan, x, out, stream)
 
 
 def nna_cqt2010(plan: Plan, x, out=None, workspace=None, stream=None):

@@ -122,6 +122,11 @@ struct nna_plan {
   int n_shift = 0, n_ct = 0, n_kc = 0;
 };
 
+// Workspace of nna_cqt2010v2_static: the downsampled waveforms of two consecutive octaves live here instead
+// of in caller memory.  Every device the library's code is loaded on holds its own copy of the array, at its
+// own address; in host code the name is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[NNA_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using nna::CQ_FRAMES;
@@ -150,19 +155,34 @@ double window_value(int win, long long n, long long N) {
 }
 
 // ---- device helpers -----------------------------------------------------------------
-// The kernels' dynamic-LDS attribute is a per-device setting: set once on every device a plan is built for
-// (that device current).
+// Per-device set-up, done once on every device a plan is built for (that device current): the kernels'
+// dynamic-LDS attribute, and the address of this device's copy of `scratch`.
 std::mutex g_init_mutex;
 std::vector<char> g_init_done;
+std::vector<void*> g_scratch_ptr;
 hipError_t ensure_kernels_init(int device) {
   std::lock_guard<std::mutex> lock(g_init_mutex);
-  if ((int)g_init_done.size() <= device) g_init_done.resize(device + 1, 0);
+  if ((int)g_init_done.size() <= device) {
+    g_init_done.resize(device + 1, 0);
+    g_scratch_ptr.resize(device + 1, nullptr);
+  }
   if (!g_init_done[device]) {
-    const hipError_t e = nna::kernels_init();
+    hipError_t e = nna::kernels_init();
     if (e != hipSuccess) return e;
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[device] = ptr;
     g_init_done[device] = 1;
   }
   return hipSuccess;
+}
+
+// this device's `scratch`, or NULL if no plan was ever built for it
+void* scratch_of(int device) {
+  std::lock_guard<std::mutex> lock(g_init_mutex);
+  return device >= 0 && device < (int)g_scratch_ptr.size() ? g_scratch_ptr[device] : nullptr;
 }
 
 template <typename T>
@@ -1566,6 +1586,31 @@ static nna_status run_octaves(const nna_plan* plan, int kind, const float* x_dev
 nna_status nna_cqt2010v2(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
                          void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
   return run_octaves(plan, NNA_KIND_CQT2010V2, x_dev, B, L, out_dev, workspace_dev, workspace_bytes, hip_stream);
+}
+
+nna_status nna_cqt2010v2_static(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
+                                void* hip_stream) {
+  if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
+  if (plan->kind != NNA_KIND_CQT2010V2) return fail(NNA_ERR_INVALID_ARG, "plan was built for a different transform");
+  if (plan->device < 0) return fail(NNA_ERR_UNSUPPORTED, "host-only plan (device = -1) cannot run transforms");
+  if (B < 1 || L < 1) return fail(NNA_ERR_SHAPE, "B and L must be >= 1");
+  // the workspace the batch needs, before any size is turned into bytes that could wrap around
+  if (B > (long long)NNA_STATIC_SCRATCH_BYTES || L > (long long)NNA_STATIC_SCRATCH_BYTES)
+    return fail(NNA_ERR_SHAPE, "batch too large for the library's static workspace (NNA_STATIC_SCRATCH_BYTES)");
+  size_t need = 0;
+  nna_status s = nna_cqt2010v2_workspace(plan, B, L, &need);
+  if (s != NNA_OK) return s;
+  if (need > (size_t)NNA_STATIC_SCRATCH_BYTES) {
+    char msg[200];
+    std::snprintf(msg, sizeof msg,
+                  "this batch needs %zu bytes of workspace; the library's static workspace holds %zu "
+                  "(NNA_STATIC_SCRATCH_BYTES): use nna_cqt2010v2 with a caller-owned workspace",
+                  need, (size_t)NNA_STATIC_SCRATCH_BYTES);
+    return fail(NNA_ERR_SHAPE, msg);
+  }
+  void* ws = scratch_of(plan->device);  // found when the plan was built, with its device current
+  if (!ws) return fail(NNA_ERR_HIP, "the static workspace of the plan's device was never located");
+  return run_octaves(plan, NNA_KIND_CQT2010V2, x_dev, B, L, out_dev, ws, (size_t)NNA_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 nna_status nna_cqt2010(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
