@@ -51,6 +51,14 @@ def _as_batch(x):
     return x.contiguous().float()
 
 
+def _no_grad_input(x):
+    """Input of a layer whose call has no derivative: a waveform that asks for a gradient would silently get none."""
+    if torch.is_grad_enabled() and x.requires_grad:
+        raise RuntimeError("this layer is not differentiable with respect to its input: build it with "
+                           "trainable=True (STFT, MelSpectrogram, CQT1992v2) or detach the waveform")
+    return _as_batch(x)
+
+
 class _StftFn(torch.autograd.Function):
     """nna_stft with nna_stft_backward as its derivative (kernels W and waveform x)."""
 
@@ -91,10 +99,11 @@ class _Trainable(torch.nn.Module):
 
     def _sync(self, param, setter, tag):
         # Tensor._version counts in-place updates (optimiser steps, load_state_dict, manual edits)
-        seen = getattr(self, "_seen_" + tag, None)
-        if seen != param._version:
+        # alone misses `param.data = ...` and a replaced Parameter object: the storage and the object count too
+        key = (param._version, param.data_ptr(), id(param))
+        if getattr(self, "_seen_" + tag, None) != key:
             setter(self.plan, param.detach())
-            setattr(self, "_seen_" + tag, param._version)
+            setattr(self, "_seen_" + tag, key)
 
 
 class STFT(_Trainable):
@@ -126,9 +135,9 @@ class STFT(_Trainable):
             self.wsin_wcos = torch.nn.Parameter(nb.nna_plan_get_bank(self.plan))
 
     def forward(self, x):
-        x = _as_batch(x)
         if not self.trainable:
-            return nb.nna_stft(self.plan, x)
+            return nb.nna_stft(self.plan, _no_grad_input(x))
+        x = _as_batch(x)
         self._sync(self.wsin_wcos, nb.nna_plan_set_bank, "bank")
         return _StftFn.apply(x, self.wsin_wcos, self)
 
@@ -162,17 +171,17 @@ class MelSpectrogram(_Trainable):
         if return_spectrogram:
             return nb.nna_mel_with_stft(self.plan, x.detach())
         if not self.trainable:
-            return nb.nna_mel(self.plan, x)
+            return nb.nna_mel(self.plan, _no_grad_input(x))
         self._sync(self.wsin_wcos, nb.nna_plan_set_bank, "bank")
         self._sync(self.mel_basis, nb.nna_plan_set_mel_weights, "mel")
         return _MelFn.apply(x, self.wsin_wcos, self.mel_basis, self)
 
 
 def _cqt_bins(sr, fmin, fmax, n_bins, bins_per_octave):
-    if fmax is None:
-        return n_bins
-    import math
-    return int(math.ceil(bins_per_octave * math.log2(fmax / fmin)))  # fmax replaces n_bins, as in the paper's layers
+    # the library's plans take the number of bins; these wrappers do no arithmetic of the method
+    if fmax is not None:
+        raise ValueError("fmax: give n_bins instead (the top bin is fmin * 2^((n_bins - 1) / bins_per_octave))")
+    return n_bins
 
 
 class _CqtFn(torch.autograd.Function):
@@ -220,9 +229,9 @@ class CQT1992v2(_Cqt):
             self.cqt_kernels = torch.nn.Parameter(nb.nna_plan_get_bank(self.plan))
 
     def forward(self, x):
-        x = _as_batch(x)
         if not self.trainable:
-            return nb.nna_cqt(self.plan, x)
+            return nb.nna_cqt(self.plan, _no_grad_input(x))
+        x = _as_batch(x)
         self._sync(self.cqt_kernels, nb.nna_plan_set_bank, "bank")
         return _CqtFn.apply(x, self.cqt_kernels, self)
 
@@ -241,7 +250,7 @@ class CQT1992(_Cqt):
                                         fmt=_format(output_format), device=_device_index(device))
 
     def forward(self, x):
-        return nb.nna_cqt1992(self.plan, _as_batch(x))
+        return nb.nna_cqt1992(self.plan, _no_grad_input(x))
 
 
 class _Cqt2010(_Cqt):
@@ -262,7 +271,7 @@ class _Cqt2010(_Cqt):
         self._workspace = None
 
     def forward(self, x):
-        x = _as_batch(x)
+        x = _no_grad_input(x)
         need = nb.nna_cqt2010v2_workspace(self.plan, x.shape[0], x.shape[1])
         if self._workspace is None or self._workspace.numel() < need or self._workspace.device != x.device:
             self._workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)

@@ -16,7 +16,7 @@ import re
 import subprocess
 import tempfile
 
-from . import build as _build
+from paper_1912_12055_amd import build as _build
 
 _REG = re.compile(r"\bv\[(\d+):(\d+)\]|\bv(\d+)\b")
 

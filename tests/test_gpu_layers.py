@@ -138,3 +138,27 @@ def test_autograd_and_an_optimiser_on_the_trainable_cqt_layer(layers):
     layer(xd.detach())
     from paper_1912_12055_amd import binding as nb
     assert not nb.nna_plan_get_bank(layer.plan).cpu().numpy()[~mask].any()
+
+
+def test_replaced_parameter_storage_reaches_the_library_and_frozen_layers_refuse_gradients(layers):
+    import torch
+    from paper_1912_12055_amd import binding as nb
+    _say("layers: param.data swap, and a waveform that asks for a gradient from a layer without one")
+    x = torch.from_numpy(signals.batch(1, B=2, L=3000)).cuda()
+    stft = layers.STFT(n_fft=64, hop_length=16, trainable=True)
+    before = stft(x).detach().clone()
+    # swapping the storage leaves Tensor._version alone: the layer must still upload the new kernels
+    stft.wsin_wcos.data = 0.5 * stft.wsin_wcos.data.clone()
+    after = stft(x).detach()
+    assert torch.allclose(after, 0.5 * before, rtol=1e-5, atol=1e-7)
+    assert torch.equal(nb.nna_plan_get_bank(stft.plan)[2:-2], stft.wsin_wcos.detach()[2:-2])
+    xg = x.clone().requires_grad_(True)
+    for layer in (layers.STFT(n_fft=64, hop_length=16), layers.MelSpectrogram(sr=8000, n_fft=256, hop_length=64, n_mels=20),
+                  layers.CQT1992v2(sr=8000, hop_length=64, fmin=220.0, n_bins=24),
+                  layers.CQT2010v2(sr=8000, hop_length=64, fmin=220.0, n_bins=24)):
+        with pytest.raises(RuntimeError):
+            layer(xg)
+        with torch.no_grad():
+            layer(xg)
+    with pytest.raises(ValueError):
+        layers.CQT1992v2(sr=8000, fmin=220.0, fmax=2000.0)

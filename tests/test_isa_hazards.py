@@ -1,7 +1,7 @@
 """The hand-scheduled (inline-asm) loads of the kernels must never have their destination
 registers copied, spilled or reused while in flight.  Compiles the kernels to assembly (no GPU
 needed) and scans them; also checks the scanner itself on two hand-written snippets."""
-from paper_1912_12055_amd import isa_check
+import isa_check
 
 
 def test_scanner_flags_a_copy_of_an_in_flight_register():
