@@ -23,6 +23,11 @@ constexpr int ST_NKG = ST_KC / ST_KG;
 constexpr int ST_LDS_ROWS = 160;  // LDS rows per buffer (frames + overlap rows)
 constexpr int ST_LDS_ROWS_WIDE = 192;  // ... of the one-workgroup-per-CU variant (ST_MODE_LIN with six output blocks)
 constexpr int ST_MEL_BLOCKS = 4;  // 32-mel MFMA blocks per pass (128 mels)
+constexpr int ST_RG = 4;          // row tiles one STFT workgroup handles (amortises its start-up, re-uses its frames)
+// folded-frame variant of the STFT / Mel kernel (nna_kernels_fold.hip): two LDS tiles per chunk
+constexpr int SF_LDS_ROWS = 136;  // LDS rows per tile: 128 frames + (J/2 - 1) overlap rows for each of two waveform segments, J <= 8
+constexpr int ST_RING_FOLD_STFT = 4;  // bank fragment groups in flight per wave
+constexpr int ST_RING_FOLD_MEL = 2;
 constexpr int ST_LIN_BLOCKS_MAX = 6;  // ST_MODE_LIN: 4 or 6 output blocks per pass (6 when that saves a pass)
 // what the STFT kernel does with a finished row tile
 constexpr int ST_MODE_STFT = 0;   // per-bin epilogue, output written per row tile
@@ -68,6 +73,13 @@ struct FrameGeom {
 struct StftParams {
   FrameGeom g;
   const float4* bank;   // [row tile][group][ST_RB][64 lanes] float4
+  // folded-frame launch only: the bank over the N/2 folded taps ([row tile of 64 bins][group][Re 0-31, Re 32-63,
+  // Im 0-31, Im 32-63][64 lanes] float4), the alternating-sign window (-1)^n w[n] for bin N/2, w[N/2], and the
+  // number of workgroups of the contraction itself (those behind them compute bin N/2).  `nj` then holds J/2.
+  const float4* bankf;
+  const float* wn;
+  float wmid;
+  long long main_blocks;
   float* out;
   int n_rt;             // row tiles
   int n_chunks;         // LDS chunks per row tile
@@ -237,6 +249,7 @@ struct MelBwParams {
 inline void clear_stale_error() { (void)hipGetLastError(); }
 
 hipError_t launch_stft(const StftParams& p, int mode, hipStream_t stream);
+hipError_t launch_stft_fold(const StftParams& p, int mode, hipStream_t stream);  // ST_MODE_STFT or ST_MODE_MEL
 hipError_t launch_mel_bw_spec(const MelBwParams& p, hipStream_t stream);    // gP
 hipError_t launch_mel_bw_weights(const MelBwParams& p, hipStream_t stream); // gW
 hipError_t launch_mel_from_logical(const float* w, float* frag, float* wnyq, float* wrm, int n_mels, int n_half, int n_rt,

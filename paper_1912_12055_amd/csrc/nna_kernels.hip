@@ -37,7 +37,6 @@ namespace nna {
 // fragments (requested RING groups earlier) and re-requesting its ring slot afterwards.
 // ---------------------------------------------------------------------------------------
 constexpr int ST_RPP = 256 / (ST_KC / 4);          // LDS rows written per loader pass (32)
-constexpr int ST_RG = 4;         // row tiles one STFT workgroup handles (amortises its start-up, re-uses its frames)
 constexpr int ST_RING_STFT = 4;  // bank fragment groups in flight per wave
 constexpr int ST_RING_MEL = 2;   // fewer in the Mel variant: its 64 extra accumulators need the registers
 

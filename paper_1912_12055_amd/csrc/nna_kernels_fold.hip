@@ -1,0 +1,497 @@
+// STFT / Mel contraction with the frame folded about its centre (gfx950 / CDNA4).
+//
+// For the plain DFT bank of eq. (DFT2) with a window that satisfies w[n] = w[N-n] (every window
+// of Sec. III-A in its periodic form does), cos(2 pi k n / N) is even and sin(2 pi k n / N) odd
+// about n = N/2, so with
+//     e[n] = x[n] + x[N-n],   o[n] = x[n] - x[N-n]      (0 < n < N/2),   e[0] = x[0]
+// the transform of one frame is
+//     Re X[k] =  sum_{n < N/2} w[n] cos(2 pi k n / N) e[n]  +  w[N/2] (-1)^k x[N/2]
+//     Im X[k] = -sum_{n < N/2} w[n] sin(2 pi k n / N) o[n]
+// -- N/2 taps instead of N for every kernel: half the multiply-adds of the direct contraction, the
+// same result up to rounding.  It applies to the kernels eq. (DFT2) defines, not to re-spaced
+// frequency axes (sigma(k) is no integer) nor to trained kernels; those keep the direct kernel.
+//
+// Structure (the direct kernel's, see nna_kernels.hip, with these differences):
+//  * A row tile is 64 bins as four 32-row blocks: Re of bins 0-31, Re of bins 32-63 (their B operand is
+//    e), Im of bins 0-31, Im of bins 32-63 (B operand o).  (Re, Im) of a bin then sit in the same
+//    register of the same lane in two accumulators.
+//  * Two LDS tiles per chunk: S[r][c] = xp[sigma(r) hop + c0 + c] (as before, shifts j < J/2) and the
+//    mirrored tile M[r][c] = xp[(sigma(r) + J/2) hop + hop - c0 - c], written to LDS back to front, so
+//    that the partner of tap (j, c) of the frame in row f is M[f + J/2 - 1 - j][c]: both fragments of
+//    a group are aligned 16-byte LDS reads, and e / o cost eight additions per sixteen MFMAs.
+//    Tap 0 has no partner (x[N] belongs to the next frame): its M element is replaced by zero.
+//  * The w[N/2] (-1)^k x[N/2] term is added to the Re accumulators in the epilogue; the sign
+//    alternates with the accumulator register index.
+//  * Bin N/2 (purely real, sum_n (-1)^n w[n] x[n]) is no row of any tile.  The STFT launch carries one
+//    extra workgroup per frame tile that computes it on the vector ALUs from per-hop-segment partial
+//    sums (each sample read once); the Mel launch needs it only when a filter has weight on that bin,
+//    in which case the direct kernel runs instead.
+//  * The tile of chunk it+1 is fetched and written while chunk `it` is multiplied: S requested in
+//    fragment group 0 and written in group 3, M requested in group 4 and written in group 7, through
+//    the same five registers (a chunk has 4 J/2 >= 8 groups).
+#include "nna_device.h"
+
+#include <type_traits>
+#include <utility>
+
+namespace nna {
+
+constexpr int SF_RPP = 256 / (ST_KC / 4);                      // LDS rows written per loader pass (32)
+constexpr int SF_NPASS = (SF_LDS_ROWS + SF_RPP - 1) / SF_RPP;  // 5; the last pass is partial
+constexpr int SF_TILE = SF_LDS_ROWS * ST_PITCH;                // floats per tile
+
+// M is stored back to front: a window the loader would write as it is gets reversed and vice versa
+template <int NPASS>
+__device__ __forceinline__ void flip_fix(TileFix<NPASS>& fx) {
+  if (fx.cls == 2) {
+#pragma unroll
+    for (int p = 0; p < NPASS; ++p) {
+      const unsigned s = fx.sel[p];
+      fx.sel[p] = ((s >> 6) & 3u) | (((s >> 4) & 3u) << 2) | (((s >> 2) & 3u) << 4) | ((s & 3u) << 6);
+    }
+  } else {
+    fx.cls = 1;
+    fx.rev = ~fx.rev;
+  }
+}
+
+// whole-tile LDS write of a tile with SF_LDS_ROWS rows (prologue, and class 2 in the main loop)
+__device__ __forceinline__ void sf_store_chunk(const f32x4 (&R)[SF_NPASS], const TileFix<SF_NPASS>& fx, float* lds, int tid) {
+  store_chunk<ST_KC, ST_PITCH, SF_NPASS>(R, fx, lds, SF_LDS_ROWS, tid);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+  return v;
+}
+
+// Bin N/2 of one frame tile: X[N/2] = sum_n (-1)^n w[n] xp[t hop + n], from partial sums over whole hop
+// segments, P[row][q] = sum_{c < hop} wn[q hop + c] xp[sigma(row) hop + c] (wn = (-1)^n w[n]), so that
+// every sample is read once: X_t[N/2] = sum_q P[row(t) + q][q].
+template <int FMT>
+__device__ __forceinline__ void store_nyquist(float* p, float re) { *p = format_power<FMT>(re * re); }
+
+__device__ void nyquist_tile(const StftParams& P, long long ft, float* lds) {
+  const FrameGeom& g = P.g;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int J = 2 * P.nj;  // P.nj holds J/2 for a folded launch
+  const int Jp = (J + 3) & ~3;  // row pitch of the partial sums: the segments' weights go four at a time
+  const long long f0 = ft * P.tile_frames;
+  if (f0 >= g.n_frames) return;
+  const int m_valid = (int)((g.n_frames - f0) < P.tile_frames ? (g.n_frames - f0) : P.tile_frames);
+  TileMap tm;
+  tm.T = g.T;
+  tm.b0 = f0 / g.T;
+  tm.t0 = (int)(f0 - tm.b0 * g.T);
+  tm.n0 = (g.T - tm.t0) < m_valid ? (g.T - tm.t0) : m_valid;
+  tm.extra = J - 1;
+  const int rows_used = tm.frame_row(m_valid - 1) + tm.extra + 1;
+  const int L = (int)g.L;
+  for (int row = wave; row < rows_used; row += 4) {
+    long long b;
+    int sigma;
+    tm.decode(row, b, sigma);
+    if (b >= g.B) continue;  // uniform over the wave
+    const float* __restrict__ xb = g.x + b * g.L;
+    const int base = sigma * g.hop - g.pad;
+    for (int q0 = 0; q0 < J; q0 += 4) {
+      float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+      for (int c = lane; c < g.hop; c += 64) {
+        const float v = xb[reflect_clamped(base + c, L)];
+        const float* __restrict__ w = P.wn + (long long)q0 * g.hop + c;
+        s0 += w[0] * v;
+        s1 += w[g.hop] * v;
+        s2 += w[2 * g.hop] * v;
+        s3 += w[3 * g.hop] * v;
+      }
+      s0 = wave_sum(s0);
+      s1 = wave_sum(s1);
+      s2 = wave_sum(s2);
+      s3 = wave_sum(s3);
+      if (lane == 0) {
+        float* dst = lds + row * Jp + q0;
+        dst[0] = s0;
+        dst[1] = s1;
+        dst[2] = s2;
+        dst[3] = s3;
+      }
+    }
+  }
+  __syncthreads();
+  if (tid < m_valid) {
+    const long long f = f0 + tid;
+    const long long b = f / g.T;
+    const int t = (int)(f - b * g.T);
+    const float* src = lds + tm.frame_row(tid) * Jp;
+    float re = 0.f;
+    for (int q = 0; q < J; ++q) re += src[q * Jp + q];
+    float* op = P.out + (b * P.out_bins + P.n_half) * g.T + t;
+    if (P.fmt == NNA_OUT_MAGNITUDE)
+      store_nyquist<NNA_OUT_MAGNITUDE>(op, re);
+    else if (P.fmt == NNA_OUT_POWER)
+      store_nyquist<NNA_OUT_POWER>(op, re);
+    else
+      store_nyquist<NNA_OUT_LOG>(op, re);
+  }
+}
+
+// Output of one finished row tile: 64 bins x this wave's 32 frames.  `op` points at (waveform, bin 0,
+// frame) of this lane; register r of lane (h, n) in block blk is bin slot_base + 32 blk + 8 (r/4) + 4 h + r%4.
+template <int FMT>
+__device__ __forceinline__ void fold_store_tile(const f32x16 (&acc)[ST_RB], float* __restrict__ op, long long T,
+                                                int slot_base, int h, int n_half) {
+  float* __restrict__ p = op + (slot_base + 4 * h) * T;
+  if (slot_base + ST_ROWS / 2 <= n_half) {
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float re = acc[blk][r], im = acc[blk + 2][r];
+        p[(32 * blk + 8 * (r >> 2) + (r & 3)) * T] = format_power<FMT>(re * re + im * im);
+      }
+  } else {
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float re = acc[blk][r], im = acc[blk + 2][r];
+        const int k = 32 * blk + 8 * (r >> 2) + (r & 3);
+        if (slot_base + 4 * h + k < n_half) p[k * T] = format_power<FMT>(re * re + im * im);
+      }
+  }
+}
+
+// MODE: ST_MODE_STFT (per-bin epilogue) or ST_MODE_MEL (power of the row tile x filterbank slice).
+template <int MODE, int RING>
+__global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
+  static_assert(ST_NKG % RING == 0, "ring depth must divide the fragment groups per LDS row");
+  constexpr bool MEL = MODE == ST_MODE_MEL;
+  constexpr int NPASS = SF_NPASS;
+  __shared__ __attribute__((aligned(16))) float lds[2][2][SF_TILE];  // [buffer][S, M]
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int h = lane >> 5, n = lane & 31;
+
+  // ---- which work item: (frame tile, row tile range) --------------------------------
+  long long ft;
+  int rt_begin, rt_end, pass = 0;
+  if constexpr (MEL) {
+    ft = (long long)blockIdx.x / P.n_pass;
+    pass = (int)(blockIdx.x % P.n_pass);
+    rt_begin = P.mel_pass_rt[2 * pass];
+    rt_end = P.mel_pass_rt[2 * pass + 1];
+  } else {
+    if ((long long)blockIdx.x >= P.main_blocks) {  // the workgroups behind the contraction's: bin N/2
+      nyquist_tile(P, (long long)blockIdx.x - P.main_blocks, &lds[0][0][0]);
+      return;
+    }
+    // XCD-aware order, as in the direct kernel: ids are dealt round-robin to the 8 XCDs, each XCD walks its
+    // own range of frame tiles in groups of 64 with the row group as the slow index
+    constexpr int GROUP = 64;
+    constexpr int RG = 4;  // row tiles per workgroup
+    const int n_rg = (P.n_rt + RG - 1) / RG;
+    const long long bid = blockIdx.x;
+    const int xcd = (int)(bid & 7);
+    const long long idx = bid >> 3;
+    const long long ft_per_xcd = (P.n_ft + 7) / 8;
+    const long long per_group = (long long)GROUP * n_rg;
+    const long long grp = idx / per_group;
+    const int rem = (int)(idx - grp * per_group);
+    const long long grp_first = grp * GROUP;
+    long long grp_size = ft_per_xcd - grp_first;
+    if (grp_size > GROUP) grp_size = GROUP;
+    if (grp_size <= 0) return;
+    const int rg = rem / (int)grp_size;
+    const int fi = rem - rg * (int)grp_size;
+    if (rg >= n_rg) return;
+    ft = xcd * ft_per_xcd + grp_first + fi;
+    if (ft >= P.n_ft) return;
+    rt_begin = rg * RG;
+    rt_end = rt_begin + RG < P.n_rt ? rt_begin + RG : P.n_rt;
+  }
+
+  const FrameGeom& g = P.g;
+  const int nj2 = P.nj;  // hop-shifts of the folded frame: J / 2
+  const long long f0 = ft * P.tile_frames;
+  const int m_valid = (int)((g.n_frames - f0) < P.tile_frames ? (g.n_frames - f0) : P.tile_frames);
+  TileMap tm;
+  tm.T = g.T;
+  tm.b0 = f0 / g.T;
+  tm.t0 = (int)(f0 - tm.b0 * g.T);
+  tm.n0 = (g.T - tm.t0) < m_valid ? (g.T - tm.t0) : m_valid;
+  tm.extra = nj2 - 1;
+  const int rows_used = tm.frame_row(m_valid - 1) + tm.extra + 1;
+
+  const int n_chunks = P.n_chunks;
+  const int total = (rt_end - rt_begin) * n_chunks;
+  if (total <= 0) return;
+
+  // Row descriptors of the two tiles.  S: sample sigma hop + 4 cv - pad (+ c0).  M: the four samples
+  // (sigma + J/2) hop + hop - 4 cv - {0..3} - pad (- c0), fetched as the stored window that starts at the
+  // lowest of them.
+  RowDesc<NPASS> rd, rdm;
+  build_rowdesc<ST_KC, NPASS>(rd, g, tm, rows_used, tid);
+  {
+    const int cv = tid % (ST_KC / 4), r0 = tid / (ST_KC / 4);
+#pragma unroll
+    for (int p = 0; p < NPASS; ++p) {
+      const int row = p * SF_RPP + r0;
+      long long b;
+      int sigma;
+      tm.decode(row, b, sigma);
+      const bool ok = row < rows_used && b < g.B;
+      rdm.xb[p] = rd.xb[p];
+      rdm.i0[p] = ok ? (sigma + nj2 + 1) * g.hop - 4 * cv - 3 - g.pad : 0;
+    }
+  }
+
+  // this lane's frame
+  const int fi_lane = wave * 32 + n;
+  const bool valid = fi_lane < m_valid;
+  const long long f_lane = f0 + fi_lane;
+  const long long b_lane = valid ? f_lane / g.T : 0;
+  const int t_lane = valid ? (int)(f_lane - b_lane * g.T) : 0;
+  const int row_lane = valid ? tm.frame_row(fi_lane) : 0;
+  const int s_off = row_lane * ST_PITCH + 4 * h;
+  const int m_off = SF_TILE + (row_lane + nj2 - 1) * ST_PITCH + 4 * h;
+  // w[N/2] x[N/2] of this lane's frame (the unpaired centre tap)
+  float xmid = 0.f;
+  if (valid) xmid = g.x[b_lane * g.L + reflect_clamped(t_lane * g.hop + nj2 * g.hop - g.pad, (int)g.L)] * P.wmid;
+  asm volatile("s_waitcnt vmcnt(0)" : "+v"(xmid));
+
+  const int groups_per_rt = n_chunks * nj2 * ST_NKG;
+
+  f32x16 acc[ST_RB];
+#pragma unroll
+  for (int rb = 0; rb < ST_RB; ++rb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
+
+  f32x16 macc[MEL ? ST_MEL_BLOCKS : 1];
+  if constexpr (MEL) {
+#pragma unroll
+    for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) macc[mb][r] = 0.f;
+  }
+
+  // ---- prologue: both tiles of chunk 0 into LDS buffer 0, first RING bank groups requested ----------
+  f32x4 R[NPASS];
+  TileFix<NPASS> fx;
+  issue_chunk<NPASS>(R, fx, g, rd, 0);
+  wait_vm<0>(R);
+  sf_store_chunk(R, fx, &lds[0][0][0], tid);
+  issue_chunk<NPASS>(R, fx, g, rdm, 0);
+  wait_vm<0>(R);
+  flip_fix<NPASS>(fx);
+  sf_store_chunk(R, fx, &lds[0][1][0], tid);
+
+  const unsigned lane_off = (unsigned)lane * 16u;
+  const char* bank_s = reinterpret_cast<const char*>(P.bankf) + ((long long)rt_begin * groups_per_rt) * (ST_RB * 64 * 16);
+  f32x4 bq[RING][ST_RB];
+#pragma unroll
+  for (int s = 0; s < RING; ++s) {
+    gload16_s<0>(bq[s][0], lane_off, bank_s);
+    gload16_s<1024>(bq[s][1], lane_off, bank_s);
+    gload16_s<2048>(bq[s][2], lane_off, bank_s);
+    gload16_s<3072>(bq[s][3], lane_off, bank_s);
+    bank_s += ST_RB * 64 * 16;
+  }
+  __syncthreads();
+
+  // Loads retire in order.  When a group starts, the requests younger than its own ring slot are at least
+  // the other RING-1 slots (tile requests in between only make the wait stricter).  A tile is requested
+  // during one group and written three groups later: the three groups in between each re-request one ring
+  // slot (ST_RB loads), so at most 3 ST_RB requests are younger than the tile's.
+  constexpr int W_SLOT = (RING - 1) * ST_RB;
+  constexpr int W_TILE = 3 * ST_RB;
+  constexpr int TASK_NONE = 0, TASK_LOAD_S = 1, TASK_STORE_S = 2, TASK_LOAD_M = 3, TASK_STORE_M = 4;
+  const int stage_off = (tid / (ST_KC / 4)) * ST_PITCH + (tid % (ST_KC / 4)) * 4;
+  const bool last_pass_row = tid / (ST_KC / 4) < SF_LDS_ROWS - (NPASS - 1) * SF_RPP;  // the partial fifth pass
+
+  int c = 0;  // chunk inside the current row tile
+  int rt = rt_begin;
+  for (int it = 0; it < total; ++it) {
+    const float* cur = &lds[it & 1][0][0];
+    float* const nxt = &lds[(it + 1) & 1][0][0];
+    const int c_next = (c + 1 == n_chunks ? 0 : c + 1) * ST_KC;  // first column of chunk it+1
+    const bool first_chunk = c == 0;
+
+    f32x4 s_cur = *reinterpret_cast<const f32x4*>(cur + s_off);
+    f32x4 m_cur = *reinterpret_cast<const f32x4*>(cur + m_off);
+    if (first_chunk && h == 0) m_cur.x = 0.f;  // tap 0 has no partner inside the frame
+
+    auto group = [&](auto task_tag, int jj, auto kg_tag) {
+      constexpr int TASK = decltype(task_tag)::value;
+      constexpr int kg = decltype(kg_tag)::value;
+      constexpr int s = kg % RING;
+      // the fragments of the next group are read from LDS while this group's MFMAs run
+      const int nj_ = kg + 1 < ST_NKG ? jj : (jj + 1 < nj2 ? jj + 1 : 0);
+      const int nk_ = kg + 1 < ST_NKG ? (kg + 1) * ST_KG : 0;
+      const f32x4 s_nxt = *reinterpret_cast<const f32x4*>(cur + s_off + nj_ * ST_PITCH + nk_);
+      const f32x4 m_nxt = *reinterpret_cast<const f32x4*>(cur + m_off - nj_ * ST_PITCH + nk_);
+      const f32x4 ev = s_cur + m_cur, ov = s_cur - m_cur;
+      const float* ptr[NPASS];
+      TileFix<NPASS> fx_store;
+      if constexpr (TASK == TASK_LOAD_S) prepare_chunk<NPASS>(ptr, fx, g, rd, c_next);
+      if constexpr (TASK == TASK_LOAD_M) {
+        prepare_chunk<NPASS>(ptr, fx, g, rdm, -c_next);
+        flip_fix<NPASS>(fx);
+      }
+      float* stage_dst = nxt + stage_off;
+      if constexpr (TASK == TASK_STORE_S || TASK == TASK_STORE_M) {
+        wait_vm<W_TILE>(R);
+        fx_store = fx;
+        if (TASK == TASK_STORE_M) stage_dst += SF_TILE;
+        if (fx_store.cls == 2) sf_store_chunk(R, fx_store, nxt + (TASK == TASK_STORE_M ? SF_TILE : 0), tid);
+      }
+      wait_vm<W_SLOT>(bq[s][0], bq[s][1], bq[s][2], bq[s][3]);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int m = 0; m < 16; ++m) {
+        const int e = m >> 2, rb = m & 3;
+        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][rb][e], rb < 2 ? ev[e] : ov[e], acc[rb], 0, 0, 0);
+        if (TASK != TASK_NONE && (m & 1) && (m >> 1) < NPASS) {
+          const int p = m >> 1;
+          __builtin_amdgcn_sched_barrier(0);
+          if constexpr (TASK == TASK_STORE_S || TASK == TASK_STORE_M) {
+            if (fx_store.cls != 2 && (p < NPASS - 1 || last_pass_row))
+              *reinterpret_cast<f32x4*>(stage_dst + p * SF_RPP * ST_PITCH) = fixed_up<NPASS>(R[p], fx_store, p);
+          } else {
+            gload16(R[p], ptr[p]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (m >= 12) {
+          // this MFMA was the last reader of fragment quad rb: re-request it (the group RING ahead; the
+          // bank allocation is padded by ST_NKG groups, so the tail stays in bounds)
+          __builtin_amdgcn_sched_barrier(0);
+          if (rb == 0) gload16_s<0>(bq[s][0], lane_off, bank_s);
+          if (rb == 1) gload16_s<1024>(bq[s][1], lane_off, bank_s);
+          if (rb == 2) gload16_s<2048>(bq[s][2], lane_off, bank_s);
+          if (rb == 3) gload16_s<3072>(bq[s][3], lane_off, bank_s);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      bank_s += ST_RB * 64 * 16;
+      s_cur = s_nxt;
+      m_cur = m_nxt;
+    };
+    using K0 = std::integral_constant<int, 0>;
+    using K1 = std::integral_constant<int, 1>;
+    using K2 = std::integral_constant<int, 2>;
+    using K3 = std::integral_constant<int, 3>;
+    using TN = std::integral_constant<int, TASK_NONE>;
+    group(std::integral_constant<int, TASK_LOAD_S>{}, 0, K0{});
+    group(TN{}, 0, K1{});
+    group(TN{}, 0, K2{});
+    group(std::integral_constant<int, TASK_STORE_S>{}, 0, K3{});
+    group(std::integral_constant<int, TASK_LOAD_M>{}, 1, K0{});
+    group(TN{}, 1, K1{});
+    group(TN{}, 1, K2{});
+    group(std::integral_constant<int, TASK_STORE_M>{}, 1, K3{});
+    for (int jj = 2; jj < nj2; ++jj) {
+      group(TN{}, jj, K0{});
+      group(TN{}, jj, K1{});
+      group(TN{}, jj, K2{});
+      group(TN{}, jj, K3{});
+    }
+
+    if (++c == n_chunks) {
+      // ---- epilogue of row tile rt ---------------------------------------------------
+      c = 0;
+      const int slot_base = rt * (ST_ROWS / 2);
+      // the centre tap: Re X[k] += (-1)^k w[N/2] x[N/2]; the parity of a register's bin is that of its index
+#pragma unroll
+      for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[blk][r] += (r & 1) ? -xmid : xmid;
+      if constexpr (!MEL) {
+        if (valid) {
+          float* __restrict__ op = P.out + (b_lane * P.out_bins) * g.T + t_lane;
+          if (P.fmt == NNA_OUT_MAGNITUDE)
+            fold_store_tile<NNA_OUT_MAGNITUDE>(acc, op, g.T, slot_base, h, P.n_half);
+          else if (P.fmt == NNA_OUT_POWER)
+            fold_store_tile<NNA_OUT_POWER>(acc, op, g.T, slot_base, h, P.n_half);
+          else
+            fold_store_tile<NNA_OUT_LOG>(acc, op, g.T, slot_base, h, P.n_half);
+        }
+      } else {
+        // the power (or magnitude) of block blk's 32 bins sits in 16 registers that are, as they stand, the B
+        // operands of 16 MFMAs against the filterbank slice: lane (h, m) supplies W[mel m][bin of (r, h)]
+        const unsigned char* __restrict__ maskp = P.mel_mask + ((long long)pass * P.n_rt + rt) * 2;
+        const float4* __restrict__ wp = P.melw + (((long long)pass * P.n_rt + rt) * 2) * (ST_MEL_BLOCKS * 4 * 64) + lane;
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+          float pw[16];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float re = acc[blk][r], im = acc[blk + 2][r];
+            const float v = re * re + im * im;
+            pw[r] = P.fmt == 1 ? __builtin_amdgcn_sqrtf(v) : v;
+          }
+          const unsigned mask = maskp[blk];
+#pragma unroll
+          for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb) {
+            if (mask & (1u << mb)) {
+#pragma unroll
+              for (int v = 0; v < 4; ++v) {
+                const float4 w = wp[((blk * ST_MEL_BLOCKS + mb) * 4 + v) * 64];
+                macc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w.x, pw[4 * v + 0], macc[mb], 0, 0, 0);
+                macc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w.y, pw[4 * v + 1], macc[mb], 0, 0, 0);
+                macc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w.z, pw[4 * v + 2], macc[mb], 0, 0, 0);
+                macc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(w.w, pw[4 * v + 3], macc[mb], 0, 0, 0);
+              }
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int rb = 0; rb < ST_RB; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
+      ++rt;
+    }
+    __syncthreads();
+  }
+
+  // Drain: the last tile requests and the last RING bank requests are never consumed; their registers
+  // stay reserved until the data has landed.
+  wait_vm<0>(R);
+#pragma unroll
+  for (int s = 0; s < RING; ++s) wait_vm<0>(bq[s][0], bq[s][1], bq[s][2], bq[s][3]);
+
+  if constexpr (MEL) {
+    float* __restrict__ op = P.out + (b_lane * P.n_mels) * g.T + t_lane;
+#pragma unroll
+    for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int mel = pass * (32 * ST_MEL_BLOCKS) + mb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+        if (valid && mel < P.n_mels) op[(long long)mel * g.T] = macc[mb][r];
+      }
+    }
+  }
+}
+
+hipError_t launch_stft_fold(const StftParams& p, int mode, hipStream_t stream) {
+  clear_stale_error();
+  if (p.nj < 2 || p.tile_frames < 1 || p.tile_frames > ST_FRAMES || !p.bankf) return hipErrorInvalidValue;
+  if (mode == ST_MODE_MEL) {
+    const long long blocks = p.n_ft * p.n_pass;
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((stft_fold_kernel<ST_MODE_MEL, ST_RING_FOLD_MEL>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  } else if (mode == ST_MODE_STFT) {
+    if (!p.wn || p.main_blocks <= 0) return hipErrorInvalidValue;
+    const long long blocks = p.main_blocks + p.n_ft;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((stft_fold_kernel<ST_MODE_STFT, ST_RING_FOLD_STFT>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  } else {
+    return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace nna

@@ -81,6 +81,19 @@ struct nna_plan {
 
   double exec_flops = 0, alg_flops = 0;
 
+  // Folded-frame contraction (nna_kernels_fold.hip): plain DFT bank, hop dividing n_fft an even number of
+  // times >= 4.  The direct bank stays (inspection, trainable plans, complex / phase output).
+  bool fold = false;
+  double exec_flops_fold = 0;
+  std::vector<float> h_bankf, h_wn;
+  size_t bankf_floats = 0;
+  float wmid = 0;
+  float* d_bankf = nullptr;
+  float* d_wn = nullptr;
+  float* d_melwf = nullptr;            // Mel weights as the folded kernel's second MFMA reads them
+  unsigned char* d_mel_maskf = nullptr;
+  bool runs_folded() const { return fold && !d_wrm && precision == 0; }
+
   // host copy of the packed bank (host-only plans keep it; device plans drop it after upload)
   std::vector<float> h_bank;
   size_t bank_floats = 0;
@@ -312,6 +325,42 @@ void build_stft_bank(nna_plan* p) {
   p->alg_flops = p->freq_scale ? 2.0 * (double)N * 2.0 * (double)p->n_half : 2.0 * (double)N * (double)N;
 }
 
+// The bank of the folded-frame kernel: Re and Im kernels of eq. (DFT2) over the taps n < N/2 only (they
+// meet x[n] + x[N-n] and x[n] - x[N-n]).  Row tile = 64 bins as four 32-row blocks (Re 0-31, Re 32-63,
+// Im 0-31, Im 32-63); fragment order as in the direct bank with J/2 hop-shifts.
+void build_stft_bank_fold(nna_plan* p) {
+  const int N = p->K, J = p->nj;
+  p->fold = !p->freq_scale && p->sliding && p->precision == 0 && J >= 4 && J % 2 == 0;
+  if (!p->fold) return;
+  const int nj2 = J / 2;
+  const long long G = (long long)p->n_chunks * nj2 * ST_NKG;
+  p->bankf_floats = (size_t)(G * p->n_rt + ST_NKG) * ST_RB * 64 * 4;
+  p->h_bankf.assign(p->bankf_floats, 0.0f);
+  DftTable tab(N, p->window);
+  for (int rt = 0; rt < p->n_rt; ++rt)
+    for (int c = 0; c < p->n_chunks; ++c)
+      for (int j = 0; j < nj2; ++j)
+        for (int kg = 0; kg < ST_NKG; ++kg) {
+          const long long g = ((long long)c * nj2 + j) * ST_NKG + kg;
+          for (int rb = 0; rb < ST_RB; ++rb)
+            for (int lane = 0; lane < 64; ++lane) {
+              const int h = lane >> 5, bin = rt * (ST_ROWS / 2) + (rb & 1) * 32 + (lane & 31);
+              float* dst = &p->h_bankf[((((size_t)rt * G + g) * ST_RB + rb) * 64 + lane) * 4];
+              if (bin >= p->n_half) continue;
+              for (int e = 0; e < 4; ++e) {
+                const int n = stft_tap(p, c, j, kg, h, e);  // < N/2
+                dst[e] = (float)(rb < 2 ? tab.re(bin, n) : tab.im(bin, n));
+              }
+            }
+        }
+  // bin N/2: (-1)^n w[n], padded with zeros to a whole number of four-segment groups
+  p->h_wn.assign((size_t)(J + 3) / 4 * 4 * p->hop, 0.0f);
+  for (int n = 0; n < N; ++n) p->h_wn[n] = (float)((n & 1) ? -tab.w[n] : tab.w[n]);
+  p->wmid = (float)tab.w[N / 2];
+  // per frame: N/2 folded taps x all rows of the row tiles, and the N multiply-adds of bin N/2
+  p->exec_flops_fold = 2.0 * ((double)p->n_chunks * nj2 * ST_KC) * (double)p->n_rt * ST_ROWS + 2.0 * N;
+}
+
 // float16 copy of the STFT bank for the half-precision kernel: same packed rows, cut into row
 // tiles of H_ROWS; each (row tile, chunk, hop-shift) tile of H_ROWS x H_KC halves is contiguous,
 // in the order the kernel walks them.  Needs the sliding layout.
@@ -399,6 +448,9 @@ void build_mel_weights(nna_plan* p, double fmin, double fmax, int scale, int nor
 }
 
 struct MelDeviceLayout {
+  std::vector<float> fragf;         // folded kernel: [pass][rt][blk 2][mb][4][64][4]
+  std::vector<unsigned char> maskf; // folded kernel: [pass][rt][blk 2]
+  double exec_blocks_f = 0;
   std::vector<float> frag;          // [pass][rt][rb][mb][2][64][4]
   std::vector<unsigned char> mask;  // [pass][rt][rb]
   std::vector<float> wnyq;          // [n_mels]
@@ -462,12 +514,46 @@ MelDeviceLayout layout_mel(nna_plan* p) {
           }
         }
   }
+  if (p->fold) {
+    // folded kernel: register r of lane (h, n) in block blk holds bin 64 rt + 32 blk + 8 (r/4) + 4 h + r%4;
+    // as the B operand of MFMA number r it meets, in lane (h, m), the weight of mel m for that bin
+    out.fragf.assign((size_t)p->n_pass * p->n_rt * 2 * ST_MEL_BLOCKS * 4 * 64 * 4, 0.0f);
+    out.maskf.assign((size_t)p->n_pass * p->n_rt * 2, 0);
+    for (int pass = 0; pass < p->n_pass; ++pass)
+      for (int rt = out.pass_rt[2 * pass]; rt < out.pass_rt[2 * pass + 1]; ++rt)
+        for (int blk = 0; blk < 2; ++blk)
+          for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb) {
+            bool any = false;
+            for (int v = 0; v < 4; ++v)
+              for (int lane = 0; lane < 64; ++lane)
+                for (int e = 0; e < 4; ++e) {
+                  const int r = 4 * v + e, mel = pass * per_pass + mb * 32 + (lane & 31);
+                  const int bin = rt * (ST_ROWS / 2) + 32 * blk + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                  const float w = mel < M && bin < p->n_half ? p->h_melW[(size_t)mel * F + bin] : 0.0f;
+                  out.fragf[((((((size_t)pass * p->n_rt + rt) * 2 + blk) * ST_MEL_BLOCKS + mb) * 4 + v) * 64 + lane) * 4 + e] = w;
+                  any = any || w != 0.0f;
+                }
+            if (any) {
+              out.maskf[((size_t)pass * p->n_rt + rt) * 2 + blk] |= (unsigned char)(1u << mb);
+              out.exec_blocks_f += 1;
+            }
+          }
+  }
   // executed flops: every pass sweeps its row tile range with the full DFT contraction
   double dft_exec = 0;
   const double k_exec = (double)p->n_chunks * p->nj * ST_KC;
   for (int pass = 0; pass < p->n_pass; ++pass)
     dft_exec += 2.0 * k_exec * ST_ROWS * (out.pass_rt[2 * pass + 1] - out.pass_rt[2 * pass]);
   p->exec_flops = dft_exec + exec_blocks * 2.0 * 32 * 16;  // 8 MFMA 32x32x2 per block, per frame: 32 mels x 16 slots
+  if (p->fold) {
+    if (p->mel_nyq_any) {
+      p->fold = false;  // a filter weighs bin N/2, which the folded contraction does not produce
+    } else {
+      double rts = 0;
+      for (int pass = 0; pass < p->n_pass; ++pass) rts += out.pass_rt[2 * pass + 1] - out.pass_rt[2 * pass];
+      p->exec_flops_fold = 2.0 * ((double)p->n_chunks * (p->nj / 2) * ST_KC) * ST_ROWS * rts + out.exec_blocks_f * 2.0 * 32 * 32;
+    }
+  }
   p->alg_flops = 2.0 * (double)p->K * (double)p->K + 2.0 * nnz;
   return out;
 }
@@ -789,6 +875,14 @@ nna_status finish_plan(nna_plan* p, nna_plan** out, const MelDeviceLayout* mel) 
       s = upload(&p->d_bank16, p->h_bank16.data(), p->bank16_halves * sizeof(_Float16), "float16 kernel bank");
     if (s == NNA_OK && p->precision == NNA_PREC_F16 && p->bank16s_halves)
       s = upload(&p->d_bank16s, p->h_bank16s.data(), p->bank16s_halves * sizeof(_Float16), "float16 kernel bank (streaming order)");
+    if (s == NNA_OK && p->fold) {
+      s = upload(&p->d_bankf, p->h_bankf.data(), p->bankf_floats * sizeof(float), "folded kernel bank");
+      if (s == NNA_OK) s = upload(&p->d_wn, p->h_wn.data(), p->h_wn.size() * sizeof(float), "alternating window");
+      if (s == NNA_OK && mel && p->kind == NNA_KIND_MEL) {
+        s = upload(&p->d_melwf, mel->fragf.data(), mel->fragf.size() * sizeof(float), "mel weights (folded kernel)");
+        if (s == NNA_OK) s = upload(&p->d_mel_maskf, mel->maskf.data(), mel->maskf.size(), "mel mask (folded kernel)");
+      }
+    }
     if (s == NNA_OK && mel) {
       s = upload(&p->d_melw, mel->frag.data(), mel->frag.size() * sizeof(float), "mel weights");
       if (s == NNA_OK) s = upload(&p->d_mel_mask, mel->mask.data(), mel->mask.size(), "mel mask");
@@ -806,6 +900,7 @@ nna_status finish_plan(nna_plan* p, nna_plan** out, const MelDeviceLayout* mel) 
       return s;
     }
     std::vector<float>().swap(p->h_bank);  // the device copy is the bank from here on
+    std::vector<float>().swap(p->h_bankf);
     std::vector<_Float16>().swap(p->h_bank16);
     std::vector<_Float16>().swap(p->h_bank16s);
   }
@@ -917,6 +1012,45 @@ nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long lo
     hipError_t e = guard.enter(plan->device);
     if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
     e = nna::launch_stft16(P, reinterpret_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    return NNA_OK;
+  }
+  if (plan->runs_folded() && !spec_out && (kind == NNA_KIND_STFT || kind == NNA_KIND_MEL)) {
+    const int nj2 = plan->nj / 2;
+    const int M = pick_tile_frames(ST_FRAMES, T, nj2 - 1, nna::SF_LDS_ROWS);
+    if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
+    nna::StftParams P;
+    std::memset(&P, 0, sizeof(P));
+    P.g = make_geom(plan, x, B, L, T);
+    P.bankf = reinterpret_cast<const float4*>(plan->d_bankf);
+    P.wn = plan->d_wn;
+    P.wmid = plan->wmid;
+    P.out = out;
+    P.n_rt = plan->n_rt;
+    P.n_chunks = plan->n_chunks;
+    P.nj = nj2;
+    P.n_half = plan->n_half;
+    P.packed = 0;
+    P.tile_frames = M;
+    P.n_ft = (P.g.n_frames + M - 1) / M;
+    if (kind == NNA_KIND_MEL) {
+      P.out_bins = plan->n_mels;
+      P.fmt = plan->mel_power;
+      P.melw = reinterpret_cast<const float4*>(plan->d_melwf);
+      P.mel_mask = plan->d_mel_maskf;
+      P.mel_pass_rt = plan->d_mel_pass_rt;
+      P.n_mels = plan->n_mels;
+      P.n_pass = plan->n_pass;
+    } else {
+      P.out_bins = plan->n_half + 1;
+      P.fmt = plan->fmt;
+      const long long ft_per_xcd = (P.n_ft + 7) / 8;
+      P.main_blocks = 8 * ((ft_per_xcd + 63) / 64) * 64 * ((plan->n_rt + nna::ST_RG - 1) / nna::ST_RG);
+    }
+    DeviceGuard guard;
+    hipError_t e = guard.enter(plan->device);
+    if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+    e = nna::launch_stft_fold(P, kind == NNA_KIND_MEL ? nna::ST_MODE_MEL : nna::ST_MODE_STFT, reinterpret_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
     return NNA_OK;
   }
@@ -1181,6 +1315,7 @@ nna_status nna_plan_stft(nna_plan** plan, int sr, int n_fft, int hop, nna_window
     p->K = n_fft;
     p->pad = center ? n_fft / 2 : 0;
     build_stft_bank(p);
+    if (fmt == NNA_OUT_MAGNITUDE || fmt == NNA_OUT_POWER || fmt == NNA_OUT_LOG) build_stft_bank_fold(p);
   } catch (const std::bad_alloc&) {
     delete p;
     return fail(NNA_ERR_ALLOC, "out of host memory while building the DFT bank");
@@ -1294,6 +1429,7 @@ nna_status nna_plan_mel(nna_plan** plan, int sr, int n_fft, int hop, nna_window 
     p->n_mels = n_mels;
     p->mel_power = power == 1.0 ? 1 : 2;
     build_stft_bank(p);
+    build_stft_bank_fold(p);
     build_mel_weights(p, fmin, fmax, scale, norm_area);
     mel = layout_mel(p);
   } catch (const std::bad_alloc&) {
@@ -2396,7 +2532,7 @@ nna_status nna_plan_info(const nna_plan* plan, int* kind, long long* bank_rows, 
                                                   : 2LL * (plan->freq_scale ? plan->n_half : plan->n_half + 1);
   if (taps) *taps = plan->K;
   if (out_bins) *out_bins = plan->out_rows();
-  if (executed_flops_per_frame) *executed_flops_per_frame = plan->exec_flops;
+  if (executed_flops_per_frame) *executed_flops_per_frame = plan->runs_folded() ? plan->exec_flops_fold : plan->exec_flops;
   if (algorithmic_flops_per_frame) *algorithmic_flops_per_frame = plan->alg_flops;
   return NNA_OK;
 }
@@ -2427,6 +2563,10 @@ void nna_plan_destroy(nna_plan* plan) {
     if (guard.enter(plan->device) == hipSuccess) {
       (void)hipFree(plan->d_bank);
       (void)hipFree(plan->d_bank16);
+      (void)hipFree(plan->d_bankf);
+      (void)hipFree(plan->d_wn);
+      (void)hipFree(plan->d_melwf);
+      (void)hipFree(plan->d_mel_maskf);
       (void)hipFree(plan->d_bank16s);
       (void)hipFree(plan->d_wrm);
       (void)hipFree(plan->d_melw_rm);

@@ -696,13 +696,17 @@ def test_mel_config4_full_sampled(nb, batch4):
     for lo, hi in ((0, 590), (590, 1770)):
         part = nb.nna_mel(plan, batch4[lo:hi], out=_poisoned(hi - lo, 128, 345))
         assert torch.equal(part, out[lo:hi]), (lo, hi)
-    # the same batch through the launch that also writes the power spectrogram: the same Mel output, bit for
-    # bit, and the spectrogram the oracle's STFT gives
+    # the same batch through the launch that also writes the power spectrogram (the direct contraction, where
+    # nna_mel folds its frames: the two agree to rounding, not bit for bit), and the spectrogram the oracle's
+    # STFT gives
     _say("mel + spectrogram in one launch, config 4")
     mel2, spec = nb.nna_mel_with_stft(plan, batch4, out=_poisoned(1770, 128, 345), spec=_poisoned(1770, 1025, 345))
     torch.cuda.synchronize()
-    assert torch.equal(mel2, out)
-    assert torch.isfinite(spec).all()
+    assert torch.isfinite(mel2).all() and torch.isfinite(spec).all()
+    assert float((mel2 - out).abs().max()) < 2e-5 * float(out.max())
+    e = _rel_err(mel2[SAMPLED].cpu().numpy(), ref)
+    _say(f"  mel rel err {e:.3e}")
+    assert e < TOL
     e = _rel_err(spec[SAMPLED].cpu().numpy(), oracle.stft(xs, n_fft=2048, hop=512, fmt=oracle.POWER))
     _say(f"  spectrogram rel err {e:.3e}")
     assert e < TOL
@@ -877,8 +881,8 @@ def test_mel_with_stft_parity(nb, case):
     e_m, e_s = _rel_err(mel.cpu().numpy(), ref_mel), _rel_err(spec.cpu().numpy(), ref_spec)
     _say(f"  mel {e_m:.2e}, spectrogram {e_s:.2e}")
     assert e_m < TOL and e_s < TOL
-    # the Mel output is the one nna_mel writes, bit for bit
-    import torch
-    assert torch.equal(mel, nb.nna_mel(plan, _dev(x)))
+    # the Mel output is the one nna_mel writes (to rounding: nna_mel may run the folded contraction)
+    assert _rel_err(nb.nna_mel(plan, _dev(x)).cpu().numpy(), ref_mel) < TOL
+    assert np.abs(mel.cpu().numpy() - nb.nna_mel(plan, _dev(x)).cpu().numpy()).max() < 2e-5 * ref_mel.max()
     with pytest.raises(nb.NnaError):
         nb.nna_mel_with_stft(nb.nna_plan_stft(n_fft=n_fft, hop=hop, device=0), _dev(x))

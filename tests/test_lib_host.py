@@ -115,8 +115,18 @@ def test_stft_bank_is_windowed_dft_kernels(n_fft, hop, win):
     np.testing.assert_allclose(bank[1::2], im, atol=1e-7)
     info = p.info()
     assert info["kind"] == nb.NNA_KIND_STFT and info["out_bins"] == F
-    assert info["algorithmic_flops_per_frame"] == 2.0 * n_fft * n_fft
-    assert info["executed_flops_per_frame"] >= info["algorithmic_flops_per_frame"]
+    assert info["algorithmic_flops_per_frame"] == 2.0 * n_fft * n_fft  # the direct contraction of eq. (DFT2)
+    J = n_fft // hop if n_fft % hop == 0 else 0
+    if J >= 4 and J % 2 == 0 and hop % 32 == 0:
+        # folded frames (x[n] +- x[N-n] against the kernels' first halves): N/2 taps for the N rows of bins
+        # 0 .. N/2-1 (padded to whole 64-bin row tiles), and bin N/2 by itself
+        rows = -(-(n_fft // 2) // 64) * 128
+        assert info["executed_flops_per_frame"] == 2.0 * (n_fft // 2) * rows + 2.0 * n_fft
+    else:
+        assert info["executed_flops_per_frame"] >= info["algorithmic_flops_per_frame"]
+    # a trainable or complex-output plan keeps the direct contraction
+    pc = nb.nna_plan_stft(n_fft=n_fft, hop=hop, win=win, fmt=nb.NNA_OUT_COMPLEX, device=-1)
+    assert pc.info()["executed_flops_per_frame"] >= 2.0 * n_fft * n_fft
 
 
 @pytest.mark.parametrize("scale,sr,n_fft,hop,fmin,fmax,bins", [
