@@ -16,19 +16,26 @@
 //    e), Im of bins 0-31, Im of bins 32-63 (B operand o).  (Re, Im) of a bin then sit in the same
 //    register of the same lane in two accumulators.
 //  * Two LDS tiles per chunk: S[r][c] = xp[sigma(r) hop + c0 + c] (as before, shifts j < J/2) and the
-//    mirrored tile M[r][c] = xp[(sigma(r) + J/2) hop + hop - c0 - c], written to LDS back to front, so
-//    that the partner of tap (j, c) of the frame in row f is M[f + J/2 - 1 - j][c]: both fragments of
-//    a group are aligned 16-byte LDS reads, and e / o cost eight additions per sixteen MFMAs.
-//    Tap 0 has no partner (x[N] belongs to the next frame): its M element is replaced by zero.
+//    mirrored tile, which holds the partners xp[(sigma(r) + J/2) hop + hop - c0 - c] of the same 32 columns
+//    in memory order (LDS column 31 - c).  The partner of taps (j, c..c+3) of the frame in row f is then one
+//    aligned 16-byte read of row f + J/2 - 1 - j with its four elements taken back to front, and e / o
+//    cost eight additions per sixteen MFMAs.  Tap 0 has no partner (x[N] belongs to the next frame): its
+//    element is replaced by zero.
+//  * Waveform rows are addressed as a uniform base plus a 32-bit byte offset per lane.  A wave all of whose
+//    windows of a frame tile lie inside their waveforms (most tiles, most waves) keeps those offsets fixed
+//    and moves the base from chunk to chunk; a wave that serves rows next to a waveform's end recomputes
+//    them per chunk with the mirror classes of the direct kernel's loader.
 //  * The w[N/2] (-1)^k x[N/2] term is added to the Re accumulators in the epilogue; the sign
 //    alternates with the accumulator register index.
 //  * Bin N/2 (purely real, sum_n (-1)^n w[n] x[n]) is no row of any tile.  The STFT launch carries one
 //    extra workgroup per frame tile that computes it on the vector ALUs from per-hop-segment partial
 //    sums (each sample read once); the Mel launch needs it only when a filter has weight on that bin,
 //    in which case the direct kernel runs instead.
-//  * The tile of chunk it+1 is fetched and written while chunk `it` is multiplied: S requested in
-//    fragment group 0 and written in group 3, M requested in group 4 and written in group 7, through
-//    the same five registers (a chunk has 4 J/2 >= 8 groups).
+//  * The tiles of chunk it+1 are fetched and written while chunk `it` is multiplied: S requested in
+//    fragment group 0 and written in group 3, the mirrored tile requested in group 4 and written in group 7,
+//    through the same five registers (a chunk has 4 J/2 >= 8 groups).  Cycle counters read inside the loop
+//    put the wait for a tile at under 20 cycles per chunk; requesting two chunks ahead through a second
+//    register set changed nothing.
 #include "nna_device.h"
 
 #include <type_traits>
@@ -40,18 +47,44 @@ constexpr int SF_RPP = 256 / (ST_KC / 4);                      // LDS rows writt
 constexpr int SF_NPASS = (SF_LDS_ROWS + SF_RPP - 1) / SF_RPP;  // 5; the last pass is partial
 constexpr int SF_TILE = SF_LDS_ROWS * ST_PITCH;                // floats per tile
 
-// M is stored back to front: a window the loader would write as it is gets reversed and vice versa
-template <int NPASS>
-__device__ __forceinline__ void flip_fix(TileFix<NPASS>& fx) {
-  if (fx.cls == 2) {
+// Rows of the two tiles as this thread serves them, one per loader pass.
+struct FoldRows {
+  int roff[SF_NPASS];  // first sample of the row's waveform, in samples from the tile's first waveform
+  int i0s[SF_NPASS];   // S tile: padded-signal index of this thread's first column, chunk 0
+  int i0m[SF_NPASS];   // mirrored tile: the same, chunk 0 (chunk c0 lies c0 samples lower)
+};
+
+// Byte offsets (from the first waveform of the tile) of the NPASS windows of a chunk and how to fix the data
+// up, for a wave that has windows outside their waveforms: the direct loader's classes (nna_device.h).
+__device__ __forceinline__ void fold_offsets(unsigned (&off)[SF_NPASS], TileFix<SF_NPASS>& fx, int L, const int (&roff)[SF_NPASS],
+                                             const int (&i0row)[SF_NPASS], int shift) {
+  unsigned rev = 0;
+  bool gen = false;
 #pragma unroll
-    for (int p = 0; p < NPASS; ++p) {
-      const unsigned s = fx.sel[p];
-      fx.sel[p] = ((s >> 6) & 3u) | (((s >> 4) & 3u) << 2) | (((s >> 2) & 3u) << 4) | ((s & 3u) << 6);
+  for (int p = 0; p < SF_NPASS; ++p) {
+    const int i0 = i0row[p] + shift;
+    int src = i0;
+    if (i0 < 0) src = -i0 - 3;
+    else if (i0 > L - 4) src = 2 * (L - 1) - i0 - 3;
+    rev |= (src != i0 ? 1u : 0u) << p;
+    gen |= (unsigned)src > (unsigned)(L - 4);
+    off[p] = (unsigned)(roff[p] + src) << 2;
+  }
+  fx.rev = rev;
+  fx.cls = __builtin_amdgcn_ballot_w64(rev != 0) != 0 ? 1 : 0;
+  if (__builtin_amdgcn_ballot_w64(gen) != 0) {
+    fx.cls = 2;
+#pragma unroll
+    for (int p = 0; p < SF_NPASS; ++p) {
+      const int i0 = i0row[p] + shift;
+      const int i_0 = reflect_clamped(i0, L), i_1 = reflect_clamped(i0 + 1, L);
+      const int i_2 = reflect_clamped(i0 + 2, L), i_3 = reflect_clamped(i0 + 3, L);
+      int w0 = min(min(i_0, i_1), min(i_2, i_3));
+      w0 = min(w0, L - 4);
+      off[p] = (unsigned)(roff[p] + w0) << 2;
+      fx.sel[p] = (unsigned)min(i_0 - w0, 3) | ((unsigned)min(i_1 - w0, 3) << 2) | ((unsigned)min(i_2 - w0, 3) << 4) |
+                  ((unsigned)min(i_3 - w0, 3) << 6);
     }
-  } else {
-    fx.cls = 1;
-    fx.rev = ~fx.rev;
   }
 }
 
@@ -76,7 +109,8 @@ __device__ void nyquist_tile(const StftParams& P, long long ft, float* lds) {
   const FrameGeom& g = P.g;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int J = 2 * P.nj;  // P.nj holds J/2 for a folded launch
-  const int Jp = (J + 3) & ~3;  // row pitch of the partial sums: the segments' weights go four at a time
+  const int Jp = (J + 3) & ~3;  // the segments' weights go four at a time (the table is zero padded)
+  const int hop = g.hop;
   const long long f0 = ft * P.tile_frames;
   if (f0 >= g.n_frames) return;
   const int m_valid = (int)((g.n_frames - f0) < P.tile_frames ? (g.n_frames - f0) : P.tile_frames);
@@ -88,34 +122,60 @@ __device__ void nyquist_tile(const StftParams& P, long long ft, float* lds) {
   tm.extra = J - 1;
   const int rows_used = tm.frame_row(m_valid - 1) + tm.extra + 1;
   const int L = (int)g.L;
-  for (int row = wave; row < rows_used; row += 4) {
+  // LDS: the weights [Jp][hop] (read by every row), then the partial sums [rows][Jp]
+  float* wl = lds;
+  float* ps = lds + Jp * hop;
+  for (int i = tid * 4; i < Jp * hop; i += 1024) *reinterpret_cast<f32x4*>(wl + i) = *reinterpret_cast<const f32x4*>(P.wn + i);
+  __syncthreads();
+  // eight lanes share a row (each four consecutive columns of every 32), a wave eight rows, the workgroup 32 rows
+  // per step; the loads of eight column blocks are issued together
+  const int sub = lane & 7, rw = lane >> 3;
+  for (int row0 = 0; row0 < rows_used; row0 += 32) {
+    const int row = row0 + wave * 8 + rw;
     long long b;
     int sigma;
     tm.decode(row, b, sigma);
-    if (b >= g.B) continue;  // uniform over the wave
-    const float* __restrict__ xb = g.x + b * g.L;
-    const int base = sigma * g.hop - g.pad;
-    for (int q0 = 0; q0 < J; q0 += 4) {
-      float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-      for (int c = lane; c < g.hop; c += 64) {
-        const float v = xb[reflect_clamped(base + c, L)];
-        const float* __restrict__ w = P.wn + (long long)q0 * g.hop + c;
-        s0 += w[0] * v;
-        s1 += w[g.hop] * v;
-        s2 += w[2 * g.hop] * v;
-        s3 += w[3 * g.hop] * v;
+    const bool ok = row < rows_used && b < g.B;
+    const float* __restrict__ xb = g.x + (ok ? b : 0) * g.L;
+    const int base = ok ? sigma * hop - g.pad : 0;
+    const bool vec = g.vec_ok && base >= 0 && base + hop <= L;
+    for (int q0 = 0; q0 < Jp; q0 += 4) {
+      f32x4 sum[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) sum[u] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      for (int c0 = 0; c0 < hop; c0 += 256) {
+        f32x4 v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int c = c0 + 32 * i + 4 * sub;
+          if (c >= hop) {
+            v[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+          } else if (vec) {
+            v[i] = *reinterpret_cast<const f32x4*>(xb + base + c);
+          } else {
+            v[i] = (f32x4){xb[reflect_clamped(base + c, L)], xb[reflect_clamped(base + c + 1, L)],
+                           xb[reflect_clamped(base + c + 2, L)], xb[reflect_clamped(base + c + 3, L)]};
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int c = c0 + 32 * i + 4 * sub;
+          if (c < hop) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) sum[u] += v[i] * *reinterpret_cast<const f32x4*>(wl + (q0 + u) * hop + c);
+          }
+        }
       }
-      s0 = wave_sum(s0);
-      s1 = wave_sum(s1);
-      s2 = wave_sum(s2);
-      s3 = wave_sum(s3);
-      if (lane == 0) {
-        float* dst = lds + row * Jp + q0;
-        dst[0] = s0;
-        dst[1] = s1;
-        dst[2] = s2;
-        dst[3] = s3;
+      f32x4 r;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        float t = sum[u].x + sum[u].y + sum[u].z + sum[u].w;
+        t += __shfl_xor(t, 1, 64);
+        t += __shfl_xor(t, 2, 64);
+        t += __shfl_xor(t, 4, 64);
+        r[u] = t;
       }
+      if (sub == 0 && row < rows_used) *reinterpret_cast<f32x4*>(ps + row * Jp + q0) = r;
     }
   }
   __syncthreads();
@@ -123,7 +183,7 @@ __device__ void nyquist_tile(const StftParams& P, long long ft, float* lds) {
     const long long f = f0 + tid;
     const long long b = f / g.T;
     const int t = (int)(f - b * g.T);
-    const float* src = lds + tm.frame_row(tid) * Jp;
+    const float* src = ps + tm.frame_row(tid) * Jp;
     float re = 0.f;
     for (int q = 0; q < J; ++q) re += src[q * Jp + q];
     float* op = P.out + (b * P.out_bins + P.n_half) * g.T + t;
@@ -228,13 +288,16 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
   const int total = (rt_end - rt_begin) * n_chunks;
   if (total <= 0) return;
 
-  // Row descriptors of the two tiles.  S: sample sigma hop + 4 cv - pad (+ c0).  M: the four samples
-  // (sigma + J/2) hop + hop - 4 cv - {0..3} - pad (- c0), fetched as the stored window that starts at the
-  // lowest of them.
-  RowDesc<NPASS> rd, rdm;
-  build_rowdesc<ST_KC, NPASS>(rd, g, tm, rows_used, tid);
+  // Row descriptors of the two tiles.  S: sample sigma hop + 4 cv - pad (+ c0).  Mirrored tile: LDS column d
+  // holds sample (sigma + J/2) hop + hop - 31 + d - pad (- c0): the partners of columns 31 - d.
+  FoldRows rows;
+  const char* const xbase = reinterpret_cast<const char*>(g.x + tm.b0 * g.L);
+  const int L = (int)g.L;
+  bool fast;
   {
     const int cv = tid % (ST_KC / 4), r0 = tid / (ST_KC / 4);
+    const int smax = (n_chunks - 1) * ST_KC;  // first column of the last chunk
+    bool bad = false;
 #pragma unroll
     for (int p = 0; p < NPASS; ++p) {
       const int row = p * SF_RPP + r0;
@@ -242,9 +305,13 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
       int sigma;
       tm.decode(row, b, sigma);
       const bool ok = row < rows_used && b < g.B;
-      rdm.xb[p] = rd.xb[p];
-      rdm.i0[p] = ok ? (sigma + nj2 + 1) * g.hop - 4 * cv - 3 - g.pad : 0;
+      // a row nobody reads: any window inside the first waveform will do
+      rows.roff[p] = ok ? (int)((b - tm.b0) * g.L) : 0;
+      rows.i0s[p] = ok ? sigma * g.hop + 4 * cv - g.pad : 0;
+      rows.i0m[p] = ok ? (sigma + nj2 + 1) * g.hop - (ST_KC - 1) + 4 * cv - g.pad : g.hop;
+      bad |= rows.i0s[p] < 0 || rows.i0s[p] + smax > L - 4 || rows.i0m[p] - smax < 0 || rows.i0m[p] > L - 4;
     }
+    fast = __builtin_amdgcn_ballot_w64(bad) == 0;  // every window of every chunk of this wave is a stored window
   }
 
   // this lane's frame
@@ -255,10 +322,10 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
   const int t_lane = valid ? (int)(f_lane - b_lane * g.T) : 0;
   const int row_lane = valid ? tm.frame_row(fi_lane) : 0;
   const int s_off = row_lane * ST_PITCH + 4 * h;
-  const int m_off = SF_TILE + (row_lane + nj2 - 1) * ST_PITCH + 4 * h;
+  const int m_off = SF_TILE + (row_lane + nj2 - 1) * ST_PITCH + (ST_KC - 4) - 4 * h;  // columns run backwards
   // w[N/2] x[N/2] of this lane's frame (the unpaired centre tap)
   float xmid = 0.f;
-  if (valid) xmid = g.x[b_lane * g.L + reflect_clamped(t_lane * g.hop + nj2 * g.hop - g.pad, (int)g.L)] * P.wmid;
+  if (valid) xmid = g.x[b_lane * g.L + reflect_clamped(t_lane * g.hop + nj2 * g.hop - g.pad, L)] * P.wmid;
   asm volatile("s_waitcnt vmcnt(0)" : "+v"(xmid));
 
   const int groups_per_rt = n_chunks * nj2 * ST_NKG;
@@ -280,13 +347,19 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
   // ---- prologue: both tiles of chunk 0 into LDS buffer 0, first RING bank groups requested ----------
   f32x4 R[NPASS];
   TileFix<NPASS> fx;
-  issue_chunk<NPASS>(R, fx, g, rd, 0);
-  wait_vm<0>(R);
-  sf_store_chunk(R, fx, &lds[0][0][0], tid);
-  issue_chunk<NPASS>(R, fx, g, rdm, 0);
-  wait_vm<0>(R);
-  flip_fix<NPASS>(fx);
-  sf_store_chunk(R, fx, &lds[0][1][0], tid);
+  {
+    unsigned off[NPASS];
+    fold_offsets(off, fx, L, rows.roff, rows.i0s, 0);
+#pragma unroll
+    for (int p = 0; p < NPASS; ++p) gload16_s<0>(R[p], off[p], xbase);
+    wait_vm<0>(R);
+    sf_store_chunk(R, fx, &lds[0][0][0], tid);
+    fold_offsets(off, fx, L, rows.roff, rows.i0m, 0);
+#pragma unroll
+    for (int p = 0; p < NPASS; ++p) gload16_s<0>(R[p], off[p], xbase);
+    wait_vm<0>(R);
+    sf_store_chunk(R, fx, &lds[0][1][0], tid);
+  }
 
   const unsigned lane_off = (unsigned)lane * 16u;
   const char* bank_s = reinterpret_cast<const char*>(P.bankf) + ((long long)rt_begin * groups_per_rt) * (ST_RB * 64 * 16);
@@ -304,7 +377,7 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
   // Loads retire in order.  When a group starts, the requests younger than its own ring slot are at least
   // the other RING-1 slots (tile requests in between only make the wait stricter).  A tile is requested
   // during one group and written three groups later: the three groups in between each re-request one ring
-  // slot (ST_RB loads), so at most 3 ST_RB requests are younger than the tile's.
+  // slot (ST_RB loads), so at least 3 ST_RB requests are younger than the tile's.
   constexpr int W_SLOT = (RING - 1) * ST_RB;
   constexpr int W_TILE = 3 * ST_RB;
   constexpr int TASK_NONE = 0, TASK_LOAD_S = 1, TASK_STORE_S = 2, TASK_LOAD_M = 3, TASK_STORE_M = 4;
@@ -321,7 +394,7 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
 
     f32x4 s_cur = *reinterpret_cast<const f32x4*>(cur + s_off);
     f32x4 m_cur = *reinterpret_cast<const f32x4*>(cur + m_off);
-    if (first_chunk && h == 0) m_cur.x = 0.f;  // tap 0 has no partner inside the frame
+    if (first_chunk && h == 0) m_cur.w = 0.f;  // tap 0 (the last element: columns run backwards) has no partner
 
     auto group = [&](auto task_tag, int jj, auto kg_tag) {
       constexpr int TASK = decltype(task_tag)::value;
@@ -331,21 +404,26 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
       const int nj_ = kg + 1 < ST_NKG ? jj : (jj + 1 < nj2 ? jj + 1 : 0);
       const int nk_ = kg + 1 < ST_NKG ? (kg + 1) * ST_KG : 0;
       const f32x4 s_nxt = *reinterpret_cast<const f32x4*>(cur + s_off + nj_ * ST_PITCH + nk_);
-      const f32x4 m_nxt = *reinterpret_cast<const f32x4*>(cur + m_off - nj_ * ST_PITCH + nk_);
-      const f32x4 ev = s_cur + m_cur, ov = s_cur - m_cur;
-      const float* ptr[NPASS];
-      TileFix<NPASS> fx_store;
-      if constexpr (TASK == TASK_LOAD_S) prepare_chunk<NPASS>(ptr, fx, g, rd, c_next);
-      if constexpr (TASK == TASK_LOAD_M) {
-        prepare_chunk<NPASS>(ptr, fx, g, rdm, -c_next);
-        flip_fix<NPASS>(fx);
+      const f32x4 m_nxt = *reinterpret_cast<const f32x4*>(cur + m_off - nj_ * ST_PITCH - nk_);
+      const f32x4 m_rev = {m_cur.w, m_cur.z, m_cur.y, m_cur.x};
+      const f32x4 ev = s_cur + m_rev, ov = s_cur - m_rev;
+      constexpr bool M_ = TASK == TASK_LOAD_M || TASK == TASK_STORE_M;  // which tile a staging task is about
+      unsigned off[NPASS];
+      const char* sb = xbase;
+      if constexpr (TASK == TASK_LOAD_S || TASK == TASK_LOAD_M) {
+        if (fast) {  // the lanes' offsets stay, the base moves with the chunk
+#pragma unroll
+          for (int p = 0; p < NPASS; ++p) off[p] = (unsigned)(rows.roff[p] + (M_ ? rows.i0m[p] : rows.i0s[p])) << 2;
+          sb = xbase + (M_ ? -4 * c_next : 4 * c_next);
+          fx.cls = 0;
+        } else {
+          fold_offsets(off, fx, L, rows.roff, M_ ? rows.i0m : rows.i0s, M_ ? -c_next : c_next);
+        }
       }
-      float* stage_dst = nxt + stage_off;
+      float* stage_dst = nxt + stage_off + (M_ ? SF_TILE : 0);
       if constexpr (TASK == TASK_STORE_S || TASK == TASK_STORE_M) {
         wait_vm<W_TILE>(R);
-        fx_store = fx;
-        if (TASK == TASK_STORE_M) stage_dst += SF_TILE;
-        if (fx_store.cls == 2) sf_store_chunk(R, fx_store, nxt + (TASK == TASK_STORE_M ? SF_TILE : 0), tid);
+        if (fx.cls == 2) sf_store_chunk(R, fx, nxt + (M_ ? SF_TILE : 0), tid);
       }
       wait_vm<W_SLOT>(bq[s][0], bq[s][1], bq[s][2], bq[s][3]);
       __builtin_amdgcn_sched_barrier(0);
@@ -357,10 +435,10 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
           const int p = m >> 1;
           __builtin_amdgcn_sched_barrier(0);
           if constexpr (TASK == TASK_STORE_S || TASK == TASK_STORE_M) {
-            if (fx_store.cls != 2 && (p < NPASS - 1 || last_pass_row))
-              *reinterpret_cast<f32x4*>(stage_dst + p * SF_RPP * ST_PITCH) = fixed_up<NPASS>(R[p], fx_store, p);
+            if (fx.cls != 2 && (p < NPASS - 1 || last_pass_row))
+              *reinterpret_cast<f32x4*>(stage_dst + p * SF_RPP * ST_PITCH) = fixed_up<NPASS>(R[p], fx, p);
           } else {
-            gload16(R[p], ptr[p]);
+            gload16_s<0>(R[p], off[p], sb);
           }
           __builtin_amdgcn_sched_barrier(0);
         }
@@ -384,14 +462,18 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
     using K2 = std::integral_constant<int, 2>;
     using K3 = std::integral_constant<int, 3>;
     using TN = std::integral_constant<int, TASK_NONE>;
-    group(std::integral_constant<int, TASK_LOAD_S>{}, 0, K0{});
+    using TLS = std::integral_constant<int, TASK_LOAD_S>;
+    using TSS = std::integral_constant<int, TASK_STORE_S>;
+    using TLM = std::integral_constant<int, TASK_LOAD_M>;
+    using TSM = std::integral_constant<int, TASK_STORE_M>;
+    group(TLS{}, 0, K0{});
     group(TN{}, 0, K1{});
     group(TN{}, 0, K2{});
-    group(std::integral_constant<int, TASK_STORE_S>{}, 0, K3{});
-    group(std::integral_constant<int, TASK_LOAD_M>{}, 1, K0{});
+    group(TSS{}, 0, K3{});
+    group(TLM{}, 1, K0{});
     group(TN{}, 1, K1{});
     group(TN{}, 1, K2{});
-    group(std::integral_constant<int, TASK_STORE_M>{}, 1, K3{});
+    group(TSM{}, 1, K3{});
     for (int jj = 2; jj < nj2; ++jj) {
       group(TN{}, jj, K0{});
       group(TN{}, jj, K1{});

@@ -330,7 +330,10 @@ void build_stft_bank(nna_plan* p) {
 // Im 0-31, Im 32-63); fragment order as in the direct bank with J/2 hop-shifts.
 void build_stft_bank_fold(nna_plan* p) {
   const int N = p->K, J = p->nj;
-  p->fold = !p->freq_scale && p->sliding && p->precision == 0 && J >= 4 && J % 2 == 0;
+  // (last condition: the workgroups that compute bin N/2 keep its weights, (J rounded up to 4) x hop floats,
+  // and up to 420 rows of partial sums in the kernel's 19,584 floats of LDS)
+  p->fold = !p->freq_scale && p->sliding && p->precision == 0 && J >= 4 && J % 2 == 0 &&
+            (long long)((J + 3) / 4 * 4) * (p->hop + 420) <= 4LL * nna::SF_LDS_ROWS * nna::ST_PITCH;
   if (!p->fold) return;
   const int nj2 = J / 2;
   const long long G = (long long)p->n_chunks * nj2 * ST_NKG;
@@ -1015,10 +1018,13 @@ nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long lo
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
     return NNA_OK;
   }
-  if (plan->runs_folded() && !spec_out && (kind == NNA_KIND_STFT || kind == NNA_KIND_MEL)) {
+  // The folded kernel addresses the rows of a frame tile as 32-bit byte offsets from the tile's first waveform:
+  // the waveforms a tile can span must lie within 2^31 bytes (else the direct kernel runs).
+  const int fold_M = plan->runs_folded() ? pick_tile_frames(ST_FRAMES, T, plan->nj / 2 - 1, nna::SF_LDS_ROWS) : 0;
+  const bool fold_fits = fold_M >= 1 && (1 + (fold_M - 1 + T - 1) / T) * L <= (1LL << 29);
+  if (fold_fits && !spec_out && (kind == NNA_KIND_STFT || kind == NNA_KIND_MEL)) {
     const int nj2 = plan->nj / 2;
-    const int M = pick_tile_frames(ST_FRAMES, T, nj2 - 1, nna::SF_LDS_ROWS);
-    if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
+    const int M = fold_M;
     nna::StftParams P;
     std::memset(&P, 0, sizeof(P));
     P.g = make_geom(plan, x, B, L, T);
