@@ -222,12 +222,18 @@ nna_status nna_out_shape(const nna_plan* plan, long long B, long long L, long lo
                          long long* n_frames);
 
 /* out_dev[B, F, T] = STFT of x_dev[B, L] in the plan's output format; F = n_fft/2+1 for a
- * plan from nna_plan_stft, freq_bins for one from nna_plan_stft_scaled. */
+ * plan from nna_plan_stft, freq_bins for one from nna_plan_stft_scaled.
+ * A plan from nna_plan_stft (magnitude, power or log output, not made trainable) whose hop divides n_fft an
+ * even number of times >= 4 and is a multiple of 32 is computed from the folded frame: the windows of Sec.
+ * III-A satisfy w[n] = w[N-n], so eq. (DFT2)'s real kernels meet x[n] + x[N-n] and its imaginary kernels
+ * x[n] - x[N-n] over n < N/2 only -- half the multiply-adds, the same result to rounding.  Every other
+ * plan runs eq. (DFT2) as it stands. */
 nna_status nna_stft(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
                     void* hip_stream);
 
 /* out_dev[B, n_mels, T] = Mel spectrogram of x_dev[B, L]; plan from nna_plan_mel.
- * The STFT itself is never written to memory. */
+ * The STFT itself is never written to memory.  Folded frames as for nna_stft, unless a filter has weight on
+ * bin n_fft/2 or the plan was made trainable. */
 nna_status nna_mel(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
                    void* hip_stream);
 
@@ -402,7 +408,9 @@ nna_status nna_plan_spectral_kernels(const nna_plan* plan, double* host_out, siz
  * output bins, flops the kernels execute per frame (multiply-add = 2, zero-padded
  * taps they do not skip included) and algorithmic flops per frame (non-zero taps only:
  * 2*K*rows_nonzero for the DFT bank, 4*sum_k N_k for the CQT, plus 2*nnz(W) for Mel;
- * nna_plan_cqt1992: the DFT plus 8 per (constant-Q bin, kept DFT bin)).
+ * nna_plan_cqt1992: the DFT plus 8 per (constant-Q bin, kept DFT bin)).  The algorithmic figure of an
+ * STFT or Mel plan is that of eq. (DFT2) taken directly, 2 K^2; a plan that runs folded frames (see
+ * nna_stft) executes about half of it, K^2 + 2K.
  */
 nna_status nna_plan_info(const nna_plan* plan, int* kind, long long* bank_rows, long long* taps,
                          long long* out_bins, double* executed_flops_per_frame,
