@@ -262,7 +262,7 @@ nna_status nna_cqt2010v2_workspace(const nna_plan* plan, long long B, long long 
 /* out_dev[B, n_bins, T] = constant-Q spectrogram of x_dev[B, L]; plan from nna_plan_cqt2010v2.
  * workspace_dev: caller-owned device memory, 16-byte aligned, of at least the size above; its
  * contents are overwritten and mean nothing afterwards.  Launches 2*octaves - 1 kernels on
- * hip_stream; nothing is allocated.  NNA_ERR_SHAPE if some octave's waveform is not longer
+ * hip_stream (one constant-Q contraction per octave, one decimation between octaves); nothing is allocated.  NNA_ERR_SHAPE if some octave's waveform is not longer
  * than the kernels' half length n_taps/2 or shorter than the filter's frame (fir_taps + 126
  * samples, rounded up to a multiple of 128). */
 nna_status nna_cqt2010v2(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
@@ -380,8 +380,10 @@ nna_status nna_mel_backward(const nna_plan* plan, const float* x_dev, long long 
 /* Downsampling CQT plans only: *part = the plan of octave `index` (0 = top; a plan as from
  * nna_plan_cqt -- from nna_plan_cqt1992 for a plan made by nna_plan_cqt2010 -- for nna_plan_bank /
  * nna_plan_info / nna_plan_cqt_lengths / nna_plan_spectral_kernels), or with index -1 the
- * filter as the kernel runs it: a bank of 64 rows, row r = the taps h shifted right by 2 r
- * (64 consecutive output samples per kernel frame).  The parts belong to `plan`. */
+ * decimation filter, for inspection, as a bank of 64 rows: row r = the taps h shifted right by 2 r
+ * (64 consecutive output samples per frame of 128 input samples).  The decimation itself runs on the
+ * vector ALUs from the same taps split by the parity of their offset from the centre (a half-band design
+ * is zero on the even offsets but for the centre: those are not multiplied).  The parts belong to `plan`. */
 nna_status nna_plan_part(const nna_plan* plan, int index, const nna_plan** part);
 
 /*

@@ -154,12 +154,10 @@ struct CqtParams {
   const CqtItem* items;    // [n_items]
   const CqtChunk* chunks;  // [n_items][n_chunks]
   float* out;
-  long long out_wave_stride;  // elements of `out` per waveform (all bins x frames; raw: samples)
+  long long out_wave_stride;  // elements of `out` per waveform (all bins x frames)
   int bin_offset;          // spectrogram: bin 0 of this bank is row bin_offset of each waveform's output
-  int raw;                 // > 0: the bank's `raw` rows are consecutive output samples of a real signal
-                           //    (frame t, row r -> out[b][raw t + r]); no magnitude is taken
-  int raw_vec;             // raw: 16-byte stores are aligned
-  long long raw_len;       // raw: output samples per waveform
+  int tap_stride;          // taps between consecutive shifts of a chunk (see CqtChunk::jlo)
+  int row_step;            // LDS rows between consecutive shifts: 1, or 16 / hop when the hop divides the chunk
   int n_items;
   int n_chunks;            // stride of `chunks` (largest n_chunks of any item)
   int n_bins;
@@ -261,6 +259,22 @@ hipError_t launch_bank_to_rowmajor(const BankPermuteParams& p, hipStream_t strea
 hipError_t launch_bank_to_logical(const BankPermuteParams& p, hipStream_t stream);    // wrm -> logical
 hipError_t launch_bw_bank(const BwParams& p, hipStream_t stream);      // gw += G x frames
 hipError_t launch_bw_wave(const BwParams& p, hipStream_t stream);      // gx += transposed convolution
+// decimation by two on the vector ALUs (fir_decimate_kernel)
+constexpr int FIR_T = 8;                // outputs per thread
+constexpr int FIR_TILE = 256 * FIR_T;   // outputs per workgroup
+struct FirParams {
+  const float* x;        // [B, L]
+  float* y;              // [B, Ln], Ln = ceil(L / 2)
+  long long B, L, Ln;
+  const float* he;       // taps on the even samples, he[k] = h[half + 2 (ve0 + k)], zero padded to a multiple of 8
+  const float* ho;       // taps on the odd samples, ho[k] = h[half + 2 (vo0 + k) + 1], likewise
+  int ne, no;            // padded tap counts
+  int ve0, vo0;          // first v of each tap list (<= 0)
+  int lds_stream;        // floats of LDS per stream: (FIR_TILE + (span of v) + 8) * 9 / 8, rounded up
+  int vec2;              // 8-byte loads of sample pairs are aligned
+  int vec4_out;          // 16-byte stores are aligned
+};
+hipError_t launch_fir_decimate(const FirParams& p, hipStream_t stream);
 hipError_t launch_cqt(const CqtParams& p, hipStream_t stream);
 size_t cqt_launch_lds_bytes(int n_chunks, int lds_rows);  // dynamic LDS launch_cqt asks for (limit: 160 KB)
 hipError_t launch_cqt_bank_from_logical(const CqtBankParams& p, hipStream_t stream);  // bank and wrm <- logical

@@ -461,7 +461,8 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
   tm.b0 = f0 / g.T;
   tm.t0 = (int)(f0 - tm.b0 * g.T);
   tm.n0 = (g.T - tm.t0) < m_valid ? (g.T - tm.t0) : m_valid;
-  tm.extra = item.jspan - 1;
+  const int row_pitch = P.row_step * CQ_PITCH;  // floats between the LDS rows of consecutive shifts
+  tm.extra = (item.jspan - 1) * P.row_step;
   const int rows_used = tm.frame_row(m_valid - 1) + tm.extra + 1;
   RowDesc<CQ_NPASS> rd;
   build_rowdesc<CQ_KC, CQ_NPASS>(rd, g, tm, rows_used, tid);
@@ -496,7 +497,7 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
 
   auto chunk_shift = [&](int i) {  // (first hop-shift) * hop + (first column) of chunk i
     const int4 v = s_chunks[3 * (i & tbl_mask)];
-    return __builtin_amdgcn_readfirstlane(v.y) * g.hop + __builtin_amdgcn_readfirstlane(v.x);
+    return __builtin_amdgcn_readfirstlane(v.y) * P.tap_stride + __builtin_amdgcn_readfirstlane(v.x);
   };
 
   f32x4 R[CQ_NPASS];
@@ -557,7 +558,7 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
       constexpr int R_ = decltype(rb_tag)::value;
       constexpr int TASK = decltype(task_tag)::value;
       constexpr int slot = decltype(slot_tag)::value;
-      const int nxt_off = jj + 1 < nj ? (jj + 1) * CQ_PITCH : 0;
+      const int nxt_off = jj + 1 < nj ? (jj + 1) * row_pitch : 0;
       f32x4 a_nxt[4];
 #pragma unroll
       for (int fb = 0; fb < 4; ++fb) a_nxt[fb] = *reinterpret_cast<const f32x4*>(base + a_off[fb] + nxt_off);
@@ -600,7 +601,7 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
       constexpr int R_ = decltype(rb_tag)::value;
       const int nj = njr[R_] & 0xffff, nr = njr[R_] >> 16;
       if (R_ >= n_rb || nj == 0) return;
-      const float* base = cur + joff[R_] * CQ_PITCH;
+      const float* base = cur + joff[R_] * row_pitch;
 #pragma unroll
       for (int fb = 0; fb < 4; ++fb) a_cur[fb] = *reinterpret_cast<const f32x4*>(base + a_off[fb]);
       // the ring's slots in order, each with its compile-time index
@@ -644,31 +645,6 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
 #pragma unroll
   for (int i = 0; i < CQ_PREFETCH; ++i) wait_vm<0>(bq[i]);
 
-  if (!GRAD && P.raw) {
-    // real-valued bank (a decimating FIR filter written as P.raw shifted copies): register i of
-    // lane (q, n) in row block rb is output sample P.raw t + 16 rb + 4 q + i of the frame's waveform
-#pragma unroll
-    for (int fb = 0; fb < 4; ++fb) {
-      if (!valid[fb]) continue;
-      const long long fr = f0 + wave * 64 + fb * 16 + n;
-      const long long b = fr / g.T;
-      const long long pos0 = (long long)P.raw * (fr - b * g.T) + 4 * q;
-#pragma unroll
-      for (int r = 0; r < CQ_ITEM_RB; ++r) {
-        if (r >= n_rb) continue;
-        const long long pos = pos0 + 16 * (item.rb_first + r);
-        float* __restrict__ op = P.out + b * P.out_wave_stride + pos;
-        if (P.raw_vec && pos + 3 < P.raw_len) {
-          *reinterpret_cast<f32x4*>(op) = acc[r][fb];
-        } else {
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if (pos + i < P.raw_len) op[i] = acc[r][fb][i];
-        }
-      }
-    }
-    return;
-  }
   const int f = P.fmt;
   if constexpr (GRAD) {
     // lane (q, n), registers 0..3 of row block rb: (Re, Im) of bins 8 rb + 2 q and + 1, frame n of the
@@ -751,6 +727,98 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
 }
 
 // ---------------------------------------------------------------------------------------
+// Decimation by two (Sec. III-C, "Downsampling"): y[m] = sum_i h[i] x~[2 m + i - half], x~ the waveform
+// mirrored at both ends.  Bound by the waveform it streams, so it runs on the vector ALUs: the input is split
+// into its even and odd samples on the way to LDS, xe[i] = x~[s0 + 2 i], xo[i] = x~[s0 + 2 i + 1], and
+//     y[m] = sum_v he[v] xe[m + v] + sum_v ho[v] xo[m + v],   he[v] = h[half + 2 v], ho[v] = h[half + 2 v + 1],
+// two plain filters.  A half-band design has a single non-zero he (its centre tap).  A thread produces eight
+// consecutive outputs from a window of samples that slides through registers: one LDS read per eight
+// multiply-adds.
+// ---------------------------------------------------------------------------------------
+// LDS position of sample i of a stream: one float of padding per eight, so that the threads of a wave, whose
+// windows start eight samples apart, read from different banks (stride 9)
+__device__ __forceinline__ int fir_pos(int i) { return i + (i >> 3); }
+
+// acc[i] += sum_k taps[k] w[off + i + k]; `wt` points at this thread's first window position for off = 0
+__device__ __forceinline__ void fir_stream(float (&acc)[FIR_T], const float* __restrict__ wt, int off, const float* __restrict__ taps, int n) {
+  float win[2 * FIR_T];
+#pragma unroll
+  for (int i = 0; i < FIR_T; ++i) win[i] = wt[fir_pos(off + i)];
+  for (int k0 = 0; k0 < n; k0 += FIR_T) {  // taps are zero padded to a multiple of eight
+#pragma unroll
+    for (int i = 0; i < FIR_T; ++i) win[FIR_T + i] = wt[fir_pos(off + k0 + FIR_T + i)];
+#pragma unroll
+    for (int kk = 0; kk < FIR_T; ++kk) {
+      const float t = taps[k0 + kk];
+#pragma unroll
+      for (int i = 0; i < FIR_T; ++i) acc[i] += t * win[i + kk];
+    }
+#pragma unroll
+    for (int i = 0; i < FIR_T; ++i) win[i] = win[i + FIR_T];
+  }
+}
+
+__global__ __launch_bounds__(256) void fir_decimate_kernel(const FirParams P) {
+  extern __shared__ __attribute__((aligned(16))) float fir_lds[];
+  const int tid = threadIdx.x;
+  const long long b = blockIdx.y;
+  const long long m0 = (long long)blockIdx.x * FIR_TILE;
+  const int vmin = P.ve0 < P.vo0 ? P.ve0 : P.vo0;
+  const int vend = P.ve0 + P.ne > P.vo0 + P.no ? P.ve0 + P.ne : P.vo0 + P.no;  // taps zero padded: ne, no multiples of 8
+  const int n_l = FIR_TILE + (vend - vmin) + 8;  // samples of each stream this workgroup needs
+  float* xe = fir_lds;
+  float* xo = fir_lds + P.lds_stream;
+  const float* __restrict__ xb = P.x + b * P.L;
+  const long long s0 = 2 * (m0 + vmin);
+  const int L = (int)P.L;
+  // sample pairs in batches of four per thread, so that four loads are out before the first is written to LDS
+  for (int i0 = tid; i0 < n_l; i0 += 4 * 256) {
+    float2 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + 256 * u;
+      const long long idx = s0 + 2LL * i;
+      v[u] = make_float2(0.f, 0.f);
+      if (i >= n_l) continue;
+      if (P.vec2 && idx >= 0 && idx + 1 < P.L) {
+        v[u] = *reinterpret_cast<const float2*>(xb + idx);
+      } else {
+        // past either end: the mirror image (far beyond it, where only padding taps reach: any sample)
+        const long long lo = -(long long)L, hi = 2LL * L;
+        const int ic = (int)(idx < lo ? lo : idx > hi ? hi : idx);
+        v[u] = make_float2(xb[reflect_clamped(ic, L)], xb[reflect_clamped(ic + 1, L)]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + 256 * u;
+      if (i < n_l) {
+        xe[fir_pos(i)] = v[u].x;
+        xo[fir_pos(i)] = v[u].y;
+      }
+    }
+  }
+  __syncthreads();
+  const int j8 = tid * FIR_T;
+  if (m0 + j8 >= P.Ln) return;
+  float acc[FIR_T];
+#pragma unroll
+  for (int i = 0; i < FIR_T; ++i) acc[i] = 0.f;
+  // sample j8 + x sits at position 9 tid + fir_pos(x) (j8 = 8 tid)
+  fir_stream(acc, xe + 9 * tid, P.ve0 - vmin, P.he, P.ne);
+  fir_stream(acc, xo + 9 * tid, P.vo0 - vmin, P.ho, P.no);
+  float* __restrict__ op = P.y + b * P.Ln + m0 + j8;
+  if (P.vec4_out && m0 + j8 + FIR_T <= P.Ln) {
+    *reinterpret_cast<f32x4*>(op) = (f32x4){acc[0], acc[1], acc[2], acc[3]};
+    *reinterpret_cast<f32x4*>(op + 4) = (f32x4){acc[4], acc[5], acc[6], acc[7]};
+  } else {
+#pragma unroll
+    for (int i = 0; i < FIR_T; ++i)
+      if (m0 + j8 + i < P.Ln) op[i] = acc[i];
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------
 // LDS per workgroup is 160 KB
@@ -762,11 +830,12 @@ size_t cqt_launch_lds_bytes(int n_chunks, int lds_rows) {
 }
 
 hipError_t kernels_init() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(cqt_kernel<false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)CQ_DYN_LDS_MAX);
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(cqt_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)CQ_DYN_LDS_MAX);
+  const void* kernels[] = {reinterpret_cast<const void*>(cqt_kernel<false>), reinterpret_cast<const void*>(cqt_kernel<true>)};
+  for (const void* k : kernels) {
+    const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)CQ_DYN_LDS_MAX);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_stft(const StftParams& p, int mode, hipStream_t stream) {
@@ -801,15 +870,26 @@ hipError_t launch_stft(const StftParams& p, int mode, hipStream_t stream) {
   return hipGetLastError();
 }
 
+hipError_t launch_fir_decimate(const FirParams& p, hipStream_t stream) {
+  clear_stale_error();
+  const long long tiles = (p.Ln + FIR_TILE - 1) / FIR_TILE;
+  if (tiles < 1 || tiles > 0x7fffffffLL || p.B < 1 || p.B > 65535 || p.L > 0x3fffffffLL) return hipErrorInvalidValue;
+  if ((p.ne & 7) || (p.no & 7) || p.lds_stream < (FIR_TILE + 8) * 9 / 8) return hipErrorInvalidValue;
+  const size_t lds = 2ull * p.lds_stream * sizeof(float);
+  if (lds > 64 * 1024) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(fir_decimate_kernel, dim3((unsigned)tiles, (unsigned)p.B), dim3(256), lds, stream, p);
+  return hipGetLastError();
+}
+
 hipError_t launch_cqt(const CqtParams& p, hipStream_t stream) {
   clear_stale_error();
   const long long blocks = p.n_ft * p.n_items;
   if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  if (p.lds_rows > CQ_LDS_ROWS_MAX) return hipErrorInvalidValue;
+  if (p.lds_rows > CQ_LDS_ROWS_MAX || p.row_step < 1) return hipErrorInvalidValue;
   const size_t lds = cqt_launch_lds_bytes(p.n_chunks, p.lds_rows);
   if (lds > CQ_DYN_LDS_MAX) return hipErrorInvalidValue;
   if (p.gbuf) {
-    if (!p.gout || p.raw || p.rows_pad < 2 * p.n_bins) return hipErrorInvalidValue;
+    if (!p.gout || p.rows_pad < 2 * p.n_bins) return hipErrorInvalidValue;
     hipLaunchKernelGGL(cqt_kernel<true>, dim3((unsigned)blocks), dim3(256), lds, stream, p);
   } else {
     hipLaunchKernelGGL(cqt_kernel<false>, dim3((unsigned)blocks), dim3(256), lds, stream, p);

@@ -37,6 +37,17 @@ struct nna_plan {
   int K = 0;    // taps: n_fft or n_taps
   int pad = 0;  // reflection padding in front
   bool sliding = false;
+  // CQT kernel: taps between consecutive shifts of a chunk's LDS rows (hop when frames share LDS rows, 16 when
+  // the hop divides the 16-tap chunk, 0 when every chunk is fetched per frame), and LDS rows per shift
+  int tap_stride = 0, row_step = 1;
+  // decimation filter: 1 = half-band (zero on the even offsets from its centre, which are then not multiplied)
+  int fir_mode = 0;
+  // the decimation kernel's taps: he[k] = h[half + 2 (fir_ve0 + k)] on the even samples, ho[k] = h[half + 2 (fir_vo0 + k) + 1]
+  // on the odd ones, each zero padded to a multiple of eight
+  std::vector<float> h_fir_he, h_fir_ho;
+  int fir_ve0 = 0, fir_vo0 = 0;
+  float* d_fir_he = nullptr;
+  float* d_fir_ho = nullptr;
 
   // STFT / Mel
   int n_half = 0, n_rt = 0, n_chunks = 0, nj = 1;  // n_half: (Re, Im) slots of the packed bank
@@ -741,17 +752,32 @@ void build_conv_bank(nna_plan* p, ValueFn value) {
   for (int rb = 0; rb < p->n_rb; ++rb) span_max = std::max(span_max, e_rb[rb] - s_rb[rb]);
   const long long shifts_max = (ceil_div(span_max, p->hop) + 1 + CQ_PREFETCH - 1) / CQ_PREFETCH * CQ_PREFETCH;
   p->sliding = J >= 1 && p->hop % CQ_KC == 0 && 16 + 2 * (shifts_max - 1) <= CQ_LDS_ROWS_MAX;
-  // chunk grid: 16-tap column chunks of the hop (shared LDS rows) or of the whole tap range
-  const int n_grid = p->sliding ? p->hop / CQ_KC : (int)ceil_div(K, CQ_KC);
-  // hop-shifts [jlo, jlo + nj) of row block rb that hold taps in grid chunk c
+  p->tap_stride = p->sliding ? p->hop : 0;
+  p->row_step = 1;
+  if (!p->sliding && p->hop < CQ_KC && CQ_KC % p->hop == 0 && K % CQ_KC == 0) {
+    // A hop that divides the 16-tap chunk (the deep octaves of a downsampling plan): the LDS rows still step
+    // by one hop, so tap 16 j + c of the frame in row t is column c of row t + j (16 / hop) -- one tile of 16
+    // columns serves every tap, shift j now counting chunks of 16 taps.
+    const int step = CQ_KC / p->hop;
+    const long long sm = (ceil_div(span_max, CQ_KC) + 1 + CQ_PREFETCH - 1) / CQ_PREFETCH * CQ_PREFETCH;
+    if (16 + 2 * (sm - 1) * step <= CQ_LDS_ROWS_MAX) {
+      p->sliding = true;
+      p->tap_stride = CQ_KC;
+      p->row_step = step;
+    }
+  }
+  const long long ts = p->tap_stride, Jts = p->sliding ? K / ts : 0;
+  // chunk grid: 16-tap column chunks of the shift stride (shared LDS rows) or of the whole tap range
+  const int n_grid = p->sliding ? (int)(ts / CQ_KC) : (int)ceil_div(K, CQ_KC);
+  // shifts [jlo, jlo + nj) of row block rb that hold taps in grid chunk c
   auto shifts_of = [&](int rb, int c, int& jlo, int& nj) {
     const long long c0 = (long long)c * CQ_KC;
     if (p->sliding) {
-      // taps j*hop + c0 + [0, KC) intersect [s, e)  <=>  j*hop + c0 + KC > s  and  j*hop + c0 < e
-      long long lo = floor_div(s_rb[rb] - c0 - CQ_KC, p->hop) + 1;
-      long long hi = ceil_div(e_rb[rb] - c0, p->hop);
+      // taps j*ts + c0 + [0, KC) intersect [s, e)  <=>  j*ts + c0 + KC > s  and  j*ts + c0 < e
+      long long lo = floor_div(s_rb[rb] - c0 - CQ_KC, ts) + 1;
+      long long hi = ceil_div(e_rb[rb] - c0, ts);
       lo = std::max(lo, 0LL);
-      hi = std::min(hi, J);
+      hi = std::min(hi, Jts);
       jlo = (int)lo;
       nj = (int)std::max(0LL, hi - lo);
     } else {
@@ -837,7 +863,7 @@ void build_conv_bank(nna_plan* p, ValueFn value) {
     for (int lane = 0; lane < 64; ++lane) {
       const int q = lane >> 4, r = lane & 15;
       const int row = rb * CQ_ROWS + r;
-      const long long tap0 = (long long)j * (p->sliding ? p->hop : 0) + c0 + 4 * q;
+      const long long tap0 = (long long)j * p->tap_stride + c0 + 4 * q;
       float* dst = &p->h_bank[((size_t)f * 64 + lane) * 4];
       for (int e = 0; e < 4; ++e) dst[e] = row < p->conv_rows && tap0 + e < K ? (float)value(row, tap0 + e) : 0.0f;
     }
@@ -891,6 +917,10 @@ nna_status finish_plan(nna_plan* p, nna_plan** out, const MelDeviceLayout* mel) 
       if (s == NNA_OK) s = upload(&p->d_mel_mask, mel->mask.data(), mel->mask.size(), "mel mask");
       if (s == NNA_OK) s = upload(&p->d_mel_wnyq, mel->wnyq.data(), mel->wnyq.size() * sizeof(float), "mel nyquist weights");
       if (s == NNA_OK) s = upload(&p->d_mel_pass_rt, mel->pass_rt.data(), mel->pass_rt.size() * sizeof(int), "mel pass table");
+    }
+    if (s == NNA_OK && !p->h_fir_he.empty()) {
+      s = upload(&p->d_fir_he, p->h_fir_he.data(), p->h_fir_he.size() * sizeof(float), "decimation taps");
+      if (s == NNA_OK) s = upload(&p->d_fir_ho, p->h_fir_ho.data(), p->h_fir_ho.size() * sizeof(float), "decimation taps");
     }
     if (s == NNA_OK && p->kind == NNA_KIND_CQT) {
       s = upload(&p->d_items, p->h_items.data(), p->h_items.size() * sizeof(nna::CqtItem), "cqt item table");
@@ -1235,6 +1265,30 @@ nna_status make_fir_plan(nna_plan** plan, int fir_taps, int device) {
       return i >= 0 && i < fir_taps ? p->h_fir[i] : 0.0;
     });
     p->alg_flops = 2.0 * fir_taps * FIR_ROWS;  // per frame of FIR_ROWS output samples
+    // The decimation itself runs on the vector ALUs from the taps split by the parity of their offset u = i - half
+    // from the centre: y[m] = sum_v h[half + 2v] x~[2 (m + v)] + sum_v h[half + 2v + 1] x~[2 (m + v) + 1].  A half-band
+    // design is zero on every even offset but 0 (sin(pi u / 2) = 0; in double the taps come out as ~1e-17):
+    // those taps are dropped, which leaves the centre tap on the even samples.
+    const int half = (fir_taps - 1) / 2;
+    double hmax = 0, zmax = 0;
+    for (int i = 0; i < fir_taps; ++i) {
+      hmax = std::max(hmax, std::fabs(p->h_fir[i]));
+      if (i != half && ((i - half) & 1) == 0) zmax = std::max(zmax, std::fabs(p->h_fir[i]));
+    }
+    const bool half_band = zmax <= 1e-12 * hmax;
+    const int ve_lo = half_band ? 0 : -(half / 2), ve_hi = half_band ? 0 : half / 2;
+    const int vo_lo = -((half + 1) / 2), vo_hi = (half - 1) / 2;
+    auto pad4 = [](int n) { return (n + 7) / 8 * 8; };  // the kernel takes eight taps per step
+    p->fir_ve0 = ve_lo;
+    p->fir_vo0 = vo_lo;
+    p->h_fir_he.assign(pad4(ve_hi - ve_lo + 1), 0.0f);
+    p->h_fir_ho.assign(pad4(std::max(vo_hi - vo_lo + 1, 1)), 0.0f);
+    for (int v = ve_lo; v <= ve_hi; ++v) p->h_fir_he[v - ve_lo] = (float)p->h_fir[half + 2 * v];
+    for (int v = vo_lo; v <= vo_hi; ++v) p->h_fir_ho[v - vo_lo] = (float)p->h_fir[half + 2 * v + 1];
+    p->fir_mode = half_band ? 1 : 0;
+    // flops per frame of FIR_ROWS output samples: the taps kept
+    p->alg_flops = 2.0 * ((ve_hi - ve_lo + 1) + (vo_hi - vo_lo + 1)) * FIR_ROWS;
+    p->exec_flops = 2.0 * (double)(p->h_fir_he.size() + p->h_fir_ho.size()) * FIR_ROWS;
   } catch (const std::bad_alloc&) {
     delete p;
     return fail(NNA_ERR_ALLOC, "out of host memory while building the filter bank");
@@ -1244,22 +1298,21 @@ nna_status make_fir_plan(nna_plan** plan, int fir_taps, int device) {
 
 // one launch of the CQT kernel: `sub`'s bank over T frames of each of the B waveforms in x
 nna_status run_conv(const nna_plan* sub, const float* x, long long B, long long L, long long T, float* out,
-                    long long out_wave_stride, int bin_offset, long long raw_len, void* hip_stream) {
-  const int extra = sub->max_jspan - 1;
+                    long long out_wave_stride, int bin_offset, void* hip_stream) {
+  const int extra = (sub->max_jspan - 1) * sub->row_step;
   const int M = pick_tile_frames(CQ_FRAMES, T, extra, CQ_LDS_ROWS_MAX);
   if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
   nna::CqtParams P;
   std::memset(&P, 0, sizeof(P));
   P.g = make_geom(sub, x, B, L, T);
+  P.tap_stride = sub->tap_stride;
+  P.row_step = sub->row_step;
   P.bank = reinterpret_cast<const float4*>(sub->d_bank);
   P.items = sub->d_items;
   P.chunks = sub->d_chunks;
   P.out = out;
   P.out_wave_stride = out_wave_stride;
   P.bin_offset = bin_offset;
-  P.raw = raw_len > 0 ? sub->conv_rows : 0;
-  P.raw_len = raw_len;
-  P.raw_vec = (raw_len % 4 == 0) && ((reinterpret_cast<uintptr_t>(out) & 15) == 0) ? 1 : 0;
   P.n_items = (int)sub->h_items.size();
   P.n_chunks = sub->n_chunks;
   P.n_bins = sub->n_bins;
@@ -1270,6 +1323,33 @@ nna_status run_conv(const nna_plan* sub, const float* x, long long B, long long 
   P.n_ft = (P.g.n_frames + M - 1) / M;
   hipError_t e = nna::launch_cqt(P, reinterpret_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  return NNA_OK;
+}
+
+// one decimation step: y[B, Ln] from x[B, L], Ln = ceil(L / 2) (arguments checked by the caller)
+nna_status run_fir(const nna_plan* fir, const float* x, long long B, long long L, float* y, long long Ln, void* hip_stream) {
+  nna::FirParams P;
+  std::memset(&P, 0, sizeof(P));
+  P.L = L;
+  P.Ln = Ln;
+  P.he = fir->d_fir_he;
+  P.ho = fir->d_fir_ho;
+  P.ne = (int)fir->h_fir_he.size();
+  P.no = (int)fir->h_fir_ho.size();
+  P.ve0 = fir->fir_ve0;
+  P.vo0 = fir->fir_vo0;
+  const int vmin = std::min(P.ve0, P.vo0), vend = std::max(P.ve0 + P.ne, P.vo0 + P.no);
+  P.lds_stream = (nna::FIR_TILE + (vend - vmin) + 16) * 9 / 8 + 8;  // one float of padding per eight samples
+  // the grid's second dimension holds at most 65,535 waveforms
+  for (long long b0 = 0; b0 < B; b0 += 65535) {
+    P.B = std::min(B - b0, 65535LL);
+    P.x = x + b0 * L;
+    P.y = y + b0 * Ln;
+    P.vec2 = ((reinterpret_cast<uintptr_t>(P.x) & 7) == 0 && (L % 2 == 0 || P.B == 1)) ? 1 : 0;
+    P.vec4_out = ((reinterpret_cast<uintptr_t>(P.y) & 15) == 0 && (Ln % 4 == 0 || P.B == 1)) ? 1 : 0;
+    const hipError_t e = nna::launch_fir_decimate(P, reinterpret_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  }
   return NNA_OK;
 }
 
@@ -1692,12 +1772,9 @@ static nna_status run_octaves(const nna_plan* plan, int kind, const float* x_dev
   for (int a = 0; a < n_oct; ++a) {
     const nna_plan* sub = plan->octave[a];
     const int lds_rows = sub->kind == NNA_KIND_CQT1992 && sub->lin_blocks == 6 ? nna::ST_LDS_ROWS_WIDE : ST_LDS_ROWS;
-    const int M = kind == NNA_KIND_CQT2010V2 ? pick_tile_frames(CQ_FRAMES, T, sub->max_jspan - 1, CQ_LDS_ROWS_MAX)
+    const int M = kind == NNA_KIND_CQT2010V2 ? pick_tile_frames(CQ_FRAMES, T, (sub->max_jspan - 1) * sub->row_step, CQ_LDS_ROWS_MAX)
                                              : pick_tile_frames(ST_FRAMES, T, sub->nj - 1, lds_rows);
-    const int Mf = a + 1 < n_oct ? pick_tile_frames(CQ_FRAMES, (La[a + 1] + FIR_ROWS - 1) / FIR_ROWS,
-                                                    plan->fir->max_jspan - 1, CQ_LDS_ROWS_MAX)
-                                 : 1;
-    if (M < 1 || Mf < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
+    if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
   }
   float* buf[2] = {static_cast<float*>(workspace_dev), nullptr};
   if (n_oct > 2) buf[1] = reinterpret_cast<float*>(static_cast<char*>(workspace_dev) + ws_round(B * ((L + 1) / 2)));
@@ -1709,7 +1786,7 @@ static nna_status run_octaves(const nna_plan* plan, int kind, const float* x_dev
     int lo, hi;
     octave_bins(plan->n_bins, plan->bpo, a, lo, hi);
     if (kind == NNA_KIND_CQT2010V2)
-      s = run_conv(plan->octave[a], cur, B, La[a], T, out_dev, (long long)plan->n_bins * T, lo, 0, hip_stream);
+      s = run_conv(plan->octave[a], cur, B, La[a], T, out_dev, (long long)plan->n_bins * T, lo, hip_stream);
     else
       s = run_stft_core(plan->octave[a], NNA_KIND_CQT1992, cur, B, La[a], T, out_dev, (long long)plan->n_bins * T, lo,
                         hip_stream);
@@ -1717,8 +1794,7 @@ static nna_status run_octaves(const nna_plan* plan, int kind, const float* x_dev
     if (a + 1 < n_oct) {
       float* dst = buf[a & 1];
       const long long Ln = La[a + 1];
-      if ((s = run_conv(plan->fir, cur, B, La[a], (Ln + FIR_ROWS - 1) / FIR_ROWS, dst, Ln, 0, Ln, hip_stream)) != NNA_OK)
-        return s;
+      if ((s = run_fir(plan->fir, cur, B, La[a], dst, Ln, hip_stream)) != NNA_OK) return s;
       cur = dst;
     }
   }
@@ -1819,7 +1895,7 @@ nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long l
   DeviceGuard guard;
   hipError_t e = guard.enter(plan->device);
   if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
-  return run_conv(plan, x_dev, B, L, T, out_dev, (long long)plan->out_rows() * T, 0, 0, hip_stream);
+  return run_conv(plan, x_dev, B, L, T, out_dev, (long long)plan->out_rows() * T, 0, hip_stream);
 }
 
 // ---- trainable Fourier kernels (Sec. IV-C) ----------------------------------------------------
@@ -1883,7 +1959,7 @@ static nna_status make_cqt_trainable(nna_plan* plan) {
       if (!real) return;
       for (int lane = 0; lane < 64; ++lane) {
         const int q = lane >> 4, row = rb * CQ_ROWS + (lane & 15);
-        const long long tap0 = (long long)j * (plan->sliding ? plan->hop : 0) + c0 + 4 * q;
+        const long long tap0 = (long long)j * plan->tap_stride + c0 + 4 * q;
         for (int e = 0; e < 4; ++e)
           if (row < rows && tap0 + e >= plan->row_s[row] && tap0 + e < plan->row_e[row])
             map[((size_t)f * 64 + lane) * 4 + e] = (int)(row * K + tap0 + e);
@@ -2205,7 +2281,7 @@ nna_status nna_cqt_backward(const nna_plan* plan, const float* x_dev, long long 
   if ((s = nna_cqt_backward_workspace(plan, B, L, &need)) != NNA_OK) return s;
   if (!workspace_dev || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace_dev) & 255))
     return fail(NNA_ERR_INVALID_ARG, "workspace_dev is NULL, not 256-byte aligned or smaller than nna_cqt_backward_workspace asks for");
-  const int extra = plan->max_jspan - 1;
+  const int extra = (plan->max_jspan - 1) * plan->row_step;
   const int M = pick_tile_frames(CQ_FRAMES, T, extra, CQ_LDS_ROWS_MAX);
   if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
@@ -2229,6 +2305,8 @@ nna_status nna_cqt_backward(const nna_plan* plan, const float* x_dev, long long 
   P.n_chunks = plan->n_chunks;
   P.n_bins = plan->n_bins;
   P.fmt = plan->fmt;
+  P.tap_stride = plan->tap_stride;
+  P.row_step = plan->row_step;
   P.tile_frames = M;
   const long long nseg = 1 + (M - 1 + T - 1) / T;
   P.lds_rows = (int)((M + nseg * extra + 63) / 64 * 64);
@@ -2452,7 +2530,7 @@ nna_status nna_plan_bank(const nna_plan* plan, double* host_out, size_t cap) {
       for (int lane = 0; lane < 64; ++lane) {
         const int q = lane >> 4, r = lane & 15;
         const long long row = (long long)rb * CQ_ROWS + r;
-        const long long tap0 = (long long)j * (plan->sliding ? plan->hop : 0) + c0 + 4 * q;
+        const long long tap0 = (long long)j * plan->tap_stride + c0 + 4 * q;
         for (int e = 0; e < 4; ++e)
           if (row < rows && tap0 + e < K) host_out[row * K + tap0 + e] = (double)src[((size_t)f * 64 + lane) * 4 + e];
       }
@@ -2570,6 +2648,8 @@ void nna_plan_destroy(nna_plan* plan) {
       (void)hipFree(plan->d_bank);
       (void)hipFree(plan->d_bank16);
       (void)hipFree(plan->d_bankf);
+      (void)hipFree(plan->d_fir_he);
+      (void)hipFree(plan->d_fir_ho);
       (void)hipFree(plan->d_wn);
       (void)hipFree(plan->d_melwf);
       (void)hipFree(plan->d_mel_maskf);

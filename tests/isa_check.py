@@ -84,8 +84,10 @@ def _step_raw(pending: tuple, lineno: int, t: str, op: str, bad: dict, in_asm: b
     return pending
 
 
-def check_kernel(lines) -> list:
-    """Violations [(line_no, text)] of one kernel.
+def check_kernel(lines, unmarked_is_asm: bool = True) -> list:
+    """Violations [(line_no, text)] of one kernel.  ``unmarked_is_asm``: a listing without inline-asm markers is
+    hand-written (every load in it is checked); compiled kernels pass False, so that a kernel that leaves all
+    its loads to the compiler is not checked against the compiler's own, correct, bookkeeping.
 
     The kernel is split into basic blocks; the set of possible in-flight load lists is propagated
     along every control-flow edge to a fixed point (loads retire in order, so a list is trimmed to
@@ -93,7 +95,7 @@ def check_kernel(lines) -> list:
     insts = []  # (lineno, text, op, inside an inline-asm block)
     labels = {}
     in_asm = False
-    marked = any("#ASMSTART" in raw for raw in lines)  # hand-written snippets carry no markers: all asm
+    marked = any("#ASMSTART" in raw for raw in lines) or not unmarked_is_asm
     for i, raw in enumerate(lines, 1):
         if "#ASMSTART" in raw:
             in_asm = True
@@ -190,7 +192,7 @@ def check_all(asm_text: str) -> dict:
         j = starts[k + 1][0] if k + 1 < len(starts) else len(src)
         body = src[i:j]
         end = next((x for x, l in enumerate(body) if l.startswith(".Lfunc_end")), len(body))
-        res[name] = check_kernel(body[:end])
+        res[name] = check_kernel(body[:end], unmarked_is_asm=False)
     return res
 
 

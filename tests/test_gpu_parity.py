@@ -313,6 +313,10 @@ CQT_CASES = [
     ("36 bins per octave", 2, 30000, 22050, 256, 110.0, 100, 36, 0, 0, True, 0),
     ("Hamming-windowed kernels", 2, 6000, 8000, 128, 220.0, 24, 12, 1024, 2, True, 0),
     ("Blackman-windowed kernels", 2, 6000, 8000, 128, 220.0, 24, 12, 1024, 3, True, 0),
+    # a hop that divides the 16-tap chunk (deep octaves of a downsampling plan): rows step by one hop, shifts by 16 taps
+    ("hop 8 (two LDS rows per 16-tap shift)", 3, 3000, 8000, 8, 500.0, 20, 12, 512, 0, True, 0),
+    ("hop 4, short kernels", 2, 1500, 8000, 4, 1000.0, 12, 12, 256, 0, True, 1),
+    ("hop 8, tiles span waveforms, no centring", 9, 700, 8000, 8, 700.0, 14, 12, 256, 1, False, 0),
     # hop 441 does not divide 65,536 taps: one chunk per 16 taps of a 46,025-tap kernel, 2,878 chunk
     # descriptors per work item -- more than the kernel keeps in LDS at a time (ring of 512)
     ("46,025-tap kernels whose frames do not overlap in LDS", 2, 40000, 44100, 441, 32.70, 30, 24, 0, 0, True, 0),
