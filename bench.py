@@ -238,6 +238,46 @@ def main() -> int:
                                    / (PEAK_F16_MFMA_TFLOPS if name == "stft_f16_operands" else PEAK_FP32_MFMA_TFLOPS), 4),
                 "mfma_peak_tflops": PEAK_F16_MFMA_TFLOPS if name == "stft_f16_operands" else PEAK_FP32_MFMA_TFLOPS,
             }
+        # The paper's own timing parameters (Sec. IV-A): n_fft 4096 / hop 512 STFT, 512 Mel filters on it, and the
+        # 24-bins-per-octave CQT, on 1,770 clips of 80,000 samples at 44.1 kHz -- the shape of its MAPS excerpts
+        # with synthetic content (the first 80,000 samples of the same waveforms).
+        Lp, Tp = 80000, 1 + 80000 // 512
+        x4p = x4[:, :Lp].contiguous()
+        x5p = x5[:, :Lp].contiguous()
+        p_s4 = nb.nna_plan_stft(sr=sr, n_fft=4096, hop=512, device=0)
+        p_m4 = nb.nna_plan_mel(sr=sr, n_fft=4096, hop=512, n_mels=512, fmin=0.0, fmax=22050.0, device=0)
+        p_c4 = nb.nna_plan_cqt(sr=sr, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24, n_taps=0, device=0)
+        o_s4 = torch.empty((B, 2049, Tp), dtype=torch.float32, device=dev)
+        o_m4 = torch.empty((B, 512, Tp), dtype=torch.float32, device=dev)
+        o_c4 = torch.empty((B, 168, Tp), dtype=torch.float32, device=dev)
+        paper = {}
+        for name, fn, plan, out_t, xin, cfg in (
+                ("stft_n4096", lambda: nb.nna_stft(p_s4, x4p, o_s4), p_s4, o_s4, x4p, 4),
+                ("mel_n4096_512mels", lambda: nb.nna_mel(p_m4, x4p, o_m4), p_m4, o_m4, x4p, 4),
+                ("cqt_168bins", lambda: nb.nna_cqt(p_c4, x5p, o_c4), p_c4, o_c4, x5p, 5)):
+            for _ in range(max(1, args.warmup)):
+                fn()
+            ev = []
+            for _ in range(args.steps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                fn()
+                b.record()
+                ev.append((a, b))
+            torch.cuda.synchronize()
+            ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+            info = plan.info()
+            exe, alg = info["executed_flops_per_frame"] * B * Tp, info["algorithmic_flops_per_frame"] * B * Tp
+            paper[name] = {
+                "ms": round(ms, 4),
+                "gsamples_per_s": round(B * Lp / ms / 1e6, 4),
+                "executed_tflops": round(exe / ms / 1e9, 3),
+                "mfma_frac": round(min(exe, alg) / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+                "mfma_frac_executed": round(exe / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+                "sample": (out_t, xin, cfg),
+            }
+        extras["paper_parameters_1770x80000"] = paper
+        del x4p, x5p
         # Mel and the power spectrogram it is computed from, both written by one launch (one contraction)
         p_mel2 = nb.nna_plan_mel(sr=sr, n_fft=2048, hop=512, n_mels=128, fmin=0.0, fmax=22050.0, device=0)
         o_mel2 = torch.empty((B, 128, T), dtype=torch.float32, device=dev)
@@ -373,6 +413,25 @@ def main() -> int:
             "sample": f"{n_cpu} of the {B} waveforms (evenly spaced indices) through the same {done} transforms, "
                       f"{t_cpu:.1f} s of float64 oracle time",
         }
+
+    if extras and "paper_parameters_1770x80000" in extras:
+        paper = extras["paper_parameters_1770x80000"]
+        if not args.no_cpu_baseline:
+            import oracle
+            pidx = [0, B // 2, B - 1]
+            for name, entry in paper.items():
+                out_t, xin, cfg = entry["sample"]
+                xs = signals.batch(cfg, pidx)[:, :80000]
+                if name == "stft_n4096":
+                    ref = oracle.stft(xs, n_fft=4096, hop=512)
+                elif name == "mel_n4096_512mels":
+                    ref = oracle.mel(xs, sr=sr, n_fft=4096, hop=512, n_mels=512, fmin=0.0, fmax=22050.0)
+                else:
+                    ref = oracle.cqt(xs, sr=sr, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24, n_taps=65536)
+                got = out_t[pidx].cpu().numpy().astype(np.float64)
+                entry["max_rel_err"] = float(max(np.abs(got[i] - ref[i]).max() / np.abs(ref[i]).max() for i in range(len(pidx))))
+        for entry in paper.values():
+            entry.pop("sample", None)
 
     line = {
         "metric": "GSamples/s per transform (STFT/Mel/CQT) + % of MFMA roofline, 1 MI355X",

@@ -39,6 +39,21 @@ struct TileMap {
 };
 
 // ---------------------------------------------------------------------------------------
+// Work item of a launch whose workgroups are (frame tile, pass) pairs (Mel filterbank passes of 128 filters,
+// constant-Q passes of 64 bins).  The passes of a Mel plan differ widely in length (the filters of the top
+// pass span half the spectrum) and sweep different row tiles of the bank.  The pass is the slow index,
+// longest (highest) pass first: the workgroups resident at any time then belong to one pass and walk the
+// same bank tiles together, so the bank streams through the L2s once per wave of workgroups instead of once
+// per workgroup, and consecutive ids (dealt round-robin to the 8 XCDs) are frame tiles of equal length.
+// Grid: n_ft * n_pass workgroups.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void pass_work_item(long long bid, long long n_ft, int n_pass, long long& ft, int& pass) {
+  const long long p = bid / n_ft;
+  pass = n_pass - 1 - (int)p;
+  ft = bid - p * n_ft;
+}
+
+// ---------------------------------------------------------------------------------------
 // Hand-scheduled global loads.  The compiler's own wait-count insertion is conservative at loop
 // headers (it waited for nearly every outstanding load at the top of each K iteration, which
 // exposed the full L2 latency), so the streaming loads are issued through inline asm and waited

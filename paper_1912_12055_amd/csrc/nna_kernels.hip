@@ -64,8 +64,7 @@ __global__ __launch_bounds__(256, LIN_NB > 4 ? 1 : 2) void stft_kernel(const Stf
   long long ft;
   int rt_begin, rt_end, pass = 0;
   if constexpr (MEL) {
-    ft = (long long)blockIdx.x / P.n_pass;
-    pass = (int)(blockIdx.x % P.n_pass);
+    pass_work_item(blockIdx.x, P.n_ft, P.n_pass, ft, pass);
     rt_begin = P.mel_pass_rt[2 * pass];
     rt_end = P.mel_pass_rt[2 * pass + 1];
     if (SPEC && pass == 0) {  // the spectrogram needs every row tile, also those no filter touches
