@@ -314,10 +314,68 @@ def cqt2010v2(x, sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, w
               fir_taps=FIR_TAPS, fmt=MAGNITUDE):
     x = _x(x)
     B, L = x.shape
+    if fmt in (COMPLEX, PHASE):
+        re, im = cqt2010v2_complex(x, sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bins_per_octave,
+                                   window=window, n_taps=n_taps, fir_taps=fir_taps)
+        return apply_complex_format(re, im, fmt)
     out = np.empty((B, n_bins, 1 + L // hop), dtype=np.float64)
     _check(lib().orc_cqt2010v2(_pf(x), B, L, sr, hop, fmin, n_bins, bins_per_octave, window, n_taps, fir_taps, fmt,
                                _pd(out)), "cqt2010v2")
     return out
+
+
+def cqt2010v2_complex(x, sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, window=WIN_HANN, n_taps=0,
+                      fir_taps=FIR_TAPS):
+    """(re, im) of the downsampling CQT with time-domain kernels before the magnitude is taken (the
+    ``output_format`` argument of the paper's CQT layers, Sec. III-C), each [B, n_bins, 1 + L // hop].
+    Sec. III-C "Downsampling" in its own order, per waveform: octave a = 0 (top), 1, ... is the complex
+    one-rate transform (``cqt_complex``: eqs. (Q), (N_k), (CQT)) of the waveform downsampled a times, with
+    hop / 2^a and the kernels of the octave's bins at frequencies times 2^a -- the readings of
+    ``orc_cqt2010v2``, whose magnitude this function's modulus must reproduce (pinned); then
+    ``downsample2``.
+    """
+    x = _x(x)
+    B, L = x.shape
+    b = bins_per_octave
+    n_oct = (n_bins + b - 1) // b
+    if hop % (1 << (n_oct - 1)):
+        raise OracleError("hop must be a multiple of 2^(octaves-1)")
+    if n_taps <= 0:
+        n_taps = cqt2010_default_taps(sr, fmin, n_bins, b)
+    h = lowpass_fir(fir_taps, 0.5)
+    T = 1 + L // hop
+    re = np.empty((B, n_bins, T), dtype=np.float64)
+    im = np.empty_like(re)
+    for bi in range(B):
+        xa = x[bi].astype(np.float64)
+        for a in range(n_oct):
+            hi = n_bins - a * b
+            lo = max(hi - b, 0)
+            # the C routines take float32 waveforms: the downsampled signal is rounded (6e-8 relative)
+            r, i = cqt_complex(xa.astype(np.float32), sr=sr, hop=hop >> a, fmin=fmin * 2.0 ** (float(lo + a * b) / float(b)),
+                               n_bins=hi - lo, bins_per_octave=b, window=window, center=True, n_taps=n_taps)
+            re[bi, lo:hi, :] = r[0, :, :T]
+            im[bi, lo:hi, :] = i[0, :, :T]
+            if a + 1 < n_oct:
+                xa = downsample2(xa, h)
+    return re, im
+
+
+def apply_complex_format(re, im, fmt):
+    """The output formats of the paper's layers from the transform's real and imaginary parts:
+    magnitude, power, log power, the interleaved (Re, Im) rows, or the phase atan2(Im, Re)."""
+    if fmt == COMPLEX:
+        return interleave(re, im)
+    if fmt == PHASE:
+        return np.arctan2(im, re)
+    pw = re ** 2 + im ** 2
+    if fmt == MAGNITUDE:
+        return np.sqrt(pw)
+    if fmt == POWER:
+        return pw
+    if fmt == LOG:
+        return np.log(np.maximum(pw, LOG_FLOOR))
+    raise OracleError("unknown output format")
 
 
 def cqt1992_spectral_kernels(sr, fmin, n_bins, bins_per_octave, window=WIN_HANN, n_fft=0):
@@ -353,14 +411,7 @@ def cqt1992(x, sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, win
     re, im = stft_complex(x, n_fft=n_fft, hop=hop, window=WIN_RECT, center=center)
     X = re + 1j * im                                    # [B, F, T]
     Xcq = np.einsum("qk,bkt->bqt", Y, X) / float(n_fft)  # [B, n_bins, T]
-    pw = Xcq.real ** 2 + Xcq.imag ** 2
-    if fmt == MAGNITUDE:
-        return np.sqrt(pw)
-    if fmt == POWER:
-        return pw
-    if fmt == LOG:
-        return np.log(np.maximum(pw, LOG_FLOOR))
-    raise OracleError("unknown output format")
+    return apply_complex_format(Xcq.real, Xcq.imag, fmt)
 
 
 def cqt2010(x, sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, window=WIN_HANN, n_fft=0,
@@ -387,7 +438,7 @@ def cqt2010(x, sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, win
     F = N // 2 + 1
     n = np.arange(N)
     dft = np.exp(-2j * np.pi * np.outer(n, np.arange(F)) / N)  # eq. (DFT2), no window: [N, F]
-    out = np.empty((B, n_bins, T), dtype=np.float64)
+    out = np.empty((B, n_bins, T), dtype=np.complex128)
     for bi in range(B):
         xa = x[bi].astype(np.float64)
         for a in range(n_oct):
@@ -415,16 +466,10 @@ def cqt2010(x, sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, win
             idx = np.where(idx >= La, 2 * (La - 1) - idx, idx)
             X = xa[idx] @ dft                       # [T, F]
             Xcq = (X @ Y.T) / float(N)               # [T, bins of the octave]
-            out[bi, lo:hi, :] = (Xcq.real ** 2 + Xcq.imag ** 2).T
+            out[bi, lo:hi, :] = Xcq.T
             if a + 1 < n_oct:
                 xa = downsample2(xa, h)
-    if fmt == MAGNITUDE:
-        return np.sqrt(out)
-    if fmt == POWER:
-        return out
-    if fmt == LOG:
-        return np.log(np.maximum(out, LOG_FLOOR))
-    raise OracleError("unknown output format")
+    return apply_complex_format(out.real, out.imag, fmt)
 
 
 # ---------------------------------------------------------------------------------------

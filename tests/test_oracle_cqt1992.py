@@ -93,6 +93,14 @@ def test_differs_from_the_time_domain_cqt_by_the_dropped_half_only(sr, fmin, nb,
     time_domain = oracle.cqt(x, sr=sr, hop=hop, fmin=fmin, n_bins=nb, bins_per_octave=b)[0]
     peak = time_domain.max()
     np.testing.assert_allclose(got, np.abs(kept), atol=1e-12 * peak)
+    # the complex output is that kept sum itself (rows 2q = Re, 2q+1 = Im), the phase output its argument
+    cplx = oracle.cqt1992(x, sr=sr, hop=hop, fmin=fmin, n_bins=nb, bins_per_octave=b, fmt=oracle.COMPLEX)[0]
+    np.testing.assert_allclose(cplx[0::2] + 1j * cplx[1::2], kept, atol=1e-12 * peak)
+    tre, tim = oracle.cqt_complex(x, sr=sr, hop=hop, fmin=fmin, n_bins=nb, bins_per_octave=b)
+    np.testing.assert_allclose(tre[0] + 1j * tim[0], kept + dropped, atol=1e-11 * peak)
+    ph = oracle.cqt1992(x, sr=sr, hop=hop, fmin=fmin, n_bins=nb, bins_per_octave=b, fmt=oracle.PHASE)[0]
+    strong = np.abs(kept) > 1e-3 * peak
+    assert np.abs(np.angle(np.exp(1j * ph) * np.exp(-1j * np.angle(kept))))[strong].max() < 1e-9
     np.testing.assert_allclose(time_domain, np.abs(kept + dropped), atol=1e-11 * peak)
     assert np.abs(dropped).max() < small * peak
     assert np.abs(got - time_domain).max() < small * peak
@@ -143,6 +151,11 @@ def test_cqt2010_octave_by_octave_against_scipy_downsampling_and_the_one_rate_tr
     got = oracle.cqt2010(x, sr=sr, hop=hop, fmin=fmin, n_bins=nb, bins_per_octave=b, fir_taps=fir)[0]
     T = 1 + L // hop
     assert got.shape == (nb, T)
+    gotc = oracle.cqt2010(x, sr=sr, hop=hop, fmin=fmin, n_bins=nb, bins_per_octave=b, fir_taps=fir, fmt=oracle.COMPLEX)[0]
+    assert gotc.shape == (2 * nb, T)
+    np.testing.assert_allclose(np.hypot(gotc[0::2], gotc[1::2]), got, atol=1e-12)
+    gotp = oracle.cqt2010(x, sr=sr, hop=hop, fmin=fmin, n_bins=nb, bins_per_octave=b, fir_taps=fir, fmt=oracle.PHASE)[0]
+    assert np.array_equal(gotp, np.arctan2(gotc[1::2], gotc[0::2]))
     h = scipy.signal.firwin(fir, 0.5)
     xa = x.astype(np.float64)
     n_oct = (nb + b - 1) // b
@@ -153,6 +166,10 @@ def test_cqt2010_octave_by_octave_against_scipy_downsampling_and_the_one_rate_tr
         ref = oracle.cqt1992(xa.astype(np.float32), sr=sr, hop=hop >> a, fmin=fmin * 2.0 ** ((lo + a * b) / b),
                              n_bins=hi - lo, bins_per_octave=b, n_fft=N)[0]
         assert np.abs(got[lo:hi] - ref[:, :T]).max() < 5e-7 * max(ref.max(), 1e-3)
+        # and before the magnitude: rows 2q / 2q+1 of the complex format against the one-rate transform's
+        refc = oracle.cqt1992(xa.astype(np.float32), sr=sr, hop=hop >> a, fmin=fmin * 2.0 ** ((lo + a * b) / b),
+                              n_bins=hi - lo, bins_per_octave=b, n_fft=N, fmt=oracle.COMPLEX)[0]
+        assert np.abs(gotc[2 * lo:2 * hi] - refc[:, :T]).max() < 5e-7 * max(ref.max(), 1e-3)
         xa = scipy.signal.convolve(np.pad(xa, fir // 2, mode="reflect"), h, mode="valid")[::2]
 
 

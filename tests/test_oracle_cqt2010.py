@@ -113,3 +113,45 @@ def test_rejects_hops_that_do_not_halve_and_short_signals():
         oracle.cqt2010v2(x[:, :2000], sr=22050, hop=512, n_bins=84)  # deepest octave shorter than half a kernel
     with pytest.raises(oracle.OracleError):
         oracle.cqt2010v2(x, sr=22050, hop=512, n_bins=84, fir_taps=256)  # even tap count has no integer delay
+
+
+# ---------------------------------------------------------------------------------------
+# complex / phase output of the downsampling CQT (the layers' output_format, Sec. III-C)
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n_bins,bpo,fir", [(36, 12, 63), (29, 12, 257)])
+def test_complex_modulus_is_the_magnitude_of_the_c_routine(n_bins, bpo, fir):
+    # the octave loop written in Python over cqt_complex / downsample2 against the C routine's own loop
+    sr, hop, fmin, L = 16000, 64, 220.0, 5000
+    x = signals.batch(3, B=2, L=L)
+    re, im = oracle.cqt2010v2_complex(x, sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, fir_taps=fir)
+    mag = oracle.cqt2010v2(x, sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, fir_taps=fir)
+    assert re.shape == mag.shape == (2, n_bins, 1 + L // hop)
+    # (the Python loop rounds each downsampled waveform to float32 on its way into the C transform)
+    np.testing.assert_allclose(np.hypot(re, im), mag, atol=2e-6 * mag.max())
+    cplx = oracle.cqt2010v2(x, sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, fir_taps=fir, fmt=oracle.COMPLEX)
+    assert cplx.shape == (2, 2 * n_bins, 1 + L // hop)
+    assert np.array_equal(cplx[:, 0::2], re) and np.array_equal(cplx[:, 1::2], im)
+    ph = oracle.cqt2010v2(x, sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, fir_taps=fir, fmt=oracle.PHASE)
+    assert np.array_equal(ph, np.arctan2(im, re))
+
+
+@pytest.mark.parametrize("k,phase", [(30, 0.4), (17, -1.3), (3, 2.6)])
+def test_complex_result_carries_the_tone_phase_in_the_lower_octaves(k, phase):
+    # Bin k lives in octave a = (n_bins - 1 - k) // b, whose kernel of N taps (at the rate sr / 2^a) starts, for
+    # frame t, at downsampled sample  t hop / 2^a - n_taps / 2 + s.  A tone that has exactly Q cycles per kernel
+    # and phase `phase` at that sample passes the zero-delay filters unchanged (pass-band ripple aside), and
+    # eq. (CQT)'s kernel exp(-2 pi i Q m / N) w / sum(w) returns (A / 2) exp(+i phase).
+    sr, hop, fmin, n_bins, b, A = 16000, 64, 220.0, 36, 12, 0.5
+    n_taps = oracle.cqt2010_default_taps(sr, fmin, n_bins, b)
+    a = (n_bins - 1 - k) // b
+    top = k + a * b  # the bin of the top octave that shares its kernel
+    Nk, _ = oracle.cqt_lengths(sr, fmin * 2.0 ** a, n_bins, b)
+    N = Nk[k]        # = length of bin `top` at rate sr = length of bin k at rate sr / 2^a
+    assert N == oracle.cqt_lengths(sr, fmin, n_bins, b)[0][top]
+    L, t = 8000, 60
+    first = t * (hop >> a) - n_taps // 2 + (n_taps - N) // 2   # in samples of the octave's rate
+    n = np.arange(L)
+    x = (A * np.cos(2 * np.pi * oracle.cqt_Q(b) * (n / 2.0 ** a - first) / N + phase)).astype(np.float32)
+    re, im = oracle.cqt2010v2_complex(x[None], sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=b)
+    z = re[0, k, t] + 1j * im[0, k, t]
+    assert abs(z - A / 2 * np.exp(1j * phase)) < 1e-2 * A, (a, z)
