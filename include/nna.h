@@ -64,7 +64,8 @@ typedef enum {
   NNA_OUT_POWER = 1,     /* Re^2 + Im^2 */
   NNA_OUT_LOG = 2,       /* ln(max(Re^2 + Im^2, 1e-10)): log compression, Fig. 1 caption */
   /* The transform itself, before the magnitude is taken (the output_format argument of the paper's
-   * CQT layer, Sec. III-C): nna_stft (float32 plans) and nna_cqt only. */
+   * CQT layers, Sec. III-C): nna_stft (float32 plans) and the four constant-Q transforms (nna_cqt, nna_cqt1992,
+   * nna_cqt2010, nna_cqt2010v2); not float16 plans. */
   NNA_OUT_COMPLEX = 3,   /* out[B, 2 bins, T]: row 2k = Re, row 2k+1 = Im of bin k (eq. (DFT2)'s signs: Im = -sum x sin) */
   NNA_OUT_PHASE = 4      /* atan2(Im, Re) in [-pi, pi] */
 } nna_output;

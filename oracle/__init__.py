@@ -12,7 +12,10 @@ frequency-domain kernels) and ``cqt2010`` (the same per octave of a recursive do
 Parity status: ``cqt1992_spectral_kernels`` / ``cqt1992`` pinned (explicit O(N^2) sums on a tiny
 case, numpy's FFT of frames cut independently, the exact dropped-half difference from the
 time-domain CQT, tone magnitude A/2); ``cqt2010`` pinned (octave by octave against ``cqt1992`` on
-SciPy-downsampled signals, its time-domain twin, tones A/2 in every octave).
+SciPy-downsampled signals, its time-domain twin, tones A/2 in every octave); their complex and phase
+outputs pinned (the kept-half sum as a complex number; rows of the complex format octave by octave);
+``cqt2010v2_complex`` (the octave loop over the C file's ``cqt_complex`` and ``downsample2``) pinned
+(modulus = the C routine's magnitude; a tone's closed-form phase in the lower octaves).
 
 Also in numpy: the layers with their kernels as weights and the gradients through them (Sec. IV-C).
 Parity status: ``stft_bank`` pinned (equals the windowed-DFT oracle for a bank written out from eq. (DFT2));

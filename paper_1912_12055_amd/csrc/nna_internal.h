@@ -108,7 +108,7 @@ struct StftParams {
   long long gpitch;           // elements between consecutive rows of gbuf (32)
   // ST_MODE_LIN only: where this plan's bins go in `out`
   long long out_wave_stride;  // elements of `out` per waveform
-  int bin_offset;             // bin 0 of this plan is row bin_offset of each waveform's output
+  int row_offset;             // the plan's first output row is row row_offset of each waveform's output
 };
 
 struct Stft16Params {
@@ -155,7 +155,7 @@ struct CqtParams {
   const CqtChunk* chunks;  // [n_items][n_chunks]
   float* out;
   long long out_wave_stride;  // elements of `out` per waveform (all bins x frames)
-  int bin_offset;          // spectrogram: bin 0 of this bank is row bin_offset of each waveform's output
+  int row_offset;          // the bank's first output row is row row_offset of each waveform's output
   int tap_stride;          // taps between consecutive shifts of a chunk (see CqtChunk::jlo)
   int row_step;            // LDS rows between consecutive shifts: 1, or 16 / hop when the hop divides the chunk
   int n_items;

@@ -374,7 +374,7 @@ __global__ __launch_bounds__(256, LIN_NB > 4 ? 1 : 2) void stft_kernel(const Stf
 
   if constexpr (LIN) {
     // output rows 2q, 2q+1 = (Re, Im) of complex bin q sit in adjacent registers of one lane
-    float* __restrict__ op = P.out + b_lane * P.out_wave_stride + (long long)P.bin_offset * g.T + t_lane;
+    float* __restrict__ op = P.out + b_lane * P.out_wave_stride + (long long)P.row_offset * g.T + t_lane;
     const int f = P.fmt;
 #pragma unroll
     for (int mb = 0; mb < NB; ++mb) {
@@ -382,6 +382,15 @@ __global__ __launch_bounds__(256, LIN_NB > 4 ? 1 : 2) void stft_kernel(const Stf
       for (int r = 0; r < 16; r += 2) {
         const int bin = (pass * (32 * NB) + mb * 32 + 8 * (r >> 2) + 4 * h + (r & 3)) >> 1;
         if (valid && bin < P.out_bins) {
+          if (f == NNA_OUT_COMPLEX) {  // rows 2q = Re, 2q+1 = Im
+            op[(2LL * bin) * g.T] = macc[mb][r];
+            op[(2LL * bin + 1) * g.T] = macc[mb][r + 1];
+            continue;
+          }
+          if (f == NNA_OUT_PHASE) {
+            op[(long long)bin * g.T] = atan2f(macc[mb][r + 1], macc[mb][r]);
+            continue;
+          }
           const float pw = macc[mb][r] * macc[mb][r] + macc[mb][r + 1] * macc[mb][r + 1];
           op[(long long)bin * g.T] = f == NNA_OUT_MAGNITUDE ? format_power<NNA_OUT_MAGNITUDE>(pw)
                                      : f == NNA_OUT_POWER   ? pw
@@ -477,7 +486,7 @@ __global__ __launch_bounds__(256, 2) void cqt_kernel(const CqtParams P) {
     const long long b = valid[fb] ? f / g.T : 0;
     const int t = valid[fb] ? (int)(f - b * g.T) : 0;
     a_off[fb] = (valid[fb] ? tm.frame_row(fi) : 0) * CQ_PITCH + 4 * q;
-    o_off[fb] = b * P.out_wave_stride + (long long)P.bin_offset * g.T + t;
+    o_off[fb] = b * P.out_wave_stride + (long long)P.row_offset * g.T + t;
   }
 
   const int n_chunks = item.n_chunks;  // >= 1; every listed chunk starts with >= CQ_PREFETCH fragments

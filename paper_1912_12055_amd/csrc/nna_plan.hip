@@ -98,7 +98,7 @@ nna_status check_fmt(int fmt, bool allow_complex) {
   if (fmt == NNA_OUT_MAGNITUDE || fmt == NNA_OUT_POWER || fmt == NNA_OUT_LOG) return NNA_OK;
   if (fmt == NNA_OUT_COMPLEX || fmt == NNA_OUT_PHASE) {
     if (allow_complex) return NNA_OK;
-    return fail(NNA_ERR_UNSUPPORTED, "the complex and phase outputs exist for nna_stft (float32) and nna_cqt only");
+    return fail(NNA_ERR_UNSUPPORTED, "the complex and phase outputs exist for the float32 STFT and the constant-Q transforms, not for float16 plans");
   }
   return fail(NNA_ERR_INVALID_ARG, "unknown output format");
 }
@@ -419,7 +419,7 @@ nna_status nna_plan_cqt1992(nna_plan** plan, int sr, int hop, double fmin, int n
                             nna_window win, int center, int n_fft, nna_output fmt, int device) {
   nna_status s = check_common(plan, sr, hop, win, center, device);
   if (s != NNA_OK) return s;
-  if ((s = check_cqt_args(fmin, n_bins, bins_per_octave, n_fft, fmt, sr)) != NNA_OK) return s;
+  if ((s = check_cqt_args(fmin, n_bins, bins_per_octave, n_fft, fmt, sr, true)) != NNA_OK) return s;
   return make_cqt1992_plan(plan, sr, hop, fmin, 0, n_bins, bins_per_octave, win, center, n_fft, fmt, device);
 }
 
@@ -430,7 +430,7 @@ static nna_status make_downsampling_plan(int kind, nna_plan** plan, int sr, int 
                                          int device) {
   nna_status s = check_common(plan, sr, hop, win, 1, device);
   if (s != NNA_OK) return s;
-  if ((s = check_cqt_args(fmin, n_bins, bins_per_octave, n_taps, fmt, sr)) != NNA_OK) return s;
+  if ((s = check_cqt_args(fmin, n_bins, bins_per_octave, n_taps, fmt, sr, true)) != NNA_OK) return s;
   if (fir_taps == 0) fir_taps = 257;
   if (fir_taps < 3 || fir_taps > 4095 || !(fir_taps & 1))
     return fail(NNA_ERR_INVALID_ARG, "fir_taps must be odd and in [3, 4095]");

@@ -92,10 +92,10 @@ nna::FrameGeom make_geom(const nna_plan* p, const float* x, long long B, long lo
 }
 
 // One launch of the STFT kernel family: T frames of each of the B waveforms (arguments checked by the
-// caller).  out_wave_stride / bin_offset place a two-stage CQT plan's bins inside a larger output
+// caller).  out_wave_stride / row_offset place a two-stage CQT plan's rows inside a larger output
 // (octave of a downsampling plan); 0 / 0 = the plan's own [B, bins, T].
 nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long long B, long long L, long long T,
-                         float* out, long long out_wave_stride, int bin_offset, void* stream, float* spec_out = nullptr) {
+                         float* out, long long out_wave_stride, int row_offset, void* stream, float* spec_out = nullptr) {
   if (plan->precision == NNA_PREC_F16) {
     const int M = pick_tile_frames(nna::H_FRAMES, T, plan->nj - 1, nna::H_LB_ROWS);
     if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
@@ -191,8 +191,8 @@ nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long lo
     P.mel_nyq_any = plan->mel_nyq_any;
   } else if (kind == NNA_KIND_CQT1992) {
     P.fmt = plan->fmt;
-    P.out_wave_stride = out_wave_stride > 0 ? out_wave_stride : (long long)plan->n_bins * T;
-    P.bin_offset = bin_offset;
+    P.out_wave_stride = out_wave_stride > 0 ? out_wave_stride : (long long)plan->out_rows() * T;
+    P.row_offset = row_offset;
     P.melw = reinterpret_cast<const float4*>(plan->d_melw);
     P.mel_mask = plan->d_mel_mask;
     P.mel_wnyq = plan->d_mel_wnyq;
@@ -226,7 +226,7 @@ nna_status run_stft_like(const nna_plan* plan, int kind, const float* x, long lo
 
 // one launch of the CQT kernel: `sub`'s bank over T frames of each of the B waveforms in x
 nna_status run_conv(const nna_plan* sub, const float* x, long long B, long long L, long long T, float* out,
-                    long long out_wave_stride, int bin_offset, void* hip_stream) {
+                    long long out_wave_stride, int row_offset, void* hip_stream) {
   const int extra = (sub->max_jspan - 1) * sub->row_step;
   const int M = pick_tile_frames(CQ_FRAMES, T, extra, CQ_LDS_ROWS_MAX);
   if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
@@ -240,7 +240,7 @@ nna_status run_conv(const nna_plan* sub, const float* x, long long B, long long 
   P.chunks = sub->d_chunks;
   P.out = out;
   P.out_wave_stride = out_wave_stride;
-  P.bin_offset = bin_offset;
+  P.row_offset = row_offset;
   P.n_items = (int)sub->h_items.size();
   P.n_chunks = sub->n_chunks;
   P.n_bins = sub->n_bins;
@@ -358,10 +358,12 @@ static nna_status run_octaves(const nna_plan* plan, int kind, const float* x_dev
   for (int a = 0; a < n_oct; ++a) {
     int lo, hi;
     octave_bins(plan->n_bins, plan->bpo, a, lo, hi);
+    // the octave's rows inside each waveform's output (the complex format writes two rows per bin)
+    const int row0 = plan->fmt == NNA_OUT_COMPLEX ? 2 * lo : lo;
     if (kind == NNA_KIND_CQT2010V2)
-      s = run_conv(plan->octave[a], cur, B, La[a], T, out_dev, (long long)plan->n_bins * T, lo, hip_stream);
+      s = run_conv(plan->octave[a], cur, B, La[a], T, out_dev, (long long)plan->out_rows() * T, row0, hip_stream);
     else
-      s = run_stft_core(plan->octave[a], NNA_KIND_CQT1992, cur, B, La[a], T, out_dev, (long long)plan->n_bins * T, lo,
+      s = run_stft_core(plan->octave[a], NNA_KIND_CQT1992, cur, B, La[a], T, out_dev, (long long)plan->out_rows() * T, row0,
                         hip_stream);
     if (s != NNA_OK) return s;
     if (a + 1 < n_oct) {
@@ -416,7 +418,7 @@ nna_status nna_out_shape(const nna_plan* plan, long long B, long long L, long lo
     long long La[MAX_OCTAVES];
     if (L < 1 || !cqt2010_lengths(plan, L, La))
       return fail(NNA_ERR_SHAPE, "L is too short: every octave's waveform must exceed the reflection padding, and all but the lowest hold one frame of the decimation filter");
-    if (n_bins) *n_bins = plan->n_bins;
+    if (n_bins) *n_bins = plan->out_rows();
     if (n_frames) *n_frames = 1 + L / plan->hop;
     return NNA_OK;
   }

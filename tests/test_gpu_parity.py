@@ -463,6 +463,39 @@ def test_cqt2010v2_parity_small(nb, case):
     assert e < TOL
 
 
+def _octave_complex_errs(got_c, got_ph, re, im, n_bins, bpo):
+    """complex-format error (every octave against its own peak too) and phase error per octave (the octaves of one
+    signal differ by orders of magnitude: each is judged on its own strong bins)"""
+    ref = oracle.interleave(re, im)
+    e, ep = _rel_err(got_c, ref), 0.0
+    for a in range(-(-n_bins // bpo)):
+        hi = n_bins - a * bpo
+        lo = max(0, hi - bpo)
+        e = max(e, _rel_err(got_c[:, 2 * lo:2 * hi], ref[:, 2 * lo:2 * hi]))
+        ep = max(ep, _phase_err(got_ph[:, lo:hi], re[:, lo:hi], im[:, lo:hi]))
+    return e, ep
+
+
+@pytest.mark.parametrize("case", [CQT2010_CASES[0], CQT2010_CASES[1], CQT2010_CASES[3], CQT2010_CASES[4]], ids=lambda c: c[0])
+def test_cqt2010v2_complex_and_phase_output(nb, case):
+    name, B, L, sr, hop, fmin, n_bins, bpo, n_taps, fir_taps, _ = case
+    _say(f"cqt2010v2 complex/phase {name}: B={B} L={L} sr={sr} hop={hop} bins={n_bins}/{bpo} fir={fir_taps}")
+    x = _rand(B, L, 2010 + n_bins)
+    kw = dict(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, n_taps=n_taps)
+    re, im = oracle.cqt2010v2_complex(x, fir_taps=fir_taps or oracle.FIR_TAPS, **kw)
+    pc = nb.nna_plan_cqt2010v2(fir_taps=fir_taps, fmt=nb.NNA_OUT_COMPLEX, device=0, **kw)
+    assert nb.nna_out_shape(pc, B, L) == (2 * n_bins, 1 + L // hop)
+    got = _poisoned(B, 2 * n_bins, 1 + L // hop)
+    nb.nna_cqt2010v2(pc, _dev(x), out=got)
+    got = got.cpu().numpy()
+    assert np.isfinite(got).all()
+    ph = nb.nna_cqt2010v2(nb.nna_plan_cqt2010v2(fir_taps=fir_taps, fmt=nb.NNA_OUT_PHASE, device=0, **kw), _dev(x)).cpu().numpy()
+    assert ph.shape == (B, n_bins, 1 + L // hop)
+    e, ep = _octave_complex_errs(got, ph, re, im, n_bins, bpo)
+    _say(f"  complex rel err {e:.3e}, phase err {ep:.3e} rad")
+    assert e < TOL and ep < 1e-3
+
+
 def test_cqt2010v2_tone_closed_form_on_gpu(nb):
     # a tone on bin k reads A/2 in whichever octave k falls (filter ripple and kernel detuning: 1 %)
     _say("cqt2010v2 closed form tones")
@@ -539,6 +572,25 @@ def test_cqt1992_parity_small(nb, case):
     assert e < TOL and e < 5e-5
 
 
+@pytest.mark.parametrize("case", [CQT1992_CASES[1], CQT1992_CASES[2], CQT1992_CASES[3], CQT1992_CASES[7]], ids=lambda c: c[0])
+def test_cqt1992_complex_and_phase_output(nb, case):
+    name, B, L, sr, hop, fmin, n_bins, bpo, n_fft, win, center, _ = case
+    _say(f"cqt1992 complex/phase {name}: B={B} L={L} sr={sr} hop={hop} bins={n_bins}/{bpo} n_fft={n_fft}")
+    x = _rand(B, L, 700 + n_bins)
+    kw = dict(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, center=center, n_fft=n_fft)
+    ref = oracle.cqt1992(x, window=win, fmt=oracle.COMPLEX, **kw)
+    pc = nb.nna_plan_cqt1992(win=win, fmt=nb.NNA_OUT_COMPLEX, device=0, **kw)
+    got = _poisoned(*ref.shape)
+    nb.nna_cqt1992(pc, _dev(x), out=got)
+    got = got.cpu().numpy()
+    assert np.isfinite(got).all()
+    e = _rel_err(got, ref)
+    ph = nb.nna_cqt1992(nb.nna_plan_cqt1992(win=win, fmt=nb.NNA_OUT_PHASE, device=0, **kw), _dev(x)).cpu().numpy()
+    ep = _phase_err(ph, ref[:, 0::2], ref[:, 1::2])
+    _say(f"  complex rel err {e:.3e}, phase err {ep:.3e} rad")
+    assert e < TOL and e < 5e-5 and ep < 1e-3
+
+
 def test_cqt1992_device_kernels_equal_host_kernels(nb):
     _say("cqt1992 spectral kernels and DFT bank read-back")
     kw = dict(sr=8000, hop=64, fmin=55.0, n_bins=70, bins_per_octave=12)
@@ -598,6 +650,24 @@ def test_cqt2010_parity_small(nb, case):
         e = max(e, _rel_err(got[:, lo:hi], ref[:, lo:hi]))
     _say(f"  rel err {e:.3e}")
     assert e < TOL
+
+
+@pytest.mark.parametrize("case", [CQT2010_CASES[0], CQT2010_CASES[1], CQT2010_CASES[3], CQT2010_CASES[4]], ids=lambda c: c[0])
+def test_cqt2010_complex_and_phase_output(nb, case):
+    name, B, L, sr, hop, fmin, n_bins, bpo, n_fft, fir_taps, _ = case
+    _say(f"cqt2010 complex/phase {name}: B={B} L={L} sr={sr} hop={hop} bins={n_bins}/{bpo} fir={fir_taps}")
+    x = _rand(B, L, 2010 + n_bins)
+    kw = dict(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, n_fft=n_fft)
+    ref = oracle.cqt2010(x, fir_taps=fir_taps or oracle.FIR_TAPS, fmt=oracle.COMPLEX, **kw)
+    re, im = ref[:, 0::2], ref[:, 1::2]
+    got = _poisoned(*ref.shape)
+    nb.nna_cqt2010(nb.nna_plan_cqt2010(fir_taps=fir_taps, fmt=nb.NNA_OUT_COMPLEX, device=0, **kw), _dev(x), out=got)
+    got = got.cpu().numpy()
+    assert np.isfinite(got).all()
+    ph = nb.nna_cqt2010(nb.nna_plan_cqt2010(fir_taps=fir_taps, fmt=nb.NNA_OUT_PHASE, device=0, **kw), _dev(x)).cpu().numpy()
+    e, ep = _octave_complex_errs(got, ph, re, im, n_bins, bpo)
+    _say(f"  complex rel err {e:.3e}, phase err {ep:.3e} rad")
+    assert e < TOL and ep < 1e-3
 
 
 def test_cqt2010_tone_closed_form_and_wrong_entry_point_on_gpu(nb):

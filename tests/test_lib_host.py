@@ -345,9 +345,14 @@ def test_complex_and_phase_formats_shapes_and_where_they_exist():
     assert nb.nna_out_shape(p, 1, 1000) == (80, 16)
     p = nb.nna_plan_cqt(sr=8000, hop=64, fmin=220.0, n_bins=24, fmt=nb.NNA_OUT_COMPLEX, device=-1)
     assert nb.nna_out_shape(p, 1, 4000)[0] == 48 and nb.nna_plan_cqt_lengths(p).size == 24
-    for fn, kw in ((nb.nna_plan_cqt2010v2, {}), (nb.nna_plan_cqt2010, {}), (nb.nna_plan_cqt1992, dict(fmin=220.0, n_bins=24)),
-                   (nb.nna_plan_stft_prec, dict(precision=nb.NNA_PREC_F16))):
-        assert _status(fn, fmt=nb.NNA_OUT_COMPLEX, device=-1, **kw) == nb.NNA_ERR_UNSUPPORTED, fn
+    # all four constant-Q transforms have them (the output_format argument of the paper's CQT layers) ...
+    for fn, kw in ((nb.nna_plan_cqt2010v2, {}), (nb.nna_plan_cqt2010, {}), (nb.nna_plan_cqt1992, dict(fmin=220.0, n_bins=24))):
+        p = fn(fmt=nb.NNA_OUT_COMPLEX, device=-1, **kw)
+        n_bins = kw.get("n_bins", 84)
+        assert nb.nna_out_shape(p, 2, 44100) == (2 * n_bins, 1 + 44100 // 512) and p.info()["out_bins"] == 2 * n_bins
+        assert nb.nna_out_shape(fn(fmt=nb.NNA_OUT_PHASE, device=-1, **kw), 2, 44100)[0] == n_bins
+    # ... float16 plans do not (a Mel plan has no output format at all)
+    assert _status(nb.nna_plan_stft_prec, fmt=nb.NNA_OUT_COMPLEX, precision=nb.NNA_PREC_F16, device=-1) == nb.NNA_ERR_UNSUPPORTED
     assert _status(nb.nna_plan_stft, fmt=5, device=-1) == nb.NNA_ERR_INVALID_ARG
 
 
