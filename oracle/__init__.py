@@ -25,7 +25,11 @@ Parity status: ``stft_bank`` pinned (equals the windowed-DFT oracle for a bank w
 equal the kernel lengths); ``cqt_bank_backward`` pinned (central differences inside the supports, exact
 zeros outside); ``dft_bank_parameter_mask`` / ``stft_dft_bank_backward`` pinned (the masked rows are exactly
 the rows of eq. (DFT2)'s bank, written out in the test, that are zero for every tap; the unmasked gradient
-there is already zero for the magnitude-type outputs).
+there is already zero for the magnitude-type outputs); ``downsample2_transpose`` pinned (adjoint identity
+against the SciPy-pinned ``downsample2``, matrix rows on a tiny case); ``cqt2010v2_bank`` /
+``cqt2010v2_bank_forward`` pinned (equal the downsampling-CQT oracle, all five output formats);
+``cqt2010v2_bank_backward`` pinned (central differences of that forward for kernel taps of shared and
+partial-octave rows and for waveform samples at the mirrored ends and inside).
 """
 from __future__ import annotations
 
@@ -540,7 +544,13 @@ def stft_bank_backward(x, W, gout, hop=512, center=True, fmt=MAGNITUDE):
     gW[r, n] = sum_{b,t} G[b, r, t] xp_b[t hop + n];   gx_b[j] = sum over all (t, n) whose padded
     sample t hop + n mirrors onto j of sum_r W[r, n] G[b, r, t] (the transposed strided convolution,
     with the reflection padding folded back)."""
-    x = _x(x).astype(np.float64)
+    return stft_bank_backward_f64(_x(x).astype(np.float64), W, gout, hop=hop, center=center, fmt=fmt)
+
+
+def stft_bank_backward_f64(x, W, gout, hop=512, center=True, fmt=MAGNITUDE):
+    """``stft_bank_backward`` on float64 waveforms as given (the layer functions round their input to
+    float32, the precision the GPU path receives it in; the octaves of a downsampling CQT stay float64)."""
+    x = np.atleast_2d(np.asarray(x, dtype=np.float64))
     W = np.ascontiguousarray(W, dtype=np.float64)
     gout = np.ascontiguousarray(gout, dtype=np.float64)
     B, L = x.shape
@@ -656,3 +666,130 @@ def cqt_bank_backward(x, W, mask, gout, hop=512, center=True, fmt=MAGNITUDE):
     that centre each kernel, not parameters, so their gradient is dropped.  (gW, gx)."""
     gW, gx = stft_bank_backward(x, W, gout, hop=hop, center=center, fmt=fmt)
     return np.where(mask, gW, 0.0), gx
+
+
+# ---------------------------------------------------------------------------------------
+# Trainable kernels of the downsampling CQT with time-domain kernels (the `trainable` argument of the
+# paper's CQT2010v2 layer, Sec. III-C / IV-C): one kernel bank -- the top octave's -- is the weight every
+# octave convolves its downsampled waveform with, so its gradient is the sum over the octaves and the
+# waveform's gradient flows back up through the transposed decimation steps.
+# ---------------------------------------------------------------------------------------
+def cqt2010v2_bank(sr=22050, fmin=32.70, n_bins=84, bins_per_octave=12, window=WIN_HANN, n_taps=0):
+    """The weight of the downsampling CQT layer: the top octave's kernels, W[2 n_top, n_taps] with
+    n_top = min(bins_per_octave, n_bins) (``cqt_bank`` for the bins n_bins - n_top .. n_bins - 1), and
+    their support mask.  Octave a uses rows of the same W (its bins sit one factor 2^a lower, its
+    waveform is downsampled a times); a partial lowest octave uses the rows of the upper bins only."""
+    b = bins_per_octave
+    n_top = min(b, n_bins)
+    if n_taps <= 0:
+        n_taps = cqt2010_default_taps(sr, fmin, n_bins, b)
+    return cqt_bank(sr, fmin * 2.0 ** (float(n_bins - n_top) / float(b)), n_top, b, window, n_taps)
+
+
+def downsample2_transpose(g, h, L):
+    """Transpose of ``downsample2`` as a linear map R^L -> R^ceil(L/2): y[m] = sum_i h[i] x~[2m + i - half]
+    with x~ the mirror extension, so out[j] collects h[i] g[m] from every (m, i) whose sample
+    2m + i - half mirrors onto j.  g: [ceil(L/2)] -> [L]."""
+    g = np.ascontiguousarray(g, dtype=np.float64)
+    h = np.ascontiguousarray(h, dtype=np.float64)
+    half = h.size // 2
+    if half > L - 1:
+        raise OracleError("signal shorter than the filter's half length")
+    idx = 2 * np.arange(g.size)[:, None] + np.arange(h.size)[None, :] - half
+    idx = np.where(idx < 0, -idx, idx)
+    idx = np.where(idx >= L, 2 * (L - 1) - idx, idx)
+    out = np.zeros(L, dtype=np.float64)
+    np.add.at(out, idx, g[:, None] * h[None, :])
+    return out
+
+
+def _cqt2010v2_octaves(n_bins, b):
+    """[(a, lo, hi, first row of W)] for the octaves a = 0 (top), 1, ...: bins [lo, hi) of the output."""
+    n_top = min(b, n_bins)
+    out = []
+    for a in range((n_bins + b - 1) // b):
+        hi = n_bins - a * b
+        lo = max(hi - b, 0)
+        out.append((a, lo, hi, 2 * (n_top - (hi - lo))))
+    return out
+
+
+def cqt2010v2_bank_forward(x, W, hop=512, n_bins=84, bins_per_octave=12, fir_taps=FIR_TAPS, fmt=MAGNITUDE):
+    """The downsampling CQT layer with the given weight W (from ``cqt2010v2_bank``): Sec. III-C
+    "Downsampling" with ``stft_bank`` as each octave's convolution.  Float64 throughout.
+    out: [B, n_bins, 1 + L // hop] ([B, 2 n_bins, T] for the complex format)."""
+    x = np.atleast_2d(np.asarray(x, dtype=np.float64))
+    W = np.asarray(W, dtype=np.float64)
+    B, L = x.shape
+    T = 1 + L // hop
+    h = lowpass_fir(fir_taps, 0.5)
+    rpb = 2 if fmt == COMPLEX else 1
+    out = np.empty((B, rpb * n_bins, T), dtype=np.float64)
+    for bi in range(B):
+        xa = x[bi]
+        for a, lo, hi, r0 in _cqt2010v2_octaves(n_bins, bins_per_octave):
+            o = _stft_bank64(xa, W[r0:r0 + 2 * (hi - lo)], hop >> a, fmt)
+            out[bi, rpb * lo:rpb * hi, :] = o[:, :T]
+            if lo > 0:
+                xa = downsample2(xa, h)
+    return out
+
+
+def _stft_bank64(xa, W, hop, fmt):
+    """``stft_bank`` for one float64 waveform (that function rounds its input to float32 first)."""
+    idx = _frame_index(xa.size, W.shape[1], hop, True)
+    C = xa[idx] @ W.T
+    if fmt == COMPLEX:
+        return C.T
+    if fmt == PHASE:
+        return np.arctan2(C[:, 1::2], C[:, 0::2]).T
+    pw = (C[:, 0::2] ** 2 + C[:, 1::2] ** 2).T
+    if fmt == MAGNITUDE:
+        return np.sqrt(pw)
+    if fmt == POWER:
+        return pw
+    if fmt == LOG:
+        return np.log(np.maximum(pw, LOG_FLOOR))
+    raise OracleError("unknown output format")
+
+
+def cqt2010v2_bank_backward(x, W, mask, gout, hop=512, n_bins=84, bins_per_octave=12, fir_taps=FIR_TAPS, fmt=MAGNITUDE):
+    """Gradients of a scalar loss through ``cqt2010v2_bank_forward`` given gout = dLoss/dout: (gW, gx).
+    Chain rule, octave by octave from the lowest up: octave a's convolution gives the gradient of its
+    rows of W and of its waveform x_a (``stft_bank_backward``; frames past 1 + L // hop are not part of
+    the output, their gradient is zero); x_a also feeds octave a + 1 through ``downsample2``, whose
+    transpose carries that octave's waveform gradient back.  gW sums over the octaves and the batch;
+    taps outside ``mask`` are structure, not parameters."""
+    x = np.atleast_2d(np.asarray(x, dtype=np.float64))
+    W = np.asarray(W, dtype=np.float64)
+    gout = np.asarray(gout, dtype=np.float64)
+    B, L = x.shape
+    T = 1 + L // hop
+    h = lowpass_fir(fir_taps, 0.5)
+    rpb = 2 if fmt == COMPLEX else 1
+    octs = _cqt2010v2_octaves(n_bins, bins_per_octave)
+    gW = np.zeros_like(W)
+    gx = np.zeros_like(x)
+    for bi in range(B):
+        xs = [x[bi]]
+        for _ in octs[1:]:
+            xs.append(downsample2(xs[-1], h))
+        g_below = None  # gradient of x_{a+1}
+        for a, lo, hi, r0 in reversed(octs):
+            Wa = W[r0:r0 + 2 * (hi - lo)]
+            Ta = num_frames(xs[a].size, W.shape[1], hop >> a, True)
+            ga = np.zeros((1, rpb * (hi - lo), Ta), dtype=np.float64)
+            ga[0, :, :T] = gout[bi, rpb * lo:rpb * hi, :]
+            gWa, gxa = _stft_bank_backward64(xs[a], Wa, ga[0], hop >> a, fmt)
+            gW[r0:r0 + 2 * (hi - lo)] += gWa
+            if g_below is not None:
+                gxa = gxa + downsample2_transpose(g_below, h, xs[a].size)
+            g_below = gxa
+        gx[bi] = g_below
+    return np.where(mask, gW, 0.0), gx
+
+
+def _stft_bank_backward64(xa, W, g, hop, fmt):
+    """``stft_bank_backward`` for one float64 waveform: g [F, T] ([2F, T] complex) -> (gW, gx)."""
+    gW, gx = stft_bank_backward_f64(xa[None], W, g[None], hop=hop, center=True, fmt=fmt)
+    return gW, gx[0]

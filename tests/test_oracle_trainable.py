@@ -276,3 +276,97 @@ def test_cqt_bank_gradient_is_the_masked_central_difference(fmt):
         Wm[r, c] -= h
         fd = (loss(Wp) - loss(Wm)) / (2 * h)
         assert abs(fd - gW[r, c]) <= 1e-5 * max(1.0, np.abs(gW).max()), (r, c, fd, gW[r, c])
+
+
+# ---- the downsampling CQT with its (shared) time-domain kernels as the weight ----------------------------
+CQ2010 = dict(sr=16000, fmin=220.0, n_bins=29, bins_per_octave=12)   # three octaves, the lowest one partial (5 bins)
+
+
+@pytest.mark.parametrize("n,L", [(63, 400), (63, 401), (257, 777), (5, 12)])
+def test_downsample2_transpose_is_the_adjoint_of_downsample2(n, L):
+    # <D x, g> = <x, D^T g> for all x, g defines the transpose of a linear map; D itself is pinned to SciPy
+    rng = np.random.default_rng(n + L)
+    h = oracle.lowpass_fir(n, 0.5)
+    Ln = (L + 1) // 2
+    for _ in range(4):
+        x, g = rng.standard_normal(L), rng.standard_normal(Ln)
+        lhs = float(oracle.downsample2(x, h) @ g)
+        rhs = float(x @ oracle.downsample2_transpose(g, h, L))
+        assert abs(lhs - rhs) < 1e-12 * max(1.0, abs(lhs))
+    # column by column on the smallest case: D^T e_m is row m of the matrix of D
+    if L <= 12:
+        D = np.stack([oracle.downsample2(e, h) for e in np.eye(L)], axis=1)      # [Ln, L]
+        for m in range(Ln):
+            np.testing.assert_allclose(oracle.downsample2_transpose(np.eye(Ln)[m], h, L), D[m], atol=1e-15)
+
+
+@pytest.mark.parametrize("fmt", [oracle.MAGNITUDE, oracle.POWER, oracle.LOG, oracle.COMPLEX, oracle.PHASE])
+def test_forward_with_the_top_octave_bank_is_the_downsampling_cqt(fmt):
+    # ties the layer form (one weight, rows shared by the octaves, upper rows for the partial octave) to the
+    # pinned downsampling-CQT oracle
+    x = signals.batch(3, B=2, L=5000)
+    W, mask = oracle.cqt2010v2_bank(**CQ2010)
+    assert W.shape == (24, oracle.cqt2010_default_taps(16000, 220.0, 29, 12)) and mask.shape == W.shape
+    got = oracle.cqt2010v2_bank_forward(x, W, hop=64, n_bins=29, bins_per_octave=12, fir_taps=63, fmt=fmt)
+    ref = oracle.cqt2010v2(x, hop=64, fir_taps=63, fmt=fmt, **CQ2010)
+    assert got.shape == ref.shape
+    if fmt == oracle.PHASE:
+        re, im = oracle.cqt2010v2_complex(x, hop=64, fir_taps=63, **CQ2010)
+        strong = np.hypot(re, im) > 1e-3 * np.hypot(re, im).max()
+        assert np.abs(np.angle(np.exp(1j * (got - ref))))[strong].max() < 1e-4
+    elif fmt == oracle.LOG:
+        np.testing.assert_allclose(np.exp(0.5 * got), np.exp(0.5 * ref), atol=2e-6 * np.exp(0.5 * ref).max())
+    else:
+        # (the reference routines round each downsampled waveform to float32: 6e-8 relative)
+        np.testing.assert_allclose(got, ref, atol=2e-6 * np.abs(ref).max())
+
+
+@pytest.mark.parametrize("fmt", [oracle.MAGNITUDE, oracle.LOG, oracle.COMPLEX, oracle.PHASE])
+def test_downsampling_cqt_gradients_against_central_differences(fmt):
+    rng = np.random.default_rng(11 + fmt)
+    kw = dict(hop=32, n_bins=29, bins_per_octave=12, fir_taps=31)
+    x = signals.batch(3, B=2, L=1500).astype(np.float64)
+    W, mask = oracle.cqt2010v2_bank(**CQ2010)
+    W = W + 1e-4 * rng.standard_normal(W.shape) * mask
+    out = oracle.cqt2010v2_bank_forward(x, W, fmt=fmt, **kw)
+    gout = rng.standard_normal(out.shape)
+    gW, gx = oracle.cqt2010v2_bank_backward(x, W, mask, gout, fmt=fmt, **kw)
+    assert gW.shape == W.shape and gx.shape == x.shape and not gW[~mask].any()
+    loss = lambda Wv, xv: float((oracle.cqt2010v2_bank_forward(xv, Wv, fmt=fmt, **kw) * gout).sum())
+    rows, cols = np.nonzero(mask)
+    # rows 0..13 serve the two full octaves only, rows 14..23 (the upper five bins) all three
+    picks = list(rng.choice(len(rows), 10, replace=False)) + [int(np.argmax(rows >= 14)) + 7, 3]
+    for i in picks:
+        r, c = rows[i], cols[i]
+        h = 1e-6
+        Wp, Wm = W.copy(), W.copy()
+        Wp[r, c] += h
+        Wm[r, c] -= h
+        fd = (loss(Wp, x) - loss(Wm, x)) / (2 * h)
+        assert abs(fd - gW[r, c]) <= 1e-5 * max(1.0, np.abs(gW).max()), (r, c, fd, gW[r, c])
+    # waveform: samples at the ends (mirror reflection of every octave and of the filter) and inside
+    for b, j in [(0, 0), (0, 1), (0, 2), (1, 1499), (1, 1498), (0, 700), (1, 333), (0, 37)]:
+        h = 1e-6
+        xp, xm = x.copy(), x.copy()
+        xp[b, j] += h
+        xm[b, j] -= h
+        fd = (loss(W, xp) - loss(W, xm)) / (2 * h)
+        assert abs(fd - gx[b, j]) <= 1e-5 * max(1.0, np.abs(gx).max()), (b, j, fd, gx[b, j])
+
+
+def test_downsampling_cqt_waveform_gradient_needs_every_octave():
+    # dropping the transposed decimation (a plausible mistake) changes the waveform gradient by the lower
+    # octaves' whole share
+    rng = np.random.default_rng(3)
+    kw = dict(hop=32, n_bins=29, bins_per_octave=12, fir_taps=31)
+    x = signals.batch(3, B=1, L=1500).astype(np.float64)
+    W, mask = oracle.cqt2010v2_bank(**CQ2010)
+    out = oracle.cqt2010v2_bank_forward(x, W, **kw)
+    gout = rng.standard_normal(out.shape)
+    _, gx = oracle.cqt2010v2_bank_backward(x, W, mask, gout, **kw)
+    g_top = gout.copy()
+    g_top[:, :17] = 0.0   # only the top octave's rows
+    _, gx_top = oracle.cqt2010v2_bank_backward(x, W, mask, g_top, **kw)
+    top_only = oracle.stft_bank_backward_f64(x, W, gout[:, 17:], hop=32)[1]
+    np.testing.assert_allclose(gx_top, top_only, atol=1e-12)
+    assert np.abs(gx - gx_top).max() > 0.05 * np.abs(gx).max()
