@@ -354,6 +354,31 @@ nna_status nna_cqt_backward(const nna_plan* plan, const float* x_dev, long long 
                             size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Trainable kernels of the downsampling CQT with time-domain kernels (Sec. IV-C; the `trainable` argument of the
+ * paper's CQT2010v2 layer, Sec. III-C "Downsampling"): nna_plan_trainable also accepts plans from
+ * nna_plan_cqt2010v2.  The layer has ONE weight, the top octave's kernels W[2 n_top, n_taps] (n_top =
+ * min(bins_per_octave, n_bins); rows and supports as for nna_plan_cqt with the top octave's bins): octave a
+ * convolves the waveform downsampled a times with the same rows at hop / 2^a; a partial lowest octave of m < n_top
+ * bins uses the rows of the upper m bins, 2 (n_top - m) onwards.  The decimation filter is not a parameter.
+ *   nna_plan_get_bank / nna_plan_set_bank   w_dev[2 n_top, n_taps]; set rewrites every octave's copy.
+ *   nna_cqt2010v2_backward   given gout_dev[B, n_bins, T] ([B, 2 n_bins, T] for NNA_OUT_COMPLEX) = dLoss/d(output of
+ *                      nna_cqt2010v2 for x_dev), writes gw_dev[2 n_top, n_taps] = the sum over the octaves of each
+ *                      octave's kernel gradient (definitions of nna_stft_backward, on that octave's waveform and
+ *                      rows of gout) and/or gx_dev[B, L]: from the lowest octave up, the octave's own waveform
+ *                      gradient plus the transposed decimation step (filter taps and mirror padding of the
+ *                      forward step, transposed) applied to the gradient of the octave below.  The downsampled
+ *                      waveforms are recomputed inside.  workspace_dev: 256-byte aligned,
+ *                      nna_cqt2010v2_backward_workspace bytes (the octaves' waveforms, one octave's G, two
+ *                      waveform gradients).  Outputs are overwritten; atomics as in nna_stft_backward; errors
+ *                      as there and as for nna_cqt2010v2.  The deepest octaves (hop below 128) run the one-rate
+ *                      layer's waveform-gradient kernel far below its best: correct, not tuned.
+ */
+nna_status nna_cqt2010v2_backward_workspace(const nna_plan* plan, long long B, long long L, size_t* bytes);
+nna_status nna_cqt2010v2_backward(const nna_plan* plan, const float* x_dev, long long B, long long L,
+                                  const float* gout_dev, float* gw_dev, float* gx_dev, void* workspace_dev,
+                                  size_t workspace_bytes, void* hip_stream);
+
+/*
  * Trainable Mel layer (Sec. IV-C; the trainable_mel / trainable_STFT arguments of the paper's
  * MelSpectrogram layer, Sec. III-B): both stages of a plan from nna_plan_mel as parameters.
  * nna_plan_trainable also accepts Mel plans; nna_plan_get_bank / nna_plan_set_bank then address the
@@ -407,7 +432,8 @@ nna_status nna_plan_mel_weights(const nna_plan* plan, double* host_out, size_t c
 nna_status nna_plan_spectral_kernels(const nna_plan* plan, double* host_out, size_t cap);
 
 /*
- * Plan facts, each written if its pointer is non-NULL: kind, logical bank rows, taps K,
+ * Plan facts, each written if its pointer is non-NULL: kind, logical bank rows (nna_plan_cqt2010v2: of the top
+ * octave's kernels, which every octave uses; nna_plan_cqt2010: 0, its parts hold the banks), taps K,
  * output bins, flops the kernels execute per frame (multiply-add = 2, zero-padded
  * taps they do not skip included) and algorithmic flops per frame (non-zero taps only:
  * 2*K*rows_nonzero for the DFT bank, 4*sum_k N_k for the CQT, plus 2*nnz(W) for Mel;

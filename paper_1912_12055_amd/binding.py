@@ -32,6 +32,7 @@ EXPORTS = [
     "nna_plan_get_mel_weights", "nna_plan_set_mel_weights", "nna_mel_backward_workspace", "nna_mel_backward",
     "nna_plan_trainable", "nna_plan_get_bank", "nna_plan_set_bank", "nna_stft_backward_workspace", "nna_stft_backward",
     "nna_cqt_backward_workspace", "nna_cqt_backward", "nna_mel_with_stft", "nna_cqt2010v2_static",
+    "nna_cqt2010v2_backward_workspace", "nna_cqt2010v2_backward",
     "nna_plan_destroy",
     "nna_status_str", "nna_last_error",
 ]
@@ -97,6 +98,8 @@ def lib():
         L.nna_stft_backward.argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _VP, _VP, _c.c_size_t, _VP]
         L.nna_cqt_backward_workspace.argtypes = [_VP, _LL, _LL, _c.POINTER(_c.c_size_t)]
         L.nna_cqt_backward.argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _VP, _VP, _c.c_size_t, _VP]
+        L.nna_cqt2010v2_backward_workspace.argtypes = [_VP, _LL, _LL, _c.POINTER(_c.c_size_t)]
+        L.nna_cqt2010v2_backward.argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _VP, _VP, _c.c_size_t, _VP]
         L.nna_mel_with_stft.argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _VP]
         L.nna_out_shape.argtypes = [_VP, _LL, _LL, _c.POINTER(_LL), _c.POINTER(_LL)]
         for name in ("nna_stft", "nna_mel", "nna_cqt", "nna_cqt1992", "nna_cqt2010v2_static"):
@@ -462,6 +465,36 @@ def nna_cqt_backward(plan: Plan, x, gout, want_gw=True, want_gx=True, workspace=
     _check(lib().nna_cqt_backward(plan.handle, x.data_ptr(), B, L, gout.data_ptr(),
                                   gw.data_ptr() if want_gw else None, gx.data_ptr() if want_gx else None,
                                   workspace.data_ptr(), ws_bytes, _stream_of(x, stream)))
+    return gw, gx
+
+
+def nna_cqt2010v2_backward_workspace(plan: Plan, B: int, L: int) -> int:
+    n = _c.c_size_t()
+    _check(lib().nna_cqt2010v2_backward_workspace(plan.handle, B, L, _c.byref(n)))
+    return n.value
+
+
+def nna_cqt2010v2_backward(plan: Plan, x, gout, want_gw=True, want_gx=True, workspace=None, stream=None):
+    """(gW[2 n_top, n_taps] or None, gx[B, L] or None) = gradients of a loss through nna_cqt2010v2(plan, x), given
+    gout = dLoss/dout.  `workspace`: a CUDA tensor of nna_cqt2010v2_backward_workspace bytes (made here if None)."""
+    import torch
+
+    if not (isinstance(x, torch.Tensor) and x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.dim() == 2):
+        raise TypeError("x must be a contiguous float32 CUDA tensor [B, L]")
+    B, L = x.shape
+    bins, frames = nna_out_shape(plan, B, L)
+    if not (gout.is_cuda and gout.dtype == torch.float32 and gout.is_contiguous()
+            and tuple(gout.shape) == (B, bins, frames) and gout.device == x.device):
+        raise TypeError(f"gout must be a contiguous float32 CUDA tensor of shape {(B, bins, frames)}")
+    need = nna_cqt2010v2_backward_workspace(plan, B, L)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    gw = torch.empty(_bank_shape(plan), dtype=torch.float32, device=x.device) if want_gw else None
+    gx = torch.empty_like(x) if want_gx else None
+    _check(lib().nna_cqt2010v2_backward(plan.handle, x.data_ptr(), B, L, gout.data_ptr(),
+                                        gw.data_ptr() if want_gw else None, gx.data_ptr() if want_gx else None,
+                                        workspace.data_ptr(), ws_bytes, _stream_of(x, stream)))
     return gw, gx
 
 

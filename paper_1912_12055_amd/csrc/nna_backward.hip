@@ -9,8 +9,8 @@ extern "C" {
 // ---- trainable Fourier kernels (Sec. IV-C) ----------------------------------------------------
 static nna_status check_trainable_kind(const nna_plan* plan) {
   if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
-  if (plan->kind != NNA_KIND_STFT && plan->kind != NNA_KIND_MEL && plan->kind != NNA_KIND_CQT)
-    return fail(NNA_ERR_INVALID_ARG, "only plans from nna_plan_stft, nna_plan_stft_scaled, nna_plan_mel and nna_plan_cqt have trainable kernels");
+  if (plan->kind != NNA_KIND_STFT && plan->kind != NNA_KIND_MEL && plan->kind != NNA_KIND_CQT && plan->kind != NNA_KIND_CQT2010V2)
+    return fail(NNA_ERR_INVALID_ARG, "only plans from nna_plan_stft, nna_plan_stft_scaled, nna_plan_mel, nna_plan_cqt and nna_plan_cqt2010v2 have trainable kernels");
   if (plan->precision != NNA_PREC_F32) return fail(NNA_ERR_UNSUPPORTED, "trainable kernels need a float32 plan");
   if (plan->device < 0) return fail(NNA_ERR_UNSUPPORTED, "host-only plan (device = -1)");
   return NNA_OK;
@@ -166,14 +166,27 @@ static nna_status make_cqt_trainable(nna_plan* plan) {
   return s;
 }
 
+static bool is_trainable(const nna_plan* plan) {
+  if (plan->kind != NNA_KIND_CQT2010V2) return plan->d_wrm != nullptr;
+  for (const nna_plan* sub : plan->octave)
+    if (!sub->d_wrm) return false;
+  return true;
+}
+
 nna_status nna_plan_trainable(nna_plan* plan) {
   nna_status s = check_trainable_kind(plan);
   if (s != NNA_OK) return s;
-  if (plan->d_wrm) return NNA_OK;
+  if (is_trainable(plan)) return NNA_OK;
   DeviceGuard guard;
   hipError_t e = guard.enter(plan->device);
   if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
   if (plan->kind == NNA_KIND_CQT) return make_cqt_trainable(plan);
+  if (plan->kind == NNA_KIND_CQT2010V2) {
+    // every octave convolves with (rows of) the one weight: each keeps its own streaming-order copy
+    for (nna_plan* sub : plan->octave)
+      if (!sub->d_wrm && (s = make_cqt_trainable(sub)) != NNA_OK) return s;
+    return NNA_OK;
+  }
   plan->rows_pad = plan->n_rt * ST_ROWS;
   plan->kp = (plan->K + nna::BW_NT - 1) / nna::BW_NT * nna::BW_NT;
   const size_t bytes = (size_t)plan->rows_pad * plan->kp * sizeof(float);
@@ -224,8 +237,14 @@ nna_status nna_plan_trainable(nna_plan* plan) {
 static nna_status check_trainable(const nna_plan* plan) {
   nna_status s = check_trainable_kind(plan);
   if (s != NNA_OK) return s;
-  if (!plan->d_wrm) return fail(NNA_ERR_INVALID_ARG, "call nna_plan_trainable on the plan first");
+  if (!is_trainable(plan)) return fail(NNA_ERR_INVALID_ARG, "call nna_plan_trainable on the plan first");
   return NNA_OK;
+}
+
+// first row, in the weight W[2 n_top, n_taps] of a downsampling plan, of the kernels octave `sub` uses: a partial
+// lowest octave holds the upper bins of an octave
+static long long octave_weight_row(const nna_plan* plan, const nna_plan* sub) {
+  return plan->octave[0]->conv_rows - sub->conv_rows;
 }
 
 nna_status nna_plan_get_bank(const nna_plan* plan, float* w_dev, void* hip_stream) {
@@ -237,6 +256,8 @@ nna_status nna_plan_get_bank(const nna_plan* plan, float* w_dev, void* hip_strea
   if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
   if (plan->kind == NNA_KIND_CQT)
     e = nna::launch_cqt_bank_to_logical(cqt_bank_params(plan, w_dev), reinterpret_cast<hipStream_t>(hip_stream));
+  else if (plan->kind == NNA_KIND_CQT2010V2)
+    e = nna::launch_cqt_bank_to_logical(cqt_bank_params(plan->octave[0], w_dev), reinterpret_cast<hipStream_t>(hip_stream));
   else
     e = nna::launch_bank_to_logical(permute_params(plan, w_dev), reinterpret_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail_hip(e, "kernel launch");
@@ -252,7 +273,13 @@ nna_status nna_plan_set_bank(nna_plan* plan, const float* w_dev, void* hip_strea
   if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
   if (plan->kind == NNA_KIND_CQT)
     e = nna::launch_cqt_bank_from_logical(cqt_bank_params(plan, const_cast<float*>(w_dev)), reinterpret_cast<hipStream_t>(hip_stream));
-  else
+  else if (plan->kind == NNA_KIND_CQT2010V2) {
+    for (const nna_plan* sub : plan->octave) {
+      float* rows = const_cast<float*>(w_dev) + octave_weight_row(plan, sub) * sub->K;
+      e = nna::launch_cqt_bank_from_logical(cqt_bank_params(sub, rows), reinterpret_cast<hipStream_t>(hip_stream));
+      if (e != hipSuccess) break;
+    }
+  } else
     e = nna::launch_bank_from_logical(permute_params(plan, const_cast<float*>(w_dev)), reinterpret_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail_hip(e, "kernel launch");
   return NNA_OK;
@@ -376,32 +403,20 @@ nna_status nna_cqt_backward_workspace(const nna_plan* plan, long long B, long lo
   return NNA_OK;
 }
 
-nna_status nna_cqt_backward(const nna_plan* plan, const float* x_dev, long long B, long long L, const float* gout_dev,
-                            float* gw_dev, float* gx_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
-  nna_status s = check_trainable(plan);
-  if (s != NNA_OK) return s;
-  if (plan->kind != NNA_KIND_CQT) return fail(NNA_ERR_INVALID_ARG, "plan was built for a different transform");
-  if (!gout_dev) return fail(NNA_ERR_INVALID_ARG, "gout_dev is NULL");
-  if (!gw_dev && !gx_dev) return fail(NNA_ERR_INVALID_ARG, "gw_dev and gx_dev are both NULL: nothing to compute");
-  long long T = 0;
-  if ((s = check_call(plan, NNA_KIND_CQT, x_dev, B, L, gw_dev ? gw_dev : gx_dev, &T)) != NNA_OK) return s;
-  size_t need = 0;
-  if ((s = nna_cqt_backward_workspace(plan, B, L, &need)) != NNA_OK) return s;
-  if (!workspace_dev || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace_dev) & 255))
-    return fail(NNA_ERR_INVALID_ARG, "workspace_dev is NULL, not 256-byte aligned or smaller than nna_cqt_backward_workspace asks for");
+// The backward pass of one constant-Q convolution: plan's bank over T frames of each of the B waveforms in x_dev.
+// gout points at the plan's first output row of waveform 0 (consecutive waveforms gout_wave_stride floats apart);
+// gw (may be NULL) receives atomic adds -- zeroed here if zero_gw, else accumulated onto; gx (may be NULL) is
+// overwritten.  gbuf: rows_pad x padded frames floats.  Arguments already checked, device current.
+static nna_status cqt_backward_core(const nna_plan* plan, const float* x_dev, long long B, long long L, long long T,
+                                    const float* gout, long long gout_wave_stride, float* gw_dev, bool zero_gw,
+                                    float* gx_dev, float* gbuf, hipStream_t stream) {
   const int extra = (plan->max_jspan - 1) * plan->row_step;
   const int M = pick_tile_frames(CQ_FRAMES, T, extra, CQ_LDS_ROWS_MAX);
   if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
-  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
-  DeviceGuard guard;
-  hipError_t e = guard.enter(plan->device);
-  if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
-
-  float* gbuf = static_cast<float*>(workspace_dev);
   const long long n_frames = B * T, gpitch = bw_gpitch(n_frames);
   // 1. G = dLoss/dC: the forward contraction again with the derivative of the output format as its
   //    epilogue.  The kernel writes the rows of existing bins and frames; the padding stays zero.
-  e = nna::launch_fill_zero(gbuf, (long long)plan->rows_pad * gpitch, stream);
+  hipError_t e = nna::launch_fill_zero(gbuf, (long long)plan->rows_pad * gpitch, stream);
   if (e != hipSuccess) return fail_hip(e, "kernel launch");
   nna::CqtParams P;
   std::memset(&P, 0, sizeof(P));
@@ -419,8 +434,8 @@ nna_status nna_cqt_backward(const nna_plan* plan, const float* x_dev, long long 
   const long long nseg = 1 + (M - 1 + T - 1) / T;
   P.lds_rows = (int)((M + nseg * extra + 63) / 64 * 64);
   P.n_ft = (n_frames + M - 1) / M;
-  P.gout = gout_dev;
-  P.gout_wave_stride = (long long)plan->out_rows() * T;
+  P.gout = gout;
+  P.gout_wave_stride = gout_wave_stride;
   P.gbuf = gbuf;
   P.rows_pad = plan->rows_pad;
   e = nna::launch_cqt(P, stream);
@@ -449,8 +464,10 @@ nna_status nna_cqt_backward(const nna_plan* plan, const float* x_dev, long long 
   Q.n_ct = plan->n_ct;
   Q.n_qt = (T + plan->n_shift - 1 + nna::BW_MT - 1) / nna::BW_MT;
   if (gw_dev) {
-    e = nna::launch_fill_zero(gw_dev, (long long)plan->conv_rows * plan->K, stream);
-    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    if (zero_gw) {
+      e = nna::launch_fill_zero(gw_dev, (long long)plan->conv_rows * plan->K, stream);
+      if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    }
     const long long chunks = gpitch / nna::BW_KC;
     // the tile count is whatever the supports give: aim at eight rounds of the 512 resident workgroups, so
     // that a partly filled last round costs little
@@ -465,6 +482,152 @@ nna_status nna_cqt_backward(const nna_plan* plan, const float* x_dev, long long 
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
     e = nna::launch_bw_wave(Q, stream);
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  }
+  return NNA_OK;
+}
+
+nna_status nna_cqt_backward(const nna_plan* plan, const float* x_dev, long long B, long long L, const float* gout_dev,
+                            float* gw_dev, float* gx_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+  nna_status s = check_trainable(plan);
+  if (s != NNA_OK) return s;
+  if (plan->kind != NNA_KIND_CQT) return fail(NNA_ERR_INVALID_ARG, "plan was built for a different transform");
+  if (!gout_dev) return fail(NNA_ERR_INVALID_ARG, "gout_dev is NULL");
+  if (!gw_dev && !gx_dev) return fail(NNA_ERR_INVALID_ARG, "gw_dev and gx_dev are both NULL: nothing to compute");
+  long long T = 0;
+  if ((s = check_call(plan, NNA_KIND_CQT, x_dev, B, L, gw_dev ? gw_dev : gx_dev, &T)) != NNA_OK) return s;
+  size_t need = 0;
+  if ((s = nna_cqt_backward_workspace(plan, B, L, &need)) != NNA_OK) return s;
+  if (!workspace_dev || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace_dev) & 255))
+    return fail(NNA_ERR_INVALID_ARG, "workspace_dev is NULL, not 256-byte aligned or smaller than nna_cqt_backward_workspace asks for");
+  DeviceGuard guard;
+  hipError_t e = guard.enter(plan->device);
+  if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+  return cqt_backward_core(plan, x_dev, B, L, T, gout_dev, (long long)plan->out_rows() * T, gw_dev, true, gx_dev,
+                           static_cast<float*>(workspace_dev), reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+// ---- trainable kernels of the downsampling CQT (time-domain kernels; the paper's CQT2010v2 layer) -----------------
+static size_t ws256f(long long floats) { return ((size_t)floats * sizeof(float) + 255) / 256 * 256; }
+
+// The workspace: the waveforms of octaves 1.. (kept from the forward recursion), G of one octave, and two waveform
+// gradients (octaves 1 and 2: the deeper ones alternate between them).  Offsets in bytes; false if L is too short.
+struct Cqt2010BwLayout {
+  long long La[MAX_OCTAVES];
+  size_t x_off[MAX_OCTAVES];  // [a] for a >= 1
+  size_t g_off, gx_off[2], total;
+};
+static bool cqt2010v2_bw_layout(const nna_plan* plan, long long B, long long L, Cqt2010BwLayout& W) {
+  if (!cqt2010_lengths(plan, L, W.La)) return false;
+  const int n_oct = (int)plan->octave.size();
+  const long long T = 1 + L / plan->hop;
+  size_t off = 0;
+  for (int a = 1; a < n_oct; ++a) {
+    W.x_off[a] = off;
+    off += ws256f(B * W.La[a]);
+  }
+  int rows_pad = 0;
+  for (const nna_plan* sub : plan->octave) rows_pad = std::max(rows_pad, sub->rows_pad);
+  W.g_off = off;
+  off += ws256f((long long)rows_pad * bw_gpitch(B * T));
+  for (int i = 0; i < 2; ++i) {
+    W.gx_off[i] = off;
+    if (n_oct > 1 + i) off += ws256f(B * W.La[1 + i]);
+  }
+  W.total = off;
+  return true;
+}
+
+static nna_status check_cqt2010v2_bw(const nna_plan* plan, long long B, long long L) {
+  nna_status s = check_trainable(plan);
+  if (s != NNA_OK) return s;
+  if (plan->kind != NNA_KIND_CQT2010V2) return fail(NNA_ERR_INVALID_ARG, "plan was built for a different transform");
+  if (B < 1) return fail(NNA_ERR_SHAPE, "B must be >= 1");
+  const long long T = 1 + L / plan->hop;
+  if (L < 1 || T > 0x7fffffffLL / 4 || L > 0x7fffffffLL - 4LL * plan->K - 64 || B > 0x7fffffffLL || B > (1LL << 40) / T)
+    return fail(NNA_ERR_SHAPE, "batch too large");
+  return NNA_OK;
+}
+
+nna_status nna_cqt2010v2_backward_workspace(const nna_plan* plan, long long B, long long L, size_t* bytes) {
+  nna_status s = check_cqt2010v2_bw(plan, B, L);
+  if (s != NNA_OK) return s;
+  if (!bytes) return fail(NNA_ERR_INVALID_ARG, "bytes is NULL");
+  Cqt2010BwLayout W;
+  if (!cqt2010v2_bw_layout(plan, B, L, W))
+    return fail(NNA_ERR_SHAPE, "L is too short: every octave's waveform must exceed the reflection padding, and all but the lowest hold one frame of the decimation filter");
+  *bytes = W.total;
+  return NNA_OK;
+}
+
+nna_status nna_cqt2010v2_backward(const nna_plan* plan, const float* x_dev, long long B, long long L,
+                                  const float* gout_dev, float* gw_dev, float* gx_dev, void* workspace_dev,
+                                  size_t workspace_bytes, void* hip_stream) {
+  nna_status s = check_cqt2010v2_bw(plan, B, L);
+  if (s != NNA_OK) return s;
+  if (!x_dev || !gout_dev) return fail(NNA_ERR_INVALID_ARG, "x_dev / gout_dev is NULL");
+  if (!gw_dev && !gx_dev) return fail(NNA_ERR_INVALID_ARG, "gw_dev and gx_dev are both NULL: nothing to compute");
+  Cqt2010BwLayout W;
+  if (!cqt2010v2_bw_layout(plan, B, L, W))
+    return fail(NNA_ERR_SHAPE, "L is too short: every octave's waveform must exceed the reflection padding, and all but the lowest hold one frame of the decimation filter");
+  if (!workspace_dev || workspace_bytes < W.total || (reinterpret_cast<uintptr_t>(workspace_dev) & 255))
+    return fail(NNA_ERR_INVALID_ARG, "workspace_dev is NULL, not 256-byte aligned or smaller than nna_cqt2010v2_backward_workspace asks for");
+  const int n_oct = (int)plan->octave.size();
+  const long long T = 1 + L / plan->hop;
+  // every launch of the call must fit before the first one is enqueued
+  for (const nna_plan* sub : plan->octave)
+    if (pick_tile_frames(CQ_FRAMES, T, (sub->max_jspan - 1) * sub->row_step, CQ_LDS_ROWS_MAX) < 1)
+      return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  DeviceGuard guard;
+  hipError_t e = guard.enter(plan->device);
+  if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+  char* ws = static_cast<char*>(workspace_dev);
+  const float* xa[MAX_OCTAVES];
+  xa[0] = x_dev;
+  // the forward recursion: every octave's waveform is kept
+  for (int a = 1; a < n_oct; ++a) {
+    float* dst = reinterpret_cast<float*>(ws + W.x_off[a]);
+    if ((s = run_fir(plan->fir, xa[a - 1], B, W.La[a - 1], dst, W.La[a], hip_stream)) != NNA_OK) return s;
+    xa[a] = dst;
+  }
+  float* gbuf = reinterpret_cast<float*>(ws + W.g_off);
+  const nna_plan* top = plan->octave[0];
+  if (gw_dev) {
+    e = nna::launch_fill_zero(gw_dev, (long long)top->conv_rows * top->K, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  }
+  const long long out_stride = (long long)plan->out_rows() * T;
+  const int rpb = plan->fmt == NNA_OUT_COMPLEX ? 2 : 1;
+  // from the lowest octave up: octave a's own convolution, then what octave a + 1 sends back through the filter
+  for (int a = n_oct - 1; a >= 0; --a) {
+    const nna_plan* sub = plan->octave[a];
+    int lo, hi;
+    octave_bins(plan->n_bins, plan->bpo, a, lo, hi);
+    float* ga = !gx_dev ? nullptr : a == 0 ? gx_dev : reinterpret_cast<float*>(ws + W.gx_off[(a - 1) & 1]);
+    float* gwa = gw_dev ? gw_dev + octave_weight_row(plan, sub) * sub->K : nullptr;
+    if ((s = cqt_backward_core(sub, xa[a], B, W.La[a], T, gout_dev + (long long)rpb * lo * T, out_stride, gwa, false, ga, gbuf,
+                               stream)) != NNA_OK)
+      return s;
+    if (ga && a + 1 < n_oct) {
+      nna::FirTParams F;
+      std::memset(&F, 0, sizeof(F));
+      F.he = plan->fir->d_fir_he;
+      F.ho = plan->fir->d_fir_ho;
+      F.ne = (int)plan->fir->h_fir_he.size();
+      F.no = (int)plan->fir->h_fir_ho.size();
+      F.ve0 = plan->fir->fir_ve0;
+      F.vo0 = plan->fir->fir_vo0;
+      F.L = W.La[a];
+      F.Ln = W.La[a + 1];
+      const float* gb = reinterpret_cast<const float*>(ws + W.gx_off[a & 1]);
+      for (long long b0 = 0; b0 < B; b0 += 65535) {  // the grid's second dimension holds at most 65,535 waveforms
+        F.B = std::min(B - b0, 65535LL);
+        F.g = gb + b0 * F.Ln;
+        F.gx = ga + b0 * F.L;
+        e = nna::launch_fir_transpose_add(F, stream);
+        if (e != hipSuccess) return fail_hip(e, "kernel launch");
+      }
+    }
   }
   return NNA_OK;
 }

@@ -311,6 +311,8 @@ inline void octave_bins(int n_bins, int bpo, int a, int& lo, int& hi) {
   lo = std::max(0, hi - bpo);
 }
 bool cqt2010_lengths(const nna_plan* plan, long long L, long long (&La)[MAX_OCTAVES]);
+// one decimation step: y[B, Ln] from x[B, L], Ln = ceil(L / 2) (arguments checked by the caller)
+nna_status run_fir(const nna_plan* fir, const float* x, long long B, long long L, float* y, long long Ln, void* hip_stream);
 
 }  // namespace host
 }  // namespace nna

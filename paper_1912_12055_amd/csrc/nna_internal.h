@@ -207,6 +207,18 @@ struct BwParams {
   long long n_qt;        // hop-row tiles of a waveform's padded signal: ceil((T + n_shift - 1) / BW_MT)
 };
 
+// Transposed decimation step (backward pass of the downsampling CQT): gx[B, L] += D^T g, g[B, Ln], with the taps
+// as the decimation kernel holds them (FirParams)
+struct FirTParams {
+  const float* g;
+  float* gx;
+  const float* he;
+  const float* ho;
+  int ne, no, ve0, vo0;
+  long long B, L, Ln;
+};
+hipError_t launch_fir_transpose_add(const FirTParams& p, hipStream_t stream);
+
 // constant-Q bank of a trainable plan: the caller's [rows][K] tensor <-> streaming order / row-major copy
 struct CqtBankParams {
   float* bank;           // streaming order, n_bank floats

@@ -717,7 +717,8 @@ nna_status nna_plan_info(const nna_plan* plan, int* kind, long long* bank_rows, 
   if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
   if (kind) *kind = plan->kind;
   if (bank_rows)
-    *bank_rows = plan->kind == NNA_KIND_CQT2010V2 || plan->kind == NNA_KIND_CQT2010 ? 0
+    *bank_rows = plan->kind == NNA_KIND_CQT2010   ? 0
+                 : plan->kind == NNA_KIND_CQT2010V2 ? (long long)plan->octave[0]->conv_rows  // the one weight all octaves share
                  : plan->kind == NNA_KIND_CQT     ? (long long)plan->conv_rows
                                                   : 2LL * (plan->freq_scale ? plan->n_half : plan->n_half + 1);
   if (taps) *taps = plan->K;

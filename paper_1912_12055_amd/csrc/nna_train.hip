@@ -46,6 +46,32 @@ __global__ void fill_zero_kernel(float* __restrict__ p, long long n) {
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.f;
 }
 
+// Transposed decimation (Sec. III-C "Downsampling", backwards): the forward step is
+//     y[m] = sum_v he[v] x~[2 (m + ve0 + v)] + sum_v ho[v] x~[2 (m + vo0 + v) + 1],   x~ = x mirrored at both ends,
+// so sample p of the extended signal collects  u[p] = sum_v taps[v] g[i - v0 - v]  (p = 2 i even: he, ve0;
+// p = 2 i + 1 odd: ho, vo0), and stored sample j collects u at j and at its mirror images -j and 2 (L - 1) - j.
+__device__ __forceinline__ float firt_u(const FirTParams& P, const float* __restrict__ g, long long p) {
+  const long long i = p >> 1;  // floor, also for negative p
+  const bool odd = p & 1;
+  const float* __restrict__ taps = odd ? P.ho : P.he;
+  const long long n = odd ? P.no : P.ne, top = i - (odd ? P.vo0 : P.ve0);  // m = top - v must lie in [0, Ln)
+  const long long vlo = top - (P.Ln - 1) > 0 ? top - (P.Ln - 1) : 0, vhi = top < n - 1 ? top : n - 1;
+  float acc = 0.f;
+  for (long long v = vlo; v <= vhi; ++v) acc += taps[v] * g[top - v];
+  return acc;
+}
+
+__global__ __launch_bounds__(256) void fir_transpose_add_kernel(const FirTParams P) {
+  const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (j >= P.L) return;
+  const long long b = blockIdx.y;
+  const float* __restrict__ g = P.g + b * P.Ln;
+  float acc = firt_u(P, g, j);
+  if (j >= 1) acc += firt_u(P, g, -j);
+  if (j <= P.L - 2) acc += firt_u(P, g, 2 * (P.L - 1) - j);
+  P.gx[b * P.L + j] += acc;
+}
+
 // frames [f0, f1) of every row of the blocked G buffer [frame / 32][rows_pad][frame % 32]
 __global__ void fill_zero_frames_kernel(float* __restrict__ p, long long rows_pad, long long f0, long long f1) {
   const long long w = f1 - f0, n = rows_pad * w;
@@ -777,6 +803,14 @@ hipError_t launch_fill_zero(float* p, long long n, hipStream_t stream) {
   clear_stale_error();
   if (n <= 0) return hipSuccess;
   hipLaunchKernelGGL(fill_zero_kernel, dim3(grid_for(n, 256 * 8)), dim3(256), 0, stream, p, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_fir_transpose_add(const FirTParams& p, hipStream_t stream) {
+  clear_stale_error();
+  if (p.L < 1 || p.Ln != (p.L + 1) / 2 || p.B < 1 || p.B > 65535 || p.L > 0x3fffffffLL || p.ne < 1 || p.no < 1)
+    return hipErrorInvalidValue;
+  hipLaunchKernelGGL(fir_transpose_add_kernel, dim3((unsigned)((p.L + 255) / 256), (unsigned)p.B), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 

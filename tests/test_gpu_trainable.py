@@ -421,6 +421,109 @@ def test_cqt_backward_config5_full_sampled(nb):
     assert not gx[rest].any()
 
 
+# ---- trainable kernels of the downsampling CQT (time-domain kernels) -----------------------------------
+# (name, sr, fmin, n_bins, bins/octave, hop, fir taps, B, L, output format)
+CQT2010V2_BACKWARD_CASES = [
+    ("three-octaves-partial-lowest", 16000, 220.0, 29, 12, 64, 63, 3, 6000, oracle.MAGNITUDE),
+    ("power", 16000, 220.0, 29, 12, 64, 63, 2, 5000, oracle.POWER),
+    ("log", 16000, 220.0, 29, 12, 64, 63, 2, 5000, oracle.LOG),
+    ("complex", 16000, 220.0, 29, 12, 64, 63, 2, 5000, oracle.COMPLEX),
+    ("phase", 16000, 220.0, 29, 12, 64, 63, 2, 5000, oracle.PHASE),
+    ("single-octave", 16000, 1000.0, 12, 12, 128, 0, 2, 9000, oracle.MAGNITUDE),
+    ("seven-octaves-default-filter-odd-lengths", 22050, 32.70, 84, 12, 512, 0, 2, 22051, oracle.MAGNITUDE),
+    ("hops-down-to-4-many-short-waveforms", 16000, 500.0, 16, 4, 32, 31, 20, 3000, oracle.POWER),
+]
+
+
+def _cqt2010v2_plan(nb, sr, fmin, n_bins, bpo, hop, fir, fmt):
+    return nb.nna_plan_trainable(nb.nna_plan_cqt2010v2(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo,
+                                                       fir_taps=fir, fmt=fmt, device=0))
+
+
+def test_cqt2010v2_get_bank_is_the_top_octaves_bank_and_set_bank_reaches_every_octave(nb):
+    import torch
+    _say("cqt2010v2 trainable: get / set bank")
+    sr, fmin, n_bins, bpo, hop = 16000, 220.0, 29, 12, 64
+    plan = _cqt2010v2_plan(nb, sr, fmin, n_bins, bpo, hop, 63, oracle.MAGNITUDE)
+    W0, mask = oracle.cqt2010v2_bank(sr, fmin, n_bins, bpo)
+    W = nb.nna_plan_get_bank(plan).cpu().numpy()
+    assert W.shape == W0.shape == (24, plan.info()["taps"]) and not W[~mask].any()
+    assert np.abs(W - W0).max() <= 1e-7 * np.abs(W0).max()
+    x = _rand(3, 6000, 2)
+    ref = oracle.cqt2010v2(x, sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, fir_taps=63)
+    assert _peak_err(nb.nna_cqt2010v2(plan, _dev(x)).cpu().numpy(), ref) < 1e-5
+    # a different weight: every octave -- the partial lowest one through its upper rows -- must follow it
+    rng = np.random.default_rng(3)
+    Wn = (W + 0.3 * np.abs(W).max() * rng.standard_normal(W.shape)).astype(np.float32)
+    nb.nna_plan_set_bank(plan, _dev(Wn))
+    Wm = np.where(mask, Wn, np.float32(0))
+    assert np.array_equal(nb.nna_plan_get_bank(plan).cpu().numpy(), Wm)
+    ref = oracle.cqt2010v2_bank_forward(x, Wm, hop=hop, n_bins=n_bins, bins_per_octave=bpo, fir_taps=63)
+    got = nb.nna_cqt2010v2(plan, _dev(x)).cpu().numpy()
+    for lo, hi in ((17, 29), (5, 17), (0, 5)):
+        assert _peak_err(got[:, lo:hi], ref[:, lo:hi]) < 1e-5, (lo, hi)
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("case", CQT2010V2_BACKWARD_CASES, ids=[c[0] for c in CQT2010V2_BACKWARD_CASES])
+def test_cqt2010v2_backward_parity_small(nb, case):
+    import torch
+    name, sr, fmin, n_bins, bpo, hop, fir, B, L, fmt = case
+    _say(f"cqt2010v2 backward {name}: sr={sr} bins={n_bins}/{bpo} hop={hop} fir={fir} B={B} L={L} fmt={fmt}")
+    plan = _cqt2010v2_plan(nb, sr, fmin, n_bins, bpo, hop, fir, fmt)
+    _, mask = oracle.cqt2010v2_bank(sr, fmin, n_bins, bpo)
+    rng = np.random.default_rng(11)
+    W = nb.nna_plan_get_bank(plan).cpu().numpy()
+    W = np.where(mask, W * (1.0 + 0.2 * rng.standard_normal(W.shape)), 0).astype(np.float32)  # no longer the initial bank
+    nb.nna_plan_set_bank(plan, _dev(W))
+    x = _rand(B, L, 12)
+    kw = dict(hop=hop, n_bins=n_bins, bins_per_octave=bpo, fir_taps=fir or oracle.FIR_TAPS, fmt=fmt)
+    ref_out = oracle.cqt2010v2_bank_forward(x, W, **kw)
+    out = nb.nna_cqt2010v2(plan, _dev(x)).cpu().numpy()
+    assert out.shape == ref_out.shape
+    if fmt not in (oracle.PHASE, oracle.LOG):
+        assert _peak_err(out, ref_out) < TOL
+    gout = rng.standard_normal(ref_out.shape).astype(np.float32)
+    ref_gw, ref_gx = oracle.cqt2010v2_bank_backward(x, W, mask, gout, **kw)
+    need = nb.nna_cqt2010v2_backward_workspace(plan, B, L)
+    ws = torch.full(((need + 3) // 4,), float("nan"), dtype=torch.float32, device="cuda:0").view(torch.uint8)
+    gw, gx = nb.nna_cqt2010v2_backward(plan, _dev(x), _dev(gout), workspace=ws)
+    torch.cuda.synchronize()
+    gw = gw.cpu().numpy()
+    assert np.isfinite(gw).all() and not gw[~mask].any()
+    e_w, e_x = _peak_err(gw, ref_gw), _peak_err(gx.cpu().numpy(), ref_gx)
+    _say(f"  bank gradient {e_w:.3e}, waveform gradient {e_x:.3e}")
+    assert e_w < TOL and e_x < TOL
+    # either gradient alone
+    gw1, none = nb.nna_cqt2010v2_backward(plan, _dev(x), _dev(gout), want_gx=False)
+    assert none is None and _peak_err(gw1.cpu().numpy(), ref_gw) < TOL
+    none, gx1 = nb.nna_cqt2010v2_backward(plan, _dev(x), _dev(gout), want_gw=False)
+    assert none is None and _peak_err(gx1.cpu().numpy(), ref_gx) < TOL
+
+
+def test_cqt2010v2_backward_refuses_wrong_plans_and_workspaces(nb):
+    import torch
+    plan = nb.nna_plan_cqt2010v2(sr=16000, hop=64, fmin=220.0, n_bins=29, fir_taps=63, device=0)
+    x, g = _dev(_rand(2, 5000, 1)), torch.zeros((2, 29, 79), dtype=torch.float32, device="cuda:0")
+    with pytest.raises(nb.NnaError) as ei:   # not made trainable
+        nb.nna_cqt2010v2_backward(plan, x, g)
+    assert ei.value.status == nb.NNA_ERR_INVALID_ARG
+    nb.nna_plan_trainable(plan)
+    with pytest.raises(nb.NnaError) as ei:   # workspace too small
+        nb.nna_cqt2010v2_backward(plan, x, g, workspace=torch.empty(1024, dtype=torch.uint8, device="cuda:0"))
+    assert ei.value.status == nb.NNA_ERR_INVALID_ARG
+    with pytest.raises(nb.NnaError) as ei:   # the one-rate entry point does not take a downsampling plan
+        nb.nna_cqt_backward_workspace(plan, 2, 5000)
+    assert ei.value.status == nb.NNA_ERR_INVALID_ARG
+    with pytest.raises(nb.NnaError) as ei:   # too short for the lowest octave
+        nb.nna_cqt2010v2_backward_workspace(plan, 2, 600)
+    assert ei.value.status == nb.NNA_ERR_SHAPE
+    p2 = nb.nna_plan_cqt2010(sr=16000, hop=64, fmin=220.0, n_bins=29, fir_taps=63, device=0)
+    with pytest.raises(nb.NnaError) as ei:   # frequency-domain kernels: no trainable form
+        nb.nna_plan_trainable(p2)
+    assert ei.value.status == nb.NNA_ERR_INVALID_ARG
+
+
 def test_destroying_plans_returns_their_device_memory(nb):
     # every buffer a plan owns (banks, row-major copies, index maps, tables) goes back when the plan is destroyed:
     # building and dropping the same plans again and again does not eat into the free memory
