@@ -29,7 +29,11 @@ there is already zero for the magnitude-type outputs); ``downsample2_transpose``
 against the SciPy-pinned ``downsample2``, matrix rows on a tiny case); ``cqt2010v2_bank`` /
 ``cqt2010v2_bank_forward`` pinned (equal the downsampling-CQT oracle, all five output formats);
 ``cqt2010v2_bank_backward`` pinned (central differences of that forward for kernel taps of shared and
-partial-octave rows and for waveform samples at the mirrored ends and inside).
+partial-octave rows and for waveform samples at the mirrored ends and inside); ``cqt1992_weights`` /
+``cqt1992_bank_forward`` and ``cqt2010_weights`` / ``cqt2010_bank_forward`` pinned (equal the ``cqt1992`` /
+``cqt2010`` oracles; the DFT bank equals eq. (DFT2) written out in the test); ``cqt1992_bank_backward`` /
+``cqt2010_bank_backward`` pinned (central differences for spectral-kernel entries, DFT-bank taps and waveform
+samples).
 """
 from __future__ import annotations
 
@@ -793,3 +797,172 @@ def _stft_bank_backward64(xa, W, g, hop, fmt):
     """``stft_bank_backward`` for one float64 waveform: g [F, T] ([2F, T] complex) -> (gW, gx)."""
     gW, gx = stft_bank_backward_f64(xa[None], W, g[None], hop=hop, center=True, fmt=fmt)
     return gW, gx[0]
+
+
+# ---------------------------------------------------------------------------------------
+# Trainable kernels of the CQT layers with frequency-domain kernels (Sec. III-C "CQT using neural networks",
+# eq. (CQT1992), Fig. 5, with both stages' kernels as weights, Sec. IV-C): the un-windowed STFT layer's bank W and
+# the spectral kernels Y.
+# ---------------------------------------------------------------------------------------
+def cqt1992_weights(sr=22050, fmin=220.0, n_bins=84, bins_per_octave=12, window=WIN_HANN, n_fft=0):
+    """(W, Ysk): W[2F, n_fft] = eq. (DFT2)'s kernels without a window (row 2k = cos, row 2k+1 = -sin of 2 pi k n /
+    n_fft, F = n_fft/2 + 1), the weight of the layer's STFT stage; Ysk[2 n_bins, F] = the spectral kernels of
+    ``cqt1992_spectral_kernels`` divided by n_fft, row 2q = real part, row 2q+1 = imaginary part -- the weight of
+    its second stage, X_cq[q, t] = sum_k X_t[k] (Ysk[2q, k] + i Ysk[2q+1, k])."""
+    if n_fft <= 0:
+        n_fft = cqt_default_taps(sr, fmin, bins_per_octave)
+    F = n_fft // 2 + 1
+    n = np.arange(n_fft)
+    W = np.empty((2 * F, n_fft), dtype=np.float64)
+    for k in range(F):
+        # (k n) mod n_fft keeps the argument small: the table is exact to the last bit or two for large n_fft
+        ang = 2.0 * np.pi * ((k * n) % n_fft) / float(n_fft)
+        W[2 * k] = np.cos(ang)
+        W[2 * k + 1] = -np.sin(ang)
+    W[1] = 0.0           # sin(0 n) and sin(pi n): identically zero
+    W[2 * F - 1] = 0.0
+    Y = cqt1992_spectral_kernels(sr, fmin, n_bins, bins_per_octave, window=window, n_fft=n_fft) / float(n_fft)
+    Ysk = np.empty((2 * n_bins, F), dtype=np.float64)
+    Ysk[0::2] = Y.real
+    Ysk[1::2] = Y.imag
+    return W, Ysk
+
+
+def _cqt1992_bank_forward64(xa, W, Ysk, hop, center, fmt):
+    """One float64 waveform through both stages: (output [rows, T], X [T, F] complex, V [T, n_bins] complex)."""
+    idx = _frame_index(xa.size, W.shape[1], hop, center)
+    C = xa[idx] @ W.T                                  # [T, 2F]
+    X = C[:, 0::2] + 1j * C[:, 1::2]
+    Y = Ysk[0::2] + 1j * Ysk[1::2]
+    V = X @ Y.T                                        # [T, n_bins]
+    out = apply_complex_format(V.real.T[None], V.imag.T[None], fmt)[0]
+    return out, X, V
+
+
+def cqt1992_bank_forward(x, W, Ysk, hop=512, center=True, fmt=MAGNITUDE):
+    """The CQT layer with frequency-domain kernels for given weights: the STFT layer ``stft_bank`` (complex output)
+    with bank W, then every time step multiplied with the spectral kernels, then the output format.
+    out: [B, n_bins, T] ([B, 2 n_bins, T] complex)."""
+    x = _x(x).astype(np.float64)
+    return np.stack([_cqt1992_bank_forward64(xb, np.asarray(W, dtype=np.float64), np.asarray(Ysk, dtype=np.float64),
+                                             hop, center, fmt)[0] for xb in x])
+
+
+def _complex_format_gradient(V, g, fmt):
+    """dLoss/dRe V, dLoss/dIm V (each [T, n_bins]) from g = dLoss/dout for one waveform ([n_bins, T], or [2 n_bins, T]
+    for the complex format): the output formats' derivatives as in ``stft_bank_backward``."""
+    re, im = V.real, V.imag
+    pw = re ** 2 + im ** 2
+    g = g.T
+    if fmt == COMPLEX:
+        return g[:, 0::2], g[:, 1::2]
+    if fmt == PHASE:
+        s = np.where(pw > 0, g / np.where(pw > 0, pw, 1.0), 0.0)
+        return -s * im, s * re
+    if fmt == MAGNITUDE:
+        s = np.where(pw > 0, g / np.sqrt(np.where(pw > 0, pw, 1.0)), 0.0)
+    elif fmt == POWER:
+        s = 2.0 * g
+    elif fmt == LOG:
+        s = np.where(pw > LOG_FLOOR, 2.0 * g / np.where(pw > LOG_FLOOR, pw, 1.0), 0.0)
+    else:
+        raise OracleError("unknown output format")
+    return s * re, s * im
+
+
+def _cqt1992_bank_backward64(xa, W, Ysk, g, hop, center, fmt):
+    """One float64 waveform: (gYsk, gW, gx) given g = dLoss/dout of that waveform."""
+    _, X, V = _cqt1992_bank_forward64(xa, W, Ysk, hop, center, fmt)
+    gVr, gVi = _complex_format_gradient(V, g, fmt)
+    Yr, Yi = Ysk[0::2], Ysk[1::2]
+    # V_re = sum_k (Yr X_re - Yi X_im),  V_im = sum_k (Yr X_im + Yi X_re)
+    gYsk = np.empty_like(Ysk)
+    gYsk[0::2] = gVr.T @ X.real + gVi.T @ X.imag
+    gYsk[1::2] = -gVr.T @ X.imag + gVi.T @ X.real
+    gXr = gVr @ Yr + gVi @ Yi                          # [T, F]
+    gXi = -gVr @ Yi + gVi @ Yr
+    gC = np.empty((2 * Yr.shape[1], gXr.shape[0]), dtype=np.float64)
+    gC[0::2] = gXr.T
+    gC[1::2] = gXi.T
+    gW, gx = stft_bank_backward_f64(xa[None], W, gC[None], hop=hop, center=center, fmt=COMPLEX)
+    return gYsk, gW, gx[0]
+
+
+def cqt1992_bank_backward(x, W, Ysk, gout, hop=512, center=True, fmt=MAGNITUDE):
+    """Gradients of a scalar loss through ``cqt1992_bank_forward`` given gout = dLoss/dout:
+    (gYsk [2 n_bins, F], gW [2F, n_fft], gx [B, L]).  Chain rule through the output format, the complex product
+    with the spectral kernels and the STFT layer (``stft_bank_backward``); the two identically zero sine rows of
+    the DFT bank are not parameters (``dft_bank_parameter_mask``)."""
+    x = _x(x).astype(np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    Ysk = np.asarray(Ysk, dtype=np.float64)
+    gout = np.asarray(gout, dtype=np.float64)
+    gY, gW, gx = np.zeros_like(Ysk), np.zeros_like(W), np.zeros_like(x)
+    for b in range(x.shape[0]):
+        a, w, gx[b] = _cqt1992_bank_backward64(x[b], W, Ysk, gout[b], hop, center, fmt)
+        gY += a
+        gW += w
+    return gY, np.where(dft_bank_parameter_mask(W.shape[1]), gW, 0.0), gx
+
+
+def cqt2010_weights(sr=22050, fmin=32.70, n_bins=84, bins_per_octave=12, window=WIN_HANN, n_fft=0):
+    """The weights of the downsampling CQT layer with frequency-domain kernels: ``cqt1992_weights`` for the top
+    octave's bins, shared by every octave (a partial lowest octave uses the rows of the upper bins)."""
+    b = bins_per_octave
+    n_top = min(b, n_bins)
+    if n_fft <= 0:
+        n_fft = cqt2010_default_taps(sr, fmin, n_bins, b)
+    return cqt1992_weights(sr, fmin * 2.0 ** (float(n_bins - n_top) / float(b)), n_top, b, window, n_fft)
+
+
+def cqt2010_bank_forward(x, W, Ysk, hop=512, n_bins=84, bins_per_octave=12, fir_taps=FIR_TAPS, fmt=MAGNITUDE):
+    """``cqt2010`` as a layer with the given weights: per octave ``cqt1992_bank_forward`` (hop / 2^a, always
+    centred) on the waveform downsampled a times.  Float64 throughout."""
+    x = np.atleast_2d(np.asarray(x, dtype=np.float64))
+    W = np.asarray(W, dtype=np.float64)
+    Ysk = np.asarray(Ysk, dtype=np.float64)
+    B, L = x.shape
+    T = 1 + L // hop
+    h = lowpass_fir(fir_taps, 0.5)
+    rpb = 2 if fmt == COMPLEX else 1
+    out = np.empty((B, rpb * n_bins, T), dtype=np.float64)
+    for bi in range(B):
+        xa = x[bi]
+        for a, lo, hi, r0 in _cqt2010v2_octaves(n_bins, bins_per_octave):
+            o = _cqt1992_bank_forward64(xa, W, Ysk[r0:r0 + 2 * (hi - lo)], hop >> a, True, fmt)[0]
+            out[bi, rpb * lo:rpb * hi, :] = o[:, :T]
+            if lo > 0:
+                xa = downsample2(xa, h)
+    return out
+
+
+def cqt2010_bank_backward(x, W, Ysk, gout, hop=512, n_bins=84, bins_per_octave=12, fir_taps=FIR_TAPS, fmt=MAGNITUDE):
+    """(gYsk, gW, gx) through ``cqt2010_bank_forward``: per octave ``cqt1992_bank_backward``'s chain, summed over
+    the octaves for the shared weights; the waveform gradient climbs through ``downsample2_transpose``."""
+    x = np.atleast_2d(np.asarray(x, dtype=np.float64))
+    W = np.asarray(W, dtype=np.float64)
+    Ysk = np.asarray(Ysk, dtype=np.float64)
+    gout = np.asarray(gout, dtype=np.float64)
+    B, L = x.shape
+    T = 1 + L // hop
+    h = lowpass_fir(fir_taps, 0.5)
+    rpb = 2 if fmt == COMPLEX else 1
+    octs = _cqt2010v2_octaves(n_bins, bins_per_octave)
+    gY, gW, gx = np.zeros_like(Ysk), np.zeros_like(W), np.zeros_like(x)
+    for bi in range(B):
+        xs = [x[bi]]
+        for _ in octs[1:]:
+            xs.append(downsample2(xs[-1], h))
+        g_below = None
+        for a, lo, hi, r0 in reversed(octs):
+            Ta = num_frames(xs[a].size, W.shape[1], hop >> a, True)
+            ga = np.zeros((rpb * (hi - lo), Ta), dtype=np.float64)
+            ga[:, :T] = gout[bi, rpb * lo:rpb * hi, :]
+            gYa, gWa, gxa = _cqt1992_bank_backward64(xs[a], W, Ysk[r0:r0 + 2 * (hi - lo)], ga, hop >> a, True, fmt)
+            gY[r0:r0 + 2 * (hi - lo)] += gYa
+            gW += gWa
+            if g_below is not None:
+                gxa = gxa + downsample2_transpose(g_below, h, xs[a].size)
+            g_below = gxa
+        gx[bi] = g_below
+    return gY, np.where(dft_bank_parameter_mask(W.shape[1]), gW, 0.0), gx

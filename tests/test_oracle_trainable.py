@@ -370,3 +370,83 @@ def test_downsampling_cqt_waveform_gradient_needs_every_octave():
     top_only = oracle.stft_bank_backward_f64(x, W, gout[:, 17:], hop=32)[1]
     np.testing.assert_allclose(gx_top, top_only, atol=1e-12)
     assert np.abs(gx - gx_top).max() > 0.05 * np.abs(gx).max()
+
+
+# ---- the CQT layers with frequency-domain kernels: DFT bank and spectral kernels as weights -----------------
+CQ92 = dict(sr=4000, fmin=220.0, n_bins=14, bins_per_octave=6)     # n_fft 256
+
+
+@pytest.mark.parametrize("fmt", [oracle.MAGNITUDE, oracle.POWER, oracle.LOG, oracle.COMPLEX, oracle.PHASE])
+def test_forward_with_the_dft_bank_and_spectral_kernels_is_the_cqt1992_oracle(fmt):
+    x = signals.batch(3, B=2, L=1500)
+    W, Ysk = oracle.cqt1992_weights(**CQ92)
+    N = oracle.cqt_default_taps(4000, 220.0, 6)
+    assert W.shape == (N + 2, N) and Ysk.shape == (28, N // 2 + 1)
+    np.testing.assert_allclose(W, _dft_bank(N, window=False), atol=1e-12)
+    got = oracle.cqt1992_bank_forward(x, W, Ysk, hop=32, fmt=fmt)
+    ref = oracle.cqt1992(x, hop=32, fmt=fmt, **CQ92)
+    if fmt == oracle.PHASE:
+        c = oracle.cqt1992(x, hop=32, fmt=oracle.COMPLEX, **CQ92)
+        strong = np.hypot(c[:, 0::2], c[:, 1::2]) > 1e-6 * np.abs(c).max()
+        assert np.abs(np.angle(np.exp(1j * (got - ref))))[strong].max() < 1e-6
+    elif fmt == oracle.LOG:
+        np.testing.assert_allclose(np.exp(got), np.exp(ref), rtol=1e-8, atol=1e-12 * np.exp(ref).max())
+    else:
+        np.testing.assert_allclose(got, ref, atol=1e-11 * np.abs(ref).max())
+
+
+def _fd_check(loss, A, gA, picks, tol=1e-5):
+    for idx in picks:
+        h = 1e-6
+        Ap, Am = A.copy(), A.copy()
+        Ap[idx] += h
+        Am[idx] -= h
+        fd = (loss(Ap) - loss(Am)) / (2 * h)
+        assert abs(fd - gA[idx]) <= tol * max(1.0, np.abs(gA).max()), (idx, fd, gA[idx])
+
+
+@pytest.mark.parametrize("fmt", [oracle.MAGNITUDE, oracle.LOG, oracle.COMPLEX, oracle.PHASE])
+def test_cqt1992_layer_gradients_against_central_differences(fmt):
+    rng = np.random.default_rng(20 + fmt)
+    x = signals.batch(3, B=2, L=900).astype(np.float32)
+    W, Ysk = oracle.cqt1992_weights(**CQ92)
+    mask = oracle.dft_bank_parameter_mask(W.shape[1])
+    W = W + 1e-3 * rng.standard_normal(W.shape) * mask
+    Ysk = Ysk + 1e-4 * rng.standard_normal(Ysk.shape)
+    out = oracle.cqt1992_bank_forward(x, W, Ysk, hop=32, fmt=fmt)
+    gout = rng.standard_normal(out.shape)
+    gY, gW, gx = oracle.cqt1992_bank_backward(x, W, Ysk, gout, hop=32, fmt=fmt)
+    assert gY.shape == Ysk.shape and gW.shape == W.shape and gx.shape == x.shape and not gW[~mask].any()
+    x64 = x.astype(np.float64)
+    fwd = lambda Wv, Yv, xv: float(sum((oracle._cqt1992_bank_forward64(xv[b], Wv, Yv, 32, True, fmt)[0] * gout[b]).sum()
+                                       for b in range(2)))
+    F = Ysk.shape[1]
+    # spectral kernels: real and imaginary rows, the purely real STFT bins 0 and n_fft/2 included
+    _fd_check(lambda Yv: fwd(W, Yv, x64), Ysk, gY, [(0, 0), (1, 0), (6, F - 1), (7, F - 1), (4, 17), (5, 17), (26, 40), (27, 99)])
+    _fd_check(lambda Wv: fwd(Wv, Ysk, x64), W, gW, [(0, 3), (2, 100), (3, 100), (2 * F - 2, 7), (40, 255), (41, 0)])
+    _fd_check(lambda xv: fwd(W, Ysk, xv), x64, gx, [(0, 0), (0, 1), (1, 899), (1, 898), (0, 450), (1, 77)])
+
+
+def test_cqt2010_layer_forward_and_gradients():
+    rng = np.random.default_rng(31)
+    geo = dict(n_bins=14, bins_per_octave=6)
+    x = signals.batch(3, B=2, L=1200).astype(np.float32)
+    W, Ysk = oracle.cqt2010_weights(sr=4000, fmin=110.0, **geo)    # three octaves, the lowest partial (2 bins); n_fft 64
+    kw = dict(hop=16, fir_taps=31, **geo)
+    ref = oracle.cqt2010(x, sr=4000, fmin=110.0, hop=16, fir_taps=31, **geo)
+    got = oracle.cqt2010_bank_forward(x, W, Ysk, **kw)
+    np.testing.assert_allclose(got, ref, atol=1e-10 * ref.max())
+    mask = oracle.dft_bank_parameter_mask(W.shape[1])
+    W = W + 1e-3 * rng.standard_normal(W.shape) * mask
+    Ysk = Ysk + 1e-4 * rng.standard_normal(Ysk.shape)
+    for fmt in (oracle.MAGNITUDE, oracle.COMPLEX):
+        out = oracle.cqt2010_bank_forward(x, W, Ysk, fmt=fmt, **kw)
+        gout = rng.standard_normal(out.shape)
+        gY, gW, gx = oracle.cqt2010_bank_backward(x, W, Ysk, gout, fmt=fmt, **kw)
+        x64 = x.astype(np.float64)
+        fwd = lambda Wv, Yv, xv: float((oracle.cqt2010_bank_forward(xv, Wv, Yv, fmt=fmt, **kw) * gout).sum())
+        F = Ysk.shape[1]
+        # rows 0..7 (bins 0..3 of the top octave's six) serve the two full octaves, rows 8..11 all three
+        _fd_check(lambda Yv: fwd(W, Yv, x64), Ysk, gY, [(0, 0), (1, F - 1), (3, 9), (8, 5), (9, 20), (11, F - 1)])
+        _fd_check(lambda Wv: fwd(Wv, Ysk, x64), W, gW, [(0, 3), (2, 10), (3, 63), (2 * F - 2, 7)])
+        _fd_check(lambda xv: fwd(W, Ysk, xv), x64, gx, [(0, 0), (0, 1), (1, 1199), (0, 600), (1, 77)])
