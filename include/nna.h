@@ -379,6 +379,47 @@ nna_status nna_cqt2010v2_backward(const nna_plan* plan, const float* x_dev, long
                                   size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Trainable kernels of the CQT layers with frequency-domain kernels (Sec. IV-C applied to Sec. III-C "CQT using neural
+ * networks", eq. (CQT1992), and its downsampling form): nna_plan_trainable also accepts plans from nna_plan_cqt1992
+ * and nna_plan_cqt2010 and makes both stages trainable.
+ *   STFT stage: nna_plan_get_bank / nna_plan_set_bank with W[2F, n_fft], F = n_fft/2 + 1 (the un-windowed kernels of
+ *     eq. (DFT2); rows 1 and 2F-1 are structural zeros as for nna_plan_stft).  A downsampling plan has one such bank,
+ *     shared by its octaves.
+ *   Spectral kernels: Ysk[2 n_bins, F], float32 row-major on the device, row 2q = Re, row 2q+1 = Im of Y[q, .]/n_fft
+ *     (the layout of nna_plan_spectral_kernels): X_cq[q, t] = sum_k X_t[k] (Ysk[2q, k] + i Ysk[2q+1, k]).  For a
+ *     plan from nna_plan_cqt2010: the top octave's kernels, n_bins -> n_top = min(bins_per_octave, n_bins), shared by
+ *     the octaves as in nna_cqt2010v2_backward.  A trained matrix is dense: no block of the second contraction
+ *     is skipped any more.
+ *     nna_plan_get_spectral_kernels   y_dev[2 n_bins, F] = the current kernels.
+ *     nna_plan_set_spectral_kernels   the kernels = y_dev (enqueued on hip_stream; the plan is modified).
+ *   nna_cqt1992_backward / nna_cqt2010_backward   given gout_dev = dLoss/d(output of nna_cqt1992 / nna_cqt2010 for
+ *     x_dev) ([B, n_bins, T], or [B, 2 n_bins, T] for NNA_OUT_COMPLEX), write any of
+ *       gy_dev[2 n_bins, F]:  gV = gout times the output format's derivative at V = X_cq (as in nna_stft_backward);
+ *                             dLoss/dRe Y[q,k] = sum (gVr Xr + gVi Xi), dLoss/dIm Y[q,k] = sum (gVi Xr - gVr Xi)
+ *                             over waveforms and frames (X = Xr + i Xi the STFT stage's output);
+ *       gw_dev[2F, n_fft] and gx_dev[B, L]: the gradient reaching the spectrum, gX = sum_q conj-transposed product
+ *                             (gXr = gVr Yr + gVi Yi, gXi = gVi Yr - gVr Yi), carried through the STFT stage as
+ *                             nna_stft_backward does for the complex output format;
+ *     NULL pointers are skipped (at least one must be given).  The downsampling form sums gy and gw over the octaves
+ *     and carries gx up through the transposed decimation steps.  workspace_dev: 256-byte aligned,
+ *     nna_cqt1992_backward_workspace / nna_cqt2010_backward_workspace bytes (the spectrum [B, 2F, T] twice, the
+ *     constant-Q values, the STFT stage's G; for nna_cqt2010 the octaves' waveforms and two waveform gradients).
+ *     Outputs are overwritten; atomics, launches on hip_stream and errors as in nna_stft_backward.  The second
+ *     stage's contractions run as plain tiled MFMA products bound by the [B, 2F, T] arrays they stream: correct,
+ *     not tuned.
+ */
+nna_status nna_plan_get_spectral_kernels(const nna_plan* plan, float* y_dev, void* hip_stream);
+nna_status nna_plan_set_spectral_kernels(nna_plan* plan, const float* y_dev, void* hip_stream);
+nna_status nna_cqt1992_backward_workspace(const nna_plan* plan, long long B, long long L, size_t* bytes);
+nna_status nna_cqt1992_backward(const nna_plan* plan, const float* x_dev, long long B, long long L, const float* gout_dev,
+                                float* gy_dev, float* gw_dev, float* gx_dev, void* workspace_dev, size_t workspace_bytes,
+                                void* hip_stream);
+nna_status nna_cqt2010_backward_workspace(const nna_plan* plan, long long B, long long L, size_t* bytes);
+nna_status nna_cqt2010_backward(const nna_plan* plan, const float* x_dev, long long B, long long L, const float* gout_dev,
+                                float* gy_dev, float* gw_dev, float* gx_dev, void* workspace_dev, size_t workspace_bytes,
+                                void* hip_stream);
+
+/*
  * Trainable Mel layer (Sec. IV-C; the trainable_mel / trainable_STFT arguments of the paper's
  * MelSpectrogram layer, Sec. III-B): both stages of a plan from nna_plan_mel as parameters.
  * nna_plan_trainable also accepts Mel plans; nna_plan_get_bank / nna_plan_set_bank then address the
@@ -433,7 +474,7 @@ nna_status nna_plan_spectral_kernels(const nna_plan* plan, double* host_out, siz
 
 /*
  * Plan facts, each written if its pointer is non-NULL: kind, logical bank rows (nna_plan_cqt2010v2: of the top
- * octave's kernels, which every octave uses; nna_plan_cqt2010: 0, its parts hold the banks), taps K,
+ * octave's kernels, which every octave uses; nna_plan_cqt2010: of the DFT bank its octaves share), taps K,
  * output bins, flops the kernels execute per frame (multiply-add = 2, zero-padded
  * taps they do not skip included) and algorithmic flops per frame (non-zero taps only:
  * 2*K*rows_nonzero for the DFT bank, 4*sum_k N_k for the CQT, plus 2*nnz(W) for Mel;

@@ -33,6 +33,8 @@ EXPORTS = [
     "nna_plan_trainable", "nna_plan_get_bank", "nna_plan_set_bank", "nna_stft_backward_workspace", "nna_stft_backward",
     "nna_cqt_backward_workspace", "nna_cqt_backward", "nna_mel_with_stft", "nna_cqt2010v2_static",
     "nna_cqt2010v2_backward_workspace", "nna_cqt2010v2_backward",
+    "nna_plan_get_spectral_kernels", "nna_plan_set_spectral_kernels", "nna_cqt1992_backward_workspace", "nna_cqt1992_backward",
+    "nna_cqt2010_backward_workspace", "nna_cqt2010_backward",
     "nna_plan_destroy",
     "nna_status_str", "nna_last_error",
 ]
@@ -100,6 +102,11 @@ def lib():
         L.nna_cqt_backward.argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _VP, _VP, _c.c_size_t, _VP]
         L.nna_cqt2010v2_backward_workspace.argtypes = [_VP, _LL, _LL, _c.POINTER(_c.c_size_t)]
         L.nna_cqt2010v2_backward.argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _VP, _VP, _c.c_size_t, _VP]
+        L.nna_plan_get_spectral_kernels.argtypes = [_VP, _VP, _VP]
+        L.nna_plan_set_spectral_kernels.argtypes = [_VP, _VP, _VP]
+        for name in ("nna_cqt1992", "nna_cqt2010"):
+            getattr(L, name + "_backward_workspace").argtypes = [_VP, _LL, _LL, _c.POINTER(_c.c_size_t)]
+            getattr(L, name + "_backward").argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _VP, _VP, _VP, _c.c_size_t, _VP]
         L.nna_mel_with_stft.argtypes = [_VP, _VP, _LL, _LL, _VP, _VP, _VP]
         L.nna_out_shape.argtypes = [_VP, _LL, _LL, _c.POINTER(_LL), _c.POINTER(_LL)]
         for name in ("nna_stft", "nna_mel", "nna_cqt", "nna_cqt1992", "nna_cqt2010v2_static"):
@@ -200,22 +207,27 @@ def nna_plan_cqt2010v2(sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave
 
 def nna_plan_cqt1992(sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, win=NNA_WIN_HANN, center=True,
                      n_fft=0, fmt=NNA_OUT_MAGNITUDE, device=0) -> Plan:
-    return _new_plan(lib().nna_plan_cqt1992,
+    plan = _new_plan(lib().nna_plan_cqt1992,
                      (sr, hop, float(fmin), n_bins, bins_per_octave, win, int(center), n_fft, fmt), device)
+    plan.spectral_rows = 2 * n_bins  # rows of the spectral kernels as a tensor: (Re, Im) per constant-Q bin
+    return plan
 
 
 def nna_plan_spectral_kernels(plan: Plan) -> np.ndarray:
     """Complex [n_bins, n_fft/2+1]: the spectral kernels of a plan from nna_plan_cqt1992, divided by n_fft."""
     i = plan.info()
-    out = np.empty((2 * i["out_bins"], i["taps"] // 2 + 1), dtype=np.float64)
+    # (a complex-format plan reports two output rows per bin; the constructor wrapper recorded the real count)
+    out = np.empty((getattr(plan, "spectral_rows", 2 * i["out_bins"]), i["taps"] // 2 + 1), dtype=np.float64)
     _check(lib().nna_plan_spectral_kernels(plan.handle, out.ctypes.data_as(_c.POINTER(_c.c_double)), out.size))
     return out[0::2] + 1j * out[1::2]
 
 
 def nna_plan_cqt2010(sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, win=NNA_WIN_HANN, n_fft=0,
                      fir_taps=0, fmt=NNA_OUT_MAGNITUDE, device=0) -> Plan:
-    return _new_plan(lib().nna_plan_cqt2010,
+    plan = _new_plan(lib().nna_plan_cqt2010,
                      (sr, hop, float(fmin), n_bins, bins_per_octave, win, n_fft, fir_taps, fmt), device)
+    plan.spectral_rows = 2 * min(n_bins, bins_per_octave)  # the top octave's kernels serve every octave
+    return plan
 
 
 def nna_plan_part(plan: Plan, index: int) -> Plan:
@@ -496,6 +508,82 @@ def nna_cqt2010v2_backward(plan: Plan, x, gout, want_gw=True, want_gx=True, work
                                         gw.data_ptr() if want_gw else None, gx.data_ptr() if want_gx else None,
                                         workspace.data_ptr(), ws_bytes, _stream_of(x, stream)))
     return gw, gx
+
+
+def _spectral_shapes(plan: Plan):
+    """(shape of the spectral kernels Ysk, shape of the STFT stage's bank) of a plan with frequency-domain kernels"""
+    i = (nna_plan_part(plan, 0) if plan.info()["kind"] == NNA_KIND_CQT2010 else plan).info()
+    return (plan.spectral_rows, i["bank_rows"] // 2), (i["bank_rows"], i["taps"])
+
+
+def nna_plan_get_spectral_kernels(plan: Plan, out=None, stream=None):
+    """Ysk[2 n_bins, F]: the spectral kernels of a trainable plan from nna_plan_cqt1992 / nna_plan_cqt2010."""
+    import torch
+
+    shape = _spectral_shapes(plan)[0]
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float32, device=f"cuda:{plan.device}")
+    elif not (out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and tuple(out.shape) == shape):
+        raise TypeError(f"out must be a contiguous float32 CUDA tensor of shape {shape}")
+    _check(lib().nna_plan_get_spectral_kernels(plan.handle, out.data_ptr(), _stream_of(out, stream)))
+    return out
+
+
+def nna_plan_set_spectral_kernels(plan: Plan, Y, stream=None):
+    shape = _spectral_shapes(plan)[0]
+    if not (Y.is_cuda and Y.dtype.is_floating_point and Y.element_size() == 4 and Y.is_contiguous()
+            and tuple(Y.shape) == shape and Y.device.index == plan.device):
+        raise TypeError(f"Y must be a contiguous float32 CUDA tensor of shape {shape} on the plan's device")
+    _check(lib().nna_plan_set_spectral_kernels(plan.handle, Y.data_ptr(), _stream_of(Y, stream)))
+
+
+def _spectral_backward(name, plan, x, gout, want_gy, want_gw, want_gx, workspace, stream):
+    import torch
+
+    if not (isinstance(x, torch.Tensor) and x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.dim() == 2):
+        raise TypeError("x must be a contiguous float32 CUDA tensor [B, L]")
+    B, L = x.shape
+    bins, frames = nna_out_shape(plan, B, L)
+    if not (gout.is_cuda and gout.dtype == torch.float32 and gout.is_contiguous()
+            and tuple(gout.shape) == (B, bins, frames) and gout.device == x.device):
+        raise TypeError(f"gout must be a contiguous float32 CUDA tensor of shape {(B, bins, frames)}")
+    n = _c.c_size_t()
+    _check(getattr(lib(), name + "_backward_workspace")(plan.handle, B, L, _c.byref(n)))
+    if workspace is None:
+        workspace = torch.empty(n.value, dtype=torch.uint8, device=x.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    y_shape, w_shape = _spectral_shapes(plan)
+    gy = torch.empty(y_shape, dtype=torch.float32, device=x.device) if want_gy else None
+    gw = torch.empty(w_shape, dtype=torch.float32, device=x.device) if want_gw else None
+    gx = torch.empty_like(x) if want_gx else None
+    _check(getattr(lib(), name + "_backward")(plan.handle, x.data_ptr(), B, L, gout.data_ptr(),
+                                              gy.data_ptr() if want_gy else None, gw.data_ptr() if want_gw else None,
+                                              gx.data_ptr() if want_gx else None, workspace.data_ptr(), ws_bytes,
+                                              _stream_of(x, stream)))
+    return gy, gw, gx
+
+
+def nna_cqt1992_backward_workspace(plan: Plan, B: int, L: int) -> int:
+    n = _c.c_size_t()
+    _check(lib().nna_cqt1992_backward_workspace(plan.handle, B, L, _c.byref(n)))
+    return n.value
+
+
+def nna_cqt2010_backward_workspace(plan: Plan, B: int, L: int) -> int:
+    n = _c.c_size_t()
+    _check(lib().nna_cqt2010_backward_workspace(plan.handle, B, L, _c.byref(n)))
+    return n.value
+
+
+def nna_cqt1992_backward(plan: Plan, x, gout, want_gy=True, want_gw=True, want_gx=True, workspace=None, stream=None):
+    """(gYsk[2 n_bins, F], gW[2F, n_fft], gx[B, L]; None where not wanted) = gradients of a loss through
+    nna_cqt1992(plan, x), given gout = dLoss/dout."""
+    return _spectral_backward("nna_cqt1992", plan, x, gout, want_gy, want_gw, want_gx, workspace, stream)
+
+
+def nna_cqt2010_backward(plan: Plan, x, gout, want_gy=True, want_gw=True, want_gx=True, workspace=None, stream=None):
+    """As nna_cqt1992_backward, through nna_cqt2010(plan, x): the top octave's kernels are the weights of every octave."""
+    return _spectral_backward("nna_cqt2010", plan, x, gout, want_gy, want_gw, want_gx, workspace, stream)
 
 
 def _mel_shape(plan: Plan):

@@ -9,8 +9,7 @@ extern "C" {
 // ---- trainable Fourier kernels (Sec. IV-C) ----------------------------------------------------
 static nna_status check_trainable_kind(const nna_plan* plan) {
   if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
-  if (plan->kind != NNA_KIND_STFT && plan->kind != NNA_KIND_MEL && plan->kind != NNA_KIND_CQT && plan->kind != NNA_KIND_CQT2010V2)
-    return fail(NNA_ERR_INVALID_ARG, "only plans from nna_plan_stft, nna_plan_stft_scaled, nna_plan_mel, nna_plan_cqt and nna_plan_cqt2010v2 have trainable kernels");
+  if (plan->kind < NNA_KIND_STFT || plan->kind > NNA_KIND_CQT2010) return fail(NNA_ERR_INVALID_ARG, "unknown kind of plan");
   if (plan->precision != NNA_PREC_F32) return fail(NNA_ERR_UNSUPPORTED, "trainable kernels need a float32 plan");
   if (plan->device < 0) return fail(NNA_ERR_UNSUPPORTED, "host-only plan (device = -1)");
   return NNA_OK;
@@ -167,10 +166,69 @@ static nna_status make_cqt_trainable(nna_plan* plan) {
 }
 
 static bool is_trainable(const nna_plan* plan) {
-  if (plan->kind != NNA_KIND_CQT2010V2) return plan->d_wrm != nullptr;
+  if (plan->kind == NNA_KIND_CQT1992) return plan->d_wrm != nullptr && plan->d_ysk != nullptr;
+  if (plan->kind != NNA_KIND_CQT2010V2 && plan->kind != NNA_KIND_CQT2010) return plan->d_wrm != nullptr;
   for (const nna_plan* sub : plan->octave)
-    if (!sub->d_wrm) return false;
+    if (!is_trainable(sub)) return false;
   return true;
+}
+
+static nna::LinLogicalParams lin_logical_params(const nna_plan* plan, const float* ysk) {
+  nna::LinLogicalParams q;
+  q.ysk = ysk;
+  q.frag = plan->d_melw;
+  q.ylin = plan->d_ylin;
+  q.ylinT = plan->d_ylinT;
+  q.n_frag = (long long)plan->lin_frag_floats;
+  q.n_bins = plan->n_bins;
+  q.n_half = plan->n_half;
+  q.n_rt = plan->n_rt;
+  q.lin_blocks = plan->lin_blocks;
+  q.mp = plan->lin_mp;
+  q.rp = plan->lin_rp;
+  return q;
+}
+
+// The second stage of a plan with frequency-domain kernels becomes trainable (device current, the STFT stage
+// already is): the spectral kernels as a tensor of their own, the two row-major forms of the matrix they make,
+// and -- a trained matrix is dense -- every block of the forward kernel's second contraction switched on.
+static nna_status make_spectral_trainable(nna_plan* plan) {
+  const int F = plan->n_half + 1, C = 2 * plan->n_half;
+  plan->lin_mp = (2 * plan->n_bins + nna::BW_MT - 1) / nna::BW_MT * nna::BW_MT;
+  plan->lin_rp = (2 * F + nna::BW_MT - 1) / nna::BW_MT * nna::BW_MT;
+  std::vector<float> ysk;
+  std::vector<unsigned char> mask;
+  try {
+    ysk.assign((size_t)2 * plan->n_bins * F, 0.0f);
+    for (int q = 0; q < plan->n_bins; ++q)
+      for (int s = 0; s < F; ++s) {
+        const size_t col = s == 0 ? 0 : s == F - 1 ? 1 : 2 * (size_t)s;  // the packed column of bin s's real part
+        ysk[(size_t)(2 * q) * F + s] = plan->h_linW[(size_t)(2 * q) * C + col];
+        ysk[(size_t)(2 * q + 1) * F + s] = plan->h_linW[(size_t)(2 * q + 1) * C + col];
+      }
+    mask.assign((size_t)plan->n_pass * plan->n_rt * ST_RB, (unsigned char)((1u << plan->lin_blocks) - 1));
+  } catch (const std::bad_alloc&) {
+    return fail(NNA_ERR_ALLOC, "out of host memory");
+  }
+  const size_t lin_bytes = (size_t)plan->lin_mp * plan->lin_rp * sizeof(float);
+  nna_status s = upload(&plan->d_ysk, ysk.data(), ysk.size() * sizeof(float), "spectral kernels");
+  if (s == NNA_OK) s = upload(&plan->d_ylin, nullptr, lin_bytes, "spectral kernel matrix");
+  if (s == NNA_OK) s = upload(&plan->d_ylinT, nullptr, lin_bytes, "spectral kernel matrix");
+  if (s == NNA_OK) {
+    hipError_t e = hipMemset(plan->d_ylin, 0, lin_bytes);
+    if (e == hipSuccess) e = hipMemset(plan->d_ylinT, 0, lin_bytes);
+    if (e == hipSuccess) e = hipMemcpy(plan->d_mel_mask, mask.data(), mask.size(), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = nna::launch_lin_from_logical(lin_logical_params(plan, plan->d_ysk), nullptr);
+    if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+    if (e != hipSuccess) s = fail_hip(e, "spectral kernel matrix");
+  }
+  if (s != NNA_OK) {
+    (void)hipFree(plan->d_ysk);
+    (void)hipFree(plan->d_ylin);
+    (void)hipFree(plan->d_ylinT);
+    plan->d_ysk = plan->d_ylin = plan->d_ylinT = nullptr;
+  }
+  return s;
 }
 
 nna_status nna_plan_trainable(nna_plan* plan) {
@@ -185,6 +243,11 @@ nna_status nna_plan_trainable(nna_plan* plan) {
     // every octave convolves with (rows of) the one weight: each keeps its own streaming-order copy
     for (nna_plan* sub : plan->octave)
       if (!sub->d_wrm && (s = make_cqt_trainable(sub)) != NNA_OK) return s;
+    return NNA_OK;
+  }
+  if (plan->kind == NNA_KIND_CQT2010) {
+    for (nna_plan* sub : plan->octave)
+      if ((s = nna_plan_trainable(sub)) != NNA_OK) return s;
     return NNA_OK;
   }
   plan->rows_pad = plan->n_rt * ST_ROWS;
@@ -231,6 +294,11 @@ nna_status nna_plan_trainable(nna_plan* plan) {
     plan->exec_flops = plan->n_pass * (2.0 * k_exec * ST_ROWS * plan->n_rt + (double)plan->n_rt * ST_RB * ST_MEL_BLOCKS * 2.0 * 32 * 16);
     plan->alg_flops = 2.0 * (double)plan->K * (double)plan->K + 2.0 * (double)plan->n_mels * F;
   }
+  if (plan->kind == NNA_KIND_CQT1992 && (s = make_spectral_trainable(plan)) != NNA_OK) {
+    (void)hipFree(plan->d_wrm);
+    plan->d_wrm = nullptr;
+    return s;
+  }
   return NNA_OK;
 }
 
@@ -258,6 +326,8 @@ nna_status nna_plan_get_bank(const nna_plan* plan, float* w_dev, void* hip_strea
     e = nna::launch_cqt_bank_to_logical(cqt_bank_params(plan, w_dev), reinterpret_cast<hipStream_t>(hip_stream));
   else if (plan->kind == NNA_KIND_CQT2010V2)
     e = nna::launch_cqt_bank_to_logical(cqt_bank_params(plan->octave[0], w_dev), reinterpret_cast<hipStream_t>(hip_stream));
+  else if (plan->kind == NNA_KIND_CQT2010)
+    e = nna::launch_bank_to_logical(permute_params(plan->octave[0], w_dev), reinterpret_cast<hipStream_t>(hip_stream));
   else
     e = nna::launch_bank_to_logical(permute_params(plan, w_dev), reinterpret_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fail_hip(e, "kernel launch");
@@ -277,6 +347,11 @@ nna_status nna_plan_set_bank(nna_plan* plan, const float* w_dev, void* hip_strea
     for (const nna_plan* sub : plan->octave) {
       float* rows = const_cast<float*>(w_dev) + octave_weight_row(plan, sub) * sub->K;
       e = nna::launch_cqt_bank_from_logical(cqt_bank_params(sub, rows), reinterpret_cast<hipStream_t>(hip_stream));
+      if (e != hipSuccess) break;
+    }
+  } else if (plan->kind == NNA_KIND_CQT2010) {
+    for (const nna_plan* sub : plan->octave) {  // the octaves share the DFT kernels; each holds them in its own hop's order
+      e = nna::launch_bank_from_logical(permute_params(sub, const_cast<float*>(w_dev)), reinterpret_cast<hipStream_t>(hip_stream));
       if (e != hipSuccess) break;
     }
   } else
@@ -304,7 +379,7 @@ nna_status nna_stft_backward_workspace(const nna_plan* plan, long long B, long l
 // With gw_dev and gx_dev both NULL only G (and pout) are produced.
 static nna_status stft_backward_core(const nna_plan* plan, const float* x_dev, long long B, long long L, long long T,
                                      const float* gout_dev, int fmt, int out_bins, float* gw_dev, float* gx_dev,
-                                     float* gbuf, void* hip_stream, float* pout = nullptr) {
+                                     float* gbuf, void* hip_stream, float* pout = nullptr, bool zero_gw = true) {
   const int M = pick_tile_frames(ST_FRAMES, T, plan->nj - 1, ST_LDS_ROWS);
   if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
@@ -351,8 +426,10 @@ static nna_status stft_backward_core(const nna_plan* plan, const float* x_dev, l
   Q.gw = gw_dev;
   Q.gx = gx_dev;
   if (gw_dev) {
-    e = nna::launch_fill_zero(gw_dev, 2LL * plan->stft_bins() * plan->K, stream);
-    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    if (zero_gw) {
+      e = nna::launch_fill_zero(gw_dev, 2LL * plan->stft_bins() * plan->K, stream);
+      if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    }
     // split the contraction over the frames so that about 1,024 workgroups exist (two per compute
     // unit, twice over), each with at least 64 chunks to amortise its start-up
     const long long tiles = (long long)(plan->rows_pad / nna::BW_MT) * (plan->kp / nna::BW_NT);
@@ -509,6 +586,29 @@ nna_status nna_cqt_backward(const nna_plan* plan, const float* x_dev, long long 
 // ---- trainable kernels of the downsampling CQT (time-domain kernels; the paper's CQT2010v2 layer) -----------------
 static size_t ws256f(long long floats) { return ((size_t)floats * sizeof(float) + 255) / 256 * 256; }
 
+// gx[B, L] += (transposed decimation step) g[B, Ln]: what the octave below sends back up through the filter
+static nna_status fir_transpose_add(const nna_plan* fir, const float* g, float* gx, long long B, long long L, long long Ln,
+                                    hipStream_t stream) {
+  nna::FirTParams F;
+  std::memset(&F, 0, sizeof(F));
+  F.he = fir->d_fir_he;
+  F.ho = fir->d_fir_ho;
+  F.ne = (int)fir->h_fir_he.size();
+  F.no = (int)fir->h_fir_ho.size();
+  F.ve0 = fir->fir_ve0;
+  F.vo0 = fir->fir_vo0;
+  F.L = L;
+  F.Ln = Ln;
+  for (long long b0 = 0; b0 < B; b0 += 65535) {  // the grid's second dimension holds at most 65,535 waveforms
+    F.B = std::min(B - b0, 65535LL);
+    F.g = g + b0 * Ln;
+    F.gx = gx + b0 * L;
+    const hipError_t e = nna::launch_fir_transpose_add(F, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  }
+  return NNA_OK;
+}
+
 // The workspace: the waveforms of octaves 1.. (kept from the forward recursion), G of one octave, and two waveform
 // gradients (octaves 1 and 2: the deeper ones alternate between them).  Offsets in bytes; false if L is too short.
 struct Cqt2010BwLayout {
@@ -609,24 +709,329 @@ nna_status nna_cqt2010v2_backward(const nna_plan* plan, const float* x_dev, long
                                stream)) != NNA_OK)
       return s;
     if (ga && a + 1 < n_oct) {
-      nna::FirTParams F;
-      std::memset(&F, 0, sizeof(F));
-      F.he = plan->fir->d_fir_he;
-      F.ho = plan->fir->d_fir_ho;
-      F.ne = (int)plan->fir->h_fir_he.size();
-      F.no = (int)plan->fir->h_fir_ho.size();
-      F.ve0 = plan->fir->fir_ve0;
-      F.vo0 = plan->fir->fir_vo0;
-      F.L = W.La[a];
-      F.Ln = W.La[a + 1];
       const float* gb = reinterpret_cast<const float*>(ws + W.gx_off[a & 1]);
-      for (long long b0 = 0; b0 < B; b0 += 65535) {  // the grid's second dimension holds at most 65,535 waveforms
-        F.B = std::min(B - b0, 65535LL);
-        F.g = gb + b0 * F.Ln;
-        F.gx = ga + b0 * F.L;
-        e = nna::launch_fir_transpose_add(F, stream);
-        if (e != hipSuccess) return fail_hip(e, "kernel launch");
-      }
+      if ((s = fir_transpose_add(plan->fir, gb, ga, B, W.La[a], W.La[a + 1], stream)) != NNA_OK) return s;
+    }
+  }
+  return NNA_OK;
+}
+
+// ---- trainable kernels of the CQT layers with frequency-domain kernels (CQT1992, CQT2010) ---------------------------
+static nna_status check_spectral(const nna_plan* plan) {
+  nna_status s = check_trainable(plan);
+  if (s != NNA_OK) return s;
+  if (plan->kind != NNA_KIND_CQT1992 && plan->kind != NNA_KIND_CQT2010)
+    return fail(NNA_ERR_INVALID_ARG, "not a plan with frequency-domain constant-Q kernels");
+  return NNA_OK;
+}
+
+nna_status nna_plan_get_spectral_kernels(const nna_plan* plan, float* y_dev, void* hip_stream) {
+  nna_status s = check_spectral(plan);
+  if (s != NNA_OK) return s;
+  if (!y_dev) return fail(NNA_ERR_INVALID_ARG, "y_dev is NULL");
+  const nna_plan* top = plan->kind == NNA_KIND_CQT2010 ? plan->octave[0] : plan;
+  DeviceGuard guard;
+  hipError_t e = guard.enter(plan->device);
+  if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+  e = hipMemcpyAsync(y_dev, top->d_ysk, (size_t)2 * top->n_bins * (top->n_half + 1) * sizeof(float), hipMemcpyDeviceToDevice,
+                     reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail_hip(e, "spectral kernel copy");
+  return NNA_OK;
+}
+
+// rows of the weight Ysk[2 n_top, F] that octave `sub` of a downsampling plan uses (a partial lowest octave: the upper bins)
+static long long octave_spectral_row(const nna_plan* plan, const nna_plan* sub) {
+  return 2LL * (plan->octave[0]->n_bins - sub->n_bins);
+}
+
+nna_status nna_plan_set_spectral_kernels(nna_plan* plan, const float* y_dev, void* hip_stream) {
+  nna_status s = check_spectral(plan);
+  if (s != NNA_OK) return s;
+  if (!y_dev) return fail(NNA_ERR_INVALID_ARG, "y_dev is NULL");
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  DeviceGuard guard;
+  hipError_t e = guard.enter(plan->device);
+  if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+  auto set_one = [&](nna_plan* p, const float* rows) -> hipError_t {
+    hipError_t e1 = hipMemcpyAsync(p->d_ysk, rows, (size_t)2 * p->n_bins * (p->n_half + 1) * sizeof(float),
+                                   hipMemcpyDeviceToDevice, stream);
+    if (e1 != hipSuccess) return e1;
+    return nna::launch_lin_from_logical(lin_logical_params(p, p->d_ysk), stream);
+  };
+  if (plan->kind == NNA_KIND_CQT1992) {
+    e = set_one(plan, y_dev);
+  } else {
+    for (nna_plan* sub : plan->octave) {
+      e = set_one(sub, y_dev + octave_spectral_row(plan, sub) * (sub->n_half + 1));
+      if (e != hipSuccess) break;
+    }
+  }
+  if (e != hipSuccess) return fail_hip(e, "spectral kernel update");
+  return NNA_OK;
+}
+
+// Workspace of one two-stage backward pass over T frames of B waveforms: the spectrum X[B][R][T] (R = 2 F rows,
+// (Re, Im) pairs), the constant-Q values V[B][M][T] (M = 2 n_bins; overwritten by their gradient), the gradient
+// reaching the spectrum, the matrix form of the spectral kernels' gradient, and the STFT stage's G.
+struct SpectralBwLayout {
+  size_t x_off, v_off, gx_off, gy_off, g_off, total;
+};
+static SpectralBwLayout spectral_bw_layout(const nna_plan* p, long long B, long long T, size_t base) {
+  SpectralBwLayout W;
+  const long long R = 2LL * (p->n_half + 1), M = 2LL * p->n_bins;
+  size_t off = base;
+  W.x_off = off;
+  off += ws256f(B * R * T);
+  W.v_off = off;
+  off += ws256f(B * M * T);
+  W.gx_off = off;
+  off += ws256f(B * R * T);
+  W.gy_off = off;
+  off += ws256f(M * R);
+  W.g_off = off;
+  off += ws256f((long long)p->rows_pad * bw_gpitch(B * T));
+  W.total = off;
+  return W;
+}
+
+// The backward pass of one two-stage transform (plan of kind CQT1992, trainable): gout points at the plan's first
+// output row of waveform 0.  gy_dev [2 n_bins][F] is overwritten or, with accumulate_gy, added to; gw_dev is
+// added to (the caller zeroes it); gx_dev is overwritten.  Any of the three may be NULL.  Device current.
+static nna_status spectral_backward_core(const nna_plan* plan, const float* x_dev, long long B, long long L, long long T,
+                                         const float* gout, long long gout_wave_stride, float* gy_dev, bool accumulate_gy,
+                                         float* gw_dev, float* gx_dev, char* ws, const SpectralBwLayout& W, void* hip_stream) {
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  const int F = plan->n_half + 1, R = 2 * F, M = 2 * plan->n_bins;
+  float* X = reinterpret_cast<float*>(ws + W.x_off);
+  float* V = reinterpret_cast<float*>(ws + W.v_off);
+  float* GX = reinterpret_cast<float*>(ws + W.gx_off);
+  float* GY = reinterpret_cast<float*>(ws + W.gy_off);
+  float* gbuf = reinterpret_cast<float*>(ws + W.g_off);
+  // 1. the spectrum itself, rows (Re, Im) per bin: the first stage's contraction with the complex epilogue
+  {
+    const int Mf = pick_tile_frames(ST_FRAMES, T, plan->nj - 1, ST_LDS_ROWS);
+    if (Mf < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
+    nna::StftParams P;
+    std::memset(&P, 0, sizeof(P));
+    P.g = make_geom(plan, x_dev, B, L, T);
+    P.bank = reinterpret_cast<const float4*>(plan->d_bank);
+    P.out = X;
+    P.n_rt = plan->n_rt;
+    P.n_chunks = plan->n_chunks;
+    P.nj = plan->nj;
+    P.n_half = plan->n_half;
+    P.packed = 1;
+    P.out_bins = R;
+    P.fmt = NNA_OUT_COMPLEX;
+    P.tile_frames = Mf;
+    P.n_ft = (P.g.n_frames + Mf - 1) / Mf;
+    hipError_t e = nna::launch_stft(P, nna::ST_MODE_CPLX, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  }
+  nna::MelBwParams Q;
+  std::memset(&Q, 0, sizeof(Q));
+  Q.B = B;
+  Q.T = (int)T;
+  // 2. V[b, m, t] = sum_r Ylin[m, r] X[b, r, t]
+  Q.g = X;
+  Q.wrm = plan->d_ylinT;
+  Q.n_mels = R;
+  Q.mels_pad = (R + nna::BW_KC - 1) / nna::BW_KC * nna::BW_KC;
+  Q.F = M;
+  Q.fp = plan->lin_mp;
+  Q.gP = V;
+  hipError_t e = nna::launch_mel_bw_spec(Q, stream);
+  if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  // 3. V <- dLoss/dV through the output format
+  nna::LinGradParams Gd;
+  std::memset(&Gd, 0, sizeof(Gd));
+  Gd.v = V;
+  Gd.gout = gout;
+  Gd.gout_wave_stride = gout_wave_stride;
+  Gd.n = B * plan->n_bins * T;
+  Gd.n_bins = plan->n_bins;
+  Gd.T = (int)T;
+  Gd.fmt = plan->fmt;
+  e = nna::launch_lin_grad(Gd, stream);
+  if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  // 4. gradient of the spectral kernels: gYlin[m, r] = sum_{b,t} gV[b, m, t] X[b, r, t], folded onto (Re Y, Im Y)
+  if (gy_dev) {
+    e = nna::launch_fill_zero(GY, (long long)M * R, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    Q.g = V;
+    Q.P = X;
+    Q.gW = GY;
+    Q.n_mels = M;
+    Q.F = R;
+    Q.fp = plan->lin_rp;
+    const long long tiles = (long long)((M + nna::BW_MT - 1) / nna::BW_MT) * (Q.fp / nna::BW_NT);
+    const long long splits = std::max(1LL, std::min(B, (1024 + tiles - 1) / tiles));
+    Q.b_per_split = (int)((B + splits - 1) / splits);
+    e = nna::launch_mel_bw_weights(Q, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    e = nna::launch_lin_fold_gradient(GY, gy_dev, plan->n_bins, F, accumulate_gy ? 1 : 0, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  }
+  if (!gw_dev && !gx_dev) return NNA_OK;
+  // 5. gradient reaching the spectrum: gX[b, r, t] = sum_m Ylin[m, r] gV[b, m, t]
+  Q.g = V;
+  Q.wrm = plan->d_ylin;
+  Q.n_mels = M;
+  Q.mels_pad = (M + nna::BW_KC - 1) / nna::BW_KC * nna::BW_KC;
+  Q.F = R;
+  Q.fp = plan->lin_rp;
+  Q.gP = GX;
+  e = nna::launch_mel_bw_spec(Q, stream);
+  if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  // 6. the STFT stage's backward pass with gX as the gradient of its complex output
+  return stft_backward_core(plan, x_dev, B, L, T, GX, NNA_OUT_COMPLEX, R, gw_dev, gx_dev, gbuf, hip_stream, nullptr, false);
+}
+
+static nna_status check_cqt1992_bw(const nna_plan* plan, long long B, long long L, long long* T) {
+  nna_status s = check_trainable(plan);
+  if (s != NNA_OK) return s;
+  if (plan->kind != NNA_KIND_CQT1992) return fail(NNA_ERR_INVALID_ARG, "plan was built for a different transform");
+  if (B < 1) return fail(NNA_ERR_SHAPE, "B must be >= 1");
+  if (L < 4) return fail(NNA_ERR_SHAPE, "L must be at least 4 samples");
+  *T = frames_of(plan, L);
+  if (*T < 1) return fail(NNA_ERR_SHAPE, plan->center ? "L must exceed the reflection padding (K/2)" : "L is shorter than one window");
+  return NNA_OK;
+}
+
+nna_status nna_cqt1992_backward_workspace(const nna_plan* plan, long long B, long long L, size_t* bytes) {
+  long long T = 0;
+  nna_status s = check_cqt1992_bw(plan, B, L, &T);
+  if (s != NNA_OK) return s;
+  if (!bytes) return fail(NNA_ERR_INVALID_ARG, "bytes is NULL");
+  *bytes = spectral_bw_layout(plan, B, T, 0).total;
+  return NNA_OK;
+}
+
+nna_status nna_cqt1992_backward(const nna_plan* plan, const float* x_dev, long long B, long long L, const float* gout_dev,
+                                float* gy_dev, float* gw_dev, float* gx_dev, void* workspace_dev, size_t workspace_bytes,
+                                void* hip_stream) {
+  long long T = 0;
+  nna_status s = check_cqt1992_bw(plan, B, L, &T);
+  if (s != NNA_OK) return s;
+  if (!gout_dev) return fail(NNA_ERR_INVALID_ARG, "gout_dev is NULL");
+  if (!gy_dev && !gw_dev && !gx_dev) return fail(NNA_ERR_INVALID_ARG, "all three gradient pointers are NULL: nothing to compute");
+  float* any_out = gy_dev ? gy_dev : gw_dev ? gw_dev : gx_dev;
+  if ((s = check_call(plan, NNA_KIND_CQT1992, x_dev, B, L, any_out, &T)) != NNA_OK) return s;
+  const SpectralBwLayout W = spectral_bw_layout(plan, B, T, 0);
+  if (!workspace_dev || workspace_bytes < W.total || (reinterpret_cast<uintptr_t>(workspace_dev) & 255))
+    return fail(NNA_ERR_INVALID_ARG, "workspace_dev is NULL, not 256-byte aligned or smaller than nna_cqt1992_backward_workspace asks for");
+  DeviceGuard guard;
+  hipError_t e = guard.enter(plan->device);
+  if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+  if (gw_dev) {
+    e = nna::launch_fill_zero(gw_dev, 2LL * plan->stft_bins() * plan->K, reinterpret_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  }
+  return spectral_backward_core(plan, x_dev, B, L, T, gout_dev, (long long)plan->out_rows() * T, gy_dev, false, gw_dev, gx_dev,
+                                static_cast<char*>(workspace_dev), W, hip_stream);
+}
+
+// The downsampling flavour: the octaves' waveforms, two waveform gradients (as for nna_cqt2010v2_backward), then one
+// octave's two-stage workspace.
+struct Cqt2010SpectralLayout {
+  Cqt2010BwLayout oct;  // x_off / gx_off (its g_off is unused)
+  SpectralBwLayout st;
+};
+static bool cqt2010_spectral_layout(const nna_plan* plan, long long B, long long L, Cqt2010SpectralLayout& W) {
+  Cqt2010BwLayout& O = W.oct;
+  if (!cqt2010_lengths(plan, L, O.La)) return false;
+  const int n_oct = (int)plan->octave.size();
+  const long long T = 1 + L / plan->hop;
+  size_t off = 0;
+  for (int a = 1; a < n_oct; ++a) {
+    O.x_off[a] = off;
+    off += ws256f(B * O.La[a]);
+  }
+  O.g_off = off;
+  for (int i = 0; i < 2; ++i) {
+    O.gx_off[i] = off;
+    if (n_oct > 1 + i) off += ws256f(B * O.La[1 + i]);
+  }
+  W.st = spectral_bw_layout(plan->octave[0], B, T, off);  // the top octave has the most bins: the largest
+  O.total = W.st.total;
+  return true;
+}
+
+static nna_status check_cqt2010_bw(const nna_plan* plan, long long B, long long L) {
+  nna_status s = check_trainable(plan);
+  if (s != NNA_OK) return s;
+  if (plan->kind != NNA_KIND_CQT2010) return fail(NNA_ERR_INVALID_ARG, "plan was built for a different transform");
+  if (B < 1) return fail(NNA_ERR_SHAPE, "B must be >= 1");
+  const long long T = 1 + L / plan->hop;
+  if (L < 1 || T > 0x7fffffffLL / 4 || L > 0x7fffffffLL - 4LL * plan->K - 64 || B > 0x7fffffffLL || B > (1LL << 40) / T)
+    return fail(NNA_ERR_SHAPE, "batch too large");
+  return NNA_OK;
+}
+
+nna_status nna_cqt2010_backward_workspace(const nna_plan* plan, long long B, long long L, size_t* bytes) {
+  nna_status s = check_cqt2010_bw(plan, B, L);
+  if (s != NNA_OK) return s;
+  if (!bytes) return fail(NNA_ERR_INVALID_ARG, "bytes is NULL");
+  Cqt2010SpectralLayout W;
+  if (!cqt2010_spectral_layout(plan, B, L, W))
+    return fail(NNA_ERR_SHAPE, "L is too short: every octave's waveform must exceed the reflection padding, and all but the lowest hold one frame of the decimation filter");
+  *bytes = W.oct.total;
+  return NNA_OK;
+}
+
+nna_status nna_cqt2010_backward(const nna_plan* plan, const float* x_dev, long long B, long long L, const float* gout_dev,
+                                float* gy_dev, float* gw_dev, float* gx_dev, void* workspace_dev, size_t workspace_bytes,
+                                void* hip_stream) {
+  nna_status s = check_cqt2010_bw(plan, B, L);
+  if (s != NNA_OK) return s;
+  if (!x_dev || !gout_dev) return fail(NNA_ERR_INVALID_ARG, "x_dev / gout_dev is NULL");
+  if (!gy_dev && !gw_dev && !gx_dev) return fail(NNA_ERR_INVALID_ARG, "all three gradient pointers are NULL: nothing to compute");
+  Cqt2010SpectralLayout W;
+  if (!cqt2010_spectral_layout(plan, B, L, W))
+    return fail(NNA_ERR_SHAPE, "L is too short: every octave's waveform must exceed the reflection padding, and all but the lowest hold one frame of the decimation filter");
+  if (!workspace_dev || workspace_bytes < W.oct.total || (reinterpret_cast<uintptr_t>(workspace_dev) & 255))
+    return fail(NNA_ERR_INVALID_ARG, "workspace_dev is NULL, not 256-byte aligned or smaller than nna_cqt2010_backward_workspace asks for");
+  const int n_oct = (int)plan->octave.size();
+  const long long T = 1 + L / plan->hop;
+  for (const nna_plan* sub : plan->octave)
+    if (pick_tile_frames(ST_FRAMES, T, sub->nj - 1, ST_LDS_ROWS) < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  DeviceGuard guard;
+  hipError_t e = guard.enter(plan->device);
+  if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+  char* ws = static_cast<char*>(workspace_dev);
+  const long long* La = W.oct.La;
+  const float* xa[MAX_OCTAVES];
+  xa[0] = x_dev;
+  for (int a = 1; a < n_oct; ++a) {
+    float* dst = reinterpret_cast<float*>(ws + W.oct.x_off[a]);
+    if ((s = run_fir(plan->fir, xa[a - 1], B, La[a - 1], dst, La[a], hip_stream)) != NNA_OK) return s;
+    xa[a] = dst;
+  }
+  const nna_plan* top = plan->octave[0];
+  const int F = top->n_half + 1;
+  if (gw_dev) {
+    e = nna::launch_fill_zero(gw_dev, 2LL * F * top->K, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  }
+  if (gy_dev) {
+    e = nna::launch_fill_zero(gy_dev, 2LL * top->n_bins * F, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  }
+  const long long out_stride = (long long)plan->out_rows() * T;
+  const int rpb = plan->fmt == NNA_OUT_COMPLEX ? 2 : 1;
+  for (int a = n_oct - 1; a >= 0; --a) {
+    const nna_plan* sub = plan->octave[a];
+    int lo, hi;
+    octave_bins(plan->n_bins, plan->bpo, a, lo, hi);
+    float* ga = !gx_dev ? nullptr : a == 0 ? gx_dev : reinterpret_cast<float*>(ws + W.oct.gx_off[(a - 1) & 1]);
+    float* gya = gy_dev ? gy_dev + octave_spectral_row(plan, sub) * F : nullptr;
+    if ((s = spectral_backward_core(sub, xa[a], B, La[a], T, gout_dev + (long long)rpb * lo * T, out_stride, gya, true, gw_dev, ga,
+                                    ws, W.st, hip_stream)) != NNA_OK)
+      return s;
+    if (ga && a + 1 < n_oct) {
+      const float* gb = reinterpret_cast<const float*>(ws + W.oct.gx_off[a & 1]);
+      if ((s = fir_transpose_add(plan->fir, gb, ga, B, La[a], La[a + 1], stream)) != NNA_OK) return s;
     }
   }
   return NNA_OK;

@@ -118,6 +118,14 @@ struct nna_plan {
   // trainable Mel plans: the filterbank row-major [mels_pad][fp], zero padded
   float* d_melw_rm = nullptr;
   int fp = 0, mels_pad = 0;
+  // trainable plans with frequency-domain constant-Q kernels: the spectral kernels as the caller's tensor
+  // Ysk[2 n_bins][n_half + 1] (row 2q = Re, 2q+1 = Im, 1/n_fft included), and the real matrix they form on the
+  // (Re, Im) rows of a spectrum, row-major both ways round, zero padded: Ylin[lin_mp][lin_rp], YlinT[lin_rp][lin_mp]
+  // (lin_mp = 2 n_bins, lin_rp = 2 (n_half + 1), each rounded up to 128)
+  float* d_ysk = nullptr;
+  float* d_ylin = nullptr;
+  float* d_ylinT = nullptr;
+  int lin_mp = 0, lin_rp = 0;
   float* d_melw = nullptr;
   unsigned char* d_mel_mask = nullptr;
   float* d_mel_wnyq = nullptr;

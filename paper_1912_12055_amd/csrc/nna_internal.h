@@ -253,6 +253,33 @@ struct MelBwParams {
   int b_per_split;       // filterbank gradient: waveforms per workgroup
 };
 
+// Spectral kernels of a trainable plan with frequency-domain constant-Q kernels: the caller's tensor
+// Ysk[2 n_bins][n_half + 1] -> the fragment-order matrix of the forward kernel's second contraction and the two
+// row-major copies the backward pass multiplies with
+struct LinLogicalParams {
+  const float* ysk;
+  float* frag;           // n_frag floats, indexed as the forward kernel reads them
+  float* ylin;           // [.][rp]: Ylin[2q][2s] = Yr, [2q][2s+1] = -Yi, [2q+1][2s] = Yi, [2q+1][2s+1] = Yr
+  float* ylinT;          // [.][mp]: its transpose
+  long long n_frag;
+  int n_bins, n_half, n_rt, lin_blocks, mp, rp;
+};
+hipError_t launch_lin_from_logical(const LinLogicalParams& p, hipStream_t stream);
+
+// Second stage of the backward pass of those plans, elementwise: v[B][2 n_bins][T] holds the complex constant-Q
+// values (rows 2q = Re, 2q+1 = Im) and is overwritten with dLoss/d(Re, Im) given gout (the output format's
+// derivative; gout: row q of a waveform, or rows 2q, 2q+1 for the complex format, waveforms gout_wave_stride apart)
+struct LinGradParams {
+  float* v;
+  const float* gout;
+  long long gout_wave_stride, n;  // n = B n_bins T
+  int n_bins, T, fmt;
+};
+hipError_t launch_lin_grad(const LinGradParams& p, hipStream_t stream);
+// gysk[2q][s] (+)= gylin[2q][2s] + gylin[2q+1][2s+1],  gysk[2q+1][s] (+)= gylin[2q+1][2s] - gylin[2q][2s+1]
+// (gylin[2 n_bins][2 F], gysk[2 n_bins][F])
+hipError_t launch_lin_fold_gradient(const float* gylin, float* gysk, int n_bins, int F, int accumulate, hipStream_t stream);
+
 // The launchers report hipGetLastError() right after their launch.  That call also returns (and clears) an
 // error some earlier, unrelated call of this thread left behind -- PyTorch shares the runtime -- so every
 // launcher first clears whatever is pending: the status it returns is then its own launch's.

@@ -717,7 +717,7 @@ nna_status nna_plan_info(const nna_plan* plan, int* kind, long long* bank_rows, 
   if (!plan) return fail(NNA_ERR_INVALID_ARG, "plan is NULL");
   if (kind) *kind = plan->kind;
   if (bank_rows)
-    *bank_rows = plan->kind == NNA_KIND_CQT2010   ? 0
+    *bank_rows = plan->kind == NNA_KIND_CQT2010   ? 2LL * (plan->octave[0]->n_half + 1)   // the DFT bank all octaves share
                  : plan->kind == NNA_KIND_CQT2010V2 ? (long long)plan->octave[0]->conv_rows  // the one weight all octaves share
                  : plan->kind == NNA_KIND_CQT     ? (long long)plan->conv_rows
                                                   : 2LL * (plan->freq_scale ? plan->n_half : plan->n_half + 1);
@@ -763,6 +763,9 @@ void nna_plan_destroy(nna_plan* plan) {
       (void)hipFree(plan->d_bank16s);
       (void)hipFree(plan->d_wrm);
       (void)hipFree(plan->d_melw_rm);
+      (void)hipFree(plan->d_ysk);
+      (void)hipFree(plan->d_ylin);
+      (void)hipFree(plan->d_ylinT);
       (void)hipFree(plan->d_melw);
       (void)hipFree(plan->d_mel_mask);
       (void)hipFree(plan->d_mel_wnyq);

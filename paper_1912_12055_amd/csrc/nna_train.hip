@@ -793,6 +793,96 @@ __global__ void mel_from_logical_kernel(const float* __restrict__ w, float* __re
   (void)n_pass;
 }
 
+// ---- spectral kernels of a trainable plan with frequency-domain constant-Q kernels -----------------------
+// Entry (output row, packed spectrum column) of the second contraction's matrix: output rows 2q / 2q+1 = Re / Im
+// of constant-Q bin q; packed columns 0, 1 = Re of the purely real bins 0 and n_half, 2s / 2s+1 = Re / Im of bin s.
+//   Re X_cq += Xr Yr - Xi Yi,   Im X_cq += Xr Yi + Xi Yr      (eq. (CQT1992) in real arithmetic)
+__device__ __forceinline__ float lin_entry(const float* __restrict__ ysk, int F, int n_half, int row, int col) {
+  const int q = row >> 1, s = col == 0 ? 0 : col == 1 ? n_half : col >> 1;
+  const bool im_part = col >= 2 && (col & 1);
+  const float yr = ysk[(long long)(2 * q) * F + s], yi = ysk[(long long)(2 * q + 1) * F + s];
+  return (row & 1) ? (im_part ? yr : yi) : (im_part ? -yi : yr);
+}
+
+__global__ void lin_from_logical_kernel(const LinLogicalParams P) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int F = P.n_half + 1;
+  if (i < P.n_frag) {
+    // ((((((pass n_rt + rt) ST_RB + rb) lin_blocks + mb) 4 + v) 64 + lane) 4 + e
+    const int e = (int)(i & 3), lane = (int)((i >> 2) & 63), v = (int)((i >> 8) & 3);
+    long long rest = i >> 10;
+    const int mb = (int)(rest % P.lin_blocks);
+    rest /= P.lin_blocks;
+    const int rb = (int)(rest % ST_RB);
+    rest /= ST_RB;
+    const int rt = (int)(rest % P.n_rt), pass = (int)(rest / P.n_rt);
+    const int row = pass * 32 * P.lin_blocks + mb * 32 + (lane & 31);
+    const int col = rt * ST_ROWS + rb * 32 + 8 * v + 4 * (lane >> 5) + e;
+    P.frag[i] = (row < 2 * P.n_bins && col < 2 * P.n_half) ? lin_entry(P.ysk, F, P.n_half, row, col) : 0.f;
+  }
+  if (i < (long long)P.n_bins * F) {
+    const int q = (int)(i / F), s = (int)(i - (long long)q * F);
+    const float yr = P.ysk[(long long)(2 * q) * F + s], yi = P.ysk[(long long)(2 * q + 1) * F + s];
+    float* a = P.ylin + (long long)(2 * q) * P.rp + 2 * s;
+    a[0] = yr;
+    a[1] = -yi;
+    a[P.rp] = yi;
+    a[P.rp + 1] = yr;
+    float* t = P.ylinT + (long long)(2 * s) * P.mp + 2 * q;
+    t[0] = yr;
+    t[1] = yi;
+    t[P.mp] = -yi;
+    t[P.mp + 1] = yr;
+  }
+}
+
+__global__ void lin_grad_kernel(const LinGradParams P) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= P.n) return;
+  const long long per_wave = (long long)P.n_bins * P.T;
+  const long long b = i / per_wave;
+  const int q = (int)((i - b * per_wave) / P.T), t = (int)(i - b * per_wave - (long long)q * P.T);
+  float* vr = P.v + (b * 2 * P.n_bins + 2 * q) * P.T + t;
+  float* vi = vr + P.T;
+  const float re = *vr, im = *vi, pw = re * re + im * im;
+  const float* gp = P.gout + b * P.gout_wave_stride + t;
+  float gr, gi;
+  if (P.fmt == NNA_OUT_COMPLEX) {
+    gr = gp[(2LL * q) * P.T];
+    gi = gp[(2LL * q + 1) * P.T];
+  } else if (P.fmt == NNA_OUT_PHASE) {  // d atan2(Im, Re) = (Re dIm - Im dRe) / P
+    const float s = pw > 0.f ? gp[(long long)q * P.T] / pw : 0.f;
+    gr = -s * im;
+    gi = s * re;
+  } else {
+    const float go = gp[(long long)q * P.T];
+    const float s = P.fmt == NNA_OUT_MAGNITUDE ? grad_scale<NNA_OUT_MAGNITUDE>(go, pw)
+                    : P.fmt == NNA_OUT_POWER   ? grad_scale<NNA_OUT_POWER>(go, pw)
+                                               : grad_scale<NNA_OUT_LOG>(go, pw);
+    gr = s * re;
+    gi = s * im;
+  }
+  *vr = gr;
+  *vi = gi;
+}
+
+__global__ void lin_fold_gradient_kernel(const float* __restrict__ gylin, float* __restrict__ gysk, int n_bins, int F, int accumulate) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (long long)n_bins * F) return;
+  const int q = (int)(i / F), s = (int)(i - (long long)q * F);
+  const long long R = 2LL * F;
+  const float* a = gylin + (2LL * q) * R + 2 * s;
+  const float gr = a[0] + a[R + 1], gi = a[R] - a[1];
+  float* o = gysk + (2LL * q) * F + s;
+  if (accumulate) {
+    o[0] += gr;
+    o[F] += gi;
+  } else {
+    o[0] = gr;
+    o[F] = gi;
+  }
+}
+
 // ---- launchers ---------------------------------------------------------------------------------
 static unsigned grid_for(long long n, int block) {
   long long b = (n + block - 1) / block;
@@ -923,6 +1013,30 @@ hipError_t launch_bw_wave(const BwParams& p, hipStream_t stream) {
   const long long blocks = (p.gpitch / BW_MT) * (p.kp / BW_NT);
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL((bw_gemm_kernel<BW_MODE_WAVE, false>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_lin_from_logical(const LinLogicalParams& p, hipStream_t stream) {
+  clear_stale_error();
+  const long long n = std::max(p.n_frag, (long long)p.n_bins * (p.n_half + 1));
+  if (n < 1 || (n + 255) / 256 > 0x7fffffffLL || p.lin_blocks < 1 || p.n_rt < 1) return hipErrorInvalidValue;
+  if (p.mp < 2 * p.n_bins || p.rp < 2 * (p.n_half + 1)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(lin_from_logical_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_lin_grad(const LinGradParams& p, hipStream_t stream) {
+  clear_stale_error();
+  if (p.n < 1 || (p.n + 255) / 256 > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(lin_grad_kernel, dim3((unsigned)((p.n + 255) / 256)), dim3(256), 0, stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_lin_fold_gradient(const float* gylin, float* gysk, int n_bins, int F, int accumulate, hipStream_t stream) {
+  clear_stale_error();
+  const long long n = (long long)n_bins * F;
+  if (n < 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(lin_fold_gradient_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, gylin, gysk, n_bins, F, accumulate);
   return hipGetLastError();
 }
 

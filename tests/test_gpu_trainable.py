@@ -90,9 +90,6 @@ def test_not_trainable_plans_are_refused(nb):
     with pytest.raises(nb.NnaError) as e:
         nb.nna_plan_get_bank(plan)
     assert e.value.status == nb.NNA_ERR_INVALID_ARG and "nna_plan_trainable" in e.value.message
-    with pytest.raises(nb.NnaError) as e:
-        nb.nna_plan_trainable(nb.nna_plan_cqt2010v2(sr=8000, hop=64, fmin=220.0, n_bins=24, device=0))
-    assert e.value.status == nb.NNA_ERR_INVALID_ARG
     with pytest.raises(nb.NnaError) as e:  # the constant-Q backward pass wants a constant-Q plan
         nb.nna_cqt_backward_workspace(nb.nna_plan_trainable(nb.nna_plan_stft(n_fft=256, hop=64, device=0)), 2, 1000)
     assert e.value.status == nb.NNA_ERR_INVALID_ARG
@@ -518,9 +515,154 @@ def test_cqt2010v2_backward_refuses_wrong_plans_and_workspaces(nb):
     with pytest.raises(nb.NnaError) as ei:   # too short for the lowest octave
         nb.nna_cqt2010v2_backward_workspace(plan, 2, 600)
     assert ei.value.status == nb.NNA_ERR_SHAPE
-    p2 = nb.nna_plan_cqt2010(sr=16000, hop=64, fmin=220.0, n_bins=29, fir_taps=63, device=0)
-    with pytest.raises(nb.NnaError) as ei:   # frequency-domain kernels: no trainable form
-        nb.nna_plan_trainable(p2)
+    p2 = nb.nna_plan_trainable(nb.nna_plan_cqt2010(sr=16000, hop=64, fmin=220.0, n_bins=29, fir_taps=63, device=0))
+    with pytest.raises(nb.NnaError) as ei:   # the time-domain entry point does not take a plan with frequency-domain kernels
+        nb.nna_cqt2010v2_backward_workspace(p2, 2, 5000)
+    assert ei.value.status == nb.NNA_ERR_INVALID_ARG
+
+
+# ---- trainable kernels of the CQT layers with frequency-domain kernels ------------------------------------
+# (name, sr, fmin, n_bins, bins/octave, hop, n_fft, B, L, output format, centred)
+CQT1992_BACKWARD_CASES = [
+    ("magnitude", 8000, 220.0, 30, 12, 64, 0, 3, 5000, oracle.MAGNITUDE, True),
+    ("power", 8000, 220.0, 30, 12, 64, 0, 2, 3000, oracle.POWER, True),
+    ("log", 8000, 220.0, 30, 12, 64, 0, 2, 3000, oracle.LOG, True),
+    ("complex", 8000, 220.0, 30, 12, 64, 0, 2, 3000, oracle.COMPLEX, True),
+    ("phase", 8000, 220.0, 30, 12, 64, 0, 2, 3000, oracle.PHASE, True),
+    ("100-bins-two-passes-odd-frames", 16000, 200.0, 100, 24, 64, 0, 3, 9001, oracle.MAGNITUDE, True),
+    ("hop-not-dividing-n_fft-no-centring", 8000, 220.0, 13, 6, 100, 1024, 2, 6000, oracle.POWER, False),
+    ("short-waveforms-many-per-tile", 8000, 220.0, 24, 12, 128, 1024, 40, 1100, oracle.MAGNITUDE, True),
+]
+
+
+def _spectral_weights(nb, plan, rng, perturb=True):
+    """the plan's two weights as float32 arrays, moved off their initial values (inside the DFT bank's mask)"""
+    W = nb.nna_plan_get_bank(plan).cpu().numpy()
+    Y = nb.nna_plan_get_spectral_kernels(plan).cpu().numpy()
+    if perturb:
+        mask = oracle.dft_bank_parameter_mask(W.shape[1])
+        W = np.where(mask, W * (1.0 + 0.1 * rng.standard_normal(W.shape)), 0).astype(np.float32)
+        Y = (Y * (1.0 + 0.2 * rng.standard_normal(Y.shape))).astype(np.float32)
+        nb.nna_plan_set_bank(plan, _dev(W))
+        nb.nna_plan_set_spectral_kernels(plan, _dev(Y))
+    return W, Y
+
+
+def test_cqt1992_trainable_weights_are_the_oracles_and_set_reaches_the_forward_kernel(nb):
+    import torch
+    _say("cqt1992 trainable: get / set of both stages")
+    kw = dict(sr=8000, fmin=220.0, n_bins=30, bins_per_octave=12)
+    plan = nb.nna_plan_trainable(nb.nna_plan_cqt1992(hop=64, device=0, **kw))
+    W0, Y0 = oracle.cqt1992_weights(**kw)
+    rng = np.random.default_rng(5)
+    W, Y = _spectral_weights(nb, plan, rng, perturb=False)
+    assert W.shape == W0.shape and Y.shape == Y0.shape
+    assert np.abs(W - W0).max() < 1e-6 and np.abs(Y - Y0).max() <= 1e-7 * np.abs(Y0).max()
+    x = _rand(3, 5000, 2)
+    ref = oracle.cqt1992(x, hop=64, **kw)
+    assert _peak_err(nb.nna_cqt1992(plan, _dev(x)).cpu().numpy(), ref) < 1e-5   # all blocks switched on: same transform
+    W, Y = _spectral_weights(nb, plan, rng)
+    assert np.array_equal(nb.nna_plan_get_spectral_kernels(plan).cpu().numpy(), Y)
+    assert np.array_equal(nb.nna_plan_get_bank(plan).cpu().numpy(), W)
+    Yc = nb.nna_plan_spectral_kernels(plan)   # the inspection call reads the forward kernel's own copy
+    assert np.array_equal(Yc.real.astype(np.float32), Y[0::2]) and np.array_equal(Yc.imag.astype(np.float32), Y[1::2])
+    ref = oracle.cqt1992_bank_forward(x, W, Y, hop=64)
+    assert _peak_err(nb.nna_cqt1992(plan, _dev(x)).cpu().numpy(), ref) < 1e-5
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("case", CQT1992_BACKWARD_CASES, ids=[c[0] for c in CQT1992_BACKWARD_CASES])
+def test_cqt1992_backward_parity_small(nb, case):
+    import torch
+    name, sr, fmin, n_bins, bpo, hop, n_fft, B, L, fmt, center = case
+    _say(f"cqt1992 backward {name}: sr={sr} bins={n_bins}/{bpo} hop={hop} n_fft={n_fft} B={B} L={L} fmt={fmt}")
+    plan = nb.nna_plan_trainable(nb.nna_plan_cqt1992(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo,
+                                                     center=center, n_fft=n_fft, fmt=fmt, device=0))
+    rng = np.random.default_rng(11)
+    W, Y = _spectral_weights(nb, plan, rng)
+    x = _rand(B, L, 12)
+    ref_out = oracle.cqt1992_bank_forward(x, W, Y, hop=hop, center=center, fmt=fmt)
+    out = nb.nna_cqt1992(plan, _dev(x)).cpu().numpy()
+    if fmt not in (oracle.PHASE, oracle.LOG):
+        assert _peak_err(out, ref_out) < TOL
+    gout = rng.standard_normal(ref_out.shape).astype(np.float32)
+    ref_gy, ref_gw, ref_gx = oracle.cqt1992_bank_backward(x, W, Y, gout, hop=hop, center=center, fmt=fmt)
+    need = nb.nna_cqt1992_backward_workspace(plan, B, L)
+    ws = torch.full(((need + 3) // 4,), float("nan"), dtype=torch.float32, device="cuda:0").view(torch.uint8)
+    gy, gw, gx = nb.nna_cqt1992_backward(plan, _dev(x), _dev(gout), workspace=ws)
+    torch.cuda.synchronize()
+    gw = gw.cpu().numpy()
+    assert not gw[1].any() and not gw[-1].any()
+    e_y, e_w, e_x = _peak_err(gy.cpu().numpy(), ref_gy), _peak_err(gw, ref_gw), _peak_err(gx.cpu().numpy(), ref_gx)
+    _say(f"  spectral kernels {e_y:.3e}, bank gradient {e_w:.3e}, waveform gradient {e_x:.3e}")
+    assert e_y < TOL and e_w < TOL and e_x < TOL
+    # each gradient alone
+    gy1, n1, n2 = nb.nna_cqt1992_backward(plan, _dev(x), _dev(gout), want_gw=False, want_gx=False)
+    assert n1 is None and n2 is None and _peak_err(gy1.cpu().numpy(), ref_gy) < TOL
+    n1, gw1, n2 = nb.nna_cqt1992_backward(plan, _dev(x), _dev(gout), want_gy=False, want_gx=False)
+    assert n1 is None and n2 is None and _peak_err(gw1.cpu().numpy(), ref_gw) < TOL
+    n1, n2, gx1 = nb.nna_cqt1992_backward(plan, _dev(x), _dev(gout), want_gy=False, want_gw=False)
+    assert n1 is None and n2 is None and _peak_err(gx1.cpu().numpy(), ref_gx) < TOL
+
+
+# (name, sr, fmin, n_bins, bins/octave, hop, fir taps, B, L, output format)
+CQT2010_BACKWARD_CASES = [
+    ("three-octaves-partial-lowest", 16000, 220.0, 29, 12, 64, 63, 3, 6000, oracle.MAGNITUDE),
+    ("complex", 16000, 220.0, 29, 12, 64, 63, 2, 5000, oracle.COMPLEX),
+    ("log", 16000, 220.0, 29, 12, 64, 63, 2, 5000, oracle.LOG),
+    ("single-octave", 16000, 1000.0, 12, 12, 128, 0, 2, 9000, oracle.POWER),
+    ("hops-down-to-4-many-short-waveforms", 16000, 500.0, 16, 4, 32, 31, 20, 3000, oracle.MAGNITUDE),
+]
+
+
+@pytest.mark.parametrize("case", CQT2010_BACKWARD_CASES, ids=[c[0] for c in CQT2010_BACKWARD_CASES])
+def test_cqt2010_backward_parity_small(nb, case):
+    import torch
+    name, sr, fmin, n_bins, bpo, hop, fir, B, L, fmt = case
+    _say(f"cqt2010 backward {name}: sr={sr} bins={n_bins}/{bpo} hop={hop} fir={fir} B={B} L={L} fmt={fmt}")
+    plan = nb.nna_plan_trainable(nb.nna_plan_cqt2010(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo,
+                                                     fir_taps=fir, fmt=fmt, device=0))
+    W0, Y0 = oracle.cqt2010_weights(sr, fmin, n_bins, bpo)
+    rng = np.random.default_rng(11)
+    W, Y = _spectral_weights(nb, plan, rng, perturb=False)
+    assert W.shape == W0.shape and Y.shape == Y0.shape and np.abs(Y - Y0).max() <= 1e-7 * np.abs(Y0).max()
+    W, Y = _spectral_weights(nb, plan, rng)
+    x = _rand(B, L, 12)
+    kw = dict(hop=hop, n_bins=n_bins, bins_per_octave=bpo, fir_taps=fir or oracle.FIR_TAPS, fmt=fmt)
+    ref_out = oracle.cqt2010_bank_forward(x, W, Y, **kw)
+    out = nb.nna_cqt2010(plan, _dev(x)).cpu().numpy()
+    if fmt not in (oracle.PHASE, oracle.LOG):
+        assert _peak_err(out, ref_out) < TOL
+    gout = rng.standard_normal(ref_out.shape).astype(np.float32)
+    ref_gy, ref_gw, ref_gx = oracle.cqt2010_bank_backward(x, W, Y, gout, **kw)
+    need = nb.nna_cqt2010_backward_workspace(plan, B, L)
+    ws = torch.full(((need + 3) // 4,), float("nan"), dtype=torch.float32, device="cuda:0").view(torch.uint8)
+    gy, gw, gx = nb.nna_cqt2010_backward(plan, _dev(x), _dev(gout), workspace=ws)
+    torch.cuda.synchronize()
+    e_y, e_w, e_x = (_peak_err(gy.cpu().numpy(), ref_gy), _peak_err(gw.cpu().numpy(), ref_gw), _peak_err(gx.cpu().numpy(), ref_gx))
+    _say(f"  spectral kernels {e_y:.3e}, bank gradient {e_w:.3e}, waveform gradient {e_x:.3e}")
+    assert e_y < TOL and e_w < TOL and e_x < TOL
+    n1, n2, gx1 = nb.nna_cqt2010_backward(plan, _dev(x), _dev(gout), want_gy=False, want_gw=False)
+    assert n1 is None and n2 is None and _peak_err(gx1.cpu().numpy(), ref_gx) < TOL
+
+
+def test_spectral_backward_refuses_wrong_plans_and_workspaces(nb):
+    import torch
+    plan = nb.nna_plan_cqt1992(sr=8000, hop=64, fmin=220.0, n_bins=30, device=0)
+    x, g = _dev(_rand(2, 5000, 1)), torch.zeros((2, 30, 79), dtype=torch.float32, device="cuda:0")
+    with pytest.raises(nb.NnaError) as ei:   # not made trainable
+        nb.nna_cqt1992_backward(plan, x, g)
+    assert ei.value.status == nb.NNA_ERR_INVALID_ARG
+    nb.nna_plan_trainable(plan)
+    with pytest.raises(nb.NnaError) as ei:   # workspace too small
+        nb.nna_cqt1992_backward(plan, x, g, workspace=torch.empty(1024, dtype=torch.uint8, device="cuda:0"))
+    assert ei.value.status == nb.NNA_ERR_INVALID_ARG
+    with pytest.raises(nb.NnaError) as ei:   # wrong entry point for this kind of plan
+        nb.nna_cqt2010_backward_workspace(plan, 2, 5000)
+    assert ei.value.status == nb.NNA_ERR_INVALID_ARG
+    stft = nb.nna_plan_trainable(nb.nna_plan_stft(n_fft=256, hop=64, device=0))
+    with pytest.raises(nb.NnaError) as ei:   # a plain STFT plan has no spectral kernels
+        nb._check(nb.lib().nna_plan_get_spectral_kernels(stft.handle, x.data_ptr(), None))
     assert ei.value.status == nb.NNA_ERR_INVALID_ARG
 
 
