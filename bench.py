@@ -377,7 +377,32 @@ def main() -> int:
             "mfma_frac": round(alg / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
             "mfma_peak_tflops": PEAK_FP32_MFMA_TFLOPS,
         }
-        del gcq, ws_bw, p_trc
+        del ws_bw, p_trc
+        # backward pass of the downsampling CQT with trainable time-domain kernels (7 octaves sharing the top octave's
+        # kernels; the waveform gradient climbs through the transposed decimation steps); flops as for its forward
+        # pass (nna_plan_info), three times: forward again, kernel gradient, waveform gradient
+        p_trv = nb.nna_plan_trainable(nb.nna_plan_cqt2010v2(sr=sr, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24, device=0))
+        ws_bw = torch.empty(nb.nna_cqt2010v2_backward_workspace(p_trv, B, L), dtype=torch.uint8, device=dev)
+        for _ in range(max(1, args.warmup)):
+            nb.nna_cqt2010v2_backward(p_trv, x5, gcq, workspace=ws_bw)
+        ev = []
+        for _ in range(args.steps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            nb.nna_cqt2010v2_backward(p_trv, x5, gcq, workspace=ws_bw)
+            b.record()
+            ev.append((a, b))
+        torch.cuda.synchronize()
+        ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+        alg = 3 * p_trv.info()["algorithmic_flops_per_frame"] * B * T
+        extras["cqt2010v2_backward"] = {
+            "ms": round(ms, 4),
+            "gsamples_per_s": round(B * L / ms / 1e6, 4),
+            "algorithmic_tflops": round(alg / ms / 1e9, 3),
+            "mfma_frac": round(alg / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+            "mfma_peak_tflops": PEAK_FP32_MFMA_TFLOPS,
+        }
+        del gcq, ws_bw, p_trv
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -557,6 +557,13 @@ static nna_status cqt_backward_core(const nna_plan* plan, const float* x_dev, lo
   if (gx_dev) {
     e = nna::launch_fill_zero(gx_dev, B * L, stream);
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    // The shift-gathering kernel tiles the hop in 128 columns: a hop far below that (the deep octaves of a
+    // downsampling plan) leaves most of every tile empty, and the plain frames x taps product over the zero-padded
+    // row-major bank does less work (multiply-adds per frame: shifts x column tiles x row chunks x 128 x 32
+    // against taps x rows).
+    const double gathered = (double)plan->n_shift * plan->n_ct * plan->n_kc * nna::BW_NT * nna::BW_KC;
+    const double dense = (double)plan->kp * plan->rows_pad;
+    if (plan->hop < nna::BW_NT && 2.0 * dense <= gathered) Q.shift_rng = nullptr;
     e = nna::launch_bw_wave(Q, stream);
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
   }

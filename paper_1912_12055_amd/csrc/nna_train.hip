@@ -61,15 +61,71 @@ __device__ __forceinline__ float firt_u(const FirTParams& P, const float* __rest
   return acc;
 }
 
+// The main image u[p], 0 <= p < L, is two plain filters over g -- u[2 i] with he, u[2 i + 1] with ho, each applied
+// back to front -- computed like the forward step: a workgroup stages the span of g its 2,048 values of i need in
+// LDS (position i + i/8: threads start eight samples apart, stride 9 keeps them on different banks), and a thread
+// produces eight consecutive i of both parities from a window that slides through registers.  The mirror images
+// only reach the samples within a filter length of either end: those few take the direct sums of firt_u.
+constexpr int FT_T = 8;                  // values of i per thread
+constexpr int FT_TILE = 256 * FT_T;      // per workgroup
+constexpr int FT_SPAN_MAX = 2064;        // (largest v0 + n - 1) - (smallest v0) the LDS buffer allows
+__device__ __forceinline__ int ft_pos(int i) { return i + (i >> 3); }
+
+// acc[ii] += sum_v taps[v] w[off + ii + (n - 1 - v)]   (n a multiple of eight)
+__device__ __forceinline__ void ft_stream(float (&acc)[FT_T], const float* __restrict__ wt, int off, const float* __restrict__ taps, int n) {
+  float win[2 * FT_T];
+#pragma unroll
+  for (int i = 0; i < FT_T; ++i) win[i] = wt[ft_pos(off + i)];
+  for (int k0 = 0; k0 < n; k0 += FT_T) {
+#pragma unroll
+    for (int i = 0; i < FT_T; ++i) win[FT_T + i] = wt[ft_pos(off + k0 + FT_T + i)];
+#pragma unroll
+    for (int kk = 0; kk < FT_T; ++kk) {
+      const float tp = taps[n - 1 - (k0 + kk)];
+#pragma unroll
+      for (int i = 0; i < FT_T; ++i) acc[i] += tp * win[i + kk];
+    }
+#pragma unroll
+    for (int i = 0; i < FT_T; ++i) win[i] = win[i + FT_T];
+  }
+}
+
 __global__ __launch_bounds__(256) void fir_transpose_add_kernel(const FirTParams P) {
-  const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (j >= P.L) return;
+  __shared__ float lds[(FT_TILE + FT_SPAN_MAX + 2 * FT_T) * 9 / 8 + 16];
+  const int tid = threadIdx.x;
   const long long b = blockIdx.y;
+  const long long i0 = (long long)blockIdx.x * FT_TILE;
   const float* __restrict__ g = P.g + b * P.Ln;
-  float acc = firt_u(P, g, j);
-  if (j >= 1) acc += firt_u(P, g, -j);
-  if (j <= P.L - 2) acc += firt_u(P, g, 2 * (P.L - 1) - j);
-  P.gx[b * P.L + j] += acc;
+  const int ext_e = P.ve0 + P.ne - 1, ext_o = P.vo0 + P.no - 1;
+  const int emax = ext_e > ext_o ? ext_e : ext_o, vmin = P.ve0 < P.vo0 ? P.ve0 : P.vo0;
+  const int n_l = FT_TILE + (emax - vmin) + FT_T;  // g[i0 - emax + k], k < n_l (zero outside the array)
+  for (int k = tid; k < n_l; k += 256) {
+    const long long idx = i0 - emax + k;
+    lds[ft_pos(k)] = (idx >= 0 && idx < P.Ln) ? g[idx] : 0.f;
+  }
+  __syncthreads();
+  const long long ib = i0 + (long long)FT_T * tid;
+  if (ib >= P.Ln) return;
+  float ue[FT_T], uo[FT_T];
+#pragma unroll
+  for (int i = 0; i < FT_T; ++i) ue[i] = uo[i] = 0.f;
+  // u[2 i] = sum_v he[v] g[i - ve0 - v]: with k = ne - 1 - v the window starts at g[i - ext_e], LDS sample i - i0 + emax - ext_e
+  ft_stream(ue, lds + 9 * tid, emax - ext_e, P.he, P.ne);
+  ft_stream(uo, lds + 9 * tid, emax - ext_o, P.ho, P.no);
+  // the mirror images of samples this close to an end can be non-zero
+  const long long margin = 2LL * (emax > -vmin ? emax : -vmin) + 4;
+  float* __restrict__ out = P.gx + b * P.L;
+#pragma unroll
+  for (int i = 0; i < FT_T; ++i)
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+      const long long p = 2 * (ib + i) + par;
+      if (p >= P.L) continue;
+      float v = par ? uo[i] : ue[i];
+      if (p >= 1 && p <= margin) v += firt_u(P, g, -p);
+      if (p <= P.L - 2 && p >= P.L - 1 - margin) v += firt_u(P, g, 2 * (P.L - 1) - p);
+      out[p] += v;
+    }
 }
 
 // frames [f0, f1) of every row of the blocked G buffer [frame / 32][rows_pad][frame % 32]
@@ -212,7 +268,7 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
     m0 = (long long)(blockIdx.x / n_nt) * BW_MT;
     n0 = (int)(blockIdx.x % n_nt) * BW_NT;
     c_begin = 0;
-    c_end = P.rows_pad / BW_KC;
+    c_end = (2 * P.n_half + BW_KC - 1) / BW_KC;  // row chunks that hold bank rows (the padding rows of G and W are zero)
   }
   if (c_begin >= c_end) return;
   const int alive = SPARSE ? alive_rt : 4;
@@ -898,9 +954,15 @@ hipError_t launch_fill_zero(float* p, long long n, hipStream_t stream) {
 
 hipError_t launch_fir_transpose_add(const FirTParams& p, hipStream_t stream) {
   clear_stale_error();
-  if (p.L < 1 || p.Ln != (p.L + 1) / 2 || p.B < 1 || p.B > 65535 || p.L > 0x3fffffffLL || p.ne < 1 || p.no < 1)
+  if (p.L < 1 || p.Ln != (p.L + 1) / 2 || p.B < 1 || p.B > 65535 || p.L > 0x3fffffffLL || p.ne < FT_T || p.no < FT_T ||
+      p.ne % FT_T || p.no % FT_T)
     return hipErrorInvalidValue;
-  hipLaunchKernelGGL(fir_transpose_add_kernel, dim3((unsigned)((p.L + 255) / 256), (unsigned)p.B), dim3(256), 0, stream, p);
+  const int ext_e = p.ve0 + p.ne - 1, ext_o = p.vo0 + p.no - 1;
+  const int span = (ext_e > ext_o ? ext_e : ext_o) - (p.ve0 < p.vo0 ? p.ve0 : p.vo0);
+  if (span < 0 || span > FT_SPAN_MAX) return hipErrorInvalidValue;
+  const long long tiles = (p.Ln + FT_TILE - 1) / FT_TILE;
+  if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(fir_transpose_add_kernel, dim3((unsigned)tiles, (unsigned)p.B), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 
