@@ -27,7 +27,7 @@ PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix peak
 PEAK_F16_MFMA_TFLOPS = 2500.0  # MI355X dense fp16 / bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
 # the kernel each transform of the step launches (names as rocprofv3 prints them)
-KERNELS = {"stft": "stft_fold_kernel<0, 4>", "mel": "stft_fold_kernel<1, 2>", "cqt": "cqt_kernel<false>"}
+KERNELS = {"stft": "stft_fold_kernel<0, 2, true>", "mel": "stft_fold_kernel<1, 2>", "cqt": "cqt_kernel<false>"}
 
 
 def _read_traffic():
@@ -145,15 +145,18 @@ def main() -> int:
         # STFT and Mel run the folded contraction (x[n] +- x[N-n] against the first halves of the kernels of
         # eq. (DFT2)): N^2 + 2N flop per frame where the direct form needs 2 N^2.  Their roofline numerator is
         # what the kernel executes (the matrix-instruction counter confirms it), never the direct form's count;
-        # that one is quoted beside it as `direct_form_equivalent_tflops`.  The CQT's numerator is the taps
+        # that one is quoted beside it as `direct_form_equivalent_tflops`.  The plain STFT halves once more (the
+        # folded taps summed by parity give bin k and bin N/2 - k from the kernels of k < N/4): N^2 / 2 + 4N.  The CQT's numerator is the taps
         # inside the kernels' own lengths (what it executes is more: the staircase of lengths in a 16-row block).
         folded = exe < alg
+        split = folded and exe < 0.3 * alg  # the plain STFT is split once more by tap parity: N^2 / 2 + 4N
         useful = exe if folded else alg
         per[n] = {
             "ms": round(ms, 4),
             "gsamples_per_s": round(B * L / ms / 1e6, 4),
             "frames_per_s": round(frames / ms * 1e3, 1),
-            "contraction": "folded frame, N^2 + 2N flop per frame" if folded else "direct",
+            "contraction": ("folded frame split by tap parity, N^2 / 2 + 4N flop per frame" if split
+                            else "folded frame, N^2 + 2N flop per frame" if folded else "direct"),
             "algorithmic_tflops": round(useful / ms / 1e9, 3),
             "executed_tflops": round(exe / ms / 1e9, 3),
             "mfma_frac": round(useful / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),

@@ -113,6 +113,20 @@ void build_stft_bank_fold(nna_plan* p) {
   p->wmid = (float)tab.w[N / 2];
   // per frame: N/2 folded taps x all rows of the row tiles, and the N multiply-adds of bin N/2
   p->exec_flops_fold = 2.0 * ((double)p->n_chunks * nj2 * ST_KC) * (double)p->n_rt * ST_ROWS + 2.0 * N;
+  // One more halving for the plain STFT (see nna_kernels_fold.hip): row tiles of the bins below N/4 only -- N/4 must be
+  // a whole number of 64-bin row tiles -- and taps whose parity is that of their position in a fragment (even hop).
+  p->fold_split = p->kind == NNA_KIND_STFT && N % 256 == 0 && p->hop % 2 == 0;
+  if (p->fold_split) {
+    // bin N/4: cos(pi n / 2) = 1, 0, -1, 0, ...; -sin(pi n / 2) = 0, -1, 0, 1, ...
+    const size_t tbl = (size_t)(J + 3) / 4 * 4 * p->hop;
+    p->h_wq.assign(2 * tbl, 0.0f);
+    for (int n = 0; n < N; ++n) {
+      const double w = tab.w[n];
+      p->h_wq[n] = (float)((n & 1) ? 0.0 : (n & 2) ? -w : w);
+      p->h_wq[tbl + n] = (float)((n & 1) ? ((n & 2) ? w : -w) : 0.0);
+    }
+    p->exec_flops_split = 2.0 * ((double)p->n_chunks * nj2 * ST_KC) * (double)(p->n_rt / 2) * ST_ROWS + 4.0 * N;
+  }
 }
 
 // float16 copy of the STFT bank for the half-precision kernel: same packed rows, cut into row

@@ -93,6 +93,14 @@ struct nna_plan {
   float* d_melwf = nullptr;            // Mel weights as the folded kernel's second MFMA reads them
   unsigned char* d_mel_maskf = nullptr;
   bool runs_folded() const { return fold && !d_wrm && precision == 0; }
+  // STFT plans whose n_fft is a multiple of 256 and whose hop is even: the folded contraction split once more by tap
+  // parity (bins below N/4 only; their partners N/2 - k from the same sums).  h_wq / d_wq: the two weight tables of
+  // bin N/4, [2][J rounded up to 4][hop]
+  bool fold_split = false;
+  double exec_flops_split = 0;
+  std::vector<float> h_wq;
+  float* d_wq = nullptr;
+  bool runs_split() const { return runs_folded() && fold_split && kind == NNA_KIND_STFT; }
 
   // host copy of the packed bank (host-only plans keep it; device plans drop it after upload)
   std::vector<float> h_bank;

@@ -28,6 +28,7 @@ constexpr int ST_RG = 4;          // row tiles one STFT workgroup handles (amort
 constexpr int SF_LDS_ROWS = 136;  // LDS rows per tile: 128 frames + (J/2 - 1) overlap rows for each of two waveform segments, J <= 8
 constexpr int ST_RING_FOLD_STFT = 4;  // bank fragment groups in flight per wave
 constexpr int ST_RING_FOLD_MEL = 2;
+constexpr int ST_RING_FOLD_SPLIT = 2;  // the launch split by tap parity: its second set of accumulators takes the registers
 constexpr int ST_LIN_BLOCKS_MAX = 6;  // ST_MODE_LIN: 4 or 6 output blocks per pass (6 when that saves a pass)
 // what the STFT kernel does with a finished row tile
 constexpr int ST_MODE_STFT = 0;   // per-bin epilogue, output written per row tile
@@ -80,6 +81,10 @@ struct StftParams {
   const float* wn;
   float wmid;
   long long main_blocks;
+  // folded launch split once more by tap parity (see nna_kernels_fold.hip): n_rt then covers the bins below N/4 only,
+  // and wn holds two weight tables, for the real and the imaginary part of bin N/4 (the workgroups behind the
+  // contraction's compute that bin; bin N/2 comes out of the contraction)
+  int split;
   float* out;
   int n_rt;             // row tiles
   int n_chunks;         // LDS chunks per row tile

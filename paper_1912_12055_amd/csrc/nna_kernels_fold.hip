@@ -102,9 +102,9 @@ __device__ __forceinline__ float wave_sum(float v) {
 // Bin N/2 of one frame tile: X[N/2] = sum_n (-1)^n w[n] xp[t hop + n], from partial sums over whole hop
 // segments, P[row][q] = sum_{c < hop} wn[q hop + c] xp[sigma(row) hop + c] (wn = (-1)^n w[n]), so that
 // every sample is read once: X_t[N/2] = sum_q P[row(t) + q][q].
-template <int FMT>
-__device__ __forceinline__ void store_nyquist(float* p, float re) { *p = format_power<FMT>(re * re); }
-
+// A launch split by tap parity has bin N/2 in its contraction and leaves out bin N/4 instead (its own partner):
+// X[N/4] = sum_n w[n] (cos(pi n / 2) - i sin(pi n / 2)) xp[t hop + n], two real sums of the same kind, taken one after the
+// other with the weight tables wn[0] (real part) and wn[1] (imaginary part).
 __device__ void nyquist_tile(const StftParams& P, long long ft, float* lds) {
   const FrameGeom& g = P.g;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -125,7 +125,12 @@ __device__ void nyquist_tile(const StftParams& P, long long ft, float* lds) {
   // LDS: the weights [Jp][hop] (read by every row), then the partial sums [rows][Jp]
   float* wl = lds;
   float* ps = lds + Jp * hop;
-  for (int i = tid * 4; i < Jp * hop; i += 1024) *reinterpret_cast<f32x4*>(wl + i) = *reinterpret_cast<const f32x4*>(P.wn + i);
+  float part[2] = {0.f, 0.f};
+  const int n_part = P.split ? 2 : 1;
+  for (int pt = 0; pt < n_part; ++pt) {
+  if (pt) __syncthreads();  // everyone is done with the first table and its partial sums
+  for (int i = tid * 4; i < Jp * hop; i += 1024)
+    *reinterpret_cast<f32x4*>(wl + i) = *reinterpret_cast<const f32x4*>(P.wn + (long long)pt * Jp * hop + i);
   __syncthreads();
   // eight lanes share a row (each four consecutive columns of every 32), a wave eight rows, the workgroup 32 rows
   // per step; the loads of eight column blocks are issued together
@@ -180,19 +185,21 @@ __device__ void nyquist_tile(const StftParams& P, long long ft, float* lds) {
   }
   __syncthreads();
   if (tid < m_valid) {
-    const long long f = f0 + tid;
-    const long long b = f / g.T;
-    const int t = (int)(f - b * g.T);
     const float* src = ps + tm.frame_row(tid) * Jp;
     float re = 0.f;
     for (int q = 0; q < J; ++q) re += src[q * Jp + q];
-    float* op = P.out + (b * P.out_bins + P.n_half) * g.T + t;
-    if (P.fmt == NNA_OUT_MAGNITUDE)
-      store_nyquist<NNA_OUT_MAGNITUDE>(op, re);
-    else if (P.fmt == NNA_OUT_POWER)
-      store_nyquist<NNA_OUT_POWER>(op, re);
-    else
-      store_nyquist<NNA_OUT_LOG>(op, re);
+    part[pt] = re;
+  }
+  }
+  if (tid < m_valid) {
+    const long long f = f0 + tid;
+    const long long b = f / g.T;
+    const int t = (int)(f - b * g.T);
+    const float pw = part[0] * part[0] + part[1] * part[1];
+    float* op = P.out + (b * P.out_bins + (P.split ? P.n_half / 2 : P.n_half)) * g.T + t;
+    *op = P.fmt == NNA_OUT_MAGNITUDE ? format_power<NNA_OUT_MAGNITUDE>(pw)
+          : P.fmt == NNA_OUT_POWER   ? pw
+                                     : format_power<NNA_OUT_LOG>(pw);
   }
 }
 
@@ -222,11 +229,39 @@ __device__ __forceinline__ void fold_store_tile(const f32x16 (&acc)[ST_RB], floa
   }
 }
 
+// The split launch's row tile: bins k = slot_base + .. (from E + O) and their partners N/2 - k (from E - O).  Blocks
+// 0-3 = the even taps' (Re 0-31, Re 32-63, Im 0-31, Im 32-63), blocks 4-7 = the odd taps'.
+template <int FMT>
+__device__ __forceinline__ void fold_store_tile_split(const f32x16 (&acc)[2 * ST_RB], float* __restrict__ op, long long T,
+                                                      int slot_base, int h, int n_half) {
+  float* __restrict__ p = op + (slot_base + 4 * h) * T;
+  float* __restrict__ pm = op + (long long)(n_half - slot_base - 4 * h) * T;
+#pragma unroll
+  for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float re_e = acc[blk][r], im_e = acc[blk + 2][r], re_o = acc[blk + 4][r], im_o = acc[blk + 6][r];
+      const int k = 32 * blk + 8 * (r >> 2) + (r & 3);
+      const float a = re_e + re_o, b = im_e + im_o, c = re_e - re_o, d = im_e - im_o;
+      p[k * T] = format_power<FMT>(a * a + b * b);
+      pm[-k * T] = format_power<FMT>(c * c + d * d);
+    }
+}
+
 // MODE: ST_MODE_STFT (per-bin epilogue) or ST_MODE_MEL (power of the row tile x filterbank slice).
-template <int MODE, int RING>
+// SPLIT (ST_MODE_STFT, N a multiple of 256, even hop): one more halving.  cos(2 pi (N/2 - k) n / N) =
+// (-1)^n cos(2 pi k n / N) and sin(2 pi (N/2 - k) n / N) = -(-1)^n sin(2 pi k n / N), so with the folded taps summed
+// separately by parity -- E over even n, O over odd n -- bin k is E + O and bin N/2 - k is E - O (imaginary part:
+// -(E - O)): only the kernels of the bins below N/4 are multiplied, into two sets of accumulators.  In a fragment of four
+// consecutive taps element e has the parity of e, and both halves of a two-tap MFMA step hold taps of one parity, so
+// the split is a choice of accumulator per MFMA.  The centre tap n = N/2 is even; bin N/4, its own partner, is
+// left to the workgroups behind the contraction's, and bin N/2 = partner of bin 0 needs none.
+template <int MODE, int RING, bool SPLIT = false>
 __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
   static_assert(ST_NKG % RING == 0, "ring depth must divide the fragment groups per LDS row");
+  static_assert(!SPLIT || MODE == ST_MODE_STFT, "the Mel variant has no registers for a second set of accumulators");
   constexpr bool MEL = MODE == ST_MODE_MEL;
+  constexpr int NACC = SPLIT ? 2 * ST_RB : ST_RB;
   constexpr int NPASS = SF_NPASS;
   __shared__ __attribute__((aligned(16))) float lds[2][2][SF_TILE];  // [buffer][S, M]
 
@@ -329,9 +364,9 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
 
   const int groups_per_rt = n_chunks * nj2 * ST_NKG;
 
-  f32x16 acc[ST_RB];
+  f32x16 acc[NACC];
 #pragma unroll
-  for (int rb = 0; rb < ST_RB; ++rb)
+  for (int rb = 0; rb < NACC; ++rb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
 
@@ -429,7 +464,8 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
 #pragma unroll
       for (int m = 0; m < 16; ++m) {
         const int e = m >> 2, rb = m & 3;
-        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][rb][e], rb < 2 ? ev[e] : ov[e], acc[rb], 0, 0, 0);
+        const int ab = SPLIT && (e & 1) ? rb + ST_RB : rb;  // odd taps: the second set
+        acc[ab] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][rb][e], rb < 2 ? ev[e] : ov[e], acc[ab], 0, 0, 0);
         if (TASK != TASK_NONE && (m & 1) && (m >> 1) < NPASS) {
           const int p = m >> 1;
           __builtin_amdgcn_sched_barrier(0);
@@ -489,7 +525,17 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
       for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[blk][r] += (r & 1) ? -xmid : xmid;
-      if constexpr (!MEL) {
+      if constexpr (SPLIT) {
+        if (valid) {
+          float* __restrict__ op = P.out + (b_lane * P.out_bins) * g.T + t_lane;
+          if (P.fmt == NNA_OUT_MAGNITUDE)
+            fold_store_tile_split<NNA_OUT_MAGNITUDE>(acc, op, g.T, slot_base, h, P.n_half);
+          else if (P.fmt == NNA_OUT_POWER)
+            fold_store_tile_split<NNA_OUT_POWER>(acc, op, g.T, slot_base, h, P.n_half);
+          else
+            fold_store_tile_split<NNA_OUT_LOG>(acc, op, g.T, slot_base, h, P.n_half);
+        }
+      } else if constexpr (!MEL) {
         if (valid) {
           float* __restrict__ op = P.out + (b_lane * P.out_bins) * g.T + t_lane;
           if (P.fmt == NNA_OUT_MAGNITUDE)
@@ -530,7 +576,7 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
         }
       }
 #pragma unroll
-      for (int rb = 0; rb < ST_RB; ++rb)
+      for (int rb = 0; rb < NACC; ++rb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[rb][r] = 0.f;
       ++rt;
@@ -568,7 +614,12 @@ hipError_t launch_stft_fold(const StftParams& p, int mode, hipStream_t stream) {
     if (!p.wn || p.main_blocks <= 0) return hipErrorInvalidValue;
     const long long blocks = p.main_blocks + p.n_ft;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((stft_fold_kernel<ST_MODE_STFT, ST_RING_FOLD_STFT>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    if (p.split) {
+      if (p.n_half % 2) return hipErrorInvalidValue;
+      hipLaunchKernelGGL((stft_fold_kernel<ST_MODE_STFT, ST_RING_FOLD_SPLIT, true>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    } else {
+      hipLaunchKernelGGL((stft_fold_kernel<ST_MODE_STFT, ST_RING_FOLD_STFT>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    }
   } else {
     return hipErrorInvalidValue;
   }

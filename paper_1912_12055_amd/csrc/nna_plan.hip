@@ -49,6 +49,7 @@ nna_status finish_plan(nna_plan* p, nna_plan** out, const MelDeviceLayout* mel) 
     if (s == NNA_OK && p->fold) {
       s = upload(&p->d_bankf, p->h_bankf.data(), p->bankf_floats * sizeof(float), "folded kernel bank");
       if (s == NNA_OK) s = upload(&p->d_wn, p->h_wn.data(), p->h_wn.size() * sizeof(float), "alternating window");
+      if (s == NNA_OK && p->fold_split) s = upload(&p->d_wq, p->h_wq.data(), p->h_wq.size() * sizeof(float), "weights of bin N/4");
       if (s == NNA_OK && mel && p->kind == NNA_KIND_MEL) {
         s = upload(&p->d_melwf, mel->fragf.data(), mel->fragf.size() * sizeof(float), "mel weights (folded kernel)");
         if (s == NNA_OK) s = upload(&p->d_mel_maskf, mel->maskf.data(), mel->maskf.size(), "mel mask (folded kernel)");
@@ -723,7 +724,8 @@ nna_status nna_plan_info(const nna_plan* plan, int* kind, long long* bank_rows, 
                                                   : 2LL * (plan->freq_scale ? plan->n_half : plan->n_half + 1);
   if (taps) *taps = plan->K;
   if (out_bins) *out_bins = plan->out_rows();
-  if (executed_flops_per_frame) *executed_flops_per_frame = plan->runs_folded() ? plan->exec_flops_fold : plan->exec_flops;
+  if (executed_flops_per_frame)
+    *executed_flops_per_frame = plan->runs_split() ? plan->exec_flops_split : plan->runs_folded() ? plan->exec_flops_fold : plan->exec_flops;
   if (algorithmic_flops_per_frame) *algorithmic_flops_per_frame = plan->alg_flops;
   return NNA_OK;
 }
@@ -758,6 +760,7 @@ void nna_plan_destroy(nna_plan* plan) {
       (void)hipFree(plan->d_fir_he);
       (void)hipFree(plan->d_fir_ho);
       (void)hipFree(plan->d_wn);
+      (void)hipFree(plan->d_wq);
       (void)hipFree(plan->d_melwf);
       (void)hipFree(plan->d_mel_maskf);
       (void)hipFree(plan->d_bank16s);

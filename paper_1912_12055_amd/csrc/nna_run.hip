@@ -154,8 +154,13 @@ nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long lo
     } else {
       P.out_bins = plan->n_half + 1;
       P.fmt = plan->fmt;
+      if (plan->runs_split()) {  // the bins below N/4 only; bin N/4 from the workgroups behind the contraction's
+        P.split = 1;
+        P.n_rt = plan->n_rt / 2;
+        P.wn = plan->d_wq;
+      }
       const long long ft_per_xcd = (P.n_ft + 7) / 8;
-      P.main_blocks = 8 * ((ft_per_xcd + 63) / 64) * 64 * ((plan->n_rt + nna::ST_RG - 1) / nna::ST_RG);
+      P.main_blocks = 8 * ((ft_per_xcd + 63) / 64) * 64 * ((P.n_rt + nna::ST_RG - 1) / nna::ST_RG);
     }
     DeviceGuard guard;
     hipError_t e = guard.enter(plan->device);
