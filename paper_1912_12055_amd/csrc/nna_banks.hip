@@ -88,6 +88,40 @@ void build_stft_bank_fold(nna_plan* p) {
   if (!p->fold) return;
   const int nj2 = J / 2;
   const long long G = (long long)p->n_chunks * nj2 * ST_NKG;
+  if (p->kind == NNA_KIND_MEL && N % 128 == 0 && p->hop % 2 == 0) {
+    // The Mel launch split by tap parity (see nna_kernels_fold.hip) replaces the plain folded one: row tiles of 32 bins
+    // below N/4, two fragments per group (Re, Im kernels of the tile's bins).
+    p->fold_split = true;
+    p->n_rt_split = N / 128;
+    p->bankf_floats = (size_t)(G * p->n_rt_split + ST_NKG) * 2 * 64 * 4;
+    p->h_bankf.assign(p->bankf_floats, 0.0f);
+    DftTable tab(N, p->window);
+    for (int rt = 0; rt < p->n_rt_split; ++rt)
+      for (int c = 0; c < p->n_chunks; ++c)
+        for (int j = 0; j < nj2; ++j)
+          for (int kg = 0; kg < ST_NKG; ++kg) {
+            const long long g = ((long long)c * nj2 + j) * ST_NKG + kg;
+            for (int rb = 0; rb < 2; ++rb)
+              for (int lane = 0; lane < 64; ++lane) {
+                const int h = lane >> 5, bin = rt * 32 + (lane & 31);
+                float* dst = &p->h_bankf[((((size_t)rt * G + g) * 2 + rb) * 64 + lane) * 4];
+                for (int e = 0; e < 4; ++e) {
+                  const int n = stft_tap(p, c, j, kg, h, e);  // < N/2
+                  dst[e] = (float)(rb == 0 ? tab.re(bin, n) : tab.im(bin, n));
+                }
+              }
+          }
+    const size_t tbl = (size_t)(J + 3) / 4 * 4 * p->hop;
+    p->h_wq.assign(2 * tbl, 0.0f);
+    for (int n = 0; n < N; ++n) {
+      const double w = tab.w[n];
+      p->h_wq[n] = (float)((n & 1) ? 0.0 : (n & 2) ? -w : w);
+      p->h_wq[tbl + n] = (float)((n & 1) ? ((n & 2) ? w : -w) : 0.0);
+    }
+    p->h_wn.assign(4, 0.0f);  // (unused by a split launch)
+    p->wmid = (float)tab.w[N / 2];
+    return;
+  }
   p->bankf_floats = (size_t)(G * p->n_rt + ST_NKG) * ST_RB * 64 * 4;
   p->h_bankf.assign(p->bankf_floats, 0.0f);
   DftTable tab(N, p->window);
@@ -117,6 +151,7 @@ void build_stft_bank_fold(nna_plan* p) {
   // a whole number of 64-bin row tiles -- and taps whose parity is that of their position in a fragment (even hop).
   p->fold_split = p->kind == NNA_KIND_STFT && N % 256 == 0 && p->hop % 2 == 0;
   if (p->fold_split) {
+    p->n_rt_split = p->n_rt / 2;
     // bin N/4: cos(pi n / 2) = 1, 0, -1, 0, ...; -sin(pi n / 2) = 0, -1, 0, 1, ...
     const size_t tbl = (size_t)(J + 3) / 4 * 4 * p->hop;
     p->h_wq.assign(2 * tbl, 0.0f);
@@ -272,7 +307,61 @@ MelDeviceLayout layout_mel(nna_plan* p) {
           }
         }
   }
-  if (p->fold) {
+  if (p->fold && p->fold_split) {
+    // Split form: row tile rt = bins 32 rt .. 32 rt + 31 (block 0) and their partners N/2 - k (block 1); register r
+    // of lane (h, n) holds bin 32 rt + 8 (r/4) + 4 h + r%4 (or its partner).  Bin N/2 is bin 0's partner; bin N/4
+    // belongs to no tile and is weighed in by the kernel's own epilogue.
+    const int n_rts = p->n_rt_split, Nh = p->n_half;
+    out.fragf.assign((size_t)p->n_pass * n_rts * 2 * ST_MEL_BLOCKS * 4 * 64 * 4, 0.0f);
+    out.maskf.assign((size_t)p->n_pass * n_rts * 2, 0);
+    out.pass_rtf.assign((size_t)p->n_pass * 2, 0);
+    out.wq.assign(M, 0.0f);
+    p->mel_q_any = 0;
+    for (int m = 0; m < M; ++m) {
+      out.wq[m] = p->h_melW[(size_t)m * F + Nh / 2];
+      if (out.wq[m] != 0.0f) p->mel_q_any = 1;
+    }
+    double rts = 0;
+    for (int pass = 0; pass < p->n_pass; ++pass) {
+      int lo = n_rts, hi = 0;
+      for (int m = pass * per_pass; m < std::min(M, (pass + 1) * per_pass); ++m)
+        for (int j = 0; j <= Nh; ++j)
+          if (j != Nh / 2 && p->h_melW[(size_t)m * F + j] != 0.0f) {
+            const int t32 = std::min(j, Nh - j) / 32;  // the tile that holds bin j or its partner
+            lo = std::min(lo, t32);
+            hi = std::max(hi, t32 + 1);
+          }
+      if (hi <= lo) {  // no weight outside bin N/4: still visit one tile so that the output gets written
+        lo = 0;
+        hi = 1;
+      }
+      out.pass_rtf[2 * pass] = lo;
+      out.pass_rtf[2 * pass + 1] = hi;
+      rts += hi - lo;
+      for (int rt = lo; rt < hi; ++rt)
+        for (int blk = 0; blk < 2; ++blk)
+          for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb) {
+            bool any = false;
+            for (int v = 0; v < 4; ++v)
+              for (int lane = 0; lane < 64; ++lane)
+                for (int e = 0; e < 4; ++e) {
+                  const int r = 4 * v + e, mel = pass * per_pass + mb * 32 + (lane & 31);
+                  const int k = rt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                  const int bin = blk ? Nh - k : k;
+                  const float w = mel < M ? p->h_melW[(size_t)mel * F + bin] : 0.0f;
+                  out.fragf[((((((size_t)pass * n_rts + rt) * 2 + blk) * ST_MEL_BLOCKS + mb) * 4 + v) * 64 + lane) * 4 + e] = w;
+                  any = any || w != 0.0f;
+                }
+            if (any) {
+              out.maskf[((size_t)pass * n_rts + rt) * 2 + blk] |= (unsigned char)(1u << mb);
+              out.exec_blocks_f += 1;
+            }
+          }
+    }
+    // per frame: N/2 folded taps x the 64 rows of every tile visited, the filterbank blocks, and bin N/4's two sums
+    p->exec_flops_split = 2.0 * ((double)p->n_chunks * (p->nj / 2) * ST_KC) * 64.0 * rts + out.exec_blocks_f * 2.0 * 32 * 32 +
+                          (p->mel_q_any ? 4.0 * p->K * p->n_pass : 0.0);
+  } else if (p->fold) {
     // folded kernel: register r of lane (h, n) in block blk holds bin 64 rt + 32 blk + 8 (r/4) + 4 h + r%4;
     // as the B operand of MFMA number r it meets, in lane (h, m), the weight of mel m for that bin
     out.fragf.assign((size_t)p->n_pass * p->n_rt * 2 * ST_MEL_BLOCKS * 4 * 64 * 4, 0.0f);
@@ -303,7 +392,7 @@ MelDeviceLayout layout_mel(nna_plan* p) {
   for (int pass = 0; pass < p->n_pass; ++pass)
     dft_exec += 2.0 * k_exec * ST_ROWS * (out.pass_rt[2 * pass + 1] - out.pass_rt[2 * pass]);
   p->exec_flops = dft_exec + exec_blocks * 2.0 * 32 * 16;  // 8 MFMA 32x32x2 per block, per frame: 32 mels x 16 slots
-  if (p->fold) {
+  if (p->fold && !p->fold_split) {
     if (p->mel_nyq_any) {
       p->fold = false;  // a filter weighs bin N/2, which the folded contraction does not produce
     } else {

@@ -81,6 +81,10 @@ __device__ __forceinline__ void wait_vm(f32x4& a) {
   asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a) : "n"(N));
 }
 template <int N>
+__device__ __forceinline__ void wait_vm(f32x4& a, f32x4& b) {
+  asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+}
+template <int N>
 __device__ __forceinline__ void wait_vm(f32x4& a, f32x4& b, f32x4& c, f32x4& d) {
   asm volatile("s_waitcnt vmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
 }

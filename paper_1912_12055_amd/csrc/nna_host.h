@@ -100,7 +100,12 @@ struct nna_plan {
   double exec_flops_split = 0;
   std::vector<float> h_wq;
   float* d_wq = nullptr;
-  bool runs_split() const { return runs_folded() && fold_split && kind == NNA_KIND_STFT; }
+  bool runs_split() const { return runs_folded() && fold_split; }
+  // Mel plans that run split: the split kernel's own pass table, the filters' weights on bin N/4 (all zero: mel_q_any = 0)
+  int* d_mel_pass_rtf = nullptr;
+  float* d_mel_wq = nullptr;
+  int mel_q_any = 0;
+  int n_rt_split = 0;  // row tiles of the split launch (STFT: 64 bins each, Mel: 32)
 
   // host copy of the packed bank (host-only plans keep it; device plans drop it after upload)
   std::vector<float> h_bank;
@@ -248,6 +253,10 @@ struct MelDeviceLayout {
   std::vector<unsigned char> mask;  // [pass][rt][rb]
   std::vector<float> wnyq;          // [n_mels]
   std::vector<int> pass_rt;         // [pass][2]
+  // split form of the folded kernel (32-bin row tiles, blk 0 = the tile's bins, blk 1 = their partners N/2 - k): fragf /
+  // maskf in that layout, the row tile range of every pass, the filters' weights on bin N/4
+  std::vector<int> pass_rtf;        // [pass][2]
+  std::vector<float> wq;            // [n_mels]
 };
 
 // index of (pass, row tile, row block, out block, quad v, lane, element e) in the fragment array of

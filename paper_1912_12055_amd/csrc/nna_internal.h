@@ -28,6 +28,7 @@ constexpr int ST_RG = 4;          // row tiles one STFT workgroup handles (amort
 constexpr int SF_LDS_ROWS = 136;  // LDS rows per tile: 128 frames + (J/2 - 1) overlap rows for each of two waveform segments, J <= 8
 constexpr int ST_RING_FOLD_STFT = 4;  // bank fragment groups in flight per wave
 constexpr int ST_RING_FOLD_MEL = 2;
+constexpr int ST_RING_FOLD_MELSPLIT = 4;  // two fragments per group: four groups in flight are as many registers as the Mel ring's
 constexpr int ST_RING_FOLD_SPLIT = 2;  // the launch split by tap parity: its second set of accumulators takes the registers
 constexpr int ST_LIN_BLOCKS_MAX = 6;  // ST_MODE_LIN: 4 or 6 output blocks per pass (6 when that saves a pass)
 // what the STFT kernel does with a finished row tile

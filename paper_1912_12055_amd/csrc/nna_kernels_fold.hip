@@ -105,14 +105,16 @@ __device__ __forceinline__ float wave_sum(float v) {
 // A launch split by tap parity has bin N/2 in its contraction and leaves out bin N/4 instead (its own partner):
 // X[N/4] = sum_n w[n] (cos(pi n / 2) - i sin(pi n / 2)) xp[t hop + n], two real sums of the same kind, taken one after the
 // other with the weight tables wn[0] (real part) and wn[1] (imaginary part).
-__device__ void nyquist_tile(const StftParams& P, long long ft, float* lds) {
+// Power of that bin for frame f0 + tid of frame tile ft (threads tid < the tile's frames; 0 elsewhere).  Every
+// thread of the workgroup must call it; `lds` is used from its start.
+__device__ float extra_bin_power(const StftParams& P, long long ft, float* lds) {
   const FrameGeom& g = P.g;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int J = 2 * P.nj;  // P.nj holds J/2 for a folded launch
   const int Jp = (J + 3) & ~3;  // the segments' weights go four at a time (the table is zero padded)
   const int hop = g.hop;
   const long long f0 = ft * P.tile_frames;
-  if (f0 >= g.n_frames) return;
+  if (f0 >= g.n_frames) return 0.f;  // (the whole workgroup)
   const int m_valid = (int)((g.n_frames - f0) < P.tile_frames ? (g.n_frames - f0) : P.tile_frames);
   TileMap tm;
   tm.T = g.T;
@@ -191,11 +193,20 @@ __device__ void nyquist_tile(const StftParams& P, long long ft, float* lds) {
     part[pt] = re;
   }
   }
+  return part[0] * part[0] + part[1] * part[1];
+}
+
+__device__ void nyquist_tile(const StftParams& P, long long ft, float* lds) {
+  const FrameGeom& g = P.g;
+  const int tid = threadIdx.x;
+  const long long f0 = ft * P.tile_frames;
+  if (f0 >= g.n_frames) return;
+  const int m_valid = (int)((g.n_frames - f0) < P.tile_frames ? (g.n_frames - f0) : P.tile_frames);
+  const float pw = extra_bin_power(P, ft, lds);
   if (tid < m_valid) {
     const long long f = f0 + tid;
     const long long b = f / g.T;
     const int t = (int)(f - b * g.T);
-    const float pw = part[0] * part[0] + part[1] * part[1];
     float* op = P.out + (b * P.out_bins + (P.split ? P.n_half / 2 : P.n_half)) * g.T + t;
     *op = P.fmt == NNA_OUT_MAGNITUDE ? format_power<NNA_OUT_MAGNITUDE>(pw)
           : P.fmt == NNA_OUT_POWER   ? pw
@@ -256,12 +267,17 @@ __device__ __forceinline__ void fold_store_tile_split(const f32x16 (&acc)[2 * ST
 // consecutive taps element e has the parity of e, and both halves of a two-tap MFMA step hold taps of one parity, so
 // the split is a choice of accumulator per MFMA.  The centre tap n = N/2 is even; bin N/4, its own partner, is
 // left to the workgroups behind the contraction's, and bin N/2 = partner of bin 0 needs none.
+// The Mel variant has no registers for eight accumulator blocks beside the filterbank's four.  Its split form works
+// on row tiles of 32 bins instead: two bank fragments per group (Re, Im of bins 0-31 of the tile) into four blocks
+// (even taps: Re, Im; odd taps: Re, Im); the power of the 32 bins and of their 32 partners then meets the filterbank
+// slices of both.  Bin N/4 is computed by the workgroup itself after its sweep (extra_bin_power) and weighed in.
 template <int MODE, int RING, bool SPLIT = false>
 __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
   static_assert(ST_NKG % RING == 0, "ring depth must divide the fragment groups per LDS row");
-  static_assert(!SPLIT || MODE == ST_MODE_STFT, "the Mel variant has no registers for a second set of accumulators");
   constexpr bool MEL = MODE == ST_MODE_MEL;
-  constexpr int NACC = SPLIT ? 2 * ST_RB : ST_RB;
+  constexpr int FR = MEL && SPLIT ? 2 : ST_RB;          // bank fragments per group
+  constexpr int NACC = SPLIT ? (MEL ? 4 : 2 * ST_RB) : ST_RB;
+  constexpr int TILE_BINS = MEL && SPLIT ? 32 : ST_ROWS / 2;
   constexpr int NPASS = SF_NPASS;
   __shared__ __attribute__((aligned(16))) float lds[2][2][SF_TILE];  // [buffer][S, M]
 
@@ -396,24 +412,26 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
   }
 
   const unsigned lane_off = (unsigned)lane * 16u;
-  const char* bank_s = reinterpret_cast<const char*>(P.bankf) + ((long long)rt_begin * groups_per_rt) * (ST_RB * 64 * 16);
-  f32x4 bq[RING][ST_RB];
+  const char* bank_s = reinterpret_cast<const char*>(P.bankf) + ((long long)rt_begin * groups_per_rt) * (FR * 64 * 16);
+  f32x4 bq[RING][FR];
 #pragma unroll
   for (int s = 0; s < RING; ++s) {
     gload16_s<0>(bq[s][0], lane_off, bank_s);
     gload16_s<1024>(bq[s][1], lane_off, bank_s);
-    gload16_s<2048>(bq[s][2], lane_off, bank_s);
-    gload16_s<3072>(bq[s][3], lane_off, bank_s);
-    bank_s += ST_RB * 64 * 16;
+    if constexpr (FR == 4) {
+      gload16_s<2048>(bq[s][2], lane_off, bank_s);
+      gload16_s<3072>(bq[s][3], lane_off, bank_s);
+    }
+    bank_s += FR * 64 * 16;
   }
   __syncthreads();
 
   // Loads retire in order.  When a group starts, the requests younger than its own ring slot are at least
   // the other RING-1 slots (tile requests in between only make the wait stricter).  A tile is requested
   // during one group and written three groups later: the three groups in between each re-request one ring
-  // slot (ST_RB loads), so at least 3 ST_RB requests are younger than the tile's.
-  constexpr int W_SLOT = (RING - 1) * ST_RB;
-  constexpr int W_TILE = 3 * ST_RB;
+  // slot (FR loads), so at least 3 FR requests are younger than the tile's.
+  constexpr int W_SLOT = (RING - 1) * FR;
+  constexpr int W_TILE = 3 * FR;
   constexpr int TASK_NONE = 0, TASK_LOAD_S = 1, TASK_STORE_S = 2, TASK_LOAD_M = 3, TASK_STORE_M = 4;
   const int stage_off = (tid / (ST_KC / 4)) * ST_PITCH + (tid % (ST_KC / 4)) * 4;
   const bool last_pass_row = tid / (ST_KC / 4) < SF_LDS_ROWS - (NPASS - 1) * SF_RPP;  // the partial fifth pass
@@ -459,15 +477,19 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
         wait_vm<W_TILE>(R);
         if (fx.cls == 2) sf_store_chunk(R, fx, nxt + (M_ ? SF_TILE : 0), tid);
       }
-      wait_vm<W_SLOT>(bq[s][0], bq[s][1], bq[s][2], bq[s][3]);
+      if constexpr (FR == 4)
+        wait_vm<W_SLOT>(bq[s][0], bq[s][1], bq[s][2], bq[s][3]);
+      else
+        wait_vm<W_SLOT>(bq[s][0], bq[s][1]);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int m = 0; m < 16; ++m) {
-        const int e = m >> 2, rb = m & 3;
-        const int ab = SPLIT && (e & 1) ? rb + ST_RB : rb;  // odd taps: the second set
-        acc[ab] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][rb][e], rb < 2 ? ev[e] : ov[e], acc[ab], 0, 0, 0);
-        if (TASK != TASK_NONE && (m & 1) && (m >> 1) < NPASS) {
-          const int p = m >> 1;
+      for (int m = 0; m < 4 * FR; ++m) {
+        const int e = m / FR, rb = m % FR;
+        const int ab = SPLIT && (e & 1) ? rb + FR : rb;  // odd taps: the second set
+        acc[ab] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][rb][e], rb < FR / 2 ? ev[e] : ov[e], acc[ab], 0, 0, 0);
+        // a staging task's NPASS steps go one behind every other MFMA (behind each of the first NPASS, where a group has eight)
+        if (TASK != TASK_NONE && (FR == 4 ? (m & 1) && (m >> 1) < NPASS : m < NPASS)) {
+          const int p = FR == 4 ? m >> 1 : m;
           __builtin_amdgcn_sched_barrier(0);
           if constexpr (TASK == TASK_STORE_S || TASK == TASK_STORE_M) {
             if (fx.cls != 2 && (p < NPASS - 1 || last_pass_row))
@@ -477,18 +499,20 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
           }
           __builtin_amdgcn_sched_barrier(0);
         }
-        if (m >= 12) {
+        if (m >= 3 * FR) {
           // this MFMA was the last reader of fragment quad rb: re-request it (the group RING ahead; the
           // bank allocation is padded by ST_NKG groups, so the tail stays in bounds)
           __builtin_amdgcn_sched_barrier(0);
           if (rb == 0) gload16_s<0>(bq[s][0], lane_off, bank_s);
           if (rb == 1) gload16_s<1024>(bq[s][1], lane_off, bank_s);
-          if (rb == 2) gload16_s<2048>(bq[s][2], lane_off, bank_s);
-          if (rb == 3) gload16_s<3072>(bq[s][3], lane_off, bank_s);
+          if constexpr (FR == 4) {
+            if (rb == 2) gload16_s<2048>(bq[s][2], lane_off, bank_s);
+            if (rb == 3) gload16_s<3072>(bq[s][3], lane_off, bank_s);
+          }
           __builtin_amdgcn_sched_barrier(0);
         }
       }
-      bank_s += ST_RB * 64 * 16;
+      bank_s += FR * 64 * 16;
       s_cur = s_nxt;
       m_cur = m_nxt;
     };
@@ -519,13 +543,13 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
     if (++c == n_chunks) {
       // ---- epilogue of row tile rt ---------------------------------------------------
       c = 0;
-      const int slot_base = rt * (ST_ROWS / 2);
+      const int slot_base = rt * TILE_BINS;
       // the centre tap: Re X[k] += (-1)^k w[N/2] x[N/2]; the parity of a register's bin is that of its index
 #pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
+      for (int blk = 0; blk < FR / 2; ++blk)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[blk][r] += (r & 1) ? -xmid : xmid;
-      if constexpr (SPLIT) {
+      if constexpr (SPLIT && !MEL) {
         if (valid) {
           float* __restrict__ op = P.out + (b_lane * P.out_bins) * g.T + t_lane;
           if (P.fmt == NNA_OUT_MAGNITUDE)
@@ -548,6 +572,7 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
       } else {
         // the power (or magnitude) of block blk's 32 bins sits in 16 registers that are, as they stand, the B
         // operands of 16 MFMAs against the filterbank slice: lane (h, m) supplies W[mel m][bin of (r, h)]
+        // (split form: "block" 0 = the tile's 32 bins, from E + O; block 1 = their partners N/2 - k, from E - O)
         const unsigned char* __restrict__ maskp = P.mel_mask + ((long long)pass * P.n_rt + rt) * 2;
         const float4* __restrict__ wp = P.melw + (((long long)pass * P.n_rt + rt) * 2) * (ST_MEL_BLOCKS * 4 * 64) + lane;
 #pragma unroll
@@ -555,7 +580,14 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
           float pw[16];
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const float re = acc[blk][r], im = acc[blk + 2][r];
+            float re, im;
+            if constexpr (SPLIT) {
+              re = blk ? acc[0][r] - acc[2][r] : acc[0][r] + acc[2][r];
+              im = blk ? acc[1][r] - acc[3][r] : acc[1][r] + acc[3][r];
+            } else {
+              re = acc[blk][r];
+              im = acc[blk + 2][r];
+            }
             const float v = re * re + im * im;
             pw[r] = P.fmt == 1 ? __builtin_amdgcn_sqrtf(v) : v;
           }
@@ -588,16 +620,37 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
   // stay reserved until the data has landed.
   wait_vm<0>(R);
 #pragma unroll
-  for (int s = 0; s < RING; ++s) wait_vm<0>(bq[s][0], bq[s][1], bq[s][2], bq[s][3]);
+  for (int s = 0; s < RING; ++s) {
+    if constexpr (FR == 4)
+      wait_vm<0>(bq[s][0], bq[s][1], bq[s][2], bq[s][3]);
+    else
+      wait_vm<0>(bq[s][0], bq[s][1]);
+  }
 
   if constexpr (MEL) {
+    float pq = 0.f;  // power (or magnitude) of bin N/4 of this lane's frame, where a filter of the pass weighs it
+    if constexpr (SPLIT) {
+      if (P.mel_nyq_any) {  // (uniform over the launch)
+        __syncthreads();    // every wave is done with the tiles: LDS is free
+        float* fl = &lds[0][0][0];
+        const float v = extra_bin_power(P, ft, fl);
+        __syncthreads();
+        if (tid < P.tile_frames) fl[tid] = P.fmt == 1 ? __builtin_amdgcn_sqrtf(v) : v;
+        __syncthreads();
+        pq = fl[fi_lane];
+      }
+    }
     float* __restrict__ op = P.out + (b_lane * P.n_mels) * g.T + t_lane;
 #pragma unroll
     for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int mel = pass * (32 * ST_MEL_BLOCKS) + mb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-        if (valid && mel < P.n_mels) op[(long long)mel * g.T] = macc[mb][r];
+        if (valid && mel < P.n_mels) {
+          float v = macc[mb][r];
+          if (SPLIT && P.mel_nyq_any) v += P.mel_wnyq[mel] * pq;
+          op[(long long)mel * g.T] = v;
+        }
       }
     }
   }
@@ -609,7 +662,12 @@ hipError_t launch_stft_fold(const StftParams& p, int mode, hipStream_t stream) {
   if (mode == ST_MODE_MEL) {
     const long long blocks = p.n_ft * p.n_pass;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((stft_fold_kernel<ST_MODE_MEL, ST_RING_FOLD_MEL>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    if (p.split) {
+      if (p.n_half % 2 || (p.mel_nyq_any && (!p.wn || !p.mel_wnyq))) return hipErrorInvalidValue;
+      hipLaunchKernelGGL((stft_fold_kernel<ST_MODE_MEL, ST_RING_FOLD_MELSPLIT, true>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    } else {
+      hipLaunchKernelGGL((stft_fold_kernel<ST_MODE_MEL, ST_RING_FOLD_MEL>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    }
   } else if (mode == ST_MODE_STFT) {
     if (!p.wn || p.main_blocks <= 0) return hipErrorInvalidValue;
     const long long blocks = p.main_blocks + p.n_ft;

@@ -151,12 +151,20 @@ nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long lo
       P.mel_pass_rt = plan->d_mel_pass_rt;
       P.n_mels = plan->n_mels;
       P.n_pass = plan->n_pass;
+      if (plan->runs_split()) {  // 32-bin row tiles below N/4, their own pass table; bin N/4 weighed in at the end
+        P.split = 1;
+        P.n_rt = plan->n_rt_split;
+        P.mel_pass_rt = plan->d_mel_pass_rtf;
+        P.wn = plan->d_wq;
+        P.mel_wnyq = plan->d_mel_wq;
+        P.mel_nyq_any = plan->mel_q_any;
+      }
     } else {
       P.out_bins = plan->n_half + 1;
       P.fmt = plan->fmt;
       if (plan->runs_split()) {  // the bins below N/4 only; bin N/4 from the workgroups behind the contraction's
         P.split = 1;
-        P.n_rt = plan->n_rt / 2;
+        P.n_rt = plan->n_rt_split;
         P.wn = plan->d_wq;
       }
       const long long ft_per_xcd = (P.n_ft + 7) / 8;
