@@ -75,6 +75,10 @@ STFT_CASES = [
     ("log output", 2, 9000, 256, 64, 0, True, 2),
     ("Hamming window", 2, 9000, 256, 64, 2, True, 0),
     ("Blackman window, power", 3, 12000, 512, 128, 3, True, 1),
+    # n_fft a multiple of 128 but not of 256: folded once, not split by tap parity (the plan's executed flops say which)
+    ("folded once: n_fft 384, six shifts", 3, 9000, 384, 64, 0, True, 0),
+    ("split: three row tiles below N/4, hop 96", 3, 9000, 768, 96, 0, True, 1),
+    ("split: Hamming window (w[0] != 0), no centring", 2, 9000, 512, 64, 2, False, 0),
 ]
 
 
@@ -260,6 +264,11 @@ MEL_CASES = [
     ("200 mels (two passes)", 2, 20000, 22050, 2048, 512, 200, 30.0, 9000.0, 0, True, 2.0),
     ("fig. 2 set-up", 1, 1000, 1000, 128, 32, 4, 0.0, 500.0, 1, False, 2.0),
     ("hop does not divide n_fft", 2, 8000, 16000, 400, 160, 64, 0.0, 0.0, 0, True, 2.0),
+    # the launch split by tap parity: row tiles of 32 bins below N/4, filters met through bins and through partners
+    ("split: n_fft 384 (three row tiles), six shifts", 3, 9000, 16000, 384, 64, 30, 0.0, 0.0, 0, True, 2.0),
+    ("split: filters below bin N/4 only", 2, 9000, 16000, 512, 128, 24, 50.0, 1500.0, 0, True, 2.0),
+    ("split: filters above bin N/4 only (partners)", 2, 9000, 16000, 512, 128, 24, 5000.0, 8000.0, 1, True, 1.0),
+    ("split: 300 mels in three band-limited passes, n_fft 4096", 2, 30000, 44100, 4096, 512, 300, 0.0, 0.0, 0, True, 2.0),
 ]
 
 
