@@ -227,21 +227,27 @@ nna_status nna_out_shape(const nna_plan* plan, long long B, long long L, long lo
  * A plan from nna_plan_stft (magnitude, power or log output, not made trainable) whose hop divides n_fft an
  * even number of times >= 4 and is a multiple of 32 is computed from the folded frame: the windows of Sec.
  * III-A satisfy w[n] = w[N-n], so eq. (DFT2)'s real kernels meet x[n] + x[N-n] and its imaginary kernels
- * x[n] - x[N-n] over n < N/2 only -- half the multiply-adds, the same result to rounding.  Every other
- * plan runs eq. (DFT2) as it stands. */
+ * x[n] - x[N-n] over n < N/2 only -- half the multiply-adds, the same result to rounding.  Where n_fft is also a
+ * multiple of 256 the folded taps are summed by parity, E over even n and O over odd n: cos(2 pi (N/2 - k) n / N) =
+ * (-1)^n cos(2 pi k n / N) (and -(-1)^n for the sine), so bin k is E + O and bin N/2 - k is E - O and only the kernels of
+ * the bins below N/4 are multiplied -- a quarter of the direct form's multiply-adds.  Every other plan runs eq. (DFT2)
+ * as it stands. */
 nna_status nna_stft(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
                     void* hip_stream);
 
 /* out_dev[B, n_mels, T] = Mel spectrogram of x_dev[B, L]; plan from nna_plan_mel.
- * The STFT itself is never written to memory.  Folded frames as for nna_stft, unless a filter has weight on
- * bin n_fft/2 or the plan was made trainable. */
+ * The STFT itself is never written to memory.  Folded frames, split by tap parity where n_fft is a multiple of 128, as
+ * for nna_stft, unless the plan was made trainable (a plan that is folded but not split also runs the direct form when
+ * a filter has weight on bin n_fft/2). */
 nna_status nna_mel(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,
                    void* hip_stream);
 
 /* nna_mel that also hands out the spectrogram its filterbank is applied to (Fig. 3: the STFT layer's
  * output feeding the Mel layer), from the one contraction: mel_dev[B, n_mels, T] as nna_mel writes it and
  * spec_dev[B, n_fft/2+1, T] = |X|^power (power 2: the power spectrogram; power 1: the magnitude).  For a
- * caller that wants both, this is one kernel launch of nna_mel's cost plus the spectrogram's stores.
+ * caller that wants both, this is one kernel launch of nna_mel's cost plus the spectrogram's stores (the first pass
+ * of a plan with more than 128 filters then sweeps every bin; a plan that does not run split by tap parity takes the
+ * direct contraction for this call).
  * Plan from nna_plan_mel (float32); errors as nna_mel, NNA_ERR_INVALID_ARG for a NULL spec_dev. */
 nna_status nna_mel_with_stft(const nna_plan* plan, const float* x_dev, long long B, long long L,
                              float* mel_dev, float* spec_dev, void* hip_stream);

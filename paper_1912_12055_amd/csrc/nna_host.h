@@ -103,6 +103,7 @@ struct nna_plan {
   bool runs_split() const { return runs_folded() && fold_split; }
   // Mel plans that run split: the split kernel's own pass table, the filters' weights on bin N/4 (all zero: mel_q_any = 0)
   int* d_mel_pass_rtf = nullptr;
+  int* d_mel_pass_rtf_spec = nullptr;  // the same with the first pass sweeping every tile (nna_mel_with_stft)
   float* d_mel_wq = nullptr;
   int mel_q_any = 0;
   int n_rt_split = 0;  // row tiles of the split launch (STFT: 64 bins each, Mel: 32)

@@ -591,6 +591,17 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
             const float v = re * re + im * im;
             pw[r] = P.fmt == 1 ? __builtin_amdgcn_sqrtf(v) : v;
           }
+          if constexpr (SPLIT) {
+            // the spectrogram the filterbank sees, where the caller wants it too (first pass only: it sweeps every tile then)
+            if (P.pout && pass == 0 && valid) {
+              float* __restrict__ sp = P.pout + (b_lane * (P.n_half + 1)) * g.T + t_lane;
+#pragma unroll
+              for (int r = 0; r < 16; ++r) {
+                const int k = slot_base + 8 * (r >> 2) + 4 * h + (r & 3);
+                sp[(long long)(blk ? P.n_half - k : k) * g.T] = pw[r];
+              }
+            }
+          }
           const unsigned mask = maskp[blk];
 #pragma unroll
           for (int mb = 0; mb < ST_MEL_BLOCKS; ++mb) {
@@ -630,14 +641,16 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
   if constexpr (MEL) {
     float pq = 0.f;  // power (or magnitude) of bin N/4 of this lane's frame, where a filter of the pass weighs it
     if constexpr (SPLIT) {
-      if (P.mel_nyq_any) {  // (uniform over the launch)
-        __syncthreads();    // every wave is done with the tiles: LDS is free
+      const bool spec = P.pout && pass == 0;
+      if (P.mel_nyq_any || spec) {  // (uniform over the workgroup)
+        __syncthreads();            // every wave is done with the tiles: LDS is free
         float* fl = &lds[0][0][0];
         const float v = extra_bin_power(P, ft, fl);
         __syncthreads();
         if (tid < P.tile_frames) fl[tid] = P.fmt == 1 ? __builtin_amdgcn_sqrtf(v) : v;
         __syncthreads();
         pq = fl[fi_lane];
+        if (spec && valid && h == 0) P.pout[(b_lane * (P.n_half + 1) + P.n_half / 2) * g.T + t_lane] = pq;
       }
     }
     float* __restrict__ op = P.out + (b_lane * P.n_mels) * g.T + t_lane;
@@ -663,7 +676,7 @@ hipError_t launch_stft_fold(const StftParams& p, int mode, hipStream_t stream) {
     const long long blocks = p.n_ft * p.n_pass;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     if (p.split) {
-      if (p.n_half % 2 || (p.mel_nyq_any && (!p.wn || !p.mel_wnyq))) return hipErrorInvalidValue;
+      if (p.n_half % 2 || (p.mel_nyq_any && (!p.wn || !p.mel_wnyq)) || (p.pout && !p.wn)) return hipErrorInvalidValue;
       hipLaunchKernelGGL((stft_fold_kernel<ST_MODE_MEL, ST_RING_FOLD_MELSPLIT, true>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
     } else {
       hipLaunchKernelGGL((stft_fold_kernel<ST_MODE_MEL, ST_RING_FOLD_MEL>), dim3((unsigned)blocks), dim3(256), 0, stream, p);

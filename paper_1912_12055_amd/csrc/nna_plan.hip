@@ -55,6 +55,12 @@ nna_status finish_plan(nna_plan* p, nna_plan** out, const MelDeviceLayout* mel) 
         if (s == NNA_OK) s = upload(&p->d_mel_maskf, mel->maskf.data(), mel->maskf.size(), "mel mask (folded kernel)");
         if (s == NNA_OK && p->fold_split) {
           s = upload(&p->d_mel_pass_rtf, mel->pass_rtf.data(), mel->pass_rtf.size() * sizeof(int), "mel pass table (folded kernel)");
+          if (s == NNA_OK) {
+            std::vector<int> spec = mel->pass_rtf;
+            spec[0] = 0;
+            spec[1] = p->n_rt_split;
+            s = upload(&p->d_mel_pass_rtf_spec, spec.data(), spec.size() * sizeof(int), "mel pass table (folded kernel)");
+          }
           if (s == NNA_OK) s = upload(&p->d_mel_wq, mel->wq.data(), mel->wq.size() * sizeof(float), "mel weights of bin N/4");
         }
       }
@@ -766,6 +772,7 @@ void nna_plan_destroy(nna_plan* plan) {
       (void)hipFree(plan->d_wn);
       (void)hipFree(plan->d_wq);
       (void)hipFree(plan->d_mel_pass_rtf);
+      (void)hipFree(plan->d_mel_pass_rtf_spec);
       (void)hipFree(plan->d_mel_wq);
       (void)hipFree(plan->d_melwf);
       (void)hipFree(plan->d_mel_maskf);

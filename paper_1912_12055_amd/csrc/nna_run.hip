@@ -126,7 +126,8 @@ nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long lo
   // the waveforms a tile can span must lie within 2^31 bytes (else the direct kernel runs).
   const int fold_M = plan->runs_folded() ? pick_tile_frames(ST_FRAMES, T, plan->nj / 2 - 1, nna::SF_LDS_ROWS) : 0;
   const bool fold_fits = fold_M >= 1 && (1 + (fold_M - 1 + T - 1) / T) * L <= (1LL << 29);
-  if (fold_fits && !spec_out && (kind == NNA_KIND_STFT || kind == NNA_KIND_MEL)) {
+  // (the Mel launch split by tap parity can write the spectrogram it forms on the way; the once-folded one cannot)
+  if (fold_fits && (!spec_out || (kind == NNA_KIND_MEL && plan->runs_split())) && (kind == NNA_KIND_STFT || kind == NNA_KIND_MEL)) {
     const int nj2 = plan->nj / 2;
     const int M = fold_M;
     nna::StftParams P;
@@ -158,6 +159,10 @@ nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long lo
         P.wn = plan->d_wq;
         P.mel_wnyq = plan->d_mel_wq;
         P.mel_nyq_any = plan->mel_q_any;
+        if (spec_out) {
+          P.pout = spec_out;
+          P.mel_pass_rt = plan->d_mel_pass_rtf_spec;
+        }
       }
     } else {
       P.out_bins = plan->n_half + 1;
