@@ -32,6 +32,7 @@
 #include "nna_device.h"
 
 #include <algorithm>
+#include <type_traits>
 
 namespace nna {
 
@@ -271,107 +272,7 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
     c_end = (2 * P.n_half + BW_KC - 1) / BW_KC;  // row chunks that hold bank rows (the padding rows of G and W are zero)
   }
   if (c_begin >= c_end) return;
-  const int alive = SPARSE ? alive_rt : 4;
-
   const FrameGeom& g = P.g;
-  f32x4 ra[4], rb[4];
-  TileFix<4> fx;
-
-  // Bank gradient: this thread stages taps n0 + 4 (tid % 32) .. + 3 of frame (chunk start) + tid/32 + 8 p,
-  // p = 0..3.  The frames' (waveform, frame-in-waveform) pairs are stepped from chunk to chunk
-  // (BW_KC frames on) instead of being divided out every time.
-  long long fb[4];
-  int ft[4];
-  bool fast = false;                        // how the chunk now in rb goes to LDS
-  const bool long_waves = g.T >= BW_KC;     // a step of BW_KC frames crosses at most one waveform boundary
-  if constexpr (MODE == BW_MODE_BANK) {
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const long long f = c_begin * BW_KC + (tid >> 5) + 8 * p;
-      fb[p] = f / g.T;
-      ft[p] = (int)(f - fb[p] * g.T);
-    }
-  }
-
-  // global -> registers for contraction chunk c
-  auto fetch = [&](long long c) {
-    if constexpr (MODE == BW_MODE_BANK) {
-      // A: G[m0 + row][32 c + 4 c4], row = tid/8 + 32 p: the tile is one contiguous run of frame block c
-      const float* ap = P.gbuf + c * ((long long)P.rows_pad * 32) + (m0 + (tid >> 3)) * 32 + 4 * (tid & 7);
-#pragma unroll
-      for (int p = 0; p < 4; ++p)
-        if (p < alive) ra[p] = *reinterpret_cast<const f32x4*>(ap + 32 * 32 * p);  // pass p = row block p
-      // B: taps n0.. of the 32 frames f0.., gathered from the mirrored waveforms (one LDS row per frame)
-      // Almost every window lies inside its waveform: then the four samples are loaded as they are
-      // stored.  Only a wave that touches a mirrored edge takes the forward kernels' general loader.
-      RowDesc<4> rd;
-      bool interior = true;
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const bool ok = fb[p] < g.B;  // frames past the last one read a dummy window: their G is zero
-        rd.xb[p] = ok ? g.x + fb[p] * g.L : g.x;
-        rd.i0[p] = ok ? ft[p] * g.hop + 4 * (tid & 31) - g.pad + n0 : 0;
-        interior = interior && (unsigned)rd.i0[p] <= (unsigned)((int)g.L - 4);
-        ft[p] += BW_KC;  // on to the next chunk
-        if (long_waves) {
-          const bool wrap = ft[p] >= g.T;
-          ft[p] -= wrap ? g.T : 0;
-          fb[p] += wrap ? 1 : 0;
-        } else {
-          while (ft[p] >= g.T) {
-            ft[p] -= g.T;
-            ++fb[p];
-          }
-        }
-      }
-      fast = __builtin_amdgcn_ballot_w64(!interior) == 0;
-      if (fast) {
-#pragma unroll
-        for (int p = 0; p < 4; ++p) rb[p] = *reinterpret_cast<const f32x4_u*>(rd.xb[p] + rd.i0[p]);
-      } else {
-        const float* ptr[4];
-        prepare_chunk<4>(ptr, fx, g, rd, 0);
-#pragma unroll
-        for (int p = 0; p < 4; ++p) rb[p] = *reinterpret_cast<const f32x4_u*>(ptr[p]);
-      }
-    } else {
-      const long long k0 = c * BW_KC;
-      // A: G[k0 + k][m0 + 4 c4], k = tid/32 + 8 p (frame block m0/32 + c4/8);  B: wrm[k0 + k][n0 + 4 c4]
-      const float* ap = P.gbuf + ((m0 >> 5) + ((tid & 31) >> 3)) * ((long long)P.rows_pad * 32) +
-                        (k0 + (tid >> 5)) * 32 + 4 * (tid & 7);
-      const float* bp = P.wrm + (k0 + (tid >> 5)) * P.kp + n0 + 4 * (tid & 31);
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        ra[p] = *reinterpret_cast<const f32x4*>(ap + 8 * p * 32);
-        rb[p] = *reinterpret_cast<const f32x4*>(bp + (long long)(8 * p) * P.kp);
-      }
-    }
-  };
-  // registers -> LDS buffer
-  auto stage = [&](int buf) {
-    if constexpr (MODE == BW_MODE_BANK) {
-      float* a = &ldsA[buf][(tid >> 3) * BW_PA_M + 4 * (tid & 7)];
-#pragma unroll
-      for (int p = 0; p < 4; ++p)
-        if (p < alive) *reinterpret_cast<f32x4*>(a + 32 * p * BW_PA_M) = ra[p];
-      if (fast) {
-        float* b = &ldsB[buf][(tid >> 5) * BW_PK + 4 * (tid & 31)];
-#pragma unroll
-        for (int p = 0; p < 4; ++p) *reinterpret_cast<f32x4*>(b + 8 * p * BW_PK) = rb[p];
-      } else {
-        store_chunk<BW_NT, BW_PK, 4>(rb, fx, ldsB[buf], BW_KC, tid);
-      }
-    } else {
-      float* a = &ldsA[buf][(tid >> 5) * BW_PK + 4 * (tid & 31)];
-      float* b = &ldsB[buf][(tid >> 5) * BW_PK + 4 * (tid & 31)];
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        *reinterpret_cast<f32x4*>(a + 8 * p * BW_PK) = ra[p];
-        *reinterpret_cast<f32x4*>(b + 8 * p * BW_PK) = rb[p];
-      }
-    }
-  };
-
   // bank gradient: acc[s] = row block s x this wave's 32 taps; waveform gradient: acc[2 mi + ni]
   f32x16 acc[4];
 #pragma unroll
@@ -379,80 +280,202 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[s][r] = 0.f;
 
-  // lane (h, r32) holds contraction indices 8 kg + 4 h + e, e = 0..3, of row / column r32
-  constexpr int NA = MODE == BW_MODE_BANK ? 4 : 2, NB = MODE == BW_MODE_BANK ? 1 : 2;
-  auto load_frags = [&](const float* A, const float* B, int kg, f32x4 (&a)[NA], f32x4 (&b)[NB]) {
+  // The count of live row blocks is a compile-time constant of the chunk loop (one copy of the loop per count):
+  // tested at run time it put a branch around every MFMA.
+  auto sweep = [&](auto alive_c) {
+    constexpr int alive = decltype(alive_c)::value;
+    f32x4 ra[4], rb[4];
+    TileFix<4> fx;
+
+    // Bank gradient: this thread stages taps n0 + 4 (tid % 32) .. + 3 of frame (chunk start) + tid/32 + 8 p,
+    // p = 0..3.  The frames' (waveform, frame-in-waveform) pairs are stepped from chunk to chunk
+    // (BW_KC frames on) instead of being divided out every time.
+    long long fb[4];
+    int ft[4];
+    bool fast = false;                        // how the chunk now in rb goes to LDS
+    const bool long_waves = g.T >= BW_KC;     // a step of BW_KC frames crosses at most one waveform boundary
     if constexpr (MODE == BW_MODE_BANK) {
 #pragma unroll
-      for (int s = 0; s < 4; ++s)
-        if (s < alive) a[s] = *reinterpret_cast<const f32x4*>(A + (s * 32 + r32) * BW_PA_M + 8 * kg + 4 * h);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) b[0][e] = B[(8 * kg + 4 * h + e) * BW_PK + wave * 32 + r32];
-    } else {
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) a[mi][e] = A[(8 * kg + 4 * h + e) * BW_PK + wm * 64 + mi * 32 + r32];
-#pragma unroll
-      for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) b[ni][e] = B[(8 * kg + 4 * h + e) * BW_PK + wn * 64 + ni * 32 + r32];
+      for (int p = 0; p < 4; ++p) {
+        const long long f = c_begin * BW_KC + (tid >> 5) + 8 * p;
+        fb[p] = f / g.T;
+        ft[p] = (int)(f - fb[p] * g.T);
+      }
     }
-  };
-  auto mfma_group = [&](const f32x4 (&a)[NA], const f32x4 (&b)[NB]) {
-    if constexpr (MODE == BW_MODE_BANK) {
+
+    // global -> registers for contraction chunk c
+    auto fetch = [&](long long c) {
+      if constexpr (MODE == BW_MODE_BANK) {
+        // A: G[m0 + row][32 c + 4 c4], row = tid/8 + 32 p: the tile is one contiguous run of frame block c
+        const float* ap = P.gbuf + c * ((long long)P.rows_pad * 32) + (m0 + (tid >> 3)) * 32 + 4 * (tid & 7);
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
+        for (int p = 0; p < 4; ++p)
+          if (p < alive) ra[p] = *reinterpret_cast<const f32x4*>(ap + 32 * 32 * p);  // pass p = row block p
+        // B: taps n0.. of the 32 frames f0.., gathered from the mirrored waveforms (one LDS row per frame)
+        // Almost every window lies inside its waveform: then the four samples are loaded as they are
+        // stored.  Only a wave that touches a mirrored edge takes the forward kernels' general loader.
+        RowDesc<4> rd;
+        bool interior = true;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const bool ok = fb[p] < g.B;  // frames past the last one read a dummy window: their G is zero
+          rd.xb[p] = ok ? g.x + fb[p] * g.L : g.x;
+          rd.i0[p] = ok ? ft[p] * g.hop + 4 * (tid & 31) - g.pad + n0 : 0;
+          interior = interior && (unsigned)rd.i0[p] <= (unsigned)((int)g.L - 4);
+          ft[p] += BW_KC;  // on to the next chunk
+          if (long_waves) {
+            const bool wrap = ft[p] >= g.T;
+            ft[p] -= wrap ? g.T : 0;
+            fb[p] += wrap ? 1 : 0;
+          } else {
+            while (ft[p] >= g.T) {
+              ft[p] -= g.T;
+              ++fb[p];
+            }
+          }
+        }
+        fast = __builtin_amdgcn_ballot_w64(!interior) == 0;
+        if (fast) {
+#pragma unroll
+          for (int p = 0; p < 4; ++p) rb[p] = *reinterpret_cast<const f32x4_u*>(rd.xb[p] + rd.i0[p]);
+        } else {
+          const float* ptr[4];
+          prepare_chunk<4>(ptr, fx, g, rd, 0);
+#pragma unroll
+          for (int p = 0; p < 4; ++p) rb[p] = *reinterpret_cast<const f32x4_u*>(ptr[p]);
+        }
+      } else {
+        const long long k0 = c * BW_KC;
+        // A: G[k0 + k][m0 + 4 c4], k = tid/32 + 8 p (frame block m0/32 + c4/8);  B: wrm[k0 + k][n0 + 4 c4]
+        const float* ap = P.gbuf + ((m0 >> 5) + ((tid & 31) >> 3)) * ((long long)P.rows_pad * 32) +
+                          (k0 + (tid >> 5)) * 32 + 4 * (tid & 7);
+        const float* bp = P.wrm + (k0 + (tid >> 5)) * P.kp + n0 + 4 * (tid & 31);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          ra[p] = *reinterpret_cast<const f32x4*>(ap + 8 * p * 32);
+          rb[p] = *reinterpret_cast<const f32x4*>(bp + (long long)(8 * p) * P.kp);
+        }
+      }
+    };
+    // registers -> LDS buffer
+    auto stage = [&](int buf) {
+      if constexpr (MODE == BW_MODE_BANK) {
+        float* a = &ldsA[buf][(tid >> 3) * BW_PA_M + 4 * (tid & 7)];
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+          if (p < alive) *reinterpret_cast<f32x4*>(a + 32 * p * BW_PA_M) = ra[p];
+        if (fast) {
+          float* b = &ldsB[buf][(tid >> 5) * BW_PK + 4 * (tid & 31)];
+#pragma unroll
+          for (int p = 0; p < 4; ++p) *reinterpret_cast<f32x4*>(b + 8 * p * BW_PK) = rb[p];
+        } else {
+          store_chunk<BW_NT, BW_PK, 4>(rb, fx, ldsB[buf], BW_KC, tid);
+        }
+      } else {
+        float* a = &ldsA[buf][(tid >> 5) * BW_PK + 4 * (tid & 31)];
+        float* b = &ldsB[buf][(tid >> 5) * BW_PK + 4 * (tid & 31)];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          *reinterpret_cast<f32x4*>(a + 8 * p * BW_PK) = ra[p];
+          *reinterpret_cast<f32x4*>(b + 8 * p * BW_PK) = rb[p];
+        }
+      }
+    };
+
+    // lane (h, r32) holds contraction indices 8 kg + 4 h + e, e = 0..3, of row / column r32
+    constexpr int NA = MODE == BW_MODE_BANK ? 4 : 2, NB = MODE == BW_MODE_BANK ? 1 : 2;
+    auto load_frags = [&](const float* A, const float* B, int kg, f32x4 (&a)[NA], f32x4 (&b)[NB]) {
+      if constexpr (MODE == BW_MODE_BANK) {
 #pragma unroll
         for (int s = 0; s < 4; ++s)
-          if (s < alive) acc[s] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s][e], b[0][e], acc[s], 0, 0, 0);
-    } else {
+          if (s < alive) a[s] = *reinterpret_cast<const f32x4*>(A + (s * 32 + r32) * BW_PA_M + 8 * kg + 4 * h);
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
+        for (int e = 0; e < 4; ++e) b[0][e] = B[(8 * kg + 4 * h + e) * BW_PK + wave * 32 + r32];
+      } else {
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-          for (int ni = 0; ni < 2; ++ni)
-            acc[2 * mi + ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][e], b[ni][e], acc[2 * mi + ni], 0, 0, 0);
+          for (int e = 0; e < 4; ++e) a[mi][e] = A[(8 * kg + 4 * h + e) * BW_PK + wm * 64 + mi * 32 + r32];
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) b[ni][e] = B[(8 * kg + 4 * h + e) * BW_PK + wn * 64 + ni * 32 + r32];
+      }
+    };
+    auto mfma_group = [&](const f32x4 (&a)[NA], const f32x4 (&b)[NB]) {
+      if constexpr (MODE == BW_MODE_BANK) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int s = 0; s < 4; ++s)
+            if (s < alive) acc[s] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s][e], b[0][e], acc[s], 0, 0, 0);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+              acc[2 * mi + ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][e], b[ni][e], acc[2 * mi + ni], 0, 0, 0);
+      }
+    };
+
+    // Pipeline: while chunk c is multiplied out of one LDS buffer, chunk c+1 (requested one iteration
+    // earlier) is written to the other and chunk c+2 is requested.  The operand fragments of a group of 8 contraction
+    // indices are read from LDS two groups ahead of their 16 MFMAs -- across the chunk boundary too: the barrier sits
+    // in the middle of a chunk, after every read of its buffer and every write of the next one, so the first two
+    // groups of chunk c+1 are read behind the barrier while the last two groups of chunk c run, and no wave starts a
+    // chunk by waiting for LDS.
+    fetch(c_begin);
+    stage(0);
+    if (c_begin + 1 < c_end) fetch(c_begin + 1);
+    __syncthreads();
+    static_assert(BW_KC == 32, "four fragment groups per chunk");
+    f32x4 a0[NA], b0[NB], a1[NA], b1[NB];
+    load_frags(ldsA[0], ldsB[0], 0, a0, b0);
+    load_frags(ldsA[0], ldsB[0], 1, a1, b1);
+
+    for (long long c = c_begin; c < c_end; ++c) {
+      const int buf = (int)((c - c_begin) & 1);
+      const float* A = ldsA[buf];
+      const float* B = ldsB[buf];
+      // The scheduling barriers pin the order: each group's LDS reads go out ahead of the previous
+      // group's 16 MFMAs (left alone, the compiler sinks every read to just before its first use and
+      // the matrix pipe idles for the LDS latency every four MFMAs), and the LDS writes of chunk c+1
+      // and the global requests for chunk c+2 sit behind reads that are already on their way, with a
+      // whole MFMA group to hide them.
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_group(a0, b0);
+      __builtin_amdgcn_sched_barrier(0);
+      load_frags(A, B, 2, a0, b0);
+      if (c + 1 < c_end) stage(buf ^ 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_group(a1, b1);
+      __builtin_amdgcn_sched_barrier(0);
+      load_frags(A, B, 3, a1, b1);
+      if (c + 2 < c_end) fetch(c + 2);
+      __syncthreads();  // buffer `buf` has been read for the last time, buffer `buf ^ 1` is complete
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_group(a0, b0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (c + 1 < c_end) load_frags(ldsA[buf ^ 1], ldsB[buf ^ 1], 0, a0, b0);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_group(a1, b1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (c + 1 < c_end) load_frags(ldsA[buf ^ 1], ldsB[buf ^ 1], 1, a1, b1);
     }
   };
-
-  // Pipeline: while chunk c is multiplied out of one LDS buffer, chunk c+1 (requested one iteration
-  // earlier) is written to the other and chunk c+2 is requested; within a chunk the operand fragments
-  // of the next group of 8 are read from LDS while the current 16 MFMAs run.
-  fetch(c_begin);
-  stage(0);
-  if (c_begin + 1 < c_end) fetch(c_begin + 1);
-  __syncthreads();
-
-  for (long long c = c_begin; c < c_end; ++c) {
-    const int buf = (int)((c - c_begin) & 1);
-    const float* A = ldsA[buf];
-    const float* B = ldsB[buf];
-    static_assert(BW_KC == 32, "four fragment groups per chunk");
-    // The scheduling barriers pin the order: each group's LDS reads go out ahead of the previous
-    // group's 16 MFMAs (left alone, the compiler sinks every read to just before its first use and
-    // the matrix pipe idles for the LDS latency every four MFMAs), and the LDS writes of chunk c+1
-    // and the global requests for chunk c+2 sit behind reads that are already on their way, with a
-    // whole MFMA group to hide them.
-    f32x4 a0[NA], b0[NB], a1[NA], b1[NB];
-    load_frags(A, B, 0, a0, b0);
-    load_frags(A, B, 1, a1, b1);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_group(a0, b0);
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(A, B, 2, a0, b0);
-    if (c + 1 < c_end) stage(buf ^ 1);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_group(a1, b1);
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(A, B, 3, a1, b1);
-    if (c + 2 < c_end) fetch(c + 2);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_group(a0, b0);
-    mfma_group(a1, b1);
-    __syncthreads();
+  if constexpr (SPARSE) {
+    switch (alive_rt) {
+      case 1: sweep(std::integral_constant<int, 1>{}); break;
+      case 2: sweep(std::integral_constant<int, 2>{}); break;
+      case 3: sweep(std::integral_constant<int, 3>{}); break;
+      default: sweep(std::integral_constant<int, 4>{}); break;
+    }
+  } else {
+    sweep(std::integral_constant<int, 4>{});
   }
+  const int alive = SPARSE ? alive_rt : 4;
 
   // ---- epilogue: accumulator register r of lane (h, r32) is output row 8 (r/4) + 4 h + r%4, column r32
   if constexpr (MODE == BW_MODE_BANK) {
@@ -516,22 +539,32 @@ constexpr int CW_SEG = BW_MT;             // shifts served by one window
 constexpr int CW_WIN = BW_MT + CW_SEG;    // frames in the window (128 tile rows + up to 127 shifts, rounded up)
 constexpr int CW_PA = CW_WIN + 4;         // its LDS pitch
 
+// WHOLE: every W tile of the launch lies inside the hop and inside the padded bank row (the launcher checks it).
+template <bool WHOLE>
 __global__ __launch_bounds__(256, 2) void cq_wave_kernel(const BwParams P) {
   __shared__ __attribute__((aligned(16))) float ldsA[BW_KC * CW_PA];
-  __shared__ __attribute__((aligned(16))) float ldsB[2][BW_KC * BW_PK];
 
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int h = lane >> 5, r32 = lane & 31;
   const FrameGeom& g = P.g;
   const int T = g.T;
 
-  // the column tiles of one (waveform, row tile) are neighbours: they share its G frames in the L2
-  const long long bq = blockIdx.x / P.n_ct;
-  const int ct = (int)(blockIdx.x - bq * P.n_ct), n0 = ct * BW_NT;
-  const long long gb = bq / P.n_qt;
-  const int q0 = (int)(bq - gb * P.n_qt) * BW_MT;
+  // The column tile is the slow index: the workgroups resident at one time then stream the same W tiles (the whole bank,
+  // 88 MB for 168 bins of 65,536 taps, goes past every workgroup; G is a hundred times smaller) and share them in the L2s.
+  const long long n_bq = (long long)gridDim.x / P.n_ct;
+  const int ct = (int)(blockIdx.x / n_bq), n0 = ct * BW_NT;
+  // Within a column tile the hop-row tile is the next slower index and the waveform the fast one.  Workgroups go to
+  // the chip's eight dies in turn, and the row tiles of a waveform differ in work (the first and the last hold rows
+  // whose frames lie outside the waveform on most shifts: 62 % and 33 % of a middle tile's MFMAs for 345 frames and
+  // 128 shifts); with the row tile as the fast index and four tiles per waveform each die saw one kind of tile only,
+  // and those with the middle tiles ran three times longer than those with the last.  The full tiles go first, the
+  // two partial ones last.
+  const long long bq = blockIdx.x - ct * n_bq;
+  const int qi = (int)(bq / g.B);
+  const long long gb = bq - (long long)qi * g.B;
+  const int qt = qi < P.n_qt - 2 ? qi + 1 : (qi == P.n_qt - 2 ? 0 : P.n_qt - 1);
+  const int q0 = qt * BW_MT;
   // shifts j with a frame q - j inside [0, T) for some row q of the tile
   const int j_lo = q0 - (T - 1) > 0 ? q0 - (T - 1) : 0;
   const int j_hi = q0 + BW_MT - 1 < P.n_shift - 1 ? q0 + BW_MT - 1 : P.n_shift - 1;
@@ -542,64 +575,75 @@ __global__ __launch_bounds__(256, 2) void cq_wave_kernel(const BwParams P) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[s][r] = 0.f;
 
-  f32x4 rb0[4], rb1[4];  // W tiles in flight: requested two shifts ahead of their use
-  const int c4 = 4 * (tid & 31);
-  // W[k0 + tid/32 + 8 p][j hop + n0 + c4 ..]; columns past the hop belong to the next shift: zero
-  auto fetch_b = [&](f32x4 (&rb)[4], int k0, int j) {
-    const long long tb = (long long)j * g.hop + n0;
-    const bool whole = n0 + BW_NT <= g.hop && tb + BW_NT <= P.kp;
+  // A wave owns 32 columns of the tile and all four of its 32-row blocks, so the W values it multiplies are its own:
+  // W[k0 + 8 kg + 4 h + e][j hop + n0 + wave 32 + r32] is element 4 kg + e of lane (h, r32), the B operand of the MFMA
+  // as it stands.  They go from memory straight into registers, one shift ahead of their use (a shift is 64 MFMAs of
+  // 64 cycles, far longer than a load takes), and never through LDS: only the G window is shared, and the waves of a
+  // workgroup meet once per window, not once per shift (staged through LDS with a barrier per shift, 45 % of the wave
+  // cycles were waits).  Columns past the hop belong to the next shift and read as zero.
+  float bw0[16], bw1[16];
+  const int colw = n0 + wave * 32;  // first column of the wave
+  // address = a base every lane of the wave shares (scalar registers) + a 32-bit lane offset that never changes
+  const unsigned lane_w = (unsigned)((4u * h * (unsigned)P.kp + r32) * sizeof(float));
+  auto fetch_b = [&](float (&bw)[16], int k0, int j) {
+    const long long tb = (long long)j * g.hop + colw;
+    const char* row = reinterpret_cast<const char*>(P.wrm + (long long)k0 * P.kp + tb);
+    const bool in = WHOLE || (colw + r32 < g.hop && tb + r32 < P.kp);
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const float* bp = P.wrm + (long long)(k0 + (tid >> 5) + 8 * p) * P.kp + tb + c4;
-      if (whole) {
-        rb[p] = *reinterpret_cast<const f32x4_u*>(bp);
-      } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) rb[p][i] = (n0 + c4 + i < g.hop && tb + c4 + i < P.kp) ? bp[i] : 0.f;
-      }
+    for (int i = 0; i < 16; ++i) {
+      const char* rp = row + (long long)(8 * (i >> 2) + (i & 3)) * P.kp * (long long)sizeof(float);
+      bw[i] = in ? *reinterpret_cast<const float*>(rp + lane_w) : 0.f;
     }
   };
-  auto stage_b = [&](const f32x4 (&rb)[4], int buf) {
-    float* b = &ldsB[buf][(tid >> 5) * BW_PK + c4];
-#pragma unroll
-    for (int p = 0; p < 4; ++p) *reinterpret_cast<f32x4*>(b + 8 * p * BW_PK) = rb[p];
-  };
-  // lane (h, r32) holds contraction indices 8 kg + 4 h + e of tile row / column r32; `w` = window index of tile row 0
+  // lane (h, r32) holds contraction indices 8 kg + 4 h + e of tile row r32; `w` = window index of tile row 0.
   // A 32-row block of the tile whose frames q - j all fall outside the waveform on this shift has a zero A
-  // operand (the first and last row tiles of a waveform are half such blocks): it is skipped.
-  bool live[2];
-  auto load_frags = [&](const float* B, int w, int kg, f32x4 (&a)[2], f32x4 (&b)[2]) {
+  // operand (the first and last row tiles of a waveform are half such blocks): it is skipped.  The live blocks of a
+  // shift are a run lo .. hi - 1.
+  auto load_a = [&](int w, int kg, int lo, int hi, f32x4 (&a)[4]) {
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
-      if (live[mi]) {
+    for (int mi = 0; mi < 4; ++mi)
+      if (mi >= lo && mi < hi) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) a[mi][e] = ldsA[(8 * kg + 4 * h + e) * CW_PA + w + wm * 64 + mi * 32 + r32];
+        for (int e = 0; e < 4; ++e) a[mi][e] = ldsA[(8 * kg + 4 * h + e) * CW_PA + w + mi * 32 + r32];
       }
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) b[ni][e] = B[(8 * kg + 4 * h + e) * BW_PK + wn * 64 + ni * 32 + r32];
   };
-  auto mfma_group = [&](const f32x4 (&a)[2], const f32x4 (&b)[2]) {
+  auto mfma_group = [&](const f32x4 (&a)[4], const float (&bw)[16], int kg, int lo, int hi) {
 #pragma unroll
     for (int e = 0; e < 4; ++e)
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-        if (live[mi]) {
-#pragma unroll
-          for (int ni = 0; ni < 2; ++ni)
-            acc[2 * mi + ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][e], b[ni][e], acc[2 * mi + ni], 0, 0, 0);
-        }
+      for (int mi = 0; mi < 4; ++mi)
+        if (mi >= lo && mi < hi)
+          acc[mi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][e], bw[4 * kg + e], acc[mi], 0, 0, 0);
   };
+  // the 64 MFMAs of a shift; lo_c, hi_c are compile-time constants for the runs that reach an end of the tile (a
+  // run-time test puts a branch around every MFMA), plain integers otherwise
+  auto shift_mfmas = [&](int w, const float (&bw)[16], auto lo_c, auto hi_c) {
+    const int lo = lo_c, hi = hi_c;
+    f32x4 a0[4], a1[4];
+    load_a(w, 0, lo, hi, a0);
+    load_a(w, 1, lo, hi, a1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_group(a0, bw, 0, lo, hi);
+    __builtin_amdgcn_sched_barrier(0);
+    load_a(w, 2, lo, hi, a0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_group(a1, bw, 1, lo, hi);
+    __builtin_amdgcn_sched_barrier(0);
+    load_a(w, 3, lo, hi, a1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_group(a0, bw, 2, lo, hi);
+    mfma_group(a1, bw, 3, lo, hi);
+  };
+  using std::integral_constant;
 
-  int buf = 0;
   for (int kc = 0; kc < P.n_kc; ++kc) {
     const int2 rng = P.shift_rng[ct * P.n_kc + kc];  // shifts on which rows k0 .. k0 + 31 hold taps
     const int ja = rng.x > j_lo ? rng.x : j_lo, jb = rng.y < j_hi ? rng.y : j_hi;
     const int k0 = kc * BW_KC;
     for (int js = ja; js <= jb; js += CW_SEG) {
       const int je = js + CW_SEG - 1 < jb ? js + CW_SEG - 1 : jb;
-      __syncthreads();  // every wave is done with the previous window and W tiles
+      fetch_b(bw0, k0, js);
+      __syncthreads();  // every wave is done with the previous window
       // window: frames q0 - je .. q0 - je + CW_WIN - 1 of rows k0 .. k0 + 31 (zero outside the waveform)
       {
         const int row = tid >> 3;
@@ -610,61 +654,65 @@ __global__ __launch_bounds__(256, 2) void cq_wave_kernel(const BwParams P) {
               load_g4(P.gbuf, (long long)P.rows_pad * 32, k0 + row, gb * T, q0 - je + w, T);
         }
       }
-      fetch_b(rb0, k0, js);
-      if (js < je) fetch_b(rb1, k0, js + 1);
-      // one shift: its W tile (requested two shifts ago) goes to LDS, the tile two shifts on is requested
-      auto step = [&](int j, f32x4 (&rb)[4]) {
-        stage_b(rb, buf);
-        __syncthreads();
-        if (j + 2 <= je) fetch_b(rb, k0, j + 2);
-        const float* B = ldsB[buf];
-        buf ^= 1;
+      __syncthreads();
+      // one shift: the W values of the next one are requested before its MFMAs start
+      auto step = [&](int j, const float (&bw)[16], float (&next)[16]) {
+        // Requested on every shift, the last of a window included (it asks for its own values again): the compiler's
+        // wait ahead of an MFMA allows as many loads in flight as every path to it guarantees were requested after the
+        // operand's own, and one path without these 16 made every MFMA of every shift wait for the next shift's values.
+        fetch_b(next, k0, j + 1 <= je ? j + 1 : je);
         const int w = je - j;
+        // block mi holds frames q0 + 32 mi - j .. + 31: live while the last of them is >= 0 and the first < T
+        int lo = 0, hi = 0;
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
-          const int t_first = q0 + wm * 64 + mi * 32 - j;  // frame of the block's first row
-          live[mi] = t_first + 31 >= 0 && t_first < T;
+        for (int mi = 0; mi < 4; ++mi) {
+          const int t_first = q0 + mi * 32 - j;
+          lo += t_first + 31 < 0 ? 1 : 0;
+          hi += t_first < T ? 1 : 0;
         }
-        if (!live[0] && !live[1]) return;
-        f32x4 a0[2], b0[2], a1[2], b1[2];
-        load_frags(B, w, 0, a0, b0);
-        load_frags(B, w, 1, a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_group(a0, b0);
-        __builtin_amdgcn_sched_barrier(0);
-        load_frags(B, w, 2, a0, b0);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_group(a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
-        load_frags(B, w, 3, a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_group(a0, b0);
-        mfma_group(a1, b1);
+        if (lo >= hi) return;
+        if (lo == 0 && hi == 4) {
+          shift_mfmas(w, bw, integral_constant<int, 0>{}, integral_constant<int, 4>{});
+        } else if (hi == 4) {
+          if (lo == 1)
+            shift_mfmas(w, bw, integral_constant<int, 1>{}, integral_constant<int, 4>{});
+          else if (lo == 2)
+            shift_mfmas(w, bw, integral_constant<int, 2>{}, integral_constant<int, 4>{});
+          else
+            shift_mfmas(w, bw, integral_constant<int, 3>{}, integral_constant<int, 4>{});
+        } else if (lo == 0) {
+          if (hi == 3)
+            shift_mfmas(w, bw, integral_constant<int, 0>{}, integral_constant<int, 3>{});
+          else if (hi == 2)
+            shift_mfmas(w, bw, integral_constant<int, 0>{}, integral_constant<int, 2>{});
+          else
+            shift_mfmas(w, bw, integral_constant<int, 0>{}, integral_constant<int, 1>{});
+        } else {
+          shift_mfmas(w, bw, lo, hi);
+        }
       };
       for (int j = js; j <= je; j += 2) {
-        step(j, rb0);
-        if (j + 1 <= je) step(j + 1, rb1);
+        step(j, bw0, bw1);
+        if (j + 1 <= je) step(j + 1, bw1, bw0);
       }
     }
   }
 
-  // register r of lane (h, r32): hop-row q0 + wm 64 + mi 32 + 8 (r/4) + 4 h + r%4, column n0 + wn 64 + ni 32 + r32
+  // register r of lane (h, r32) of block mi: hop-row q0 + mi 32 + 8 (r/4) + 4 h + r%4, column n0 + wave 32 + r32
   const int L = (int)g.L;
   const long long ext = (long long)(T - 1) * g.hop + P.K;  // samples of the padded signal that frames cover
   float* __restrict__ xrow = P.gx + gb * g.L;
+  const int col = n0 + wave * 32 + r32;
+  if (col < g.hop) {
 #pragma unroll
-  for (int ni = 0; ni < 2; ++ni) {
-    const int col = n0 + wn * 64 + ni * 32 + r32;
-    if (col >= g.hop) continue;
-#pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const long long pos = (long long)(q0 + wm * 64 + mi * 32 + 8 * (r >> 2) + 4 * h + (r & 3)) * g.hop + col;
+        const long long pos = (long long)(q0 + mi * 32 + 8 * (r >> 2) + 4 * h + (r & 3)) * g.hop + col;
         if (pos < ext) {
           long long j = pos - g.pad;
           j = j < 0 ? -j : (j >= L ? 2 * (L - 1) - j : j);  // mirror padding folded back
-          unsafeAtomicAdd(xrow + j, acc[2 * mi + ni][r]);
+          unsafeAtomicAdd(xrow + j, acc[mi][r]);
         }
       }
   }
@@ -1069,7 +1117,10 @@ hipError_t launch_bw_wave(const BwParams& p, hipStream_t stream) {
       return hipErrorInvalidValue;
     const long long blocks = p.g.B * p.n_qt * p.n_ct;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(cq_wave_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    if (p.g.hop % BW_NT == 0 && (long long)p.n_shift * p.g.hop <= p.kp)
+      hipLaunchKernelGGL(cq_wave_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    else
+      hipLaunchKernelGGL(cq_wave_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, p);
     return hipGetLastError();
   }
   const long long blocks = (p.gpitch / BW_MT) * (p.kp / BW_NT);
