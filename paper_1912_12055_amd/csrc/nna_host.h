@@ -73,6 +73,15 @@ struct nna_plan {
   // CQT by recursive downsampling: one CQT sub-plan per octave (0 = top) and the decimating filter
   std::vector<nna_plan*> octave;
   nna_plan* fir = nullptr;
+  // Device plans with more than one octave: two streams of their own and the events that order a call's launches
+  // across them (the filter chain stays on the caller's stream, the octaves' kernels go to the two others in turn);
+  // created with the plan, so that a call allocates nothing.  oct_mutex: one call enqueues at a time.
+  static constexpr int OCT_EVENTS = 16;  // = MAX_OCTAVES
+  hipStream_t oct_stream[2] = {nullptr, nullptr};
+  hipEvent_t ev_fork = nullptr;
+  hipEvent_t ev_fir[OCT_EVENTS] = {};
+  hipEvent_t ev_oct[OCT_EVENTS] = {};
+  std::mutex oct_mutex;
   int fir_taps = 0;
   std::vector<double> h_fir;
   std::vector<nna::CqtItem> h_items;
@@ -331,6 +340,7 @@ int pick_tile_frames(int cap, long long T, int extra, int rows_max);
 nna_status check_call(const nna_plan* plan, int kind, const float* x, long long B, long long L, float* out, long long* T_out);
 nna::FrameGeom make_geom(const nna_plan* p, const float* x, long long B, long long L, long long T);
 constexpr int MAX_OCTAVES = 16;
+static_assert(MAX_OCTAVES == nna_plan::OCT_EVENTS, "one event per octave");
 inline int octaves_of(int n_bins, int bpo) { return (n_bins + bpo - 1) / bpo; }
 inline void octave_bins(int n_bins, int bpo, int a, int& lo, int& hi) {
   hi = n_bins - a * bpo;

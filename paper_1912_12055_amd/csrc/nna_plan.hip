@@ -495,6 +495,21 @@ static nna_status make_downsampling_plan(int kind, nna_plan** plan, int sr, int 
     g_err = keep;
     return s;
   }
+  if (device >= 0 && n_oct > 1) {
+    // streams at the default priority; events carry no timestamps
+    DeviceGuard guard;
+    hipError_t e = guard.enter(device);
+    for (int i = 0; i < 2 && e == hipSuccess; ++i) e = hipStreamCreateWithFlags(&p->oct_stream[i], hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming);
+    for (int a = 0; a < n_oct && e == hipSuccess; ++a) {
+      e = hipEventCreateWithFlags(&p->ev_fir[a], hipEventDisableTiming);
+      if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_oct[a], hipEventDisableTiming);
+    }
+    if (e != hipSuccess) {
+      nna_plan_destroy(p);
+      return fail_hip(e, "stream / event creation");
+    }
+  }
   // per frame of the output: every octave's kernels once, and hop / 2^(a+1) filter outputs for
   // each downsampling step a -> a+1 (the filter plan counts flops per frame of FIR_ROWS outputs)
   for (int a = 0; a < n_oct; ++a) {
@@ -764,6 +779,16 @@ void nna_plan_destroy(nna_plan* plan) {
   if (plan->device >= 0) {
     DeviceGuard guard;
     if (guard.enter(plan->device) == hipSuccess) {
+      for (hipStream_t st : plan->oct_stream)
+        if (st) {
+          (void)hipStreamSynchronize(st);
+          (void)hipStreamDestroy(st);
+        }
+      if (plan->ev_fork) (void)hipEventDestroy(plan->ev_fork);
+      for (hipEvent_t ev : plan->ev_fir)
+        if (ev) (void)hipEventDestroy(ev);
+      for (hipEvent_t ev : plan->ev_oct)
+        if (ev) (void)hipEventDestroy(ev);
       (void)hipFree(plan->d_bank);
       (void)hipFree(plan->d_bank16);
       (void)hipFree(plan->d_bankf);

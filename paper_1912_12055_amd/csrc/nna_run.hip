@@ -372,25 +372,73 @@ static nna_status run_octaves(const nna_plan* plan, int kind, const float* x_dev
   DeviceGuard guard;
   hipError_t e = guard.enter(plan->device);
   if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
+  // The filter chain x_0 -> x_1 -> ... runs on the caller's stream; octave a's kernels need x_a only and go to one of the
+  // plan's two streams (even / odd octaves), so they run beside the next filter steps and beside each other: the
+  // filter is bound by the vector ALUs, the octaves' kernels by the matrix pipe, and the deep octaves' launches are too
+  // small to fill the chip alone.  Every stream is back on the caller's before the call returns, so the call still
+  // is one piece of work on that stream (under stream capture: a fork and a join).
+  hipStream_t main_stream = static_cast<hipStream_t>(hip_stream);
+  const bool forked = n_oct > 1 && plan->oct_stream[0] != nullptr;
+  std::unique_lock<std::mutex> lock(const_cast<nna_plan*>(plan)->oct_mutex, std::defer_lock);
+  if (forked) {
+    lock.lock();
+    if ((e = hipEventRecord(plan->ev_fork, main_stream)) != hipSuccess) return fail_hip(e, "hipEventRecord");
+    for (hipStream_t st : plan->oct_stream)
+      if ((e = hipStreamWaitEvent(st, plan->ev_fork, 0)) != hipSuccess) return fail_hip(e, "hipStreamWaitEvent");
+  }
+  int launched = 0;  // octaves whose kernels were enqueued on the plan's streams
+  // the caller's stream waits for the last octave enqueued on each of the plan's streams (also on an error path)
+  auto join = [&]() -> hipError_t {
+    hipError_t r = hipSuccess;
+    for (int a = std::max(0, launched - 2); a < launched; ++a) {
+      const hipError_t w = hipStreamWaitEvent(main_stream, plan->ev_oct[a], 0);
+      if (r == hipSuccess) r = w;
+    }
+    return r;
+  };
   const float* cur = x_dev;
   for (int a = 0; a < n_oct; ++a) {
     int lo, hi;
     octave_bins(plan->n_bins, plan->bpo, a, lo, hi);
     // the octave's rows inside each waveform's output (the complex format writes two rows per bin)
     const int row0 = plan->fmt == NNA_OUT_COMPLEX ? 2 * lo : lo;
+    hipStream_t st = forked ? plan->oct_stream[a & 1] : main_stream;
+    if (forked && a >= 1 && (e = hipStreamWaitEvent(st, plan->ev_fir[a], 0)) != hipSuccess) {  // x_a is complete
+      (void)join();
+      return fail_hip(e, "hipStreamWaitEvent");
+    }
     if (kind == NNA_KIND_CQT2010V2)
-      s = run_conv(plan->octave[a], cur, B, La[a], T, out_dev, (long long)plan->out_rows() * T, row0, hip_stream);
+      s = run_conv(plan->octave[a], cur, B, La[a], T, out_dev, (long long)plan->out_rows() * T, row0, st);
     else
-      s = run_stft_core(plan->octave[a], NNA_KIND_CQT1992, cur, B, La[a], T, out_dev, (long long)plan->out_rows() * T, row0,
-                        hip_stream);
-    if (s != NNA_OK) return s;
+      s = run_stft_core(plan->octave[a], NNA_KIND_CQT1992, cur, B, La[a], T, out_dev, (long long)plan->out_rows() * T, row0, st);
+    if (forked) {
+      e = hipEventRecord(plan->ev_oct[a], st);
+      if (e == hipSuccess) launched = a + 1;
+      if (s == NNA_OK && e != hipSuccess) s = fail_hip(e, "hipEventRecord");
+    }
+    if (s != NNA_OK) {
+      if (forked) (void)join();
+      return s;
+    }
     if (a + 1 < n_oct) {
       float* dst = buf[a & 1];
       const long long Ln = La[a + 1];
-      if ((s = run_fir(plan->fir, cur, B, La[a], dst, Ln, hip_stream)) != NNA_OK) return s;
+      // dst held x_(a-1): octave a-1 must have read it
+      if (forked && a >= 2 && (e = hipStreamWaitEvent(main_stream, plan->ev_oct[a - 1], 0)) != hipSuccess) {
+        (void)join();
+        return fail_hip(e, "hipStreamWaitEvent");
+      }
+      s = run_fir(plan->fir, cur, B, La[a], dst, Ln, main_stream);
+      if (s == NNA_OK && forked && (e = hipEventRecord(plan->ev_fir[a + 1], main_stream)) != hipSuccess)
+        s = fail_hip(e, "hipEventRecord");
+      if (s != NNA_OK) {
+        if (forked) (void)join();
+        return s;
+      }
       cur = dst;
     }
   }
+  if (forked && (e = join()) != hipSuccess) return fail_hip(e, "hipStreamWaitEvent");
   return NNA_OK;
 }
 

@@ -9,17 +9,16 @@
 //   waveform gradient  D[f, n]   = sum_r G[r, f] W[r, n], then gx[mirror(f hop + n)] += D[f, n]
 //                                                              (frames x taps, over bank rows)
 //
-// Both are dense GEMMs on v_mfma_f32_32x32x2_f32 with one kernel: a 128 x 128 output tile per
-// workgroup (4 waves, four 32 x 32 accumulators each: 2 x 2 waves of 64 x 64 for the waveform gradient,
-// 4 waves of 128 rows x 32 taps for the bank gradient), the contraction
-// staged through LDS in chunks of 32 (double buffered, one barrier per chunk), two workgroups per
-// compute unit.  The B operand is always stored k-major in LDS ([k][column], read with 4-byte LDS
-// loads: at the float32 MFMA rate LDS bandwidth is nowhere near a limit); the A operand is m-major
-// for the bank gradient (G rows are contiguous along the contraction index) and k-major for the
-// waveform gradient (G rows are contiguous along the output index).  Lanes of an accumulator
-// register run along the output's contiguous axis (taps) in both, so the final atomic adds go out
-// in 128-byte runs.  The bank gradient's B operand is the frames matrix, never built: the framing
-// loader of the forward kernels gathers 32 frames x 128 taps per chunk, reflection included.
+// Both are dense GEMMs on v_mfma_f32_32x32x2_f32: a 128 x 128 output tile per workgroup (4 waves, four 32 x 32
+// accumulators each), the contraction in chunks of 32 (double buffered, one barrier per chunk, in the middle of it),
+// two workgroups per compute unit.  Lanes of an accumulator register run along the output's contiguous axis (taps) in
+// both, so the final atomic adds go out in 128-byte runs.
+//   bw_bank_kernel   4 waves of 128 rows x 32 taps.  The G tile (m-major: G rows are contiguous along the contraction
+//                    index) goes through LDS, read by all four waves; the frames matrix, never built, is each wave's
+//                    own operand and goes from the waveform straight into registers in MFMA layout, reflection
+//                    included.
+//   bw_wave_kernel   2 x 2 waves of 64 x 64; both operands k-major in LDS ([k][column], 4-byte LDS reads: at the
+//                    float32 MFMA rate LDS bandwidth is nowhere near a limit).
 //
 // A constant-Q bank (rows zero outside a tap range each, hundreds of hop-shifts) uses the same bank-gradient
 // kernel restricted to the output tiles and 32-row blocks that hold taps, and a waveform-gradient kernel of
@@ -40,7 +39,6 @@ typedef f32x4 f32x4_u __attribute__((aligned(4)));
 
 constexpr int BW_PA_M = BW_KC + 4;   // LDS pitch of an m-major A tile (conflict-free 16-byte reads)
 constexpr int BW_PK = BW_NT + 4;     // LDS pitch of a k-major tile
-constexpr int BW_MODE_BANK = 0, BW_MODE_WAVE = 1;
 
 __global__ void fill_zero_kernel(float* __restrict__ p, long long n) {
   const long long stride = (long long)gridDim.x * blockDim.x;
@@ -222,247 +220,314 @@ __device__ __forceinline__ f32x4 load_g4(const float* __restrict__ gbuf, long lo
   return v;
 }
 
-// SPARSE: the bank's rows are zero outside a tap range each (P.tiles, P.row_lo / row_hi are given); bank gradient only
-template <int MODE, bool SPARSE>
-__global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
-  constexpr int A_FLOATS = MODE == BW_MODE_BANK ? BW_MT * BW_PA_M : BW_KC * BW_PK;
-  constexpr int B_FLOATS = BW_KC * BW_PK;
-  __shared__ __attribute__((aligned(16))) float ldsA[2][A_FLOATS];
-  __shared__ __attribute__((aligned(16))) float ldsB[2][B_FLOATS];
+// Waveform gradient as a plain product over the bank's rows: frames x taps tile = G^T [frames, rows] x W [rows, taps],
+// added onto the waveform sample each (frame, tap) pair reads.  For short kernels (the STFT's, the deep octaves of a
+// downsampling CQT); the long constant-Q kernels go through cq_wave_kernel below.
+__global__ __launch_bounds__(256, 2) void bw_wave_kernel(const BwParams P) {
+  __shared__ __attribute__((aligned(16))) float ldsA[2][BW_KC * BW_PK];
+  __shared__ __attribute__((aligned(16))) float ldsB[2][BW_KC * BW_PK];
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave >> 1, wn = wave & 1;  // 2 x 2 waves of 64 x 64
   const int h = lane >> 5, r32 = lane & 31;
+  const FrameGeom& g = P.g;
+
+  // the tap tiles of one frame tile are neighbours: they share its G columns in the L2
+  const int n_nt = P.kp / BW_NT;
+  const long long m0 = (long long)(blockIdx.x / n_nt) * BW_MT;
+  const int n0 = (int)(blockIdx.x % n_nt) * BW_NT;
+  const long long c_end = (2 * P.n_half + BW_KC - 1) / BW_KC;  // row chunks that hold bank rows (the padding rows of G and W are zero)
+  if (c_end < 1) return;
+
+  f32x4 ra[4], rb[4];
+  // global -> registers for contraction chunk c:
+  // A: G[k0 + k][m0 + 4 c4], k = tid/32 + 8 p (frame block m0/32 + c4/8);  B: wrm[k0 + k][n0 + 4 c4]
+  auto fetch = [&](long long c) {
+    const long long k0 = c * BW_KC;
+    const float* ap = P.gbuf + ((m0 >> 5) + ((tid & 31) >> 3)) * ((long long)P.rows_pad * 32) + (k0 + (tid >> 5)) * 32 + 4 * (tid & 7);
+    const float* bp = P.wrm + (k0 + (tid >> 5)) * P.kp + n0 + 4 * (tid & 31);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      ra[p] = *reinterpret_cast<const f32x4*>(ap + 8 * p * 32);
+      rb[p] = *reinterpret_cast<const f32x4*>(bp + (long long)(8 * p) * P.kp);
+    }
+  };
+  // registers -> LDS buffer
+  auto stage = [&](int buf) {
+    float* a = &ldsA[buf][(tid >> 5) * BW_PK + 4 * (tid & 31)];
+    float* b = &ldsB[buf][(tid >> 5) * BW_PK + 4 * (tid & 31)];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      *reinterpret_cast<f32x4*>(a + 8 * p * BW_PK) = ra[p];
+      *reinterpret_cast<f32x4*>(b + 8 * p * BW_PK) = rb[p];
+    }
+  };
+
+  f32x16 acc[4];  // acc[2 mi + ni]
+#pragma unroll
+  for (int s = 0; s < 4; ++s)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[s][r] = 0.f;
+
+  // lane (h, r32) holds contraction indices 8 kg + 4 h + e, e = 0..3, of row / column r32
+  auto load_frags = [&](const float* A, const float* B, int kg, f32x4 (&a)[2], f32x4 (&b)[2]) {
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) a[mi][e] = A[(8 * kg + 4 * h + e) * BW_PK + wm * 64 + mi * 32 + r32];
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) b[ni][e] = B[(8 * kg + 4 * h + e) * BW_PK + wn * 64 + ni * 32 + r32];
+  };
+  auto mfma_group = [&](const f32x4 (&a)[2], const f32x4 (&b)[2]) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+          acc[2 * mi + ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][e], b[ni][e], acc[2 * mi + ni], 0, 0, 0);
+  };
+
+  // Pipeline: while chunk c is multiplied out of one LDS buffer, chunk c+1 (requested one iteration
+  // earlier) is written to the other and chunk c+2 is requested.  The operand fragments of a group of 8 contraction
+  // indices are read from LDS two groups ahead of their 16 MFMAs -- across the chunk boundary too: the barrier sits
+  // in the middle of a chunk, after every read of its buffer and every write of the next one, so the first two
+  // groups of chunk c+1 are read behind the barrier while the last two groups of chunk c run, and no wave starts a
+  // chunk by waiting for LDS.
+  fetch(0);
+  stage(0);
+  if (1 < c_end) fetch(1);
+  __syncthreads();
+  static_assert(BW_KC == 32, "four fragment groups per chunk");
+  f32x4 a0[2], b0[2], a1[2], b1[2];
+  load_frags(ldsA[0], ldsB[0], 0, a0, b0);
+  load_frags(ldsA[0], ldsB[0], 1, a1, b1);
+
+  for (long long c = 0; c < c_end; ++c) {
+    const int buf = (int)(c & 1);
+    const float* A = ldsA[buf];
+    const float* B = ldsB[buf];
+    // The scheduling barriers pin the order: each group's LDS reads go out ahead of the previous
+    // group's 16 MFMAs (left alone, the compiler sinks every read to just before its first use and
+    // the matrix pipe idles for the LDS latency every four MFMAs), and the LDS writes of chunk c+1
+    // and the global requests for chunk c+2 sit behind reads that are already on their way, with a
+    // whole MFMA group to hide them.
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_group(a0, b0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(A, B, 2, a0, b0);
+    if (c + 1 < c_end) stage(buf ^ 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_group(a1, b1);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(A, B, 3, a1, b1);
+    if (c + 2 < c_end) fetch(c + 2);
+    __syncthreads();  // buffer `buf` has been read for the last time, buffer `buf ^ 1` is complete
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_group(a0, b0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (c + 1 < c_end) load_frags(ldsA[buf ^ 1], ldsB[buf ^ 1], 0, a0, b0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_group(a1, b1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (c + 1 < c_end) load_frags(ldsA[buf ^ 1], ldsB[buf ^ 1], 1, a1, b1);
+  }
+
+  // ---- epilogue: accumulator register r of lane (h, r32) is output row 8 (r/4) + 4 h + r%4, column r32
+  const int L = (int)g.L;
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      // four consecutive frames per register quad
+      long long f = m0 + wm * 64 + mi * 32 + 8 * q + 4 * h;
+      long long b = f / g.T;
+      int t = (int)(f - b * g.T);
+#pragma unroll
+      for (int i = 0; i < 4; ++i, ++f) {
+        if (f < g.n_frames) {
+          float* __restrict__ row = P.gx + b * g.L;
+#pragma unroll
+          for (int ni = 0; ni < 2; ++ni) {
+            const int tap = n0 + wn * 64 + ni * 32 + r32;
+            if (tap < P.K) {
+              int j = t * g.hop + tap - g.pad;
+              j = j < 0 ? -j : (j >= L ? 2 * (L - 1) - j : j);  // mirror padding folded back
+              unsafeAtomicAdd(row + j, acc[2 * mi + ni][4 * q + i]);
+            }
+          }
+        }
+        if (++t == g.T) {
+          t = 0;
+          ++b;
+        }
+      }
+    }
+}
+
+// ---- bank gradient with the frames operand straight from memory --------------------------------
+// gw[row, tap] = sum_f G[row, f] x_pad[f hop + tap].  A workgroup owns 128 rows x 128 taps and a range of frame chunks;
+// a wave owns 32 of the taps and all four 32-row blocks, so the frames operand it multiplies is its own:
+// x_pad[(f0 + 8 kg + 4 h + e) hop + n0 + 32 wave + r32] is element 4 kg + e of lane (h, r32), the MFMA's B operand as
+// it stands -- sixteen coalesced one-sample loads per chunk (one sample at a time the mirrored edges are an index
+// fold, no special path), requested one chunk ahead into the other of two register sets.  Only the G tile, which all
+// four waves read, goes through LDS.
+template <bool SPARSE>
+__global__ __launch_bounds__(256, 2) void bw_bank_kernel(const BwParams P) {
+  __shared__ __attribute__((aligned(16))) float ldsA[2][BW_MT * BW_PA_M];
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int h = lane >> 5, r32 = lane & 31;
+  const FrameGeom& g = P.g;
 
   const int n_nt = P.kp / BW_NT;
-  long long m0, c_begin, c_end;
-  int n0;
-  // Bank gradient: the four waves split the tile's taps (32 each) and every wave sweeps the tile's four
-  // 32-row blocks, of which the first `alive` hold taps here (rows are ordered longest kernel first; a
-  // dense bank has all four): the blocks past that are neither read from LDS nor multiplied, and the
-  // waves stay balanced whatever `alive` is.  Waveform gradient: 2 x 2 waves of 64 x 64.
-  int alive_rt = 4;
-  if constexpr (MODE == BW_MODE_BANK) {
-    const int n_mt = P.rows_pad / BW_MT;
-    const long long tiles = SPARSE ? P.n_tiles : (long long)n_mt * n_nt;
-    const long long split = blockIdx.x / tiles;
-    int tile = (int)(blockIdx.x - split * tiles);
-    // Workgroup ids are dealt round-robin to the 8 XCDs, each with an L2 of its own.  Give every XCD a
-    // contiguous run of tiles in row-major order: it then reads only its own rows of G (the large
-    // operand) instead of all of them.
-    if (tiles % 8 == 0) tile = (tile & 7) * (int)(tiles / 8) + (tile >> 3);
-    if constexpr (SPARSE) {
-      const int2 t = P.tiles[tile];
-      m0 = (long long)(t.x & 0xffff) * BW_MT;
-      n0 = t.y * BW_NT;
-      alive_rt = t.x >> 16;
-    } else {
-      m0 = (long long)(tile / n_nt) * BW_MT;
-      n0 = (tile % n_nt) * BW_NT;
-    }
-    const long long n_chunks = P.gpitch / BW_KC;
-    c_begin = split * P.chunks_per_split;
-    c_end = c_begin + P.chunks_per_split < n_chunks ? c_begin + P.chunks_per_split : n_chunks;
+  const int n_mt = P.rows_pad / BW_MT;
+  const long long tiles = SPARSE ? P.n_tiles : (long long)n_mt * n_nt;
+  const long long split = blockIdx.x / tiles;
+  int tile = (int)(blockIdx.x - split * tiles);
+  long long m0;
+  int n0, alive_rt = 4;
+  if constexpr (SPARSE) {
+    // the list is ordered heaviest tile first; neighbours in it go to different dies, which balances them
+    const int2 t = P.tiles[tile];
+    m0 = (long long)(t.x & 0xffff) * BW_MT;
+    n0 = t.y * BW_NT;
+    alive_rt = t.x >> 16;
   } else {
-    // the tap tiles of one frame tile are neighbours: they share its G columns in the L2
-    m0 = (long long)(blockIdx.x / n_nt) * BW_MT;
-    n0 = (int)(blockIdx.x % n_nt) * BW_NT;
-    c_begin = 0;
-    c_end = (2 * P.n_half + BW_KC - 1) / BW_KC;  // row chunks that hold bank rows (the padding rows of G and W are zero)
+    // Workgroup ids are dealt round-robin to the 8 dies, each with an L2 of its own.  Give every die a contiguous
+    // run of tiles in row-major order: it then reads only its own rows of G (the large operand).
+    if (tiles % 8 == 0) tile = (tile & 7) * (int)(tiles / 8) + (tile >> 3);
+    m0 = (long long)(tile / n_nt) * BW_MT;
+    n0 = (tile % n_nt) * BW_NT;
   }
+  const long long n_chunks = P.gpitch / BW_KC;
+  const long long c_begin = split * P.chunks_per_split;
+  const long long c_end = c_begin + P.chunks_per_split < n_chunks ? c_begin + P.chunks_per_split : n_chunks;
   if (c_begin >= c_end) return;
-  const FrameGeom& g = P.g;
-  // bank gradient: acc[s] = row block s x this wave's 32 taps; waveform gradient: acc[2 mi + ni]
+
   f32x16 acc[4];
 #pragma unroll
   for (int s = 0; s < 4; ++s)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[s][r] = 0.f;
 
+  // (waveform, frame in it) of the first frame of the chunk the next fetch_b asks for: stepped, not divided out
+  long long nfb = c_begin * BW_KC / g.T;
+  int nft = (int)(c_begin * BW_KC - nfb * g.T);
+  const int tap = n0 + wave * 32 + r32;
+  const int L = (int)g.L;
+  auto fetch_b = [&](float (&bw)[16]) {
+    // Almost every chunk lies inside one waveform and clear of its mirrored ends (one test for the whole workgroup):
+    // a base every lane shares plus a lane offset that never changes.
+    const long long lo = (long long)nft * g.hop + n0 - g.pad;
+    if (nft + BW_KC <= g.T && nfb < g.B && lo >= 0 && lo + (long long)(BW_KC - 1) * g.hop + BW_NT <= g.L) {
+      const float* base = g.x + nfb * g.L + lo;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) bw[i] = base[(8 * (i >> 2) + 4 * h + (i & 3)) * g.hop + wave * 32 + r32];
+      nft += BW_KC;
+      if (nft >= g.T) {
+        nft -= g.T;
+        ++nfb;
+      }
+      return;
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      int t = nft + 8 * (i >> 2) + 4 * h + (i & 3);
+      long long b = nfb;
+      while (t >= g.T) {
+        t -= g.T;
+        ++b;
+      }
+      b = b < g.B ? b : g.B - 1;  // frames past the last one: their G is zero, any sample serves
+      int j = t * g.hop + tap - g.pad;
+      j = j < 0 ? -j : j;
+      j = j >= L ? 2 * (L - 1) - j : j;  // mirror padding folded back
+      j = j < 0 ? 0 : (j >= L ? L - 1 : j);  // taps of the padding columns past K: never stored
+      bw[i] = g.x[b * g.L + j];
+    }
+    nft += BW_KC;
+    while (nft >= g.T) {
+      nft -= g.T;
+      ++nfb;
+    }
+  };
+
   // The count of live row blocks is a compile-time constant of the chunk loop (one copy of the loop per count):
   // tested at run time it put a branch around every MFMA.
   auto sweep = [&](auto alive_c) {
     constexpr int alive = decltype(alive_c)::value;
-    f32x4 ra[4], rb[4];
-    TileFix<4> fx;
-
-    // Bank gradient: this thread stages taps n0 + 4 (tid % 32) .. + 3 of frame (chunk start) + tid/32 + 8 p,
-    // p = 0..3.  The frames' (waveform, frame-in-waveform) pairs are stepped from chunk to chunk
-    // (BW_KC frames on) instead of being divided out every time.
-    long long fb[4];
-    int ft[4];
-    bool fast = false;                        // how the chunk now in rb goes to LDS
-    const bool long_waves = g.T >= BW_KC;     // a step of BW_KC frames crosses at most one waveform boundary
-    if constexpr (MODE == BW_MODE_BANK) {
+    f32x4 ra[4];
+    // G[m0 + row][32 c + 4 c4], row = tid/8 + 32 p: the tile is one contiguous run of frame block c
+    auto fetch_a = [&](long long c) {
+      const float* ap = P.gbuf + c * ((long long)P.rows_pad * 32) + (m0 + (tid >> 3)) * 32 + 4 * (tid & 7);
 #pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const long long f = c_begin * BW_KC + (tid >> 5) + 8 * p;
-        fb[p] = f / g.T;
-        ft[p] = (int)(f - fb[p] * g.T);
-      }
-    }
-
-    // global -> registers for contraction chunk c
-    auto fetch = [&](long long c) {
-      if constexpr (MODE == BW_MODE_BANK) {
-        // A: G[m0 + row][32 c + 4 c4], row = tid/8 + 32 p: the tile is one contiguous run of frame block c
-        const float* ap = P.gbuf + c * ((long long)P.rows_pad * 32) + (m0 + (tid >> 3)) * 32 + 4 * (tid & 7);
-#pragma unroll
-        for (int p = 0; p < 4; ++p)
-          if (p < alive) ra[p] = *reinterpret_cast<const f32x4*>(ap + 32 * 32 * p);  // pass p = row block p
-        // B: taps n0.. of the 32 frames f0.., gathered from the mirrored waveforms (one LDS row per frame)
-        // Almost every window lies inside its waveform: then the four samples are loaded as they are
-        // stored.  Only a wave that touches a mirrored edge takes the forward kernels' general loader.
-        RowDesc<4> rd;
-        bool interior = true;
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          const bool ok = fb[p] < g.B;  // frames past the last one read a dummy window: their G is zero
-          rd.xb[p] = ok ? g.x + fb[p] * g.L : g.x;
-          rd.i0[p] = ok ? ft[p] * g.hop + 4 * (tid & 31) - g.pad + n0 : 0;
-          interior = interior && (unsigned)rd.i0[p] <= (unsigned)((int)g.L - 4);
-          ft[p] += BW_KC;  // on to the next chunk
-          if (long_waves) {
-            const bool wrap = ft[p] >= g.T;
-            ft[p] -= wrap ? g.T : 0;
-            fb[p] += wrap ? 1 : 0;
-          } else {
-            while (ft[p] >= g.T) {
-              ft[p] -= g.T;
-              ++fb[p];
-            }
-          }
-        }
-        fast = __builtin_amdgcn_ballot_w64(!interior) == 0;
-        if (fast) {
-#pragma unroll
-          for (int p = 0; p < 4; ++p) rb[p] = *reinterpret_cast<const f32x4_u*>(rd.xb[p] + rd.i0[p]);
-        } else {
-          const float* ptr[4];
-          prepare_chunk<4>(ptr, fx, g, rd, 0);
-#pragma unroll
-          for (int p = 0; p < 4; ++p) rb[p] = *reinterpret_cast<const f32x4_u*>(ptr[p]);
-        }
-      } else {
-        const long long k0 = c * BW_KC;
-        // A: G[k0 + k][m0 + 4 c4], k = tid/32 + 8 p (frame block m0/32 + c4/8);  B: wrm[k0 + k][n0 + 4 c4]
-        const float* ap = P.gbuf + ((m0 >> 5) + ((tid & 31) >> 3)) * ((long long)P.rows_pad * 32) +
-                          (k0 + (tid >> 5)) * 32 + 4 * (tid & 7);
-        const float* bp = P.wrm + (k0 + (tid >> 5)) * P.kp + n0 + 4 * (tid & 31);
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          ra[p] = *reinterpret_cast<const f32x4*>(ap + 8 * p * 32);
-          rb[p] = *reinterpret_cast<const f32x4*>(bp + (long long)(8 * p) * P.kp);
-        }
-      }
+      for (int p = 0; p < alive; ++p) ra[p] = *reinterpret_cast<const f32x4*>(ap + 32 * 32 * p);
     };
-    // registers -> LDS buffer
-    auto stage = [&](int buf) {
-      if constexpr (MODE == BW_MODE_BANK) {
-        float* a = &ldsA[buf][(tid >> 3) * BW_PA_M + 4 * (tid & 7)];
+    auto stage_a = [&](int buf) {
+      float* a = &ldsA[buf][(tid >> 3) * BW_PA_M + 4 * (tid & 7)];
 #pragma unroll
-        for (int p = 0; p < 4; ++p)
-          if (p < alive) *reinterpret_cast<f32x4*>(a + 32 * p * BW_PA_M) = ra[p];
-        if (fast) {
-          float* b = &ldsB[buf][(tid >> 5) * BW_PK + 4 * (tid & 31)];
+      for (int p = 0; p < alive; ++p) *reinterpret_cast<f32x4*>(a + 32 * p * BW_PA_M) = ra[p];
+    };
+    // lane (h, r32) holds contraction indices 8 kg + 4 h + e, e = 0..3, of row r32 of each block
+    auto load_a = [&](const float* A, int kg, f32x4 (&a)[4]) {
 #pragma unroll
-          for (int p = 0; p < 4; ++p) *reinterpret_cast<f32x4*>(b + 8 * p * BW_PK) = rb[p];
-        } else {
-          store_chunk<BW_NT, BW_PK, 4>(rb, fx, ldsB[buf], BW_KC, tid);
-        }
-      } else {
-        float* a = &ldsA[buf][(tid >> 5) * BW_PK + 4 * (tid & 31)];
-        float* b = &ldsB[buf][(tid >> 5) * BW_PK + 4 * (tid & 31)];
+      for (int s = 0; s < alive; ++s) a[s] = *reinterpret_cast<const f32x4*>(A + (s * 32 + r32) * BW_PA_M + 8 * kg + 4 * h);
+    };
+    auto mfma_group = [&](const f32x4 (&a)[4], const float (&bw)[16], int kg) {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          *reinterpret_cast<f32x4*>(a + 8 * p * BW_PK) = ra[p];
-          *reinterpret_cast<f32x4*>(b + 8 * p * BW_PK) = rb[p];
-        }
-      }
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int s = 0; s < alive; ++s)
+          acc[s] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s][e], bw[4 * kg + e], acc[s], 0, 0, 0);
     };
 
-    // lane (h, r32) holds contraction indices 8 kg + 4 h + e, e = 0..3, of row / column r32
-    constexpr int NA = MODE == BW_MODE_BANK ? 4 : 2, NB = MODE == BW_MODE_BANK ? 1 : 2;
-    auto load_frags = [&](const float* A, const float* B, int kg, f32x4 (&a)[NA], f32x4 (&b)[NB]) {
-      if constexpr (MODE == BW_MODE_BANK) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-          if (s < alive) a[s] = *reinterpret_cast<const f32x4*>(A + (s * 32 + r32) * BW_PA_M + 8 * kg + 4 * h);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) b[0][e] = B[(8 * kg + 4 * h + e) * BW_PK + wave * 32 + r32];
-      } else {
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) a[mi][e] = A[(8 * kg + 4 * h + e) * BW_PK + wm * 64 + mi * 32 + r32];
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) b[ni][e] = B[(8 * kg + 4 * h + e) * BW_PK + wn * 64 + ni * 32 + r32];
-      }
-    };
-    auto mfma_group = [&](const f32x4 (&a)[NA], const f32x4 (&b)[NB]) {
-      if constexpr (MODE == BW_MODE_BANK) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-#pragma unroll
-          for (int s = 0; s < 4; ++s)
-            if (s < alive) acc[s] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s][e], b[0][e], acc[s], 0, 0, 0);
-      } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-#pragma unroll
-          for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-              acc[2 * mi + ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][e], b[ni][e], acc[2 * mi + ni], 0, 0, 0);
-      }
-    };
-
-    // Pipeline: while chunk c is multiplied out of one LDS buffer, chunk c+1 (requested one iteration
-    // earlier) is written to the other and chunk c+2 is requested.  The operand fragments of a group of 8 contraction
-    // indices are read from LDS two groups ahead of their 16 MFMAs -- across the chunk boundary too: the barrier sits
-    // in the middle of a chunk, after every read of its buffer and every write of the next one, so the first two
-    // groups of chunk c+1 are read behind the barrier while the last two groups of chunk c run, and no wave starts a
-    // chunk by waiting for LDS.
-    fetch(c_begin);
-    stage(0);
-    if (c_begin + 1 < c_end) fetch(c_begin + 1);
+    float bw0[16], bw1[16];
+    f32x4 a0[4], a1[4];
+    fetch_a(c_begin);
+    fetch_b(bw0);
+    stage_a(0);
+    if (c_begin + 1 < c_end) fetch_a(c_begin + 1);
     __syncthreads();
     static_assert(BW_KC == 32, "four fragment groups per chunk");
-    f32x4 a0[NA], b0[NB], a1[NA], b1[NB];
-    load_frags(ldsA[0], ldsB[0], 0, a0, b0);
-    load_frags(ldsA[0], ldsB[0], 1, a1, b1);
-
-    for (long long c = c_begin; c < c_end; ++c) {
-      const int buf = (int)((c - c_begin) & 1);
+    load_a(ldsA[0], 0, a0);
+    load_a(ldsA[0], 1, a1);
+    // One chunk out of LDS buffer `buf`: the next chunk's frames operand is requested at its head (on every chunk,
+    // the last one's request reads frames past the range and is dropped: one path, so that the compiler's wait ahead
+    // of an MFMA counts these sixteen as younger than its operand), the next chunk's G tile goes to the other
+    // buffer behind the first MFMA group, the one after that is requested behind the second.  The barrier sits in
+    // the middle of the chunk, after every read of its buffer and every write of the other one, and the first
+    // fragments of the next chunk are read behind it while the last two groups run.
+    auto chunk = [&](long long c, int buf, const float (&bw)[16], float (&next)[16]) {
       const float* A = ldsA[buf];
-      const float* B = ldsB[buf];
-      // The scheduling barriers pin the order: each group's LDS reads go out ahead of the previous
-      // group's 16 MFMAs (left alone, the compiler sinks every read to just before its first use and
-      // the matrix pipe idles for the LDS latency every four MFMAs), and the LDS writes of chunk c+1
-      // and the global requests for chunk c+2 sit behind reads that are already on their way, with a
-      // whole MFMA group to hide them.
+      fetch_b(next);
       __builtin_amdgcn_sched_barrier(0);
-      mfma_group(a0, b0);
+      mfma_group(a0, bw, 0);
       __builtin_amdgcn_sched_barrier(0);
-      load_frags(A, B, 2, a0, b0);
-      if (c + 1 < c_end) stage(buf ^ 1);
+      load_a(A, 2, a0);
+      if (c + 1 < c_end) stage_a(buf ^ 1);
       __builtin_amdgcn_sched_barrier(0);
-      mfma_group(a1, b1);
+      mfma_group(a1, bw, 1);
       __builtin_amdgcn_sched_barrier(0);
-      load_frags(A, B, 3, a1, b1);
-      if (c + 2 < c_end) fetch(c + 2);
-      __syncthreads();  // buffer `buf` has been read for the last time, buffer `buf ^ 1` is complete
+      load_a(A, 3, a1);
+      if (c + 2 < c_end) fetch_a(c + 2);
+      __syncthreads();
       __builtin_amdgcn_sched_barrier(0);
-      mfma_group(a0, b0);
+      mfma_group(a0, bw, 2);
       __builtin_amdgcn_sched_barrier(0);
-      if (c + 1 < c_end) load_frags(ldsA[buf ^ 1], ldsB[buf ^ 1], 0, a0, b0);
+      if (c + 1 < c_end) load_a(ldsA[buf ^ 1], 0, a0);
       __builtin_amdgcn_sched_barrier(0);
-      mfma_group(a1, b1);
+      mfma_group(a1, bw, 3);
       __builtin_amdgcn_sched_barrier(0);
-      if (c + 1 < c_end) load_frags(ldsA[buf ^ 1], ldsB[buf ^ 1], 1, a1, b1);
+      if (c + 1 < c_end) load_a(ldsA[buf ^ 1], 1, a1);
+    };
+    for (long long c = c_begin; c < c_end; c += 2) {
+      chunk(c, 0, bw0, bw1);
+      if (c + 1 < c_end) chunk(c + 1, 1, bw1, bw0);
     }
   };
   if constexpr (SPARSE) {
@@ -475,53 +540,19 @@ __global__ __launch_bounds__(256, 2) void bw_gemm_kernel(const BwParams P) {
   } else {
     sweep(std::integral_constant<int, 4>{});
   }
-  const int alive = SPARSE ? alive_rt : 4;
 
-  // ---- epilogue: accumulator register r of lane (h, r32) is output row 8 (r/4) + 4 h + r%4, column r32
-  if constexpr (MODE == BW_MODE_BANK) {
-    const int tap = n0 + wave * 32 + r32;
-    if (tap < P.K) {
+  // accumulator register r of lane (h, r32) of block s is output row m0 + 32 s + 8 (r/4) + 4 h + r%4, column `tap`
+  if (tap < P.K) {
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        if (s >= alive) continue;
+    for (int s = 0; s < 4; ++s) {
+      if (s >= alive_rt) continue;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int pr = (int)m0 + s * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-          if ((pr >> 1) < P.n_half && (!SPARSE || (tap >= P.row_lo[pr] && tap < P.row_hi[pr])))
-            unsafeAtomicAdd(P.gw + (long long)logical_row(pr, P.n_half, P.packed) * P.K + tap, acc[s][r]);
-        }
+      for (int r = 0; r < 16; ++r) {
+        const int pr = (int)m0 + s * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+        if ((pr >> 1) < P.n_half && (!SPARSE || (tap >= P.row_lo[pr] && tap < P.row_hi[pr])))
+          unsafeAtomicAdd(P.gw + (long long)logical_row(pr, P.n_half, P.packed) * P.K + tap, acc[s][r]);
       }
     }
-  } else {
-    const int L = (int)g.L;
-#pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        // four consecutive frames per register quad
-        long long f = m0 + wm * 64 + mi * 32 + 8 * q + 4 * h;
-        long long b = f / g.T;
-        int t = (int)(f - b * g.T);
-#pragma unroll
-        for (int i = 0; i < 4; ++i, ++f) {
-          if (f < g.n_frames) {
-            float* __restrict__ row = P.gx + b * g.L;
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
-              const int tap = n0 + wn * 64 + ni * 32 + r32;
-              if (tap < P.K) {
-                int j = t * g.hop + tap - g.pad;
-                j = j < 0 ? -j : (j >= L ? 2 * (L - 1) - j : j);  // mirror padding folded back
-                unsafeAtomicAdd(row + j, acc[2 * mi + ni][4 * q + i]);
-              }
-            }
-          }
-          if (++t == g.T) {
-            t = 0;
-            ++b;
-          }
-        }
-      }
   }
 }
 
@@ -737,7 +768,7 @@ __device__ __forceinline__ f32x4 load4_guarded(const float* row, int c, int lim)
 
 constexpr int MEL_BW_SPEC = 0, MEL_BW_WEIGHTS = 1;
 
-// Same 128 x 128 tile, wave grid and MFMA as bw_gemm_kernel; these two contractions are small
+// Same 128 x 128 tile, wave grid and MFMA as bw_wave_kernel; these two contractions are small
 // (2 n_mels F flop per frame each, 3 % of the STFT's) and bound by reading / writing the [B, F, T]
 // arrays, so the chunk loop is the plain one: load, barrier, write LDS, barrier, multiply.
 //   MEL_BW_SPEC:    C[k, t] (one waveform)  A = W[m][k] (k-major: row = contraction index), B = g[b][m][t] (k-major)
@@ -1102,9 +1133,9 @@ hipError_t launch_bw_bank(const BwParams& p, hipStream_t stream) {
   const long long blocks = tiles * p.n_split;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   if (sparse)
-    hipLaunchKernelGGL((bw_gemm_kernel<BW_MODE_BANK, true>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL(bw_bank_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, p);
   else
-    hipLaunchKernelGGL((bw_gemm_kernel<BW_MODE_BANK, false>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL(bw_bank_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 
@@ -1125,7 +1156,7 @@ hipError_t launch_bw_wave(const BwParams& p, hipStream_t stream) {
   }
   const long long blocks = (p.gpitch / BW_MT) * (p.kp / BW_NT);
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((bw_gemm_kernel<BW_MODE_WAVE, false>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  hipLaunchKernelGGL(bw_wave_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 
