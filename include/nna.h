@@ -268,8 +268,13 @@ nna_status nna_cqt2010v2_workspace(const nna_plan* plan, long long B, long long 
 
 /* out_dev[B, n_bins, T] = constant-Q spectrogram of x_dev[B, L]; plan from nna_plan_cqt2010v2.
  * workspace_dev: caller-owned device memory, 16-byte aligned, of at least the size above; its
- * contents are overwritten and mean nothing afterwards.  Launches 2*octaves - 1 kernels on
- * hip_stream (one constant-Q contraction per octave, one decimation between octaves); nothing is allocated.  NNA_ERR_SHAPE if some octave's waveform is not longer
+ * contents are overwritten and mean nothing afterwards.  Launches 2*octaves - 1 kernels (one constant-Q contraction per
+ * octave, one decimation between octaves); nothing is allocated.  The decimations run on hip_stream; an octave's
+ * contraction needs only that octave's waveform, so the contractions go to two streams the plan owns (created with the
+ * plan, default priority), which wait for hip_stream's work queued before the call and for the decimation they need, and
+ * which hip_stream waits for before the call returns: to the caller the call is one piece of work on hip_stream, and
+ * under stream capture those streams join the capture and leave it again.  Calls on one plan from several host threads
+ * enqueue one after the other (a lock in the plan).  NNA_ERR_SHAPE if some octave's waveform is not longer
  * than the kernels' half length n_taps/2 or shorter than the filter's frame (fir_taps + 126
  * samples, rounded up to a multiple of 128). */
 nna_status nna_cqt2010v2(const nna_plan* plan, const float* x_dev, long long B, long long L, float* out_dev,

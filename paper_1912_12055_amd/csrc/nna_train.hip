@@ -675,11 +675,12 @@ __global__ __launch_bounds__(256, 2) void cq_wave_kernel(const BwParams P) {
       const int je = js + CW_SEG - 1 < jb ? js + CW_SEG - 1 : jb;
       fetch_b(bw0, k0, js);
       __syncthreads();  // every wave is done with the previous window
-      // window: frames q0 - je .. q0 - je + CW_WIN - 1 of rows k0 .. k0 + 31 (zero outside the waveform)
+      // window: frames q0 - je .. of rows k0 .. k0 + 31 (zero outside the waveform), as many as the tile's 128 rows
+      // reach over the shifts js .. je
       {
         const int row = tid >> 3;
-#pragma unroll
-        for (int i = 0; i < CW_WIN / 32; ++i) {
+        const int n_it = (je - js + BW_MT + 31) / 32;  // <= CW_WIN / 32
+        for (int i = 0; i < n_it; ++i) {
           const int w = 4 * (tid & 7) + 32 * i;
           *reinterpret_cast<f32x4*>(&ldsA[row * CW_PA + w]) =
               load_g4(P.gbuf, (long long)P.rows_pad * 32, k0 + row, gb * T, q0 - je + w, T);
