@@ -93,13 +93,13 @@ static nna_status make_cqt_trainable(nna_plan* plan) {
     }
     // heaviest tiles first (a tile's time goes with its live row blocks): the light ones fill the launch's tail
     std::stable_sort(tiles.begin(), tiles.end(), [](const int2& a, const int2& b) { return (a.x >> 16) > (b.x >> 16); });
-    // waveform gradient: how many rows (in chunks of 32; rows are ordered longest first) hold taps on each
+    // waveform gradient: how many rows (in chunks of CW_KC; rows are ordered longest first) hold taps on each
     // 128-tap tile, and from that, per 128-column tile of the hop, the running count over the hop-shifts
     for (int nt = 0; nt < n_nt; ++nt) {
       int r_max = 0;
       for (int r = 0; r < rows; ++r)
         if (plan->row_s[r] < (long long)(nt + 1) * nna::BW_NT && plan->row_e[r] > (long long)nt * nna::BW_NT) r_max = r + 1;
-      nt_chunks[nt] = (r_max + nna::BW_KC - 1) / nna::BW_KC;
+      nt_chunks[nt] = (r_max + nna::CW_KC - 1) / nna::CW_KC;
     }
     if (tiles.empty()) return fail(NNA_ERR_UNSUPPORTED, "the bank has no taps");
     const int J = (int)((K + plan->hop - 1) / plan->hop), n_ct = (plan->hop + nna::BW_NT - 1) / nna::BW_NT;
@@ -561,7 +561,7 @@ static nna_status cqt_backward_core(const nna_plan* plan, const float* x_dev, lo
     // downsampling plan) leaves most of every tile empty, and the plain frames x taps product over the zero-padded
     // row-major bank does less work (multiply-adds per frame: shifts x column tiles x row chunks x 128 x 32
     // against taps x rows).
-    const double gathered = (double)plan->n_shift * plan->n_ct * plan->n_kc * nna::BW_NT * nna::BW_KC;
+    const double gathered = (double)plan->n_shift * plan->n_ct * plan->n_kc * nna::BW_NT * nna::CW_KC;
     const double dense = (double)plan->kp * plan->rows_pad;
     if (plan->hop < nna::BW_NT && 2.0 * dense <= gathered) Q.shift_rng = nullptr;
     e = nna::launch_bw_wave(Q, stream);

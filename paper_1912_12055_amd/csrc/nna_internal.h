@@ -182,6 +182,7 @@ struct CqtParams {
 constexpr int BW_MT = 128;   // output tile rows per workgroup
 constexpr int BW_NT = 128;   // output tile columns per workgroup
 constexpr int BW_KC = 32;    // contraction chunk staged in LDS
+constexpr int CW_KC = 16;    // bank rows per chunk of the shift-gathering waveform gradient (cq_wave_kernel)
 
 struct BwParams {
   FrameGeom g;           // the batch (x may be NULL when only the waveform gradient is wanted)
@@ -205,7 +206,7 @@ struct BwParams {
   const int* row_lo;     // bank gradient: row r is a parameter on taps [row_lo[r], row_hi[r]) only
   const int* row_hi;
   // waveform gradient, gathered over the hop-shifts (see cq_wave_kernel): shift_rng[ct][kc], ct = 128-column
-  // tile of the hop, kc = chunk of BW_KC rows: first and last shift on which those rows hold taps (x > y: none)
+  // tile of the hop, kc = chunk of CW_KC rows: first and last shift on which those rows hold taps (x > y: none)
   const int2* shift_rng;
   int n_kc;              // row chunks listed per column tile
   int n_shift;           // hop-shifts: ceil(K / hop)

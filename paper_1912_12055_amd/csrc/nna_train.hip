@@ -563,7 +563,7 @@ __global__ __launch_bounds__(256, 2) void bw_bank_kernel(const BwParams P) {
 // inside the workgroup:
 //   out[q, c] = sum_r sum_j G[r, q - j] W[r, j hop + c],
 // a contraction over (row r, shift j) pairs whose A operand is G read j frames back.  Rows go in chunks
-// of BW_KC, the outer loop; for one chunk the frames q0 - j .. q0 - j + 127 of all its shifts form
+// of CW_KC, the outer loop; for one chunk the frames q0 - j .. q0 - j + 127 of all its shifts form
 // one window of G that stays in LDS while only W tiles stream.  Each padded sample is written once
 // (the atomic add only folds the mirrored samples onto the waveform).
 constexpr int CW_SEG = BW_MT;             // shifts served by one window
@@ -573,7 +573,7 @@ constexpr int CW_PA = CW_WIN + 4;         // its LDS pitch
 // WHOLE: every W tile of the launch lies inside the hop and inside the padded bank row (the launcher checks it).
 template <bool WHOLE>
 __global__ __launch_bounds__(256, 2) void cq_wave_kernel(const BwParams P) {
-  __shared__ __attribute__((aligned(16))) float ldsA[BW_KC * CW_PA];
+  __shared__ __attribute__((aligned(16))) float ldsA[CW_KC * CW_PA];
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -606,49 +606,63 @@ __global__ __launch_bounds__(256, 2) void cq_wave_kernel(const BwParams P) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[s][r] = 0.f;
 
+  // Rows go in chunks of CW_KC = 16 (8 bins: the kernels of 16 adjacent bins differ by 2^(16/24) in length, and a
+  // chunk runs over the shifts of its longest), shifts in pairs: the 32 contraction indices of an MFMA sweep are
+  // 16 rows x 2 shifts, index 16 s + 8 kg + 4 h + e = shift j + s, row k0 + 8 kg + 4 h + e.
   // A wave owns 32 columns of the tile and all four of its 32-row blocks, so the W values it multiplies are its own:
-  // W[k0 + 8 kg + 4 h + e][j hop + n0 + wave 32 + r32] is element 4 kg + e of lane (h, r32), the B operand of the MFMA
-  // as it stands.  They go from memory straight into registers, one shift ahead of their use (a shift is 64 MFMAs of
-  // 64 cycles, far longer than a load takes), and never through LDS: only the G window is shared, and the waves of a
-  // workgroup meet once per window, not once per shift (staged through LDS with a barrier per shift, 45 % of the wave
-  // cycles were waits).  Columns past the hop belong to the next shift and read as zero.
+  // W[k0 + 8 kg + 4 h + e][(j + s) hop + n0 + wave 32 + r32] is element 8 s + 4 kg + e of lane (h, r32), the B operand
+  // of the MFMA as it stands.  They go from memory straight into registers, one pair of shifts ahead of their use (a
+  // pair is 64 MFMAs of 64 cycles, far longer than a load takes), and never through LDS: only the G window is shared,
+  // and the waves of a workgroup meet once per window, not once per shift (staged through LDS with a barrier per
+  // shift, 45 % of the wave cycles were waits).  Columns past the hop belong to the next shift and read as zero, and
+  // so does the second shift of a pair past the last one.
   float bw0[16], bw1[16];
   const int colw = n0 + wave * 32;  // first column of the wave
   // address = a base every lane of the wave shares (scalar registers) + a 32-bit lane offset that never changes
   const unsigned lane_w = (unsigned)((4u * h * (unsigned)P.kp + r32) * sizeof(float));
-  auto fetch_b = [&](float (&bw)[16], int k0, int j) {
-    const long long tb = (long long)j * g.hop + colw;
-    const char* row = reinterpret_cast<const char*>(P.wrm + (long long)k0 * P.kp + tb);
-    const bool in = WHOLE || (colw + r32 < g.hop && tb + r32 < P.kp);
+  auto fetch_b = [&](float (&bw)[16], int k0, int j, int je) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const char* rp = row + (long long)(8 * (i >> 2) + (i & 3)) * P.kp * (long long)sizeof(float);
-      bw[i] = in ? *reinterpret_cast<const float*>(rp + lane_w) : 0.f;
+    for (int s2 = 0; s2 < 2; ++s2) {
+      const bool there = j + s2 <= je;
+      const long long tb = (long long)(there ? j + s2 : je) * g.hop + colw;
+      const char* row = reinterpret_cast<const char*>(P.wrm + (long long)k0 * P.kp + tb);
+      const bool in = there && (WHOLE || (colw + r32 < g.hop && tb + r32 < P.kp));
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const char* rp = row + (long long)(8 * (i >> 2) + (i & 3)) * P.kp * (long long)sizeof(float);
+        if constexpr (WHOLE) {
+          const float v = *reinterpret_cast<const float*>(rp + lane_w);
+          bw[8 * s2 + i] = there ? v : 0.f;
+        } else {
+          bw[8 * s2 + i] = in ? *reinterpret_cast<const float*>(rp + lane_w) : 0.f;
+        }
+      }
     }
   };
-  // lane (h, r32) holds contraction indices 8 kg + 4 h + e of tile row r32; `w` = window index of tile row 0.
-  // A 32-row block of the tile whose frames q - j all fall outside the waveform on this shift has a zero A
-  // operand (the first and last row tiles of a waveform are half such blocks): it is skipped.  The live blocks of a
-  // shift are a run lo .. hi - 1.
-  auto load_a = [&](int w, int kg, int lo, int hi, f32x4 (&a)[4]) {
+  // Fragment group g4 = 0..3 of a pair: shift g4 / 2, rows 8 (g4 % 2) + 4 h + e; `w` = window index of tile row 0 on the
+  // pair's first shift (one less on the second).
+  // A 32-row block of the tile whose frames q - j all fall outside the waveform has a zero A operand (the first and
+  // last row tiles of a waveform are half such blocks): it is skipped.  The live blocks of a pair are a run lo .. hi - 1.
+  auto load_a = [&](int w, int g4, int lo, int hi, f32x4 (&a)[4]) {
+    const int ws = w - (g4 >> 1) > 0 ? w - (g4 >> 1) : 0;  // (a pair's missing second shift: its W values are zero)
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
       if (mi >= lo && mi < hi) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) a[mi][e] = ldsA[(8 * kg + 4 * h + e) * CW_PA + w + mi * 32 + r32];
+        for (int e = 0; e < 4; ++e) a[mi][e] = ldsA[(8 * (g4 & 1) + 4 * h + e) * CW_PA + ws + mi * 32 + r32];
       }
   };
-  auto mfma_group = [&](const f32x4 (&a)[4], const float (&bw)[16], int kg, int lo, int hi) {
+  auto mfma_group = [&](const f32x4 (&a)[4], const float (&bw)[16], int g4, int lo, int hi) {
 #pragma unroll
     for (int e = 0; e < 4; ++e)
 #pragma unroll
       for (int mi = 0; mi < 4; ++mi)
         if (mi >= lo && mi < hi)
-          acc[mi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][e], bw[4 * kg + e], acc[mi], 0, 0, 0);
+          acc[mi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][e], bw[4 * g4 + e], acc[mi], 0, 0, 0);
   };
-  // the 64 MFMAs of a shift; lo_c, hi_c are compile-time constants for the runs that reach an end of the tile (a
-  // run-time test puts a branch around every MFMA), plain integers otherwise
-  auto shift_mfmas = [&](int w, const float (&bw)[16], auto lo_c, auto hi_c) {
+  // the 64 MFMAs of a pair of shifts; lo_c, hi_c are compile-time constants for the runs that reach an end of the
+  // tile (a run-time test puts a branch around every MFMA), plain integers otherwise
+  auto pair_mfmas = [&](int w, const float (&bw)[16], auto lo_c, auto hi_c) {
     const int lo = lo_c, hi = hi_c;
     f32x4 a0[4], a1[4];
     load_a(w, 0, lo, hi, a0);
@@ -668,64 +682,66 @@ __global__ __launch_bounds__(256, 2) void cq_wave_kernel(const BwParams P) {
   using std::integral_constant;
 
   for (int kc = 0; kc < P.n_kc; ++kc) {
-    const int2 rng = P.shift_rng[ct * P.n_kc + kc];  // shifts on which rows k0 .. k0 + 31 hold taps
+    const int2 rng = P.shift_rng[ct * P.n_kc + kc];  // shifts on which rows k0 .. k0 + 15 hold taps
     const int ja = rng.x > j_lo ? rng.x : j_lo, jb = rng.y < j_hi ? rng.y : j_hi;
-    const int k0 = kc * BW_KC;
+    const int k0 = kc * CW_KC;
     for (int js = ja; js <= jb; js += CW_SEG) {
       const int je = js + CW_SEG - 1 < jb ? js + CW_SEG - 1 : jb;
-      fetch_b(bw0, k0, js);
+      fetch_b(bw0, k0, js, je);
       __syncthreads();  // every wave is done with the previous window
-      // window: frames q0 - je .. of rows k0 .. k0 + 31 (zero outside the waveform), as many as the tile's 128 rows
+      // window: frames q0 - je .. of rows k0 .. k0 + 15 (zero outside the waveform), as many as the tile's 128 rows
       // reach over the shifts js .. je
       {
-        const int row = tid >> 3;
-        const int n_it = (je - js + BW_MT + 31) / 32;  // <= CW_WIN / 32
+        const int row = tid >> 4;
+        const int n_it = (je - js + BW_MT + 63) / 64;  // <= CW_WIN / 64
         for (int i = 0; i < n_it; ++i) {
-          const int w = 4 * (tid & 7) + 32 * i;
+          const int w = 4 * (tid & 15) + 64 * i;
           *reinterpret_cast<f32x4*>(&ldsA[row * CW_PA + w]) =
               load_g4(P.gbuf, (long long)P.rows_pad * 32, k0 + row, gb * T, q0 - je + w, T);
         }
       }
       __syncthreads();
-      // one shift: the W values of the next one are requested before its MFMAs start
-      auto step = [&](int j, const float (&bw)[16], float (&next)[16]) {
-        // Requested on every shift, the last of a window included (it asks for its own values again): the compiler's
+      // one pair of shifts j, j + 1: the W values of the next pair are requested before its MFMAs start
+      auto pair = [&](int j, const float (&bw)[16], float (&next)[16]) {
+        // Requested on every pair, the last of a window included (it asks for its own values again): the compiler's
         // wait ahead of an MFMA allows as many loads in flight as every path to it guarantees were requested after the
-        // operand's own, and one path without these 16 made every MFMA of every shift wait for the next shift's values.
-        fetch_b(next, k0, j + 1 <= je ? j + 1 : je);
+        // operand's own, and one path without these 16 made every MFMA of every pair wait for the next pair's values.
+        fetch_b(next, k0, j + 2 <= je ? j + 2 : j, je);
         const int w = je - j;
-        // block mi holds frames q0 + 32 mi - j .. + 31: live while the last of them is >= 0 and the first < T
+        // block mi holds frames q0 + 32 mi - j .. + 31 on the first shift (one frame earlier on the second): live while
+        // the last of them is >= 0 on the first shift and the first < T on the second
+        const int back = j + 1 <= je ? 1 : 0;
         int lo = 0, hi = 0;
 #pragma unroll
         for (int mi = 0; mi < 4; ++mi) {
           const int t_first = q0 + mi * 32 - j;
           lo += t_first + 31 < 0 ? 1 : 0;
-          hi += t_first < T ? 1 : 0;
+          hi += t_first - back < T ? 1 : 0;
         }
         if (lo >= hi) return;
         if (lo == 0 && hi == 4) {
-          shift_mfmas(w, bw, integral_constant<int, 0>{}, integral_constant<int, 4>{});
+          pair_mfmas(w, bw, integral_constant<int, 0>{}, integral_constant<int, 4>{});
         } else if (hi == 4) {
           if (lo == 1)
-            shift_mfmas(w, bw, integral_constant<int, 1>{}, integral_constant<int, 4>{});
+            pair_mfmas(w, bw, integral_constant<int, 1>{}, integral_constant<int, 4>{});
           else if (lo == 2)
-            shift_mfmas(w, bw, integral_constant<int, 2>{}, integral_constant<int, 4>{});
+            pair_mfmas(w, bw, integral_constant<int, 2>{}, integral_constant<int, 4>{});
           else
-            shift_mfmas(w, bw, integral_constant<int, 3>{}, integral_constant<int, 4>{});
+            pair_mfmas(w, bw, integral_constant<int, 3>{}, integral_constant<int, 4>{});
         } else if (lo == 0) {
           if (hi == 3)
-            shift_mfmas(w, bw, integral_constant<int, 0>{}, integral_constant<int, 3>{});
+            pair_mfmas(w, bw, integral_constant<int, 0>{}, integral_constant<int, 3>{});
           else if (hi == 2)
-            shift_mfmas(w, bw, integral_constant<int, 0>{}, integral_constant<int, 2>{});
+            pair_mfmas(w, bw, integral_constant<int, 0>{}, integral_constant<int, 2>{});
           else
-            shift_mfmas(w, bw, integral_constant<int, 0>{}, integral_constant<int, 1>{});
+            pair_mfmas(w, bw, integral_constant<int, 0>{}, integral_constant<int, 1>{});
         } else {
-          shift_mfmas(w, bw, lo, hi);
+          pair_mfmas(w, bw, lo, hi);
         }
       };
-      for (int j = js; j <= je; j += 2) {
-        step(j, bw0, bw1);
-        if (j + 1 <= je) step(j + 1, bw1, bw0);
+      for (int j = js; j <= je; j += 4) {
+        pair(j, bw0, bw1);
+        if (j + 2 <= je) pair(j + 2, bw1, bw0);
       }
     }
   }
@@ -1144,7 +1160,7 @@ hipError_t launch_bw_wave(const BwParams& p, hipStream_t stream) {
   clear_stale_error();
   if (!bw_shapes_ok(p)) return hipErrorInvalidValue;
   if (p.shift_rng) {
-    if (p.n_shift < 1 || p.n_kc < 1 || p.n_kc > p.rows_pad / BW_KC || p.n_ct != (p.g.hop + BW_NT - 1) / BW_NT ||
+    if (p.n_shift < 1 || p.n_kc < 1 || p.n_kc > p.rows_pad / CW_KC || p.n_ct != (p.g.hop + BW_NT - 1) / BW_NT ||
         p.n_qt != (p.g.T + p.n_shift - 1 + BW_MT - 1) / BW_MT || (long long)p.n_shift * p.g.hop < p.K)
       return hipErrorInvalidValue;
     const long long blocks = p.g.B * p.n_qt * p.n_ct;
