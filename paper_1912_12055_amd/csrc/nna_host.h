@@ -81,7 +81,7 @@ struct nna_plan {
   hipEvent_t ev_fork = nullptr;
   hipEvent_t ev_fir[OCT_EVENTS] = {};
   hipEvent_t ev_oct[OCT_EVENTS] = {};
-  std::mutex oct_mutex;
+  mutable std::mutex oct_mutex;
   int fir_taps = 0;
   std::vector<double> h_fir;
   std::vector<nna::CqtItem> h_items;

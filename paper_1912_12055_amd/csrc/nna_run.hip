@@ -379,7 +379,7 @@ static nna_status run_octaves(const nna_plan* plan, int kind, const float* x_dev
   // is one piece of work on that stream (under stream capture: a fork and a join).
   hipStream_t main_stream = static_cast<hipStream_t>(hip_stream);
   const bool forked = n_oct > 1 && plan->oct_stream[0] != nullptr;
-  std::unique_lock<std::mutex> lock(const_cast<nna_plan*>(plan)->oct_mutex, std::defer_lock);
+  std::unique_lock<std::mutex> lock(plan->oct_mutex, std::defer_lock);
   if (forked) {
     lock.lock();
     if ((e = hipEventRecord(plan->ev_fork, main_stream)) != hipSuccess) return fail_hip(e, "hipEventRecord");

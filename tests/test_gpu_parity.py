@@ -541,6 +541,42 @@ def test_cqt2010v2_workspace_and_shape_checks(nb):
     assert torch.equal(a, b)
 
 
+def test_cqt2010v2_one_plan_two_host_threads_two_streams(nb):
+    """The octave loop forks onto streams the plan owns and joins them again; calls on one plan from two host
+    threads, each on a stream and with a workspace of its own, must give what the calls give one after the other."""
+    import threading
+    import torch
+    _say("cqt2010v2: one plan, two host threads on two streams")
+    plan = nb.nna_plan_cqt2010v2(sr=22050, hop=256, fmin=110.0, n_bins=48, bins_per_octave=12, device=0)
+    B, L = 6, 30000
+    xs = [_dev(_rand(B, L, 4100 + i)) for i in range(2)]
+    need = nb.nna_cqt2010v2_workspace(plan, B, L)
+    expect = [nb.nna_cqt2010v2(plan, x) for x in xs]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(device="cuda:0") for _ in range(2)]
+    wss = [torch.empty(need, dtype=torch.uint8, device="cuda:0") for _ in range(2)]
+    outs = [torch.full_like(e, float("nan")) for e in expect]
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(i):
+        try:
+            for _ in range(20):
+                nb.nna_cqt2010v2(plan, xs[i], out=outs[i], workspace=wss[i], stream=streams[i].cuda_stream)
+        except Exception as e:  # noqa: BLE001 -- reported by the asserting thread
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for got, want in zip(outs, expect):
+        assert torch.equal(got, want)
+
+
 # ---------------------------------------------------------------------------------------
 # CQT with frequency-domain kernels (un-windowed STFT x spectral kernels, one kernel)
 # ---------------------------------------------------------------------------------------
