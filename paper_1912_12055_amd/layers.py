@@ -205,7 +205,8 @@ class _Cqt(_Trainable):
     def __init__(self, trainable):
         super().__init__()
         if trainable:
-            raise NotImplementedError("trainable kernels: only CQT1992v2 (time-domain kernels at one rate)")
+            raise NotImplementedError("this wrapper hooks only CQT1992v2 into autograd; the other constant-Q layers train through "
+                                      "binding.nna_cqt2010v2_backward / nna_cqt1992_backward / nna_cqt2010_backward")
 
 
 class CQT1992v2(_Cqt):
