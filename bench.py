@@ -410,7 +410,59 @@ def main() -> int:
             "mfma_frac": round(alg / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
             "mfma_peak_tflops": PEAK_FP32_MFMA_TFLOPS,
         }
-        del gcq, ws_bw, p_trv
+        del ws_bw, p_trv
+        # backward pass of the downsampling CQT with trainable frequency-domain kernels (both stages' kernels are
+        # weights: the DFT bank of the un-windowed STFT and the spectral kernels); flops: its forward pass three times
+        p_trf = nb.nna_plan_trainable(nb.nna_plan_cqt2010(sr=sr, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24, device=0))
+        ws_bw = torch.empty(nb.nna_cqt2010_backward_workspace(p_trf, B, L), dtype=torch.uint8, device=dev)
+        for _ in range(max(1, args.warmup)):
+            nb.nna_cqt2010_backward(p_trf, x5, gcq, workspace=ws_bw)
+        ev = []
+        for _ in range(args.steps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            nb.nna_cqt2010_backward(p_trf, x5, gcq, workspace=ws_bw)
+            b.record()
+            ev.append((a, b))
+        torch.cuda.synchronize()
+        ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+        alg = 3 * p_trf.info()["algorithmic_flops_per_frame"] * B * T
+        extras["cqt2010_backward"] = {
+            "ms": round(ms, 4),
+            "gsamples_per_s": round(B * L / ms / 1e6, 4),
+            "algorithmic_tflops": round(alg / ms / 1e9, 3),
+            "mfma_frac": round(alg / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+            "mfma_peak_tflops": PEAK_FP32_MFMA_TFLOPS,
+        }
+        del gcq, ws_bw, p_trf
+        # backward pass of the one-rate CQT with trainable frequency-domain kernels, on the 152-waveform batch of its
+        # forward figure above (84 bins, n_fft 16,384)
+        x92 = torch.from_numpy(signals.batch(3, list(range(152)), workers=16)).to(dev)
+        p_tr92 = nb.nna_plan_trainable(nb.nna_plan_cqt1992(sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, device=0))
+        B92, L92 = x92.shape
+        T92 = 1 + L92 // 512
+        g92 = torch.ones((B92, 84, T92), dtype=torch.float32, device=dev)
+        ws_bw = torch.empty(nb.nna_cqt1992_backward_workspace(p_tr92, B92, L92), dtype=torch.uint8, device=dev)
+        for _ in range(max(1, args.warmup)):
+            nb.nna_cqt1992_backward(p_tr92, x92, g92, workspace=ws_bw)
+        ev = []
+        for _ in range(args.steps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            nb.nna_cqt1992_backward(p_tr92, x92, g92, workspace=ws_bw)
+            b.record()
+            ev.append((a, b))
+        torch.cuda.synchronize()
+        ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+        alg = 3 * p_tr92.info()["algorithmic_flops_per_frame"] * B92 * T92
+        extras["cqt1992_backward_152x220500"] = {
+            "ms": round(ms, 4),
+            "gsamples_per_s": round(B92 * L92 / ms / 1e6, 4),
+            "algorithmic_tflops": round(alg / ms / 1e9, 3),
+            "mfma_frac": round(alg / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+            "mfma_peak_tflops": PEAK_FP32_MFMA_TFLOPS,
+        }
+        del x92, g92, ws_bw, p_tr92
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -409,7 +409,11 @@ static nna_status stft_backward_core(const nna_plan* plan, const float* x_dev, l
   P.pout = pout;
   P.gbuf = gbuf;
   P.gpitch = 32;  // G is stored in blocks of 32 frames: [frame / 32][packed row][frame % 32]
-  e = nna::launch_stft(P, nna::ST_MODE_GRAD, stream);
+  // (a complex-format output is C itself: its gradient is G, and nothing needs to be recomputed)
+  if (fmt == NNA_OUT_COMPLEX && !pout)
+    e = nna::launch_g_from_complex(gbuf, gout_dev, n_frames, (int)T, out_bins, plan->rows_pad, plan->n_half, packed, stream);
+  else
+    e = nna::launch_stft(P, nna::ST_MODE_GRAD, stream);
   if (e != hipSuccess) return fail_hip(e, "kernel launch");
   // 2. the two contractions with G
   nna::BwParams Q;

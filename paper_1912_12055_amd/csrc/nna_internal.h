@@ -300,6 +300,9 @@ hipError_t launch_mel_from_logical(const float* w, float* frag, float* wnyq, flo
                                    int n_pass, int fp, hipStream_t stream);
 hipError_t launch_fill_zero(float* p, long long n, hipStream_t stream);
 hipError_t launch_fill_zero_frames(float* gbuf, long long rows_pad, long long f0, long long f1, hipStream_t stream);
+// G <- the upstream gradient of a complex-format output, re-laid out (see g_from_complex_kernel)
+hipError_t launch_g_from_complex(float* gbuf, const float* gout, long long n_frames, int T, int out_rows, int rows_pad,
+                                 int n_half, int packed, hipStream_t stream);
 hipError_t launch_bank_from_logical(const BankPermuteParams& p, hipStream_t stream);  // logical -> bank, wrm
 hipError_t launch_bank_to_rowmajor(const BankPermuteParams& p, hipStream_t stream);   // bank -> wrm
 hipError_t launch_bank_to_logical(const BankPermuteParams& p, hipStream_t stream);    // wrm -> logical

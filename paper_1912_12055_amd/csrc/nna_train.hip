@@ -143,6 +143,29 @@ __global__ __launch_bounds__(256) void fir_transpose_add_kernel(const FirTParams
     }
 }
 
+// G of a stage whose output is the transform itself (complex format): the upstream gradient as it stands, moved into
+// the blocked layout [frame / 32][packed row][frame % 32].  Packed banks keep (Re_0, Re_{N/2}) in rows 0, 1 and drop
+// the two identically-zero sine rows; rows past the bank's are written as zeros.  One workgroup per block of 32
+// frames: 8 rows x 32 frames per step, 128-byte runs on both sides.
+__global__ __launch_bounds__(256) void g_from_complex_kernel(float* __restrict__ gbuf, const float* __restrict__ gout,
+                                                             long long n_frames, int T, int out_rows, int rows_pad,
+                                                             int n_half, int packed) {
+  const long long f = (long long)blockIdx.x * 32 + (threadIdx.x & 31);
+  if (f >= n_frames) return;
+  const long long b = f / T;
+  const int t = (int)(f - b * T);
+  const float* __restrict__ gp = gout + b * (long long)out_rows * T + t;
+  float* __restrict__ Gp = gbuf + (long long)blockIdx.x * rows_pad * 32 + (threadIdx.x & 31);
+  for (int pr = threadIdx.x >> 5; pr < rows_pad; pr += 8) {
+    float v = 0.f;
+    if ((pr >> 1) < n_half) {
+      const int lrow = packed && pr < 2 ? (pr == 0 ? 0 : 2 * n_half) : pr;
+      v = gp[(long long)lrow * T];
+    }
+    Gp[(long long)pr * 32] = v;
+  }
+}
+
 // frames [f0, f1) of every row of the blocked G buffer [frame / 32][rows_pad][frame % 32]
 __global__ void fill_zero_frames_kernel(float* __restrict__ p, long long rows_pad, long long f0, long long f1) {
   const long long w = f1 - f0, n = rows_pad * w;
@@ -1113,6 +1136,18 @@ hipError_t launch_cqt_bank_to_logical(const CqtBankParams& p, hipStream_t stream
   const long long n = (long long)p.rows * p.K;
   if (n < 1 || (n + 255) / 256 > 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(cqt_bank_to_logical_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_g_from_complex(float* gbuf, const float* gout, long long n_frames, int T, int out_rows, int rows_pad,
+                                 int n_half, int packed, hipStream_t stream) {
+  clear_stale_error();
+  if (n_frames < 1 || T < 1 || rows_pad < 1 || 2 * n_half > rows_pad || (packed ? 2 * n_half + 1 : 2 * n_half) > out_rows)
+    return hipErrorInvalidValue;
+  const long long blocks = (n_frames + 31) / 32;
+  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(g_from_complex_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, gbuf, gout, n_frames, T, out_rows,
+                     rows_pad, n_half, packed);
   return hipGetLastError();
 }
 
