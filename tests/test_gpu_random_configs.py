@@ -239,3 +239,92 @@ def test_random_cqt_and_mel_backward(nb, seed):
         g = g.cpu().numpy().astype(np.float64)
         e = np.abs(g - r).max() / np.abs(r).max()
         assert np.all(np.isfinite(g)) and e < TOL, (name, e)
+
+
+def _peak(got, ref):
+    return float(np.abs(np.asarray(got, dtype=np.float64) - ref).max() / np.abs(ref).max())
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_downsampling_and_spectral_backward(nb, seed):
+    """Backward passes of the three other constant-Q layers (downsampling with time-domain kernels; frequency-domain
+    kernels at one rate and downsampling) on configurations nobody hand-picked."""
+    import torch
+    rng = np.random.default_rng([19, seed])
+    sr = int(rng.choice([8000, 16000, 22050]))
+    bpo = int(rng.choice([4, 6, 12]))
+    n_oct = int(rng.integers(1, 4))
+    n_bins = int(n_oct * bpo - rng.integers(0, max(1, bpo // 2)))
+    top = float(rng.uniform(0.06, 0.4)) * sr / 2.0 ** (1.0 / bpo)   # low tops: top-octave kernels of up to ~2,000 taps
+    fmin = float(top / 2.0 ** ((n_bins - 1) / bpo) * rng.uniform(0.6, 1.0))
+    hop = int(rng.choice([16, 32, 64, 128]))                 # multiples of 2^(octaves - 1)
+    fir = int(rng.choice([31, 63, 127]))
+    fmt = int(rng.choice([0, 1, 3]))                         # magnitude, power, complex (log / phase: ill-conditioned)
+    B = int(rng.choice([1, 2, 5]))
+    n_oct = -(-n_bins // bpo)
+    taps_top = oracle.cqt2010_default_taps(sr, fmin, n_bins, bpo)
+    frame = (fir + 126 + 127) // 128 * 128                   # the filter stage's frame (see nna_cqt2010v2)
+    L = max(taps_top // 2 + 2, frame) * 2 ** (n_oct - 1) + int(rng.integers(100, 3000))
+    _say(f"random downsampling / spectral backward seed={seed}: sr={sr} fmin={fmin:.1f} bins={n_bins}/{bpo} hop={hop} "
+         f"fir={fir} fmt={fmt} B={B} L={L}")
+    x = _wave(rng, B, L)
+    kw = dict(hop=hop, n_bins=n_bins, bins_per_octave=bpo, fir_taps=fir, fmt=fmt)
+
+    # time-domain kernels, downsampling
+    plan = nb.nna_plan_trainable(nb.nna_plan_cqt2010v2(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo,
+                                                       fir_taps=fir, fmt=fmt, device=0))
+    _, mask = oracle.cqt2010v2_bank(sr, fmin, n_bins, bpo)
+    W = nb.nna_plan_get_bank(plan).cpu().numpy()
+    W = np.where(mask, W * (1.0 + 0.2 * rng.standard_normal(W.shape)), 0).astype(np.float32)
+    nb.nna_plan_set_bank(plan, _dev(W))
+    gout = rng.standard_normal(oracle.cqt2010v2_bank_forward(x, W, **kw).shape).astype(np.float32)
+    ref_gw, ref_gx = oracle.cqt2010v2_bank_backward(x, W, mask, gout, **kw)
+    gw, gx = nb.nna_cqt2010v2_backward(plan, _dev(x), _dev(gout))
+    torch.cuda.synchronize()
+    gw = gw.cpu().numpy()
+    assert np.isfinite(gw).all() and not gw[~mask].any()
+    assert _peak(gw, ref_gw) < TOL and _peak(gx.cpu().numpy(), ref_gx) < TOL
+
+    # frequency-domain kernels, downsampling
+    plan = nb.nna_plan_trainable(nb.nna_plan_cqt2010(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo,
+                                                     fir_taps=fir, fmt=fmt, device=0))
+    Wd = nb.nna_plan_get_bank(plan).cpu().numpy()
+    Y = nb.nna_plan_get_spectral_kernels(plan).cpu().numpy()
+    dmask = oracle.dft_bank_parameter_mask(Wd.shape[1])
+    Wd = np.where(dmask, Wd * (1.0 + 0.1 * rng.standard_normal(Wd.shape)), 0).astype(np.float32)
+    Y = (Y * (1.0 + 0.2 * rng.standard_normal(Y.shape))).astype(np.float32)
+    nb.nna_plan_set_bank(plan, _dev(Wd))
+    nb.nna_plan_set_spectral_kernels(plan, _dev(Y))
+    gout = rng.standard_normal(oracle.cqt2010_bank_forward(x, Wd, Y, **kw).shape).astype(np.float32)
+    ref = oracle.cqt2010_bank_backward(x, Wd, Y, gout, **kw)
+    got = nb.nna_cqt2010_backward(plan, _dev(x), _dev(gout))
+    torch.cuda.synchronize()
+    for g, r, name in zip(got, ref, ("spectral kernels", "bank", "waveform")):
+        g = g.cpu().numpy()
+        assert np.isfinite(g).all() and _peak(g, r) < TOL, (name, _peak(g, r))
+
+    # frequency-domain kernels, one rate (its n_fft holds the longest kernel: keep that one short)
+    bins1 = min(n_bins, 2 * bpo)
+    fmin1 = float(top / 2.0 ** ((bins1 - 1) / bpo))
+    hop1 = int(rng.choice([32, 64, 100, 128]))
+    center = bool(rng.integers(0, 2))
+    plan = nb.nna_plan_trainable(nb.nna_plan_cqt1992(sr=sr, hop=hop1, fmin=fmin1, n_bins=bins1, bins_per_octave=bpo,
+                                                     center=center, fmt=fmt, device=0))
+    Wd = nb.nna_plan_get_bank(plan).cpu().numpy()
+    Y = nb.nna_plan_get_spectral_kernels(plan).cpu().numpy()
+    n_fft = Wd.shape[1]
+    dmask = oracle.dft_bank_parameter_mask(n_fft)
+    Wd = np.where(dmask, Wd * (1.0 + 0.1 * rng.standard_normal(Wd.shape)), 0).astype(np.float32)
+    Y = (Y * (1.0 + 0.2 * rng.standard_normal(Y.shape))).astype(np.float32)
+    nb.nna_plan_set_bank(plan, _dev(Wd))
+    nb.nna_plan_set_spectral_kernels(plan, _dev(Y))
+    L1 = (n_fft // 2 + 1 if center else n_fft) + int(rng.integers(0, 20)) * hop1 + int(rng.integers(0, hop1))
+    x1 = _wave(rng, B, L1)
+    _say(f"  one rate: bins={bins1} fmin={fmin1:.1f} hop={hop1} n_fft={n_fft} center={center} L={L1}")
+    gout = rng.standard_normal(oracle.cqt1992_bank_forward(x1, Wd, Y, hop=hop1, center=center, fmt=fmt).shape).astype(np.float32)
+    ref = oracle.cqt1992_bank_backward(x1, Wd, Y, gout, hop=hop1, center=center, fmt=fmt)
+    got = nb.nna_cqt1992_backward(plan, _dev(x1), _dev(gout))
+    torch.cuda.synchronize()
+    for g, r, name in zip(got, ref, ("spectral kernels", "bank", "waveform")):
+        g = g.cpu().numpy()
+        assert np.isfinite(g).all() and _peak(g, r) < TOL, (name, _peak(g, r))
