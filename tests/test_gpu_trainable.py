@@ -498,6 +498,46 @@ def test_cqt2010v2_backward_parity_small(nb, case):
     assert none is None and _peak_err(gx1.cpu().numpy(), ref_gx) < TOL
 
 
+def test_cqt2010v2_backward_config5_full_sampled(nb):
+    # the 1,770-waveform batch through the seven octaves (the launch shapes bench.py times: hops 512 .. 8, all three
+    # waveform-gradient kernels, 44 x 1770 tiles of the transposed decimation); the upstream gradient is non-zero on
+    # seven waveforms only, so the oracle's sum over those is the whole kernel gradient
+    import torch
+    _say("cqt2010v2 backward config 5 (1770 x 176400 @ 44100 Hz, 168 bins, 7 octaves) sampled waveforms")
+    wl = signals.WORKLOADS[5]
+    B, L = wl["B"], wl["L"]
+    x = torch.empty((B, L), dtype=torch.float32, device="cuda:0")
+    for s in range(0, B, 128):
+        idx = list(range(s, min(B, s + 128)))
+        x[s:s + len(idx)] = torch.from_numpy(signals.batch(5, idx)).to("cuda:0")
+    sampled = SAMPLED_BW[::2] + [1769]
+    plan = _cqt2010v2_plan(nb, 44100, 32.70, 168, 24, 512, 0, oracle.MAGNITUDE)
+    _, mask = oracle.cqt2010v2_bank(44100, 32.70, 168, 24)
+    rng = np.random.default_rng(56)
+    W = nb.nna_plan_get_bank(plan).cpu().numpy()
+    W = np.where(mask, W * (1.0 + 0.1 * rng.standard_normal(W.shape)), 0).astype(np.float32)
+    nb.nna_plan_set_bank(plan, _dev(W))
+    T = 1 + L // 512
+    gs = rng.standard_normal((len(sampled), 168, T)).astype(np.float32)
+    gout = torch.zeros((B, 168, T), dtype=torch.float32, device="cuda:0")
+    gout[sampled] = torch.from_numpy(gs).to("cuda:0")
+    gw, gx = nb.nna_cqt2010v2_backward(plan, x, gout)
+    torch.cuda.synchronize()
+    _say("  gpu done; oracle on the sampled waveforms")
+    xs = signals.batch(5, sampled)
+    ref_gw, ref_gx = oracle.cqt2010v2_bank_backward(xs, W, mask, gs, hop=512, n_bins=168, bins_per_octave=24,
+                                                    fir_taps=oracle.FIR_TAPS, fmt=oracle.MAGNITUDE)
+    gw = gw.cpu().numpy()
+    assert np.isfinite(gw).all() and not gw[~mask].any()
+    e_w = _peak_err(gw, ref_gw)
+    e_x = _peak_err(gx[sampled].cpu().numpy(), ref_gx)
+    _say(f"  bank gradient {e_w:.3e}, waveform gradient {e_x:.3e}")
+    assert e_w < TOL and e_x < TOL
+    rest = torch.ones(B, dtype=torch.bool, device="cuda:0")
+    rest[sampled] = False
+    assert not gx[rest].any()
+
+
 def test_cqt2010v2_backward_refuses_wrong_plans_and_workspaces(nb):
     import torch
     plan = nb.nna_plan_cqt2010v2(sr=16000, hop=64, fmin=220.0, n_bins=29, fir_taps=63, device=0)
