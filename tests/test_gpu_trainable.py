@@ -686,6 +686,40 @@ def test_cqt2010_backward_parity_small(nb, case):
     assert n1 is None and n2 is None and _peak_err(gx1.cpu().numpy(), ref_gx) < TOL
 
 
+def test_cqt2010_backward_config5_full_sampled(nb):
+    # the 1,770-waveform batch through the seven octaves of the layer with frequency-domain kernels (n_fft 1,024 per
+    # octave); the upstream gradient is non-zero on five waveforms only
+    import torch
+    _say("cqt2010 backward config 5 (1770 x 176400 @ 44100 Hz, 168 bins, 7 octaves) sampled waveforms")
+    wl = signals.WORKLOADS[5]
+    B, L = wl["B"], wl["L"]
+    x = torch.empty((B, L), dtype=torch.float32, device="cuda:0")
+    for s in range(0, B, 128):
+        idx = list(range(s, min(B, s + 128)))
+        x[s:s + len(idx)] = torch.from_numpy(signals.batch(5, idx)).to("cuda:0")
+    sampled = SAMPLED_BW[::3] + [1769]
+    plan = nb.nna_plan_trainable(nb.nna_plan_cqt2010(sr=44100, hop=512, fmin=32.70, n_bins=168, bins_per_octave=24, device=0))
+    rng = np.random.default_rng(57)
+    W, Y = _spectral_weights(nb, plan, rng)
+    T = 1 + L // 512
+    gs = rng.standard_normal((len(sampled), 168, T)).astype(np.float32)
+    gout = torch.zeros((B, 168, T), dtype=torch.float32, device="cuda:0")
+    gout[sampled] = torch.from_numpy(gs).to("cuda:0")
+    gy, gw, gx = nb.nna_cqt2010_backward(plan, x, gout)
+    torch.cuda.synchronize()
+    _say("  gpu done; oracle on the sampled waveforms")
+    xs = signals.batch(5, sampled)
+    ref_gy, ref_gw, ref_gx = oracle.cqt2010_bank_backward(xs, W, Y, gs, hop=512, n_bins=168, bins_per_octave=24,
+                                                          fir_taps=oracle.FIR_TAPS, fmt=oracle.MAGNITUDE)
+    e_y, e_w = _peak_err(gy.cpu().numpy(), ref_gy), _peak_err(gw.cpu().numpy(), ref_gw)
+    e_x = _peak_err(gx[sampled].cpu().numpy(), ref_gx)
+    _say(f"  spectral kernels {e_y:.3e}, bank gradient {e_w:.3e}, waveform gradient {e_x:.3e}")
+    assert e_y < TOL and e_w < TOL and e_x < TOL
+    rest = torch.ones(B, dtype=torch.bool, device="cuda:0")
+    rest[sampled] = False
+    assert not gx[rest].any()
+
+
 def test_spectral_backward_refuses_wrong_plans_and_workspaces(nb):
     import torch
     plan = nb.nna_plan_cqt1992(sr=8000, hop=64, fmin=220.0, n_bins=30, device=0)
