@@ -720,6 +720,36 @@ def test_cqt2010_backward_config5_full_sampled(nb):
     assert not gx[rest].any()
 
 
+def test_cqt1992_backward_152_waveforms_sampled(nb):
+    # the batch bench.py times this layer on (152 x 220,500 @ 22,050 Hz, 84 bins, n_fft 16,384: 512 workgroups of the
+    # one-workgroup-per-CU forward kernel, 16,386-row banks in the gradient kernels); the upstream gradient is non-zero
+    # on two waveforms, which the oracle follows
+    import torch
+    _say("cqt1992 backward 152 x 220500 @ 22050 Hz, 84 bins, n_fft 16384, sampled waveforms")
+    B, L = 152, 220500
+    x = torch.from_numpy(signals.batch(3, list(range(B)))).to("cuda:0")
+    sampled = [0, 151]
+    plan = nb.nna_plan_trainable(nb.nna_plan_cqt1992(sr=22050, hop=512, fmin=32.70, n_bins=84, bins_per_octave=12, device=0))
+    rng = np.random.default_rng(58)
+    W, Y = _spectral_weights(nb, plan, rng)
+    T = 1 + L // 512
+    gs = rng.standard_normal((len(sampled), 84, T)).astype(np.float32)
+    gout = torch.zeros((B, 84, T), dtype=torch.float32, device="cuda:0")
+    gout[sampled] = torch.from_numpy(gs).to("cuda:0")
+    gy, gw, gx = nb.nna_cqt1992_backward(plan, x, gout)
+    torch.cuda.synchronize()
+    _say("  gpu done; oracle on the sampled waveforms")
+    xs = signals.batch(3, sampled)
+    ref_gy, ref_gw, ref_gx = oracle.cqt1992_bank_backward(xs, W, Y, gs, hop=512)
+    e_y, e_w = _peak_err(gy.cpu().numpy(), ref_gy), _peak_err(gw.cpu().numpy(), ref_gw)
+    e_x = _peak_err(gx[sampled].cpu().numpy(), ref_gx)
+    _say(f"  spectral kernels {e_y:.3e}, bank gradient {e_w:.3e}, waveform gradient {e_x:.3e}")
+    assert e_y < TOL and e_w < TOL and e_x < TOL
+    rest = torch.ones(B, dtype=torch.bool, device="cuda:0")
+    rest[sampled] = False
+    assert not gx[rest].any()
+
+
 def test_spectral_backward_refuses_wrong_plans_and_workspaces(nb):
     import torch
     plan = nb.nna_plan_cqt1992(sr=8000, hop=64, fmin=220.0, n_bins=30, device=0)
