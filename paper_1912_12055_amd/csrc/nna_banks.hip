@@ -88,6 +88,14 @@ void build_stft_bank_fold(nna_plan* p) {
   if (!p->fold) return;
   const int nj2 = J / 2;
   const long long G = (long long)p->n_chunks * nj2 * ST_NKG;
+  // Split launches with J = 4 visit the chunks in pairs 0, n-1, 1, n-2, ...: position ci of the bank's stream holds
+  // chunk visit(ci)
+  const bool will_split = (p->kind == NNA_KIND_MEL && N % 128 == 0 && p->hop % 2 == 0) ||
+                          (p->kind == NNA_KIND_STFT && N % 256 == 0 && p->hop % 2 == 0);
+  p->fold_pair = will_split && nj2 == 2 && p->n_chunks % 2 == 0;
+  const bool pair = p->fold_pair;
+  const int n_ch = p->n_chunks;
+  auto visit = [pair, n_ch](int ci) { return !pair ? ci : (ci & 1) ? n_ch - 1 - ci / 2 : ci / 2; };
   if (p->kind == NNA_KIND_MEL && N % 128 == 0 && p->hop % 2 == 0) {
     // The Mel launch split by tap parity (see nna_kernels_fold.hip) replaces the plain folded one: row tiles of 32 bins
     // below N/4, two fragments per group (Re, Im kernels of the tile's bins).
@@ -97,10 +105,11 @@ void build_stft_bank_fold(nna_plan* p) {
     p->h_bankf.assign(p->bankf_floats, 0.0f);
     DftTable tab(N, p->window);
     for (int rt = 0; rt < p->n_rt_split; ++rt)
-      for (int c = 0; c < p->n_chunks; ++c)
+      for (int ci = 0; ci < p->n_chunks; ++ci)
         for (int j = 0; j < nj2; ++j)
           for (int kg = 0; kg < ST_NKG; ++kg) {
-            const long long g = ((long long)c * nj2 + j) * ST_NKG + kg;
+            const int c = visit(ci);
+            const long long g = ((long long)ci * nj2 + j) * ST_NKG + kg;
             for (int rb = 0; rb < 2; ++rb)
               for (int lane = 0; lane < 64; ++lane) {
                 const int h = lane >> 5, bin = rt * 32 + (lane & 31);
@@ -126,10 +135,11 @@ void build_stft_bank_fold(nna_plan* p) {
   p->h_bankf.assign(p->bankf_floats, 0.0f);
   DftTable tab(N, p->window);
   for (int rt = 0; rt < p->n_rt; ++rt)
-    for (int c = 0; c < p->n_chunks; ++c)
+    for (int ci = 0; ci < p->n_chunks; ++ci)
       for (int j = 0; j < nj2; ++j)
         for (int kg = 0; kg < ST_NKG; ++kg) {
-          const long long g = ((long long)c * nj2 + j) * ST_NKG + kg;
+          const int c = visit(ci);
+          const long long g = ((long long)ci * nj2 + j) * ST_NKG + kg;
           for (int rb = 0; rb < ST_RB; ++rb)
             for (int lane = 0; lane < 64; ++lane) {
               const int h = lane >> 5, bin = rt * (ST_ROWS / 2) + (rb & 1) * 32 + (lane & 31);

@@ -76,6 +76,14 @@ template <int OFF>
 __device__ __forceinline__ void gload16_s(f32x4& dst, unsigned lane_off, const void* sbase) {
   asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3" : "=v"(dst) : "v"(lane_off), "s"(sbase), "n"(OFF));
 }
+// one dword per lane, scalar base + per-lane 32-bit offset
+__device__ __forceinline__ void gload4_s(float& dst, unsigned lane_off, const void* sbase) {
+  asm volatile("global_load_dword %0, %1, %2" : "=v"(dst) : "v"(lane_off), "s"(sbase));
+}
+template <int N>
+__device__ __forceinline__ void wait_vm(f32x4 (&r)[5], float& x) {
+  asm volatile("s_waitcnt vmcnt(%6)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(x) : "n"(N));
+}
 template <int N>
 __device__ __forceinline__ void wait_vm(f32x4& a) {
   asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a) : "n"(N));

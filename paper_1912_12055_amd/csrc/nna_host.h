@@ -106,6 +106,9 @@ struct nna_plan {
   // parity (bins below N/4 only; their partners N/2 - k from the same sums).  h_wq / d_wq: the two weight tables of
   // bin N/4, [2][J rounded up to 4][hop]
   bool fold_split = false;
+  // ... with its chunks visited in pairs c, n_chunks - 1 - c: each chunk's tile then holds the other's mirrored partners
+  // (J = 4 and an even number of chunks; the folded bank is stored in the visiting order)
+  bool fold_pair = false;
   double exec_flops_split = 0;
   std::vector<float> h_wq;
   float* d_wq = nullptr;

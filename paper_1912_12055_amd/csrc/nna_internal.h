@@ -86,6 +86,8 @@ struct StftParams {
   // and wn holds two weight tables, for the real and the imaginary part of bin N/4 (the workgroups behind the
   // contraction's compute that bin; bin N/2 comes out of the contraction)
   int split;
+  // split launch whose chunks go in pairs c, n_chunks - 1 - c (the bank is stored in that order; see nna_kernels_fold.hip)
+  int pair;
   float* out;
   int n_rt;             // row tiles
   int n_chunks;         // LDS chunks per row tile

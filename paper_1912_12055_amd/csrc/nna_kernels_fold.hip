@@ -43,6 +43,8 @@
 
 namespace nna {
 
+typedef f32x4 f32x4_u __attribute__((aligned(4)));  // a 16-byte LDS read from a 4-byte boundary
+
 constexpr int SF_RPP = 256 / (ST_KC / 4);                      // LDS rows written per loader pass (32)
 constexpr int SF_NPASS = (SF_LDS_ROWS + SF_RPP - 1) / SF_RPP;  // 5; the last pass is partial
 constexpr int SF_TILE = SF_LDS_ROWS * ST_PITCH;                // floats per tile
@@ -271,9 +273,17 @@ __device__ __forceinline__ void fold_store_tile_split(const f32x16 (&acc)[2 * ST
 // on row tiles of 32 bins instead: two bank fragments per group (Re, Im of bins 0-31 of the tile) into four blocks
 // (even taps: Re, Im; odd taps: Re, Im); the power of the 32 bins and of their 32 partners then meets the filterbank
 // slices of both.  Bin N/4 is computed by the workgroup itself after its sweep (extra_bin_power) and weighed in.
-template <int MODE, int RING, bool SPLIT = false>
+// PAIR: the chunks of a row tile are visited in pairs ca = k, cb = n_chunks - 1 - k.  The partners N - n of chunk ca's
+// taps are the columns hop - 32 ca - c = 32 cb + 32 - c of rows J/2 further on: chunk cb's own columns moved up by one.
+// So both tiles of a step are plain windows, A = columns 32 ca .. 32 ca + 32 and B = columns 32 cb .. 32 cb + 32 (33
+// columns: the last in the pitch's padding), each the forward window of one chunk and the mirrored one of the other,
+// and a step multiplies both chunks: half the tile loads and twice the MFMAs per barrier.  The mirrored reads start one
+// column off a 16-byte boundary (two 8-byte LDS reads instead of one of 16).  Rows: a frame's partners lie up to
+// J - 1 rows below it (J/2 - 1 when the mirrored tile was stored J/2 rows on), so the launcher sizes the tile for that.
+template <int MODE, int RING, bool SPLIT = false, bool PAIR = false>
 __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
   static_assert(ST_NKG % RING == 0, "ring depth must divide the fragment groups per LDS row");
+  static_assert(!PAIR || SPLIT, "pairs of chunks: split launches only");
   constexpr bool MEL = MODE == ST_MODE_MEL;
   constexpr int FR = MEL && SPLIT ? 2 : ST_RB;          // bank fragments per group
   constexpr int NACC = SPLIT ? (MEL ? 4 : 2 * ST_RB) : ST_RB;
@@ -331,11 +341,12 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
   tm.b0 = f0 / g.T;
   tm.t0 = (int)(f0 - tm.b0 * g.T);
   tm.n0 = (g.T - tm.t0) < m_valid ? (g.T - tm.t0) : m_valid;
-  tm.extra = nj2 - 1;
+  tm.extra = PAIR ? 2 * nj2 - 1 : nj2 - 1;
   const int rows_used = tm.frame_row(m_valid - 1) + tm.extra + 1;
 
   const int n_chunks = P.n_chunks;
-  const int total = (rt_end - rt_begin) * n_chunks;
+  const int n_steps = PAIR ? n_chunks / 2 : n_chunks;  // barriers per row tile
+  const int total = (rt_end - rt_begin) * n_steps;
   if (total <= 0) return;
 
   // Row descriptors of the two tiles.  S: sample sigma hop + 4 cv - pad (+ c0).  Mirrored tile: LDS column d
@@ -359,9 +370,24 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
       rows.roff[p] = ok ? (int)((b - tm.b0) * g.L) : 0;
       rows.i0s[p] = ok ? sigma * g.hop + 4 * cv - g.pad : 0;
       rows.i0m[p] = ok ? (sigma + nj2 + 1) * g.hop - (ST_KC - 1) + 4 * cv - g.pad : g.hop;
-      bad |= rows.i0s[p] < 0 || rows.i0s[p] + smax > L - 4 || rows.i0m[p] - smax < 0 || rows.i0m[p] > L - 4;
+      if constexpr (PAIR)
+        bad |= rows.i0s[p] < 0 || rows.i0s[p] + smax > L - 4;
+      else
+        bad |= rows.i0s[p] < 0 || rows.i0s[p] + smax > L - 4 || rows.i0m[p] - smax < 0 || rows.i0m[p] > L - 4;
     }
     fast = __builtin_amdgcn_ballot_w64(bad) == 0;  // every window of every chunk of this wave is a stored window
+  }
+  // PAIR: column 32 of LDS row `tid` (threads below SF_LDS_ROWS), one sample per row and tile
+  int roff33 = 0, i033 = 0;
+  if constexpr (PAIR) {
+    if (tid < SF_LDS_ROWS) {
+      long long b;
+      int sigma;
+      tm.decode(tid, b, sigma);
+      const bool ok = tid < rows_used && b < g.B;
+      roff33 = ok ? (int)((b - tm.b0) * g.L) : 0;
+      i033 = ok ? sigma * g.hop + ST_KC - g.pad : 0;
+    }
   }
 
   // this lane's frame
@@ -372,7 +398,10 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
   const int t_lane = valid ? (int)(f_lane - b_lane * g.T) : 0;
   const int row_lane = valid ? tm.frame_row(fi_lane) : 0;
   const int s_off = row_lane * ST_PITCH + 4 * h;
-  const int m_off = SF_TILE + (row_lane + nj2 - 1) * ST_PITCH + (ST_KC - 4) - 4 * h;  // columns run backwards
+  // columns run backwards (PAIR: relative to the tile that serves as the mirrored one; taps c .. c + 3 pair with its
+  // columns 32 - c .. 29 - c)
+  const int m_off = PAIR ? (row_lane + 2 * nj2 - 1) * ST_PITCH + (ST_KC - 3) - 4 * h
+                         : SF_TILE + (row_lane + nj2 - 1) * ST_PITCH + (ST_KC - 4) - 4 * h;
   // w[N/2] x[N/2] of this lane's frame (the unpaired centre tap)
   float xmid = 0.f;
   if (valid) xmid = g.x[b_lane * g.L + reflect_clamped(t_lane * g.hop + nj2 * g.hop - g.pad, L)] * P.wmid;
@@ -396,18 +425,37 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
 
   // ---- prologue: both tiles of chunk 0 into LDS buffer 0, first RING bank groups requested ----------
   f32x4 R[NPASS];
+  float r33 = 0.f;  // PAIR: the tile's column 32 of this thread's row
   TileFix<NPASS> fx;
+  // byte offset of the column-32 sample of a tile whose first column is `shift`
+  auto off33 = [&](int shift) { return (unsigned)(roff33 + reflect_clamped(i033 + shift, L)) << 2; };
   {
     unsigned off[NPASS];
     fold_offsets(off, fx, L, rows.roff, rows.i0s, 0);
 #pragma unroll
     for (int p = 0; p < NPASS; ++p) gload16_s<0>(R[p], off[p], xbase);
-    wait_vm<0>(R);
+    if constexpr (PAIR) {
+      gload4_s(r33, off33(0), xbase);
+      wait_vm<0>(R, r33);
+      if (tid < SF_LDS_ROWS) lds[0][0][tid * ST_PITCH + ST_KC] = r33;
+    } else {
+      wait_vm<0>(R);
+    }
     sf_store_chunk(R, fx, &lds[0][0][0], tid);
-    fold_offsets(off, fx, L, rows.roff, rows.i0m, 0);
+    const int shiftB = (n_chunks - 1) * ST_KC;  // PAIR: tile B is the last chunk's window
+    if constexpr (PAIR)
+      fold_offsets(off, fx, L, rows.roff, rows.i0s, shiftB);
+    else
+      fold_offsets(off, fx, L, rows.roff, rows.i0m, 0);
 #pragma unroll
     for (int p = 0; p < NPASS; ++p) gload16_s<0>(R[p], off[p], xbase);
-    wait_vm<0>(R);
+    if constexpr (PAIR) {
+      gload4_s(r33, off33(shiftB), xbase);
+      wait_vm<0>(R, r33);
+      if (tid < SF_LDS_ROWS) lds[0][1][tid * ST_PITCH + ST_KC] = r33;
+    } else {
+      wait_vm<0>(R);
+    }
     sf_store_chunk(R, fx, &lds[0][1][0], tid);
   }
 
@@ -441,40 +489,61 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
   for (int it = 0; it < total; ++it) {
     const float* cur = &lds[it & 1][0][0];
     float* const nxt = &lds[(it + 1) & 1][0][0];
-    const int c_next = (c + 1 == n_chunks ? 0 : c + 1) * ST_KC;  // first column of chunk it+1
+    // first column of chunk it+1 (PAIR: of the next step's chunk in tile A; tile B's is n_chunks - 1 minus that chunk)
+    const int c_next = (c + 1 == n_steps ? 0 : c + 1) * ST_KC;
+    const int c_next_b = (n_chunks - 1) * ST_KC - c_next;
     const bool first_chunk = c == 0;
 
     f32x4 s_cur = *reinterpret_cast<const f32x4*>(cur + s_off);
-    f32x4 m_cur = *reinterpret_cast<const f32x4*>(cur + m_off);
+    f32x4 m_cur;
+    if constexpr (PAIR)
+      m_cur = *reinterpret_cast<const f32x4_u*>(cur + SF_TILE + m_off);
+    else
+      m_cur = *reinterpret_cast<const f32x4*>(cur + m_off);
     if (first_chunk && h == 0) m_cur.w = 0.f;  // tap 0 (the last element: columns run backwards) has no partner
 
-    auto group = [&](auto task_tag, int jj, auto kg_tag) {
+    // sweep_tag (PAIR): 0 = chunk ca (forward window in tile A, mirrored in B), 1 = chunk cb (the other way round)
+    auto group = [&](auto task_tag, int jj, auto kg_tag, auto sweep_tag) {
       constexpr int TASK = decltype(task_tag)::value;
       constexpr int kg = decltype(kg_tag)::value;
+      constexpr int SW = decltype(sweep_tag)::value;
       constexpr int s = kg % RING;
       // the fragments of the next group are read from LDS while this group's MFMAs run
+      const bool last_of_sweep = !(kg + 1 < ST_NKG) && !(jj + 1 < nj2);
       const int nj_ = kg + 1 < ST_NKG ? jj : (jj + 1 < nj2 ? jj + 1 : 0);
       const int nk_ = kg + 1 < ST_NKG ? (kg + 1) * ST_KG : 0;
-      const f32x4 s_nxt = *reinterpret_cast<const f32x4*>(cur + s_off + nj_ * ST_PITCH + nk_);
-      const f32x4 m_nxt = *reinterpret_cast<const f32x4*>(cur + m_off - nj_ * ST_PITCH - nk_);
+      f32x4 s_nxt, m_nxt;
+      if constexpr (PAIR) {
+        const int sw_n = last_of_sweep ? SW ^ 1 : SW;  // (after sweep 1 the next step reads its own first fragments)
+        s_nxt = *reinterpret_cast<const f32x4*>(cur + (sw_n ? SF_TILE : 0) + s_off + nj_ * ST_PITCH + nk_);
+        m_nxt = *reinterpret_cast<const f32x4_u*>(cur + (sw_n ? 0 : SF_TILE) + m_off - nj_ * ST_PITCH - nk_);
+      } else {
+        s_nxt = *reinterpret_cast<const f32x4*>(cur + s_off + nj_ * ST_PITCH + nk_);
+        m_nxt = *reinterpret_cast<const f32x4*>(cur + m_off - nj_ * ST_PITCH - nk_);
+      }
       const f32x4 m_rev = {m_cur.w, m_cur.z, m_cur.y, m_cur.x};
       const f32x4 ev = s_cur + m_rev, ov = s_cur - m_rev;
       constexpr bool M_ = TASK == TASK_LOAD_M || TASK == TASK_STORE_M;  // which tile a staging task is about
       unsigned off[NPASS];
       const char* sb = xbase;
+      // PAIR: both tiles are forward windows, the second one of the chunk that mirrors the first
+      const int shift = PAIR ? (M_ ? c_next_b : c_next) : (M_ ? -c_next : c_next);
       if constexpr (TASK == TASK_LOAD_S || TASK == TASK_LOAD_M) {
         if (fast) {  // the lanes' offsets stay, the base moves with the chunk
 #pragma unroll
-          for (int p = 0; p < NPASS; ++p) off[p] = (unsigned)(rows.roff[p] + (M_ ? rows.i0m[p] : rows.i0s[p])) << 2;
-          sb = xbase + (M_ ? -4 * c_next : 4 * c_next);
+          for (int p = 0; p < NPASS; ++p) off[p] = (unsigned)(rows.roff[p] + (M_ && !PAIR ? rows.i0m[p] : rows.i0s[p])) << 2;
+          sb = xbase + 4 * shift;
           fx.cls = 0;
         } else {
-          fold_offsets(off, fx, L, rows.roff, M_ ? rows.i0m : rows.i0s, M_ ? -c_next : c_next);
+          fold_offsets(off, fx, L, rows.roff, M_ && !PAIR ? rows.i0m : rows.i0s, shift);
         }
       }
       float* stage_dst = nxt + stage_off + (M_ ? SF_TILE : 0);
       if constexpr (TASK == TASK_STORE_S || TASK == TASK_STORE_M) {
-        wait_vm<W_TILE>(R);
+        if constexpr (PAIR)
+          wait_vm<W_TILE>(R, r33);
+        else
+          wait_vm<W_TILE>(R);
         if (fx.cls == 2) sf_store_chunk(R, fx, nxt + (M_ ? SF_TILE : 0), tid);
       }
       if constexpr (FR == 4)
@@ -496,6 +565,16 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
               *reinterpret_cast<f32x4*>(stage_dst + p * SF_RPP * ST_PITCH) = fixed_up<NPASS>(R[p], fx, p);
           } else {
             gload16_s<0>(R[p], off[p], sb);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        // PAIR: the tile's 33rd column, one step behind its last pass
+        if (PAIR && TASK != TASK_NONE && m == (FR == 4 ? 2 * NPASS + 1 : NPASS)) {
+          __builtin_amdgcn_sched_barrier(0);
+          if constexpr (TASK == TASK_STORE_S || TASK == TASK_STORE_M) {
+            if (tid < SF_LDS_ROWS) nxt[(M_ ? SF_TILE : 0) + tid * ST_PITCH + ST_KC] = r33;
+          } else {
+            gload4_s(r33, off33(shift), xbase);
           }
           __builtin_amdgcn_sched_barrier(0);
         }
@@ -525,22 +604,32 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
     using TSS = std::integral_constant<int, TASK_STORE_S>;
     using TLM = std::integral_constant<int, TASK_LOAD_M>;
     using TSM = std::integral_constant<int, TASK_STORE_M>;
-    group(TLS{}, 0, K0{});
-    group(TN{}, 0, K1{});
-    group(TN{}, 0, K2{});
-    group(TSS{}, 0, K3{});
-    group(TLM{}, 1, K0{});
-    group(TN{}, 1, K1{});
-    group(TN{}, 1, K2{});
-    group(TSM{}, 1, K3{});
+    using W0 = std::integral_constant<int, 0>;
+    using W1 = std::integral_constant<int, 1>;
+    group(TLS{}, 0, K0{}, W0{});
+    group(TN{}, 0, K1{}, W0{});
+    group(TN{}, 0, K2{}, W0{});
+    group(TSS{}, 0, K3{}, W0{});
+    group(TLM{}, 1, K0{}, W0{});
+    group(TN{}, 1, K1{}, W0{});
+    group(TN{}, 1, K2{}, W0{});
+    group(TSM{}, 1, K3{}, W0{});
     for (int jj = 2; jj < nj2; ++jj) {
-      group(TN{}, jj, K0{});
-      group(TN{}, jj, K1{});
-      group(TN{}, jj, K2{});
-      group(TN{}, jj, K3{});
+      group(TN{}, jj, K0{}, W0{});
+      group(TN{}, jj, K1{}, W0{});
+      group(TN{}, jj, K2{}, W0{});
+      group(TN{}, jj, K3{}, W0{});
+    }
+    if constexpr (PAIR) {  // the second chunk of the pair out of the same two tiles
+      for (int jj = 0; jj < nj2; ++jj) {
+        group(TN{}, jj, K0{}, W1{});
+        group(TN{}, jj, K1{}, W1{});
+        group(TN{}, jj, K2{}, W1{});
+        group(TN{}, jj, K3{}, W1{});
+      }
     }
 
-    if (++c == n_chunks) {
+    if (++c == n_steps) {
       // ---- epilogue of row tile rt ---------------------------------------------------
       c = 0;
       const int slot_base = rt * TILE_BINS;
@@ -629,7 +718,10 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
 
   // Drain: the last tile requests and the last RING bank requests are never consumed; their registers
   // stay reserved until the data has landed.
-  wait_vm<0>(R);
+  if constexpr (PAIR)
+    wait_vm<0>(R, r33);
+  else
+    wait_vm<0>(R);
 #pragma unroll
   for (int s = 0; s < RING; ++s) {
     if constexpr (FR == 4)
@@ -672,12 +764,16 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
 hipError_t launch_stft_fold(const StftParams& p, int mode, hipStream_t stream) {
   clear_stale_error();
   if (p.nj < 2 || p.tile_frames < 1 || p.tile_frames > ST_FRAMES || !p.bankf) return hipErrorInvalidValue;
+  if (p.pair && (!p.split || p.nj != 2 || p.n_chunks % 2)) return hipErrorInvalidValue;
   if (mode == ST_MODE_MEL) {
     const long long blocks = p.n_ft * p.n_pass;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     if (p.split) {
       if (p.n_half % 2 || (p.mel_nyq_any && (!p.wn || !p.mel_wnyq)) || (p.pout && !p.wn)) return hipErrorInvalidValue;
-      hipLaunchKernelGGL((stft_fold_kernel<ST_MODE_MEL, ST_RING_FOLD_MELSPLIT, true>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+      if (p.pair)
+        hipLaunchKernelGGL((stft_fold_kernel<ST_MODE_MEL, ST_RING_FOLD_MELSPLIT, true, true>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+      else
+        hipLaunchKernelGGL((stft_fold_kernel<ST_MODE_MEL, ST_RING_FOLD_MELSPLIT, true>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
     } else {
       hipLaunchKernelGGL((stft_fold_kernel<ST_MODE_MEL, ST_RING_FOLD_MEL>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
     }
@@ -687,7 +783,10 @@ hipError_t launch_stft_fold(const StftParams& p, int mode, hipStream_t stream) {
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     if (p.split) {
       if (p.n_half % 2) return hipErrorInvalidValue;
-      hipLaunchKernelGGL((stft_fold_kernel<ST_MODE_STFT, ST_RING_FOLD_SPLIT, true>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+      if (p.pair)
+        hipLaunchKernelGGL((stft_fold_kernel<ST_MODE_STFT, ST_RING_FOLD_SPLIT, true, true>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+      else
+        hipLaunchKernelGGL((stft_fold_kernel<ST_MODE_STFT, ST_RING_FOLD_SPLIT, true>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
     } else {
       hipLaunchKernelGGL((stft_fold_kernel<ST_MODE_STFT, ST_RING_FOLD_STFT>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
     }

@@ -124,7 +124,9 @@ nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long lo
   }
   // The folded kernel addresses the rows of a frame tile as 32-bit byte offsets from the tile's first waveform:
   // the waveforms a tile can span must lie within 2^31 bytes (else the direct kernel runs).
-  const int fold_M = plan->runs_folded() ? pick_tile_frames(ST_FRAMES, T, plan->nj / 2 - 1, nna::SF_LDS_ROWS) : 0;
+  // (chunks visited in pairs: a tile also holds the mirrored partners' rows, J/2 further on)
+  const bool fold_pair = plan->runs_split() && plan->fold_pair;
+  const int fold_M = plan->runs_folded() ? pick_tile_frames(ST_FRAMES, T, fold_pair ? plan->nj - 1 : plan->nj / 2 - 1, nna::SF_LDS_ROWS) : 0;
   const bool fold_fits = fold_M >= 1 && (1 + (fold_M - 1 + T - 1) / T) * L <= (1LL << 29);
   // (the Mel launch split by tap parity can write the spectrogram it forms on the way; the once-folded one cannot)
   if (fold_fits && (!spec_out || (kind == NNA_KIND_MEL && plan->runs_split())) && (kind == NNA_KIND_STFT || kind == NNA_KIND_MEL)) {
@@ -154,6 +156,7 @@ nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long lo
       P.n_pass = plan->n_pass;
       if (plan->runs_split()) {  // 32-bin row tiles below N/4, their own pass table; bin N/4 weighed in at the end
         P.split = 1;
+        P.pair = plan->fold_pair ? 1 : 0;
         P.n_rt = plan->n_rt_split;
         P.mel_pass_rt = plan->d_mel_pass_rtf;
         P.wn = plan->d_wq;
@@ -169,6 +172,7 @@ nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long lo
       P.fmt = plan->fmt;
       if (plan->runs_split()) {  // the bins below N/4 only; bin N/4 from the workgroups behind the contraction's
         P.split = 1;
+        P.pair = plan->fold_pair ? 1 : 0;
         P.n_rt = plan->n_rt_split;
         P.wn = plan->d_wq;
       }
