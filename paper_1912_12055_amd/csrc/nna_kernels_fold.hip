@@ -479,7 +479,8 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
   // during one group and written three groups later: the three groups in between each re-request one ring
   // slot (FR loads), so at least 3 FR requests are younger than the tile's.
   constexpr int W_SLOT = (RING - 1) * FR;
-  constexpr int W_TILE = 3 * FR;
+  // (split launches: of the group that requests the tile only the quads re-requested behind the tile's last load count)
+  constexpr int W_TILE = SPLIT ? 2 * FR + (FR == 4 ? 2 : 1) : 3 * FR;
   constexpr int TASK_NONE = 0, TASK_LOAD_S = 1, TASK_STORE_S = 2, TASK_LOAD_M = 3, TASK_STORE_M = 4;
   const int stage_off = (tid / (ST_KC / 4)) * ST_PITCH + (tid % (ST_KC / 4)) * 4;
   const bool last_pass_row = tid / (ST_KC / 4) < SF_LDS_ROWS - (NPASS - 1) * SF_RPP;  // the partial fifth pass
@@ -553,7 +554,10 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int m = 0; m < 4 * FR; ++m) {
-        const int e = m / FR, rb = m % FR;
+        // Split launches take a fragment quad's four taps in a row (even and odd taps go to different accumulators, so
+        // consecutive MFMAs do not depend on each other) and re-request the quad right behind its fourth: the request
+        // is out up to three quarters of a group earlier than when every quad's last tap comes in the last quarter.
+        const int e = SPLIT ? m % 4 : m / FR, rb = SPLIT ? m / 4 : m % FR;
         const int ab = SPLIT && (e & 1) ? rb + FR : rb;  // odd taps: the second set
         acc[ab] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[s][rb][e], rb < FR / 2 ? ev[e] : ov[e], acc[ab], 0, 0, 0);
         // a staging task's NPASS steps go one behind every other MFMA (behind each of the first NPASS, where a group has eight)
@@ -578,7 +582,7 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
           }
           __builtin_amdgcn_sched_barrier(0);
         }
-        if (m >= 3 * FR) {
+        if (SPLIT ? (m & 3) == 3 : m >= 3 * FR) {
           // this MFMA was the last reader of fragment quad rb: re-request it (the group RING ahead; the
           // bank allocation is padded by ST_NKG groups, so the tail stays in bounds)
           __builtin_amdgcn_sched_barrier(0);
