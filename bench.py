@@ -27,7 +27,7 @@ PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix peak
 PEAK_F16_MFMA_TFLOPS = 2500.0  # MI355X dense fp16 / bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
 # the kernel each transform of the step launches (names as rocprofv3 prints them)
-KERNELS = {"stft": "stft_fold_kernel<0, 2, true>", "mel": "stft_fold_kernel<1, 4, true>", "cqt": "cqt_kernel<false>"}
+KERNELS = {"stft": "stft_fold_kernel<0, 2, true, true>", "mel": "stft_fold_kernel<1, 4, true, true>", "cqt": "cqt_kernel<false>"}
 
 
 def _read_traffic():

@@ -43,7 +43,12 @@
 
 namespace nna {
 
-typedef f32x4 f32x4_u __attribute__((aligned(4)));  // a 16-byte LDS read from a 4-byte boundary
+// Four floats from p, which lies one float past a 16-byte boundary: the aligned quad below it (its last three) and one
+// float more -- a 16-byte read from a 4-byte boundary becomes two 8-byte reads whose lanes collide on the LDS banks.
+__device__ __forceinline__ f32x4 mirrored4(const float* p) {
+  const f32x4 lo = *reinterpret_cast<const f32x4*>(p - 1);
+  return (f32x4){lo.y, lo.z, lo.w, p[3]};
+}
 
 constexpr int SF_RPP = 256 / (ST_KC / 4);                      // LDS rows written per loader pass (32)
 constexpr int SF_NPASS = (SF_LDS_ROWS + SF_RPP - 1) / SF_RPP;  // 5; the last pass is partial
@@ -498,7 +503,7 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
     f32x4 s_cur = *reinterpret_cast<const f32x4*>(cur + s_off);
     f32x4 m_cur;
     if constexpr (PAIR)
-      m_cur = *reinterpret_cast<const f32x4_u*>(cur + SF_TILE + m_off);
+      m_cur = mirrored4(cur + SF_TILE + m_off);
     else
       m_cur = *reinterpret_cast<const f32x4*>(cur + m_off);
     if (first_chunk && h == 0) m_cur.w = 0.f;  // tap 0 (the last element: columns run backwards) has no partner
@@ -517,7 +522,7 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
       if constexpr (PAIR) {
         const int sw_n = last_of_sweep ? SW ^ 1 : SW;  // (after sweep 1 the next step reads its own first fragments)
         s_nxt = *reinterpret_cast<const f32x4*>(cur + (sw_n ? SF_TILE : 0) + s_off + nj_ * ST_PITCH + nk_);
-        m_nxt = *reinterpret_cast<const f32x4_u*>(cur + (sw_n ? 0 : SF_TILE) + m_off - nj_ * ST_PITCH - nk_);
+        m_nxt = mirrored4(cur + (sw_n ? 0 : SF_TILE) + m_off - nj_ * ST_PITCH - nk_);
       } else {
         s_nxt = *reinterpret_cast<const f32x4*>(cur + s_off + nj_ * ST_PITCH + nk_);
         m_nxt = *reinterpret_cast<const f32x4*>(cur + m_off - nj_ * ST_PITCH - nk_);
