@@ -26,6 +26,7 @@ constexpr int ST_MEL_BLOCKS = 4;  // 32-mel MFMA blocks per pass (128 mels)
 constexpr int ST_RG = 4;          // row tiles one STFT workgroup handles (amortises its start-up, re-uses its frames)
 // folded-frame variant of the STFT / Mel kernel (nna_kernels_fold.hip): two LDS tiles per chunk
 constexpr int SF_LDS_ROWS = 136;  // LDS rows per tile: 128 frames + (J/2 - 1) overlap rows for each of two waveform segments, J <= 8
+                                  // (chunks in mirrored pairs, J = 4: J - 1 overlap rows per segment)
 constexpr int ST_RING_FOLD_STFT = 4;  // bank fragment groups in flight per wave
 constexpr int ST_RING_FOLD_MEL = 2;
 constexpr int ST_RING_FOLD_MELSPLIT = 4;  // two fragments per group: four groups in flight are as many registers as the Mel ring's

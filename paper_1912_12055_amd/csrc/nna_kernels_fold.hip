@@ -36,6 +36,8 @@
 //    through the same five registers (a chunk has 4 J/2 >= 8 groups).  Cycle counters read inside the loop
 //    put the wait for a tile at under 20 cycles per chunk; requesting two chunks ahead through a second
 //    register set changed nothing.
+//  * Launches split by tap parity with J = 4 visit the chunks of a row tile in mirrored pairs and stage two forward
+//    windows instead of a forward and a mirrored tile (template argument PAIR, described at the kernel).
 #include "nna_device.h"
 
 #include <type_traits>
