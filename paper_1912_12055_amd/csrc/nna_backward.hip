@@ -820,10 +820,16 @@ static nna_status spectral_backward_core(const nna_plan* plan, const float* x_de
   float* gbuf = reinterpret_cast<float*>(ws + W.g_off);
   // 1. the spectrum itself, rows (Re, Im) per bin: the first stage's contraction with the complex epilogue
   {
-    const int Mf = pick_tile_frames(ST_FRAMES, T, plan->nj - 1, ST_LDS_ROWS);
+    // With many hop-shifts (n_fft 16,384 at hop 512: 32) the 160-row tile of the two-workgroups-per-CU build holds
+    // 98 frames of the 128 the MFMA tile multiplies; the 192-row tile of the one-workgroup build holds them all.
+    int Mf = pick_tile_frames(ST_FRAMES, T, plan->nj - 1, ST_LDS_ROWS);
+    const int Mw = pick_tile_frames(ST_FRAMES, T, plan->nj - 1, nna::ST_LDS_ROWS_WIDE);
+    const bool wide = Mw * 7 > Mf * 8;  // (more than 8/7 of the frames per tile)
+    if (wide) Mf = Mw;
     if (Mf < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
     nna::StftParams P;
     std::memset(&P, 0, sizeof(P));
+    P.wide = wide ? 1 : 0;
     P.g = make_geom(plan, x_dev, B, L, T);
     P.bank = reinterpret_cast<const float4*>(plan->d_bank);
     P.out = X;

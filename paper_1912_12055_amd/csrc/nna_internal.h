@@ -102,6 +102,7 @@ struct StftParams {
   // Mel only
   const float4* melw;   // [pass][row tile][ST_RB][ST_MEL_BLOCKS][2][64 lanes] float4 (ST_MODE_LIN: [lin_blocks][4])
   int lin_blocks;       // ST_MODE_LIN: 32-row output blocks per pass, 4 or 6
+  int wide;             // ST_MODE_CPLX: the one-workgroup-per-CU instantiation with ST_LDS_ROWS_WIDE rows per tile
   const unsigned char* mel_mask;  // [pass][row tile][ST_RB]: bit mb set if that 32-mel block is non-zero
   const float* mel_wnyq;          // [n_mels] weight of the Nyquist bin
   const int* mel_pass_rt;         // [pass][2]: first row tile, one past the last

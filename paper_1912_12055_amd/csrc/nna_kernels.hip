@@ -41,7 +41,8 @@ constexpr int ST_RING_STFT = 4;  // bank fragment groups in flight per wave
 constexpr int ST_RING_MEL = 2;   // fewer in the Mel variant: its 64 extra accumulators need the registers
 
 // MODE (ST_MODE_*): what follows the contraction of a row tile.
-// LIN_NB (ST_MODE_LIN only): 32-row blocks of the second contraction's output per pass.
+// LIN_NB: 32-row blocks of the second contraction's output per pass (ST_MODE_LIN); in every mode a value above 4 selects
+// the one-workgroup-per-CU build with the 192-row LDS tile.
 template <int MODE, int RING, int LIN_NB = ST_MEL_BLOCKS>
 __global__ __launch_bounds__(256, LIN_NB > 4 ? 1 : 2) void stft_kernel(const StftParams P) {
   static_assert(ST_NKG % RING == 0, "ring depth must divide the fragment groups per LDS row");
@@ -872,7 +873,11 @@ hipError_t launch_stft(const StftParams& p, int mode, hipStream_t stream) {
   else if (mode == ST_MODE_GRAD)
     hipLaunchKernelGGL((stft_kernel<ST_MODE_GRAD, ST_RING_STFT>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   else if (mode == ST_MODE_CPLX)
-    hipLaunchKernelGGL((stft_kernel<ST_MODE_CPLX, ST_RING_STFT>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    // (many hop-shifts: the 192-row tile of the one-workgroup-per-CU instantiation keeps the frame tile whole)
+    if (p.wide)
+      hipLaunchKernelGGL((stft_kernel<ST_MODE_CPLX, ST_RING_STFT, 6>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    else
+      hipLaunchKernelGGL((stft_kernel<ST_MODE_CPLX, ST_RING_STFT>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   else
     hipLaunchKernelGGL((stft_kernel<ST_MODE_STFT, ST_RING_STFT>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
   return hipGetLastError();

@@ -186,11 +186,18 @@ nna_status run_stft_core(const nna_plan* plan, int kind, const float* x, long lo
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
     return NNA_OK;
   }
-  const int lds_rows = kind == NNA_KIND_CQT1992 && plan->lin_blocks == 6 ? nna::ST_LDS_ROWS_WIDE : ST_LDS_ROWS;
+  const bool cplx = kind == NNA_KIND_STFT && (plan->fmt == NNA_OUT_COMPLEX || plan->fmt == NNA_OUT_PHASE);
+  int lds_rows = kind == NNA_KIND_CQT1992 && plan->lin_blocks == 6 ? nna::ST_LDS_ROWS_WIDE : ST_LDS_ROWS;
+  // complex / phase output with many hop-shifts: the one-workgroup-per-CU build when its 192-row tile holds more than
+  // 8/7 of the frames the 160-row tile does
+  const bool wide = cplx && pick_tile_frames(ST_FRAMES, T, plan->nj - 1, nna::ST_LDS_ROWS_WIDE) * 7 >
+                                pick_tile_frames(ST_FRAMES, T, plan->nj - 1, ST_LDS_ROWS) * 8;
+  if (wide) lds_rows = nna::ST_LDS_ROWS_WIDE;
   const int M = pick_tile_frames(ST_FRAMES, T, plan->nj - 1, lds_rows);
   if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
   nna::StftParams P;
   std::memset(&P, 0, sizeof(P));
+  P.wide = wide ? 1 : 0;
   P.g = make_geom(plan, x, B, L, T);
   P.bank = reinterpret_cast<const float4*>(plan->d_bank);
   P.out = out;

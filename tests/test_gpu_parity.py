@@ -215,6 +215,7 @@ COMPLEX_STFT_CASES = [
     ("no centring, rect window", 2, 9000, 512, 128, 1, False),
     ("hop does not divide n_fft", 3, 5000, 96, 25, 0, True),
     ("n_fft = 2048, hop 512", 2, 20000, 2048, 512, 0, True),
+    ("32 hop-shifts: the 192-row tile of the one-workgroup-per-CU build, tiles span waveforms", 3, 14000, 2048, 64, 0, True),
 ]
 
 
