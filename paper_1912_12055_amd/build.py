@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libnna.so")
-SOURCES = ["nna_plan.hip", "nna_banks.hip", "nna_run.hip", "nna_backward.hip", "nna_kernels.hip", "nna_kernels_fold.hip", "nna_kernels_f16.hip", "nna_train.hip"]
+SOURCES = ["nna_plan.hip", "nna_banks.hip", "nna_run.hip", "nna_backward.hip", "nna_kernels.hip", "nna_kernels_fold.hip", "nna_kernels_cqf.hip", "nna_kernels_f16.hip", "nna_train.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",

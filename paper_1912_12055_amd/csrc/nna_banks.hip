@@ -681,6 +681,174 @@ void build_cqt_bank(nna_plan* p) {
   p->alg_flops = 4.0 * sumN;
 }
 
+// ---- CQT bank folded about the kernels' centres (nna_kernels_cqf.hip) --------------------------
+// Kernel k of eq. (CQT) is window(N_k)[n] exp(-2 pi i Q n / N_k): a symmetric window times a phase that is linear
+// in n, so about its centre n = N_k / 2 the kernel is exp(-i pi Q) times a sequence g with g[-m] = conj(g[m]).
+// Centred in K taps (K even), kernels of even length have that centre on tap K/2, kernels of odd length half a
+// tap before it.  With the frame folded about the same point, e[m] = x[K/2 + m] + x[K/2 - p - m] and
+// o[m] = x[K/2 + m] - x[K/2 - p - m] (p = 0 / 1 for even / odd lengths),
+//     C_k = exp(-i pi Q) ( sum_m e[m] Re g_k[m]  +  i sum_m o[m] Im g_k[m] ),
+// half the multiply-adds.  Rows that share an MFMA share its frame operand, so a 16-row block holds the
+// cosine kernels Re g (or the sine kernels Im g) of 16 bins of one parity; the bins of each parity are taken in
+// order of length, 16 at a time.  The symmetry is checked on the values themselves: a window that does not
+// vanish at n = 0 (its partner n = N_k lies outside the kernel) leaves the plan on the direct bank.
+void build_cqt_bank_fold(nna_plan* p) {
+  p->cq_fold = false;
+  const long long K = p->K, hop = p->hop;
+  if (!p->sliding || p->tap_stride != p->hop || p->row_step != 1) return;
+  if (K % (2 * hop) != 0 || K / hop < 8 || hop / CQ_KC > CQF_TABLE_CAP) return;
+  const long long c = K / 2;
+  const double rc = std::cos(kPi * std::fmod(p->Q, 2.0)), rs = std::sin(kPi * std::fmod(p->Q, 2.0));
+  CqtKernelGen gen(p);
+  // g_k[m] = exp(+i pi Q) h_k[c + m]; its mirrored partner exp(+i pi Q) h_k[c - par - m] must be its conjugate
+  auto g_at = [&](int k, long long tap, double& re, double& im) {
+    const double hr = tap >= 0 && tap < K ? gen.value(2 * k, tap) : 0.0, hi = tap >= 0 && tap < K ? gen.value(2 * k + 1, tap) : 0.0;
+    re = rc * hr - rs * hi;
+    im = rs * hr + rc * hi;
+  };
+  std::vector<int> par(p->n_bins);
+  std::vector<long long> M(p->n_bins);  // folded taps of bin k: m in [0, M[k])
+  for (int k = 0; k < p->n_bins; ++k) {
+    par[k] = (int)(p->Nk[k] & 1);
+    const long long reach = p->Nk[k] / 2 + 2;  // no tap of the kernel lies further from the centre
+    double peak = 0;
+    for (long long m = 0; m < reach; ++m) {
+      double a, b;
+      g_at(k, c + m, a, b);
+      peak = std::max(peak, std::max(std::fabs(a), std::fabs(b)));
+    }
+    long long last = -1;
+    for (long long m = 0; m < reach; ++m) {
+      double a, b, ma, mb;
+      g_at(k, c + m, a, b);
+      g_at(k, c - par[k] - m, ma, mb);
+      if (std::fabs(a - ma) > 1e-9 * peak || std::fabs(b + mb) > 1e-9 * peak) return;  // not symmetric: stay direct
+      if (a != 0.0 || b != 0.0) last = m;
+    }
+    M[k] = std::max(1LL, last + 1);
+  }
+  // groups: the bins of each parity in order of decreasing length, 16 at a time; groups ordered by their longest kernel
+  struct Group { int parity; std::vector<int> bins; long long Mmax; };
+  std::vector<Group> groups;
+  for (int parity = 0; parity < 2; ++parity) {
+    std::vector<int> ks;
+    for (int k = 0; k < p->n_bins; ++k)
+      if (par[k] == parity) ks.push_back(k);
+    std::stable_sort(ks.begin(), ks.end(), [&](int a, int b) { return M[a] > M[b]; });
+    for (size_t i = 0; i < ks.size(); i += CQ_ROWS) {
+      Group gp{parity, {}, 0};
+      for (size_t u = i; u < std::min(ks.size(), i + CQ_ROWS); ++u) {
+        gp.bins.push_back(ks[u]);
+        gp.Mmax = std::max(gp.Mmax, M[ks[u]]);
+      }
+      groups.push_back(gp);
+    }
+  }
+  // items: groups of one parity, consecutive in that parity's order; a short group takes the next one along
+  std::vector<std::vector<int>> items;  // indices into groups
+  for (int parity = 0; parity < 2; ++parity) {
+    std::vector<int> gs;
+    for (size_t gi = 0; gi < groups.size(); ++gi)
+      if (groups[gi].parity == parity) gs.push_back((int)gi);
+    for (size_t i = 0; i < gs.size();) {
+      const long long shifts = ceil_div(groups[gs[i]].Mmax, hop);
+      if (i + 1 < gs.size() && shifts < 24) {
+        items.push_back({gs[i], gs[i + 1]});
+        i += 2;
+      } else {
+        items.push_back({gs[i]});
+        i += 1;
+      }
+    }
+  }
+  std::stable_sort(items.begin(), items.end(), [&](const std::vector<int>& a, const std::vector<int>& b) {
+    return groups[a[0]].Mmax > groups[b[0]].Mmax;
+  });
+  // device order of the groups = order of appearance in the items
+  p->h_qbins.clear();
+  p->h_qitems.clear();
+  std::vector<std::vector<nna::CqfChunk>> item_chunks(items.size());
+  const int n_grid = (int)(hop / CQ_KC);
+  long long frag = 0, exec_pair_groups = 0;
+  p->q_n_chunks = 1;
+  p->q_max_jspan = 1;
+  auto ring_pad = [](long long n) { return (n + 1) / 2 * 2; };  // a ring of CQ_PREFETCH = 4 fragments is two pair groups
+  static_assert(CQ_PREFETCH == 4, "two pair groups per ring");
+  for (size_t it = 0; it < items.size(); ++it) {
+    nna::CqfItem item{};
+    item.frag0 = frag;
+    item.grp_first = (int)(p->h_qbins.size() / CQ_ROWS);
+    item.n_pair = (int)items[it].size();
+    item.parity = groups[items[it][0]].parity;
+    item.jspan = 1;
+    for (int gi : items[it]) {
+      const Group& gp = groups[gi];
+      for (int r = 0; r < CQ_ROWS; ++r) p->h_qbins.push_back(r < (int)gp.bins.size() ? gp.bins[r] : -1);
+    }
+    for (int cidx = 0; cidx < n_grid; ++cidx) {
+      const long long c0 = (long long)cidx * CQ_KC;
+      nna::CqfChunk ck{};
+      ck.c0 = (int)c0;
+      bool any = false;
+      for (int u = 0; u < item.n_pair; ++u) {
+        const long long Mm = groups[items[it][u]].Mmax;
+        // shifts j with j hop + c0 < Mm
+        const long long nj = Mm > c0 ? ceil_div(Mm - c0, hop) : 0;
+        // the first pair always runs one ring: its waits are the ones that let the tile requests pass
+        const long long padded = u == 0 ? std::max(ring_pad(nj), 2LL) : ring_pad(nj);
+        ck.nj[u] = (int)(padded | (nj << 16));
+        item.jspan = std::max(item.jspan, (int)std::max(nj, 1LL));
+        any = any || nj > 0;
+      }
+      if (!any) continue;
+      for (int u = 0; u < item.n_pair; ++u) {
+        frag += 2 * (ck.nj[u] & 0xffff);
+        exec_pair_groups += ck.nj[u] >> 16;
+      }
+      item_chunks[it].push_back(ck);
+    }
+    item.n_chunks = (int)item_chunks[it].size();
+    p->q_n_chunks = std::max(p->q_n_chunks, item.n_chunks);
+    p->q_max_jspan = std::max(p->q_max_jspan, item.jspan);
+    p->h_qitems.push_back(item);
+  }
+  if (p->q_max_jspan > K / (2 * hop)) return;  // (cannot happen: the folded taps end before K/2)
+  if (16 + 2 * (p->q_max_jspan - 1) > CQF_LDS_ROWS) return;  // no room for a tile that spans two waveforms
+  p->h_qchunks.assign(items.size() * (size_t)p->q_n_chunks, nna::CqfChunk{});
+  for (size_t it = 0; it < items.size(); ++it)
+    for (size_t ci = 0; ci < item_chunks[it].size(); ++ci) p->h_qchunks[it * p->q_n_chunks + ci] = item_chunks[it][ci];
+  // fragments in loop order: per chunk, per pair, per shift: cosine rows, then sine rows
+  p->h_bankq.assign((size_t)(frag + CQ_PREFETCH) * 64 * 4, 0.0f);
+  long long f = 0;
+  for (size_t it = 0; it < items.size(); ++it)
+    for (const nna::CqfChunk& ck : item_chunks[it])
+      for (int u = 0; u < (int)items[it].size(); ++u) {
+        const Group& gp = groups[items[it][u]];
+        const int padded = ck.nj[u] & 0xffff, real = ck.nj[u] >> 16;
+        for (int jj = 0; jj < padded; ++jj, f += 2) {
+          if (jj >= real) continue;
+          for (int lane = 0; lane < 64; ++lane) {
+            const int q = lane >> 4, r = lane & 15;
+            if (r >= (int)gp.bins.size()) continue;
+            const int k = gp.bins[r];
+            float* dc = &p->h_bankq[((size_t)f * 64 + lane) * 4];
+            float* ds = &p->h_bankq[((size_t)(f + 1) * 64 + lane) * 4];
+            for (int e = 0; e < 4; ++e) {
+              const long long m = (long long)jj * hop + ck.c0 + 4 * q + e;
+              if (m >= M[k]) continue;
+              double a, b;
+              g_at(k, c + m, a, b);
+              if (m == 0 && gp.parity == 0) a *= 0.5;  // the centre tap meets itself in the fold
+              dc[e] = (float)a;
+              ds[e] = (float)b;
+            }
+          }
+        }
+      }
+  p->exec_flops_cqf = 2.0 * (double)exec_pair_groups * 2.0 * CQ_KC * CQ_ROWS;
+  p->cq_fold = true;
+}
+
 // Window-method low-pass at half the Nyquist frequency (Sec. III-C, "Downsampling"): the ideal
 // response's samples under a Hamming window, scaled to unit gain at 0 Hz.
 std::vector<double> half_band_taps(int n) {

@@ -158,6 +158,21 @@ struct nna_plan {
   int* d_mel_pass_rt = nullptr;
   nna::CqtItem* d_items = nullptr;
   nna::CqtChunk* d_chunks = nullptr;
+  // Constant-Q kernels folded about their centres (nna_kernels_cqf.hip): one-rate plans with time-domain kernels
+  // whose kernels are mirror symmetric up to one common phase and span at least eight hops.  The direct bank stays
+  // (inspection, trainable plans).
+  bool cq_fold = false;
+  std::vector<nna::CqfItem> h_qitems;
+  std::vector<nna::CqfChunk> h_qchunks;  // [item][q_n_chunks]
+  std::vector<int> h_qbins;              // [group][16]
+  std::vector<float> h_bankq;
+  int q_n_chunks = 1, q_max_jspan = 1;
+  double exec_flops_cqf = 0;
+  float* d_bankq = nullptr;
+  nna::CqfItem* d_qitems = nullptr;
+  nna::CqfChunk* d_qchunks = nullptr;
+  int* d_qbins = nullptr;
+  bool runs_cqfold() const { return cq_fold && !d_wrm; }
   // trainable CQT plans: index map caller's tensor -> streaming order, each row's tap support, and the
   // tables that let the backward contractions skip what lies outside every support
   int* d_cq_map = nullptr;
@@ -328,6 +343,7 @@ MelDeviceLayout layout_mel(nna_plan* p);
 void build_cqt1992_matrix(nna_plan* p);
 MelDeviceLayout layout_cqt1992(nna_plan* p);
 void build_cqt_bank(nna_plan* p);
+void build_cqt_bank_fold(nna_plan* p);  // sets p->cq_fold if the plan qualifies
 // the decimation filter of `fir_taps` taps: its taps, their split by parity for the decimation kernel, and the
 // 64-row bank form kept for inspection
 constexpr int FIR_ROWS = CQ_ITEM_RB * CQ_ROWS;

@@ -182,6 +182,50 @@ struct CqtParams {
   int rows_pad;
 };
 
+// ---- constant-Q kernels folded about their centres (nna_kernels_cqf.hip) ----------------------
+constexpr int CQF_NPASS = 5;                  // loader passes of 64 rows per tile
+constexpr int CQF_LDS_ROWS = CQF_NPASS * 64;  // rows of each of the two tiles (taps in front of / behind the centre)
+constexpr int CQF_TABLE_CAP = 1024;           // chunk descriptors per work item (16 bytes each)
+
+// One 16-tap column chunk of a work item: every hop-shift from 0 on that holds folded taps of a block pair.
+struct CqfChunk {
+  int c0;      // first folded-tap column of the chunk within the hop
+  int nj[2];   // per block pair: low 16 bits = pair groups (one cosine + one sine fragment each), a multiple of two
+               // (0 = none); high 16 bits = how many of them, from the front, hold taps
+  int pad0;
+};
+
+// A work item: one or two groups of 16 bins whose kernel lengths have the same parity; each group is a block pair
+// (cosine rows against the even fold, sine rows against the odd fold).  The groups share the item's two tiles.
+struct CqfItem {
+  long long frag0;  // first bank fragment
+  int grp_first;    // first 16-bin group (row of `bins`)
+  int n_pair;       // 1 or 2
+  int parity;       // 0: kernels symmetric about tap K/2, 1: about K/2 - 1/2
+  int jspan;        // hop-shifts the longest kernel of the item spans
+  int n_chunks;
+  int pad0;
+};
+
+struct CqfParams {
+  FrameGeom g;
+  const float4* bank;      // per item: [fragment][64 lanes] float4 in loop order
+  const CqfItem* items;
+  const CqfChunk* chunks;  // [n_items][n_chunks]
+  const int* bins;         // [group][16]: output bin of each row, -1 = none
+  float* out;
+  long long out_wave_stride;
+  int row_offset;
+  int n_items;
+  int n_chunks;            // stride of `chunks`
+  int fmt;
+  int lds_rows;            // rows per tile (multiple of 64, <= CQF_LDS_ROWS)
+  int tile_frames;
+  int centre;              // K / 2: folded tap m pairs the samples centre + m and centre - parity - m of a frame
+  float rot_c, rot_s;      // cos, sin of pi Q: the kernels' common phase at their centres
+  long long n_ft;
+};
+
 // ---- backward pass of the STFT layer (trainable kernel banks) --------------------------------
 constexpr int BW_MT = 128;   // output tile rows per workgroup
 constexpr int BW_NT = 128;   // output tile columns per workgroup
@@ -329,6 +373,8 @@ struct FirParams {
 };
 hipError_t launch_fir_decimate(const FirParams& p, hipStream_t stream);
 hipError_t launch_cqt(const CqtParams& p, hipStream_t stream);
+hipError_t launch_cqt_fold(const CqfParams& p, hipStream_t stream);
+hipError_t cqf_kernels_init();  // per-process function attributes of nna_kernels_cqf.hip
 size_t cqt_launch_lds_bytes(int n_chunks, int lds_rows);  // dynamic LDS launch_cqt asks for (limit: 160 KB)
 hipError_t launch_cqt_bank_from_logical(const CqtBankParams& p, hipStream_t stream);  // bank and wrm <- logical
 hipError_t launch_cqt_bank_to_logical(const CqtBankParams& p, hipStream_t stream);    // logical <- wrm

@@ -78,6 +78,12 @@ nna_status finish_plan(nna_plan* p, nna_plan** out, const MelDeviceLayout* mel) 
     if (s == NNA_OK && p->kind == NNA_KIND_CQT) {
       s = upload(&p->d_items, p->h_items.data(), p->h_items.size() * sizeof(nna::CqtItem), "cqt item table");
       if (s == NNA_OK) s = upload(&p->d_chunks, p->h_chunks.data(), p->h_chunks.size() * sizeof(nna::CqtChunk), "cqt chunk table");
+      if (s == NNA_OK && p->cq_fold) {
+        s = upload(&p->d_bankq, p->h_bankq.data(), p->h_bankq.size() * sizeof(float), "folded cqt bank");
+        if (s == NNA_OK) s = upload(&p->d_qitems, p->h_qitems.data(), p->h_qitems.size() * sizeof(nna::CqfItem), "folded cqt item table");
+        if (s == NNA_OK) s = upload(&p->d_qchunks, p->h_qchunks.data(), p->h_qchunks.size() * sizeof(nna::CqfChunk), "folded cqt chunk table");
+        if (s == NNA_OK) s = upload(&p->d_qbins, p->h_qbins.data(), p->h_qbins.size() * sizeof(int), "folded cqt bin table");
+      }
     }
     if (s != NNA_OK) {
       const std::string keep = g_err;
@@ -87,6 +93,7 @@ nna_status finish_plan(nna_plan* p, nna_plan** out, const MelDeviceLayout* mel) 
     }
     std::vector<float>().swap(p->h_bank);  // the device copy is the bank from here on
     std::vector<float>().swap(p->h_bankf);
+    std::vector<float>().swap(p->h_bankq);
     std::vector<_Float16>().swap(p->h_bank16);
     std::vector<_Float16>().swap(p->h_bank16s);
   }
@@ -180,6 +187,7 @@ nna_status make_cqt_plan(nna_plan** plan, int sr, int hop, double fmin, int k_fi
     p->pad = center ? (int)(taps / 2) : 0;
     for (int k = 0; k < n_bins; ++k) p->sk[k] = (taps - p->Nk[k]) / 2;
     build_cqt_bank(p);
+    build_cqt_bank_fold(p);
   } catch (const std::bad_alloc&) {
     delete p;
     return fail(NNA_ERR_ALLOC, "out of host memory while building the CQT bank");
@@ -750,7 +758,10 @@ nna_status nna_plan_info(const nna_plan* plan, int* kind, long long* bank_rows, 
   if (taps) *taps = plan->K;
   if (out_bins) *out_bins = plan->out_rows();
   if (executed_flops_per_frame)
-    *executed_flops_per_frame = plan->runs_split() ? plan->exec_flops_split : plan->runs_folded() ? plan->exec_flops_fold : plan->exec_flops;
+    *executed_flops_per_frame = plan->runs_split()    ? plan->exec_flops_split
+                                : plan->runs_folded() ? plan->exec_flops_fold
+                                : plan->runs_cqfold() ? plan->exec_flops_cqf
+                                                      : plan->exec_flops;
   if (algorithmic_flops_per_frame) *algorithmic_flops_per_frame = plan->alg_flops;
   return NNA_OK;
 }
@@ -813,6 +824,10 @@ void nna_plan_destroy(nna_plan* plan) {
       (void)hipFree(plan->d_mel_pass_rt);
       (void)hipFree(plan->d_items);
       (void)hipFree(plan->d_chunks);
+      (void)hipFree(plan->d_bankq);
+      (void)hipFree(plan->d_qitems);
+      (void)hipFree(plan->d_qchunks);
+      (void)hipFree(plan->d_qbins);
       (void)hipFree(plan->d_cq_map);
       (void)hipFree(plan->d_row_lo);
       (void)hipFree(plan->d_row_hi);

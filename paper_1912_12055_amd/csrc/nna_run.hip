@@ -24,6 +24,7 @@ hipError_t ensure_kernels_init(int device) {
   }
   if (!g_init_done[device]) {
     hipError_t e = nna::kernels_init();
+    if (e == hipSuccess) e = nna::cqf_kernels_init();
     if (e != hipSuccess) return e;
     void* ptr = nullptr;
     e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
@@ -253,11 +254,47 @@ nna_status run_stft_like(const nna_plan* plan, int kind, const float* x, long lo
   return run_stft_core(plan, kind, x, B, L, T, out, 0, 0, stream);
 }
 
+// the kernels folded about their centres (nna_kernels_cqf.hip): M frames per tile
+nna_status run_conv_fold(const nna_plan* sub, const float* x, long long B, long long L, long long T, float* out,
+                         long long out_wave_stride, int row_offset, int M, void* hip_stream) {
+  nna::CqfParams P;
+  std::memset(&P, 0, sizeof(P));
+  P.g = make_geom(sub, x, B, L, T);
+  P.bank = reinterpret_cast<const float4*>(sub->d_bankq);
+  P.items = sub->d_qitems;
+  P.chunks = sub->d_qchunks;
+  P.bins = sub->d_qbins;
+  P.out = out;
+  P.out_wave_stride = out_wave_stride;
+  P.row_offset = row_offset;
+  P.n_items = (int)sub->h_qitems.size();
+  P.n_chunks = sub->q_n_chunks;
+  P.fmt = sub->fmt;
+  P.tile_frames = M;
+  const int extra = sub->q_max_jspan - 1;
+  const long long nseg = 1 + (M - 1 + T - 1) / T;
+  P.lds_rows = (int)((M + nseg * extra + 63) / 64 * 64);
+  P.centre = sub->K / 2;
+  const double turn = std::fmod(sub->Q, 2.0);
+  P.rot_c = (float)std::cos(kPi * turn);
+  P.rot_s = (float)std::sin(kPi * turn);
+  P.n_ft = (P.g.n_frames + M - 1) / M;
+  hipError_t e = nna::launch_cqt_fold(P, reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail_hip(e, "kernel launch");
+  return NNA_OK;
+}
+
 // one launch of the CQT kernel: `sub`'s bank over T frames of each of the B waveforms in x
 nna_status run_conv(const nna_plan* sub, const float* x, long long B, long long L, long long T, float* out,
-                    long long out_wave_stride, int row_offset, void* hip_stream) {
+                    long long out_wave_stride, int row_offset, void* hip_stream, bool may_fold = false) {
   const int extra = (sub->max_jspan - 1) * sub->row_step;
   const int M = pick_tile_frames(CQ_FRAMES, T, extra, CQ_LDS_ROWS_MAX);
+  if (may_fold && sub->runs_cqfold()) {
+    // the folded kernel does half the work per frame; its tiles hold fewer rows, so batches of very short
+    // waveforms (many waveform segments, each with its overlap rows, in one tile) can leave it the smaller tile
+    const int Mf = pick_tile_frames(CQ_FRAMES, T, sub->q_max_jspan - 1, nna::CQF_LDS_ROWS);
+    if (Mf >= 1 && 2 * Mf >= M) return run_conv_fold(sub, x, B, L, T, out, out_wave_stride, row_offset, Mf, hip_stream);
+  }
   if (M < 1) return fail(NNA_ERR_UNSUPPORTED, "frame tile does not fit in LDS");
   nna::CqtParams P;
   std::memset(&P, 0, sizeof(P));
@@ -532,6 +569,6 @@ nna_status nna_cqt(const nna_plan* plan, const float* x_dev, long long B, long l
   DeviceGuard guard;
   hipError_t e = guard.enter(plan->device);
   if (e != hipSuccess) return fail_hip(e, "hipSetDevice");
-  return run_conv(plan, x_dev, B, L, T, out_dev, (long long)plan->out_rows() * T, 0, hip_stream);
+  return run_conv(plan, x_dev, B, L, T, out_dev, (long long)plan->out_rows() * T, 0, hip_stream, true);
 }
 }  // extern "C"

@@ -166,7 +166,7 @@ def check_kernel(lines, unmarked_is_asm: bool = True) -> list:
 
 # the files whose kernels issue loads through inline asm (nna_train.hip leaves its loads to the compiler,
 # which tracks them itself)
-KERNEL_SOURCES = ("nna_kernels.hip", "nna_kernels_fold.hip", "nna_kernels_f16.hip")
+KERNEL_SOURCES = ("nna_kernels.hip", "nna_kernels_fold.hip", "nna_kernels_cqf.hip", "nna_kernels_f16.hip")
 
 
 def compile_to_asm(extra_flags=()) -> str:
