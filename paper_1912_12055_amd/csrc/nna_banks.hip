@@ -846,7 +846,11 @@ void build_cqt_bank_fold(nna_plan* p) {
         }
       }
   p->exec_flops_cqf = 2.0 * (double)exec_pair_groups * 2.0 * CQ_KC * CQ_ROWS;
-  p->cq_fold = true;
+  // Blocks of one parity span twice as many adjacent bins as the direct bank's (16 bins of a parity against 8 of
+  // either), so with few bins per octave the longest kernel of a block dwarfs the others and the fold's half is
+  // eaten up; the folded kernel also keeps the matrix pipe less busy (it forms the folds on the vector ALUs).  It
+  // runs where it multiplies at most three quarters of what the direct kernel does.
+  p->cq_fold = p->exec_flops_cqf <= 0.75 * p->exec_flops;
 }
 
 // Window-method low-pass at half the Nyquist frequency (Sec. III-C, "Downsampling"): the ideal

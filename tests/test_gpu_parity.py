@@ -364,6 +364,70 @@ def test_cqt_complex_and_phase_output(nb, case):
     assert e < TOL and e < 5e-5 and ep < 1e-3
 
 
+# Plans whose kernels run folded about their centres (many bins per octave, kernels of eight hops or more): the
+# blocks of the folded bank hold bins of one length parity, tiles come in pairs (behind / in front of the frame
+# centre), and the epilogue turns the two sums back by the kernels' common phase.
+CQT_FOLD_CASES = [
+    # name, B, L, sr, hop, fmin, n_bins, bpo, win, center, fmt
+    ("36 per octave, 64 hop-shifts, tiles span waveforms", 3, 9000, 8000, 32, 200.0, 60, 36, 0, True, 0),
+    ("Blackman kernels, no centring, power", 2, 9000, 8000, 32, 200.0, 60, 36, 3, False, 1),
+    ("48 per octave, ragged batch, no centring", 5, 4000, 8000, 64, 300.0, 33, 48, 0, False, 0),
+    ("waveforms of 36 frames, eight to a tile", 20, 4500, 16000, 128, 100.0, 40, 24, 0, True, 2),
+]
+
+
+def _fold_plan(nb, case, fmt=None, trainable=False):
+    name, B, L, sr, hop, fmin, n_bins, bpo, win, center, f = case
+    plan = nb.nna_plan_cqt(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, win=win, center=center,
+                           n_taps=0, fmt=f if fmt is None else fmt, device=0)
+    return nb.nna_plan_trainable(plan) if trainable else plan
+
+
+@pytest.mark.parametrize("case", CQT_FOLD_CASES, ids=[c[0] for c in CQT_FOLD_CASES])
+def test_cqt_folded_kernels_parity(nb, case):
+    name, B, L, sr, hop, fmin, n_bins, bpo, win, center, fmt = case
+    _say(f"cqt folded {name}: B={B} L={L} sr={sr} hop={hop} bins={n_bins}/{bpo}")
+    x = _rand(B, L, 700 + n_bins)
+    plan = _fold_plan(nb, case)
+    info = plan.info()
+    # the plan does run the folded kernel: it multiplies less than the direct form's 4 sum N_k
+    assert info["executed_flops_per_frame"] < info["algorithmic_flops_per_frame"]
+    got = nb.nna_cqt(plan, _dev(x)).cpu().numpy()
+    ref = oracle.cqt(x, sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, window=win, center=center,
+                     n_taps=0, fmt=fmt)
+    e = _rel_err(got, ref)
+    _say(f"  rel err {e:.3e}")
+    assert e < TOL and e < 5e-5
+
+
+@pytest.mark.parametrize("case", [CQT_FOLD_CASES[0], CQT_FOLD_CASES[2], CQT_FOLD_CASES[3]], ids=lambda c: c[0])
+def test_cqt_folded_kernels_complex_and_phase_output(nb, case):
+    name, B, L, sr, hop, fmin, n_bins, bpo, win, center, _ = case
+    _say(f"cqt folded complex/phase {name}")
+    x = _rand(B, L, 700 + n_bins)
+    re, im = oracle.cqt_complex(x, sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, window=win,
+                                center=center, n_taps=0)
+    got = nb.nna_cqt(_fold_plan(nb, case, fmt=nb.NNA_OUT_COMPLEX), _dev(x)).cpu().numpy()
+    e = _rel_err(got, oracle.interleave(re, im))
+    ph = nb.nna_cqt(_fold_plan(nb, case, fmt=nb.NNA_OUT_PHASE), _dev(x)).cpu().numpy()
+    ep = _phase_err(ph, re, im)
+    _say(f"  complex rel err {e:.3e}, phase err {ep:.3e} rad")
+    assert e < TOL and e < 5e-5 and ep < 1e-3
+
+
+def test_cqt_folded_and_direct_kernels_agree(nb):
+    # the same plan made trainable keeps its kernels as free parameters and runs the direct kernel
+    case = CQT_FOLD_CASES[0]
+    _say("cqt folded against direct kernel")
+    x = _dev(_rand(case[1], case[2], 77))
+    folded, direct = _fold_plan(nb, case, fmt=nb.NNA_OUT_COMPLEX), _fold_plan(nb, case, fmt=nb.NNA_OUT_COMPLEX, trainable=True)
+    assert folded.info()["executed_flops_per_frame"] < 0.75 * direct.info()["executed_flops_per_frame"]
+    a, b = nb.nna_cqt(folded, x).cpu().numpy(), nb.nna_cqt(direct, x).cpu().numpy()
+    e = float(np.max(np.abs(a - b)) / np.max(np.abs(b)))
+    _say(f"  rel diff {e:.3e}")
+    assert e < 2e-5
+
+
 def test_cqt_device_bank_equals_host_bank(nb):
     _say("cqt bank read-back")
     kw = dict(sr=8000, hop=128, fmin=220.0, n_bins=24, bins_per_octave=12, n_taps=1024)
