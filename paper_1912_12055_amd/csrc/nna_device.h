@@ -107,6 +107,13 @@ __device__ __forceinline__ void wait_vm(f32x4 (&a)[5], f32x4 (&b)[5]) {
                : "n"(N));
 }
 template <int N>
+__device__ __forceinline__ void wait_vm(f32x4 (&a)[6], f32x4 (&b)[6]) {
+  asm volatile("s_waitcnt vmcnt(%12)"
+               : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(b[0]), "+v"(b[1]), "+v"(b[2]),
+                 "+v"(b[3]), "+v"(b[4]), "+v"(b[5])
+               : "n"(N));
+}
+template <int N>
 __device__ __forceinline__ void wait_vm(f32x4 (&r)[6]) {
   asm volatile("s_waitcnt vmcnt(%6)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]) : "n"(N));
 }

@@ -183,7 +183,7 @@ struct CqtParams {
 };
 
 // ---- constant-Q kernels folded about their centres (nna_kernels_cqf.hip) ----------------------
-constexpr int CQF_NPASS = 5;                  // loader passes of 64 rows per tile
+constexpr int CQF_NPASS = 6;                  // loader passes of 64 rows per tile
 constexpr int CQF_LDS_ROWS = CQF_NPASS * 64;  // rows of each of the two tiles (taps in front of / behind the centre)
 constexpr int CQF_TABLE_CAP = 1024;           // chunk descriptors per work item (16 bytes each)
 
