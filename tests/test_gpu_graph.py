@@ -33,10 +33,13 @@ def test_forward_and_backward_calls_replay_from_a_graph(nb):
     p_stft = nb.nna_plan_trainable(nb.nna_plan_stft(n_fft=512, hop=128, device=0))
     p_mel = nb.nna_plan_mel(n_fft=512, hop=128, n_mels=40, device=0)
     p_cqt = nb.nna_plan_trainable(nb.nna_plan_cqt(sr=16000, hop=128, fmin=110.0, n_bins=48, device=0))
+    # 24 bins per octave, 8,192-tap kernels: the plan folds its kernels about their centres (another kernel)
+    p_cqf = nb.nna_plan_cqt(sr=16000, hop=128, fmin=100.0, n_bins=40, bins_per_octave=24, device=0)
+    assert p_cqf.info()["executed_flops_per_frame"] < p_cqf.info()["algorithmic_flops_per_frame"]
     p_v2 = nb.nna_plan_cqt2010v2(sr=16000, hop=128, fmin=110.0, n_bins=48, device=0)
     p_fd = nb.nna_plan_cqt2010(sr=16000, hop=128, fmin=110.0, n_bins=48, device=0)
     outs = {k: torch.empty((B,) + nb.nna_out_shape(p, B, L), device=dev)
-            for k, p in (("stft", p_stft), ("mel", p_mel), ("cqt", p_cqt), ("v2", p_v2), ("fd", p_fd))}
+            for k, p in (("stft", p_stft), ("mel", p_mel), ("cqt", p_cqt), ("cqf", p_cqf), ("v2", p_v2), ("fd", p_fd))}
     outs["mel2"] = torch.empty_like(outs["mel"])
     outs["spec"] = torch.empty_like(outs["stft"])
     ws_v2 = torch.empty(max(16, nb.nna_cqt2010v2_workspace(p_v2, B, L)), dtype=torch.uint8, device=dev)
@@ -56,6 +59,7 @@ def test_forward_and_backward_calls_replay_from_a_graph(nb):
         nb.nna_mel(p_mel, x, outs["mel"])
         nb.nna_mel_with_stft(p_mel, x, outs["mel2"], outs["spec"])
         nb.nna_cqt(p_cqt, x, outs["cqt"])
+        nb.nna_cqt(p_cqf, x, outs["cqf"])
         nb.nna_cqt2010v2(p_v2, x, outs["v2"], workspace=ws_v2)
         nb.nna_cqt2010(p_fd, x, outs["fd"], workspace=ws_fd)
         st = torch.cuda.current_stream().cuda_stream
