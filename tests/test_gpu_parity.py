@@ -369,10 +369,11 @@ def test_cqt_complex_and_phase_output(nb, case):
 # centre), and the epilogue turns the two sums back by the kernels' common phase.
 CQT_FOLD_CASES = [
     # name, B, L, sr, hop, fmin, n_bins, bpo, win, center, fmt
-    ("36 per octave, 64 hop-shifts, tiles span waveforms", 3, 9000, 8000, 32, 200.0, 60, 36, 0, True, 0),
+    # (lengths that are no multiples of four: the mirrored samples at the waveform's ends straddle the loader's windows)
+    ("36 per octave, 64 hop-shifts, tiles span waveforms", 3, 9002, 8000, 32, 200.0, 60, 36, 0, True, 0),
     ("Blackman kernels, no centring, power", 2, 9000, 8000, 32, 200.0, 60, 36, 3, False, 1),
     ("48 per octave, ragged batch, no centring", 5, 4000, 8000, 64, 300.0, 33, 48, 0, False, 0),
-    ("waveforms of 36 frames, eight to a tile", 20, 4500, 16000, 128, 100.0, 40, 24, 0, True, 2),
+    ("waveforms of 36 frames, eight to a tile", 20, 4501, 16000, 128, 100.0, 40, 24, 0, True, 2),
 ]
 
 
