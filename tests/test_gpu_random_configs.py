@@ -147,6 +147,36 @@ def test_random_cqt_layers(nb, seed):
         assert _err(nb.nna_cqt2010(nb.nna_plan_cqt2010(win=win, device=0, **cfg), xd), oracle.cqt2010(x, window=win, **cfg)) < TOL
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_cqt_many_bins_per_octave(nb, seed):
+    # the region where nna_cqt folds its kernels about their centres: many bins per octave, kernels of many hops,
+    # windows that vanish at n = 0 (Hann, Blackman); every output format
+    rng = np.random.default_rng([17, seed])
+    sr = int(rng.choice([8000, 16000, 22050]))
+    bpo = int(rng.choice([24, 30, 36, 48]))
+    n_bins = int(rng.integers(bpo + bpo // 2, 3 * bpo))
+    top = float(rng.uniform(0.25, 0.45)) * sr / 2.0 ** (1.0 / bpo)
+    fmin = float(top / 2.0 ** ((n_bins - 1) / bpo))
+    hop = int(rng.choice([16, 32, 64, 128]))
+    win = int(rng.choice([0, 3]))
+    center = bool(rng.integers(0, 2))
+    fmt = int(rng.integers(0, 3))
+    B = int(rng.choice([1, 3, 6]))
+    taps = oracle.cqt_default_taps(sr, fmin, bpo)
+    L = taps + int(rng.integers(1, 3000))
+    cfg = dict(sr=sr, hop=hop, fmin=fmin, n_bins=n_bins, bins_per_octave=bpo, center=center)
+    plan = nb.nna_plan_cqt(win=win, fmt=fmt, device=0, **cfg)
+    info = plan.info()
+    folded = info["executed_flops_per_frame"] < info["algorithmic_flops_per_frame"]
+    _say(f"random cqt, many bins per octave, seed={seed}: {cfg} win={win} fmt={fmt} B={B} L={L} taps={taps} folded={folded}")
+    x = _wave(rng, B, L)
+    xd = _dev(x)
+    assert _err(nb.nna_cqt(plan, xd), oracle.cqt(x, window=win, fmt=fmt, **cfg)) < TOL
+    re, im = oracle.cqt_complex(x, window=win, **cfg)
+    got = nb.nna_cqt(nb.nna_plan_cqt(win=win, fmt=nb.NNA_OUT_COMPLEX, device=0, **cfg), xd)
+    assert _err(got, oracle.interleave(re, im)) < TOL
+
+
 @pytest.mark.parametrize("seed", range(10))
 def test_random_backward(nb, seed):
     import torch
