@@ -160,8 +160,8 @@ nna_status nna_plan_mel(nna_plan** plan, int sr, int n_fft, int hop, nna_window 
  * must be even and >= N_0, and the top bin must lie below sr/2.  Output bins = n_bins.
  * How nna_cqt evaluates eq. (CQT) is the plan's choice and changes no result beyond rounding:
  * the kernels are symmetric about their centres up to the common phase exp(-i pi Q), and where
- * it saves at least a quarter of the multiply-adds (many bins per octave, kernels of eight hops
- * or more, hop a multiple of 16 dividing n_taps / 2, a window that vanishes at n = 0) they are
+ * that pays (a seventh or more of the multiply-adds saved: 12 or more bins per octave, kernels of
+ * eight hops or more, hop a multiple of 16 dividing n_taps / 2, a window that vanishes at n = 0) they are
  * applied to the frame folded about that centre.  nna_plan_info reports the flops of the form
  * that runs; nna_plan_bank always returns the kernels as defined above.
  */

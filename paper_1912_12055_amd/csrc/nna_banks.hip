@@ -848,9 +848,10 @@ void build_cqt_bank_fold(nna_plan* p) {
   p->exec_flops_cqf = 2.0 * (double)exec_pair_groups * 2.0 * CQ_KC * CQ_ROWS;
   // Blocks of one parity span twice as many adjacent bins as the direct bank's (16 bins of a parity against 8 of
   // either), so with few bins per octave the longest kernel of a block dwarfs the others and the fold's half is
-  // eaten up; the folded kernel also keeps the matrix pipe less busy (it forms the folds on the vector ALUs).  It
-  // runs where it multiplies at most three quarters of what the direct kernel does.
-  p->cq_fold = p->exec_flops_cqf <= 0.75 * p->exec_flops;
+  // eaten up; the folded kernel also keeps the matrix pipe less busy (it forms the folds on the vector ALUs: 0.77
+  // against 0.86 measured).  Timed on 1,770 waveforms it breaks even where it multiplies 0.86 of what the direct
+  // kernel does (12 bins per octave, 0.84-0.85: 1-5 % faster); beyond that the direct kernel runs.
+  p->cq_fold = p->exec_flops_cqf <= 0.86 * p->exec_flops;
 }
 
 // Window-method low-pass at half the Nyquist frequency (Sec. III-C, "Downsampling"): the ideal

@@ -207,7 +207,8 @@ def test_cqt_bank_matches_oracle_kernels(sr, hop, fmin, nbins, bpo, taps):
     np.testing.assert_array_equal(nb.nna_plan_cqt_lengths(p), Nk)
     info = p.info()
     assert info["algorithmic_flops_per_frame"] == 4.0 * Nk.sum()
-    assert info["executed_flops_per_frame"] >= info["algorithmic_flops_per_frame"]  # (12 bins per octave: direct kernel)
+    # (12 bins per octave or fewer: whichever kernel runs multiplies more than the taps of the direct form)
+    assert info["executed_flops_per_frame"] >= info["algorithmic_flops_per_frame"]
 
 
 def test_cqt_plans_fold_their_kernels_where_it_pays():
