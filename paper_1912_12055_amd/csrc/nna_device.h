@@ -233,10 +233,11 @@ __device__ __forceinline__ float pick4(const f32x4& v, unsigned k) {
   return k == 0 ? v.x : k == 1 ? v.y : k == 2 ? v.z : v.w;
 }
 
-// the value of pass p as it goes to LDS (classes 0 and 1)
+// the value of pass p as it goes to LDS (classes 0 and 1; in class 0 no lane has a bit of `rev` set, and the class
+// is not tested here: the compiler turns that test into a second layer of selects, and vector-ALU instructions in
+// the kernels' main loops cost the matrix pipe their four cycles each)
 template <int NPASS>
 __device__ __forceinline__ f32x4 fixed_up(const f32x4& v, const TileFix<NPASS>& fx, int p) {
-  if (fx.cls == 0) return v;
   const bool r = (fx.rev >> p) & 1u;
   return (f32x4){r ? v.w : v.x, r ? v.z : v.y, r ? v.y : v.z, r ? v.x : v.w};
 }

@@ -542,6 +542,7 @@ __global__ __launch_bounds__(256, 2) void stft_fold_kernel(const StftParams P) {
           for (int p = 0; p < NPASS; ++p) off[p] = (unsigned)(rows.roff[p] + (M_ && !PAIR ? rows.i0m[p] : rows.i0s[p])) << 2;
           sb = xbase + 4 * shift;
           fx.cls = 0;
+          fx.rev = 0;
         } else {
           fold_offsets(off, fx, L, rows.roff, M_ && !PAIR ? rows.i0m : rows.i0s, shift);
         }
